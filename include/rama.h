@@ -1,0 +1,182 @@
+/*
+ * rama.h -- C ABI of the MI355X (gfx950) primal-dual multicut library.
+ *
+ * The library implements one round -- and the loop over rounds -- of the primal-dual
+ * multicut algorithm of "RAMA: A Rapid Multicut Algorithm on GPU" (arXiv 2109.01838):
+ * conflicted-cycle separation, edge<->triangle message passing, and parallel edge
+ * contraction.  Every step runs in hand-written HIP kernels on one GPU.
+ *
+ * Problem statement (paper Sec. 3, eq. 2): an undirected graph with `n_nodes` nodes and
+ * `n_edges` edges given as endpoint arrays i[], j[] (int32) and costs c[] (fp32).
+ * c > 0: attractive (the endpoints want to share a cluster); c < 0: repulsive; c == 0:
+ * neither.  The objective is the sum of the costs of the edges whose endpoints end up in
+ * different clusters.
+ *
+ * General conventions
+ *   - "device" pointers are HIP device memory valid on the ctx's device; "host" pointers are
+ *     ordinary host memory.  All graph arrays are DEVICE pointers; all scalar results are
+ *     HOST pointers.
+ *   - The caller owns every input and output buffer.  Inputs are never modified.  The
+ *     library keeps no reference to caller memory after a call returns.  Workspace is
+ *     allocated with hipMalloc through the ctx, cached for reuse, and released by
+ *     rama_destroy.
+ *   - Every call enqueues its kernels on the ctx's stream and synchronises that stream
+ *     before it returns (scalar results are on the host when the call returns).
+ *   - Any edge list is accepted: either orientation, self-loops (dropped; they can never
+ *     be cut) and duplicate / antiparallel edges (their costs are added in input order,
+ *     Lemma 1(b)).  A "canonical" edge list has i<j, is sorted by (i,j) and has no
+ *     duplicates; all edge lists the library RETURNS are canonical.
+ *   - No exception crosses the boundary; every call returns a rama_status.  On failure
+ *     outputs are unspecified unless stated otherwise; rama_last_error() describes the
+ *     failure.  Endpoints outside [0,n_nodes) and non-finite costs give RAMA_ERR_BAD_GRAPH.
+ *   - Element counts of any one array must stay below 2^31 (RAMA_ERR_CAPACITY otherwise).
+ *   - One ctx must not be used from two threads at once.
+ */
+#ifndef RAMA_H
+#define RAMA_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rama_ctx rama_ctx; /* opaque: device, stream, cached workspace, last error */
+
+typedef enum {
+    RAMA_OK = 0,
+    RAMA_ERR_INVALID_ARG = -1, /* null pointer, negative size, cycle length not in {3,4,5}, ... */
+    RAMA_ERR_BAD_GRAPH = -2,   /* endpoint out of range, non-finite cost, a cycle that is not in the graph */
+    RAMA_ERR_CAPACITY = -3,    /* a caller buffer is too small (needed sizes are written) or a count reaches 2^31 */
+    RAMA_ERR_OOM = -4,         /* hipMalloc failed */
+    RAMA_ERR_HIP = -5          /* any other HIP runtime error */
+} rama_status;
+
+/* Parameters of the primal-dual loop (paper Alg. "Primal-Dual Multicut" and Sec. 4, solver
+ * variants).  rama_params_default() fills the values of solver "PD". */
+typedef struct {
+    int32_t max_cycle_len_first;  /* longest conflicted cycle separated on the original graph: 5 (0 = no separation) */
+    int32_t max_cycle_len_later;  /* ... on contracted graphs: 3 for "PD", 5 for "PD+" */
+    int32_t mp_iters_first;       /* message-passing iterations k in the first round: 10 */
+    int32_t mp_iters_later;       /* ... in later rounds: 5 */
+    int32_t matching_rounds_cap;  /* upper limit on handshake rounds per matching: 32 */
+    float contract_threshold;     /* tau: an edge is a contraction candidate iff c > tau; 0 */
+    int32_t max_rounds;           /* stop after this many rounds; <=0: until no candidate edge is left */
+} rama_params;
+
+/* What rama_solve did (all host memory). */
+typedef struct {
+    int32_t rounds;             /* rounds of the outer loop that ran */
+    int32_t n_clusters;         /* clusters in the result */
+    int64_t n_cycles_first[3];  /* conflicted 3-, 4-, 5-cycles found on the original graph */
+    int64_t n_triangles_first;  /* triangles after triangulation, first round */
+    int64_t n_edges_aug_first;  /* edges after adding chords, first round */
+    int64_t n_edges_final;      /* edges of the last contracted graph */
+    double ms_total;            /* wall time of the call */
+    double ms_cycles, ms_dual, ms_contract, ms_other; /* host-clock split by stage */
+} rama_stats;
+
+/* Create a context on the current HIP device.  `hip_stream` is a hipStream_t (may be NULL
+ * for the default stream) on which all work is enqueued; the caller keeps ownership of it. */
+rama_status rama_create(rama_ctx **out, void *hip_stream);
+/* Free the workspace and the context.  NULL is allowed. */
+rama_status rama_destroy(rama_ctx *ctx);
+/* Text for the last failure on this ctx; owned by the ctx, valid until the next call. */
+const char *rama_last_error(const rama_ctx *ctx);
+/* Defaults of solver "PD" (Sec. 4): cycles up to 5 then 3, k = 10 then 5, tau = 0. */
+void rama_params_default(rama_params *p);
+/* Bytes of device workspace currently cached by the ctx. */
+int64_t rama_workspace_bytes(const rama_ctx *ctx);
+
+/*
+ * Conflicted-cycle separation (Sec. 3.2.2, definition "Conflicted cycles", and the appendix
+ * algorithm "Parallel Conf. 5-Cycles"): every simple cycle of length L in {3,..,max_cycle_len}
+ * with exactly one repulsive edge and L-1 attractive edges.
+ *
+ * A cycle is stored as the node tuple (v0,...,v_{L-1}) where (v0,v_{L-1}) is its repulsive
+ * edge, v0 < v_{L-1}, and v0,v1,...,v_{L-1} is the attractive path.  Each list is ordered by
+ * (v0, v_{L-1}, v1, v_{L-2}, v2): grouped by repulsive edge, then ends-inward along the path.
+ *
+ *   i, j, c            device, [n_edges]
+ *   max_cycle_len      3, 4 or 5
+ *   cap3, cap4, cap5   capacities of the output lists, in cycles
+ *   cycles3/4/5        device, [3*cap3], [4*cap4], [5*cap5]; may be NULL when its cap is 0
+ *   n_cycles_out       host, [3]: number of 3-, 4-, 5-cycles found (always written on
+ *                      RAMA_OK and RAMA_ERR_CAPACITY)
+ * RAMA_ERR_CAPACITY if any list does not fit; then nothing is written to the lists, and
+ * calling again with the reported counts succeeds (calling with all caps 0 is the way to
+ * size the buffers).
+ */
+rama_status rama_find_conflicted_cycles(rama_ctx *ctx, int32_t n_nodes, int64_t n_edges,
+                                        const int32_t *i, const int32_t *j, const float *c,
+                                        int32_t max_cycle_len, int64_t cap3, int64_t cap4, int64_t cap5,
+                                        int32_t *cycles3, int32_t *cycles4, int32_t *cycles5,
+                                        int64_t *n_cycles_out);
+
+/*
+ * Dual update of one round (Sec. 3.2.1 Lagrange decomposition, eq. 5 and 6; Sec. 3.2.3,
+ * algorithm "Parallel-Message-Passing"; inner loop of "Primal-Dual Multicut"):
+ * triangulate the given cycles, run k_iters iterations of edge->triangle and
+ * triangle->edge message passing, and return the reparametrised graph.
+ *
+ * Triangulation (the paper leaves the rule open): a cycle (v0,...,v_{L-1}) becomes the
+ * triangles {v0,v_m,v_{m+1}}, m=1..L-2; a chord (v0,v_m) that is not yet an edge is added
+ * with cost 0.  The triangle set is the sorted set of distinct node triples.
+ *
+ *   cyclesL, nL        device lists in the format of rama_find_conflicted_cycles (any order);
+ *                      every cycle edge must be an edge of the graph, nodes distinct
+ *   k_iters            >= 0
+ *   edge_cap           capacity of i_out/j_out/c_out; n_edges + n4 + 2*n5 always suffices
+ *   i_out,j_out,c_out  device: canonical edge list incl. new chords, c_out = reduced costs c^lambda (eq. 6a)
+ *   n_edges_out        host: number of edges written (needed size on RAMA_ERR_CAPACITY)
+ *   lower_bound        host, optional: LB(lambda) of eq. 5 after the last iteration
+ *   lb_trace           host, optional, [k_iters+1]: LB before the first and after every iteration
+ */
+rama_status rama_message_passing(rama_ctx *ctx, int32_t n_nodes, int64_t n_edges,
+                                 const int32_t *i, const int32_t *j, const float *c,
+                                 const int32_t *cycles3, int64_t n3, const int32_t *cycles4, int64_t n4,
+                                 const int32_t *cycles5, int64_t n5, int32_t k_iters, int64_t edge_cap,
+                                 int32_t *i_out, int32_t *j_out, float *c_out, int64_t *n_edges_out,
+                                 double *lower_bound, double *lb_trace);
+
+/*
+ * Primal update (Sec. 3.1: Lemma 1, Lemma 3, algorithm "Parallel-Edge-Contraction", "Finding
+ * contraction edge set S: Maximum matching"; appendix algorithm "GPU Edge-Contraction").
+ * S is a handshake matching on the edges with c > params->contract_threshold (larger cost
+ * wins, ties go to the edge that comes first in the canonical list); the contraction mapping
+ * is the connected-component map of (V,S), numbered by ascending smallest member; the
+ * contracted graph is K^T A K without its diagonal.
+ *
+ *   repeat             1: one primal update.  0: repeat until no edge with c > tau is left
+ *                      (the purely primal solver "P" of Sec. 4)
+ *   mapping            device, [n_nodes]: node -> node of the contracted graph, in [0,*n_nodes_out)
+ *   i_out,j_out,c_out  device, capacity n_edges each: canonical contracted edge list
+ *   diag_out           device, optional, [n_nodes]: first *n_nodes_out entries = diagonal of
+ *                      K^T A K (Lemma 3(b)): per new node the summed cost of the input edges inside it
+ *   n_nodes_out, n_edges_out   host
+ * If no edge qualifies the mapping is the identity and the output is the canonical input.
+ */
+rama_status rama_contract(rama_ctx *ctx, int32_t n_nodes, int64_t n_edges,
+                          const int32_t *i, const int32_t *j, const float *c,
+                          const rama_params *params, int32_t repeat,
+                          int32_t *mapping, int32_t *i_out, int32_t *j_out, float *c_out, float *diag_out,
+                          int32_t *n_nodes_out, int64_t *n_edges_out);
+
+/*
+ * The whole solver (algorithm "Primal-Dual Multicut"): repeat { separate conflicted cycles;
+ * k message-passing iterations; contract on the reduced costs; compose the mapping } until
+ * the contraction set is empty.
+ *
+ *   labels        device, [n_nodes]: label of a node = smallest node id in its cluster
+ *   primal_cost   host, optional: cost (eq. 2) of the returned clustering on the input costs
+ *   lower_bound   host, optional: LB(lambda) recorded after message passing on the original graph
+ *   stats         host, optional
+ */
+rama_status rama_solve(rama_ctx *ctx, int32_t n_nodes, int64_t n_edges,
+                       const int32_t *i, const int32_t *j, const float *c, const rama_params *params,
+                       int32_t *labels, double *primal_cost, double *lower_bound, rama_stats *stats);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RAMA_H */

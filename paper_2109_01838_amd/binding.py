@@ -1,0 +1,219 @@
+"""Thin ctypes binding of librama_hip.so (include/rama.h).  Argument marshalling only: torch
+supplies device memory and the stream, every step of the method runs inside the library.
+
+There is no CPU fallback: if the library is missing or no GPU is present the calls raise.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "librama_hip.so")
+
+RAMA_OK, RAMA_ERR_INVALID_ARG, RAMA_ERR_BAD_GRAPH, RAMA_ERR_CAPACITY, RAMA_ERR_OOM, RAMA_ERR_HIP = 0, -1, -2, -3, -4, -5
+
+EXPORTS = [
+    "rama_create", "rama_destroy", "rama_last_error", "rama_params_default", "rama_workspace_bytes",
+    "rama_find_conflicted_cycles", "rama_message_passing", "rama_contract", "rama_solve",
+]
+
+
+class RamaParams(C.Structure):
+    _fields_ = [
+        ("max_cycle_len_first", C.c_int32), ("max_cycle_len_later", C.c_int32),
+        ("mp_iters_first", C.c_int32), ("mp_iters_later", C.c_int32),
+        ("matching_rounds_cap", C.c_int32), ("contract_threshold", C.c_float),
+        ("max_rounds", C.c_int32),
+    ]
+
+
+class RamaStats(C.Structure):
+    _fields_ = [
+        ("rounds", C.c_int32), ("n_clusters", C.c_int32), ("n_cycles_first", C.c_int64 * 3),
+        ("n_triangles_first", C.c_int64), ("n_edges_aug_first", C.c_int64), ("n_edges_final", C.c_int64),
+        ("ms_total", C.c_double), ("ms_cycles", C.c_double), ("ms_dual", C.c_double),
+        ("ms_contract", C.c_double), ("ms_other", C.c_double),
+    ]
+
+
+class RamaError(RuntimeError):
+    def __init__(self, status, where, msg):
+        super().__init__(f"{where} failed with status {status}: {msg}")
+        self.status = status
+
+
+_lib = None
+
+
+def load_library():
+    """Load librama_hip.so; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    # torch ships its own HIP runtime (same soname as ROCm's).  Import torch first so that the
+    # library binds to that one runtime; loaded the other way round the process ends up with two
+    # runtimes and torch's streams and pointers mean nothing to the library.
+    import torch  # noqa: F401
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2109_01838_amd.build` "
+                           "(or __graft_entry__.build()); there is no CPU fallback")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    lib.rama_create.argtypes = [C.POINTER(vp), vp]
+    lib.rama_destroy.argtypes = [vp]
+    lib.rama_last_error.argtypes = [vp]
+    lib.rama_last_error.restype = C.c_char_p
+    lib.rama_params_default.argtypes = [C.POINTER(RamaParams)]
+    lib.rama_params_default.restype = None
+    lib.rama_workspace_bytes.argtypes = [vp]
+    lib.rama_workspace_bytes.restype = i64
+    lib.rama_find_conflicted_cycles.argtypes = [vp, i32, i64, vp, vp, vp, i32, i64, i64, i64, vp, vp, vp,
+                                                C.POINTER(i64)]
+    lib.rama_message_passing.argtypes = [vp, i32, i64, vp, vp, vp, vp, i64, vp, i64, vp, i64, i32, i64, vp, vp, vp,
+                                         C.POINTER(i64), C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    lib.rama_contract.argtypes = [vp, i32, i64, vp, vp, vp, C.POINTER(RamaParams), i32, vp, vp, vp, vp, vp,
+                                  C.POINTER(i32), C.POINTER(i64)]
+    lib.rama_solve.argtypes = [vp, i32, i64, vp, vp, vp, C.POINTER(RamaParams), vp, C.POINTER(C.c_double),
+                               C.POINTER(C.c_double), C.POINTER(RamaStats)]
+    for name in EXPORTS:
+        if name not in ("rama_last_error", "rama_params_default", "rama_workspace_bytes"):
+            getattr(lib, name).restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def default_params(**overrides):
+    p = RamaParams()
+    load_library().rama_params_default(C.byref(p))
+    for k, v in overrides.items():
+        if not hasattr(p, k):
+            raise TypeError(f"unknown parameter {k}")
+        setattr(p, k, v)
+    return p
+
+
+def _dev(t, dtype, torch):
+    if t.device.type != "cuda":
+        raise ValueError("device tensors required")
+    if t.dtype != dtype or not t.is_contiguous():
+        raise ValueError(f"expected contiguous {dtype} tensor, got {t.dtype}")
+    return t
+
+
+class Rama:
+    """One library context bound to the current torch device and stream."""
+
+    def __init__(self, device="cuda:0"):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU visible: the HIP path cannot run and there is no CPU fallback")
+        self.torch = torch
+        self.lib = load_library()
+        self.device = torch.device(device)
+        torch.cuda.set_device(self.device)
+        self.stream = torch.cuda.current_stream(self.device)
+        self.ctx = C.c_void_p()
+        st = self.lib.rama_create(C.byref(self.ctx), C.c_void_p(self.stream.cuda_stream))
+        if st != RAMA_OK:
+            raise RamaError(st, "rama_create", "")
+
+    def close(self):
+        if self.ctx:
+            self.lib.rama_destroy(self.ctx)
+            self.ctx = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- helpers ------------------------------------------------------------------------------
+    def _check(self, st, where):
+        if st != RAMA_OK:
+            raise RamaError(st, where, self.lib.rama_last_error(self.ctx).decode())
+
+    def _graph(self, i, j, c):
+        t = self.torch
+        i = _dev(t.as_tensor(i, device=self.device), t.int32, t)
+        j = _dev(t.as_tensor(j, device=self.device), t.int32, t)
+        c = _dev(t.as_tensor(c, device=self.device), t.float32, t)
+        if not (i.numel() == j.numel() == c.numel()):
+            raise ValueError("i, j, c must have equal length")
+        return i, j, c
+
+    def _empty(self, n, dtype):
+        return self.torch.empty(max(int(n), 1), dtype=dtype, device=self.device)
+
+    def workspace_bytes(self):
+        return int(self.lib.rama_workspace_bytes(self.ctx))
+
+    # -- entry points ---------------------------------------------------------------------------
+    def find_conflicted_cycles(self, n_nodes, i, j, c, max_cycle_len=5):
+        t = self.torch
+        i, j, c = self._graph(i, j, c)
+        cnt = (C.c_int64 * 3)()
+        st = self.lib.rama_find_conflicted_cycles(self.ctx, n_nodes, i.numel(), i.data_ptr(), j.data_ptr(),
+                                                  c.data_ptr(), max_cycle_len, 0, 0, 0, None, None, None, cnt)
+        if st not in (RAMA_OK, RAMA_ERR_CAPACITY):
+            self._check(st, "rama_find_conflicted_cycles")
+        outs = [self._empty(cnt[k] * (k + 3), t.int32) for k in range(3)]
+        want = [cnt[0], cnt[1], cnt[2]]
+        st = self.lib.rama_find_conflicted_cycles(self.ctx, n_nodes, i.numel(), i.data_ptr(), j.data_ptr(),
+                                                  c.data_ptr(), max_cycle_len, want[0], want[1], want[2],
+                                                  outs[0].data_ptr(), outs[1].data_ptr(), outs[2].data_ptr(), cnt)
+        self._check(st, "rama_find_conflicted_cycles")
+        return [outs[k][: want[k] * (k + 3)].view(-1, k + 3) for k in range(3)]
+
+    def message_passing(self, n_nodes, i, j, c, cycles, k_iters, trace=False):
+        t = self.torch
+        i, j, c = self._graph(i, j, c)
+        cyc = [_dev(t.as_tensor(x, device=self.device).reshape(-1), t.int32, t) for x in cycles]
+        n3, n4, n5 = cyc[0].numel() // 3, cyc[1].numel() // 4, cyc[2].numel() // 5
+        cap = i.numel() + n4 + 2 * n5
+        io, jo, co = self._empty(cap, t.int32), self._empty(cap, t.int32), self._empty(cap, t.float32)
+        mo, lb = C.c_int64(0), C.c_double(0.0)
+        tr = (C.c_double * (k_iters + 1))() if trace else None
+        st = self.lib.rama_message_passing(self.ctx, n_nodes, i.numel(), i.data_ptr(), j.data_ptr(), c.data_ptr(),
+                                           cyc[0].data_ptr(), n3, cyc[1].data_ptr(), n4, cyc[2].data_ptr(), n5,
+                                           k_iters, cap, io.data_ptr(), jo.data_ptr(), co.data_ptr(),
+                                           C.byref(mo), C.byref(lb), tr)
+        self._check(st, "rama_message_passing")
+        k = mo.value
+        return dict(i=io[:k], j=jo[:k], c=co[:k], lower_bound=lb.value,
+                    lb_trace=None if tr is None else list(tr))
+
+    def contract(self, n_nodes, i, j, c, params=None, repeat=1, want_diag=True):
+        t = self.torch
+        i, j, c = self._graph(i, j, c)
+        params = params or default_params()
+        m = i.numel()
+        mapping = self._empty(n_nodes, t.int32)
+        io, jo, co = self._empty(m, t.int32), self._empty(m, t.int32), self._empty(m, t.float32)
+        diag = self._empty(n_nodes, t.float32) if want_diag else None
+        nn, mo = C.c_int32(0), C.c_int64(0)
+        st = self.lib.rama_contract(self.ctx, n_nodes, m, i.data_ptr(), j.data_ptr(), c.data_ptr(), C.byref(params),
+                                    repeat, mapping.data_ptr(), io.data_ptr(), jo.data_ptr(), co.data_ptr(),
+                                    diag.data_ptr() if want_diag else None, C.byref(nn), C.byref(mo))
+        self._check(st, "rama_contract")
+        k = mo.value
+        return dict(mapping=mapping[:n_nodes], i=io[:k], j=jo[:k], c=co[:k],
+                    diag=diag[: nn.value] if want_diag else None, n_nodes=nn.value)
+
+    def solve(self, n_nodes, i, j, c, params=None):
+        t = self.torch
+        i, j, c = self._graph(i, j, c)
+        params = params or default_params()
+        labels = self._empty(n_nodes, t.int32)
+        primal, lb = C.c_double(0.0), C.c_double(0.0)
+        stats = RamaStats()
+        st = self.lib.rama_solve(self.ctx, n_nodes, i.numel(), i.data_ptr(), j.data_ptr(), c.data_ptr(),
+                                 C.byref(params), labels.data_ptr(), C.byref(primal), C.byref(lb), C.byref(stats))
+        self._check(st, "rama_solve")
+        return dict(labels=labels[:n_nodes], primal=primal.value, lower_bound=lb.value,
+                    rounds=stats.rounds, n_clusters=stats.n_clusters,
+                    n_cycles_first=list(stats.n_cycles_first), n_triangles_first=stats.n_triangles_first,
+                    n_edges_aug_first=stats.n_edges_aug_first, n_edges_final=stats.n_edges_final,
+                    ms=dict(total=stats.ms_total, cycles=stats.ms_cycles, dual=stats.ms_dual,
+                            contract=stats.ms_contract, other=stats.ms_other))

@@ -1,0 +1,316 @@
+// C ABI: argument checks, the four entry points, and the primal-dual loop
+// (paper algorithm "Primal-Dual Multicut").  Host code here only sequences the stage kernels.
+#include <chrono>
+
+#include "prim.h"
+
+using namespace rama;
+
+namespace {
+
+double now_ms()
+{
+    using clk = std::chrono::steady_clock;
+    return std::chrono::duration<double, std::milli>(clk::now().time_since_epoch()).count();
+}
+
+rama_status finish(Ctx &ctx, rama_status st)
+{
+    hipError_t e = hipStreamSynchronize(ctx.stream);
+    if (st == RAMA_OK && e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(ctx, RAMA_ERR_HIP, std::string("stream synchronize: ") + hipGetErrorString(e));
+    }
+    return st;
+}
+
+rama_status copy_out(Ctx &ctx, void *dst, const void *src, size_t bytes)
+{
+    if (bytes == 0) return RAMA_OK;
+    HIP_TRY(ctx, hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, ctx.stream));
+    return RAMA_OK;
+}
+
+__global__ __launch_bounds__(kBlock) void k_iota32(size_t n, int32_t *p)
+{
+    size_t v = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (v < n) p[v] = (int32_t)v;
+}
+
+// f <- f' o f  (last line of the loop body of "Primal-Dual Multicut")
+__global__ __launch_bounds__(kBlock) void k_compose(size_t n, int32_t *f, const int32_t *fprime)
+{
+    size_t v = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (v < n) f[v] = fprime[f[v]];
+}
+
+__global__ __launch_bounds__(kBlock) void k_cluster_min(size_t n, const int32_t *f, int32_t *first)
+{
+    size_t v = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (v < n) atomicMin(&first[f[v]], (int32_t)v);
+}
+
+__global__ __launch_bounds__(kBlock) void k_labels(size_t n, const int32_t *f, const int32_t *first, int32_t *labels)
+{
+    size_t v = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (v < n) labels[v] = first[f[v]];
+}
+
+// objective of eq. 2 on the caller's edge list
+struct CutCost {
+    const int32_t *i, *j;
+    const float *c;
+    const int32_t *labels;
+    __device__ __forceinline__ double operator()(size_t e) const
+    {
+        return labels[i[e]] != labels[j[e]] ? (double)c[e] : 0.0;
+    }
+};
+
+bool bad_graph_args(int32_t n, int64_t m, const void *i, const void *j, const void *c)
+{
+    return n < 0 || m < 0 || (m > 0 && (!i || !j || !c));
+}
+
+rama_status solve_impl(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const int32_t *j, const float *c,
+                       const rama_params &P, int32_t *labels, double *primal, double *lower_bound, rama_stats *stats)
+{
+    const double t_begin = now_ms();
+    double t_cyc = 0, t_dual = 0, t_con = 0;
+    rama_stats S;
+    memset(&S, 0, sizeof S);
+    Graph g;
+    RAMA_TRY(canonicalise(ctx, n, m, i, j, c, g));
+    Buf<int32_t> f;
+    RAMA_TRY(f.alloc(ctx, (size_t)(n > 0 ? n : 1)));
+    k_iota32<<<grid_for((size_t)n), kBlock, 0, ctx.stream>>>((size_t)n, f.get());
+    LAUNCH_TRY(ctx, "iota");
+    double lb = 0.0;
+    bool have_lb = false;
+    int32_t n_cur = n;
+    for (int round = 1; P.max_rounds <= 0 || round <= P.max_rounds; ++round) {
+        const int lmax = round == 1 ? P.max_cycle_len_first : P.max_cycle_len_later;
+        const int k = round == 1 ? P.mp_iters_first : P.mp_iters_later;
+        double t0 = now_ms();
+        CycleLists cyc;
+        if (lmax >= 3 && k > 0) RAMA_TRY(find_cycles(ctx, g, lmax, false, cyc));
+        RAMA_TRY(finish(ctx, RAMA_OK));
+        double t1 = now_ms();
+        t_cyc += t1 - t0;
+        if (round == 1) for (int q = 0; q < 3; ++q) S.n_cycles_first[q] = cyc.n[q];
+        if (cyc.n[0] + cyc.n[1] + cyc.n[2] > 0) {
+            Graph aug;
+            DualInfo info;
+            double lbr = 0.0;
+            RAMA_TRY(dual_update(ctx, g, cyc.v[0].get(), cyc.n[0], cyc.v[1].get(), cyc.n[1], cyc.v[2].get(), cyc.n[2],
+                                 false, k, aug, round == 1 ? &lbr : nullptr, nullptr, &info));
+            if (round == 1) { lb = lbr; have_lb = true; S.n_triangles_first = info.n_triangles; }
+            g = std::move(aug);
+        }
+        for (int q = 0; q < 3; ++q) cyc.v[q].reset();
+        if (round == 1) {
+            if (!have_lb) { RAMA_TRY(negative_cost_sum(ctx, g.c.get(), g.m, &lb)); have_lb = true; }
+            S.n_edges_aug_first = g.m;
+        }
+        RAMA_TRY(finish(ctx, RAMA_OK));
+        double t2 = now_ms();
+        t_dual += t2 - t1;
+        Buf<int32_t> fprime;
+        Graph gn;
+        int32_t n_new = n_cur;
+        int64_t ns = 0;
+        RAMA_TRY(contract_once(ctx, g, P.contract_threshold, P.matching_rounds_cap, fprime, n_new, gn, ns));
+        S.rounds = round;
+        if (ns > 0) {
+            k_compose<<<grid_for((size_t)n), kBlock, 0, ctx.stream>>>((size_t)n, f.get(), fprime.get());
+            LAUNCH_TRY(ctx, "compose");
+            g = std::move(gn);
+            n_cur = n_new;
+        }
+        RAMA_TRY(finish(ctx, RAMA_OK));
+        t_con += now_ms() - t2;
+        if (ns == 0) break;
+    }
+    // labels: smallest original node per cluster; primal cost on the caller's costs
+    {
+        Buf<int32_t> first;
+        RAMA_TRY(first.alloc(ctx, (size_t)(n_cur > 0 ? n_cur : 1)));
+        RAMA_TRY(fill<int32_t>(ctx, first.get(), 0x7FFFFFFF, (size_t)n_cur));
+        if (n > 0) {
+            k_cluster_min<<<grid_for((size_t)n), kBlock, 0, ctx.stream>>>((size_t)n, f.get(), first.get());
+            LAUNCH_TRY(ctx, "cluster_min");
+            k_labels<<<grid_for((size_t)n), kBlock, 0, ctx.stream>>>((size_t)n, f.get(), first.get(), labels);
+            LAUNCH_TRY(ctx, "labels");
+        }
+    }
+    if (primal) {
+        Buf<double> d;
+        RAMA_TRY(d.alloc(ctx, 1));
+        RAMA_TRY(device_sum(ctx, CutCost{i, j, c, labels}, (size_t)m, d.get(), false));
+        RAMA_TRY(read_back(ctx, primal, d.get(), 8));
+    }
+    if (lower_bound) *lower_bound = lb;
+    RAMA_TRY(finish(ctx, RAMA_OK));
+    S.n_clusters = n_cur;
+    S.n_edges_final = g.m;
+    S.ms_total = now_ms() - t_begin;
+    S.ms_cycles = t_cyc; S.ms_dual = t_dual; S.ms_contract = t_con;
+    S.ms_other = S.ms_total - t_cyc - t_dual - t_con;
+    if (stats) *stats = S;
+    return RAMA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+rama_status rama_create(rama_ctx **out, void *hip_stream)
+{
+    if (!out) return RAMA_ERR_INVALID_ARG;
+    *out = nullptr;
+    rama_ctx *ctx = new (std::nothrow) rama_ctx();
+    if (!ctx) return RAMA_ERR_OOM;
+    ctx->stream = (hipStream_t)hip_stream;
+    hipError_t e = hipGetDevice(&ctx->device);
+    if (e == hipSuccess) e = hipHostMalloc(&ctx->pinned, rama_ctx::kPinnedBytes, hipHostMallocDefault);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        fprintf(stderr, "rama_create: %s\n", hipGetErrorString(e));
+        delete ctx;
+        return RAMA_ERR_HIP;
+    }
+    *out = ctx;
+    return RAMA_OK;
+}
+
+rama_status rama_destroy(rama_ctx *ctx)
+{
+    if (!ctx) return RAMA_OK;
+    (void)hipStreamSynchronize(ctx->stream);
+    ctx->pool.destroy();
+    if (ctx->pinned) (void)hipHostFree(ctx->pinned);
+    delete ctx;
+    return RAMA_OK;
+}
+
+const char *rama_last_error(const rama_ctx *ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+void rama_params_default(rama_params *p)
+{
+    if (!p) return;
+    p->max_cycle_len_first = 5;
+    p->max_cycle_len_later = 3;
+    p->mp_iters_first = 10;
+    p->mp_iters_later = 5;
+    p->matching_rounds_cap = 32;
+    p->contract_threshold = 0.0f;
+    p->max_rounds = 0;
+}
+
+int64_t rama_workspace_bytes(const rama_ctx *ctx) { return ctx ? (int64_t)ctx->pool.total() : 0; }
+
+rama_status rama_find_conflicted_cycles(rama_ctx *ctx, int32_t n_nodes, int64_t n_edges, const int32_t *i,
+                                        const int32_t *j, const float *c, int32_t max_cycle_len, int64_t cap3,
+                                        int64_t cap4, int64_t cap5, int32_t *cycles3, int32_t *cycles4,
+                                        int32_t *cycles5, int64_t *n_cycles_out)
+{
+    if (!ctx) return RAMA_ERR_INVALID_ARG;
+    if (bad_graph_args(n_nodes, n_edges, i, j, c) || !n_cycles_out || max_cycle_len < 3 || max_cycle_len > 5 ||
+        cap3 < 0 || cap4 < 0 || cap5 < 0 || (cap3 > 0 && !cycles3) || (cap4 > 0 && !cycles4) || (cap5 > 0 && !cycles5))
+        return fail(*ctx, RAMA_ERR_INVALID_ARG, "rama_find_conflicted_cycles: bad arguments");
+    auto body = [&]() -> rama_status {
+        Graph g;
+        RAMA_TRY(canonicalise(*ctx, n_nodes, n_edges, i, j, c, g));
+        CycleLists cnt;
+        RAMA_TRY(find_cycles(*ctx, g, max_cycle_len, true, cnt));
+        for (int q = 0; q < 3; ++q) n_cycles_out[q] = cnt.n[q];
+        if (cnt.n[0] > cap3 || cnt.n[1] > cap4 || cnt.n[2] > cap5)
+            return fail(*ctx, RAMA_ERR_CAPACITY, "cycle output lists are too small; needed sizes written to n_cycles_out");
+        if (cnt.n[0] + cnt.n[1] + cnt.n[2] == 0) return RAMA_OK;
+        CycleLists cyc;
+        RAMA_TRY(find_cycles(*ctx, g, max_cycle_len, false, cyc));
+        int32_t *dst[3] = {cycles3, cycles4, cycles5};
+        for (int q = 0; q < 3; ++q)
+            RAMA_TRY(copy_out(*ctx, dst[q], cyc.v[q].get(), (size_t)cyc.n[q] * (q + 3) * 4));
+        return finish(*ctx, RAMA_OK);
+    };
+    return finish(*ctx, body());
+}
+
+rama_status rama_message_passing(rama_ctx *ctx, int32_t n_nodes, int64_t n_edges, const int32_t *i, const int32_t *j,
+                                 const float *c, const int32_t *cycles3, int64_t n3, const int32_t *cycles4,
+                                 int64_t n4, const int32_t *cycles5, int64_t n5, int32_t k_iters, int64_t edge_cap,
+                                 int32_t *i_out, int32_t *j_out, float *c_out, int64_t *n_edges_out,
+                                 double *lower_bound, double *lb_trace)
+{
+    if (!ctx) return RAMA_ERR_INVALID_ARG;
+    if (bad_graph_args(n_nodes, n_edges, i, j, c) || !n_edges_out || k_iters < 0 || edge_cap < 0 || n3 < 0 || n4 < 0 ||
+        n5 < 0 || (edge_cap > 0 && (!i_out || !j_out || !c_out)))
+        return fail(*ctx, RAMA_ERR_INVALID_ARG, "rama_message_passing: bad arguments");
+    auto body = [&]() -> rama_status {
+        Graph g, out;
+        RAMA_TRY(canonicalise(*ctx, n_nodes, n_edges, i, j, c, g));
+        RAMA_TRY(dual_update(*ctx, g, cycles3, n3, cycles4, n4, cycles5, n5, true, k_iters, out, lower_bound, lb_trace,
+                             nullptr));
+        *n_edges_out = out.m;
+        if (out.m > edge_cap)
+            return fail(*ctx, RAMA_ERR_CAPACITY, "edge output buffers are too small; needed size written to n_edges_out");
+        RAMA_TRY(copy_out(*ctx, i_out, out.i.get(), (size_t)out.m * 4));
+        RAMA_TRY(copy_out(*ctx, j_out, out.j.get(), (size_t)out.m * 4));
+        RAMA_TRY(copy_out(*ctx, c_out, out.c.get(), (size_t)out.m * 4));
+        return finish(*ctx, RAMA_OK);
+    };
+    return finish(*ctx, body());
+}
+
+rama_status rama_contract(rama_ctx *ctx, int32_t n_nodes, int64_t n_edges, const int32_t *i, const int32_t *j,
+                          const float *c, const rama_params *params, int32_t repeat, int32_t *mapping, int32_t *i_out,
+                          int32_t *j_out, float *c_out, float *diag_out, int32_t *n_nodes_out, int64_t *n_edges_out)
+{
+    if (!ctx) return RAMA_ERR_INVALID_ARG;
+    if (bad_graph_args(n_nodes, n_edges, i, j, c) || !params || !n_nodes_out || !n_edges_out ||
+        (n_nodes > 0 && !mapping) || (n_edges > 0 && (!i_out || !j_out || !c_out)))
+        return fail(*ctx, RAMA_ERR_INVALID_ARG, "rama_contract: bad arguments");
+    auto body = [&]() -> rama_status {
+        Graph g0, g;
+        RAMA_TRY(canonicalise(*ctx, n_nodes, n_edges, i, j, c, g0));
+        k_iota32<<<grid_for((size_t)n_nodes), kBlock, 0, ctx->stream>>>((size_t)n_nodes, mapping);
+        LAUNCH_TRY(*ctx, "iota");
+        const Graph *cur = &g0;
+        int32_t n_cur = n_nodes;
+        for (;;) {
+            Buf<int32_t> fprime;
+            Graph gn;
+            int32_t n_new = n_cur;
+            int64_t ns = 0;
+            RAMA_TRY(contract_once(*ctx, *cur, params->contract_threshold, params->matching_rounds_cap, fprime, n_new, gn, ns));
+            if (ns == 0) break;
+            k_compose<<<grid_for((size_t)n_nodes), kBlock, 0, ctx->stream>>>((size_t)n_nodes, mapping, fprime.get());
+            LAUNCH_TRY(*ctx, "compose");
+            g = std::move(gn);
+            cur = &g;
+            n_cur = n_new;
+            if (repeat) break;
+        }
+        *n_nodes_out = n_cur;
+        *n_edges_out = cur->m;
+        RAMA_TRY(copy_out(*ctx, i_out, cur->i.get(), (size_t)cur->m * 4));
+        RAMA_TRY(copy_out(*ctx, j_out, cur->j.get(), (size_t)cur->m * 4));
+        RAMA_TRY(copy_out(*ctx, c_out, cur->c.get(), (size_t)cur->m * 4));
+        if (diag_out) RAMA_TRY(contraction_diagonal(*ctx, g0, mapping, n_cur, diag_out));
+        return finish(*ctx, RAMA_OK);
+    };
+    return finish(*ctx, body());
+}
+
+rama_status rama_solve(rama_ctx *ctx, int32_t n_nodes, int64_t n_edges, const int32_t *i, const int32_t *j,
+                       const float *c, const rama_params *params, int32_t *labels, double *primal_cost,
+                       double *lower_bound, rama_stats *stats)
+{
+    if (!ctx) return RAMA_ERR_INVALID_ARG;
+    if (bad_graph_args(n_nodes, n_edges, i, j, c) || !params || (n_nodes > 0 && !labels))
+        return fail(*ctx, RAMA_ERR_INVALID_ARG, "rama_solve: bad arguments");
+    return finish(*ctx, solve_impl(*ctx, n_nodes, n_edges, i, j, c, *params, labels, primal_cost, lower_bound, stats));
+}
+
+}  // extern "C"

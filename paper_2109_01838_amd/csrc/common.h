@@ -1,0 +1,223 @@
+// Shared host-side plumbing of the library: context, cached device workspace, status handling.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <utility>
+#include <vector>
+
+#include "../../include/rama.h"
+
+namespace rama {
+
+constexpr int kBlock = 256;  // threads per workgroup everywhere: four wave64
+
+// Device memory cache.  All work of one ctx is enqueued on one stream, so a block released by
+// an earlier step can be handed to a later step without synchronisation.
+class Pool {
+public:
+    hipError_t alloc(size_t bytes, void **out)
+    {
+        if (bytes == 0) bytes = 256;
+        bytes = (bytes + 255) & ~size_t(255);
+        int best = -1;
+        for (int k = 0; k < (int)free_.size(); ++k)
+            if (free_[k].bytes >= bytes && (best < 0 || free_[k].bytes < free_[best].bytes)) best = k;
+        if (best >= 0 && free_[best].bytes <= 2 * bytes + (size_t(1) << 20)) {
+            *out = free_[best].ptr;
+            used_.push_back(free_[best]);
+            free_.erase(free_.begin() + best);
+            return hipSuccess;
+        }
+        void *p = nullptr;
+        hipError_t e = hipMalloc(&p, bytes);
+        if (e != hipSuccess) {  // give cached blocks back to the driver and retry once
+            (void)hipGetLastError();
+            trim();
+            e = hipMalloc(&p, bytes);
+            if (e != hipSuccess) return e;
+        }
+        total_ += bytes;
+        used_.push_back({p, bytes});
+        *out = p;
+        return hipSuccess;
+    }
+    void release(void *p)
+    {
+        for (int k = (int)used_.size() - 1; k >= 0; --k)
+            if (used_[k].ptr == p) {
+                free_.push_back(used_[k]);
+                used_.erase(used_.begin() + k);
+                return;
+            }
+    }
+    void trim()
+    {
+        for (auto &b : free_) { (void)hipFree(b.ptr); total_ -= b.bytes; }
+        free_.clear();
+    }
+    void destroy()
+    {
+        trim();
+        for (auto &b : used_) { (void)hipFree(b.ptr); total_ -= b.bytes; }
+        used_.clear();
+    }
+    size_t total() const { return total_; }
+
+private:
+    struct Blk { void *ptr; size_t bytes; };
+    std::vector<Blk> free_, used_;
+    size_t total_ = 0;
+};
+
+}  // namespace rama
+
+struct rama_ctx {
+    hipStream_t stream = nullptr;
+    int device = 0;
+    rama::Pool pool;
+    std::string err;
+    void *pinned = nullptr;  // small pinned host block for scalar read-backs
+    static constexpr size_t kPinnedBytes = 4096;
+};
+
+namespace rama {
+
+using Ctx = rama_ctx;
+
+inline rama_status fail(Ctx &ctx, rama_status st, const std::string &msg)
+{
+    ctx.err = msg;
+    return st;
+}
+
+#define RAMA_TRY(expr)                                   \
+    do {                                                 \
+        rama_status _st = (expr);                        \
+        if (_st != RAMA_OK) return _st;                  \
+    } while (0)
+
+#define HIP_TRY(ctx, call)                                                                       \
+    do {                                                                                         \
+        hipError_t _e = (call);                                                                  \
+        if (_e != hipSuccess) {                                                                  \
+            (void)hipGetLastError();                                                             \
+            return ::rama::fail((ctx), _e == hipErrorOutOfMemory ? RAMA_ERR_OOM : RAMA_ERR_HIP,  \
+                                std::string(#call) + ": " + hipGetErrorString(_e));              \
+        }                                                                                        \
+    } while (0)
+
+// launch check: the launch itself can fail (bad configuration); kernel faults surface at the next sync
+#define LAUNCH_TRY(ctx, what) HIP_TRY(ctx, hipGetLastError())
+
+// RAII device array from the ctx pool
+template <typename T>
+class Buf {
+public:
+    Buf() = default;
+    Buf(const Buf &) = delete;
+    Buf &operator=(const Buf &) = delete;
+    Buf(Buf &&o) noexcept { steal(o); }
+    Buf &operator=(Buf &&o) noexcept
+    {
+        if (this != &o) { reset(); steal(o); }
+        return *this;
+    }
+    ~Buf() { reset(); }
+    rama_status alloc(Ctx &ctx, size_t count)
+    {
+        reset();
+        void *p = nullptr;
+        hipError_t e = ctx.pool.alloc(count * sizeof(T), &p);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(ctx, RAMA_ERR_OOM, "device allocation of " + std::to_string(count * sizeof(T)) + " bytes failed");
+        }
+        ctx_ = &ctx; ptr_ = (T *)p; count_ = count;
+        return RAMA_OK;
+    }
+    void reset()
+    {
+        if (ptr_) ctx_->pool.release(ptr_);
+        ptr_ = nullptr; count_ = 0; ctx_ = nullptr;
+    }
+    T *get() const { return ptr_; }
+    operator T *() const { return ptr_; }
+    size_t size() const { return count_; }
+    void swap(Buf &o) { std::swap(ctx_, o.ctx_); std::swap(ptr_, o.ptr_); std::swap(count_, o.count_); }
+
+private:
+    void steal(Buf &o) { ctx_ = o.ctx_; ptr_ = o.ptr_; count_ = o.count_; o.ptr_ = nullptr; o.count_ = 0; o.ctx_ = nullptr; }
+    Ctx *ctx_ = nullptr;
+    T *ptr_ = nullptr;
+    size_t count_ = 0;
+};
+
+inline unsigned grid_for(size_t n, int per_block = kBlock) { return (unsigned)((n + per_block - 1) / per_block); }
+
+// number of bits needed to write values in [0, n)
+inline int bits_for(uint64_t n)
+{
+    int b = 1;
+    while (b < 64 && (uint64_t(1) << b) < n) ++b;
+    return b;
+}
+
+// copy `bytes` from device to host and wait
+inline rama_status read_back(Ctx &ctx, void *host, const void *dev, size_t bytes)
+{
+    if (bytes <= Ctx::kPinnedBytes) {
+        HIP_TRY(ctx, hipMemcpyAsync(ctx.pinned, dev, bytes, hipMemcpyDeviceToHost, ctx.stream));
+        HIP_TRY(ctx, hipStreamSynchronize(ctx.stream));
+        memcpy(host, ctx.pinned, bytes);
+    } else {
+        HIP_TRY(ctx, hipMemcpyAsync(host, dev, bytes, hipMemcpyDeviceToHost, ctx.stream));
+        HIP_TRY(ctx, hipStreamSynchronize(ctx.stream));
+    }
+    return RAMA_OK;
+}
+
+// A canonical graph in device memory: i<j, sorted by (i,j), no duplicates.
+struct Graph {
+    int32_t n = 0;
+    int64_t m = 0;
+    Buf<int32_t> i, j;
+    Buf<float> c;
+};
+
+struct CycleLists {
+    int64_t n[3] = {0, 0, 0};
+    Buf<int32_t> v[3];  // [L*n[L-3]]
+};
+
+// ---- stage entry points on canonical device graphs (defined in the stage files) ----
+
+// a0: any edge list -> canonical graph
+rama_status canonicalise(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const int32_t *j, const float *c, Graph &out);
+
+// a1: conflicted cycles of lengths 3..max_len.  With count_only the lists stay empty.
+rama_status find_cycles(Ctx &ctx, const Graph &g, int max_len, bool count_only, CycleLists &out);
+
+// a2+a3: triangulate, k iterations of message passing; `out` = augmented graph with reduced costs
+struct DualInfo {
+    int64_t n_triangles = 0;
+};
+rama_status dual_update(Ctx &ctx, const Graph &g, const int32_t *c3, int64_t n3, const int32_t *c4, int64_t n4,
+                        const int32_t *c5, int64_t n5, bool validate_cycles, int k_iters, Graph &out,
+                        double *lower_bound, double *lb_trace, DualInfo *info);
+
+// a4..a6: one primal update.  fmap[n] -> [0,n_new); n_matched = |S|.  If |S|==0 nothing else is produced.
+rama_status contract_once(Ctx &ctx, const Graph &g, float tau, int rounds_cap, Buf<int32_t> &fmap, int32_t &n_new,
+                          Graph &out, int64_t &n_matched);
+
+// diagonal of K^T A K for a mapping F on canonical graph g: diag[a] = sum of edges with F(i)=F(j)=a
+rama_status contraction_diagonal(Ctx &ctx, const Graph &g, const int32_t *fmap, int32_t n_new, float *diag);
+
+// sum of min(0,c) over the edges, in double
+rama_status negative_cost_sum(Ctx &ctx, const float *c, int64_t m, double *out);
+
+}  // namespace rama

@@ -1,0 +1,462 @@
+// Steps a2 + a3: triangulation of the separated cycles, edge<->triangle incidence, and the
+// message-passing iterations (paper Sec. 3.2.1, eq. 5 and 6; Sec. 3.2.3, algorithm
+// "Parallel-Message-Passing").
+//
+// Triangulation (the paper only says that longer cycles are triangulated): fan from v0 --
+// triangles {v0,v_m,v_{m+1}}, chords (v0,v_m); unseen chords join the edge list with cost 0 and
+// the list stays canonical.  Triangles are the sorted set of distinct node triples u<v<w, keyed
+// as (edge id of (u,v), w); slots of a triangle are its edges (u,v),(u,w),(v,w).
+//
+// Message passing keeps c_e (reduced edge costs, eq. 6a) and c_t (triangle costs, eq. 6b).
+// One iteration = edges->triangles (every edge in N_e triangles hands each of them c_e/N_e and
+// drops to 0) + triangles->edges (six min-marginal updates with weights 1/3,1/2,1,1/2,1,1).
+// It runs as two kernels without atomics:
+//   triangle kernel: gathers the three shares, does the six updates in registers, writes c_t and
+//                    the three outgoing messages;
+//   edge kernel:     adds the messages of an edge in ascending triangle order (slot list built
+//                    once per round by a stable sort) and stores the next share c_e/N_e.
+#include "prim.h"
+
+namespace rama {
+
+namespace {
+
+// ---------------------------------------------------------------------------------------------
+// cycle access: one flat index space over the fan pieces of all cycles
+// ---------------------------------------------------------------------------------------------
+struct CycleSet {
+    const int32_t *c3, *c4, *c5;
+    int64_t n3, n4, n5;
+};
+
+// q-th chord: 4-cycles give one (v0,v2), 5-cycles two (v0,v2),(v0,v3)
+__device__ __forceinline__ void chord_of(const CycleSet &s, size_t q, int32_t &a, int32_t &b)
+{
+    if (q < (size_t)s.n4) {
+        const int32_t *v = s.c4 + 4 * q;
+        a = v[0]; b = v[2];
+    } else {
+        size_t r = q - (size_t)s.n4;
+        const int32_t *v = s.c5 + 5 * (r >> 1);
+        a = v[0]; b = v[2 + (r & 1)];
+    }
+}
+
+// q-th fan triangle (unsorted nodes)
+__device__ __forceinline__ void fan_triangle(const CycleSet &s, size_t q, int32_t &a, int32_t &b, int32_t &c)
+{
+    if (q < (size_t)s.n3) {
+        const int32_t *v = s.c3 + 3 * q;
+        a = v[0]; b = v[1]; c = v[2];
+        return;
+    }
+    q -= (size_t)s.n3;
+    if (q < 2 * (size_t)s.n4) {
+        const int32_t *v = s.c4 + 4 * (q >> 1);
+        int mm = 1 + (int)(q & 1);
+        a = v[0]; b = v[mm]; c = v[mm + 1];
+        return;
+    }
+    q -= 2 * (size_t)s.n4;
+    const int32_t *v = s.c5 + 5 * (q / 3);
+    int mm = 1 + (int)(q % 3);
+    a = v[0]; b = v[mm]; c = v[mm + 1];
+}
+
+__device__ __forceinline__ void sort3(int32_t &a, int32_t &b, int32_t &c)
+{
+    int32_t t;
+    if (a > b) { t = a; a = b; b = t; }
+    if (b > c) { t = b; b = c; c = t; }
+    if (a > b) { t = a; a = b; b = t; }
+}
+
+// every cycle: nodes in range and distinct, every cycle edge present in the graph
+__global__ __launch_bounds__(kBlock) void k_validate_cycles(CycleSet s, int32_t n, const int32_t *rowptr,
+                                                            const int32_t *j, int32_t *flag)
+{
+    size_t q = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    size_t total = (size_t)(s.n3 + s.n4 + s.n5);
+    if (q >= total) return;
+    const int32_t *v;
+    int L;
+    if (q < (size_t)s.n3) { v = s.c3 + 3 * q; L = 3; }
+    else if (q < (size_t)(s.n3 + s.n4)) { v = s.c4 + 4 * (q - s.n3); L = 4; }
+    else { v = s.c5 + 5 * (q - s.n3 - s.n4); L = 5; }
+    int32_t x[5];
+    bool bad = false;
+    for (int a = 0; a < L; ++a) {
+        x[a] = v[a];
+        if (x[a] < 0 || x[a] >= n) bad = true;
+        for (int b = 0; b < a; ++b) if (x[b] == x[a]) bad = true;
+    }
+    if (!bad)
+        for (int a = 0; a < L; ++a) {
+            int32_t p = x[a], r = x[(a + 1) % L];
+            if (find_edge_in_row(rowptr, j, min(p, r), max(p, r)) < 0) bad = true;
+        }
+    if (bad) *flag = 1;
+}
+
+__global__ __launch_bounds__(kBlock) void k_chord_keys(CycleSet s, size_t nch, int nbits, uint64_t *key)
+{
+    size_t q = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (q >= nch) return;
+    int32_t a, b;
+    chord_of(s, q, a, b);
+    key[q] = ((uint64_t)(uint32_t)min(a, b) << nbits) | (uint32_t)max(a, b);
+}
+
+// first-of-run flag that also requires the chord to be absent from the graph
+struct NewChordFlag {
+    const uint64_t *key;
+    const int32_t *rowptr, *j;
+    int nbits;
+    __device__ __forceinline__ uint32_t operator()(size_t q) const
+    {
+        uint64_t k = key[q];
+        if (q > 0 && key[q - 1] == k) return 0u;
+        int32_t u = (int32_t)(k >> nbits), v = (int32_t)(k & ((1ull << nbits) - 1ull));
+        return find_edge_in_row(rowptr, j, u, v) < 0 ? 1u : 0u;
+    }
+};
+
+// compacts the new chords and records, for each, the number of graph edges that precede it
+__global__ __launch_bounds__(kBlock) void k_emit_chords(size_t nch, const uint64_t *key, const uint32_t *pos,
+                                                        const int32_t *rowptr, const int32_t *j, int nbits,
+                                                        int32_t *ci, int32_t *cj, int32_t *before)
+{
+    size_t q = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (q >= nch) return;
+    if (pos[q] == pos[q + 1]) return;
+    uint64_t k = key[q];
+    int32_t u = (int32_t)(k >> nbits), v = (int32_t)(k & ((1ull << nbits) - 1ull));
+    int32_t lo = rowptr[u], hi = rowptr[u + 1];
+    while (lo < hi) {
+        int32_t mid = lo + ((hi - lo) >> 1);
+        if (j[mid] < v) lo = mid + 1; else hi = mid;
+    }
+    uint32_t p = pos[q];
+    ci[p] = u; cj[p] = v; before[p] = lo;
+}
+
+// merge of the canonical edge list with the (sorted, disjoint) new chords.
+// ins[e] = number of chords placed before graph edge e  (row bounds of `before`)
+__global__ __launch_bounds__(kBlock) void k_merge_edges(size_t m, const int32_t *i, const int32_t *j, const float *c,
+                                                        const int32_t *ins, size_t nnew, const int32_t *ci,
+                                                        const int32_t *cj, const int32_t *before, int32_t *io,
+                                                        int32_t *jo, float *co)
+{
+    size_t e = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (e < m) {
+        size_t d = e + (size_t)ins[e + 1];
+        io[d] = i[e]; jo[d] = j[e]; co[d] = c[e];
+    }
+    if (e < nnew) {
+        size_t d = (size_t)before[e] + e;
+        io[d] = ci[e]; jo[d] = cj[e]; co[d] = 0.0f;
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_triangle_keys(CycleSet s, size_t nt, const int32_t *rowptr,
+                                                          const int32_t *j, int nbits, uint64_t *key, int32_t *flag)
+{
+    size_t q = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (q >= nt) return;
+    int32_t a, b, c;
+    fan_triangle(s, q, a, b, c);
+    sort3(a, b, c);
+    int32_t e0 = find_edge_in_row(rowptr, j, a, b);
+    if (e0 < 0) { *flag = 1; e0 = 0; }
+    key[q] = ((uint64_t)(uint32_t)e0 << nbits) | (uint32_t)c;
+}
+
+struct HeadFlag64 {
+    const uint64_t *key;
+    __device__ __forceinline__ uint32_t operator()(size_t e) const { return (e == 0 || key[e] != key[e - 1]) ? 1u : 0u; }
+};
+
+// unique triangles -> their three edge ids, and the (edge, slot) pairs for the incidence sort
+__global__ __launch_bounds__(kBlock) void k_triangle_edges(size_t nt, const uint64_t *key, const uint32_t *pos,
+                                                           const int32_t *rowptr, const int32_t *i, const int32_t *j,
+                                                           int nbits, int32_t *tri_edge, uint32_t *skey, uint32_t *sval,
+                                                           int32_t *flag)
+{
+    size_t q = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (q >= nt) return;
+    if (pos[q] == pos[q + 1]) return;
+    uint64_t k = key[q];
+    int32_t e0 = (int32_t)(k >> nbits), w = (int32_t)(k & ((1ull << nbits) - 1ull));
+    int32_t u = i[e0], v = j[e0];
+    int32_t e1 = find_edge_in_row(rowptr, j, u, w);
+    int32_t e2 = find_edge_in_row(rowptr, j, v, w);
+    if (e1 < 0 || e2 < 0) { *flag = 1; e1 = max(e1, 0); e2 = max(e2, 0); }
+    size_t t = pos[q];
+    tri_edge[3 * t + 0] = e0; tri_edge[3 * t + 1] = e1; tri_edge[3 * t + 2] = e2;
+    for (int sl = 0; sl < 3; ++sl) {
+        skey[3 * t + sl] = (uint32_t)tri_edge[3 * t + sl];
+        sval[3 * t + sl] = (uint32_t)(3 * t + sl);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// message passing
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void k_edge_init(size_t m, const float *ce, const int32_t *slot_ptr, float *share)
+{
+    size_t e = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (e >= m) return;
+    int32_t cnt = slot_ptr[e + 1] - slot_ptr[e];
+    share[e] = cnt > 0 ? ce[e] / (float)cnt : 0.0f;
+}
+
+// costs of the four non-trivial labelings of M_T = {000,110,101,011,111}
+struct TriCosts {
+    float l110, l101, l011, l111;
+};
+__device__ __forceinline__ TriCosts labeling_costs(float a, float b, float c)
+{
+    TriCosts r;
+    r.l110 = a + b;
+    r.l101 = a + c;
+    r.l011 = b + c;
+    r.l111 = (a + b) + c;
+    return r;
+}
+// min-marginal of slot s: min over labelings that cut s minus min over those that do not
+__device__ __forceinline__ float min_marginal(float a, float b, float c, int s)
+{
+    TriCosts l = labeling_costs(a, b, c);
+    if (s == 0) return fminf(fminf(l.l110, l.l101), l.l111) - fminf(0.0f, l.l011);
+    if (s == 1) return fminf(fminf(l.l110, l.l011), l.l111) - fminf(0.0f, l.l101);
+    return fminf(fminf(l.l101, l.l011), l.l111) - fminf(0.0f, l.l110);
+}
+
+__global__ __launch_bounds__(kBlock) void k_triangle_update(size_t T, const int32_t *tri_edge, const float *share,
+                                                            float *ct, float *msg)
+{
+    size_t t = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (t >= T) return;
+    const int32_t e0 = tri_edge[3 * t], e1 = tri_edge[3 * t + 1], e2 = tri_edge[3 * t + 2];
+    // edges -> triangles
+    float a = ct[3 * t] + share[e0];
+    float b = ct[3 * t + 1] + share[e1];
+    float c = ct[3 * t + 2] + share[e2];
+    // triangles -> edges
+    const float third = 1.0f / 3.0f, half = 1.0f / 2.0f;
+    float oa = 0.0f, ob = 0.0f, oc = 0.0f, d;
+    d = third * min_marginal(a, b, c, 0); a = a - d; oa = oa + d;
+    d = half * min_marginal(a, b, c, 1);  b = b - d; ob = ob + d;
+    d = 1.0f * min_marginal(a, b, c, 2);  c = c - d; oc = oc + d;
+    d = half * min_marginal(a, b, c, 0);  a = a - d; oa = oa + d;
+    d = 1.0f * min_marginal(a, b, c, 1);  b = b - d; ob = ob + d;
+    d = 1.0f * min_marginal(a, b, c, 0);  a = a - d; oa = oa + d;
+    ct[3 * t] = a; ct[3 * t + 1] = b; ct[3 * t + 2] = c;
+    msg[3 * t] = oa; msg[3 * t + 1] = ob; msg[3 * t + 2] = oc;
+}
+
+__global__ __launch_bounds__(kBlock) void k_edge_update(size_t m, const int32_t *slot_ptr, const uint32_t *slot,
+                                                        const float *msg, float *ce, float *share)
+{
+    size_t e = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (e >= m) return;
+    int32_t p0 = slot_ptr[e], p1 = slot_ptr[e + 1];
+    if (p0 == p1) return;                  // edge in no triangle keeps its cost
+    float acc = 0.0f;
+    for (int32_t p = p0; p < p1; ++p) acc = acc + msg[slot[p]];
+    ce[e] = acc;
+    share[e] = acc / (float)(p1 - p0);
+}
+
+struct EdgeLB {
+    const float *ce;
+    __device__ __forceinline__ double operator()(size_t e) const { float w = ce[e]; return w < 0.0f ? (double)w : 0.0; }
+};
+struct TriLB {
+    const float *ct;
+    __device__ __forceinline__ double operator()(size_t t) const
+    {
+        TriCosts l = labeling_costs(ct[3 * t], ct[3 * t + 1], ct[3 * t + 2]);
+        return (double)fminf(fminf(fminf(0.0f, l.l110), fminf(l.l101, l.l011)), l.l111);
+    }
+};
+
+// LB(lambda), eq. 5.  After a full iteration c_e and c_t are the stored state.
+rama_status lower_bound_now(Ctx &ctx, const float *ce, size_t m, const float *ct, size_t T, double *dev_out)
+{
+    RAMA_TRY(device_sum(ctx, EdgeLB{ce}, m, dev_out, false));
+    if (T > 0) RAMA_TRY(device_sum(ctx, TriLB{ct}, T, dev_out, true));
+    return RAMA_OK;
+}
+
+rama_status copy_graph(Ctx &ctx, const Graph &g, Graph &out)
+{
+    out.n = g.n; out.m = g.m;
+    size_t m = (size_t)(g.m > 0 ? g.m : 1);
+    RAMA_TRY(out.i.alloc(ctx, m));
+    RAMA_TRY(out.j.alloc(ctx, m));
+    RAMA_TRY(out.c.alloc(ctx, m));
+    if (g.m > 0) {
+        HIP_TRY(ctx, hipMemcpyAsync(out.i.get(), g.i.get(), (size_t)g.m * 4, hipMemcpyDeviceToDevice, ctx.stream));
+        HIP_TRY(ctx, hipMemcpyAsync(out.j.get(), g.j.get(), (size_t)g.m * 4, hipMemcpyDeviceToDevice, ctx.stream));
+        HIP_TRY(ctx, hipMemcpyAsync(out.c.get(), g.c.get(), (size_t)g.m * 4, hipMemcpyDeviceToDevice, ctx.stream));
+    }
+    return RAMA_OK;
+}
+
+}  // namespace
+
+rama_status dual_update(Ctx &ctx, const Graph &g, const int32_t *c3, int64_t n3, const int32_t *c4, int64_t n4,
+                        const int32_t *c5, int64_t n5, bool validate_cycles, int k_iters, Graph &out,
+                        double *lower_bound, double *lb_trace, DualInfo *info)
+{
+    if (n3 < 0 || n4 < 0 || n5 < 0 || k_iters < 0) return fail(ctx, RAMA_ERR_INVALID_ARG, "message passing: negative count");
+    if ((n3 > 0 && !c3) || (n4 > 0 && !c4) || (n5 > 0 && !c5))
+        return fail(ctx, RAMA_ERR_INVALID_ARG, "message passing: null cycle list");
+    const size_t m = (size_t)g.m;
+    const size_t nfan = (size_t)n3 + 2 * (size_t)n4 + 3 * (size_t)n5;
+    const size_t nch = (size_t)n4 + 2 * (size_t)n5;
+    if (3 * nfan >= (size_t(1) << 31) || m + nch >= (size_t(1) << 31))
+        return fail(ctx, RAMA_ERR_CAPACITY, "triangle slots or augmented edges reach 2^31");
+    if (info) info->n_triangles = 0;
+    Buf<double> lb_dev;
+    RAMA_TRY(lb_dev.alloc(ctx, 1));
+    if (nfan == 0 || m == 0) {
+        if (nfan > 0) return fail(ctx, RAMA_ERR_BAD_GRAPH, "cycles given for a graph without edges");
+        RAMA_TRY(copy_graph(ctx, g, out));
+        double lb = 0.0;
+        if (lower_bound || lb_trace) RAMA_TRY(negative_cost_sum(ctx, g.c.get(), g.m, &lb));
+        if (lower_bound) *lower_bound = lb;
+        if (lb_trace) for (int k = 0; k <= k_iters; ++k) lb_trace[k] = lb;
+        return RAMA_OK;
+    }
+    const int32_t n = g.n;
+    const int nbits = bits_for((uint64_t)n);
+    CycleSet cs{c3, c4, c5, n3, n4, n5};
+    Buf<int32_t> flag;
+    RAMA_TRY(flag.alloc(ctx, 1));
+    RAMA_TRY(fill<int32_t>(ctx, flag.get(), 0, 1));
+    // rows of the canonical edge list (upper CSR)
+    Buf<int32_t> rowptr;
+    RAMA_TRY(rowptr.alloc(ctx, (size_t)n + 1));
+    RAMA_TRY((row_bounds<int32_t, int32_t>(ctx, g.i.get(), m, n, rowptr.get())));
+    if (validate_cycles) {
+        k_validate_cycles<<<grid_for((size_t)(n3 + n4 + n5)), kBlock, 0, ctx.stream>>>(cs, n, rowptr.get(), g.j.get(),
+                                                                                     flag.get());
+        LAUNCH_TRY(ctx, "validate_cycles");
+        int32_t hf = 0;
+        RAMA_TRY(read_back(ctx, &hf, flag.get(), 4));
+        if (hf) return fail(ctx, RAMA_ERR_BAD_GRAPH, "a cycle has repeated / out-of-range nodes or uses an edge that is not in the graph");
+    }
+    // ---- chords -> augmented edge list -------------------------------------------------------
+    Graph aug;
+    aug.n = n;
+    uint32_t nnew = 0;
+    if (nch > 0) {
+        Buf<uint64_t> ckey;
+        RAMA_TRY(ckey.alloc(ctx, nch));
+        k_chord_keys<<<grid_for(nch), kBlock, 0, ctx.stream>>>(cs, nch, nbits, ckey.get());
+        LAUNCH_TRY(ctx, "chord_keys");
+        RAMA_TRY((radix_sort_keys<uint64_t>(ctx, ckey, nch, 2 * nbits)));
+        Buf<uint32_t> cpos;
+        RAMA_TRY(cpos.alloc(ctx, nch + 1));
+        RAMA_TRY((exclusive_scan<uint32_t>(ctx, NewChordFlag{ckey.get(), rowptr.get(), g.j.get(), nbits}, cpos.get(), nch)));
+        RAMA_TRY(read_back(ctx, &nnew, cpos.get() + nch, 4));
+        if (nnew > 0) {
+            Buf<int32_t> ci, cj, before, ins;
+            RAMA_TRY(ci.alloc(ctx, nnew));
+            RAMA_TRY(cj.alloc(ctx, nnew));
+            RAMA_TRY(before.alloc(ctx, nnew));
+            RAMA_TRY(ins.alloc(ctx, m + 2));
+            k_emit_chords<<<grid_for(nch), kBlock, 0, ctx.stream>>>(nch, ckey.get(), cpos.get(), rowptr.get(), g.j.get(),
+                                                                   nbits, ci.get(), cj.get(), before.get());
+            LAUNCH_TRY(ctx, "emit_chords");
+            // ins[v] = number of chords with before < v ; chords placed before edge e: before <= e -> ins[e+1]
+            RAMA_TRY((row_bounds<int32_t, int32_t>(ctx, before.get(), nnew, (int64_t)m + 1, ins.get())));
+            aug.m = (int64_t)(m + nnew);
+            RAMA_TRY(aug.i.alloc(ctx, (size_t)aug.m));
+            RAMA_TRY(aug.j.alloc(ctx, (size_t)aug.m));
+            RAMA_TRY(aug.c.alloc(ctx, (size_t)aug.m));
+            size_t span = m > nnew ? m : nnew;
+            k_merge_edges<<<grid_for(span), kBlock, 0, ctx.stream>>>(m, g.i.get(), g.j.get(), g.c.get(), ins.get(), nnew,
+                                                                    ci.get(), cj.get(), before.get(), aug.i.get(),
+                                                                    aug.j.get(), aug.c.get());
+            LAUNCH_TRY(ctx, "merge_edges");
+            RAMA_TRY((row_bounds<int32_t, int32_t>(ctx, aug.i.get(), (size_t)aug.m, n, rowptr.get())));
+        }
+    }
+    if (nnew == 0) RAMA_TRY(copy_graph(ctx, g, aug));
+    const size_t ma = (size_t)aug.m;
+    // ---- triangles -----------------------------------------------------------------------------
+    Buf<uint64_t> tkey;
+    RAMA_TRY(tkey.alloc(ctx, nfan));
+    k_triangle_keys<<<grid_for(nfan), kBlock, 0, ctx.stream>>>(cs, nfan, rowptr.get(), aug.j.get(), nbits, tkey.get(),
+                                                              flag.get());
+    LAUNCH_TRY(ctx, "triangle_keys");
+    RAMA_TRY((radix_sort_keys<uint64_t>(ctx, tkey, nfan, bits_for((uint64_t)ma) + nbits)));
+    Buf<uint32_t> tpos;
+    RAMA_TRY(tpos.alloc(ctx, nfan + 1));
+    RAMA_TRY((exclusive_scan<uint32_t>(ctx, HeadFlag64{tkey.get()}, tpos.get(), nfan)));
+    uint32_t T32 = 0;
+    RAMA_TRY(read_back(ctx, &T32, tpos.get() + nfan, 4));
+    const size_t T = T32;
+    if (info) info->n_triangles = (int64_t)T;
+    Buf<int32_t> tri_edge;
+    Buf<uint32_t> skey, slot;
+    RAMA_TRY(tri_edge.alloc(ctx, 3 * T));
+    RAMA_TRY(skey.alloc(ctx, 3 * T));
+    RAMA_TRY(slot.alloc(ctx, 3 * T));
+    k_triangle_edges<<<grid_for(nfan), kBlock, 0, ctx.stream>>>(nfan, tkey.get(), tpos.get(), rowptr.get(), aug.i.get(),
+                                                               aug.j.get(), nbits, tri_edge.get(), skey.get(),
+                                                               slot.get(), flag.get());
+    LAUNCH_TRY(ctx, "triangle_edges");
+    tkey.reset();
+    tpos.reset();
+    {
+        int32_t hf = 0;
+        RAMA_TRY(read_back(ctx, &hf, flag.get(), 4));
+        if (hf) return fail(ctx, RAMA_ERR_BAD_GRAPH, "a cycle uses an edge that is not in the graph");
+    }
+    // ---- incidence: slots of every edge in ascending triangle order ----------------------------
+    RAMA_TRY((radix_sort_pairs<uint32_t, uint32_t>(ctx, skey, slot, 3 * T, bits_for((uint64_t)ma))));
+    Buf<int32_t> slot_ptr;
+    RAMA_TRY(slot_ptr.alloc(ctx, ma + 1));
+    RAMA_TRY((row_bounds<uint32_t, int32_t>(ctx, skey.get(), 3 * T, (int64_t)ma, slot_ptr.get())));
+    skey.reset();
+    rowptr.reset();
+    // ---- iterations ----------------------------------------------------------------------------
+    Buf<float> share, ct, msg;
+    RAMA_TRY(share.alloc(ctx, ma));
+    RAMA_TRY(ct.alloc(ctx, 3 * T));
+    RAMA_TRY(msg.alloc(ctx, 3 * T));
+    RAMA_TRY(fill<float>(ctx, ct.get(), 0.0f, 3 * T));
+    float *ce = aug.c.get();
+    k_edge_init<<<grid_for(ma), kBlock, 0, ctx.stream>>>(ma, ce, slot_ptr.get(), share.get());
+    LAUNCH_TRY(ctx, "edge_init");
+    if (lb_trace) {
+        RAMA_TRY(lower_bound_now(ctx, ce, ma, ct.get(), T, lb_dev.get()));
+        RAMA_TRY(read_back(ctx, &lb_trace[0], lb_dev.get(), 8));
+    }
+    for (int it = 1; it <= k_iters; ++it) {
+        k_triangle_update<<<grid_for(T), kBlock, 0, ctx.stream>>>(T, tri_edge.get(), share.get(), ct.get(), msg.get());
+        LAUNCH_TRY(ctx, "triangle_update");
+        k_edge_update<<<grid_for(ma), kBlock, 0, ctx.stream>>>(ma, slot_ptr.get(), slot.get(), msg.get(), ce, share.get());
+        LAUNCH_TRY(ctx, "edge_update");
+        if (lb_trace) {
+            RAMA_TRY(lower_bound_now(ctx, ce, ma, ct.get(), T, lb_dev.get()));
+            RAMA_TRY(read_back(ctx, &lb_trace[it], lb_dev.get(), 8));
+        }
+    }
+    if (lower_bound) {
+        if (lb_trace) *lower_bound = lb_trace[k_iters];
+        else {
+            RAMA_TRY(lower_bound_now(ctx, ce, ma, ct.get(), T, lb_dev.get()));
+            RAMA_TRY(read_back(ctx, lower_bound, lb_dev.get(), 8));
+        }
+    }
+    out.n = aug.n; out.m = aug.m;
+    out.i = std::move(aug.i); out.j = std::move(aug.j); out.c = std::move(aug.c);
+    return RAMA_OK;
+}
+
+}  // namespace rama

@@ -1,0 +1,132 @@
+// Step a0: problem statement -> canonical device graph (paper Sec. 3: graph and cost vector;
+// Lemma 1(b): parallel edges carry the sum of their costs).
+#include "prim.h"
+
+namespace rama {
+
+namespace {
+
+// flags[0]: endpoint out of range or non-finite cost; flags[1]: list is not canonical
+__global__ __launch_bounds__(kBlock) void k_validate(int32_t n, size_t m, const int32_t *i, const int32_t *j,
+                                                     const float *c, int32_t *flags)
+{
+    size_t e = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (e >= m) return;
+    int32_t a = i[e], b = j[e];
+    float w = c[e];
+    bool bad = a < 0 || a >= n || b < 0 || b >= n || !(fabsf(w) <= 3.402823466e+38f);
+    if (bad) { flags[0] = 1; return; }
+    bool canon = a < b;
+    if (canon && e > 0) {
+        int32_t pa = i[e - 1], pb = j[e - 1];
+        canon = pa < a || (pa == a && pb < b);
+    }
+    if (!canon) flags[1] = 1;
+}
+
+struct NotLoop {
+    const int32_t *i, *j;
+    __device__ __forceinline__ uint32_t operator()(size_t e) const { return i[e] != j[e] ? 1u : 0u; }
+};
+
+__global__ __launch_bounds__(kBlock) void k_pack_edges(size_t m, const int32_t *i, const int32_t *j, const float *c,
+                                                       const uint32_t *pos, int nbits, uint64_t *key, uint32_t *val)
+{
+    size_t e = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (e >= m) return;
+    int32_t a = i[e], b = j[e];
+    if (a == b) return;
+    uint32_t lo = (uint32_t)min(a, b), hi = (uint32_t)max(a, b);
+    uint32_t p = pos[e];
+    key[p] = ((uint64_t)lo << nbits) | hi;
+    val[p] = __float_as_uint(c[e]);
+}
+
+struct HeadFlag {
+    const uint64_t *key;
+    __device__ __forceinline__ uint32_t operator()(size_t e) const { return (e == 0 || key[e] != key[e - 1]) ? 1u : 0u; }
+};
+
+}  // namespace
+
+rama_status canonicalise(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const int32_t *j, const float *c, Graph &out)
+{
+    if (n < 0 || m < 0 || (m > 0 && (!i || !j || !c))) return fail(ctx, RAMA_ERR_INVALID_ARG, "canonicalise: bad arguments");
+    if (m >= (int64_t(1) << 31) - 1) return fail(ctx, RAMA_ERR_CAPACITY, "edge count reaches 2^31");
+    out.n = n;
+    out.m = 0;
+    if (m == 0) {
+        RAMA_TRY(out.i.alloc(ctx, 1));
+        RAMA_TRY(out.j.alloc(ctx, 1));
+        RAMA_TRY(out.c.alloc(ctx, 1));
+        return RAMA_OK;
+    }
+    Buf<int32_t> flags;
+    RAMA_TRY(flags.alloc(ctx, 2));
+    RAMA_TRY(fill<int32_t>(ctx, flags.get(), 0, 2));
+    k_validate<<<grid_for(m), kBlock, 0, ctx.stream>>>(n, (size_t)m, i, j, c, flags.get());
+    LAUNCH_TRY(ctx, "validate");
+    int32_t hf[2];
+    RAMA_TRY(read_back(ctx, hf, flags.get(), sizeof hf));
+    if (hf[0]) return fail(ctx, RAMA_ERR_BAD_GRAPH, "edge endpoint outside [0,n_nodes) or non-finite cost");
+    if (!hf[1]) {  // already canonical: plain copy
+        RAMA_TRY(out.i.alloc(ctx, m));
+        RAMA_TRY(out.j.alloc(ctx, m));
+        RAMA_TRY(out.c.alloc(ctx, m));
+        HIP_TRY(ctx, hipMemcpyAsync(out.i.get(), i, (size_t)m * 4, hipMemcpyDeviceToDevice, ctx.stream));
+        HIP_TRY(ctx, hipMemcpyAsync(out.j.get(), j, (size_t)m * 4, hipMemcpyDeviceToDevice, ctx.stream));
+        HIP_TRY(ctx, hipMemcpyAsync(out.c.get(), c, (size_t)m * 4, hipMemcpyDeviceToDevice, ctx.stream));
+        out.m = m;
+        return RAMA_OK;
+    }
+    const int nbits = bits_for((uint64_t)n);
+    Buf<uint32_t> pos;
+    RAMA_TRY(pos.alloc(ctx, (size_t)m + 1));
+    RAMA_TRY((exclusive_scan<uint32_t>(ctx, NotLoop{i, j}, pos.get(), (size_t)m)));
+    uint32_t kept = 0;
+    RAMA_TRY(read_back(ctx, &kept, pos.get() + m, 4));
+    if (kept == 0) {
+        RAMA_TRY(out.i.alloc(ctx, 1));
+        RAMA_TRY(out.j.alloc(ctx, 1));
+        RAMA_TRY(out.c.alloc(ctx, 1));
+        return RAMA_OK;
+    }
+    Buf<uint64_t> key;
+    Buf<uint32_t> val;
+    RAMA_TRY(key.alloc(ctx, kept));
+    RAMA_TRY(val.alloc(ctx, kept));
+    k_pack_edges<<<grid_for(m), kBlock, 0, ctx.stream>>>((size_t)m, i, j, c, pos.get(), nbits, key.get(), val.get());
+    LAUNCH_TRY(ctx, "pack_edges");
+    pos.reset();
+    RAMA_TRY((radix_sort_pairs<uint64_t, uint32_t>(ctx, key, val, kept, 2 * nbits)));
+    Buf<uint32_t> opos;
+    RAMA_TRY(opos.alloc(ctx, (size_t)kept + 1));
+    RAMA_TRY((exclusive_scan<uint32_t>(ctx, HeadFlag{key.get()}, opos.get(), (size_t)kept)));
+    uint32_t uniq = 0;
+    RAMA_TRY(read_back(ctx, &uniq, opos.get() + kept, 4));
+    RAMA_TRY(out.i.alloc(ctx, uniq));
+    RAMA_TRY(out.j.alloc(ctx, uniq));
+    RAMA_TRY(out.c.alloc(ctx, uniq));
+    k_reduce_runs<<<grid_for(kept), kBlock, 0, ctx.stream>>>(kept, key.get(), val.get(), opos.get(), nbits, out.i.get(),
+                                                            out.j.get(), out.c.get());
+    LAUNCH_TRY(ctx, "reduce_runs");
+    out.m = uniq;
+    return RAMA_OK;
+}
+
+namespace {
+struct NegPart {
+    const float *c;
+    __device__ __forceinline__ double operator()(size_t e) const { float w = c[e]; return w < 0.0f ? (double)w : 0.0; }
+};
+}  // namespace
+
+rama_status negative_cost_sum(Ctx &ctx, const float *c, int64_t m, double *out)
+{
+    Buf<double> d;
+    RAMA_TRY(d.alloc(ctx, 1));
+    RAMA_TRY(device_sum(ctx, NegPart{c}, (size_t)m, d.get(), false));
+    return read_back(ctx, out, d.get(), 8);
+}
+
+}  // namespace rama

@@ -1,0 +1,408 @@
+// Device-wide primitives for gfx950, written for 64-wide wavefronts:
+//   exclusive scan (reduce-then-scan, functor input), stable LSD radix sort (wave-level
+//   match-any ranking), row boundaries of a sorted key array, deterministic sum reductions.
+// Everything is integer-exact or uses a fixed reduction tree, so results do not depend on
+// scheduling.
+#pragma once
+
+#include "common.h"
+
+namespace rama {
+
+// ------------------------------------------------------------------------------------------
+// wave / block helpers
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & 63); }
+
+template <typename T>
+__device__ __forceinline__ T wave_inclusive_scan(T v)
+{
+    const int lane = lane_id();
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        T t = __shfl_up(v, off, 64);
+        if (lane >= off) v += t;
+    }
+    return v;
+}
+
+template <typename T>
+__device__ __forceinline__ T wave_sum(T v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// inclusive scan over the 256 threads of a block; *total gets the block sum
+template <typename T>
+__device__ __forceinline__ T block_inclusive_scan(T v, T *total)
+{
+    __shared__ T wave_tot[4];
+    const int w = threadIdx.x >> 6;
+    T inc = wave_inclusive_scan(v);
+    if (lane_id() == 63) wave_tot[w] = inc;
+    __syncthreads();
+    T pre = 0, tot = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        T x = wave_tot[k];
+        if (k < w) pre += x;
+        tot += x;
+    }
+    __syncthreads();
+    *total = tot;
+    return inc + pre;
+}
+
+// sum over the block in a fixed order (lane tree, then waves 0..3)
+template <typename T>
+__device__ __forceinline__ T block_sum(T v)
+{
+    __shared__ T wave_tot[4];
+    T s = wave_sum(v);
+    if (lane_id() == 0) wave_tot[threadIdx.x >> 6] = s;
+    __syncthreads();
+    T tot = ((wave_tot[0] + wave_tot[1]) + wave_tot[2]) + wave_tot[3];
+    __syncthreads();
+    return tot;
+}
+
+// ------------------------------------------------------------------------------------------
+// exclusive scan of f(0..n-1) into out[0..n] (out[n] = total)
+// ------------------------------------------------------------------------------------------
+constexpr int kScanItems = 8;
+constexpr int kScanTile = kBlock * kScanItems;
+
+template <typename T>
+struct PtrInput {
+    const T *p;
+    __device__ __forceinline__ T operator()(size_t k) const { return p[k]; }
+};
+
+template <typename TO, typename F>
+__global__ __launch_bounds__(kBlock) void k_scan_reduce(F f, TO *block_sums, size_t n)
+{
+    size_t base = (size_t)blockIdx.x * kScanTile + (size_t)threadIdx.x * kScanItems;
+    TO s = 0;
+#pragma unroll
+    for (int q = 0; q < kScanItems; ++q)
+        if (base + q < n) s += (TO)f(base + q);
+    TO tot = block_sum(s);
+    if (threadIdx.x == 0) block_sums[blockIdx.x] = tot;
+}
+
+template <typename TO, typename F>
+__global__ __launch_bounds__(kBlock) void k_scan_apply(F f, TO *out, const TO *block_offsets, size_t n)
+{
+    size_t base = (size_t)blockIdx.x * kScanTile + (size_t)threadIdx.x * kScanItems;
+    TO v[kScanItems];
+    TO s = 0;
+#pragma unroll
+    for (int q = 0; q < kScanItems; ++q) {
+        v[q] = (base + q < n) ? (TO)f(base + q) : (TO)0;
+        s += v[q];
+    }
+    TO tot;
+    TO inc = block_inclusive_scan(s, &tot);
+    TO run = inc - s + (block_offsets ? block_offsets[blockIdx.x] : (TO)0);
+#pragma unroll
+    for (int q = 0; q < kScanItems; ++q) {
+        if (base + q < n) out[base + q] = run;
+        run += v[q];
+    }
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == kBlock - 1) out[n] = run;
+}
+
+template <typename TO>
+__global__ void k_store_zero(TO *p) { *p = 0; }
+
+template <typename TO, typename F>
+rama_status exclusive_scan(Ctx &ctx, F f, TO *out, size_t n)
+{
+    if (n == 0) {
+        k_store_zero<TO><<<1, 1, 0, ctx.stream>>>(out);
+        LAUNCH_TRY(ctx, "scan0");
+        return RAMA_OK;
+    }
+    unsigned nb = grid_for(n, kScanTile);
+    if (nb == 1) {
+        k_scan_apply<TO, F><<<1, kBlock, 0, ctx.stream>>>(f, out, (const TO *)nullptr, n);
+        LAUNCH_TRY(ctx, "scan1");
+        return RAMA_OK;
+    }
+    Buf<TO> sums, offs;
+    RAMA_TRY(sums.alloc(ctx, nb));
+    RAMA_TRY(offs.alloc(ctx, (size_t)nb + 1));
+    k_scan_reduce<TO, F><<<nb, kBlock, 0, ctx.stream>>>(f, sums.get(), n);
+    LAUNCH_TRY(ctx, "scan_reduce");
+    RAMA_TRY((exclusive_scan<TO, PtrInput<TO>>(ctx, PtrInput<TO>{sums.get()}, offs.get(), nb)));
+    k_scan_apply<TO, F><<<nb, kBlock, 0, ctx.stream>>>(f, out, offs.get(), n);
+    LAUNCH_TRY(ctx, "scan_apply");
+    return RAMA_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// row boundaries: keys[0..m) ascending with values in [0,n); ptr[v] = first position whose key
+// is >= v, for v in [0,n]  (ptr[n] = m).  One thread per position, each fills the gap before it.
+// ------------------------------------------------------------------------------------------
+template <typename K, typename P>
+__global__ __launch_bounds__(kBlock) void k_row_bounds(const K *keys, size_t m, int64_t n, P *ptr)
+{
+    size_t e = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (e > m) return;
+    int64_t prev = (e == 0) ? -1 : (int64_t)keys[e - 1];
+    int64_t cur = (e == m) ? n : (int64_t)keys[e];
+    for (int64_t v = prev + 1; v <= cur; ++v) ptr[v] = (P)e;
+}
+
+template <typename K, typename P>
+rama_status row_bounds(Ctx &ctx, const K *keys, size_t m, int64_t n, P *ptr)
+{
+    k_row_bounds<K, P><<<grid_for(m + 1), kBlock, 0, ctx.stream>>>(keys, m, n, ptr);
+    LAUNCH_TRY(ctx, "row_bounds");
+    return RAMA_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// stable LSD radix sort, up to 8 bits per pass, 4096 keys per workgroup.
+// Ranking inside a wave uses ballot-based match-any, so equal digits keep their order
+// without any atomics in the scatter pass.
+// ------------------------------------------------------------------------------------------
+constexpr int kSortItems = 16;
+constexpr int kSortTile = kBlock * kSortItems;
+
+struct NoVal {};
+
+template <typename K>
+__global__ __launch_bounds__(kBlock) void k_rs_hist(const K *keys, uint32_t *hist, size_t n, int shift, int bits,
+                                                    uint32_t nb)
+{
+    __shared__ uint32_t h[256];
+    h[threadIdx.x] = 0;
+    __syncthreads();
+    const uint32_t mask = (1u << bits) - 1u;
+    size_t base = (size_t)blockIdx.x * kSortTile + threadIdx.x;
+#pragma unroll
+    for (int r = 0; r < kSortItems; ++r) {
+        size_t idx = base + (size_t)r * kBlock;
+        if (idx < n) atomicAdd(&h[(uint32_t)(keys[idx] >> shift) & mask], 1u);
+    }
+    __syncthreads();
+    if (threadIdx.x <= mask) hist[(size_t)threadIdx.x * nb + blockIdx.x] = h[threadIdx.x];
+}
+
+__device__ __forceinline__ uint64_t match_digit(uint32_t d, int bits, uint64_t valid)
+{
+    uint64_t m = valid;
+    for (int b = 0; b < bits; ++b) {
+        bool bit = (d >> b) & 1u;
+        uint64_t bal = __ballot(bit);
+        m &= bit ? bal : ~bal;
+    }
+    return m;
+}
+
+template <typename K, typename V, bool HAS_V>
+__global__ __launch_bounds__(kBlock) void k_rs_scatter(const K *kin, const V *vin, K *kout, V *vout,
+                                                       const uint32_t *offs, size_t n, int shift, int bits,
+                                                       uint32_t nb)
+{
+    __shared__ uint32_t whist[4][256];
+    __shared__ uint32_t wbase[4][256];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const uint32_t mask = (1u << bits) - 1u;
+    for (int k = tid; k < 1024; k += kBlock) (&whist[0][0])[k] = 0;
+    __syncthreads();
+    const size_t wave_base = (size_t)blockIdx.x * kSortTile + (size_t)w * (64 * kSortItems);
+    const uint64_t lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    K key[kSortItems];
+    uint32_t val[kSortItems];
+    uint32_t rank[kSortItems];
+#pragma unroll
+    for (int r = 0; r < kSortItems; ++r) {
+        size_t idx = wave_base + (size_t)r * 64 + lane;
+        bool valid = idx < n;
+        key[r] = valid ? kin[idx] : (K)0;
+        if (HAS_V) val[r] = valid ? (uint32_t)vin[idx] : 0u;
+        uint32_t d = (uint32_t)(key[r] >> shift) & mask;
+        uint64_t m = match_digit(d, bits, __ballot(valid));
+        uint32_t before = whist[w][d];
+        rank[r] = before + (uint32_t)__popcll(m & lt);
+        __builtin_amdgcn_wave_barrier();
+        if (valid && lane == (__ffsll((long long)m) - 1)) whist[w][d] = before + (uint32_t)__popcll(m);
+        __builtin_amdgcn_wave_barrier();
+    }
+    __syncthreads();
+    if ((uint32_t)tid <= mask) {
+        uint32_t g = offs[(size_t)tid * nb + blockIdx.x];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            wbase[k][tid] = g;
+            g += whist[k][tid];
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < kSortItems; ++r) {
+        size_t idx = wave_base + (size_t)r * 64 + lane;
+        if (idx < n) {
+            uint32_t d = (uint32_t)(key[r] >> shift) & mask;
+            uint32_t pos = wbase[w][d] + rank[r];
+            kout[pos] = key[r];
+            if (HAS_V) vout[pos] = (V)val[r];
+        }
+    }
+}
+
+// Sorts keys (and 32-bit values) by the low `total_bits` bits of the key.  a/b are two buffers
+// of n elements each; input in a; on return *result_in_b says where the sorted data is.
+template <typename K, typename V, bool HAS_V>
+rama_status radix_sort_impl(Ctx &ctx, K *ka, V *va, K *kb, V *vb, size_t n, int total_bits, bool *result_in_b)
+{
+    *result_in_b = false;
+    if (n <= 1 || total_bits <= 0) return RAMA_OK;
+    if (n >= (size_t(1) << 32)) return fail(ctx, RAMA_ERR_CAPACITY, "radix sort: more than 2^32 keys");
+    const uint32_t nb = grid_for(n, kSortTile);
+    int passes = (total_bits + 7) / 8;
+    Buf<uint32_t> hist, offs;
+    RAMA_TRY(hist.alloc(ctx, (size_t)256 * nb));
+    RAMA_TRY(offs.alloc(ctx, (size_t)256 * nb + 1));
+    int shift = 0, remaining = total_bits;
+    for (int p = 0; p < passes; ++p) {
+        int bits = (remaining + (passes - p) - 1) / (passes - p);
+        k_rs_hist<K><<<nb, kBlock, 0, ctx.stream>>>(ka, hist.get(), n, shift, bits, nb);
+        LAUNCH_TRY(ctx, "rs_hist");
+        RAMA_TRY((exclusive_scan<uint32_t, PtrInput<uint32_t>>(ctx, PtrInput<uint32_t>{hist.get()}, offs.get(),
+                                                                (size_t)nb << bits)));
+        k_rs_scatter<K, V, HAS_V><<<nb, kBlock, 0, ctx.stream>>>(ka, va, kb, vb, offs.get(), n, shift, bits, nb);
+        LAUNCH_TRY(ctx, "rs_scatter");
+        std::swap(ka, kb);
+        std::swap(va, vb);
+        *result_in_b = !*result_in_b;
+        shift += bits;
+        remaining -= bits;
+    }
+    return RAMA_OK;
+}
+
+// Convenience wrappers working on Buf pairs: after the call `k`/`v` hold the sorted data.
+template <typename K, typename V>
+rama_status radix_sort_pairs(Ctx &ctx, Buf<K> &k, Buf<V> &v, size_t n, int total_bits)
+{
+    static_assert(sizeof(V) == 4, "32-bit payload");
+    if (n <= 1) return RAMA_OK;
+    Buf<K> k2;
+    Buf<V> v2;
+    RAMA_TRY(k2.alloc(ctx, n));
+    RAMA_TRY(v2.alloc(ctx, n));
+    bool in_b = false;
+    RAMA_TRY((radix_sort_impl<K, V, true>(ctx, k.get(), v.get(), k2.get(), v2.get(), n, total_bits, &in_b)));
+    if (in_b) { k.swap(k2); v.swap(v2); }
+    return RAMA_OK;
+}
+
+template <typename K>
+rama_status radix_sort_keys(Ctx &ctx, Buf<K> &k, size_t n, int total_bits)
+{
+    if (n <= 1) return RAMA_OK;
+    Buf<K> k2;
+    RAMA_TRY(k2.alloc(ctx, n));
+    bool in_b = false;
+    RAMA_TRY((radix_sort_impl<K, uint32_t, false>(ctx, k.get(), (uint32_t *)nullptr, k2.get(), (uint32_t *)nullptr, n,
+                                                  total_bits, &in_b)));
+    if (in_b) k.swap(k2);
+    return RAMA_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// deterministic sum of f(0..n-1) in double: per-block partials, then one block adds them in order
+// ------------------------------------------------------------------------------------------
+constexpr int kSumItems = 8;
+
+template <typename F>
+__global__ __launch_bounds__(kBlock) void k_sum_partial(F f, double *partial, size_t n)
+{
+    size_t base = (size_t)blockIdx.x * (kBlock * kSumItems) + threadIdx.x;
+    double s = 0.0;
+#pragma unroll
+    for (int q = 0; q < kSumItems; ++q) {
+        size_t idx = base + (size_t)q * kBlock;
+        if (idx < n) s += f(idx);
+    }
+    double tot = block_sum(s);
+    if (threadIdx.x == 0) partial[blockIdx.x] = tot;
+}
+
+static __global__ __launch_bounds__(kBlock) void k_sum_final(const double *partial, size_t nb, double *out, int accumulate)
+{
+    // thread t adds partial[t], partial[t+256], ... in order; then the fixed block tree
+    double s = 0.0;
+    for (size_t k = threadIdx.x; k < nb; k += kBlock) s += partial[k];
+    double tot = block_sum(s);
+    if (threadIdx.x == 0) *out = accumulate ? (*out + tot) : tot;
+}
+
+template <typename F>
+rama_status device_sum(Ctx &ctx, F f, size_t n, double *out_dev, bool accumulate)
+{
+    unsigned nb = grid_for(n, kBlock * kSumItems);
+    if (nb == 0) nb = 1;
+    Buf<double> partial;
+    RAMA_TRY(partial.alloc(ctx, nb));
+    k_sum_partial<F><<<nb, kBlock, 0, ctx.stream>>>(f, partial.get(), n);
+    LAUNCH_TRY(ctx, "sum_partial");
+    k_sum_final<<<1, kBlock, 0, ctx.stream>>>(partial.get(), nb, out_dev, accumulate ? 1 : 0);
+    LAUNCH_TRY(ctx, "sum_final");
+    return RAMA_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// small fill / iota kernels
+// ------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(kBlock) void k_fill(T *p, T v, size_t n)
+{
+    size_t k = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (k < n) p[k] = v;
+}
+template <typename T>
+rama_status fill(Ctx &ctx, T *p, T v, size_t n)
+{
+    if (n == 0) return RAMA_OK;
+    k_fill<T><<<grid_for(n), kBlock, 0, ctx.stream>>>(p, v, n);
+    LAUNCH_TRY(ctx, "fill");
+    return RAMA_OK;
+}
+
+// Sums runs of equal keys in order of appearance (one thread per run, sequential adds) and
+// writes endpoint pair + cost of run r at position pos[first element of r].
+static __global__ __launch_bounds__(kBlock) void k_reduce_runs(size_t m, const uint64_t *key, const uint32_t *val,
+                                                        const uint32_t *pos, int nbits, int32_t *io, int32_t *jo,
+                                                        float *co)
+{
+    size_t e = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (e >= m) return;
+    uint64_t k = key[e];
+    if (e > 0 && key[e - 1] == k) return;
+    float acc = __uint_as_float(val[e]);
+    for (size_t f = e + 1; f < m && key[f] == k; ++f) acc = acc + __uint_as_float(val[f]);
+    uint32_t p = pos[e];
+    io[p] = (int32_t)(k >> nbits);
+    jo[p] = (int32_t)(k & ((1ull << nbits) - 1ull));
+    co[p] = acc;
+}
+
+// position of the canonical edge (u,v), u<v, in rows given by rowptr over i (upper CSR) or -1
+__device__ __forceinline__ int32_t find_edge_in_row(const int32_t *rowptr, const int32_t *j, int32_t u, int32_t v)
+{
+    int32_t lo = rowptr[u], hi = rowptr[u + 1];
+    const int32_t end = hi;
+    while (lo < hi) {
+        int32_t mid = lo + ((hi - lo) >> 1);
+        if (j[mid] < v) lo = mid + 1; else hi = mid;
+    }
+    return (lo < end && j[lo] == v) ? lo : -1;
+}
+
+}  // namespace rama

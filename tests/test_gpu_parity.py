@@ -1,0 +1,258 @@
+"""GPU parity: every stage of the HIP library against the CPU oracle on the same seeded inputs,
+called through the C ABI (paper_2109_01838_amd.binding -> librama_hip.so).
+
+Stage-wise tests hand each GPU stage the oracle's input for that stage.  Integer results
+(cycle lists, edge lists, contraction mappings, labels) must match bit-exactly; fp32 reduced
+costs and lower bounds within 1e-4 relative; end to end the primal cost within 0.5 % and the
+lower bound within 1e-4 relative.
+"""
+import numpy as np
+import pytest
+
+from paper_2109_01838_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+REL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def rama():
+    from paper_2109_01838_amd import Rama
+    r = Rama("cuda:0")
+    yield r
+    r.close()
+
+
+def np_(t):
+    return t.detach().cpu().numpy()
+
+
+def signed(g, seed, pos=0.7):
+    rng = np.random.default_rng(seed)
+    c = np.where(rng.random(g["c"].size) < pos, np.abs(g["c"]), -np.abs(g["c"])).astype(np.float32)
+    return dict(g, c=c)
+
+
+def cases():
+    """name -> instance; sizes span several 4096-key sort tiles and 2048-item scan tiles with ragged tails."""
+    out = {}
+    out["cfg1"] = inputs.cfg1()
+    out["grid2d_longrange_96"] = inputs.cfg2(h=96, w=96, n_seeds=20)
+    out["knn_20000"] = inputs.cfg3(n_points=20000, n_seeds=100)
+    out["grid3d_24"] = inputs.cfg5_crop(24)
+    out["random_dense"] = signed(inputs.random_graph(300, 6000, 11), 11, 0.6)
+    out["random_sparse"] = signed(inputs.random_graph(5000, 14000, 12), 12, 0.8)
+    out["messy"] = inputs.random_graph(200, 3000, 13, allow_messy=True)
+    return out
+
+
+CASES = cases()
+
+
+def rel_close(a, b, rel=REL):
+    a, b = np.asarray(a, np.float64), np.asarray(b, np.float64)
+    scale = max(1.0, float(np.abs(b).max()) if b.size else 1.0)
+    return np.all(np.abs(a - b) <= rel * scale)
+
+
+# --------------------------------------------------------------------------------------------
+# a1 cycles
+# --------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("name", list(CASES))
+@pytest.mark.parametrize("lmax", [3, 4, 5])
+def test_cycles_bit_exact(rama, oracle32, name, lmax):
+    g = CASES[name]
+    if name == "random_dense" and lmax == 5:
+        g = dict(g, i=g["i"][:2500], j=g["j"][:2500], c=g["c"][:2500])
+    want = oracle32.find_conflicted_cycles(g["n_nodes"], g["i"], g["j"], g["c"], lmax)
+    got = rama.find_conflicted_cycles(g["n_nodes"], g["i"], g["j"], g["c"], lmax)
+    for L in range(3):
+        assert np.array_equal(np_(got[L]), want[L]), (name, lmax, L + 3, got[L].shape, want[L].shape)
+
+
+def test_cycles_capacity_protocol(rama):
+    import ctypes as C
+    import torch
+    from paper_2109_01838_amd import binding
+    g = CASES["cfg1"]
+    i, j, c = (torch.as_tensor(g[k], device="cuda") for k in ("i", "j", "c"))
+    cnt = (C.c_int64 * 3)()
+    st = rama.lib.rama_find_conflicted_cycles(rama.ctx, g["n_nodes"], i.numel(), i.data_ptr(), j.data_ptr(),
+                                              c.data_ptr(), 5, 0, 0, 0, None, None, None, cnt)
+    assert st == binding.RAMA_ERR_CAPACITY and cnt[1] > 0
+    buf = torch.full((4 * (cnt[1] - 1) + 1,), -7, dtype=torch.int32, device="cuda")
+    st = rama.lib.rama_find_conflicted_cycles(rama.ctx, g["n_nodes"], i.numel(), i.data_ptr(), j.data_ptr(),
+                                              c.data_ptr(), 5, 0, cnt[1] - 1, 0, None, buf.data_ptr(), None, cnt)
+    assert st == binding.RAMA_ERR_CAPACITY
+    assert bool((buf == -7).all())          # nothing written on capacity failure
+    st = rama.lib.rama_find_conflicted_cycles(rama.ctx, g["n_nodes"], i.numel(), i.data_ptr(), j.data_ptr(),
+                                              c.data_ptr(), 6, 0, 0, 0, None, None, None, cnt)
+    assert st == binding.RAMA_ERR_INVALID_ARG
+
+
+# --------------------------------------------------------------------------------------------
+# a2 + a3 message passing
+# --------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("name", list(CASES))
+@pytest.mark.parametrize("k", [0, 1, 10])
+def test_message_passing_parity(rama, oracle32, name, k):
+    g = CASES[name]
+    n = g["n_nodes"]
+    lmax = 4 if name == "random_dense" else 5
+    cyc = oracle32.find_conflicted_cycles(n, g["i"], g["j"], g["c"], lmax)
+    want = oracle32.message_passing(n, g["i"], g["j"], g["c"], cyc, k, trace=True)
+    got = rama.message_passing(n, g["i"], g["j"], g["c"], cyc, k, trace=True)
+    assert np.array_equal(np_(got["i"]), want["i"]) and np.array_equal(np_(got["j"]), want["j"])
+    assert rel_close(np_(got["c"]), want["c"])
+    assert abs(got["lower_bound"] - want["lower_bound"]) <= REL * max(1.0, abs(want["lower_bound"]))
+    assert rel_close(got["lb_trace"], want["lb_trace"])
+    tr = np.asarray(got["lb_trace"])
+    assert np.all(np.diff(tr) >= -1e-5 * (1.0 + np.abs(tr[:-1])))       # monotone (Appendix, LB lemma)
+    # the arithmetic is ordered identically on both sides, so in practice the match is exact
+    print(name, k, "max |dc| =", float(np.abs(np_(got["c"]) - want["c"]).max()) if want["c"].size else 0.0,
+          "bit-exact:", bool(np.array_equal(np_(got["c"]), want["c"])))
+
+
+def test_message_passing_cycle_order_is_irrelevant(rama, oracle32):
+    g = CASES["knn_20000"]
+    n = g["n_nodes"]
+    cyc = oracle32.find_conflicted_cycles(n, g["i"], g["j"], g["c"], 5)
+    rng = np.random.default_rng(0)
+    shuffled = [x[rng.permutation(x.shape[0])] for x in cyc]
+    a = rama.message_passing(n, g["i"], g["j"], g["c"], cyc, 3)
+    b = rama.message_passing(n, g["i"], g["j"], g["c"], shuffled, 3)
+    assert np.array_equal(np_(a["c"]), np_(b["c"])) and a["lower_bound"] == b["lower_bound"]
+
+
+def test_message_passing_rejects_foreign_cycles(rama):
+    from paper_2109_01838_amd import RamaError, binding
+    g = CASES["cfg1"]
+    bad = [np.array([[0, 1, 40]], np.int32), np.zeros((0, 4), np.int32), np.zeros((0, 5), np.int32)]
+    with pytest.raises(RamaError) as ei:
+        rama.message_passing(g["n_nodes"], g["i"], g["j"], g["c"], bad, 1)
+    assert ei.value.status == binding.RAMA_ERR_BAD_GRAPH
+    bad[0] = np.array([[0, 1, 5000]], np.int32)
+    with pytest.raises(RamaError):
+        rama.message_passing(g["n_nodes"], g["i"], g["j"], g["c"], bad, 1)
+
+
+# --------------------------------------------------------------------------------------------
+# a4-a6 contraction
+# --------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("name", list(CASES))
+@pytest.mark.parametrize("repeat", [1, 0])
+def test_contract_parity(rama, oracle32, name, repeat):
+    g = CASES[name]
+    n = g["n_nodes"]
+    # the stage input is what the oracle's dual step hands over: reduced costs incl. chords
+    cyc = oracle32.find_conflicted_cycles(n, g["i"], g["j"], g["c"], 4)
+    mp = oracle32.message_passing(n, g["i"], g["j"], g["c"], cyc, 5)
+    want = oracle32.contract(n, mp["i"], mp["j"], mp["c"], repeat=repeat)
+    got = rama.contract(n, mp["i"], mp["j"], mp["c"], repeat=repeat)
+    assert got["n_nodes"] == want["n_nodes"]
+    assert np.array_equal(np_(got["mapping"]), want["mapping"])
+    assert np.array_equal(np_(got["i"]), want["i"]) and np.array_equal(np_(got["j"]), want["j"])
+    assert rel_close(np_(got["c"]), want["c"])
+    assert rel_close(np_(got["diag"]), want["diag"])
+    print(name, repeat, "costs bit-exact:", bool(np.array_equal(np_(got["c"]), want["c"])),
+          "diag bit-exact:", bool(np.array_equal(np_(got["diag"]), want["diag"])))
+
+
+def test_contract_fig2_graph(rama, oracle32):
+    # the graph of the paper's Fig. 2; with the matching rule S={st} (cost 4 is the best edge at s and t;
+    # rs=3 loses at s), so only the mechanics are compared with the oracle here
+    i = np.array([0, 0, 1, 1, 2, 3, 2], np.int32)
+    j = np.array([1, 2, 3, 4, 3, 4, 4], np.int32)
+    c = np.array([1, -2, -3, 1, 3, 4, 1], np.float32)
+    want = oracle32.contract(5, i, j, c, repeat=1)
+    got = rama.contract(5, i, j, c, repeat=1)
+    assert np.array_equal(np_(got["mapping"]), want["mapping"])
+    assert np.array_equal(np_(got["c"]), want["c"]) and np.array_equal(np_(got["diag"]), want["diag"])
+
+
+def test_canonicalisation_of_large_shuffled_input(rama, oracle32):
+    # no attractive edge -> rama_contract returns the canonical form of its input: this drives the
+    # 64-bit radix sort, the run reduction and the scans over many tiles with a ragged tail
+    g = inputs.random_graph(3000, 100003, 21, allow_messy=True)
+    c = -np.abs(g["c"]) - 0.01
+    wi, wj, wc = oracle32.canonicalise(3000, g["i"], g["j"], c)
+    got = rama.contract(3000, g["i"], g["j"], c, repeat=1)
+    assert got["n_nodes"] == 3000 and np.array_equal(np_(got["mapping"]), np.arange(3000))
+    assert np.array_equal(np_(got["i"]), wi) and np.array_equal(np_(got["j"]), wj)
+    assert np.array_equal(np_(got["c"]), wc)       # duplicates are added in input order on both sides
+
+
+# --------------------------------------------------------------------------------------------
+# end to end
+# --------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("name", list(CASES))
+def test_solve_end_to_end(rama, oracle32, name):
+    g = CASES[name]
+    n = g["n_nodes"]
+    want = oracle32.solve(n, g["i"], g["j"], g["c"])
+    got = rama.solve(n, g["i"], g["j"], g["c"])
+    labels = np_(got["labels"])
+    assert abs(got["lower_bound"] - want["lower_bound"]) <= REL * max(1.0, abs(want["lower_bound"]))
+    assert abs(got["primal"] - want["primal"]) <= 5e-3 * max(1.0, abs(want["primal"]))
+    # the reported primal is the cost of the returned labels, and labels are canonical
+    assert abs(oracle32.multicut_cost(g["i"], g["j"], g["c"], labels) - got["primal"]) <= 1e-6 * max(1.0, abs(got["primal"]))
+    assert np.all(labels[labels] == labels) and np.all(labels <= np.arange(n))
+    assert got["lower_bound"] <= got["primal"] + 1e-6 * max(1.0, abs(got["primal"]))
+    assert got["n_cycles_first"] == want["n_cycles_first"]
+    assert got["n_edges_aug_first"] == want["n_edges_aug_first"]
+    print(name, "labels identical:", bool(np.array_equal(labels, want["labels"])), "rounds", got["rounds"],
+          want["rounds"], "primal", got["primal"], want["primal"], "LB", got["lower_bound"], want["lower_bound"])
+
+
+@pytest.mark.parametrize("variant", ["P", "PD+", "D"])
+def test_solver_variants(rama, oracle32, variant):
+    from paper_2109_01838_amd import default_params
+    g = CASES["knn_20000"]
+    n = g["n_nodes"]
+    kw = {"P": dict(max_cycle_len_first=0, max_cycle_len_later=0),
+          "PD+": dict(max_cycle_len_later=5),
+          "D": dict(max_rounds=1)}[variant]
+    want = oracle32.solve(n, g["i"], g["j"], g["c"], **kw)
+    got = rama.solve(n, g["i"], g["j"], g["c"], default_params(**kw))
+    assert abs(got["lower_bound"] - want["lower_bound"]) <= REL * max(1.0, abs(want["lower_bound"]))
+    assert abs(got["primal"] - want["primal"]) <= 5e-3 * max(1.0, abs(want["primal"]))
+
+
+def test_determinism(rama):
+    g = CASES["knn_20000"]
+    n = g["n_nodes"]
+    a = rama.solve(n, g["i"], g["j"], g["c"])
+    b = rama.solve(n, g["i"], g["j"], g["c"])
+    assert np.array_equal(np_(a["labels"]), np_(b["labels"]))
+    assert a["primal"] == b["primal"] and a["lower_bound"] == b["lower_bound"]
+    c1 = rama.find_conflicted_cycles(n, g["i"], g["j"], g["c"], 5)
+    m1 = rama.message_passing(n, g["i"], g["j"], g["c"], c1, 4)
+    m2 = rama.message_passing(n, g["i"], g["j"], g["c"], c1, 4)
+    assert np.array_equal(np_(m1["c"]), np_(m2["c"])) and m1["lower_bound"] == m2["lower_bound"]
+
+
+def test_degenerate_inputs(rama):
+    from paper_2109_01838_amd import RamaError, binding
+    e32, ef = np.zeros(0, np.int32), np.zeros(0, np.float32)
+    r = rama.solve(4, e32, e32, ef)
+    assert np_(r["labels"]).tolist() == [0, 1, 2, 3] and r["primal"] == 0.0 and r["lower_bound"] == 0.0
+    i, j = np.array([0, 1], np.int32), np.array([1, 2], np.int32)
+    r = rama.solve(3, i, j, np.array([-1.0, -2.0], np.float32))
+    assert np_(r["labels"]).tolist() == [0, 1, 2] and r["primal"] == -3.0 and r["lower_bound"] == -3.0
+    r = rama.solve(3, i, j, np.array([1.0, 2.0], np.float32))
+    assert np_(r["labels"]).tolist() == [0, 0, 0] and r["primal"] == 0.0
+    # only self-loops
+    r = rama.solve(2, np.array([0, 1], np.int32), np.array([0, 1], np.int32), np.array([1.0, -1.0], np.float32))
+    assert np_(r["labels"]).tolist() == [0, 1]
+    cyc = rama.find_conflicted_cycles(3, i, j, np.array([1.0, 2.0], np.float32), 5)
+    assert [x.shape[0] for x in cyc] == [0, 0, 0]
+    with pytest.raises(RamaError) as ei:
+        rama.solve(3, i, np.array([1, 3], np.int32), np.array([1.0, 1.0], np.float32))
+    assert ei.value.status == binding.RAMA_ERR_BAD_GRAPH
+    with pytest.raises(RamaError) as ei:
+        rama.solve(3, i, j, np.array([1.0, np.inf], np.float32))
+    assert ei.value.status == binding.RAMA_ERR_BAD_GRAPH
+    # the context stays usable after an error
+    r = rama.solve(3, i, j, np.array([1.0, 2.0], np.float32))
+    assert np_(r["labels"]).tolist() == [0, 0, 0]

@@ -1,0 +1,57 @@
+"""The C-ABI library loads and exports every symbol include/rama.h declares (no GPU needed)."""
+import ctypes as C
+import os
+import re
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "rama.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(rama_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    from paper_2109_01838_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2109_01838_amd import build
+        build.build_hip()
+    lib = binding.load_library()
+    names = declared_symbols()
+    assert {"rama_create", "rama_destroy", "rama_last_error", "rama_find_conflicted_cycles",
+            "rama_message_passing", "rama_contract", "rama_solve"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+    assert set(names) == set(binding.EXPORTS)
+
+
+def test_params_default_and_struct_layout():
+    from paper_2109_01838_amd import binding
+    p = binding.default_params()
+    assert (p.max_cycle_len_first, p.max_cycle_len_later, p.mp_iters_first, p.mp_iters_later) == (5, 3, 10, 5)
+    assert p.matching_rounds_cap == 32 and p.contract_threshold == 0.0 and p.max_rounds == 0
+    assert C.sizeof(binding.RamaParams) == 28
+    assert C.sizeof(binding.RamaStats) == 96
+
+
+def test_no_cpu_fallback_without_gpu():
+    import pytest
+    import torch
+    from paper_2109_01838_amd import Rama
+    if torch.cuda.is_available():
+        pytest.skip("GPU present")
+    with pytest.raises(RuntimeError):
+        Rama("cuda:0")
+
+
+def test_product_does_not_import_oracle():
+    pkg = os.path.join(ROOT, "paper_2109_01838_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "rama_oracle" not in text, f
+    for f in ("__init__.py", "rama_oracle.c"):
+        text = open(os.path.join(ROOT, "oracle", f)).read()
+        assert "paper_2109_01838_amd" not in text and "librama_hip" not in text
