@@ -89,6 +89,20 @@ void rama_params_default(rama_params *p);
 int64_t rama_workspace_bytes(const rama_ctx *ctx);
 
 /*
+ * Measurement hooks (not operations of the paper): per-kernel timers for roofline reports.
+ * While enabled, every kernel launch of the library is bracketed by two HIP events on the ctx
+ * stream and accounted under the kernel's name together with the algorithmic bytes that launch
+ * has to move (the launch site computes them from the array sizes).  Enabling resets the
+ * accumulators; `only` (may be NULL) restricts the timers to kernels whose name starts with it,
+ * which keeps the event overhead out of a timed region.  rama_profile_get returns entry `index` in [0, rama_profile_count): name
+ * (owned by the library), number of launches, summed milliseconds, summed algorithmic bytes.
+ */
+rama_status rama_profile_enable(rama_ctx *ctx, int32_t on, const char *only);
+int32_t rama_profile_count(const rama_ctx *ctx);
+rama_status rama_profile_get(const rama_ctx *ctx, int32_t index, const char **name, int64_t *launches, double *ms,
+                             double *bytes);
+
+/*
  * Conflicted-cycle separation (Sec. 3.2.2, definition "Conflicted cycles", and the appendix
  * algorithm "Parallel Conf. 5-Cycles"): every simple cycle of length L in {3,..,max_cycle_len}
  * with exactly one repulsive edge and L-1 attractive edges.

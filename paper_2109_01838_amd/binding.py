@@ -15,6 +15,7 @@ RAMA_OK, RAMA_ERR_INVALID_ARG, RAMA_ERR_BAD_GRAPH, RAMA_ERR_CAPACITY, RAMA_ERR_O
 
 EXPORTS = [
     "rama_create", "rama_destroy", "rama_last_error", "rama_params_default", "rama_workspace_bytes",
+    "rama_profile_enable", "rama_profile_count", "rama_profile_get",
     "rama_find_conflicted_cycles", "rama_message_passing", "rama_contract", "rama_solve",
 ]
 
@@ -76,8 +77,13 @@ def load_library():
                                   C.POINTER(i32), C.POINTER(i64)]
     lib.rama_solve.argtypes = [vp, i32, i64, vp, vp, vp, C.POINTER(RamaParams), vp, C.POINTER(C.c_double),
                                C.POINTER(C.c_double), C.POINTER(RamaStats)]
+    lib.rama_profile_enable.argtypes = [vp, i32, C.c_char_p]
+    lib.rama_profile_count.argtypes = [vp]
+    lib.rama_profile_count.restype = i32
+    lib.rama_profile_get.argtypes = [vp, i32, C.POINTER(C.c_char_p), C.POINTER(i64), C.POINTER(C.c_double),
+                                     C.POINTER(C.c_double)]
     for name in EXPORTS:
-        if name not in ("rama_last_error", "rama_params_default", "rama_workspace_bytes"):
+        if name not in ("rama_last_error", "rama_params_default", "rama_workspace_bytes", "rama_profile_count"):
             getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -148,6 +154,21 @@ class Rama:
 
     def workspace_bytes(self):
         return int(self.lib.rama_workspace_bytes(self.ctx))
+
+    def profile_enable(self, on=True, only=None):
+        self._check(self.lib.rama_profile_enable(self.ctx, 1 if on else 0, only.encode() if only else None),
+                    "rama_profile_enable")
+
+    def profile_get(self):
+        """Per-kernel totals since profiling was enabled: name, launches, ms, algorithmic bytes."""
+        self.torch.cuda.synchronize()
+        out = []
+        for k in range(self.lib.rama_profile_count(self.ctx)):
+            name, n, ms, by = C.c_char_p(), C.c_int64(0), C.c_double(0.0), C.c_double(0.0)
+            self._check(self.lib.rama_profile_get(self.ctx, k, C.byref(name), C.byref(n), C.byref(ms), C.byref(by)),
+                        "rama_profile_get")
+            out.append(dict(name=name.value.decode(), launches=n.value, ms=ms.value, bytes=by.value))
+        return out
 
     # -- entry points ---------------------------------------------------------------------------
     def find_conflicted_cycles(self, n_nodes, i, j, c, max_cycle_len=5):

@@ -16,7 +16,7 @@ double now_ms()
 
 rama_status finish(Ctx &ctx, rama_status st)
 {
-    hipError_t e = hipStreamSynchronize(ctx.stream);
+    hipError_t e = sync_stream(ctx);
     if (st == RAMA_OK && e != hipSuccess) {
         (void)hipGetLastError();
         return fail(ctx, RAMA_ERR_HIP, std::string("stream synchronize: ") + hipGetErrorString(e));
@@ -58,6 +58,8 @@ __global__ __launch_bounds__(kBlock) void k_labels(size_t n, const int32_t *f, c
 
 // objective of eq. 2 on the caller's edge list
 struct CutCost {
+    static constexpr int bytes = 20;   // bytes read per item
+    static constexpr const char *tag = "CutCost";
     const int32_t *i, *j;
     const float *c;
     const int32_t *labels;
@@ -83,7 +85,10 @@ rama_status solve_impl(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const i
     RAMA_TRY(canonicalise(ctx, n, m, i, j, c, g));
     Buf<int32_t> f;
     RAMA_TRY(f.alloc(ctx, (size_t)(n > 0 ? n : 1)));
-    k_iota32<<<grid_for((size_t)n), kBlock, 0, ctx.stream>>>((size_t)n, f.get());
+    {
+        ProfScope ps_(ctx, "k_iota32", (double)((size_t)n * 4));
+        k_iota32<<<grid_for((size_t)n), kBlock, 0, ctx.stream>>>((size_t)n, f.get());
+    }
     LAUNCH_TRY(ctx, "iota");
     double lb = 0.0;
     bool have_lb = false;
@@ -122,7 +127,10 @@ rama_status solve_impl(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const i
         RAMA_TRY(contract_once(ctx, g, P.contract_threshold, P.matching_rounds_cap, fprime, n_new, gn, ns));
         S.rounds = round;
         if (ns > 0) {
-            k_compose<<<grid_for((size_t)n), kBlock, 0, ctx.stream>>>((size_t)n, f.get(), fprime.get());
+            {
+                ProfScope ps_(ctx, "k_compose", (double)((size_t)n * 12));
+                k_compose<<<grid_for((size_t)n), kBlock, 0, ctx.stream>>>((size_t)n, f.get(), fprime.get());
+            }
             LAUNCH_TRY(ctx, "compose");
             g = std::move(gn);
             n_cur = n_new;
@@ -137,9 +145,15 @@ rama_status solve_impl(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const i
         RAMA_TRY(first.alloc(ctx, (size_t)(n_cur > 0 ? n_cur : 1)));
         RAMA_TRY(fill<int32_t>(ctx, first.get(), 0x7FFFFFFF, (size_t)n_cur));
         if (n > 0) {
-            k_cluster_min<<<grid_for((size_t)n), kBlock, 0, ctx.stream>>>((size_t)n, f.get(), first.get());
+            {
+                ProfScope ps_(ctx, "k_cluster_min", (double)((size_t)n * 12));
+                k_cluster_min<<<grid_for((size_t)n), kBlock, 0, ctx.stream>>>((size_t)n, f.get(), first.get());
+            }
             LAUNCH_TRY(ctx, "cluster_min");
-            k_labels<<<grid_for((size_t)n), kBlock, 0, ctx.stream>>>((size_t)n, f.get(), first.get(), labels);
+            {
+                ProfScope ps_(ctx, "k_labels", (double)((size_t)n * 12));
+                k_labels<<<grid_for((size_t)n), kBlock, 0, ctx.stream>>>((size_t)n, f.get(), first.get(), labels);
+            }
             LAUNCH_TRY(ctx, "labels");
         }
     }
@@ -187,6 +201,7 @@ rama_status rama_destroy(rama_ctx *ctx)
 {
     if (!ctx) return RAMA_OK;
     (void)hipStreamSynchronize(ctx->stream);
+    ctx->prof.destroy();
     ctx->pool.destroy();
     if (ctx->pinned) (void)hipHostFree(ctx->pinned);
     delete ctx;
@@ -208,6 +223,31 @@ void rama_params_default(rama_params *p)
 }
 
 int64_t rama_workspace_bytes(const rama_ctx *ctx) { return ctx ? (int64_t)ctx->pool.total() : 0; }
+
+rama_status rama_profile_enable(rama_ctx *ctx, int32_t on, const char *only)
+{
+    if (!ctx) return RAMA_ERR_INVALID_ARG;
+    ctx->prof.only = only ? only : "";
+    (void)hipStreamSynchronize(ctx->stream);
+    ctx->prof.collect();
+    if (on) ctx->prof.reset();
+    ctx->prof.on = on != 0;
+    return RAMA_OK;
+}
+
+int32_t rama_profile_count(const rama_ctx *ctx) { return ctx ? (int32_t)ctx->prof.stats.size() : 0; }
+
+rama_status rama_profile_get(const rama_ctx *ctx, int32_t index, const char **name, int64_t *launches, double *ms,
+                             double *bytes)
+{
+    if (!ctx || index < 0 || index >= (int32_t)ctx->prof.stats.size()) return RAMA_ERR_INVALID_ARG;
+    const KernelStat &k = ctx->prof.stats[index];
+    if (name) *name = k.name;
+    if (launches) *launches = (int64_t)k.launches;
+    if (ms) *ms = k.ms;
+    if (bytes) *bytes = k.bytes;
+    return RAMA_OK;
+}
 
 rama_status rama_find_conflicted_cycles(rama_ctx *ctx, int32_t n_nodes, int64_t n_edges, const int32_t *i,
                                         const int32_t *j, const float *c, int32_t max_cycle_len, int64_t cap3,
@@ -274,7 +314,10 @@ rama_status rama_contract(rama_ctx *ctx, int32_t n_nodes, int64_t n_edges, const
     auto body = [&]() -> rama_status {
         Graph g0, g;
         RAMA_TRY(canonicalise(*ctx, n_nodes, n_edges, i, j, c, g0));
-        k_iota32<<<grid_for((size_t)n_nodes), kBlock, 0, ctx->stream>>>((size_t)n_nodes, mapping);
+        {
+            ProfScope ps_(*ctx, "k_iota32", (double)((size_t)n_nodes * 4));
+            k_iota32<<<grid_for((size_t)n_nodes), kBlock, 0, ctx->stream>>>((size_t)n_nodes, mapping);
+        }
         LAUNCH_TRY(*ctx, "iota");
         const Graph *cur = &g0;
         int32_t n_cur = n_nodes;
@@ -285,7 +328,10 @@ rama_status rama_contract(rama_ctx *ctx, int32_t n_nodes, int64_t n_edges, const
             int64_t ns = 0;
             RAMA_TRY(contract_once(*ctx, *cur, params->contract_threshold, params->matching_rounds_cap, fprime, n_new, gn, ns));
             if (ns == 0) break;
-            k_compose<<<grid_for((size_t)n_nodes), kBlock, 0, ctx->stream>>>((size_t)n_nodes, mapping, fprime.get());
+            {
+                ProfScope ps_(*ctx, "k_compose", (double)((size_t)n_nodes * 12));
+                k_compose<<<grid_for((size_t)n_nodes), kBlock, 0, ctx->stream>>>((size_t)n_nodes, mapping, fprime.get());
+            }
             LAUNCH_TRY(*ctx, "compose");
             g = std::move(gn);
             cur = &g;

@@ -74,12 +74,79 @@ private:
     size_t total_ = 0;
 };
 
+// Per-kernel timers: when switched on, every instrumented launch is bracketed by two HIP events
+// on the ctx stream; elapsed times are collected at the next stream synchronisation.
+struct KernelStat {
+    const char *name;
+    uint64_t launches;
+    double ms;
+    double bytes;  // algorithmic bytes, summed over launches
+};
+class Profiler {
+public:
+    bool on = false;
+    std::string only;   // when non-empty, only kernels whose name starts with this are timed
+    std::vector<KernelStat> stats;
+    bool wants(const char *name) const { return on && (only.empty() || strncmp(name, only.c_str(), only.size()) == 0); }
+    void begin(hipStream_t s, const char *name, double bytes)
+    {
+        Pending p{id_of(name), get_event(), get_event(), bytes};
+        (void)hipEventRecord(p.a, s);
+        pending_.push_back(p);
+    }
+    void end(hipStream_t s) { (void)hipEventRecord(pending_.back().b, s); }
+    // call only when the stream has been synchronised
+    void collect()
+    {
+        for (auto &p : pending_) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, p.a, p.b) == hipSuccess) {
+                stats[p.id].launches += 1;
+                stats[p.id].ms += ms;
+                stats[p.id].bytes += p.bytes;
+            } else {
+                (void)hipGetLastError();
+            }
+            free_.push_back(p.a);
+            free_.push_back(p.b);
+        }
+        pending_.clear();
+    }
+    void reset() { stats.clear(); }
+    void destroy()
+    {
+        collect();
+        for (auto e : free_) (void)hipEventDestroy(e);
+        free_.clear();
+    }
+
+private:
+    struct Pending { int id; hipEvent_t a, b; double bytes; };
+    int id_of(const char *name)
+    {
+        for (int k = 0; k < (int)stats.size(); ++k)
+            if (stats[k].name == name || strcmp(stats[k].name, name) == 0) return k;
+        stats.push_back({name, 0, 0.0, 0.0});
+        return (int)stats.size() - 1;
+    }
+    hipEvent_t get_event()
+    {
+        if (!free_.empty()) { hipEvent_t e = free_.back(); free_.pop_back(); return e; }
+        hipEvent_t e = nullptr;
+        (void)hipEventCreate(&e);
+        return e;
+    }
+    std::vector<Pending> pending_;
+    std::vector<hipEvent_t> free_;
+};
+
 }  // namespace rama
 
 struct rama_ctx {
     hipStream_t stream = nullptr;
     int device = 0;
     rama::Pool pool;
+    rama::Profiler prof;
     std::string err;
     void *pinned = nullptr;  // small pinned host block for scalar read-backs
     static constexpr size_t kPinnedBytes = 4096;
@@ -88,6 +155,27 @@ struct rama_ctx {
 namespace rama {
 
 using Ctx = rama_ctx;
+
+// brackets the launches made during its lifetime with the profiler's events (no-op when off)
+struct ProfScope {
+    Ctx &ctx;
+    bool active;
+    ProfScope(Ctx &c, const char *name, double bytes) : ctx(c), active(c.prof.wants(name))
+    {
+        if (active) ctx.prof.begin(ctx.stream, name, bytes);
+    }
+    ~ProfScope()
+    {
+        if (active) ctx.prof.end(ctx.stream);
+    }
+};
+
+inline hipError_t sync_stream(Ctx &ctx)
+{
+    hipError_t e = hipStreamSynchronize(ctx.stream);
+    if (e == hipSuccess && ctx.prof.on) ctx.prof.collect();
+    return e;
+}
 
 inline rama_status fail(Ctx &ctx, rama_status st, const std::string &msg)
 {
@@ -172,11 +260,11 @@ inline rama_status read_back(Ctx &ctx, void *host, const void *dev, size_t bytes
 {
     if (bytes <= Ctx::kPinnedBytes) {
         HIP_TRY(ctx, hipMemcpyAsync(ctx.pinned, dev, bytes, hipMemcpyDeviceToHost, ctx.stream));
-        HIP_TRY(ctx, hipStreamSynchronize(ctx.stream));
+        HIP_TRY(ctx, sync_stream(ctx));
         memcpy(host, ctx.pinned, bytes);
     } else {
         HIP_TRY(ctx, hipMemcpyAsync(host, dev, bytes, hipMemcpyDeviceToHost, ctx.stream));
-        HIP_TRY(ctx, hipStreamSynchronize(ctx.stream));
+        HIP_TRY(ctx, sync_stream(ctx));
     }
     return RAMA_OK;
 }

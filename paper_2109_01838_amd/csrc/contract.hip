@@ -27,6 +27,8 @@ __device__ __forceinline__ unsigned long long edge_rank(float cost, uint32_t e)
 }
 
 struct CandFlag {
+    static constexpr int bytes = 4;   // bytes read per item
+    static constexpr const char *tag = "CandFlag";
     const float *c;
     float tau;
     __device__ __forceinline__ uint32_t operator()(size_t e) const { return c[e] > tau ? 1u : 0u; }
@@ -61,6 +63,8 @@ __global__ __launch_bounds__(kBlock) void k_accept(size_t na, const uint32_t *ac
 }
 
 struct StillFree {
+    static constexpr int bytes = 20;   // bytes read per item
+    static constexpr const char *tag = "StillFree";
     const uint32_t *act;
     const int32_t *i, *j, *mate;
     __device__ __forceinline__ uint32_t operator()(size_t a) const
@@ -85,6 +89,8 @@ __global__ __launch_bounds__(kBlock) void k_advance(size_t na, const uint32_t *a
 }
 
 struct MatchedLow {
+    static constexpr int bytes = 4;   // bytes read per item
+    static constexpr const char *tag = "MatchedLow";
     const int32_t *mate;
     __device__ __forceinline__ uint32_t operator()(size_t v) const { return mate[v] > (int32_t)v ? 1u : 0u; }
 };
@@ -130,6 +136,8 @@ __global__ __launch_bounds__(kBlock) void k_flatten(size_t n, int32_t *parent)
 }
 
 struct IsRoot {
+    static constexpr int bytes = 4;   // bytes read per item
+    static constexpr const char *tag = "IsRoot";
     const int32_t *rep;
     __device__ __forceinline__ uint32_t operator()(size_t v) const { return rep[v] == (int32_t)v ? 1u : 0u; }
 };
@@ -142,10 +150,14 @@ __global__ __launch_bounds__(kBlock) void k_number(size_t n, const int32_t *rep,
 
 // ---- contraction ---------------------------------------------------------------------------------
 struct CrossFlag {
+    static constexpr int bytes = 16;   // bytes read per item
+    static constexpr const char *tag = "CrossFlag";
     const int32_t *i, *j, *fmap;
     __device__ __forceinline__ uint32_t operator()(size_t e) const { return fmap[i[e]] != fmap[j[e]] ? 1u : 0u; }
 };
 struct InnerFlag {
+    static constexpr int bytes = 16;   // bytes read per item
+    static constexpr const char *tag = "InnerFlag";
     const int32_t *i, *j, *fmap;
     __device__ __forceinline__ uint32_t operator()(size_t e) const { return fmap[i[e]] == fmap[j[e]] ? 1u : 0u; }
 };
@@ -177,6 +189,8 @@ __global__ __launch_bounds__(kBlock) void k_inner(size_t m, const int32_t *i, co
 }
 
 struct HeadFlag {
+    static constexpr int bytes = 8;   // bytes read per item
+    static constexpr const char *tag = "HeadFlag";
     const uint64_t *key;
     __device__ __forceinline__ uint32_t operator()(size_t e) const { return (e == 0 || key[e] != key[e - 1]) ? 1u : 0u; }
 };
@@ -210,23 +224,35 @@ static rama_status matching(Ctx &ctx, const Graph &g, float tau, int rounds_cap,
     if (na == 0) return RAMA_OK;
     RAMA_TRY(act.alloc(ctx, na));
     RAMA_TRY(act2.alloc(ctx, na));
-    k_collect<<<grid_for(m), kBlock, 0, ctx.stream>>>(m, g.c.get(), tau, pos.get(), act.get());
+    {
+        ProfScope ps_(ctx, "k_collect", (double)(m * 8 + (size_t)na * 4));
+        k_collect<<<grid_for(m), kBlock, 0, ctx.stream>>>(m, g.c.get(), tau, pos.get(), act.get());
+    }
     LAUNCH_TRY(ctx, "collect");
     Buf<unsigned long long> best;
     RAMA_TRY(best.alloc(ctx, n));
     RAMA_TRY(fill<unsigned long long>(ctx, best.get(), 0ull, n));
     for (int r = 0; r < rounds_cap && na > 0; ++r) {
-        k_propose<<<grid_for(na), kBlock, 0, ctx.stream>>>(na, act.get(), g.i.get(), g.j.get(), g.c.get(), best.get());
+        {
+            ProfScope ps_(ctx, "k_propose", (double)((size_t)na * 32));
+            k_propose<<<grid_for(na), kBlock, 0, ctx.stream>>>(na, act.get(), g.i.get(), g.j.get(), g.c.get(), best.get());
+        }
         LAUNCH_TRY(ctx, "propose");
-        k_accept<<<grid_for(na), kBlock, 0, ctx.stream>>>(na, act.get(), g.i.get(), g.j.get(), g.c.get(), best.get(),
+        {
+            ProfScope ps_(ctx, "k_accept", (double)((size_t)na * 40));
+            k_accept<<<grid_for(na), kBlock, 0, ctx.stream>>>(na, act.get(), g.i.get(), g.j.get(), g.c.get(), best.get(),
                                                          mate.get());
+        }
         LAUNCH_TRY(ctx, "accept");
         RAMA_TRY((exclusive_scan<uint32_t>(ctx, StillFree{act.get(), g.i.get(), g.j.get(), mate.get()}, pos.get(), (size_t)na)));
         uint32_t nn = 0;
         RAMA_TRY(read_back(ctx, &nn, pos.get() + na, 4));
         if (nn > 0) {
-            k_advance<<<grid_for(na), kBlock, 0, ctx.stream>>>(na, act.get(), pos.get(), g.i.get(), g.j.get(), act2.get(),
+            {
+                ProfScope ps_(ctx, "k_advance", (double)((size_t)na * 16 + (size_t)nn * 24));
+                k_advance<<<grid_for(na), kBlock, 0, ctx.stream>>>(na, act.get(), pos.get(), g.i.get(), g.j.get(), act2.get(),
                                                               best.get());
+            }
             LAUNCH_TRY(ctx, "advance");
             act.swap(act2);
         }
@@ -245,16 +271,25 @@ static rama_status matching(Ctx &ctx, const Graph &g, float tau, int rounds_cap,
 static rama_status components(Ctx &ctx, size_t n, size_t ns, const int32_t *si, const int32_t *sj, Buf<int32_t> &rep)
 {
     RAMA_TRY(rep.alloc(ctx, n > 0 ? n : 1));
-    k_iota<<<grid_for(n), kBlock, 0, ctx.stream>>>(n, rep.get());
+    {
+        ProfScope ps_(ctx, "k_iota", (double)(n * 4));
+        k_iota<<<grid_for(n), kBlock, 0, ctx.stream>>>(n, rep.get());
+    }
     LAUNCH_TRY(ctx, "iota");
     if (ns == 0) return RAMA_OK;
     Buf<int32_t> changed;
     RAMA_TRY(changed.alloc(ctx, 1));
     for (int it = 0; it < 64; ++it) {   // the number of trees at least halves per sweep
         RAMA_TRY(fill<int32_t>(ctx, changed.get(), 0, 1));
-        k_hook<<<grid_for(ns), kBlock, 0, ctx.stream>>>(ns, si, sj, rep.get(), changed.get());
+        {
+            ProfScope ps_(ctx, "k_hook", (double)(ns * 24));
+            k_hook<<<grid_for(ns), kBlock, 0, ctx.stream>>>(ns, si, sj, rep.get(), changed.get());
+        }
         LAUNCH_TRY(ctx, "hook");
-        k_flatten<<<grid_for(n), kBlock, 0, ctx.stream>>>(n, rep.get());
+        {
+            ProfScope ps_(ctx, "k_flatten", (double)(n * 12));
+            k_flatten<<<grid_for(n), kBlock, 0, ctx.stream>>>(n, rep.get());
+        }
         LAUNCH_TRY(ctx, "flatten");
         int32_t h = 0;
         RAMA_TRY(read_back(ctx, &h, changed.get(), 4));
@@ -285,8 +320,11 @@ static rama_status contract_edges(Ctx &ctx, const Graph &g, const int32_t *fmap,
     Buf<uint32_t> val;
     RAMA_TRY(key.alloc(ctx, kept));
     RAMA_TRY(val.alloc(ctx, kept));
-    k_relabel<<<grid_for(m), kBlock, 0, ctx.stream>>>(m, g.i.get(), g.j.get(), g.c.get(), fmap, pos.get(), nbits,
+    {
+        ProfScope ps_(ctx, "k_relabel", (double)(m * 28 + (size_t)kept * 12));
+        k_relabel<<<grid_for(m), kBlock, 0, ctx.stream>>>(m, g.i.get(), g.j.get(), g.c.get(), fmap, pos.get(), nbits,
                                                       key.get(), val.get());
+    }
     LAUNCH_TRY(ctx, "relabel");
     pos.reset();
     RAMA_TRY((radix_sort_pairs<uint64_t, uint32_t>(ctx, key, val, kept, 2 * nbits)));
@@ -298,8 +336,11 @@ static rama_status contract_edges(Ctx &ctx, const Graph &g, const int32_t *fmap,
     RAMA_TRY(out.i.alloc(ctx, uniq));
     RAMA_TRY(out.j.alloc(ctx, uniq));
     RAMA_TRY(out.c.alloc(ctx, uniq));
-    k_reduce_runs<<<grid_for(kept), kBlock, 0, ctx.stream>>>(kept, key.get(), val.get(), opos.get(), nbits, out.i.get(),
+    {
+        ProfScope ps_(ctx, "k_reduce_runs", (double)((size_t)kept * 16 + (size_t)uniq * 12));
+        k_reduce_runs<<<grid_for(kept), kBlock, 0, ctx.stream>>>(kept, key.get(), val.get(), opos.get(), nbits, out.i.get(),
                                                             out.j.get(), out.c.get());
+    }
     LAUNCH_TRY(ctx, "reduce_runs");
     out.m = uniq;
     return RAMA_OK;
@@ -320,7 +361,10 @@ rama_status contract_once(Ctx &ctx, const Graph &g, float tau, int rounds_cap, B
     RAMA_TRY((exclusive_scan<uint32_t>(ctx, MatchedLow{mate.get()}, npos.get(), n)));
     RAMA_TRY(si.alloc(ctx, ns));
     RAMA_TRY(sj.alloc(ctx, ns));
-    k_emit_pairs<<<grid_for(n), kBlock, 0, ctx.stream>>>(n, mate.get(), npos.get(), si.get(), sj.get());
+    {
+        ProfScope ps_(ctx, "k_emit_pairs", (double)(n * 8 + ns * 8));
+        k_emit_pairs<<<grid_for(n), kBlock, 0, ctx.stream>>>(n, mate.get(), npos.get(), si.get(), sj.get());
+    }
     LAUNCH_TRY(ctx, "emit_pairs");
     RAMA_TRY(components(ctx, n, ns, si.get(), sj.get(), rep));
     RAMA_TRY((exclusive_scan<uint32_t>(ctx, IsRoot{rep.get()}, npos.get(), n)));
@@ -328,7 +372,10 @@ rama_status contract_once(Ctx &ctx, const Graph &g, float tau, int rounds_cap, B
     RAMA_TRY(read_back(ctx, &nn, npos.get() + n, 4));
     n_new = (int32_t)nn;
     RAMA_TRY(fmap.alloc(ctx, n));
-    k_number<<<grid_for(n), kBlock, 0, ctx.stream>>>(n, rep.get(), npos.get(), fmap.get());
+    {
+        ProfScope ps_(ctx, "k_number", (double)(n * 12));
+        k_number<<<grid_for(n), kBlock, 0, ctx.stream>>>(n, rep.get(), npos.get(), fmap.get());
+    }
     LAUNCH_TRY(ctx, "number");
     RAMA_TRY(contract_edges(ctx, g, fmap.get(), n_new, out));
     return RAMA_OK;
@@ -348,10 +395,16 @@ rama_status contraction_diagonal(Ctx &ctx, const Graph &g, const int32_t *fmap, 
     Buf<uint32_t> key, val;
     RAMA_TRY(key.alloc(ctx, kept));
     RAMA_TRY(val.alloc(ctx, kept));
-    k_inner<<<grid_for(m), kBlock, 0, ctx.stream>>>(m, g.i.get(), g.j.get(), g.c.get(), fmap, pos.get(), key.get(), val.get());
+    {
+        ProfScope ps_(ctx, "k_inner", (double)(m * 28 + (size_t)kept * 8));
+        k_inner<<<grid_for(m), kBlock, 0, ctx.stream>>>(m, g.i.get(), g.j.get(), g.c.get(), fmap, pos.get(), key.get(), val.get());
+    }
     LAUNCH_TRY(ctx, "inner");
     RAMA_TRY((radix_sort_pairs<uint32_t, uint32_t>(ctx, key, val, kept, bits_for((uint64_t)n_new))));
-    k_diag_runs<<<grid_for(kept), kBlock, 0, ctx.stream>>>(kept, key.get(), val.get(), diag);
+    {
+        ProfScope ps_(ctx, "k_diag_runs", (double)((size_t)kept * 12));
+        k_diag_runs<<<grid_for(kept), kBlock, 0, ctx.stream>>>(kept, key.get(), val.get(), diag);
+    }
     LAUNCH_TRY(ctx, "diag_runs");
     return RAMA_OK;
 }

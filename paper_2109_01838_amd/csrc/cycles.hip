@@ -17,10 +17,14 @@ namespace rama {
 namespace {
 
 struct PosFlag {
+    static constexpr int bytes = 4;   // bytes read per item
+    static constexpr const char *tag = "PosFlag";
     const float *c;
     __device__ __forceinline__ uint32_t operator()(size_t e) const { return c[e] > 0.0f ? 1u : 0u; }
 };
 struct NegFlag {
+    static constexpr int bytes = 4;   // bytes read per item
+    static constexpr const char *tag = "NegFlag";
     const float *c;
     __device__ __forceinline__ uint32_t operator()(size_t e) const { return c[e] < 0.0f ? 1u : 0u; }
 };
@@ -178,8 +182,11 @@ rama_status find_cycles(Ctx &ctx, const Graph &g, int max_len, bool count_only, 
     RAMA_TRY(lval.alloc(ctx, mp));
     RAMA_TRY(ri.alloc(ctx, mr));
     RAMA_TRY(rj.alloc(ctx, mr));
-    k_split_sign<<<grid_for(m), kBlock, 0, ctx.stream>>>(m, g.i.get(), g.j.get(), g.c.get(), ppos.get(), npos.get(),
+    {
+        ProfScope ps_(ctx, "k_split_sign", (double)(m * 20 + (size_t)mp * 16 + (size_t)mr * 8));
+        k_split_sign<<<grid_for(m), kBlock, 0, ctx.stream>>>(m, g.i.get(), g.j.get(), g.c.get(), ppos.get(), npos.get(),
                                                          pi.get(), pj.get(), lkey.get(), lval.get(), ri.get(), rj.get());
+    }
     LAUNCH_TRY(ctx, "split_sign");
     ppos.reset();
     npos.reset();
@@ -193,10 +200,16 @@ rama_status find_cycles(Ctx &ctx, const Graph &g, int max_len, bool count_only, 
     RAMA_TRY((row_bounds<int32_t, int32_t>(ctx, pi.get(), mp, n, up_ptr.get())));
     RAMA_TRY((radix_sort_pairs<uint32_t, uint32_t>(ctx, lkey, lval, mp, bits_for((uint64_t)n))));
     RAMA_TRY((row_bounds<uint32_t, int32_t>(ctx, lkey.get(), mp, n, low_ptr.get())));
-    k_add_ptr<<<grid_for((size_t)n + 1), kBlock, 0, ctx.stream>>>(n, up_ptr.get(), low_ptr.get(), rowptr.get());
+    {
+        ProfScope ps_(ctx, "k_add_ptr", (double)(((size_t)n + 1) * 12));
+        k_add_ptr<<<grid_for((size_t)n + 1), kBlock, 0, ctx.stream>>>(n, up_ptr.get(), low_ptr.get(), rowptr.get());
+    }
     LAUNCH_TRY(ctx, "add_ptr");
-    k_fill_adj<<<grid_for(mp), kBlock, 0, ctx.stream>>>(mp, pi.get(), pj.get(), lkey.get(), lval.get(), up_ptr.get(),
+    {
+        ProfScope ps_(ctx, "k_fill_adj", (double)((size_t)mp * 24 + ((size_t)n + 1) * 12));
+        k_fill_adj<<<grid_for(mp), kBlock, 0, ctx.stream>>>(mp, pi.get(), pj.get(), lkey.get(), lval.get(), up_ptr.get(),
                                                         low_ptr.get(), rowptr.get(), nb.get());
+    }
     LAUNCH_TRY(ctx, "fill_adj");
     pi.reset(); pj.reset(); lkey.reset(); lval.reset(); up_ptr.reset(); low_ptr.reset();
     Adj adj{rowptr.get(), nb.get()};
@@ -207,8 +220,11 @@ rama_status find_cycles(Ctx &ctx, const Graph &g, int max_len, bool count_only, 
         RAMA_TRY(cnt[k].alloc(ctx, mr));
         RAMA_TRY(off[k].alloc(ctx, (size_t)mr + 1));
     }
-    k_count_cycles<<<grid_for(mr), kBlock, 0, ctx.stream>>>(mr, ri.get(), rj.get(), adj, max_len, cnt[0].get(),
+    {
+        ProfScope ps_(ctx, "k_count_cycles", (double)((size_t)mr * 20 + ((size_t)n + 1) * 4 + (size_t)mp * 8));
+        k_count_cycles<<<grid_for(mr), kBlock, 0, ctx.stream>>>(mr, ri.get(), rj.get(), adj, max_len, cnt[0].get(),
                                                            cnt[1].get(), cnt[2].get());
+    }
     LAUNCH_TRY(ctx, "count_cycles");
     uint64_t tot[3];
     for (int k = 0; k < 3; ++k) {
@@ -223,9 +239,12 @@ rama_status find_cycles(Ctx &ctx, const Graph &g, int max_len, bool count_only, 
         RAMA_TRY(out.v[k].alloc(ctx, (size_t)(k + 3) * tot[k]));
     }
     if (tot[0] + tot[1] + tot[2] == 0) return RAMA_OK;
-    k_fill_cycles<<<grid_for(mr), kBlock, 0, ctx.stream>>>(mr, ri.get(), rj.get(), adj, max_len, off[0].get(),
+    {
+        ProfScope ps_(ctx, "k_fill_cycles", (double)((size_t)mr * 32 + ((size_t)n + 1) * 4 + (size_t)mp * 8 + 12.0 * tot[0] + 16.0 * tot[1] + 20.0 * tot[2]));
+        k_fill_cycles<<<grid_for(mr), kBlock, 0, ctx.stream>>>(mr, ri.get(), rj.get(), adj, max_len, off[0].get(),
                                                           off[1].get(), off[2].get(), out.v[0].get(), out.v[1].get(),
                                                           out.v[2].get());
+    }
     LAUNCH_TRY(ctx, "fill_cycles");
     return RAMA_OK;
 }

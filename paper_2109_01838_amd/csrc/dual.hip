@@ -13,8 +13,9 @@
 // It runs as two kernels without atomics:
 //   triangle kernel: gathers the three shares, does the six updates in registers, writes c_t and
 //                    the three outgoing messages;
-//   edge kernel:     adds the messages of an edge in ascending triangle order (slot list built
-//                    once per round by a stable sort) and stores the next share c_e/N_e.
+//   edge kernel:     one thread per edge that lies in a triangle; adds its messages in ascending
+//                    triangle order (slot list built once per round by a stable sort) and stores
+//                    the next share c_e/N_e.  Work is proportional to the triangles, not the edges.
 #include "prim.h"
 
 namespace rama {
@@ -109,6 +110,8 @@ __global__ __launch_bounds__(kBlock) void k_chord_keys(CycleSet s, size_t nch, i
 
 // first-of-run flag that also requires the chord to be absent from the graph
 struct NewChordFlag {
+    static constexpr int bytes = 16;   // bytes read per item
+    static constexpr const char *tag = "NewChordFlag";
     const uint64_t *key;
     const int32_t *rowptr, *j;
     int nbits;
@@ -172,6 +175,8 @@ __global__ __launch_bounds__(kBlock) void k_triangle_keys(CycleSet s, size_t nt,
 }
 
 struct HeadFlag64 {
+    static constexpr int bytes = 8;   // bytes read per item
+    static constexpr const char *tag = "HeadFlag64";
     const uint64_t *key;
     __device__ __forceinline__ uint32_t operator()(size_t e) const { return (e == 0 || key[e] != key[e - 1]) ? 1u : 0u; }
 };
@@ -202,12 +207,32 @@ __global__ __launch_bounds__(kBlock) void k_triangle_edges(size_t nt, const uint
 // ---------------------------------------------------------------------------------------------
 // message passing
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kBlock) void k_edge_init(size_t m, const float *ce, const int32_t *slot_ptr, float *share)
+// edges that lie in at least one triangle ("active"): runs of equal edge id in the sorted slot list
+struct HeadFlag32 {
+    static constexpr int bytes = 4;   // bytes read per item
+    static constexpr const char *tag = "HeadFlag32";
+    const uint32_t *key;
+    __device__ __forceinline__ uint32_t operator()(size_t p) const { return (p == 0 || key[p] != key[p - 1]) ? 1u : 0u; }
+};
+
+__global__ __launch_bounds__(kBlock) void k_active_edges(size_t ns, const uint32_t *skey, const uint32_t *pos,
+                                                         uint32_t *act_edge, uint32_t *act_start)
 {
-    size_t e = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    if (e >= m) return;
-    int32_t cnt = slot_ptr[e + 1] - slot_ptr[e];
-    share[e] = cnt > 0 ? ce[e] / (float)cnt : 0.0f;
+    size_t p = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (p >= ns) return;
+    if (p == 0) act_start[pos[ns]] = (uint32_t)ns;
+    if (pos[p] == pos[p + 1]) return;
+    act_edge[pos[p]] = skey[p];
+    act_start[pos[p]] = (uint32_t)p;
+}
+
+__global__ __launch_bounds__(kBlock) void k_edge_init(size_t na, const uint32_t *act_edge, const uint32_t *act_start,
+                                                      const float *ce, float *share)
+{
+    size_t a = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (a >= na) return;
+    uint32_t e = act_edge[a];
+    share[e] = ce[e] / (float)(act_start[a + 1] - act_start[a]);
 }
 
 // costs of the four non-trivial labelings of M_T = {000,110,101,011,111}
@@ -255,24 +280,28 @@ __global__ __launch_bounds__(kBlock) void k_triangle_update(size_t T, const int3
     msg[3 * t] = oa; msg[3 * t + 1] = ob; msg[3 * t + 2] = oc;
 }
 
-__global__ __launch_bounds__(kBlock) void k_edge_update(size_t m, const int32_t *slot_ptr, const uint32_t *slot,
-                                                        const float *msg, float *ce, float *share)
+// one thread per active edge; an edge in no triangle is never touched and keeps its cost
+__global__ __launch_bounds__(kBlock) void k_edge_update(size_t na, const uint32_t *act_edge, const uint32_t *act_start,
+                                                        const uint32_t *slot, const float *msg, float *ce, float *share)
 {
-    size_t e = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    if (e >= m) return;
-    int32_t p0 = slot_ptr[e], p1 = slot_ptr[e + 1];
-    if (p0 == p1) return;                  // edge in no triangle keeps its cost
+    size_t a = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (a >= na) return;
+    const uint32_t e = act_edge[a], p0 = act_start[a], p1 = act_start[a + 1];
     float acc = 0.0f;
-    for (int32_t p = p0; p < p1; ++p) acc = acc + msg[slot[p]];
+    for (uint32_t p = p0; p < p1; ++p) acc = acc + msg[slot[p]];
     ce[e] = acc;
     share[e] = acc / (float)(p1 - p0);
 }
 
 struct EdgeLB {
+    static constexpr int bytes = 4;   // bytes read per item
+    static constexpr const char *tag = "EdgeLB";
     const float *ce;
     __device__ __forceinline__ double operator()(size_t e) const { float w = ce[e]; return w < 0.0f ? (double)w : 0.0; }
 };
 struct TriLB {
+    static constexpr int bytes = 12;   // bytes read per item
+    static constexpr const char *tag = "TriLB";
     const float *ct;
     __device__ __forceinline__ double operator()(size_t t) const
     {
@@ -341,8 +370,11 @@ rama_status dual_update(Ctx &ctx, const Graph &g, const int32_t *c3, int64_t n3,
     RAMA_TRY(rowptr.alloc(ctx, (size_t)n + 1));
     RAMA_TRY((row_bounds<int32_t, int32_t>(ctx, g.i.get(), m, n, rowptr.get())));
     if (validate_cycles) {
-        k_validate_cycles<<<grid_for((size_t)(n3 + n4 + n5)), kBlock, 0, ctx.stream>>>(cs, n, rowptr.get(), g.j.get(),
+        {
+            ProfScope ps_(ctx, "k_validate_cycles", (double)(12.0 * n3 + 16.0 * n4 + 20.0 * n5));
+            k_validate_cycles<<<grid_for((size_t)(n3 + n4 + n5)), kBlock, 0, ctx.stream>>>(cs, n, rowptr.get(), g.j.get(),
                                                                                      flag.get());
+        }
         LAUNCH_TRY(ctx, "validate_cycles");
         int32_t hf = 0;
         RAMA_TRY(read_back(ctx, &hf, flag.get(), 4));
@@ -355,7 +387,10 @@ rama_status dual_update(Ctx &ctx, const Graph &g, const int32_t *c3, int64_t n3,
     if (nch > 0) {
         Buf<uint64_t> ckey;
         RAMA_TRY(ckey.alloc(ctx, nch));
-        k_chord_keys<<<grid_for(nch), kBlock, 0, ctx.stream>>>(cs, nch, nbits, ckey.get());
+        {
+            ProfScope ps_(ctx, "k_chord_keys", (double)(nch * 24));
+            k_chord_keys<<<grid_for(nch), kBlock, 0, ctx.stream>>>(cs, nch, nbits, ckey.get());
+        }
         LAUNCH_TRY(ctx, "chord_keys");
         RAMA_TRY((radix_sort_keys<uint64_t>(ctx, ckey, nch, 2 * nbits)));
         Buf<uint32_t> cpos;
@@ -368,8 +403,11 @@ rama_status dual_update(Ctx &ctx, const Graph &g, const int32_t *c3, int64_t n3,
             RAMA_TRY(cj.alloc(ctx, nnew));
             RAMA_TRY(before.alloc(ctx, nnew));
             RAMA_TRY(ins.alloc(ctx, m + 2));
-            k_emit_chords<<<grid_for(nch), kBlock, 0, ctx.stream>>>(nch, ckey.get(), cpos.get(), rowptr.get(), g.j.get(),
+            {
+                ProfScope ps_(ctx, "k_emit_chords", (double)(nch * 16 + (size_t)nnew * 12));
+                k_emit_chords<<<grid_for(nch), kBlock, 0, ctx.stream>>>(nch, ckey.get(), cpos.get(), rowptr.get(), g.j.get(),
                                                                    nbits, ci.get(), cj.get(), before.get());
+            }
             LAUNCH_TRY(ctx, "emit_chords");
             // ins[v] = number of chords with before < v ; chords placed before edge e: before <= e -> ins[e+1]
             RAMA_TRY((row_bounds<int32_t, int32_t>(ctx, before.get(), nnew, (int64_t)m + 1, ins.get())));
@@ -378,9 +416,12 @@ rama_status dual_update(Ctx &ctx, const Graph &g, const int32_t *c3, int64_t n3,
             RAMA_TRY(aug.j.alloc(ctx, (size_t)aug.m));
             RAMA_TRY(aug.c.alloc(ctx, (size_t)aug.m));
             size_t span = m > nnew ? m : nnew;
-            k_merge_edges<<<grid_for(span), kBlock, 0, ctx.stream>>>(m, g.i.get(), g.j.get(), g.c.get(), ins.get(), nnew,
+            {
+                ProfScope ps_(ctx, "k_merge_edges", (double)(m * 16 + (size_t)nnew * 12 + (m + nnew) * 12));
+                k_merge_edges<<<grid_for(span), kBlock, 0, ctx.stream>>>(m, g.i.get(), g.j.get(), g.c.get(), ins.get(), nnew,
                                                                     ci.get(), cj.get(), before.get(), aug.i.get(),
                                                                     aug.j.get(), aug.c.get());
+            }
             LAUNCH_TRY(ctx, "merge_edges");
             RAMA_TRY((row_bounds<int32_t, int32_t>(ctx, aug.i.get(), (size_t)aug.m, n, rowptr.get())));
         }
@@ -390,8 +431,11 @@ rama_status dual_update(Ctx &ctx, const Graph &g, const int32_t *c3, int64_t n3,
     // ---- triangles -----------------------------------------------------------------------------
     Buf<uint64_t> tkey;
     RAMA_TRY(tkey.alloc(ctx, nfan));
-    k_triangle_keys<<<grid_for(nfan), kBlock, 0, ctx.stream>>>(cs, nfan, rowptr.get(), aug.j.get(), nbits, tkey.get(),
+    {
+        ProfScope ps_(ctx, "k_triangle_keys", (double)(nfan * 20));
+        k_triangle_keys<<<grid_for(nfan), kBlock, 0, ctx.stream>>>(cs, nfan, rowptr.get(), aug.j.get(), nbits, tkey.get(),
                                                               flag.get());
+    }
     LAUNCH_TRY(ctx, "triangle_keys");
     RAMA_TRY((radix_sort_keys<uint64_t>(ctx, tkey, nfan, bits_for((uint64_t)ma) + nbits)));
     Buf<uint32_t> tpos;
@@ -406,9 +450,12 @@ rama_status dual_update(Ctx &ctx, const Graph &g, const int32_t *c3, int64_t n3,
     RAMA_TRY(tri_edge.alloc(ctx, 3 * T));
     RAMA_TRY(skey.alloc(ctx, 3 * T));
     RAMA_TRY(slot.alloc(ctx, 3 * T));
-    k_triangle_edges<<<grid_for(nfan), kBlock, 0, ctx.stream>>>(nfan, tkey.get(), tpos.get(), rowptr.get(), aug.i.get(),
+    {
+        ProfScope ps_(ctx, "k_triangle_edges", (double)(nfan * 12 + T * 44));
+        k_triangle_edges<<<grid_for(nfan), kBlock, 0, ctx.stream>>>(nfan, tkey.get(), tpos.get(), rowptr.get(), aug.i.get(),
                                                                aug.j.get(), nbits, tri_edge.get(), skey.get(),
                                                                slot.get(), flag.get());
+    }
     LAUNCH_TRY(ctx, "triangle_edges");
     tkey.reset();
     tpos.reset();
@@ -419,9 +466,21 @@ rama_status dual_update(Ctx &ctx, const Graph &g, const int32_t *c3, int64_t n3,
     }
     // ---- incidence: slots of every edge in ascending triangle order ----------------------------
     RAMA_TRY((radix_sort_pairs<uint32_t, uint32_t>(ctx, skey, slot, 3 * T, bits_for((uint64_t)ma))));
-    Buf<int32_t> slot_ptr;
-    RAMA_TRY(slot_ptr.alloc(ctx, ma + 1));
-    RAMA_TRY((row_bounds<uint32_t, int32_t>(ctx, skey.get(), 3 * T, (int64_t)ma, slot_ptr.get())));
+    Buf<uint32_t> apos, act_edge, act_start;
+    RAMA_TRY(apos.alloc(ctx, 3 * T + 1));
+    RAMA_TRY((exclusive_scan<uint32_t>(ctx, HeadFlag32{skey.get()}, apos.get(), 3 * T)));
+    uint32_t na32 = 0;
+    RAMA_TRY(read_back(ctx, &na32, apos.get() + 3 * T, 4));
+    const size_t na = na32;
+    RAMA_TRY(act_edge.alloc(ctx, na));
+    RAMA_TRY(act_start.alloc(ctx, na + 1));
+    {
+        ProfScope ps_(ctx, "k_active_edges", (double)(3 * T * 8 + na * 8));
+        k_active_edges<<<grid_for(3 * T), kBlock, 0, ctx.stream>>>(3 * T, skey.get(), apos.get(), act_edge.get(),
+                                                             act_start.get());
+    }
+    LAUNCH_TRY(ctx, "active_edges");
+    apos.reset();
     skey.reset();
     rowptr.reset();
     // ---- iterations ----------------------------------------------------------------------------
@@ -431,16 +490,26 @@ rama_status dual_update(Ctx &ctx, const Graph &g, const int32_t *c3, int64_t n3,
     RAMA_TRY(msg.alloc(ctx, 3 * T));
     RAMA_TRY(fill<float>(ctx, ct.get(), 0.0f, 3 * T));
     float *ce = aug.c.get();
-    k_edge_init<<<grid_for(ma), kBlock, 0, ctx.stream>>>(ma, ce, slot_ptr.get(), share.get());
+    {
+        ProfScope ps_(ctx, "k_edge_init", (double)(na * 16));
+        k_edge_init<<<grid_for(na), kBlock, 0, ctx.stream>>>(na, act_edge.get(), act_start.get(), ce, share.get());
+    }
     LAUNCH_TRY(ctx, "edge_init");
     if (lb_trace) {
         RAMA_TRY(lower_bound_now(ctx, ce, ma, ct.get(), T, lb_dev.get()));
         RAMA_TRY(read_back(ctx, &lb_trace[0], lb_dev.get(), 8));
     }
     for (int it = 1; it <= k_iters; ++it) {
-        k_triangle_update<<<grid_for(T), kBlock, 0, ctx.stream>>>(T, tri_edge.get(), share.get(), ct.get(), msg.get());
+        {
+            ProfScope ps_(ctx, "k_triangle_update", (double)(T * 60));
+            k_triangle_update<<<grid_for(T), kBlock, 0, ctx.stream>>>(T, tri_edge.get(), share.get(), ct.get(), msg.get());
+        }
         LAUNCH_TRY(ctx, "triangle_update");
-        k_edge_update<<<grid_for(ma), kBlock, 0, ctx.stream>>>(ma, slot_ptr.get(), slot.get(), msg.get(), ce, share.get());
+        {
+            ProfScope ps_(ctx, "k_edge_update", (double)(na * 16 + 3 * T * 8));
+            k_edge_update<<<grid_for(na), kBlock, 0, ctx.stream>>>(na, act_edge.get(), act_start.get(), slot.get(), msg.get(),
+                                                               ce, share.get());
+        }
         LAUNCH_TRY(ctx, "edge_update");
         if (lb_trace) {
             RAMA_TRY(lower_bound_now(ctx, ce, ma, ct.get(), T, lb_dev.get()));

@@ -25,6 +25,8 @@ __global__ __launch_bounds__(kBlock) void k_validate(int32_t n, size_t m, const 
 }
 
 struct NotLoop {
+    static constexpr int bytes = 8;   // bytes read per item
+    static constexpr const char *tag = "NotLoop";
     const int32_t *i, *j;
     __device__ __forceinline__ uint32_t operator()(size_t e) const { return i[e] != j[e] ? 1u : 0u; }
 };
@@ -43,6 +45,8 @@ __global__ __launch_bounds__(kBlock) void k_pack_edges(size_t m, const int32_t *
 }
 
 struct HeadFlag {
+    static constexpr int bytes = 8;   // bytes read per item
+    static constexpr const char *tag = "HeadFlag";
     const uint64_t *key;
     __device__ __forceinline__ uint32_t operator()(size_t e) const { return (e == 0 || key[e] != key[e - 1]) ? 1u : 0u; }
 };
@@ -64,7 +68,10 @@ rama_status canonicalise(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const
     Buf<int32_t> flags;
     RAMA_TRY(flags.alloc(ctx, 2));
     RAMA_TRY(fill<int32_t>(ctx, flags.get(), 0, 2));
-    k_validate<<<grid_for(m), kBlock, 0, ctx.stream>>>(n, (size_t)m, i, j, c, flags.get());
+    {
+        ProfScope ps_(ctx, "k_validate", (double)((size_t)m * 12));
+        k_validate<<<grid_for(m), kBlock, 0, ctx.stream>>>(n, (size_t)m, i, j, c, flags.get());
+    }
     LAUNCH_TRY(ctx, "validate");
     int32_t hf[2];
     RAMA_TRY(read_back(ctx, hf, flags.get(), sizeof hf));
@@ -95,7 +102,10 @@ rama_status canonicalise(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const
     Buf<uint32_t> val;
     RAMA_TRY(key.alloc(ctx, kept));
     RAMA_TRY(val.alloc(ctx, kept));
-    k_pack_edges<<<grid_for(m), kBlock, 0, ctx.stream>>>((size_t)m, i, j, c, pos.get(), nbits, key.get(), val.get());
+    {
+        ProfScope ps_(ctx, "k_pack_edges", (double)((size_t)m * 16 + (size_t)kept * 12));
+        k_pack_edges<<<grid_for(m), kBlock, 0, ctx.stream>>>((size_t)m, i, j, c, pos.get(), nbits, key.get(), val.get());
+    }
     LAUNCH_TRY(ctx, "pack_edges");
     pos.reset();
     RAMA_TRY((radix_sort_pairs<uint64_t, uint32_t>(ctx, key, val, kept, 2 * nbits)));
@@ -107,8 +117,11 @@ rama_status canonicalise(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const
     RAMA_TRY(out.i.alloc(ctx, uniq));
     RAMA_TRY(out.j.alloc(ctx, uniq));
     RAMA_TRY(out.c.alloc(ctx, uniq));
-    k_reduce_runs<<<grid_for(kept), kBlock, 0, ctx.stream>>>(kept, key.get(), val.get(), opos.get(), nbits, out.i.get(),
+    {
+        ProfScope ps_(ctx, "k_reduce_runs", (double)((size_t)kept * 16 + (size_t)uniq * 12));
+        k_reduce_runs<<<grid_for(kept), kBlock, 0, ctx.stream>>>(kept, key.get(), val.get(), opos.get(), nbits, out.i.get(),
                                                             out.j.get(), out.c.get());
+    }
     LAUNCH_TRY(ctx, "reduce_runs");
     out.m = uniq;
     return RAMA_OK;
@@ -116,6 +129,8 @@ rama_status canonicalise(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const
 
 namespace {
 struct NegPart {
+    static constexpr int bytes = 4;   // bytes read per item
+    static constexpr const char *tag = "NegPart";
     const float *c;
     __device__ __forceinline__ double operator()(size_t e) const { float w = c[e]; return w < 0.0f ? (double)w : 0.0; }
 };

@@ -5,6 +5,8 @@
 // scheduling.
 #pragma once
 
+#include <list>
+
 #include "common.h"
 
 namespace rama {
@@ -76,9 +78,21 @@ constexpr int kScanTile = kBlock * kScanItems;
 
 template <typename T>
 struct PtrInput {
+    static constexpr int bytes = (int)sizeof(T);   // bytes read per item
+    static constexpr const char *tag = "PtrInput";
     const T *p;
     __device__ __forceinline__ T operator()(size_t k) const { return p[k]; }
 };
+
+// "<kernel><<functor tag>>", built once per (kernel, functor) pair
+template <typename F>
+inline const char *kernel_name(const char *kernel)
+{
+    static std::list<std::pair<std::string, std::string>> names;   // list: stable addresses
+    for (auto &p : names) if (p.first == kernel) return p.second.c_str();
+    names.emplace_back(std::string(kernel), std::string(kernel) + "<" + F::tag + ">");
+    return names.back().second.c_str();
+}
 
 template <typename TO, typename F>
 __global__ __launch_bounds__(kBlock) void k_scan_reduce(F f, TO *block_sums, size_t n)
@@ -121,47 +135,73 @@ template <typename TO, typename F>
 rama_status exclusive_scan(Ctx &ctx, F f, TO *out, size_t n)
 {
     if (n == 0) {
-        k_store_zero<TO><<<1, 1, 0, ctx.stream>>>(out);
+        {
+            ProfScope ps_(ctx, "k_store_zero", (double)(0));
+            k_store_zero<TO><<<1, 1, 0, ctx.stream>>>(out);
+        }
         LAUNCH_TRY(ctx, "scan0");
         return RAMA_OK;
     }
     unsigned nb = grid_for(n, kScanTile);
     if (nb == 1) {
-        k_scan_apply<TO, F><<<1, kBlock, 0, ctx.stream>>>(f, out, (const TO *)nullptr, n);
+        {
+            ProfScope ps_(ctx, kernel_name<F>("k_scan_apply"), (double)(n * (F::bytes + sizeof(TO))));
+            k_scan_apply<TO, F><<<1, kBlock, 0, ctx.stream>>>(f, out, (const TO *)nullptr, n);
+        }
         LAUNCH_TRY(ctx, "scan1");
         return RAMA_OK;
     }
     Buf<TO> sums, offs;
     RAMA_TRY(sums.alloc(ctx, nb));
     RAMA_TRY(offs.alloc(ctx, (size_t)nb + 1));
-    k_scan_reduce<TO, F><<<nb, kBlock, 0, ctx.stream>>>(f, sums.get(), n);
+    {
+        ProfScope ps_(ctx, kernel_name<F>("k_scan_reduce"), (double)(n * F::bytes));
+        k_scan_reduce<TO, F><<<nb, kBlock, 0, ctx.stream>>>(f, sums.get(), n);
+    }
     LAUNCH_TRY(ctx, "scan_reduce");
     RAMA_TRY((exclusive_scan<TO, PtrInput<TO>>(ctx, PtrInput<TO>{sums.get()}, offs.get(), nb)));
-    k_scan_apply<TO, F><<<nb, kBlock, 0, ctx.stream>>>(f, out, offs.get(), n);
+    {
+        ProfScope ps_(ctx, kernel_name<F>("k_scan_apply"), (double)(n * (F::bytes + sizeof(TO))));
+        k_scan_apply<TO, F><<<nb, kBlock, 0, ctx.stream>>>(f, out, offs.get(), n);
+    }
     LAUNCH_TRY(ctx, "scan_apply");
     return RAMA_OK;
 }
 
 // ------------------------------------------------------------------------------------------
 // row boundaries: keys[0..m) ascending with values in [0,n); ptr[v] = first position whose key
-// is >= v, for v in [0,n]  (ptr[n] = m).  One thread per position, each fills the gap before it.
+// is >= v, for v in [0,n]  (ptr[n] = m).
+// One thread per position fills the short gap of rows before it; rows inside a long gap (empty
+// stretches of a sparse key set) are left marked and found by binary search, one thread per row,
+// so no thread ever loops over a long stretch.
 // ------------------------------------------------------------------------------------------
+constexpr int kRowGapInline = 32;
+
 template <typename K, typename P>
-__global__ __launch_bounds__(kBlock) void k_row_bounds(const K *keys, size_t m, int64_t n, P *ptr)
+__global__ __launch_bounds__(kBlock) void k_row_bounds_mark(const K *keys, size_t m, int64_t n, P *ptr)
 {
     size_t e = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (e > m) return;
     int64_t prev = (e == 0) ? -1 : (int64_t)keys[e - 1];
     int64_t cur = (e == m) ? n : (int64_t)keys[e];
-    for (int64_t v = prev + 1; v <= cur; ++v) ptr[v] = (P)e;
+    if (cur == prev) return;
+    if (cur - prev <= kRowGapInline)
+        for (int64_t v = prev + 1; v <= cur; ++v) ptr[v] = (P)e;
+    else
+        ptr[cur] = (P)e;
 }
 
 template <typename K, typename P>
-rama_status row_bounds(Ctx &ctx, const K *keys, size_t m, int64_t n, P *ptr)
+__global__ __launch_bounds__(kBlock) void k_row_bounds_search(const K *keys, size_t m, int64_t n, P *ptr)
 {
-    k_row_bounds<K, P><<<grid_for(m + 1), kBlock, 0, ctx.stream>>>(keys, m, n, ptr);
-    LAUNCH_TRY(ctx, "row_bounds");
-    return RAMA_OK;
+    int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (v > n || ptr[v] != (P)-1) return;
+    size_t lo = 0, hi = m;
+    while (lo < hi) {
+        size_t mid = lo + ((hi - lo) >> 1);
+        if ((int64_t)keys[mid] < v) lo = mid + 1; else hi = mid;
+    }
+    ptr[v] = (P)lo;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -255,6 +295,13 @@ __global__ __launch_bounds__(kBlock) void k_rs_scatter(const K *kin, const V *vi
     }
 }
 
+template <typename K, bool HAS_V>
+inline const char *rs_scatter_name()
+{
+    if (HAS_V) return sizeof(K) == 8 ? "k_rs_scatter<u64,u32>" : "k_rs_scatter<u32,u32>";
+    return sizeof(K) == 8 ? "k_rs_scatter<u64>" : "k_rs_scatter<u32>";
+}
+
 // Sorts keys (and 32-bit values) by the low `total_bits` bits of the key.  a/b are two buffers
 // of n elements each; input in a; on return *result_in_b says where the sorted data is.
 template <typename K, typename V, bool HAS_V>
@@ -271,11 +318,17 @@ rama_status radix_sort_impl(Ctx &ctx, K *ka, V *va, K *kb, V *vb, size_t n, int 
     int shift = 0, remaining = total_bits;
     for (int p = 0; p < passes; ++p) {
         int bits = (remaining + (passes - p) - 1) / (passes - p);
-        k_rs_hist<K><<<nb, kBlock, 0, ctx.stream>>>(ka, hist.get(), n, shift, bits, nb);
+        {
+            ProfScope ps_(ctx, (sizeof(K) == 8 ? "k_rs_hist<u64>" : "k_rs_hist<u32>"), (double)(n * sizeof(K)));
+            k_rs_hist<K><<<nb, kBlock, 0, ctx.stream>>>(ka, hist.get(), n, shift, bits, nb);
+        }
         LAUNCH_TRY(ctx, "rs_hist");
         RAMA_TRY((exclusive_scan<uint32_t, PtrInput<uint32_t>>(ctx, PtrInput<uint32_t>{hist.get()}, offs.get(),
                                                                 (size_t)nb << bits)));
-        k_rs_scatter<K, V, HAS_V><<<nb, kBlock, 0, ctx.stream>>>(ka, va, kb, vb, offs.get(), n, shift, bits, nb);
+        {
+            ProfScope ps_(ctx, rs_scatter_name<K, HAS_V>(), (double)(n * (2 * sizeof(K) + (HAS_V ? 8 : 0))));
+            k_rs_scatter<K, V, HAS_V><<<nb, kBlock, 0, ctx.stream>>>(ka, va, kb, vb, offs.get(), n, shift, bits, nb);
+        }
         LAUNCH_TRY(ctx, "rs_scatter");
         std::swap(ka, kb);
         std::swap(va, vb);
@@ -350,9 +403,15 @@ rama_status device_sum(Ctx &ctx, F f, size_t n, double *out_dev, bool accumulate
     if (nb == 0) nb = 1;
     Buf<double> partial;
     RAMA_TRY(partial.alloc(ctx, nb));
-    k_sum_partial<F><<<nb, kBlock, 0, ctx.stream>>>(f, partial.get(), n);
+    {
+        ProfScope ps_(ctx, kernel_name<F>("k_sum_partial"), (double)(n * F::bytes));
+        k_sum_partial<F><<<nb, kBlock, 0, ctx.stream>>>(f, partial.get(), n);
+    }
     LAUNCH_TRY(ctx, "sum_partial");
-    k_sum_final<<<1, kBlock, 0, ctx.stream>>>(partial.get(), nb, out_dev, accumulate ? 1 : 0);
+    {
+        ProfScope ps_(ctx, "k_sum_final", (double)(nb * 8));
+        k_sum_final<<<1, kBlock, 0, ctx.stream>>>(partial.get(), nb, out_dev, accumulate ? 1 : 0);
+    }
     LAUNCH_TRY(ctx, "sum_final");
     return RAMA_OK;
 }
@@ -370,8 +429,28 @@ template <typename T>
 rama_status fill(Ctx &ctx, T *p, T v, size_t n)
 {
     if (n == 0) return RAMA_OK;
-    k_fill<T><<<grid_for(n), kBlock, 0, ctx.stream>>>(p, v, n);
+    {
+        ProfScope ps_(ctx, "k_fill", (double)(n * sizeof(T)));
+        k_fill<T><<<grid_for(n), kBlock, 0, ctx.stream>>>(p, v, n);
+    }
     LAUNCH_TRY(ctx, "fill");
+    return RAMA_OK;
+}
+
+template <typename K, typename P>
+rama_status row_bounds(Ctx &ctx, const K *keys, size_t m, int64_t n, P *ptr)
+{
+    RAMA_TRY(fill<P>(ctx, ptr, (P)-1, (size_t)n + 1));
+    {
+        ProfScope ps_(ctx, "k_row_bounds_mark", (double)(m * sizeof(K) + ((size_t)n + 1) * sizeof(P)));
+        k_row_bounds_mark<K, P><<<grid_for(m + 1), kBlock, 0, ctx.stream>>>(keys, m, n, ptr);
+    }
+    LAUNCH_TRY(ctx, "row_bounds_mark");
+    {
+        ProfScope ps_(ctx, "k_row_bounds_search", (double)(((size_t)n + 1) * sizeof(P)));
+        k_row_bounds_search<K, P><<<grid_for((size_t)n + 1), kBlock, 0, ctx.stream>>>(keys, m, n, ptr);
+    }
+    LAUNCH_TRY(ctx, "row_bounds_search");
     return RAMA_OK;
 }
 
