@@ -109,7 +109,7 @@ rama_status rama_profile_get(const rama_ctx *ctx, int32_t index, const char **na
  *
  * A cycle is stored as the node tuple (v0,...,v_{L-1}) where (v0,v_{L-1}) is its repulsive
  * edge, v0 < v_{L-1}, and v0,v1,...,v_{L-1} is the attractive path.  Each list is ordered by
- * (v0, v_{L-1}, v1, v_{L-2}, v2): grouped by repulsive edge, then ends-inward along the path.
+ * (v0, v_{L-1}, v1, ..., v_{L-2}): grouped by repulsive edge, then lexicographic along the path.
  *
  *   i, j, c            device, [n_edges]
  *   max_cycle_len      3, 4 or 5

@@ -162,7 +162,7 @@ static int posadj_has(const posadj *a, int32_t u, int32_t v)
 /* Plain definition: every simple cycle of length L in {3,..,Lmax} with exactly one edge of   */
 /* E- and L-1 edges of E+.  For the repulsive edge (v0,v_{L-1}), v0<v_{L-1}, that is every    */
 /* simple path v0,v1,..,v_{L-1} along E+.  Depth-first enumeration, nothing pruned.           */
-/* Stored as the tuple (v0,..,v_{L-1}); lists ordered by (v0, v_{L-1}, v1, v_{L-2}, v2).      */
+/* Stored as the tuple (v0,..,v_{L-1}); lists ordered by (v0, v_{L-1}, v1, .., v_{L-2}).      */
 /* ------------------------------------------------------------------------------------------ */
 typedef struct {
     int L;
@@ -199,9 +199,10 @@ static int cmp_cycle(const void *pa, const void *pb)
 {
     const int32_t *x = (const int32_t *)pa, *y = (const int32_t *)pb;
     const int L = g_cyc_L;
-    /* ends-inward order: v0, v_{L-1}, v1, v_{L-2}, v2 */
-    int order[5], cntk = 0, lo = 0, hi = L - 1;
-    while (lo <= hi) { order[cntk++] = lo; if (hi != lo) order[cntk++] = hi; ++lo; --hi; }
+    /* repulsive edge first, then the path: v0, v_{L-1}, v1, .., v_{L-2} */
+    int order[5];
+    order[0] = 0; order[1] = L - 1;
+    for (int q = 1; q <= L - 2; ++q) order[q + 1] = q;
     for (int q = 0; q < L; ++q) {
         int32_t xa = x[order[q]], ya = y[order[q]];
         if (xa != ya) return xa < ya ? -1 : 1;

@@ -1,6 +1,7 @@
 // C ABI: argument checks, the four entry points, and the primal-dual loop
 // (paper algorithm "Primal-Dual Multicut").  Host code here only sequences the stage kernels.
 #include <chrono>
+#include <cstdlib>
 
 #include "prim.h"
 
@@ -93,6 +94,7 @@ rama_status solve_impl(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const i
     double lb = 0.0;
     bool have_lb = false;
     int32_t n_cur = n;
+    const bool trace = getenv("RAMA_TRACE") != nullptr;   // per-round sizes and times on stderr
     for (int round = 1; P.max_rounds <= 0 || round <= P.max_rounds; ++round) {
         const int lmax = round == 1 ? P.max_cycle_len_first : P.max_cycle_len_later;
         const int k = round == 1 ? P.mp_iters_first : P.mp_iters_later;
@@ -136,7 +138,12 @@ rama_status solve_impl(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const i
             n_cur = n_new;
         }
         RAMA_TRY(finish(ctx, RAMA_OK));
-        t_con += now_ms() - t2;
+        const double t3 = now_ms();
+        t_con += t3 - t2;
+        if (trace)
+            fprintf(stderr, "round %2d: cycles %lld/%lld/%lld  |S| %lld  -> nodes %d edges %lld   ms: cycles %.3f dual %.3f contract %.3f\n",
+                    round, (long long)cyc.n[0], (long long)cyc.n[1], (long long)cyc.n[2], (long long)ns, n_cur,
+                    (long long)g.m, t1 - t0, t2 - t1, t3 - t2);
         if (ns == 0) break;
     }
     // labels: smallest original node per cluster; primal cost on the caller's costs

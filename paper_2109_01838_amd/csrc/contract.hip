@@ -62,30 +62,43 @@ __global__ __launch_bounds__(kBlock) void k_accept(size_t na, const uint32_t *ac
     if (best[u] == r && best[v] == r) { mate[u] = v; mate[v] = u; }
 }
 
-struct StillFree {
-    static constexpr int bytes = 20;   // bytes read per item
-    static constexpr const char *tag = "StillFree";
-    const uint32_t *act;
-    const int32_t *i, *j, *mate;
-    __device__ __forceinline__ uint32_t operator()(size_t a) const
-    {
-        uint32_t e = act[a];
-        return (mate[i[e]] < 0 && mate[j[e]] < 0) ? 1u : 0u;
-    }
-};
-
-// survivors move to the next list; the pointers of their endpoints are cleared for the next round
-__global__ __launch_bounds__(kBlock) void k_advance(size_t na, const uint32_t *act, const uint32_t *pos,
-                                                    const int32_t *i, const int32_t *j, uint32_t *act_next,
-                                                    unsigned long long *best)
+// Survivors (both endpoints still free) move to the next list and the pointers of their
+// endpoints are cleared for the next round.  Every workgroup compacts 2048 candidates locally and
+// reserves its output range with a single atomicAdd; the order of the ranges varies from run to
+// run, which is harmless: the atomicMax proposals and the accept test do not depend on the order
+// of the list.
+constexpr int kAdvItems = 8;
+__global__ __launch_bounds__(kBlock) void k_advance(size_t na, const uint32_t *act, const int32_t *i, const int32_t *j,
+                                                    const int32_t *mate, uint32_t *act_next,
+                                                    unsigned long long *best, uint32_t *counter)
 {
-    size_t a = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    if (a >= na) return;
-    if (pos[a] == pos[a + 1]) return;
-    uint32_t e = act[a];
-    act_next[pos[a]] = e;
-    best[i[e]] = 0ull;
-    best[j[e]] = 0ull;
+    __shared__ uint32_t s_base;
+    const size_t tile = (size_t)blockIdx.x * (kBlock * kAdvItems);
+    uint32_t e[kAdvItems];
+    uint32_t keep = 0, cnt = 0;
+#pragma unroll
+    for (int q = 0; q < kAdvItems; ++q) {
+        size_t a = tile + (size_t)threadIdx.x * kAdvItems + q;
+        e[q] = 0;
+        if (a < na) {
+            e[q] = act[a];
+            int32_t u = i[e[q]], v = j[e[q]];
+            if (mate[u] < 0 && mate[v] < 0) {
+                keep |= 1u << q;
+                ++cnt;
+                best[u] = 0ull;
+                best[v] = 0ull;
+            }
+        }
+    }
+    uint32_t total;
+    uint32_t off = block_inclusive_scan(cnt, &total) - cnt;
+    if (threadIdx.x == 0) s_base = total ? atomicAdd(counter, total) : 0u;
+    __syncthreads();
+    off += s_base;
+#pragma unroll
+    for (int q = 0; q < kAdvItems; ++q)
+        if (keep & (1u << q)) act_next[off++] = e[q];
 }
 
 struct MatchedLow {
@@ -232,6 +245,9 @@ static rama_status matching(Ctx &ctx, const Graph &g, float tau, int rounds_cap,
     Buf<unsigned long long> best;
     RAMA_TRY(best.alloc(ctx, n));
     RAMA_TRY(fill<unsigned long long>(ctx, best.get(), 0ull, n));
+    Buf<uint32_t> counters;                      // one survivor counter per handshake round
+    RAMA_TRY(counters.alloc(ctx, (size_t)(rounds_cap > 0 ? rounds_cap : 1)));
+    RAMA_TRY(fill<uint32_t>(ctx, counters.get(), 0u, (size_t)(rounds_cap > 0 ? rounds_cap : 1)));
     for (int r = 0; r < rounds_cap && na > 0; ++r) {
         {
             ProfScope ps_(ctx, "k_propose", (double)((size_t)na * 32));
@@ -241,21 +257,18 @@ static rama_status matching(Ctx &ctx, const Graph &g, float tau, int rounds_cap,
         {
             ProfScope ps_(ctx, "k_accept", (double)((size_t)na * 40));
             k_accept<<<grid_for(na), kBlock, 0, ctx.stream>>>(na, act.get(), g.i.get(), g.j.get(), g.c.get(), best.get(),
-                                                         mate.get());
+                                                             mate.get());
         }
         LAUNCH_TRY(ctx, "accept");
-        RAMA_TRY((exclusive_scan<uint32_t>(ctx, StillFree{act.get(), g.i.get(), g.j.get(), mate.get()}, pos.get(), (size_t)na)));
-        uint32_t nn = 0;
-        RAMA_TRY(read_back(ctx, &nn, pos.get() + na, 4));
-        if (nn > 0) {
-            {
-                ProfScope ps_(ctx, "k_advance", (double)((size_t)na * 16 + (size_t)nn * 24));
-                k_advance<<<grid_for(na), kBlock, 0, ctx.stream>>>(na, act.get(), pos.get(), g.i.get(), g.j.get(), act2.get(),
-                                                              best.get());
-            }
-            LAUNCH_TRY(ctx, "advance");
-            act.swap(act2);
+        {
+            ProfScope ps_(ctx, "k_advance", (double)((size_t)na * 20));
+            k_advance<<<grid_for(na, kBlock * kAdvItems), kBlock, 0, ctx.stream>>>(na, act.get(), g.i.get(), g.j.get(), mate.get(), act2.get(),
+                                                              best.get(), counters.get() + r);
         }
+        LAUNCH_TRY(ctx, "advance");
+        uint32_t nn = 0;
+        RAMA_TRY(read_back(ctx, &nn, counters.get() + r, 4));
+        act.swap(act2);
         na = nn;
     }
     Buf<uint32_t> npos;

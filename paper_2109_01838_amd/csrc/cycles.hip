@@ -6,10 +6,11 @@
 // ascending rows:
 //   3-cycles: v1 in N+(v0) & N+(vL)
 //   4-cycles: v1 in N+(v0), v2 in N+(v1) & N+(vL)
-//   5-cycles: (v1,v3) in N+(v0) x N+(vL), v2 in N+(v1) & N+(v3)      (the appendix algorithm)
+//   5-cycles: v1 in N+(v0), v2 in N+(v1), v3 in N+(v2) & N+(vL); the same set as the appendix
+//             algorithm's pairs (v1,v3) in N+(v0) x N+(vL) with common neighbour v2
 // A count pass, a scan and a fill pass produce the lists already in their final order
-// (v0, vL, v1, v_{L-2}, v2), because repulsive edges are visited in canonical order and every
-// row is ascending.
+// (v0, vL, then the path v1, v2, v3), because repulsive edges are visited in canonical order
+// and every row is ascending.
 #include "prim.h"
 
 namespace rama {
@@ -94,24 +95,70 @@ __device__ __forceinline__ void intersect_rows(const Adj &g, int32_t a, int32_t 
     }
 }
 
+// N+(vL) of the repulsive edge under work: kept in registers when it has at most 8 entries
+// (always the case on grid-like inputs), otherwise searched in memory
+constexpr int kRowRegs = 8;
+struct EndRow {
+    int32_t r[kRowRegs];
+    int32_t b0, b1;
+    const int32_t *nb;
+    bool in_regs;
+    __device__ __forceinline__ void load(const Adj &g, int32_t vl)
+    {
+        nb = g.nb; b0 = g.ptr[vl]; b1 = g.ptr[vl + 1];
+        in_regs = (b1 - b0) <= kRowRegs;
+#pragma unroll
+        for (int k = 0; k < kRowRegs; ++k) r[k] = (in_regs && b0 + k < b1) ? nb[b0 + k] : -1;
+    }
+    __device__ __forceinline__ bool has(int32_t x) const
+    {
+        if (in_regs) {
+            bool f = false;
+#pragma unroll
+            for (int k = 0; k < kRowRegs; ++k) f |= (r[k] == x);
+            return f;
+        }
+        int32_t lo = b0, hi = b1;
+        while (lo < hi) {
+            int32_t mid = lo + ((hi - lo) >> 1);
+            if (nb[mid] < x) lo = mid + 1; else hi = mid;
+        }
+        return lo < b1 && nb[lo] == x;
+    }
+};
+
+// Depth-first walk v0 -> v1 -> v2 -> v3 along N+, closing on N+(vL) at every depth:
+//   v1 in N+(vL)                      -> 3-cycle (v0,v1,vL)
+//   v2 in N+(vL)                      -> 4-cycle (v0,v1,v2,vL)
+//   v3 in N+(vL), v3 != v1            -> 5-cycle (v0,v1,v2,v3,vL)   (the appendix algorithm's
+//                                        pairs (v1,v3) with common neighbour v2, visited path-first)
+// vL and v0 are never in N+(vL) / N+(v0) of a repulsive edge, which settles the other
+// distinctness conditions.  Rows are ascending, so every list comes out in path order.
 template <typename Emit>
 __device__ __forceinline__ void enumerate_cycles(const Adj &g, int32_t v0, int32_t vl, int max_len, Emit &emit)
 {
-    intersect_rows(g, v0, vl, [&](int32_t v1) { emit.c3(v1); });
-    if (max_len < 4) return;
+    if (max_len <= 3) {
+        intersect_rows(g, v0, vl, [&](int32_t v1) { emit.c3(v1); });
+        return;
+    }
+    EndRow end;
+    end.load(g, vl);
+    if (end.b0 == end.b1) return;
     const int32_t r0 = g.ptr[v0], r0e = g.ptr[v0 + 1];
     for (int32_t p = r0; p < r0e; ++p) {
-        int32_t v1 = g.nb[p];
-        intersect_rows(g, v1, vl, [&](int32_t v2) { emit.c4(v1, v2); });
-    }
-    if (max_len < 5) return;
-    const int32_t rl = g.ptr[vl], rle = g.ptr[vl + 1];
-    for (int32_t p = r0; p < r0e; ++p) {
-        int32_t v1 = g.nb[p];
-        for (int32_t q = rl; q < rle; ++q) {
-            int32_t v3 = g.nb[q];
-            if (v3 == v1) continue;
-            intersect_rows(g, v1, v3, [&](int32_t v2) { if (v2 != v0 && v2 != vl) emit.c5(v1, v2, v3); });
+        const int32_t v1 = g.nb[p];
+        if (end.has(v1)) emit.c3(v1);
+        const int32_t r1 = g.ptr[v1], r1e = g.ptr[v1 + 1];
+        for (int32_t q = r1; q < r1e; ++q) {
+            const int32_t v2 = g.nb[q];
+            if (v2 == v0) continue;
+            if (end.has(v2)) emit.c4(v1, v2);
+            if (max_len < 5 || v2 == vl) continue;
+            const int32_t r2 = g.ptr[v2], r2e = g.ptr[v2 + 1];
+            for (int32_t t = r2; t < r2e; ++t) {
+                const int32_t v3 = g.nb[t];
+                if (v3 != v1 && end.has(v3)) emit.c5(v1, v2, v3);
+            }
         }
     }
 }
@@ -144,17 +191,34 @@ __global__ __launch_bounds__(kBlock) void k_count_cycles(size_t nr, const int32_
     c3[r] = em.n3; c4[r] = em.n4; c5[r] = em.n5;
 }
 
-__global__ __launch_bounds__(kBlock) void k_fill_cycles(size_t nr, const int32_t *ri, const int32_t *rj, Adj g,
-                                                        int max_len, const uint64_t *off3, const uint64_t *off4,
+struct HasCycles {
+    static constexpr int bytes = 12;   // bytes read per item
+    static constexpr const char *tag = "HasCycles";
+    const uint32_t *c3, *c4, *c5;
+    __device__ __forceinline__ uint32_t operator()(size_t r) const { return (c3[r] | c4[r] | c5[r]) ? 1u : 0u; }
+};
+
+__global__ __launch_bounds__(kBlock) void k_collect_hits(size_t nr, const uint32_t *c3, const uint32_t *c4,
+                                                         const uint32_t *c5, const uint32_t *pos, uint32_t *hit)
+{
+    size_t r = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (r < nr && (c3[r] | c4[r] | c5[r])) hit[pos[r]] = (uint32_t)r;
+}
+
+// second walk, only over the repulsive edges that have cycles and only as deep as their
+// longest cycle; writes every list at the offsets of the scan
+__global__ __launch_bounds__(kBlock) void k_fill_cycles(size_t nh, const uint32_t *hit, const int32_t *ri,
+                                                        const int32_t *rj, Adj g, const uint32_t *c4,
+                                                        const uint32_t *c5, const uint64_t *off3, const uint64_t *off4,
                                                         const uint64_t *off5, int32_t *out3, int32_t *out4,
                                                         int32_t *out5)
 {
-    size_t r = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    if (r >= nr) return;
-    // skip repulsive edges without any cycle (their offsets do not advance)
-    if (off3[r] == off3[r + 1] && off4[r] == off4[r + 1] && off5[r] == off5[r + 1]) return;
+    size_t h = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (h >= nh) return;
+    const uint32_t r = hit[h];
+    const int depth = c5[r] ? 5 : (c4[r] ? 4 : 3);
     FillEmit em{ri[r], rj[r], out3 + 3 * off3[r], out4 + 4 * off4[r], out5 + 5 * off5[r]};
-    enumerate_cycles(g, em.v0, em.vl, max_len, em);
+    enumerate_cycles(g, em.v0, em.vl, depth, em);
 }
 
 }  // namespace
@@ -239,11 +303,23 @@ rama_status find_cycles(Ctx &ctx, const Graph &g, int max_len, bool count_only, 
         RAMA_TRY(out.v[k].alloc(ctx, (size_t)(k + 3) * tot[k]));
     }
     if (tot[0] + tot[1] + tot[2] == 0) return RAMA_OK;
+    Buf<uint32_t> hpos, hit;
+    RAMA_TRY(hpos.alloc(ctx, (size_t)mr + 1));
+    RAMA_TRY((exclusive_scan<uint32_t>(ctx, HasCycles{cnt[0].get(), cnt[1].get(), cnt[2].get()}, hpos.get(), (size_t)mr)));
+    uint32_t nh = 0;
+    RAMA_TRY(read_back(ctx, &nh, hpos.get() + mr, 4));
+    RAMA_TRY(hit.alloc(ctx, nh));
     {
-        ProfScope ps_(ctx, "k_fill_cycles", (double)((size_t)mr * 32 + ((size_t)n + 1) * 4 + (size_t)mp * 8 + 12.0 * tot[0] + 16.0 * tot[1] + 20.0 * tot[2]));
-        k_fill_cycles<<<grid_for(mr), kBlock, 0, ctx.stream>>>(mr, ri.get(), rj.get(), adj, max_len, off[0].get(),
-                                                          off[1].get(), off[2].get(), out.v[0].get(), out.v[1].get(),
-                                                          out.v[2].get());
+        ProfScope ps_(ctx, "k_collect_hits", (double)((size_t)mr * 16 + (size_t)nh * 4));
+        k_collect_hits<<<grid_for(mr), kBlock, 0, ctx.stream>>>(mr, cnt[0].get(), cnt[1].get(), cnt[2].get(), hpos.get(),
+                                                               hit.get());
+    }
+    LAUNCH_TRY(ctx, "collect_hits");
+    {
+        ProfScope ps_(ctx, "k_fill_cycles", (double)((size_t)nh * 44 + ((size_t)n + 1) * 4 + (size_t)mp * 8 + 12.0 * tot[0] + 16.0 * tot[1] + 20.0 * tot[2]));
+        k_fill_cycles<<<grid_for(nh), kBlock, 0, ctx.stream>>>(nh, hit.get(), ri.get(), rj.get(), adj, cnt[1].get(),
+                                                              cnt[2].get(), off[0].get(), off[1].get(), off[2].get(),
+                                                              out.v[0].get(), out.v[1].get(), out.v[2].get());
     }
     LAUNCH_TRY(ctx, "fill_cycles");
     return RAMA_OK;

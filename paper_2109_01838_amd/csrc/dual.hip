@@ -5,7 +5,8 @@
 // Triangulation (the paper only says that longer cycles are triangulated): fan from v0 --
 // triangles {v0,v_m,v_{m+1}}, chords (v0,v_m); unseen chords join the edge list with cost 0 and
 // the list stays canonical.  Triangles are the sorted set of distinct node triples u<v<w, keyed
-// as (edge id of (u,v), w); slots of a triangle are its edges (u,v),(u,w),(v,w).
+// as (edge id of (u,v), in-row distance to edge (u,w)); slots of a triangle are its edges
+// (u,v),(u,w),(v,w).
 //
 // Message passing keeps c_e (reduced edge costs, eq. 6a) and c_t (triangle costs, eq. 6b).
 // One iteration = edges->triangles (every edge in N_e triangles hands each of them c_e/N_e and
@@ -161,8 +162,29 @@ __global__ __launch_bounds__(kBlock) void k_merge_edges(size_t m, const int32_t 
     }
 }
 
+// longest row of the upper CSR (bounds the in-row distance between two edges of one row)
+__global__ __launch_bounds__(kBlock) void k_max_row(int32_t n, const int32_t *rowptr, uint32_t *out)
+{
+    __shared__ uint32_t wmax[4];
+    int32_t v = blockIdx.x * kBlock + threadIdx.x;
+    uint32_t len = v < n ? (uint32_t)(rowptr[v + 1] - rowptr[v]) : 0u;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) len = max(len, (uint32_t)__shfl_xor((int)len, off, 64));
+    if (lane_id() == 0) wmax[threadIdx.x >> 6] = len;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        len = max(max(wmax[0], wmax[1]), max(wmax[2], wmax[3]));
+        // the stored maximum only grows, so a stale read can only cause a redundant atomic
+        if (len > *(volatile uint32_t *)out) atomicMax(out, len);
+    }
+}
+
+// A triangle u<v<w is keyed by (position e0 of edge (u,v), distance e1-e0 to edge (u,w) in the
+// same row): ascending keys = ascending (u,v,w), and the key needs only
+// bits(|E'|) + bits(longest row) bits -- four 8-bit passes of 32-bit keys on grid-like graphs.
+template <typename KT>
 __global__ __launch_bounds__(kBlock) void k_triangle_keys(CycleSet s, size_t nt, const int32_t *rowptr,
-                                                          const int32_t *j, int nbits, uint64_t *key, int32_t *flag)
+                                                          const int32_t *j, int dbits, KT *key, int32_t *flag)
 {
     size_t q = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (q >= nt) return;
@@ -170,38 +192,39 @@ __global__ __launch_bounds__(kBlock) void k_triangle_keys(CycleSet s, size_t nt,
     fan_triangle(s, q, a, b, c);
     sort3(a, b, c);
     int32_t e0 = find_edge_in_row(rowptr, j, a, b);
-    if (e0 < 0) { *flag = 1; e0 = 0; }
-    key[q] = ((uint64_t)(uint32_t)e0 << nbits) | (uint32_t)c;
+    int32_t e1 = find_edge_in_row(rowptr, j, a, c);
+    if (e0 < 0 || e1 < 0) { *flag = 1; e0 = 0; e1 = 0; }
+    key[q] = ((KT)(uint32_t)e0 << dbits) | (KT)(uint32_t)(e1 - e0);
 }
 
-struct HeadFlag64 {
-    static constexpr int bytes = 8;   // bytes read per item
-    static constexpr const char *tag = "HeadFlag64";
-    const uint64_t *key;
+template <typename KT>
+struct HeadFlagT {
+    static constexpr int bytes = (int)sizeof(KT);   // bytes read per item
+    static constexpr const char *tag = sizeof(KT) == 8 ? "HeadFlag64" : "HeadFlag32";
+    const KT *key;
     __device__ __forceinline__ uint32_t operator()(size_t e) const { return (e == 0 || key[e] != key[e - 1]) ? 1u : 0u; }
 };
 
 // unique triangles -> their three edge ids, and the (edge, slot) pairs for the incidence sort
-__global__ __launch_bounds__(kBlock) void k_triangle_edges(size_t nt, const uint64_t *key, const uint32_t *pos,
-                                                           const int32_t *rowptr, const int32_t *i, const int32_t *j,
-                                                           int nbits, int32_t *tri_edge, uint32_t *skey, uint32_t *sval,
+template <typename KT>
+__global__ __launch_bounds__(kBlock) void k_triangle_edges(size_t nt, const KT *key, const uint32_t *pos,
+                                                           const int32_t *rowptr, const int32_t *j, int dbits,
+                                                           int32_t *tri_edge, uint32_t *skey, uint32_t *sval,
                                                            int32_t *flag)
 {
     size_t q = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (q >= nt) return;
     if (pos[q] == pos[q + 1]) return;
-    uint64_t k = key[q];
-    int32_t e0 = (int32_t)(k >> nbits), w = (int32_t)(k & ((1ull << nbits) - 1ull));
-    int32_t u = i[e0], v = j[e0];
-    int32_t e1 = find_edge_in_row(rowptr, j, u, w);
+    KT k = key[q];
+    int32_t e0 = (int32_t)(k >> dbits);
+    int32_t e1 = e0 + (int32_t)(k & (((KT)1 << dbits) - 1));
+    int32_t v = j[e0], w = j[e1];
     int32_t e2 = find_edge_in_row(rowptr, j, v, w);
-    if (e1 < 0 || e2 < 0) { *flag = 1; e1 = max(e1, 0); e2 = max(e2, 0); }
+    if (e2 < 0) { *flag = 1; e2 = 0; }
     size_t t = pos[q];
     tri_edge[3 * t + 0] = e0; tri_edge[3 * t + 1] = e1; tri_edge[3 * t + 2] = e2;
-    for (int sl = 0; sl < 3; ++sl) {
-        skey[3 * t + sl] = (uint32_t)tri_edge[3 * t + sl];
-        sval[3 * t + sl] = (uint32_t)(3 * t + sl);
-    }
+    skey[3 * t + 0] = (uint32_t)e0; skey[3 * t + 1] = (uint32_t)e1; skey[3 * t + 2] = (uint32_t)e2;
+    sval[3 * t + 0] = (uint32_t)(3 * t); sval[3 * t + 1] = (uint32_t)(3 * t + 1); sval[3 * t + 2] = (uint32_t)(3 * t + 2);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -429,35 +452,53 @@ rama_status dual_update(Ctx &ctx, const Graph &g, const int32_t *c3, int64_t n3,
     if (nnew == 0) RAMA_TRY(copy_graph(ctx, g, aug));
     const size_t ma = (size_t)aug.m;
     // ---- triangles -----------------------------------------------------------------------------
-    Buf<uint64_t> tkey;
-    RAMA_TRY(tkey.alloc(ctx, nfan));
+    Buf<uint32_t> maxrow;
+    RAMA_TRY(maxrow.alloc(ctx, 1));
+    RAMA_TRY(fill<uint32_t>(ctx, maxrow.get(), 0u, 1));
     {
-        ProfScope ps_(ctx, "k_triangle_keys", (double)(nfan * 20));
-        k_triangle_keys<<<grid_for(nfan), kBlock, 0, ctx.stream>>>(cs, nfan, rowptr.get(), aug.j.get(), nbits, tkey.get(),
-                                                              flag.get());
+        ProfScope ps_(ctx, "k_max_row", (double)(((size_t)n + 1) * 4));
+        k_max_row<<<grid_for((size_t)n), kBlock, 0, ctx.stream>>>(n, rowptr.get(), maxrow.get());
     }
-    LAUNCH_TRY(ctx, "triangle_keys");
-    RAMA_TRY((radix_sort_keys<uint64_t>(ctx, tkey, nfan, bits_for((uint64_t)ma) + nbits)));
+    LAUNCH_TRY(ctx, "max_row");
+    uint32_t hmax = 0;
+    RAMA_TRY(read_back(ctx, &hmax, maxrow.get(), 4));
+    const int dbits = bits_for((uint64_t)hmax + 1);
+    const int kbits = bits_for((uint64_t)ma) + dbits;
     Buf<uint32_t> tpos;
     RAMA_TRY(tpos.alloc(ctx, nfan + 1));
-    RAMA_TRY((exclusive_scan<uint32_t>(ctx, HeadFlag64{tkey.get()}, tpos.get(), nfan)));
-    uint32_t T32 = 0;
-    RAMA_TRY(read_back(ctx, &T32, tpos.get() + nfan, 4));
-    const size_t T = T32;
-    if (info) info->n_triangles = (int64_t)T;
     Buf<int32_t> tri_edge;
     Buf<uint32_t> skey, slot;
-    RAMA_TRY(tri_edge.alloc(ctx, 3 * T));
-    RAMA_TRY(skey.alloc(ctx, 3 * T));
-    RAMA_TRY(slot.alloc(ctx, 3 * T));
-    {
-        ProfScope ps_(ctx, "k_triangle_edges", (double)(nfan * 12 + T * 44));
-        k_triangle_edges<<<grid_for(nfan), kBlock, 0, ctx.stream>>>(nfan, tkey.get(), tpos.get(), rowptr.get(), aug.i.get(),
-                                                               aug.j.get(), nbits, tri_edge.get(), skey.get(),
-                                                               slot.get(), flag.get());
-    }
-    LAUNCH_TRY(ctx, "triangle_edges");
-    tkey.reset();
+    size_t T = 0;
+    auto triangles = [&](auto key_tag) -> rama_status {
+        using KT = decltype(key_tag);
+        Buf<KT> tkey;
+        RAMA_TRY(tkey.alloc(ctx, nfan));
+        {
+            ProfScope ps_(ctx, "k_triangle_keys", (double)(nfan * (12 + sizeof(KT))));
+            k_triangle_keys<KT><<<grid_for(nfan), kBlock, 0, ctx.stream>>>(cs, nfan, rowptr.get(), aug.j.get(), dbits,
+                                                                          tkey.get(), flag.get());
+        }
+        LAUNCH_TRY(ctx, "triangle_keys");
+        RAMA_TRY((radix_sort_keys<KT>(ctx, tkey, nfan, kbits)));
+        RAMA_TRY((exclusive_scan<uint32_t>(ctx, HeadFlagT<KT>{tkey.get()}, tpos.get(), nfan)));
+        uint32_t T32 = 0;
+        RAMA_TRY(read_back(ctx, &T32, tpos.get() + nfan, 4));
+        T = T32;
+        RAMA_TRY(tri_edge.alloc(ctx, 3 * T));
+        RAMA_TRY(skey.alloc(ctx, 3 * T));
+        RAMA_TRY(slot.alloc(ctx, 3 * T));
+        {
+            ProfScope ps_(ctx, "k_triangle_edges", (double)(nfan * (4 + sizeof(KT)) + T * 44));
+            k_triangle_edges<KT><<<grid_for(nfan), kBlock, 0, ctx.stream>>>(nfan, tkey.get(), tpos.get(), rowptr.get(),
+                                                                           aug.j.get(), dbits, tri_edge.get(),
+                                                                           skey.get(), slot.get(), flag.get());
+        }
+        LAUNCH_TRY(ctx, "triangle_edges");
+        return RAMA_OK;
+    };
+    if (kbits <= 32) RAMA_TRY(triangles(uint32_t{}));
+    else RAMA_TRY(triangles(uint64_t{}));
+    if (info) info->n_triangles = (int64_t)T;
     tpos.reset();
     {
         int32_t hf = 0;

@@ -205,21 +205,29 @@ __global__ __launch_bounds__(kBlock) void k_row_bounds_search(const K *keys, siz
 }
 
 // ------------------------------------------------------------------------------------------
-// stable LSD radix sort, up to 8 bits per pass, 4096 keys per workgroup.
+// stable LSD radix sort, up to kRadixBits bits per pass, 4096 keys per workgroup.
 // Ranking inside a wave uses ballot-based match-any, so equal digits keep their order
 // without any atomics in the scatter pass.
 // ------------------------------------------------------------------------------------------
-constexpr int kSortItems = 16;
+#ifndef RAMA_SORT_ITEMS
+#define RAMA_SORT_ITEMS 16
+#endif
+constexpr int kSortItems = RAMA_SORT_ITEMS;
 constexpr int kSortTile = kBlock * kSortItems;
-
-struct NoVal {};
+#ifndef RAMA_RADIX_BITS
+#define RAMA_RADIX_BITS 8
+#endif
+constexpr int kRadixBits = RAMA_RADIX_BITS;        // widest digit of a pass
+constexpr int kRadix = 1 << kRadixBits;
+constexpr int kDigitsPerThread = kRadix / kBlock;   // digits owned by one thread in the prefix step
+static_assert(kRadix >= kBlock && kRadix % kBlock == 0, "radix must be a multiple of the block size");
 
 template <typename K>
 __global__ __launch_bounds__(kBlock) void k_rs_hist(const K *keys, uint32_t *hist, size_t n, int shift, int bits,
                                                     uint32_t nb)
 {
-    __shared__ uint32_t h[256];
-    h[threadIdx.x] = 0;
+    __shared__ uint32_t h[kRadix];
+    for (int k = threadIdx.x; k < kRadix; k += kBlock) h[k] = 0;
     __syncthreads();
     const uint32_t mask = (1u << bits) - 1u;
     size_t base = (size_t)blockIdx.x * kSortTile + threadIdx.x;
@@ -229,7 +237,7 @@ __global__ __launch_bounds__(kBlock) void k_rs_hist(const K *keys, uint32_t *his
         if (idx < n) atomicAdd(&h[(uint32_t)(keys[idx] >> shift) & mask], 1u);
     }
     __syncthreads();
-    if (threadIdx.x <= mask) hist[(size_t)threadIdx.x * nb + blockIdx.x] = h[threadIdx.x];
+    for (uint32_t d = threadIdx.x; d <= mask; d += kBlock) hist[(size_t)d * nb + blockIdx.x] = h[d];
 }
 
 __device__ __forceinline__ uint64_t match_digit(uint32_t d, int bits, uint64_t valid)
@@ -243,18 +251,26 @@ __device__ __forceinline__ uint64_t match_digit(uint32_t d, int bits, uint64_t v
     return m;
 }
 
+// One pass of the sort for one tile: (1) every wave ranks its 16x64 keys by digit with ballots,
+// (2) per-digit prefix over the four waves and over the digits gives each key its place in the
+// tile's digit-sorted order, (3) keys (and values) are staged in LDS in that order, (4) the tile
+// is written out linearly -- neighbouring lanes hold neighbouring keys of the same digit, so the
+// global stores fall into contiguous runs instead of 64 scattered lines per instruction.
 template <typename K, typename V, bool HAS_V>
 __global__ __launch_bounds__(kBlock) void k_rs_scatter(const K *kin, const V *vin, K *kout, V *vout,
                                                        const uint32_t *offs, size_t n, int shift, int bits,
                                                        uint32_t nb)
 {
-    __shared__ uint32_t whist[4][256];
-    __shared__ uint32_t wbase[4][256];
+    __shared__ uint32_t whist[4][kRadix];
+    __shared__ uint32_t gdelta[kRadix];
+    __shared__ K skey[kSortTile];
+    __shared__ uint32_t sval[HAS_V ? kSortTile : 1];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const uint32_t mask = (1u << bits) - 1u;
-    for (int k = tid; k < 1024; k += kBlock) (&whist[0][0])[k] = 0;
+    for (int k = tid; k < 4 * kRadix; k += kBlock) (&whist[0][0])[k] = 0;
     __syncthreads();
-    const size_t wave_base = (size_t)blockIdx.x * kSortTile + (size_t)w * (64 * kSortItems);
+    const size_t tile_base = (size_t)blockIdx.x * kSortTile;
+    const size_t wave_base = tile_base + (size_t)w * (64 * kSortItems);
     const uint64_t lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
     K key[kSortItems];
     uint32_t val[kSortItems];
@@ -265,6 +281,11 @@ __global__ __launch_bounds__(kBlock) void k_rs_scatter(const K *kin, const V *vi
         bool valid = idx < n;
         key[r] = valid ? kin[idx] : (K)0;
         if (HAS_V) val[r] = valid ? (uint32_t)vin[idx] : 0u;
+    }
+#pragma unroll
+    for (int r = 0; r < kSortItems; ++r) {
+        size_t idx = wave_base + (size_t)r * 64 + lane;
+        bool valid = idx < n;
         uint32_t d = (uint32_t)(key[r] >> shift) & mask;
         uint64_t m = match_digit(d, bits, __ballot(valid));
         uint32_t before = whist[w][d];
@@ -274,12 +295,25 @@ __global__ __launch_bounds__(kBlock) void k_rs_scatter(const K *kin, const V *vi
         __builtin_amdgcn_wave_barrier();
     }
     __syncthreads();
-    if ((uint32_t)tid <= mask) {
-        uint32_t g = offs[(size_t)tid * nb + blockIdx.x];
+    {   // this thread owns the digits [tid*kDigitsPerThread, +kDigitsPerThread)
+        uint32_t c[kDigitsPerThread][4], tot = 0, all;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            wbase[k][tid] = g;
-            g += whist[k][tid];
+        for (int q = 0; q < kDigitsPerThread; ++q)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                c[q][k] = whist[k][tid * kDigitsPerThread + q];
+                tot += c[q][k];
+            }
+        uint32_t run = block_inclusive_scan(tot, &all) - tot;
+#pragma unroll
+        for (int q = 0; q < kDigitsPerThread; ++q) {
+            const uint32_t d = (uint32_t)(tid * kDigitsPerThread + q);
+            gdelta[d] = (d <= mask ? offs[(size_t)d * nb + blockIdx.x] : 0u) - run;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                whist[k][d] = run;
+                run += c[q][k];
+            }
         }
     }
     __syncthreads();
@@ -288,9 +322,21 @@ __global__ __launch_bounds__(kBlock) void k_rs_scatter(const K *kin, const V *vi
         size_t idx = wave_base + (size_t)r * 64 + lane;
         if (idx < n) {
             uint32_t d = (uint32_t)(key[r] >> shift) & mask;
-            uint32_t pos = wbase[w][d] + rank[r];
-            kout[pos] = key[r];
-            if (HAS_V) vout[pos] = (V)val[r];
+            uint32_t lpos = whist[w][d] + rank[r];
+            skey[lpos] = key[r];
+            if (HAS_V) sval[lpos] = val[r];
+        }
+    }
+    __syncthreads();
+    const uint32_t cnt = (uint32_t)((n - tile_base) < (size_t)kSortTile ? (n - tile_base) : (size_t)kSortTile);
+#pragma unroll
+    for (int r = 0; r < kSortItems; ++r) {
+        uint32_t idx = (uint32_t)r * kBlock + tid;
+        if (idx < cnt) {
+            K k = skey[idx];
+            uint32_t pos = gdelta[(uint32_t)(k >> shift) & mask] + idx;
+            kout[pos] = k;
+            if (HAS_V) vout[pos] = (V)sval[idx];
         }
     }
 }
@@ -311,10 +357,10 @@ rama_status radix_sort_impl(Ctx &ctx, K *ka, V *va, K *kb, V *vb, size_t n, int 
     if (n <= 1 || total_bits <= 0) return RAMA_OK;
     if (n >= (size_t(1) << 32)) return fail(ctx, RAMA_ERR_CAPACITY, "radix sort: more than 2^32 keys");
     const uint32_t nb = grid_for(n, kSortTile);
-    int passes = (total_bits + 7) / 8;
+    int passes = (total_bits + kRadixBits - 1) / kRadixBits;
     Buf<uint32_t> hist, offs;
-    RAMA_TRY(hist.alloc(ctx, (size_t)256 * nb));
-    RAMA_TRY(offs.alloc(ctx, (size_t)256 * nb + 1));
+    RAMA_TRY(hist.alloc(ctx, (size_t)kRadix * nb));
+    RAMA_TRY(offs.alloc(ctx, (size_t)kRadix * nb + 1));
     int shift = 0, remaining = total_bits;
     for (int p = 0; p < passes; ++p) {
         int bits = (remaining + (passes - p) - 1) / (passes - p);

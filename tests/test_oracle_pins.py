@@ -145,7 +145,7 @@ def test_cycle_list_order(oracle32):
     g = inputs.random_graph(9, 30, 5)
     c = np.where(np.arange(g["c"].size) % 4 == 0, -np.abs(g["c"]), np.abs(g["c"])).astype(np.float32)
     for L, cyc in zip((3, 4, 5), oracle32.find_conflicted_cycles(9, g["i"], g["j"], c, 5)):
-        order = {3: [0, 2, 1], 4: [0, 3, 1, 2], 5: [0, 4, 1, 3, 2]}[L]
+        order = {3: [0, 2, 1], 4: [0, 3, 1, 2], 5: [0, 4, 1, 2, 3]}[L]
         keys = [tuple(int(r[q]) for q in order) for r in cyc]
         assert keys == sorted(keys) and len(set(keys)) == len(keys)
         assert np.all(cyc[:, 0] < cyc[:, -1])
