@@ -131,6 +131,33 @@ __global__ __launch_bounds__(kBlock) void k_scan_apply(F f, TO *out, const TO *b
 template <typename TO>
 __global__ void k_store_zero(TO *p) { *p = 0; }
 
+// exclusive scan of up to kScanMidMax tile sums by one workgroup, chunk after chunk
+constexpr unsigned kScanMidMax = 1u << 13;
+template <typename TO>
+__global__ __launch_bounds__(kBlock) void k_scan_mid(const TO *in, TO *out, unsigned nb)
+{
+    TO carry = 0;
+    for (unsigned c0 = 0; c0 < nb; c0 += kScanTile) {
+        unsigned base = c0 + threadIdx.x * kScanItems;
+        TO v[kScanItems];
+        TO s = 0;
+#pragma unroll
+        for (int q = 0; q < kScanItems; ++q) {
+            v[q] = (base + q < nb) ? in[base + q] : (TO)0;
+            s += v[q];
+        }
+        TO tot;
+        TO run = block_inclusive_scan(s, &tot) - s + carry;
+#pragma unroll
+        for (int q = 0; q < kScanItems; ++q) {
+            if (base + q < nb) out[base + q] = run;
+            run += v[q];
+        }
+        carry += tot;
+    }
+    if (threadIdx.x == 0) out[nb] = carry;
+}
+
 template <typename TO, typename F>
 rama_status exclusive_scan(Ctx &ctx, F f, TO *out, size_t n)
 {
@@ -159,7 +186,15 @@ rama_status exclusive_scan(Ctx &ctx, F f, TO *out, size_t n)
         k_scan_reduce<TO, F><<<nb, kBlock, 0, ctx.stream>>>(f, sums.get(), n);
     }
     LAUNCH_TRY(ctx, "scan_reduce");
-    RAMA_TRY((exclusive_scan<TO, PtrInput<TO>>(ctx, PtrInput<TO>{sums.get()}, offs.get(), nb)));
+    if (nb <= kScanMidMax) {   // one workgroup walks all tile sums: three launches in total
+        {
+            ProfScope ps_(ctx, "k_scan_mid", (double)((size_t)nb * 2 * sizeof(TO)));
+            k_scan_mid<TO><<<1, kBlock, 0, ctx.stream>>>(sums.get(), offs.get(), nb);
+        }
+        LAUNCH_TRY(ctx, "scan_mid");
+    } else {
+        RAMA_TRY((exclusive_scan<TO, PtrInput<TO>>(ctx, PtrInput<TO>{sums.get()}, offs.get(), nb)));
+    }
     {
         ProfScope ps_(ctx, kernel_name<F>("k_scan_apply"), (double)(n * (F::bytes + sizeof(TO))));
         k_scan_apply<TO, F><<<nb, kBlock, 0, ctx.stream>>>(f, out, offs.get(), n);
