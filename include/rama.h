@@ -61,6 +61,8 @@ typedef struct {
     int32_t mp_iters_later;       /* ... in later rounds: 5 */
     int32_t matching_rounds_cap;  /* upper limit on handshake rounds per matching: 32 */
     float contract_threshold;     /* tau: an edge is a contraction candidate iff c > tau; 0 */
+    float forest_ratio;           /* if the matching joins fewer than forest_ratio*|V| pairs, S is the spanning
+                                     forest without conflicts instead; 0.1 (<= 0: matching only) */
     int32_t max_rounds;           /* stop after this many rounds; <=0: until no candidate edge is left */
 } rama_params;
 
@@ -157,7 +159,11 @@ rama_status rama_message_passing(rama_ctx *ctx, int32_t n_nodes, int64_t n_edges
  * Primal update (Sec. 3.1: Lemma 1, Lemma 3, algorithm "Parallel-Edge-Contraction", "Finding
  * contraction edge set S: Maximum matching"; appendix algorithm "GPU Edge-Contraction").
  * S is a handshake matching on the edges with c > params->contract_threshold (larger cost
- * wins, ties go to the edge that comes first in the canonical list); the contraction mapping
+ * wins, ties go to the edge that comes first in the canonical list).  If it joins fewer than
+ * params->forest_ratio * n_nodes pairs, S is instead the maximum spanning forest of those edges
+ * (same edge order) minus, for every repulsive edge whose endpoints share a tree, the
+ * lowest-ranked edge on its tree path ("Maximum spanning forest without conflicts").  The
+ * contraction mapping
  * is the connected-component map of (V,S), numbered by ascending smallest member; the
  * contracted graph is K^T A K without its diagonal.
  *

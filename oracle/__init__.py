@@ -174,6 +174,18 @@ class Oracle:
             raise OracleError(r, "matching")
         return mate
 
+    def forest_set(self, n, i, j, c, tau=0.0):
+        """Input must be canonical.  Returns (in_forest[m], removed[m], S as (si, sj))."""
+        i, j, c = _i32(i), _i32(j), _f32(c)
+        inf, rem = np.zeros(max(i.size, 1), np.uint8), np.zeros(max(i.size, 1), np.uint8)
+        si, sj = np.empty(n + 1, np.int32), np.empty(n + 1, np.int32)
+        self.lib.rama_oracle_forest_set.restype = C.c_int64
+        ns = self.lib.rama_oracle_forest_set(C.c_int32(n), C.c_int64(i.size), _ptr(i), _ptr(j), _ptr(c), C.c_float(tau),
+                                             _ptr(inf), _ptr(rem), _ptr(si), _ptr(sj))
+        if ns < 0:
+            raise OracleError(ns, "forest_set")
+        return inf[:i.size].astype(bool), rem[:i.size].astype(bool), si[:ns].copy(), sj[:ns].copy()
+
     def components(self, n, si, sj):
         si, sj = _i32(si), _i32(sj)
         rep, fmap = np.empty(n, np.int32), np.empty(n, np.int32)
@@ -198,7 +210,7 @@ class Oracle:
         k = mo.value
         return io[:k].copy(), jo[:k].copy(), co[:k].copy(), diag
 
-    def contract(self, n, i, j, c, tau=0.0, rounds_cap=32, repeat=1):
+    def contract(self, n, i, j, c, tau=0.0, rounds_cap=32, repeat=1, forest_ratio=0.1):
         i, j, c = _i32(i), _i32(j), _f32(c)
         m = max(i.size, 1)
         mapping = np.empty(n, np.int32)
@@ -207,7 +219,7 @@ class Oracle:
         nn, mo = C.c_int32(0), C.c_int64(0)
         st = self.lib.rama_oracle_contract(
             C.c_int32(n), C.c_int64(i.size), _ptr(i), _ptr(j), _ptr(c), C.c_float(tau), C.c_int32(rounds_cap),
-            C.c_int32(repeat), _ptr(mapping), _ptr(io), _ptr(jo), _ptr(co), _ptr(diag), C.byref(nn), C.byref(mo))
+            C.c_float(forest_ratio), C.c_int32(repeat), _ptr(mapping), _ptr(io), _ptr(jo), _ptr(co), _ptr(diag), C.byref(nn), C.byref(mo))
         if st != OK:
             raise OracleError(st, "contract")
         k = mo.value
@@ -220,7 +232,7 @@ class Oracle:
         return self.lib.rama_oracle_multicut_cost(C.c_int64(i.size), _ptr(i), _ptr(j), _ptr(c), _ptr(labels))
 
     def solve(self, n, i, j, c, max_cycle_len_first=5, max_cycle_len_later=3, mp_iters_first=10,
-              mp_iters_later=5, matching_rounds_cap=32, tau=0.0, max_rounds=0):
+              mp_iters_later=5, matching_rounds_cap=32, tau=0.0, max_rounds=0, forest_ratio=0.1):
         i, j, c = _i32(i), _i32(j), _f32(c)
         labels = np.empty(n, np.int32)
         primal, lb = C.c_double(0.0), C.c_double(0.0)
@@ -229,7 +241,7 @@ class Oracle:
             C.c_int32(n), C.c_int64(i.size), _ptr(i), _ptr(j), _ptr(c),
             C.c_int32(max_cycle_len_first), C.c_int32(max_cycle_len_later),
             C.c_int32(mp_iters_first), C.c_int32(mp_iters_later),
-            C.c_int32(matching_rounds_cap), C.c_float(tau), C.c_int32(max_rounds),
+            C.c_int32(matching_rounds_cap), C.c_float(tau), C.c_float(forest_ratio), C.c_int32(max_rounds),
             _ptr(labels), C.byref(primal), C.byref(lb), stats)
         if st != OK:
             raise OracleError(st, "solve")

@@ -586,6 +586,101 @@ int64_t rama_oracle_matching(int32_t n, int64_t m, const int32_t *i, const int32
 }
 
 /* ------------------------------------------------------------------------------------------ */
+/* Step a4, second strategy: maximum spanning forest without conflicts (Sec. 3.1).             */
+/* The paper names Boruvka's algorithm and says: for every negative edge ij find the unique    */
+/* i-j path in the forest (if there is one) and remove its smallest positive edge.  Reading:   */
+/*  - the forest is the maximum spanning forest of the candidate edges (c > tau) under the     */
+/*    same total order as the matching (larger cost first, then earlier canonical position);   */
+/*    with a strict order it is unique, so Kruskal's algorithm gives the same forest;          */
+/*  - all repulsive edges (c < 0) look at the forest as built; each marks the lowest edge of   */
+/*    its path; all marked edges are removed together.  Then no repulsive edge has both        */
+/*    endpoints in one component, so every join lowers the objective.                          */
+/* Input canonical.  in_forest / removed (optional, [m]) flag the forest edges and the marked  */
+/* ones; S = forest minus marked is written to si/sj (capacity n).  Returns |S|.               */
+/* ------------------------------------------------------------------------------------------ */
+static int32_t uf_find(int32_t *p, int32_t v);
+typedef struct { float c; int64_t pos; } ranked_edge;
+static int cmp_ranked_desc(const void *pa, const void *pb)
+{
+    const ranked_edge *x = (const ranked_edge *)pa, *y = (const ranked_edge *)pb;
+    if (x->c != y->c) return x->c > y->c ? -1 : 1;
+    if (x->pos != y->pos) return x->pos < y->pos ? -1 : 1;
+    return 0;
+}
+/* 1 if edge e ranks below edge f in the contraction order */
+static int ranks_below(const float *c, int64_t e, int64_t f) { return c[e] < c[f] || (c[e] == c[f] && e > f); }
+
+int64_t rama_oracle_forest_set(int32_t n, int64_t m, const int32_t *i, const int32_t *j, const float *c, float tau,
+                               uint8_t *in_forest, uint8_t *removed, int32_t *si, int32_t *sj)
+{
+    ranked_edge *cand = (ranked_edge *)xmalloc((size_t)m * sizeof *cand);
+    int32_t *uf = (int32_t *)xmalloc(((size_t)n + 1) * 4);
+    uint8_t *inf = (uint8_t *)calloc((size_t)m + 1, 1), *rem = (uint8_t *)calloc((size_t)m + 1, 1);
+    int64_t *adj_ptr = (int64_t *)calloc((size_t)n + 2, sizeof(int64_t));
+    if (!cand || !uf || !inf || !rem || !adj_ptr) return ERR_OOM;
+    /* Kruskal on the candidates in descending order */
+    int64_t nc = 0;
+    for (int64_t e = 0; e < m; ++e) if (c[e] > tau) { cand[nc].c = c[e]; cand[nc].pos = e; ++nc; }
+    qsort(cand, (size_t)nc, sizeof *cand, cmp_ranked_desc);
+    for (int32_t v = 0; v < n; ++v) uf[v] = v;
+    int64_t nf = 0;
+    for (int64_t q = 0; q < nc; ++q) {
+        int64_t e = cand[q].pos;
+        int32_t a = uf_find(uf, i[e]), b = uf_find(uf, j[e]);
+        if (a == b) continue;
+        if (a < b) uf[b] = a; else uf[a] = b;
+        inf[e] = 1; ++nf;
+    }
+    /* adjacency of the forest */
+    for (int64_t e = 0; e < m; ++e) if (inf[e]) { adj_ptr[i[e] + 1]++; adj_ptr[j[e] + 1]++; }
+    for (int32_t v = 0; v < n; ++v) adj_ptr[v + 1] += adj_ptr[v];
+    int64_t *adj_edge = (int64_t *)xmalloc((size_t)(2 * nf) * sizeof(int64_t));
+    int64_t *fillp = (int64_t *)xmalloc(((size_t)n + 1) * sizeof(int64_t));
+    int32_t *up = (int32_t *)xmalloc(((size_t)n + 1) * 4), *depth = (int32_t *)xmalloc(((size_t)n + 1) * 4);
+    int32_t *tree = (int32_t *)xmalloc(((size_t)n + 1) * 4), *queue = (int32_t *)xmalloc(((size_t)n + 1) * 4);
+    int64_t *up_edge = (int64_t *)xmalloc(((size_t)n + 1) * sizeof(int64_t));
+    if (!adj_edge || !fillp || !up || !depth || !tree || !queue || !up_edge) return ERR_OOM;
+    memcpy(fillp, adj_ptr, ((size_t)n + 1) * sizeof(int64_t));
+    for (int64_t e = 0; e < m; ++e) if (inf[e]) { adj_edge[fillp[i[e]]++] = e; adj_edge[fillp[j[e]]++] = e; }
+    /* root every tree (breadth first) */
+    for (int32_t v = 0; v < n; ++v) depth[v] = -1;
+    for (int32_t r = 0; r < n; ++r) {
+        if (depth[r] >= 0) continue;
+        int64_t head = 0, tail = 0;
+        depth[r] = 0; up[r] = r; up_edge[r] = -1; tree[r] = r; queue[tail++] = r;
+        while (head < tail) {
+            int32_t v = queue[head++];
+            for (int64_t p = adj_ptr[v]; p < adj_ptr[v + 1]; ++p) {
+                int64_t e = adj_edge[p];
+                int32_t w = i[e] == v ? j[e] : i[e];
+                if (depth[w] >= 0) continue;
+                depth[w] = depth[v] + 1; up[w] = v; up_edge[w] = e; tree[w] = r; queue[tail++] = w;
+            }
+        }
+    }
+    /* every repulsive edge inside a tree marks the lowest edge of its forest path */
+    for (int64_t e = 0; e < m; ++e) {
+        if (!(c[e] < 0.0f)) continue;
+        int32_t a = i[e], b = j[e];
+        if (tree[a] != tree[b]) continue;
+        int64_t low = -1;
+        while (a != b) {
+            int64_t pe;
+            if (depth[a] >= depth[b]) { pe = up_edge[a]; a = up[a]; } else { pe = up_edge[b]; b = up[b]; }
+            if (low < 0 || ranks_below(c, pe, low)) low = pe;
+        }
+        if (low >= 0) rem[low] = 1;
+    }
+    int64_t ns = 0;
+    for (int64_t e = 0; e < m; ++e) if (inf[e] && !rem[e]) { si[ns] = i[e]; sj[ns] = j[e]; ++ns; }
+    if (in_forest) memcpy(in_forest, inf, (size_t)m);
+    if (removed) memcpy(removed, rem, (size_t)m);
+    free(cand); free(uf); free(inf); free(rem); free(adj_ptr); free(adj_edge); free(fillp);
+    free(up); free(depth); free(tree); free(queue); free(up_edge);
+    return ns;
+}
+
+/* ------------------------------------------------------------------------------------------ */
 /* Step a5: contraction mapping from S (Lemma 1(a)): f(u)=f(v) iff u,v are joined by a path in */
 /* (V,S).  rep[v] = smallest node id of v's component; f'[v] = number of component             */
 /* representatives smaller than rep[v].  Union-find with the smaller id as root.               */
@@ -647,20 +742,26 @@ int rama_oracle_contract_with_mapping(int32_t n, int64_t m, const int32_t *i, co
     return OK;
 }
 
-/* One primal update (Alg. "Parallel-Edge-Contraction"): S by matching, f' by components,
- * A' = K^T A K - diag.  Input canonical.  Returns |S| through n_matched. */
+/* One primal update (Alg. "Parallel-Edge-Contraction"): S by matching -- or, when the matching
+ * joins fewer than forest_ratio*|V| pairs, by the spanning forest without conflicts (Sec. 3.1,
+ * last paragraph of "Finding contraction edge set S"; forest_ratio <= 0 disables the switch) --
+ * then f' by components and A' = K^T A K - diag.  Input canonical.  Returns |S| through n_matched. */
 static int contract_once(int32_t n, int64_t m, const int32_t *i, const int32_t *j, const float *c,
-                         float tau, int32_t rounds_cap, int32_t *fmap, int32_t *n_new,
+                         float tau, int32_t rounds_cap, float forest_ratio, int32_t *fmap, int32_t *n_new,
                          int32_t *io, int32_t *jo, float *co, int64_t *m_out, float *diag, int64_t *n_matched)
 {
     int32_t *mate = (int32_t *)xmalloc((size_t)n * 4), *rep = (int32_t *)xmalloc((size_t)n * 4);
-    if (!mate || !rep) return ERR_OOM;
+    int32_t *si = (int32_t *)xmalloc(((size_t)n + 1) * 4), *sj = (int32_t *)xmalloc(((size_t)n + 1) * 4);
+    if (!mate || !rep || !si || !sj) return ERR_OOM;
     int64_t ns = rama_oracle_matching(n, m, i, j, c, tau, rounds_cap, mate);
     if (ns < 0) return (int)ns;
-    int32_t *si = (int32_t *)xmalloc((size_t)ns * 4), *sj = (int32_t *)xmalloc((size_t)ns * 4);
-    if (!si || !sj) return ERR_OOM;
-    int64_t q = 0;
-    for (int32_t v = 0; v < n; ++v) if (mate[v] > v) { si[q] = v; sj[q] = mate[v]; ++q; }
+    if (ns > 0 && forest_ratio > 0.0f && (double)ns < (double)forest_ratio * (double)n) {
+        ns = rama_oracle_forest_set(n, m, i, j, c, tau, NULL, NULL, si, sj);
+        if (ns < 0) return (int)ns;
+    } else {
+        int64_t q = 0;
+        for (int32_t v = 0; v < n; ++v) if (mate[v] > v) { si[q] = v; sj[q] = mate[v]; ++q; }
+    }
     int st = rama_oracle_components(n, ns, si, sj, rep, fmap, n_new);
     if (st == OK) st = rama_oracle_contract_with_mapping(n, m, i, j, c, fmap, *n_new, io, jo, co, m_out, diag);
     *n_matched = ns;
@@ -673,7 +774,7 @@ static int contract_once(int32_t n, int64_t m, const int32_t *i, const int32_t *
  * final node.  diag (optional): diagonal of K^T A K for the composed mapping, i.e. for every
  * final node the sum of the input edges inside it, added in canonical edge order. */
 int rama_oracle_contract(int32_t n, int64_t m, const int32_t *i, const int32_t *j, const float *c,
-                         float tau, int32_t rounds_cap, int32_t repeat,
+                         float tau, int32_t rounds_cap, float forest_ratio, int32_t repeat,
                          int32_t *mapping, int32_t *io, int32_t *jo, float *co, float *diag,
                          int32_t *n_out, int64_t *m_out)
 {
@@ -695,7 +796,7 @@ int rama_oracle_contract(int32_t n, int64_t m, const int32_t *i, const int32_t *
     for (int32_t v = 0; v < n; ++v) mapping[v] = v;
     for (;;) {
         int32_t nn = 0; int64_t mn = 0, ns = 0;
-        st = contract_once(ncur, mcur, gi, gj, gc, tau, rounds_cap, fm, &nn, ni, nj, nc, &mn, NULL, &ns);
+        st = contract_once(ncur, mcur, gi, gj, gc, tau, rounds_cap, forest_ratio, fm, &nn, ni, nj, nc, &mn, NULL, &ns);
         if (st != OK) goto done;
         if (ns == 0) break;
         for (int32_t v = 0; v < n; ++v) mapping[v] = fm[mapping[v]];       /* f <- f' o f */
@@ -737,7 +838,7 @@ double rama_oracle_multicut_cost(int64_t m, const int32_t *i, const int32_t *j, 
 int rama_oracle_solve(int32_t n, int64_t m, const int32_t *i, const int32_t *j, const float *c,
                       int32_t max_cycle_len_first, int32_t max_cycle_len_later,
                       int32_t mp_iters_first, int32_t mp_iters_later,
-                      int32_t matching_rounds_cap, float tau, int32_t max_rounds,
+                      int32_t matching_rounds_cap, float tau, float forest_ratio, int32_t max_rounds,
                       int32_t *labels, double *primal_cost, double *lower_bound, int64_t *stats)
 {
     if (!labels || n < 0) return ERR_ARG;
@@ -792,7 +893,7 @@ int rama_oracle_solve(int32_t n, int64_t m, const int32_t *i, const int32_t *j, 
         float *nc = (float *)xmalloc(mq * 4);
         int32_t nn = 0; int64_t mn = 0, ns = 0;
         if (!ni || !nj || !nc) { st = ERR_OOM; goto fail; }
-        st = contract_once(ncur, mcur, gi, gj, gc, tau, matching_rounds_cap, fm, &nn, ni, nj, nc, &mn, NULL, &ns);
+        st = contract_once(ncur, mcur, gi, gj, gc, tau, matching_rounds_cap, forest_ratio, fm, &nn, ni, nj, nc, &mn, NULL, &ns);
         if (st != OK) goto fail;
         st_rounds = round;
         if (ns == 0) { free(ni); free(nj); free(nc); break; }

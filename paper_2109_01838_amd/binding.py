@@ -25,7 +25,7 @@ class RamaParams(C.Structure):
         ("max_cycle_len_first", C.c_int32), ("max_cycle_len_later", C.c_int32),
         ("mp_iters_first", C.c_int32), ("mp_iters_later", C.c_int32),
         ("matching_rounds_cap", C.c_int32), ("contract_threshold", C.c_float),
-        ("max_rounds", C.c_int32),
+        ("forest_ratio", C.c_float), ("max_rounds", C.c_int32),
     ]
 
 

@@ -126,7 +126,7 @@ rama_status solve_impl(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const i
         Graph gn;
         int32_t n_new = n_cur;
         int64_t ns = 0;
-        RAMA_TRY(contract_once(ctx, g, P.contract_threshold, P.matching_rounds_cap, fprime, n_new, gn, ns));
+        RAMA_TRY(contract_once(ctx, g, P.contract_threshold, P.matching_rounds_cap, P.forest_ratio, fprime, n_new, gn, ns));
         S.rounds = round;
         if (ns > 0) {
             {
@@ -226,6 +226,7 @@ void rama_params_default(rama_params *p)
     p->mp_iters_later = 5;
     p->matching_rounds_cap = 32;
     p->contract_threshold = 0.0f;
+    p->forest_ratio = 0.1f;
     p->max_rounds = 0;
 }
 
@@ -333,7 +334,8 @@ rama_status rama_contract(rama_ctx *ctx, int32_t n_nodes, int64_t n_edges, const
             Graph gn;
             int32_t n_new = n_cur;
             int64_t ns = 0;
-            RAMA_TRY(contract_once(*ctx, *cur, params->contract_threshold, params->matching_rounds_cap, fprime, n_new, gn, ns));
+            RAMA_TRY(contract_once(*ctx, *cur, params->contract_threshold, params->matching_rounds_cap, params->forest_ratio, fprime,
+                                   n_new, gn, ns));
             if (ns == 0) break;
             {
                 ProfScope ps_(*ctx, "k_compose", (double)((size_t)n_nodes * 12));

@@ -299,8 +299,8 @@ rama_status dual_update(Ctx &ctx, const Graph &g, const int32_t *c3, int64_t n3,
                         double *lower_bound, double *lb_trace, DualInfo *info);
 
 // a4..a6: one primal update.  fmap[n] -> [0,n_new); n_matched = |S|.  If |S|==0 nothing else is produced.
-rama_status contract_once(Ctx &ctx, const Graph &g, float tau, int rounds_cap, Buf<int32_t> &fmap, int32_t &n_new,
-                          Graph &out, int64_t &n_matched);
+rama_status contract_once(Ctx &ctx, const Graph &g, float tau, int rounds_cap, float forest_ratio, Buf<int32_t> &fmap,
+                          int32_t &n_new, Graph &out, int64_t &n_matched);
 
 // diagonal of K^T A K for a mapping F on canonical graph g: diag[a] = sum of edges with F(i)=F(j)=a
 rama_status contraction_diagonal(Ctx &ctx, const Graph &g, const int32_t *fmap, int32_t n_new, float *diag);

@@ -8,6 +8,10 @@
 //         on the shrinking list of edges whose endpoints are both still free.
 //   f'  : connected components of (V,S) by min-label hooking + pointer jumping; a component is
 //         represented by its smallest node; new ids are the ranks of the representatives.
+//   S'  : when the matching joins fewer than forest_ratio*|V| pairs: maximum spanning forest of the
+//         candidate edges (Boruvka rounds with the same atomicMax ranks) minus, for every
+//         repulsive edge inside a tree, the lowest edge of its tree path (trees rooted breadth
+//         first, paths walked up from both ends).
 //   A'  : endpoints relabelled through f', re-oriented, sorted by (row, col) with the cost as
 //         payload (stable), runs of equal pairs summed in order, loops dropped.
 #include "prim.h"
@@ -219,6 +223,160 @@ __global__ __launch_bounds__(kBlock) void k_diag_runs(size_t m, const uint32_t *
     diag[k] = acc;
 }
 
+
+// ---- maximum spanning forest without conflicts (second strategy for S, Sec. 3.1) ----------------
+// Boruvka rounds on the candidate edges under the matching's edge order.  comp[] is kept flat
+// (comp[v] = current component root of v).  Every component points at its best outgoing edge by
+// atomicMax; the chosen edges join the forest; a component hooks onto the component across its
+// edge, except that of two components choosing the same edge the smaller id stays a root.
+// With a strict edge order the hook graph has no other cycles, and the forest is the unique
+// maximum spanning forest whatever the execution order.
+__global__ __launch_bounds__(kBlock) void k_bor_propose(size_t na, const uint32_t *act, const int32_t *i,
+                                                        const int32_t *j, const float *c, const int32_t *comp,
+                                                        unsigned long long *best)
+{
+    size_t a = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (a >= na) return;
+    uint32_t e = act[a];
+    int32_t cu = comp[i[e]], cv = comp[j[e]];
+    if (cu == cv) return;
+    unsigned long long r = edge_rank(c[e], e);
+    atomicMax(&best[cu], r);
+    atomicMax(&best[cv], r);
+}
+
+__global__ __launch_bounds__(kBlock) void k_bor_select(size_t na, const uint32_t *act, const int32_t *i,
+                                                       const int32_t *j, const float *c, const int32_t *comp,
+                                                       const unsigned long long *best, int32_t *hook,
+                                                       uint8_t *in_forest)
+{
+    size_t a = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (a >= na) return;
+    uint32_t e = act[a];
+    int32_t cu = comp[i[e]], cv = comp[j[e]];
+    if (cu == cv) return;
+    unsigned long long r = edge_rank(c[e], e);
+    const bool bu = best[cu] == r, bv = best[cv] == r;
+    if (!(bu || bv)) return;
+    in_forest[e] = 1;
+    if (bu && !(bv && cu < cv)) hook[cu] = cv;
+    if (bv && !(bu && cv < cu)) hook[cv] = cu;
+}
+
+// comp[v] <- root of comp[v] in the hook forest (roots have hook[r] == r)
+__global__ __launch_bounds__(kBlock) void k_bor_flatten(size_t n, const int32_t *hook, int32_t *comp)
+{
+    size_t v = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (v >= n) return;
+    int32_t r = comp[v], h = hook[r];
+    while (h != r) { r = h; h = hook[r]; }   // every chain ends in a root: the hook graph is a forest
+    comp[v] = r;
+}
+
+// edges still joining two components move on; best[] and hook[] of their components are reset
+__global__ __launch_bounds__(kBlock) void k_bor_advance(size_t na, const uint32_t *act, const int32_t *i,
+                                                        const int32_t *j, const int32_t *comp, uint32_t *act_next,
+                                                        unsigned long long *best, int32_t *hook, uint32_t *counter)
+{
+    __shared__ uint32_t s_base;
+    const size_t tile = (size_t)blockIdx.x * (kBlock * kAdvItems);
+    uint32_t e[kAdvItems];
+    uint32_t keep = 0, cnt = 0;
+#pragma unroll
+    for (int q = 0; q < kAdvItems; ++q) {
+        size_t a = tile + (size_t)threadIdx.x * kAdvItems + q;
+        e[q] = 0;
+        if (a < na) {
+            e[q] = act[a];
+            int32_t cu = comp[i[e[q]]], cv = comp[j[e[q]]];
+            if (cu != cv) {
+                keep |= 1u << q;
+                ++cnt;
+                best[cu] = 0ull; best[cv] = 0ull;
+                hook[cu] = cu; hook[cv] = cv;
+            }
+        }
+    }
+    uint32_t total;
+    uint32_t off = block_inclusive_scan(cnt, &total) - cnt;
+    if (threadIdx.x == 0) s_base = total ? atomicAdd(counter, total) : 0u;
+    __syncthreads();
+    off += s_base;
+#pragma unroll
+    for (int q = 0; q < kAdvItems; ++q)
+        if (keep & (1u << q)) act_next[off++] = e[q];
+}
+
+struct ForestFlag {
+    static constexpr int bytes = 1;   // bytes read per item
+    static constexpr const char *tag = "ForestFlag";
+    const uint8_t *in_forest;
+    __device__ __forceinline__ uint32_t operator()(size_t e) const { return in_forest[e] ? 1u : 0u; }
+};
+struct KeptFlag {
+    static constexpr int bytes = 2;   // bytes read per item
+    static constexpr const char *tag = "KeptFlag";
+    const uint8_t *in_forest, *removed;
+    __device__ __forceinline__ uint32_t operator()(size_t e) const { return (in_forest[e] && !removed[e]) ? 1u : 0u; }
+};
+
+__global__ __launch_bounds__(kBlock) void k_collect_flagged(size_t m, const uint8_t *flag, const uint8_t *veto,
+                                                            const uint32_t *pos, const int32_t *i, const int32_t *j,
+                                                            uint32_t *ids, int32_t *si, int32_t *sj)
+{
+    size_t e = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (e >= m || !flag[e] || (veto && veto[e])) return;
+    uint32_t p = pos[e];
+    if (ids) ids[p] = (uint32_t)e;
+    if (si) { si[p] = i[e]; sj[p] = j[e]; }
+}
+
+// rooting of the forest, one breadth-first level per launch: a node at depth `lvl` adopts its
+// still unrooted forest neighbours.  up[v] = parent, up_edge[v] = edge to the parent.
+__global__ __launch_bounds__(kBlock) void k_root_init(size_t n, const int32_t *comp, int32_t *depth, int32_t *up)
+{
+    size_t v = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (v >= n) return;
+    bool root = comp[v] == (int32_t)v;
+    depth[v] = root ? 0 : -1;
+    up[v] = (int32_t)v;
+}
+
+__global__ __launch_bounds__(kBlock) void k_root_level(size_t nf, const uint32_t *fe, const int32_t *i, const int32_t *j,
+                                                       int32_t lvl, int32_t *depth, int32_t *up, uint32_t *up_edge,
+                                                       int32_t *changed)
+{
+    size_t q = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (q >= nf) return;
+    uint32_t e = fe[q];
+    int32_t a = i[e], b = j[e];
+    int32_t da = depth[a], db = depth[b];
+    if (da == lvl && db < 0) { depth[b] = lvl + 1; up[b] = a; up_edge[b] = e; *changed = 1; }
+    else if (db == lvl && da < 0) { depth[a] = lvl + 1; up[a] = b; up_edge[a] = e; *changed = 1; }
+}
+
+// every repulsive edge whose endpoints share a tree walks the two ends up to their meeting
+// point and marks the lowest-ranked edge of the path
+__global__ __launch_bounds__(kBlock) void k_mark_conflicts(size_t m, const int32_t *i, const int32_t *j, const float *c,
+                                                           const int32_t *comp, const int32_t *depth, const int32_t *up,
+                                                           const uint32_t *up_edge, uint8_t *removed)
+{
+    size_t e = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (e >= m || !(c[e] < 0.0f)) return;
+    int32_t a = i[e], b = j[e];
+    if (comp[a] != comp[b]) return;
+    int32_t da = depth[a], db = depth[b];
+    unsigned long long low = ~0ull;
+    uint32_t low_e = 0;
+    while (a != b) {
+        uint32_t pe;
+        if (da >= db) { pe = up_edge[a]; a = up[a]; --da; } else { pe = up_edge[b]; b = up[b]; --db; }
+        unsigned long long r = edge_rank(c[pe], pe);
+        if (r < low) { low = r; low_e = pe; }
+    }
+    if (low != ~0ull) removed[low_e] = 1;
+}
+
 }  // namespace
 
 // handshake matching; mate[v] = partner or -1; returns |S| in n_matched
@@ -277,6 +435,137 @@ static rama_status matching(Ctx &ctx, const Graph &g, float tau, int rounds_cap,
     uint32_t ns = 0;
     RAMA_TRY(read_back(ctx, &ns, npos.get() + n, 4));
     n_matched = ns;
+    return RAMA_OK;
+}
+
+// S by the spanning forest without conflicts; writes the S edges to si/sj (allocated here)
+static rama_status forest_set(Ctx &ctx, const Graph &g, float tau, Buf<int32_t> &si, Buf<int32_t> &sj, int64_t &n_set)
+{
+    const size_t m = (size_t)g.m, n = (size_t)g.n;
+    n_set = 0;
+    Buf<uint32_t> pos, act, act2, counters;
+    RAMA_TRY(pos.alloc(ctx, m + 1));
+    RAMA_TRY((exclusive_scan<uint32_t>(ctx, CandFlag{g.c.get(), tau}, pos.get(), m)));
+    uint32_t na = 0;
+    RAMA_TRY(read_back(ctx, &na, pos.get() + m, 4));
+    if (na == 0) return RAMA_OK;
+    RAMA_TRY(act.alloc(ctx, na));
+    RAMA_TRY(act2.alloc(ctx, na));
+    {
+        ProfScope ps_(ctx, "k_collect", (double)(m * 8 + (size_t)na * 4));
+        k_collect<<<grid_for(m), kBlock, 0, ctx.stream>>>(m, g.c.get(), tau, pos.get(), act.get());
+    }
+    LAUNCH_TRY(ctx, "collect");
+    Buf<unsigned long long> best;
+    Buf<int32_t> comp, hook;
+    Buf<uint8_t> in_forest, removed;
+    RAMA_TRY(best.alloc(ctx, n));
+    RAMA_TRY(comp.alloc(ctx, n));
+    RAMA_TRY(hook.alloc(ctx, n));
+    RAMA_TRY(in_forest.alloc(ctx, m));
+    RAMA_TRY(removed.alloc(ctx, m));
+    RAMA_TRY(fill<unsigned long long>(ctx, best.get(), 0ull, n));
+    RAMA_TRY(fill<uint8_t>(ctx, in_forest.get(), (uint8_t)0, m));
+    RAMA_TRY(fill<uint8_t>(ctx, removed.get(), (uint8_t)0, m));
+    {
+        ProfScope ps_(ctx, "k_iota", (double)(n * 8));
+        k_iota<<<grid_for(n), kBlock, 0, ctx.stream>>>(n, comp.get());
+        k_iota<<<grid_for(n), kBlock, 0, ctx.stream>>>(n, hook.get());
+    }
+    LAUNCH_TRY(ctx, "iota");
+    const int max_rounds = 64;   // the number of components with an outgoing edge at least halves per round
+    RAMA_TRY(counters.alloc(ctx, max_rounds));
+    RAMA_TRY(fill<uint32_t>(ctx, counters.get(), 0u, max_rounds));
+    int round = 0;
+    for (; round < max_rounds && na > 0; ++round) {
+        {
+            ProfScope ps_(ctx, "k_bor_propose", (double)((size_t)na * 40));
+            k_bor_propose<<<grid_for(na), kBlock, 0, ctx.stream>>>(na, act.get(), g.i.get(), g.j.get(), g.c.get(), comp.get(),
+                                                                  best.get());
+        }
+        LAUNCH_TRY(ctx, "bor_propose");
+        {
+            ProfScope ps_(ctx, "k_bor_select", (double)((size_t)na * 48));
+            k_bor_select<<<grid_for(na), kBlock, 0, ctx.stream>>>(na, act.get(), g.i.get(), g.j.get(), g.c.get(), comp.get(),
+                                                                 best.get(), hook.get(), in_forest.get());
+        }
+        LAUNCH_TRY(ctx, "bor_select");
+        {
+            ProfScope ps_(ctx, "k_bor_flatten", (double)(n * 12));
+            k_bor_flatten<<<grid_for(n), kBlock, 0, ctx.stream>>>(n, hook.get(), comp.get());
+        }
+        LAUNCH_TRY(ctx, "bor_flatten");
+        {
+            ProfScope ps_(ctx, "k_bor_advance", (double)((size_t)na * 28));
+            k_bor_advance<<<grid_for(na, kBlock * kAdvItems), kBlock, 0, ctx.stream>>>(
+                na, act.get(), g.i.get(), g.j.get(), comp.get(), act2.get(), best.get(), hook.get(), counters.get() + round);
+        }
+        LAUNCH_TRY(ctx, "bor_advance");
+        uint32_t nn = 0;
+        RAMA_TRY(read_back(ctx, &nn, counters.get() + round, 4));
+        act.swap(act2);
+        na = nn;
+    }
+    if (na > 0) return fail(ctx, RAMA_ERR_HIP, "spanning forest did not converge");
+    act.reset(); act2.reset(); best.reset();
+    // forest edge list
+    RAMA_TRY((exclusive_scan<uint32_t>(ctx, ForestFlag{in_forest.get()}, pos.get(), m)));
+    uint32_t nf = 0;
+    RAMA_TRY(read_back(ctx, &nf, pos.get() + m, 4));
+    if (nf == 0) return RAMA_OK;
+    Buf<uint32_t> fe, up_edge;
+    Buf<int32_t> depth, up, changed;
+    RAMA_TRY(fe.alloc(ctx, nf));
+    {
+        ProfScope ps_(ctx, "k_collect_flagged", (double)(m * 5 + (size_t)nf * 4));
+        k_collect_flagged<<<grid_for(m), kBlock, 0, ctx.stream>>>(m, in_forest.get(), (const uint8_t *)nullptr, pos.get(),
+                                                                 g.i.get(), g.j.get(), fe.get(), (int32_t *)nullptr,
+                                                                 (int32_t *)nullptr);
+    }
+    LAUNCH_TRY(ctx, "collect_flagged");
+    // root the trees at their component representative, level by level
+    RAMA_TRY(depth.alloc(ctx, n));
+    RAMA_TRY(up.alloc(ctx, n));
+    RAMA_TRY(up_edge.alloc(ctx, n));
+    RAMA_TRY(changed.alloc(ctx, 1));
+    {
+        ProfScope ps_(ctx, "k_root_init", (double)(n * 12));
+        k_root_init<<<grid_for(n), kBlock, 0, ctx.stream>>>(n, comp.get(), depth.get(), up.get());
+    }
+    LAUNCH_TRY(ctx, "root_init");
+    const int levels_per_check = 8;
+    for (int32_t lvl = 0;; lvl += levels_per_check) {
+        if ((size_t)lvl > n) return fail(ctx, RAMA_ERR_HIP, "forest rooting did not converge");
+        RAMA_TRY(fill<int32_t>(ctx, changed.get(), 0, 1));
+        for (int q = 0; q < levels_per_check; ++q) {
+            ProfScope ps_(ctx, "k_root_level", (double)((size_t)nf * 20));
+            k_root_level<<<grid_for(nf), kBlock, 0, ctx.stream>>>(nf, fe.get(), g.i.get(), g.j.get(), lvl + q, depth.get(),
+                                                                 up.get(), up_edge.get(), changed.get());
+        }
+        LAUNCH_TRY(ctx, "root_level");
+        int32_t h = 0;
+        RAMA_TRY(read_back(ctx, &h, changed.get(), 4));
+        if (!h) break;
+    }
+    {
+        ProfScope ps_(ctx, "k_mark_conflicts", (double)(m * 12));
+        k_mark_conflicts<<<grid_for(m), kBlock, 0, ctx.stream>>>(m, g.i.get(), g.j.get(), g.c.get(), comp.get(), depth.get(),
+                                                                up.get(), up_edge.get(), removed.get());
+    }
+    LAUNCH_TRY(ctx, "mark_conflicts");
+    RAMA_TRY((exclusive_scan<uint32_t>(ctx, KeptFlag{in_forest.get(), removed.get()}, pos.get(), m)));
+    uint32_t ns = 0;
+    RAMA_TRY(read_back(ctx, &ns, pos.get() + m, 4));
+    n_set = ns;
+    if (ns == 0) return RAMA_OK;
+    RAMA_TRY(si.alloc(ctx, ns));
+    RAMA_TRY(sj.alloc(ctx, ns));
+    {
+        ProfScope ps_(ctx, "k_collect_flagged", (double)(m * 6 + (size_t)ns * 8));
+        k_collect_flagged<<<grid_for(m), kBlock, 0, ctx.stream>>>(m, in_forest.get(), removed.get(), pos.get(), g.i.get(),
+                                                                 g.j.get(), (uint32_t *)nullptr, si.get(), sj.get());
+    }
+    LAUNCH_TRY(ctx, "collect_flagged");
     return RAMA_OK;
 }
 
@@ -359,26 +648,33 @@ static rama_status contract_edges(Ctx &ctx, const Graph &g, const int32_t *fmap,
     return RAMA_OK;
 }
 
-rama_status contract_once(Ctx &ctx, const Graph &g, float tau, int rounds_cap, Buf<int32_t> &fmap, int32_t &n_new,
-                          Graph &out, int64_t &n_matched)
+rama_status contract_once(Ctx &ctx, const Graph &g, float tau, int rounds_cap, float forest_ratio, Buf<int32_t> &fmap,
+                          int32_t &n_new, Graph &out, int64_t &n_matched)
 {
     const size_t n = (size_t)g.n;
     Buf<int32_t> mate;
     RAMA_TRY(matching(ctx, g, tau, rounds_cap, mate, n_matched));
     n_new = g.n;
     if (n_matched == 0) return RAMA_OK;
-    const size_t ns = (size_t)n_matched;
     Buf<uint32_t> npos;
     Buf<int32_t> si, sj, rep;
     RAMA_TRY(npos.alloc(ctx, n + 1));
-    RAMA_TRY((exclusive_scan<uint32_t>(ctx, MatchedLow{mate.get()}, npos.get(), n)));
-    RAMA_TRY(si.alloc(ctx, ns));
-    RAMA_TRY(sj.alloc(ctx, ns));
-    {
-        ProfScope ps_(ctx, "k_emit_pairs", (double)(n * 8 + ns * 8));
-        k_emit_pairs<<<grid_for(n), kBlock, 0, ctx.stream>>>(n, mate.get(), npos.get(), si.get(), sj.get());
+    // too few pairs: switch to the spanning forest without conflicts (Sec. 3.1, "fewer than 0.1|V|")
+    if (forest_ratio > 0.0f && (double)n_matched < (double)forest_ratio * (double)g.n) {
+        mate.reset();
+        RAMA_TRY(forest_set(ctx, g, tau, si, sj, n_matched));
+        if (n_matched == 0) return RAMA_OK;
+    } else {
+        RAMA_TRY((exclusive_scan<uint32_t>(ctx, MatchedLow{mate.get()}, npos.get(), n)));
+        RAMA_TRY(si.alloc(ctx, (size_t)n_matched));
+        RAMA_TRY(sj.alloc(ctx, (size_t)n_matched));
+        {
+            ProfScope ps_(ctx, "k_emit_pairs", (double)(n * 8 + (size_t)n_matched * 8));
+            k_emit_pairs<<<grid_for(n), kBlock, 0, ctx.stream>>>(n, mate.get(), npos.get(), si.get(), sj.get());
+        }
+        LAUNCH_TRY(ctx, "emit_pairs");
     }
-    LAUNCH_TRY(ctx, "emit_pairs");
+    const size_t ns = (size_t)n_matched;
     RAMA_TRY(components(ctx, n, ns, si.get(), sj.get(), rep));
     RAMA_TRY((exclusive_scan<uint32_t>(ctx, IsRoot{rep.get()}, npos.get(), n)));
     uint32_t nn = 0;

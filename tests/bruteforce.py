@@ -86,3 +86,21 @@ def tri_min_marginal(ct, s):
 def tri_lb(ct):
     ct = np.asarray(ct, dtype=np.float64)
     return min(float(np.dot(ct, y)) for y in M_T)
+
+
+def forest_path(n, forest_edges, a, b):
+    """Edges (as indices into forest_edges) on the unique a-b path of a forest, or None."""
+    adj = {v: [] for v in range(n)}
+    for k, (u, v) in enumerate(forest_edges):
+        adj[u].append((v, k))
+        adj[v].append((u, k))
+    stack, seen = [(a, [])], {a}
+    while stack:
+        v, path = stack.pop()
+        if v == b:
+            return path
+        for w, k in adj[v]:
+            if w not in seen:
+                seen.add(w)
+                stack.append((w, path + [k]))
+    return None

@@ -159,6 +159,46 @@ def test_contract_parity(rama, oracle32, name, repeat):
           "diag bit-exact:", bool(np.array_equal(np_(got["diag"]), want["diag"])))
 
 
+@pytest.mark.parametrize("name", list(CASES))
+@pytest.mark.parametrize("repeat", [1, 0])
+def test_contract_forest_parity(rama, oracle32, name, repeat):
+    """forest_ratio=1 forces the spanning forest without conflicts in every primal update."""
+    from paper_2109_01838_amd import default_params
+    g = CASES[name]
+    n = g["n_nodes"]
+    cyc = oracle32.find_conflicted_cycles(n, g["i"], g["j"], g["c"], 4)
+    mp = oracle32.message_passing(n, g["i"], g["j"], g["c"], cyc, 5)
+    want = oracle32.contract(n, mp["i"], mp["j"], mp["c"], repeat=repeat, forest_ratio=1.0)
+    got = rama.contract(n, mp["i"], mp["j"], mp["c"], params=default_params(forest_ratio=1.0), repeat=repeat)
+    assert got["n_nodes"] == want["n_nodes"]
+    assert np.array_equal(np_(got["mapping"]), want["mapping"])
+    assert np.array_equal(np_(got["i"]), want["i"]) and np.array_equal(np_(got["j"]), want["j"])
+    assert rel_close(np_(got["c"]), want["c"])
+    assert rel_close(np_(got["diag"]), want["diag"])
+    # no repulsive input edge ends up inside a cluster after ONE forest update
+    if repeat == 1:
+        mp_ = want["mapping"]
+        assert not np.any((mp["c"] < 0) & (mp_[mp["i"]] == mp_[mp["j"]]))
+
+
+def test_forest_deep_tree(rama, oracle32):
+    # a long attractive path with a few repulsive chords: trees of depth ~ thousands of levels
+    n = 6000
+    i = np.arange(n - 1, dtype=np.int32)
+    j = i + 1
+    rng = np.random.default_rng(3)
+    c = rng.uniform(0.5, 1.5, n - 1).astype(np.float32)
+    ci = rng.integers(0, n - 200, 40).astype(np.int32)
+    cj = (ci + rng.integers(2, 200, 40)).astype(np.int32)
+    ii, jj = np.concatenate([i, ci]), np.concatenate([j, cj])
+    cc = np.concatenate([c, -np.ones(40, np.float32)])
+    from paper_2109_01838_amd import default_params
+    want = oracle32.contract(n, ii, jj, cc, repeat=1, forest_ratio=1.0)
+    got = rama.contract(n, ii, jj, cc, params=default_params(forest_ratio=1.0), repeat=1)
+    assert np.array_equal(np_(got["mapping"]), want["mapping"]) and got["n_nodes"] == want["n_nodes"]
+    assert np.array_equal(np_(got["c"]), want["c"])
+
+
 def test_contract_fig2_graph(rama, oracle32):
     # the graph of the paper's Fig. 2; with the matching rule S={st} (cost 4 is the best edge at s and t;
     # rs=3 loses at s), so only the mechanics are compared with the oracle here
@@ -205,14 +245,16 @@ def test_solve_end_to_end(rama, oracle32, name):
           want["rounds"], "primal", got["primal"], want["primal"], "LB", got["lower_bound"], want["lower_bound"])
 
 
-@pytest.mark.parametrize("variant", ["P", "PD+", "D"])
+@pytest.mark.parametrize("variant", ["P", "PD+", "D", "PD-matching-only", "PD-forest-always"])
 def test_solver_variants(rama, oracle32, variant):
     from paper_2109_01838_amd import default_params
     g = CASES["knn_20000"]
     n = g["n_nodes"]
     kw = {"P": dict(max_cycle_len_first=0, max_cycle_len_later=0),
           "PD+": dict(max_cycle_len_later=5),
-          "D": dict(max_rounds=1)}[variant]
+          "D": dict(max_rounds=1),
+          "PD-matching-only": dict(forest_ratio=0.0),
+          "PD-forest-always": dict(forest_ratio=1.0)}[variant]
     want = oracle32.solve(n, g["i"], g["j"], g["c"], **kw)
     got = rama.solve(n, g["i"], g["j"], g["c"], default_params(**kw))
     assert abs(got["lower_bound"] - want["lower_bound"]) <= REL * max(1.0, abs(want["lower_bound"]))

@@ -31,7 +31,8 @@ def test_params_default_and_struct_layout():
     p = binding.default_params()
     assert (p.max_cycle_len_first, p.max_cycle_len_later, p.mp_iters_first, p.mp_iters_later) == (5, 3, 10, 5)
     assert p.matching_rounds_cap == 32 and p.contract_threshold == 0.0 and p.max_rounds == 0
-    assert C.sizeof(binding.RamaParams) == 28
+    assert abs(p.forest_ratio - 0.1) < 1e-7
+    assert C.sizeof(binding.RamaParams) == 32
     assert C.sizeof(binding.RamaStats) == 96
 
 

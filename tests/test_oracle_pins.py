@@ -524,3 +524,81 @@ def test_f32_and_f64_oracles_agree_stagewise(oracle32, oracle64):
     assert abs(a["lower_bound"] - b["lower_bound"]) <= 1e-4 * abs(b["lower_bound"])
     scale = np.abs(b["c"]).max()
     assert np.max(np.abs(a["c"] - b["c"])) <= 1e-4 * scale
+
+
+# --------------------------------------------------------------------------------------------
+# a4, second strategy: maximum spanning forest without conflicts
+# --------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("seed", range(8))
+def test_forest_is_the_maximum_spanning_forest(oracle32, seed):
+    from scipy.sparse.csgraph import minimum_spanning_tree
+    g = inputs.random_graph(40, 160, 900 + seed)
+    n = 40
+    i, j, c = oracle32.canonicalise(n, g["i"], g["j"], g["c"])
+    inf, rem, si, sj = oracle32.forest_set(n, i, j, c)
+    pos = c > 0
+    # library routine: minimum spanning forest of the negated positive costs (costs are distinct)
+    assert np.unique(c[pos]).size == pos.sum()
+    W = sp.coo_matrix((-c[pos].astype(np.float64), (i[pos], j[pos])), shape=(n, n)).tocsr()
+    T = minimum_spanning_tree(W).tocoo()
+    want = {(min(a, b), max(a, b)) for a, b in zip(T.row.tolist(), T.col.tolist())}
+    got = {(a, b) for a, b, f in zip(i.tolist(), j.tolist(), inf.tolist()) if f}
+    assert got == want
+    assert not inf[~pos].any() and not rem[~inf].any()
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_forest_conflict_removal_by_brute_force(oracle32, seed):
+    rng = np.random.default_rng(950 + seed)
+    n = 30
+    g = inputs.random_graph(n, 70, 950 + seed)
+    c = np.where(rng.random(g["c"].size) < 0.7, np.abs(g["c"]), -np.abs(g["c"])).astype(np.float32)
+    i, j, c = oracle32.canonicalise(n, g["i"], g["j"], c)
+    inf, rem, si, sj = oracle32.forest_set(n, i, j, c)
+    fidx = np.where(inf)[0]
+    fedges = list(zip(i[fidx].tolist(), j[fidx].tolist()))
+    want = set()
+    for e in np.where(c < 0)[0]:
+        path = bf.forest_path(n, fedges, int(i[e]), int(j[e]))
+        if path:
+            # lowest edge: smallest cost, ties to the later canonical position
+            want.add(min((fidx[k] for k in path), key=lambda q: (c[q], -q)))
+    assert set(np.where(rem)[0].tolist()) == want
+    kept = inf & ~rem
+    assert np.array_equal(si, i[kept]) and np.array_equal(sj, j[kept])
+    # no repulsive edge inside a component of (V,S); the best edge of every tree survives
+    rep, fmap, nn = oracle32.components(n, si, sj)
+    assert not np.any((c < 0) & (fmap[i] == fmap[j]))
+    k, lab = connected_components(sp.coo_matrix((np.ones(fidx.size), (i[fidx], j[fidx])), shape=(n, n)), directed=False)
+    for t in range(k):
+        es = [q for q in fidx if lab[i[q]] == t]
+        if es:
+            assert kept[max(es, key=lambda q: (c[q], -q))]
+
+
+def test_forest_switch_in_contraction(oracle32):
+    # a star: the matching can only join one pair, the forest joins the whole star
+    i = np.zeros(9, np.int32)
+    j = np.arange(1, 10, dtype=np.int32)
+    c = np.linspace(1.0, 2.0, 9).astype(np.float32)
+    a = oracle32.contract(10, i, j, c, repeat=1, forest_ratio=0.0)
+    b = oracle32.contract(10, i, j, c, repeat=1, forest_ratio=0.2)
+    assert a["n_nodes"] == 9 and b["n_nodes"] == 1
+    assert abs(float(b["diag"][0]) - float(c.astype(np.float64).sum())) < 1e-5
+    # with a repulsive edge between two leaves the weaker of the two spokes is dropped
+    i2 = np.concatenate([i, [1]]).astype(np.int32)
+    j2 = np.concatenate([j, [2]]).astype(np.int32)
+    c2 = np.concatenate([c, [-5.0]]).astype(np.float32)
+    r = oracle32.contract(10, i2, j2, c2, repeat=1, forest_ratio=0.2)
+    assert r["n_nodes"] == 2 and r["mapping"][1] != r["mapping"][2] and r["mapping"][2] == r["mapping"][0]
+    assert r["c"].tolist() == [float(c[0]) + (-5.0)]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_solve_with_forest_sandwich(oracle32, seed):
+    g = small_random(970 + seed)
+    n = g["n_nodes"]
+    opt, _ = bf.optimal_multicut(n, g["i"], g["j"], g["c"])
+    for fr in (0.0, 0.1, 1.0):
+        r = oracle32.solve(n, g["i"], g["j"], g["c"], forest_ratio=fr)
+        assert r["lower_bound"] <= opt + 1e-4 * (1 + abs(opt)) <= r["primal"] + 2e-4 * (1 + abs(opt))
