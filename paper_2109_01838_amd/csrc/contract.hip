@@ -166,12 +166,6 @@ __global__ __launch_bounds__(kBlock) void k_number(size_t n, const int32_t *rep,
 }
 
 // ---- contraction ---------------------------------------------------------------------------------
-struct CrossFlag {
-    static constexpr int bytes = 16;   // bytes read per item
-    static constexpr const char *tag = "CrossFlag";
-    const int32_t *i, *j, *fmap;
-    __device__ __forceinline__ uint32_t operator()(size_t e) const { return fmap[i[e]] != fmap[j[e]] ? 1u : 0u; }
-};
 struct InnerFlag {
     static constexpr int bytes = 16;   // bytes read per item
     static constexpr const char *tag = "InnerFlag";
@@ -179,17 +173,33 @@ struct InnerFlag {
     __device__ __forceinline__ uint32_t operator()(size_t e) const { return fmap[i[e]] == fmap[j[e]] ? 1u : 0u; }
 };
 
-// relabelled, re-oriented cross edges -> (key, cost) in input order
-__global__ __launch_bounds__(kBlock) void k_relabel(size_t m, const int32_t *i, const int32_t *j, const float *c,
-                                                    const int32_t *fmap, const uint32_t *pos, int nbits, uint64_t *key,
-                                                    uint32_t *val)
+// Relabelling gathers f' for both endpoints of every edge -- random 4-byte reads, the expensive
+// part of the contraction -- so it is done exactly once: the packed pair of every edge is stored
+// (loops get an all-ones key), the scan and the compaction then stream over the stored keys.
+constexpr uint64_t kLoopKey = ~0ull;
+__global__ __launch_bounds__(kBlock) void k_relabel_keys(size_t m, const int32_t *i, const int32_t *j,
+                                                         const int32_t *fmap, int nbits, uint64_t *raw)
 {
     size_t e = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (e >= m) return;
     int32_t a = fmap[i[e]], b = fmap[j[e]];
-    if (a == b) return;
+    raw[e] = (a == b) ? kLoopKey : (((uint64_t)(uint32_t)min(a, b) << nbits) | (uint32_t)max(a, b));
+}
+struct NotLoopKey {
+    static constexpr int bytes = 8;   // bytes read per item
+    static constexpr const char *tag = "NotLoopKey";
+    const uint64_t *raw;
+    __device__ __forceinline__ uint32_t operator()(size_t e) const { return raw[e] != kLoopKey ? 1u : 0u; }
+};
+__global__ __launch_bounds__(kBlock) void k_compact_keys(size_t m, const uint64_t *raw, const float *c,
+                                                         const uint32_t *pos, uint64_t *key, uint32_t *val)
+{
+    size_t e = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (e >= m) return;
+    uint64_t k = raw[e];
+    if (k == kLoopKey) return;
     uint32_t p = pos[e];
-    key[p] = ((uint64_t)(uint32_t)min(a, b) << nbits) | (uint32_t)max(a, b);
+    key[p] = k;
     val[p] = __float_as_uint(c[e]);
 }
 
@@ -606,9 +616,17 @@ static rama_status contract_edges(Ctx &ctx, const Graph &g, const int32_t *fmap,
     const size_t m = (size_t)g.m;
     out.n = n_new;
     out.m = 0;
+    const int nbits = bits_for((uint64_t)n_new);
     Buf<uint32_t> pos;
+    Buf<uint64_t> raw;
     RAMA_TRY(pos.alloc(ctx, m + 1));
-    RAMA_TRY((exclusive_scan<uint32_t>(ctx, CrossFlag{g.i.get(), g.j.get(), fmap}, pos.get(), m)));
+    RAMA_TRY(raw.alloc(ctx, m));
+    {
+        ProfScope ps_(ctx, "k_relabel_keys", (double)(m * 24));
+        k_relabel_keys<<<grid_for(m), kBlock, 0, ctx.stream>>>(m, g.i.get(), g.j.get(), fmap, nbits, raw.get());
+    }
+    LAUNCH_TRY(ctx, "relabel_keys");
+    RAMA_TRY((exclusive_scan<uint32_t>(ctx, NotLoopKey{raw.get()}, pos.get(), m)));
     uint32_t kept = 0;
     RAMA_TRY(read_back(ctx, &kept, pos.get() + m, 4));
     if (kept == 0) {
@@ -617,18 +635,17 @@ static rama_status contract_edges(Ctx &ctx, const Graph &g, const int32_t *fmap,
         RAMA_TRY(out.c.alloc(ctx, 1));
         return RAMA_OK;
     }
-    const int nbits = bits_for((uint64_t)n_new);
     Buf<uint64_t> key;
     Buf<uint32_t> val;
     RAMA_TRY(key.alloc(ctx, kept));
     RAMA_TRY(val.alloc(ctx, kept));
     {
-        ProfScope ps_(ctx, "k_relabel", (double)(m * 28 + (size_t)kept * 12));
-        k_relabel<<<grid_for(m), kBlock, 0, ctx.stream>>>(m, g.i.get(), g.j.get(), g.c.get(), fmap, pos.get(), nbits,
-                                                      key.get(), val.get());
+        ProfScope ps_(ctx, "k_compact_keys", (double)(m * 16 + (size_t)kept * 12));
+        k_compact_keys<<<grid_for(m), kBlock, 0, ctx.stream>>>(m, raw.get(), g.c.get(), pos.get(), key.get(), val.get());
     }
-    LAUNCH_TRY(ctx, "relabel");
+    LAUNCH_TRY(ctx, "compact_keys");
     pos.reset();
+    raw.reset();
     RAMA_TRY((radix_sort_pairs<uint64_t, uint32_t>(ctx, key, val, kept, 2 * nbits)));
     Buf<uint32_t> opos;
     RAMA_TRY(opos.alloc(ctx, (size_t)kept + 1));

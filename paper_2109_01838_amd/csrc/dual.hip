@@ -109,39 +109,45 @@ __global__ __launch_bounds__(kBlock) void k_chord_keys(CycleSet s, size_t nch, i
     key[q] = ((uint64_t)(uint32_t)min(a, b) << nbits) | (uint32_t)max(a, b);
 }
 
-// first-of-run flag that also requires the chord to be absent from the graph
-struct NewChordFlag {
-    static constexpr int bytes = 16;   // bytes read per item
-    static constexpr const char *tag = "NewChordFlag";
-    const uint64_t *key;
-    const int32_t *rowptr, *j;
-    int nbits;
-    __device__ __forceinline__ uint32_t operator()(size_t q) const
-    {
-        uint64_t k = key[q];
-        if (q > 0 && key[q - 1] == k) return 0u;
-        int32_t u = (int32_t)(k >> nbits), v = (int32_t)(k & ((1ull << nbits) - 1ull));
-        return find_edge_in_row(rowptr, j, u, v) < 0 ? 1u : 0u;
-    }
-};
-
-// compacts the new chords and records, for each, the number of graph edges that precede it
-__global__ __launch_bounds__(kBlock) void k_emit_chords(size_t nch, const uint64_t *key, const uint32_t *pos,
-                                                        const int32_t *rowptr, const int32_t *j, int nbits,
-                                                        int32_t *ci, int32_t *cj, int32_t *before)
+// For every sorted chord key: where it would be inserted in the canonical edge list, or -1 if
+// it repeats the previous key or is an edge already.  One binary search per chord, done once.
+__global__ __launch_bounds__(kBlock) void k_chord_lookup(size_t nch, const uint64_t *key, const int32_t *rowptr,
+                                                         const int32_t *j, int nbits, int32_t *where)
 {
     size_t q = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (q >= nch) return;
-    if (pos[q] == pos[q + 1]) return;
     uint64_t k = key[q];
+    if (q > 0 && key[q - 1] == k) { where[q] = -1; return; }
     int32_t u = (int32_t)(k >> nbits), v = (int32_t)(k & ((1ull << nbits) - 1ull));
     int32_t lo = rowptr[u], hi = rowptr[u + 1];
+    const int32_t end = hi;
     while (lo < hi) {
         int32_t mid = lo + ((hi - lo) >> 1);
         if (j[mid] < v) lo = mid + 1; else hi = mid;
     }
+    where[q] = (lo < end && j[lo] == v) ? -1 : lo;
+}
+struct NewChordFlag {
+    static constexpr int bytes = 4;   // bytes read per item
+    static constexpr const char *tag = "NewChordFlag";
+    const int32_t *where;
+    __device__ __forceinline__ uint32_t operator()(size_t q) const { return where[q] >= 0 ? 1u : 0u; }
+};
+
+// compacts the new chords together with the number of graph edges that precede each
+__global__ __launch_bounds__(kBlock) void k_emit_chords(size_t nch, const uint64_t *key, const int32_t *where,
+                                                        const uint32_t *pos, int nbits, int32_t *ci, int32_t *cj,
+                                                        int32_t *before)
+{
+    size_t q = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (q >= nch) return;
+    int32_t w = where[q];
+    if (w < 0) return;
+    uint64_t k = key[q];
     uint32_t p = pos[q];
-    ci[p] = u; cj[p] = v; before[p] = lo;
+    ci[p] = (int32_t)(k >> nbits);
+    cj[p] = (int32_t)(k & ((1ull << nbits) - 1ull));
+    before[p] = w;
 }
 
 // merge of the canonical edge list with the (sorted, disjoint) new chords.
@@ -417,8 +423,16 @@ rama_status dual_update(Ctx &ctx, const Graph &g, const int32_t *c3, int64_t n3,
         LAUNCH_TRY(ctx, "chord_keys");
         RAMA_TRY((radix_sort_keys<uint64_t>(ctx, ckey, nch, 2 * nbits)));
         Buf<uint32_t> cpos;
+        Buf<int32_t> where;
         RAMA_TRY(cpos.alloc(ctx, nch + 1));
-        RAMA_TRY((exclusive_scan<uint32_t>(ctx, NewChordFlag{ckey.get(), rowptr.get(), g.j.get(), nbits}, cpos.get(), nch)));
+        RAMA_TRY(where.alloc(ctx, nch));
+        {
+            ProfScope ps_(ctx, "k_chord_lookup", (double)(nch * 20));
+            k_chord_lookup<<<grid_for(nch), kBlock, 0, ctx.stream>>>(nch, ckey.get(), rowptr.get(), g.j.get(), nbits,
+                                                                    where.get());
+        }
+        LAUNCH_TRY(ctx, "chord_lookup");
+        RAMA_TRY((exclusive_scan<uint32_t>(ctx, NewChordFlag{where.get()}, cpos.get(), nch)));
         RAMA_TRY(read_back(ctx, &nnew, cpos.get() + nch, 4));
         if (nnew > 0) {
             Buf<int32_t> ci, cj, before, ins;
@@ -428,8 +442,8 @@ rama_status dual_update(Ctx &ctx, const Graph &g, const int32_t *c3, int64_t n3,
             RAMA_TRY(ins.alloc(ctx, m + 2));
             {
                 ProfScope ps_(ctx, "k_emit_chords", (double)(nch * 16 + (size_t)nnew * 12));
-                k_emit_chords<<<grid_for(nch), kBlock, 0, ctx.stream>>>(nch, ckey.get(), cpos.get(), rowptr.get(), g.j.get(),
-                                                                   nbits, ci.get(), cj.get(), before.get());
+                k_emit_chords<<<grid_for(nch), kBlock, 0, ctx.stream>>>(nch, ckey.get(), where.get(), cpos.get(), nbits,
+                                                                       ci.get(), cj.get(), before.get());
             }
             LAUNCH_TRY(ctx, "emit_chords");
             // ins[v] = number of chords with before < v ; chords placed before edge e: before <= e -> ins[e+1]

@@ -1,0 +1,37 @@
+"""End-to-end parity on the named configurations the oracle can still solve (cfg2: 512x512 grid
+with long-range edges, 1.56e6 edges; cfg3: 1e6-point 6-NN graph, ~3.5e6 edges) at their full
+sizes: primal within 0.5 %, lower bound within 1e-4 relative, and -- because both sides order
+their arithmetic identically -- in practice identical labels."""
+import numpy as np
+import pytest
+
+from paper_2109_01838_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def rama():
+    from paper_2109_01838_amd import Rama
+    r = Rama("cuda:0")
+    yield r
+    r.close()
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name", ["cfg2", "cfg3"])
+def test_named_config_end_to_end(rama, oracle32, name):
+    g = inputs.make(name)
+    n = g["n_nodes"]
+    got = rama.solve(n, g["i"], g["j"], g["c"])
+    print(name, "gpu:", {k: v for k, v in got.items() if k not in ("labels",)}, flush=True)
+    want = oracle32.solve(n, g["i"], g["j"], g["c"])
+    labels = got["labels"].cpu().numpy()
+    assert abs(got["lower_bound"] - want["lower_bound"]) <= 1e-4 * abs(want["lower_bound"])
+    assert abs(got["primal"] - want["primal"]) <= 5e-3 * abs(want["primal"])
+    assert got["n_cycles_first"] == want["n_cycles_first"]
+    assert got["n_edges_aug_first"] == want["n_edges_aug_first"]
+    assert abs(oracle32.multicut_cost(g["i"], g["j"], g["c"], labels) - got["primal"]) <= 1e-6 * abs(got["primal"])
+    assert got["lower_bound"] <= got["primal"]
+    print(name, "labels identical:", bool(np.array_equal(labels, want["labels"])), "rounds", got["rounds"], want["rounds"],
+          "primal", got["primal"], want["primal"])
