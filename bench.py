@@ -112,8 +112,16 @@ def main():
         launches_per_step = d["launches"] / args.steps
         avg_ms = d["ms"] / max(d["launches"], 1)
         gbps = (d["bytes"] / 1e9) / (d["ms"] / 1e3) if d["ms"] > 0 else 0.0
+        # measured HBM bytes per launch of this kernel from the committed rocprofv3 --pmc summary
+        # (FETCH_SIZE / WRITE_SIZE runs of this same workload, scaled by the copy-kernel calibration)
+        traffic = None
+        tpath = os.path.join(ROOT, "profiles", "cfg5_solve_hbm_traffic.json")
+        if args.workload == "cfg5" and os.path.exists(tpath):
+            t = json.load(open(tpath))["kernels"].get(dominant)
+            if t:
+                traffic = t["read_bytes_per_launch"] + t["written_bytes_per_launch"]
         roofline = {"bound": "hbm", "kernel": dominant, "achieved": gbps, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": gbps / HBM_PEAK_GBS, "traffic": None,
+                    "frac": gbps / HBM_PEAK_GBS, "traffic": traffic,
                     "launches_per_step": launches_per_step, "avg_launch_ms": avg_ms,
                     "algorithmic_bytes_per_launch": d["bytes"] / max(d["launches"], 1),
                     "share_of_kernel_time": kernels[0]["share"],

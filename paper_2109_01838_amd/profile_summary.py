@@ -2,6 +2,7 @@
 
   python -m paper_2109_01838_amd.profile_summary stats  <..._kernel_stats.csv> [n_solves]
   python -m paper_2109_01838_amd.profile_summary pmc    <..._counter_collection.csv> <COUNTER> [kernel substrings..]
+  python -m paper_2109_01838_amd.profile_summary traffic <fetch.csv> <write.csv> <fetch_scale> <write_scale> <out.json>
 """
 import csv
 import sys
@@ -40,8 +41,44 @@ def pmc(path, counter, subs):
         print(f"{name[:70]:<70} {n:>10} {v:>18.1f} {v / n:>16.1f}")
 
 
+def event_name(rocprof_name):
+    """Kernel name as the library's own timers spell it (bench.py's `kernels` table)."""
+    n = short(rocprof_name)
+    n = (n.replace("unsigned long", "u64").replace("unsigned int", "u32").replace(", ", ",")
+          .replace(",true>", ">").replace("<u64,u32,false>", "<u64>").replace("<u32,u32,false>", "<u32>"))
+    if n.startswith(("k_scan_", "k_sum_partial")) and "<" in n:
+        head, args = n.split("<", 1)
+        functor = args.rstrip(">").split(",")[-1].split("<")[0].strip()
+        n = f"{head}<{functor}>"
+    if n.startswith("k_rs_hist<"):
+        n = n.replace(">", ">")
+    return n
+
+
+def traffic_json(fetch_csv, write_csv, fetch_scale, write_scale, out_path):
+    """Per kernel: average HBM bytes per launch = scale*FETCH_SIZE + scale*WRITE_SIZE (KiB -> bytes)."""
+    import json
+    acc = defaultdict(lambda: [0, 0.0, 0, 0.0])
+    for path, counter, slot in ((fetch_csv, "FETCH_SIZE", 0), (write_csv, "WRITE_SIZE", 2)):
+        for r in csv.DictReader(open(path)):
+            if r.get("Counter_Name") != counter:
+                continue
+            a = acc[event_name(r["Kernel_Name"])]
+            a[slot] += 1
+            a[slot + 1] += float(r["Counter_Value"])
+    out = {}
+    for name, (nf, f, nw, w) in acc.items():
+        if nf and nw and (name.startswith("k_") or name.startswith("__amd")):
+            out[name] = {"launches": nf, "read_bytes_per_launch": 1024.0 * fetch_scale * f / nf,
+                         "written_bytes_per_launch": 1024.0 * write_scale * w / nw}
+    json.dump({"fetch_scale": fetch_scale, "write_scale": write_scale, "kernels": out}, open(out_path, "w"), indent=1,
+              sort_keys=True)
+
+
 if __name__ == "__main__":
-    if sys.argv[1] == "stats":
+    if sys.argv[1] == "traffic":
+        traffic_json(sys.argv[2], sys.argv[3], float(sys.argv[4]), float(sys.argv[5]), sys.argv[6])
+    elif sys.argv[1] == "stats":
         stats(sys.argv[2], int(sys.argv[3]) if len(sys.argv) > 3 else 1)
     else:
         pmc(sys.argv[2], sys.argv[3], sys.argv[4:])
