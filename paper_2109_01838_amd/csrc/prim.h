@@ -291,7 +291,10 @@ __device__ __forceinline__ uint64_t match_digit(uint32_t d, int bits, uint64_t v
 // tile's digit-sorted order, (3) keys (and values) are staged in LDS in that order, (4) the tile
 // is written out linearly -- neighbouring lanes hold neighbouring keys of the same digit, so the
 // global stores fall into contiguous runs instead of 64 scattered lines per instruction.
-template <typename K, typename V, bool HAS_V>
+// With LOCAL_SCAN (few tiles) `offs` is the raw [digit][tile] histogram and every workgroup derives
+// its own global offsets from it, which saves the three scan launches of the pass.
+constexpr uint32_t kSortLocalScanTiles = 32;
+template <typename K, typename V, bool HAS_V, bool LOCAL_SCAN>
 __global__ __launch_bounds__(kBlock) void k_rs_scatter(const K *kin, const V *vin, K *kout, V *vout,
                                                        const uint32_t *offs, size_t n, int shift, int bits,
                                                        uint32_t nb)
@@ -340,10 +343,37 @@ __global__ __launch_bounds__(kBlock) void k_rs_scatter(const K *kin, const V *vi
                 tot += c[q][k];
             }
         uint32_t run = block_inclusive_scan(tot, &all) - tot;
+        uint32_t goff[kDigitsPerThread];
+        if (LOCAL_SCAN) {
+            // keys of smaller digits (all tiles) + keys of the same digit in earlier tiles
+            uint32_t rows = 0, before[kDigitsPerThread], rowsum[kDigitsPerThread];
+#pragma unroll
+            for (int q = 0; q < kDigitsPerThread; ++q) {
+                const uint32_t d = (uint32_t)(tid * kDigitsPerThread + q);
+                before[q] = 0; rowsum[q] = 0;
+                if (d <= mask)
+                    for (uint32_t b = 0; b < nb; ++b) {
+                        uint32_t h = offs[(size_t)d * nb + b];
+                        if (b < blockIdx.x) before[q] += h;
+                        rowsum[q] += h;
+                    }
+                rows += rowsum[q];
+            }
+            uint32_t dummy;
+            uint32_t dig = block_inclusive_scan(rows, &dummy) - rows;
+#pragma unroll
+            for (int q = 0; q < kDigitsPerThread; ++q) { goff[q] = dig + before[q]; dig += rowsum[q]; }
+        } else {
+#pragma unroll
+            for (int q = 0; q < kDigitsPerThread; ++q) {
+                const uint32_t d = (uint32_t)(tid * kDigitsPerThread + q);
+                goff[q] = d <= mask ? offs[(size_t)d * nb + blockIdx.x] : 0u;
+            }
+        }
 #pragma unroll
         for (int q = 0; q < kDigitsPerThread; ++q) {
             const uint32_t d = (uint32_t)(tid * kDigitsPerThread + q);
-            gdelta[d] = (d <= mask ? offs[(size_t)d * nb + blockIdx.x] : 0u) - run;
+            gdelta[d] = goff[q] - run;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 whist[k][d] = run;
@@ -404,11 +434,14 @@ rama_status radix_sort_impl(Ctx &ctx, K *ka, V *va, K *kb, V *vb, size_t n, int 
             k_rs_hist<K><<<nb, kBlock, 0, ctx.stream>>>(ka, hist.get(), n, shift, bits, nb);
         }
         LAUNCH_TRY(ctx, "rs_hist");
-        RAMA_TRY((exclusive_scan<uint32_t, PtrInput<uint32_t>>(ctx, PtrInput<uint32_t>{hist.get()}, offs.get(),
-                                                                (size_t)nb << bits)));
-        {
+        if (nb <= kSortLocalScanTiles) {
             ProfScope ps_(ctx, rs_scatter_name<K, HAS_V>(), (double)(n * (2 * sizeof(K) + (HAS_V ? 8 : 0))));
-            k_rs_scatter<K, V, HAS_V><<<nb, kBlock, 0, ctx.stream>>>(ka, va, kb, vb, offs.get(), n, shift, bits, nb);
+            k_rs_scatter<K, V, HAS_V, true><<<nb, kBlock, 0, ctx.stream>>>(ka, va, kb, vb, hist.get(), n, shift, bits, nb);
+        } else {
+            RAMA_TRY((exclusive_scan<uint32_t, PtrInput<uint32_t>>(ctx, PtrInput<uint32_t>{hist.get()}, offs.get(),
+                                                                    (size_t)nb << bits)));
+            ProfScope ps_(ctx, rs_scatter_name<K, HAS_V>(), (double)(n * (2 * sizeof(K) + (HAS_V ? 8 : 0))));
+            k_rs_scatter<K, V, HAS_V, false><<<nb, kBlock, 0, ctx.stream>>>(ka, va, kb, vb, offs.get(), n, shift, bits, nb);
         }
         LAUNCH_TRY(ctx, "rs_scatter");
         std::swap(ka, kb);
