@@ -5,7 +5,8 @@
 //         the canonical list) packed into one 64-bit word, so "each node points at its best
 //         incident candidate" is an integer atomicMax per endpoint -- order independent, hence
 //         deterministic.  An edge both of whose endpoints point at it is matched; rounds repeat
-//         on the shrinking list of edges whose endpoints are both still free.
+//         on the shrinking list of edges whose endpoints are both still free (two kernels per
+//         round: accept, then compaction of the survivors fused with their next proposals).
 //   f'  : connected components of (V,S) by min-label hooking + pointer jumping; a component is
 //         represented by its smallest node; new ids are the ranks of the representatives.
 //   S'  : when the matching joins fewer than forest_ratio*|V| pairs: maximum spanning forest of the
@@ -44,19 +45,44 @@ __global__ __launch_bounds__(kBlock) void k_collect(size_t m, const float *c, fl
     if (e < m && c[e] > tau) act[pos[e]] = (uint32_t)e;
 }
 
+// Both endpoints of a candidate edge learn its rank.  The candidate list of the first round is
+// in canonical order, so neighbouring lanes often share the first endpoint: those lanes combine
+// their ranks with shuffles and only the last lane of a run issues the atomic.  (Combining any
+// two lanes with the same node is valid whatever the list order; runs only make it pay.)
+__device__ __forceinline__ void propose_edge(bool valid, int32_t u, int32_t v, unsigned long long r,
+                                             unsigned long long *best)
+{
+    const int lane = lane_id();
+    unsigned long long ru = valid ? r : 0ull;
+    const int32_t key = valid ? u : -1 - lane;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        unsigned long long other_r = __shfl_up(ru, off, 64);
+        int32_t other_k = __shfl_up(key, off, 64);
+        if (lane >= off && other_k == key && other_r > ru) ru = other_r;
+    }
+    const int32_t next_k = __shfl_down(key, 1, 64);
+    if (valid) {
+        if (lane == 63 || next_k != key) atomicMax(&best[u], ru);
+        atomicMax(&best[v], r);
+    }
+}
+
 __global__ __launch_bounds__(kBlock) void k_propose(size_t na, const uint32_t *act, const int32_t *i, const int32_t *j,
                                                     const float *c, unsigned long long *best)
 {
     size_t a = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    if (a >= na) return;
-    uint32_t e = act[a];
-    unsigned long long r = edge_rank(c[e], e);
-    atomicMax(&best[i[e]], r);
-    atomicMax(&best[j[e]], r);
+    const bool valid = a < na;
+    uint32_t e = valid ? act[a] : 0u;
+    int32_t u = valid ? i[e] : 0, v = valid ? j[e] : 0;
+    propose_edge(valid, u, v, valid ? edge_rank(c[e], e) : 0ull, best);
 }
 
+// matched edges fix their endpoints; the rank words the next round will use are cleared for the
+// endpoints of every edge still listed (the two rank arrays alternate between rounds)
 __global__ __launch_bounds__(kBlock) void k_accept(size_t na, const uint32_t *act, const int32_t *i, const int32_t *j,
-                                                   const float *c, const unsigned long long *best, int32_t *mate)
+                                                   const float *c, const unsigned long long *best,
+                                                   unsigned long long *best_next, int32_t *mate)
 {
     size_t a = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (a >= na) return;
@@ -64,17 +90,18 @@ __global__ __launch_bounds__(kBlock) void k_accept(size_t na, const uint32_t *ac
     unsigned long long r = edge_rank(c[e], e);
     int32_t u = i[e], v = j[e];
     if (best[u] == r && best[v] == r) { mate[u] = v; mate[v] = u; }
+    best_next[u] = 0ull;
+    best_next[v] = 0ull;
 }
 
-// Survivors (both endpoints still free) move to the next list and the pointers of their
-// endpoints are cleared for the next round.  Every workgroup compacts 2048 candidates locally and
-// reserves its output range with a single atomicAdd; the order of the ranges varies from run to
-// run, which is harmless: the atomicMax proposals and the accept test do not depend on the order
-// of the list.
+// Survivors (both endpoints still free) move to the next list and at once propose for the next
+// round.  Every workgroup compacts 2048 candidates locally and reserves its output range with a
+// single atomicAdd; the order of the ranges varies from run to run, which is harmless: proposals
+// (atomicMax) and the accept test do not depend on the order of the list.
 constexpr int kAdvItems = 8;
 __global__ __launch_bounds__(kBlock) void k_advance(size_t na, const uint32_t *act, const int32_t *i, const int32_t *j,
-                                                    const int32_t *mate, uint32_t *act_next,
-                                                    unsigned long long *best, uint32_t *counter)
+                                                    const float *c, const int32_t *mate, uint32_t *act_next,
+                                                    unsigned long long *best_next, uint32_t *counter)
 {
     __shared__ uint32_t s_base;
     const size_t tile = (size_t)blockIdx.x * (kBlock * kAdvItems);
@@ -84,16 +111,15 @@ __global__ __launch_bounds__(kBlock) void k_advance(size_t na, const uint32_t *a
     for (int q = 0; q < kAdvItems; ++q) {
         size_t a = tile + (size_t)threadIdx.x * kAdvItems + q;
         e[q] = 0;
+        bool ok = false;
+        int32_t u = 0, v = 0;
         if (a < na) {
             e[q] = act[a];
-            int32_t u = i[e[q]], v = j[e[q]];
-            if (mate[u] < 0 && mate[v] < 0) {
-                keep |= 1u << q;
-                ++cnt;
-                best[u] = 0ull;
-                best[v] = 0ull;
-            }
+            u = i[e[q]]; v = j[e[q]];
+            ok = mate[u] < 0 && mate[v] < 0;
         }
+        if (ok) { keep |= 1u << q; ++cnt; }
+        propose_edge(ok, u, v, ok ? edge_rank(c[e[q]], e[q]) : 0ull, best_next);
     }
     uint32_t total;
     uint32_t off = block_inclusive_scan(cnt, &total) - cnt;
@@ -410,33 +436,36 @@ static rama_status matching(Ctx &ctx, const Graph &g, float tau, int rounds_cap,
         k_collect<<<grid_for(m), kBlock, 0, ctx.stream>>>(m, g.c.get(), tau, pos.get(), act.get());
     }
     LAUNCH_TRY(ctx, "collect");
-    Buf<unsigned long long> best;
+    Buf<unsigned long long> best, best_next;     // rank words of the current and of the next round
     RAMA_TRY(best.alloc(ctx, n));
+    RAMA_TRY(best_next.alloc(ctx, n));
     RAMA_TRY(fill<unsigned long long>(ctx, best.get(), 0ull, n));
+    RAMA_TRY(fill<unsigned long long>(ctx, best_next.get(), 0ull, n));
     Buf<uint32_t> counters;                      // one survivor counter per handshake round
     RAMA_TRY(counters.alloc(ctx, (size_t)(rounds_cap > 0 ? rounds_cap : 1)));
     RAMA_TRY(fill<uint32_t>(ctx, counters.get(), 0u, (size_t)(rounds_cap > 0 ? rounds_cap : 1)));
+    if (rounds_cap > 0) {
+        ProfScope ps_(ctx, "k_propose", (double)((size_t)na * 32));
+        k_propose<<<grid_for(na), kBlock, 0, ctx.stream>>>(na, act.get(), g.i.get(), g.j.get(), g.c.get(), best.get());
+    }
+    LAUNCH_TRY(ctx, "propose");
     for (int r = 0; r < rounds_cap && na > 0; ++r) {
         {
-            ProfScope ps_(ctx, "k_propose", (double)((size_t)na * 32));
-            k_propose<<<grid_for(na), kBlock, 0, ctx.stream>>>(na, act.get(), g.i.get(), g.j.get(), g.c.get(), best.get());
-        }
-        LAUNCH_TRY(ctx, "propose");
-        {
-            ProfScope ps_(ctx, "k_accept", (double)((size_t)na * 40));
+            ProfScope ps_(ctx, "k_accept", (double)((size_t)na * 56));
             k_accept<<<grid_for(na), kBlock, 0, ctx.stream>>>(na, act.get(), g.i.get(), g.j.get(), g.c.get(), best.get(),
-                                                             mate.get());
+                                                             best_next.get(), mate.get());
         }
         LAUNCH_TRY(ctx, "accept");
         {
-            ProfScope ps_(ctx, "k_advance", (double)((size_t)na * 20));
-            k_advance<<<grid_for(na, kBlock * kAdvItems), kBlock, 0, ctx.stream>>>(na, act.get(), g.i.get(), g.j.get(), mate.get(), act2.get(),
-                                                              best.get(), counters.get() + r);
+            ProfScope ps_(ctx, "k_advance", (double)((size_t)na * 40));
+            k_advance<<<grid_for(na, kBlock * kAdvItems), kBlock, 0, ctx.stream>>>(
+                na, act.get(), g.i.get(), g.j.get(), g.c.get(), mate.get(), act2.get(), best_next.get(), counters.get() + r);
         }
         LAUNCH_TRY(ctx, "advance");
         uint32_t nn = 0;
         RAMA_TRY(read_back(ctx, &nn, counters.get() + r, 4));
         act.swap(act2);
+        best.swap(best_next);
         na = nn;
     }
     Buf<uint32_t> npos;

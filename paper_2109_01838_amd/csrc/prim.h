@@ -240,15 +240,17 @@ __global__ __launch_bounds__(kBlock) void k_row_bounds_search(const K *keys, siz
 }
 
 // ------------------------------------------------------------------------------------------
-// stable LSD radix sort, up to kRadixBits bits per pass, 4096 keys per workgroup.
+// stable LSD radix sort, up to kRadixBits bits per pass, 6144 / 5120 keys per workgroup.
 // Ranking inside a wave uses ballot-based match-any, so equal digits keep their order
 // without any atomics in the scatter pass.
 // ------------------------------------------------------------------------------------------
-#ifndef RAMA_SORT_ITEMS
-#define RAMA_SORT_ITEMS 16
-#endif
-constexpr int kSortItems = RAMA_SORT_ITEMS;
-constexpr int kSortTile = kBlock * kSortItems;
+// keys per thread: larger tiles give longer contiguous runs per digit on the way out; 24 (64-bit
+// keys) and 20 (32-bit keys) measured best, beyond that the LDS footprint costs more than it gains
+template <typename K>
+struct SortTile {
+    static constexpr int items = sizeof(K) == 8 ? 24 : 20;
+    static constexpr int size = kBlock * items;
+};
 #ifndef RAMA_RADIX_BITS
 #define RAMA_RADIX_BITS 8
 #endif
@@ -265,9 +267,9 @@ __global__ __launch_bounds__(kBlock) void k_rs_hist(const K *keys, uint32_t *his
     for (int k = threadIdx.x; k < kRadix; k += kBlock) h[k] = 0;
     __syncthreads();
     const uint32_t mask = (1u << bits) - 1u;
-    size_t base = (size_t)blockIdx.x * kSortTile + threadIdx.x;
+    size_t base = (size_t)blockIdx.x * SortTile<K>::size + threadIdx.x;
 #pragma unroll
-    for (int r = 0; r < kSortItems; ++r) {
+    for (int r = 0; r < SortTile<K>::items; ++r) {
         size_t idx = base + (size_t)r * kBlock;
         if (idx < n) atomicAdd(&h[(uint32_t)(keys[idx] >> shift) & mask], 1u);
     }
@@ -286,7 +288,7 @@ __device__ __forceinline__ uint64_t match_digit(uint32_t d, int bits, uint64_t v
     return m;
 }
 
-// One pass of the sort for one tile: (1) every wave ranks its 16x64 keys by digit with ballots,
+// One pass of the sort for one tile: (1) every wave ranks its items x 64 keys by digit with ballots,
 // (2) per-digit prefix over the four waves and over the digits gives each key its place in the
 // tile's digit-sorted order, (3) keys (and values) are staged in LDS in that order, (4) the tile
 // is written out linearly -- neighbouring lanes hold neighbouring keys of the same digit, so the
@@ -299,6 +301,8 @@ __global__ __launch_bounds__(kBlock) void k_rs_scatter(const K *kin, const V *vi
                                                        const uint32_t *offs, size_t n, int shift, int bits,
                                                        uint32_t nb)
 {
+    constexpr int kSortItems = SortTile<K>::items;
+    constexpr int kSortTile = SortTile<K>::size;
     __shared__ uint32_t whist[4][kRadix];
     __shared__ uint32_t gdelta[kRadix];
     __shared__ K skey[kSortTile];
@@ -421,7 +425,7 @@ rama_status radix_sort_impl(Ctx &ctx, K *ka, V *va, K *kb, V *vb, size_t n, int 
     *result_in_b = false;
     if (n <= 1 || total_bits <= 0) return RAMA_OK;
     if (n >= (size_t(1) << 32)) return fail(ctx, RAMA_ERR_CAPACITY, "radix sort: more than 2^32 keys");
-    const uint32_t nb = grid_for(n, kSortTile);
+    const uint32_t nb = grid_for(n, SortTile<K>::size);
     int passes = (total_bits + kRadixBits - 1) / kRadixBits;
     Buf<uint32_t> hist, offs;
     RAMA_TRY(hist.alloc(ctx, (size_t)kRadix * nb));
