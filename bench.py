@@ -55,6 +55,7 @@ def main():
     ap.add_argument("--workload", default="cfg5")
     ap.add_argument("--cpu-side", type=int, default=128, help="cube side of the oracle's timed sample (0 = skip)")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event timers")
+    ap.add_argument("--max-rounds", type=int, default=0, help="stop the solver after this many rounds (0 = run to the end)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain 1 GiB device copy three times (reference reading for rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE runs)")
@@ -64,13 +65,14 @@ def main():
         sys.exit(2)
 
     import torch
-    from paper_2109_01838_amd import Rama
+    from paper_2109_01838_amd import Rama, default_params
 
     g = make_workload(args.workload)
     n, m = g["n_nodes"], int(g["i"].size)
     dev = torch.device("cuda:0")
     i, j, c = (torch.as_tensor(g[k]).to(dev) for k in ("i", "j", "c"))
     rama = Rama("cuda:0")
+    params = default_params(max_rounds=args.max_rounds)
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB read + 1 GiB written per copy
         dst = torch.empty_like(src)
@@ -84,11 +86,11 @@ def main():
     # (two events per launch of one kernel: ~1 % overhead instead of ~15 % for all kernels).
     res = None
     for _ in range(args.warmup):
-        res = rama.solve(n, i, j, c)
+        res = rama.solve(n, i, j, c, params)
     kernels, dominant = None, None
     if not args.no_profile:
         rama.profile_enable(True)
-        rama.solve(n, i, j, c)
+        rama.solve(n, i, j, c, params)
         kernels = sorted(rama.profile_get(), key=lambda k: -k["ms"])
         rama.profile_enable(False)
         tot = sum(k["ms"] for k in kernels)
@@ -100,7 +102,7 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        res = rama.solve(n, i, j, c)
+        res = rama.solve(n, i, j, c, params)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms = 1e3 * dt / args.steps

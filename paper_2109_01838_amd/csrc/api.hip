@@ -82,6 +82,13 @@ rama_status solve_impl(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const i
     double t_cyc = 0, t_dual = 0, t_con = 0;
     rama_stats S;
     memset(&S, 0, sizeof S);
+    if (n == 0) {   // no nodes: nothing to label (edges would have been rejected as out of range)
+        if (m > 0) return fail(ctx, RAMA_ERR_BAD_GRAPH, "edges given for a graph without nodes");
+        if (primal) *primal = 0.0;
+        if (lower_bound) *lower_bound = 0.0;
+        if (stats) *stats = S;
+        return RAMA_OK;
+    }
     Graph g;
     RAMA_TRY(canonicalise(ctx, n, m, i, j, c, g));
     Buf<int32_t> f;
@@ -320,6 +327,12 @@ rama_status rama_contract(rama_ctx *ctx, int32_t n_nodes, int64_t n_edges, const
         (n_nodes > 0 && !mapping) || (n_edges > 0 && (!i_out || !j_out || !c_out)))
         return fail(*ctx, RAMA_ERR_INVALID_ARG, "rama_contract: bad arguments");
     auto body = [&]() -> rama_status {
+        if (n_nodes == 0) {
+            if (n_edges > 0) return fail(*ctx, RAMA_ERR_BAD_GRAPH, "edges given for a graph without nodes");
+            *n_nodes_out = 0;
+            *n_edges_out = 0;
+            return RAMA_OK;
+        }
         Graph g0, g;
         RAMA_TRY(canonicalise(*ctx, n_nodes, n_edges, i, j, c, g0));
         {

@@ -238,6 +238,7 @@ rama_status find_cycles(Ctx &ctx, const Graph &g, int max_len, bool count_only, 
     RAMA_TRY(read_back(ctx, &mp, ppos.get() + m, 4));
     RAMA_TRY(read_back(ctx, &mr, npos.get() + m, 4));
     if (mp == 0 || mr == 0) return RAMA_OK;
+    if ((uint64_t)2 * mp >= (uint64_t(1) << 31)) return fail(ctx, RAMA_ERR_CAPACITY, "positive adjacency reaches 2^31 entries");
     Buf<int32_t> pi, pj, ri, rj;
     Buf<uint32_t> lkey, lval;
     RAMA_TRY(pi.alloc(ctx, mp));

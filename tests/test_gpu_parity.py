@@ -284,6 +284,11 @@ def test_degenerate_inputs(rama):
     assert np_(r["labels"]).tolist() == [0, 1, 2] and r["primal"] == -3.0 and r["lower_bound"] == -3.0
     r = rama.solve(3, i, j, np.array([1.0, 2.0], np.float32))
     assert np_(r["labels"]).tolist() == [0, 0, 0] and r["primal"] == 0.0
+    # no nodes at all
+    r = rama.solve(0, e32, e32, ef)
+    assert r["labels"].numel() == 0 and r["primal"] == 0.0 and r["n_clusters"] == 0
+    r = rama.contract(0, e32, e32, ef)
+    assert r["n_nodes"] == 0 and r["i"].numel() == 0
     # only self-loops
     r = rama.solve(2, np.array([0, 1], np.int32), np.array([0, 1], np.int32), np.array([1.0, -1.0], np.float32))
     assert np_(r["labels"]).tolist() == [0, 1]
