@@ -203,13 +203,18 @@ struct InnerFlag {
 // part of the contraction -- so it is done exactly once: the packed pair of every edge is stored
 // (loops get an all-ones key), the scan and the compaction then stream over the stored keys.
 constexpr uint64_t kLoopKey = ~0ull;
+// raw[e] = (lo, hi-lo) in two 32-bit halves; *maxdiff collects the largest hi-lo
 __global__ __launch_bounds__(kBlock) void k_relabel_keys(size_t m, const int32_t *i, const int32_t *j,
-                                                         const int32_t *fmap, int nbits, uint64_t *raw)
+                                                         const int32_t *fmap, uint64_t *raw, uint32_t *maxdiff)
 {
     size_t e = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    if (e >= m) return;
-    int32_t a = fmap[i[e]], b = fmap[j[e]];
-    raw[e] = (a == b) ? kLoopKey : (((uint64_t)(uint32_t)min(a, b) << nbits) | (uint32_t)max(a, b));
+    uint32_t diff = 0;
+    if (e < m) {
+        int32_t a = fmap[i[e]], b = fmap[j[e]];
+        diff = (uint32_t)abs(a - b);
+        raw[e] = (a == b) ? kLoopKey : (((uint64_t)(uint32_t)min(a, b) << 32) | diff);
+    }
+    block_max_into(diff, maxdiff);
 }
 struct NotLoopKey {
     static constexpr int bytes = 8;   // bytes read per item
@@ -218,14 +223,14 @@ struct NotLoopKey {
     __device__ __forceinline__ uint32_t operator()(size_t e) const { return raw[e] != kLoopKey ? 1u : 0u; }
 };
 __global__ __launch_bounds__(kBlock) void k_compact_keys(size_t m, const uint64_t *raw, const float *c,
-                                                         const uint32_t *pos, uint64_t *key, uint32_t *val)
+                                                         const uint32_t *pos, int dbits, uint64_t *key, uint32_t *val)
 {
     size_t e = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (e >= m) return;
     uint64_t k = raw[e];
     if (k == kLoopKey) return;
     uint32_t p = pos[e];
-    key[p] = k;
+    key[p] = ((k >> 32) << dbits) | (k & 0xFFFFFFFFull);
     val[p] = __float_as_uint(c[e]);
 }
 
@@ -648,16 +653,19 @@ static rama_status contract_edges(Ctx &ctx, const Graph &g, const int32_t *fmap,
     const int nbits = bits_for((uint64_t)n_new);
     Buf<uint32_t> pos;
     Buf<uint64_t> raw;
-    RAMA_TRY(pos.alloc(ctx, m + 1));
+    RAMA_TRY(pos.alloc(ctx, m + 2));                       // pos[m] = kept edges, pos[m+1] = largest hi-lo
     RAMA_TRY(raw.alloc(ctx, m));
+    RAMA_TRY(fill<uint32_t>(ctx, pos.get() + m + 1, 0u, 1));
     {
         ProfScope ps_(ctx, "k_relabel_keys", (double)(m * 24));
-        k_relabel_keys<<<grid_for(m), kBlock, 0, ctx.stream>>>(m, g.i.get(), g.j.get(), fmap, nbits, raw.get());
+        k_relabel_keys<<<grid_for(m), kBlock, 0, ctx.stream>>>(m, g.i.get(), g.j.get(), fmap, raw.get(), pos.get() + m + 1);
     }
     LAUNCH_TRY(ctx, "relabel_keys");
     RAMA_TRY((exclusive_scan<uint32_t>(ctx, NotLoopKey{raw.get()}, pos.get(), m)));
-    uint32_t kept = 0;
-    RAMA_TRY(read_back(ctx, &kept, pos.get() + m, 4));
+    uint32_t tail[2] = {0, 0};
+    RAMA_TRY(read_back(ctx, tail, pos.get() + m, 8));
+    const uint32_t kept = tail[0];
+    const int dbits = bits_for((uint64_t)tail[1] + 1);
     if (kept == 0) {
         RAMA_TRY(out.i.alloc(ctx, 1));
         RAMA_TRY(out.j.alloc(ctx, 1));
@@ -670,12 +678,13 @@ static rama_status contract_edges(Ctx &ctx, const Graph &g, const int32_t *fmap,
     RAMA_TRY(val.alloc(ctx, kept));
     {
         ProfScope ps_(ctx, "k_compact_keys", (double)(m * 16 + (size_t)kept * 12));
-        k_compact_keys<<<grid_for(m), kBlock, 0, ctx.stream>>>(m, raw.get(), g.c.get(), pos.get(), key.get(), val.get());
+        k_compact_keys<<<grid_for(m), kBlock, 0, ctx.stream>>>(m, raw.get(), g.c.get(), pos.get(), dbits, key.get(),
+                                                               val.get());
     }
     LAUNCH_TRY(ctx, "compact_keys");
     pos.reset();
     raw.reset();
-    RAMA_TRY((radix_sort_pairs<uint64_t, uint32_t>(ctx, key, val, kept, 2 * nbits)));
+    RAMA_TRY((radix_sort_pairs<uint64_t, uint32_t>(ctx, key, val, kept, nbits + dbits)));
     Buf<uint32_t> opos;
     RAMA_TRY(opos.alloc(ctx, (size_t)kept + 1));
     RAMA_TRY((exclusive_scan<uint32_t>(ctx, HeadFlag{key.get()}, opos.get(), (size_t)kept)));
@@ -686,7 +695,7 @@ static rama_status contract_edges(Ctx &ctx, const Graph &g, const int32_t *fmap,
     RAMA_TRY(out.c.alloc(ctx, uniq));
     {
         ProfScope ps_(ctx, "k_reduce_runs", (double)((size_t)kept * 16 + (size_t)uniq * 12));
-        k_reduce_runs<<<grid_for(kept), kBlock, 0, ctx.stream>>>(kept, key.get(), val.get(), opos.get(), nbits, out.i.get(),
+        k_reduce_runs<<<grid_for(kept), kBlock, 0, ctx.stream>>>(kept, key.get(), val.get(), opos.get(), dbits, out.i.get(),
                                                             out.j.get(), out.c.get());
     }
     LAUNCH_TRY(ctx, "reduce_runs");

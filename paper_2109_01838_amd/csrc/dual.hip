@@ -171,18 +171,8 @@ __global__ __launch_bounds__(kBlock) void k_merge_edges(size_t m, const int32_t 
 // longest row of the upper CSR (bounds the in-row distance between two edges of one row)
 __global__ __launch_bounds__(kBlock) void k_max_row(int32_t n, const int32_t *rowptr, uint32_t *out)
 {
-    __shared__ uint32_t wmax[4];
     int32_t v = blockIdx.x * kBlock + threadIdx.x;
-    uint32_t len = v < n ? (uint32_t)(rowptr[v + 1] - rowptr[v]) : 0u;
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) len = max(len, (uint32_t)__shfl_xor((int)len, off, 64));
-    if (lane_id() == 0) wmax[threadIdx.x >> 6] = len;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        len = max(max(wmax[0], wmax[1]), max(wmax[2], wmax[3]));
-        // the stored maximum only grows, so a stale read can only cause a redundant atomic
-        if (len > *(volatile uint32_t *)out) atomicMax(out, len);
-    }
+    block_max_into(v < n ? (uint32_t)(rowptr[v + 1] - rowptr[v]) : 0u, out);
 }
 
 // A triangle u<v<w is keyed by (position e0 of edge (u,v), distance e1-e0 to edge (u,w) in the

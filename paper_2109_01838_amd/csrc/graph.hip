@@ -6,22 +6,30 @@ namespace rama {
 
 namespace {
 
-// flags[0]: endpoint out of range or non-finite cost; flags[1]: list is not canonical
+// flags[0]: endpoint out of range or non-finite cost; flags[1]: list is not canonical;
+// flags[2]: largest |i-j| of a valid edge
 __global__ __launch_bounds__(kBlock) void k_validate(int32_t n, size_t m, const int32_t *i, const int32_t *j,
                                                      const float *c, int32_t *flags)
 {
     size_t e = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    if (e >= m) return;
-    int32_t a = i[e], b = j[e];
-    float w = c[e];
-    bool bad = a < 0 || a >= n || b < 0 || b >= n || !(fabsf(w) <= 3.402823466e+38f);
-    if (bad) { flags[0] = 1; return; }
-    bool canon = a < b;
-    if (canon && e > 0) {
-        int32_t pa = i[e - 1], pb = j[e - 1];
-        canon = pa < a || (pa == a && pb < b);
+    uint32_t diff = 0;
+    if (e < m) {
+        int32_t a = i[e], b = j[e];
+        float w = c[e];
+        bool bad = a < 0 || a >= n || b < 0 || b >= n || !(fabsf(w) <= 3.402823466e+38f);
+        if (bad) {
+            flags[0] = 1;
+        } else {
+            diff = (uint32_t)abs(a - b);
+            bool canon = a < b;
+            if (canon && e > 0) {
+                int32_t pa = i[e - 1], pb = j[e - 1];
+                canon = pa < a || (pa == a && pb < b);
+            }
+            if (!canon) flags[1] = 1;
+        }
     }
-    if (!canon) flags[1] = 1;
+    block_max_into(diff, (uint32_t *)&flags[2]);
 }
 
 struct NotLoop {
@@ -32,7 +40,7 @@ struct NotLoop {
 };
 
 __global__ __launch_bounds__(kBlock) void k_pack_edges(size_t m, const int32_t *i, const int32_t *j, const float *c,
-                                                       const uint32_t *pos, int nbits, uint64_t *key, uint32_t *val)
+                                                       const uint32_t *pos, int dbits, uint64_t *key, uint32_t *val)
 {
     size_t e = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (e >= m) return;
@@ -40,7 +48,7 @@ __global__ __launch_bounds__(kBlock) void k_pack_edges(size_t m, const int32_t *
     if (a == b) return;
     uint32_t lo = (uint32_t)min(a, b), hi = (uint32_t)max(a, b);
     uint32_t p = pos[e];
-    key[p] = ((uint64_t)lo << nbits) | hi;
+    key[p] = edge_key(lo, hi, dbits);
     val[p] = __float_as_uint(c[e]);
 }
 
@@ -66,14 +74,14 @@ rama_status canonicalise(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const
         return RAMA_OK;
     }
     Buf<int32_t> flags;
-    RAMA_TRY(flags.alloc(ctx, 2));
-    RAMA_TRY(fill<int32_t>(ctx, flags.get(), 0, 2));
+    RAMA_TRY(flags.alloc(ctx, 3));
+    RAMA_TRY(fill<int32_t>(ctx, flags.get(), 0, 3));
     {
         ProfScope ps_(ctx, "k_validate", (double)((size_t)m * 12));
         k_validate<<<grid_for(m), kBlock, 0, ctx.stream>>>(n, (size_t)m, i, j, c, flags.get());
     }
     LAUNCH_TRY(ctx, "validate");
-    int32_t hf[2];
+    int32_t hf[3];
     RAMA_TRY(read_back(ctx, hf, flags.get(), sizeof hf));
     if (hf[0]) return fail(ctx, RAMA_ERR_BAD_GRAPH, "edge endpoint outside [0,n_nodes) or non-finite cost");
     if (!hf[1]) {  // already canonical: plain copy
@@ -86,7 +94,7 @@ rama_status canonicalise(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const
         out.m = m;
         return RAMA_OK;
     }
-    const int nbits = bits_for((uint64_t)n);
+    const int nbits = bits_for((uint64_t)n), dbits = bits_for((uint64_t)hf[2] + 1);
     Buf<uint32_t> pos;
     RAMA_TRY(pos.alloc(ctx, (size_t)m + 1));
     RAMA_TRY((exclusive_scan<uint32_t>(ctx, NotLoop{i, j}, pos.get(), (size_t)m)));
@@ -104,11 +112,11 @@ rama_status canonicalise(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const
     RAMA_TRY(val.alloc(ctx, kept));
     {
         ProfScope ps_(ctx, "k_pack_edges", (double)((size_t)m * 16 + (size_t)kept * 12));
-        k_pack_edges<<<grid_for(m), kBlock, 0, ctx.stream>>>((size_t)m, i, j, c, pos.get(), nbits, key.get(), val.get());
+        k_pack_edges<<<grid_for(m), kBlock, 0, ctx.stream>>>((size_t)m, i, j, c, pos.get(), dbits, key.get(), val.get());
     }
     LAUNCH_TRY(ctx, "pack_edges");
     pos.reset();
-    RAMA_TRY((radix_sort_pairs<uint64_t, uint32_t>(ctx, key, val, kept, 2 * nbits)));
+    RAMA_TRY((radix_sort_pairs<uint64_t, uint32_t>(ctx, key, val, kept, nbits + dbits)));
     Buf<uint32_t> opos;
     RAMA_TRY(opos.alloc(ctx, (size_t)kept + 1));
     RAMA_TRY((exclusive_scan<uint32_t>(ctx, HeadFlag{key.get()}, opos.get(), (size_t)kept)));
@@ -119,7 +127,7 @@ rama_status canonicalise(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const
     RAMA_TRY(out.c.alloc(ctx, uniq));
     {
         ProfScope ps_(ctx, "k_reduce_runs", (double)((size_t)kept * 16 + (size_t)uniq * 12));
-        k_reduce_runs<<<grid_for(kept), kBlock, 0, ctx.stream>>>(kept, key.get(), val.get(), opos.get(), nbits, out.i.get(),
+        k_reduce_runs<<<grid_for(kept), kBlock, 0, ctx.stream>>>(kept, key.get(), val.get(), opos.get(), dbits, out.i.get(),
                                                             out.j.get(), out.c.get());
     }
     LAUNCH_TRY(ctx, "reduce_runs");

@@ -572,10 +572,30 @@ rama_status row_bounds(Ctx &ctx, const K *keys, size_t m, int64_t n, P *ptr)
     return RAMA_OK;
 }
 
+// Edge keys.  An undirected edge (lo,hi), lo<hi, sorts as the pair (lo, hi-lo): same order as
+// (lo,hi), but the second field only needs bits(max hi-lo) bits -- on grid-like graphs that saves
+// a radix pass.  key = lo << dbits | (hi-lo).
+__device__ __forceinline__ uint64_t edge_key(uint32_t lo, uint32_t hi, int dbits) { return ((uint64_t)lo << dbits) | (hi - lo); }
+
+// maximum over the workgroup folded into *out (which only ever grows, so a stale read can only
+// cause a redundant atomic)
+__device__ __forceinline__ void block_max_into(uint32_t v, uint32_t *out)
+{
+    __shared__ uint32_t wmax[4];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = max(v, (uint32_t)__shfl_xor((int)v, off, 64));
+    if (lane_id() == 0) wmax[threadIdx.x >> 6] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        v = max(max(wmax[0], wmax[1]), max(wmax[2], wmax[3]));
+        if (v > *(volatile uint32_t *)out) atomicMax(out, v);
+    }
+}
+
 // Sums runs of equal keys in order of appearance (one thread per run, sequential adds) and
 // writes endpoint pair + cost of run r at position pos[first element of r].
 static __global__ __launch_bounds__(kBlock) void k_reduce_runs(size_t m, const uint64_t *key, const uint32_t *val,
-                                                        const uint32_t *pos, int nbits, int32_t *io, int32_t *jo,
+                                                        const uint32_t *pos, int dbits, int32_t *io, int32_t *jo,
                                                         float *co)
 {
     size_t e = (size_t)blockIdx.x * kBlock + threadIdx.x;
@@ -585,8 +605,9 @@ static __global__ __launch_bounds__(kBlock) void k_reduce_runs(size_t m, const u
     float acc = __uint_as_float(val[e]);
     for (size_t f = e + 1; f < m && key[f] == k; ++f) acc = acc + __uint_as_float(val[f]);
     uint32_t p = pos[e];
-    io[p] = (int32_t)(k >> nbits);
-    jo[p] = (int32_t)(k & ((1ull << nbits) - 1ull));
+    const uint32_t lo = (uint32_t)(k >> dbits);
+    io[p] = (int32_t)lo;
+    jo[p] = (int32_t)(lo + (uint32_t)(k & ((1ull << dbits) - 1ull)));
     co[p] = acc;
 }
 
