@@ -23,6 +23,7 @@ _LIBS = {"f32": os.path.join(_HERE, "librama_oracle_f32.so"),
 _CFLAGS = ["-O2", "-ffp-contract=off", "-fno-fast-math", "-std=c11", "-shared", "-fPIC", "-Wall", "-Wextra"]
 
 OK, ERR_ARG, ERR_GRAPH, ERR_CAP, ERR_OOM = 0, -1, -2, -3, -4
+MAX_CYCLE_LEN = 7   # longest cycle the C source separates
 
 
 def build(force=True):
@@ -88,19 +89,32 @@ class Oracle:
         return io[:k].copy(), jo[:k].copy(), co[:k].copy()
 
     # -- a1 -----------------------------------------------------------------------------------
-    def find_conflicted_cycles(self, n, i, j, c, max_cycle_len=5):
+    @staticmethod
+    def _lists(cycles):
+        """list of [n_L, L] arrays, L = 3.. -> (max_cycle_len, arrays, pointer array, count array)"""
+        arrs = [_i32(x).reshape(-1, k + 3) for k, x in enumerate(cycles)]
+        while len(arrs) < 1:
+            arrs.append(np.empty((0, 3), np.int32))
+        ptrs = (C.c_void_p * len(arrs))(*[a.ctypes.data for a in arrs])
+        cnts = (C.c_int64 * len(arrs))(*[a.shape[0] for a in arrs])
+        return len(arrs) + 2, arrs, ptrs, cnts
+
+    def find_conflicted_cycles(self, n, i, j, c, max_cycle_len=5, shortest_only=False):
+        """Returns max_cycle_len-2 arrays: entry L-3 is [n_L, L], the conflicted L-cycles."""
         i, j, c = _i32(i), _i32(j), _f32(c)
-        cnt = (C.c_int64 * 3)()
+        nl = max_cycle_len - 2
+        cnt = (C.c_int64 * max(nl, 1))()
         st = self.lib.rama_oracle_find_conflicted_cycles(
             C.c_int32(n), C.c_int64(i.size), _ptr(i), _ptr(j), _ptr(c), C.c_int32(max_cycle_len),
-            C.c_int64(0), C.c_int64(0), C.c_int64(0), None, None, None, cnt)
+            C.c_int32(int(shortest_only)), None, None, cnt)
         if st not in (OK, ERR_CAP):
             raise OracleError(st, "find_conflicted_cycles(count)")
-        outs = [np.empty((cnt[k], k + 3), np.int32) for k in range(3)]
+        outs = [np.empty((cnt[k], k + 3), np.int32) for k in range(nl)]
+        ptrs = (C.c_void_p * nl)(*[o.ctypes.data for o in outs])
+        cap = (C.c_int64 * nl)(*[cnt[k] for k in range(nl)])
         st = self.lib.rama_oracle_find_conflicted_cycles(
             C.c_int32(n), C.c_int64(i.size), _ptr(i), _ptr(j), _ptr(c), C.c_int32(max_cycle_len),
-            C.c_int64(cnt[0]), C.c_int64(cnt[1]), C.c_int64(cnt[2]),
-            _ptr(outs[0]), _ptr(outs[1]), _ptr(outs[2]), cnt)
+            C.c_int32(int(shortest_only)), cap, ptrs, cnt)
         if st != OK:
             raise OracleError(st, "find_conflicted_cycles")
         return outs
@@ -109,15 +123,14 @@ class Oracle:
     def triangulate(self, n, i, j, c, cycles):
         """Input must be canonical.  Returns (ia, ja, ca, tri_nodes[T,3], tri_edge[T,3])."""
         i, j, c = _i32(i), _i32(j), _f32(c)
-        c3, c4, c5 = (_i32(x).reshape(-1, k + 3) for k, x in enumerate(cycles))
-        n3, n4, n5 = c3.shape[0], c4.shape[0], c5.shape[0]
-        room, tmax = i.size + n4 + 2 * n5, n3 + 2 * n4 + 3 * n5
+        lmax, arrs, ptrs, cnts = self._lists(cycles)
+        room = i.size + sum(k * a.shape[0] for k, a in enumerate(arrs))
+        tmax = sum((k + 1) * a.shape[0] for k, a in enumerate(arrs))
         ia, ja, ca = np.empty(room, np.int32), np.empty(room, np.int32), np.empty(room, np.float32)
         tn, te = np.empty((tmax, 3), np.int32), np.empty((tmax, 3), np.int32)
         ma, nt = C.c_int64(0), C.c_int64(0)
         st = self.lib.rama_oracle_triangulate(
-            C.c_int32(n), C.c_int64(i.size), _ptr(i), _ptr(j), _ptr(c),
-            _ptr(c3), C.c_int64(n3), _ptr(c4), C.c_int64(n4), _ptr(c5), C.c_int64(n5),
+            C.c_int32(n), C.c_int64(i.size), _ptr(i), _ptr(j), _ptr(c), C.c_int32(lmax), ptrs, cnts,
             _ptr(ia), _ptr(ja), _ptr(ca), C.byref(ma), _ptr(tn), _ptr(te), C.byref(nt))
         if st != OK:
             raise OracleError(st, "triangulate")
@@ -148,15 +161,13 @@ class Oracle:
 
     def message_passing(self, n, i, j, c, cycles, k_iters, trace=False):
         i, j, c = _i32(i), _i32(j), _f32(c)
-        c3, c4, c5 = (_i32(x).reshape(-1, k + 3) for k, x in enumerate(cycles))
-        n3, n4, n5 = c3.shape[0], c4.shape[0], c5.shape[0]
-        room = i.size + n4 + 2 * n5
+        lmax, arrs, ptrs, cnts = self._lists(cycles)
+        room = i.size + sum(k * a.shape[0] for k, a in enumerate(arrs))
         io, jo, co = np.empty(room, np.int32), np.empty(room, np.int32), np.empty(room, np.float32)
         mo, lb = C.c_int64(0), C.c_double(0.0)
         tr = np.zeros(k_iters + 1, np.float64) if trace else None
         st = self.lib.rama_oracle_message_passing(
-            C.c_int32(n), C.c_int64(i.size), _ptr(i), _ptr(j), _ptr(c),
-            _ptr(c3), C.c_int64(n3), _ptr(c4), C.c_int64(n4), _ptr(c5), C.c_int64(n5),
+            C.c_int32(n), C.c_int64(i.size), _ptr(i), _ptr(j), _ptr(c), C.c_int32(lmax), ptrs, cnts,
             C.c_int32(k_iters), C.c_int64(room), _ptr(io), _ptr(jo), _ptr(co), C.byref(mo), C.byref(lb), _ptr(tr))
         if st != OK:
             raise OracleError(st, "message_passing")
@@ -232,19 +243,20 @@ class Oracle:
         return self.lib.rama_oracle_multicut_cost(C.c_int64(i.size), _ptr(i), _ptr(j), _ptr(c), _ptr(labels))
 
     def solve(self, n, i, j, c, max_cycle_len_first=5, max_cycle_len_later=3, mp_iters_first=10,
-              mp_iters_later=5, matching_rounds_cap=32, tau=0.0, max_rounds=0, forest_ratio=0.1):
+              mp_iters_later=5, matching_rounds_cap=32, tau=0.0, max_rounds=0, forest_ratio=0.1,
+              shortest_only=False):
         i, j, c = _i32(i), _i32(j), _f32(c)
         labels = np.empty(n, np.int32)
         primal, lb = C.c_double(0.0), C.c_double(0.0)
-        stats = (C.c_int64 * 8)()
+        stats = (C.c_int64 * 16)()
         st = self.lib.rama_oracle_solve(
             C.c_int32(n), C.c_int64(i.size), _ptr(i), _ptr(j), _ptr(c),
-            C.c_int32(max_cycle_len_first), C.c_int32(max_cycle_len_later),
+            C.c_int32(max_cycle_len_first), C.c_int32(max_cycle_len_later), C.c_int32(int(shortest_only)),
             C.c_int32(mp_iters_first), C.c_int32(mp_iters_later),
             C.c_int32(matching_rounds_cap), C.c_float(tau), C.c_float(forest_ratio), C.c_int32(max_rounds),
             _ptr(labels), C.byref(primal), C.byref(lb), stats)
         if st != OK:
             raise OracleError(st, "solve")
         return dict(labels=labels, primal=primal.value, lower_bound=lb.value, rounds=int(stats[0]),
-                    n_clusters=int(stats[1]), n_cycles_first=[int(stats[2]), int(stats[3]), int(stats[4])],
-                    n_edges_aug_first=int(stats[6]), n_edges_final=int(stats[7]))
+                    n_clusters=int(stats[1]), n_cycles_first=[int(stats[5 + q]) for q in range(MAX_CYCLE_LEN - 2)],
+                    n_edges_aug_first=int(stats[3]), n_edges_final=int(stats[4]))

@@ -17,7 +17,8 @@
  * -ffp-contract=off so that no multiply-add is fused.
  *
  * Pins (tests/test_oracle_*.py): the contraction worked example of Fig. 2,
- * brute-force optimal multicuts, brute-force cycle enumeration, dense K^T A K,
+ * brute-force optimal multicuts, brute-force cycle enumeration (lengths 3..7; the
+ * shortest-only filter against that set and against scipy's hop distances), dense K^T A K,
  * scipy connected components / duplicate summation, closed-form min-marginals,
  * monotone lower bound, zero min-marginals after a triangle update.
  * Parity unpinned: the *choice* of triangulation (fan from the repulsive edge's
@@ -45,6 +46,9 @@ typedef ORACLE_REAL real;
 #define ERR_GRAPH (-2)
 #define ERR_CAP (-3)
 #define ERR_OOM (-4)
+
+#define MAX_CYCLE_LEN 7            /* longest conflicted cycle the oracle separates */
+#define N_LISTS (MAX_CYCLE_LEN - 2) /* one list per length 3..MAX_CYCLE_LEN; list L-3 holds the L-cycles */
 
 /* ------------------------------------------------------------------------------------------ */
 /* small helpers                                                                              */
@@ -158,11 +162,18 @@ static int posadj_has(const posadj *a, int32_t u, int32_t v)
 
 /* ------------------------------------------------------------------------------------------ */
 /* Step a1: conflicted cycles (Sec. 3.2.2 "Conflicted cycles" definition; Lemma on the search */
-/* per repulsive edge; appendix Alg. "Parallel Conf. 5-Cycles"; maximum length 5).            */
+/* per repulsive edge; appendix Alg. "Parallel Conf. 5-Cycles"; the paper stops at length 5    */
+/* and names longer cycles as future work, Sec. 5 -- the definition is the same for any L).   */
 /* Plain definition: every simple cycle of length L in {3,..,Lmax} with exactly one edge of   */
 /* E- and L-1 edges of E+.  For the repulsive edge (v0,v_{L-1}), v0<v_{L-1}, that is every    */
 /* simple path v0,v1,..,v_{L-1} along E+.  Depth-first enumeration, nothing pruned.           */
 /* Stored as the tuple (v0,..,v_{L-1}); lists ordered by (v0, v_{L-1}, v1, .., v_{L-2}).      */
+/*                                                                                            */
+/* shortest_only (the separation Lemma read literally: per repulsive edge, the shortest paths */
+/* w.r.t. hop distance in (V,E+)): with d = hop distance between the endpoints of the         */
+/* repulsive edge in (V,E+), only its cycles of length d+1 are kept (all of them), and none   */
+/* if d+1 > Lmax.  d comes from a breadth-first search that is independent of the             */
+/* enumeration above.                                                                         */
 /* ------------------------------------------------------------------------------------------ */
 typedef struct {
     int L;
@@ -194,13 +205,37 @@ static void cycles_extend(const posadj *a, int32_t *path, int len, int L, int32_
     }
 }
 
+/* hop distance src -> dst in (V,E+) by breadth-first search, given up beyond `limit` hops
+ * (returns limit+1 then).  seen[] holds the id of the last search that reached a node. */
+static int hop_distance(const posadj *a, int32_t src, int32_t dst, int limit, int64_t search_id,
+                        int64_t *seen, int32_t *queue, int32_t *depth)
+{
+    int64_t head = 0, tail = 0;
+    queue[tail] = src; depth[tail] = 0; ++tail;
+    seen[src] = search_id;
+    while (head < tail) {
+        int32_t u = queue[head];
+        int d = depth[head];
+        ++head;
+        if (u == dst) return d;
+        if (d == limit) continue;
+        for (int64_t p = a->ptr[u]; p < a->ptr[u + 1]; ++p) {
+            int32_t w = a->nb[p];
+            if (seen[w] == search_id) continue;
+            seen[w] = search_id;
+            queue[tail] = w; depth[tail] = d + 1; ++tail;
+        }
+    }
+    return limit + 1;
+}
+
 static int g_cyc_L;
 static int cmp_cycle(const void *pa, const void *pb)
 {
     const int32_t *x = (const int32_t *)pa, *y = (const int32_t *)pb;
     const int L = g_cyc_L;
     /* repulsive edge first, then the path: v0, v_{L-1}, v1, .., v_{L-2} */
-    int order[5];
+    int order[MAX_CYCLE_LEN];
     order[0] = 0; order[1] = L - 1;
     for (int q = 1; q <= L - 2; ++q) order[q + 1] = q;
     for (int q = 0; q < L; ++q) {
@@ -210,11 +245,13 @@ static int cmp_cycle(const void *pa, const void *pb)
     return 0;
 }
 
+/* cap[L-3] / cycles[L-3] / n_out[L-3] belong to the L-cycles, L = 3..max_cycle_len; cap and
+ * cycles may be NULL (count only).  n_out gets max_cycle_len-2 entries. */
 int rama_oracle_find_conflicted_cycles(int32_t n, int64_t m, const int32_t *i, const int32_t *j, const float *c,
-                                       int32_t max_cycle_len, int64_t cap3, int64_t cap4, int64_t cap5,
-                                       int32_t *cycles3, int32_t *cycles4, int32_t *cycles5, int64_t *n_out)
+                                       int32_t max_cycle_len, int32_t shortest_only, const int64_t *cap,
+                                       int32_t *const *cycles, int64_t *n_out)
 {
-    if (!n_out || max_cycle_len < 3 || max_cycle_len > 5) return ERR_ARG;
+    if (!n_out || max_cycle_len < 3 || max_cycle_len > MAX_CYCLE_LEN) return ERR_ARG;
     int32_t *ci = (int32_t *)xmalloc((size_t)m * 4), *cj = (int32_t *)xmalloc((size_t)m * 4);
     float *cc = (float *)xmalloc((size_t)m * 4);
     int64_t mc = 0;
@@ -224,24 +261,34 @@ int rama_oracle_find_conflicted_cycles(int32_t n, int64_t m, const int32_t *i, c
     posadj a;
     st = posadj_build(&a, n, mc, ci, cj, cc);
     if (st != OK) return st;
-    int32_t *outs[3] = { cycles3, cycles4, cycles5 };
-    int64_t caps[3] = { cap3, cap4, cap5 };
+    int *dist = NULL;                                    /* per edge: hop distance of its endpoints in (V,E+) */
+    if (shortest_only) {
+        dist = (int *)xmalloc((size_t)mc * sizeof(int));
+        int64_t *seen = (int64_t *)xmalloc(((size_t)n + 1) * 8);
+        int32_t *queue = (int32_t *)xmalloc(((size_t)n + 1) * 4), *depth = (int32_t *)xmalloc(((size_t)n + 1) * 4);
+        if (!dist || !seen || !queue || !depth) return ERR_OOM;
+        for (int32_t v = 0; v < n; ++v) seen[v] = -1;
+        for (int64_t e = 0; e < mc; ++e)
+            if (cc[e] < 0.0f) dist[e] = hop_distance(&a, ci[e], cj[e], max_cycle_len - 1, e, seen, queue, depth);
+        free(seen); free(queue); free(depth);
+    }
     int over = 0;
-    for (int L = 3; L <= 5; ++L) {
-        cycle_sink s = { L, (L <= max_cycle_len && outs[L - 3]) ? caps[L - 3] : 0, 0, outs[L - 3] };
-        if (L <= max_cycle_len) {
-            for (int64_t e = 0; e < mc; ++e) {
-                if (!(cc[e] < 0.0f)) continue;           /* e in E- */
-                int32_t path[5];
-                path[0] = ci[e];
-                cycles_extend(&a, path, 1, L, cj[e], &s);
-            }
-            if (s.cnt > s.cap) over = 1;
-            else if (s.cnt > 1) { g_cyc_L = L; qsort(s.out, (size_t)s.cnt, (size_t)L * 4, cmp_cycle); }
+    for (int L = 3; L <= max_cycle_len; ++L) {
+        int32_t *out = cycles ? cycles[L - 3] : NULL;
+        cycle_sink s = { L, (out && cap) ? cap[L - 3] : 0, 0, out };
+        for (int64_t e = 0; e < mc; ++e) {
+            if (!(cc[e] < 0.0f)) continue;               /* e in E- */
+            if (shortest_only && dist[e] != L - 1) continue;
+            int32_t path[MAX_CYCLE_LEN];
+            path[0] = ci[e];
+            cycles_extend(&a, path, 1, L, cj[e], &s);
         }
+        if (s.cnt > s.cap) over = 1;
+        else if (s.cnt > 1) { g_cyc_L = L; qsort(s.out, (size_t)s.cnt, (size_t)L * 4, cmp_cycle); }
         n_out[L - 3] = s.cnt;
     }
     posadj_free(&a);
+    free(dist);
     free(ci); free(cj); free(cc);
     return over ? ERR_CAP : OK;
 }
@@ -252,8 +299,9 @@ int rama_oracle_find_conflicted_cycles(int32_t n, int64_t m, const int32_t *i, c
 /* (v0,v_m), m=2..L-2.  A chord that is not an edge yet joins the edge set with cost 0.  The  */
 /* augmented edge list stays canonical; T is the sorted set of node triples u<v<w;            */
 /* tri_edge[3t+s] is the edge id of slot s, slots ordered (u,v),(u,w),(v,w).                  */
-/* Input must be canonical.  ia/ja/ca need room for m + n4 + 2*n5 edges, tri_* for            */
-/* n3+2*n4+3*n5 triangles.                                                                     */
+/* Input must be canonical.  cycles[L-3] holds the n_cycles[L-3] cycles of length L,           */
+/* L = 3..max_cycle_len.  ia/ja/ca need room for m + sum (L-3)*n_L edges, tri_* for            */
+/* sum (L-2)*n_L triangles.                                                                    */
 /* ------------------------------------------------------------------------------------------ */
 typedef struct { int32_t u, v, w; } tri3;
 static int cmp_tri3(const void *pa, const void *pb)
@@ -273,23 +321,24 @@ static void sort3(int32_t *p)
 }
 
 int rama_oracle_triangulate(int32_t n, int64_t m, const int32_t *i, const int32_t *j, const float *c,
-                            const int32_t *cycles3, int64_t n3, const int32_t *cycles4, int64_t n4,
-                            const int32_t *cycles5, int64_t n5,
+                            int32_t max_cycle_len, const int32_t *const *cycles, const int64_t *n_cycles,
                             int32_t *ia, int32_t *ja, float *ca, int64_t *m_aug,
                             int32_t *tri_nodes, int32_t *tri_edge, int64_t *n_tri)
 {
-    const int32_t *cyc[3] = { cycles3, cycles4, cycles5 };
-    const int64_t cn[3] = { n3, n4, n5 };
-    if (!m_aug || !n_tri || n3 < 0 || n4 < 0 || n5 < 0) return ERR_ARG;
+    if (!m_aug || !n_tri || max_cycle_len < 3 || max_cycle_len > MAX_CYCLE_LEN || !cycles || !n_cycles) return ERR_ARG;
     /* chords */
-    int64_t n_chord_max = n4 + 2 * n5, nch = 0;
+    int64_t n_chord_max = 0, nch = 0, n_tri_max = 0, nt = 0;
+    for (int L = 3; L <= max_cycle_len; ++L) {
+        if (n_cycles[L - 3] < 0) return ERR_ARG;
+        n_chord_max += (L - 3) * n_cycles[L - 3];
+        n_tri_max += (L - 2) * n_cycles[L - 3];
+    }
     keyed_edge *ch = (keyed_edge *)xmalloc((size_t)n_chord_max * sizeof *ch);
-    int64_t n_tri_max = n3 + 2 * n4 + 3 * n5, nt = 0;
     tri3 *tr = (tri3 *)xmalloc((size_t)n_tri_max * sizeof *tr);
     if (!ch || !tr) return ERR_OOM;
-    for (int L = 3; L <= 5; ++L) {
-        for (int64_t q = 0; q < cn[L - 3]; ++q) {
-            const int32_t *v = cyc[L - 3] + q * L;
+    for (int L = 3; L <= max_cycle_len; ++L) {
+        for (int64_t q = 0; q < n_cycles[L - 3]; ++q) {
+            const int32_t *v = cycles[L - 3] + q * L;
             for (int s = 0; s < L; ++s) {
                 if (v[s] < 0 || v[s] >= n) { free(ch); free(tr); return ERR_GRAPH; }
                 for (int s2 = 0; s2 < s; ++s2) if (v[s2] == v[s]) { free(ch); free(tr); return ERR_GRAPH; }
@@ -506,25 +555,30 @@ double rama_oracle_lower_bound(int64_t m, const float *ce, int64_t T, const floa
  * reparametrised costs, LB after the k-th iteration and optionally LB after every iteration
  * (lb_trace[0] is LB before the first). */
 int rama_oracle_message_passing(int32_t n, int64_t m, const int32_t *i, const int32_t *j, const float *c,
-                                const int32_t *cycles3, int64_t n3, const int32_t *cycles4, int64_t n4,
-                                const int32_t *cycles5, int64_t n5, int32_t k_iters, int64_t edge_cap,
+                                int32_t max_cycle_len, const int32_t *const *cycles, const int64_t *n_cycles,
+                                int32_t k_iters, int64_t edge_cap,
                                 int32_t *io, int32_t *jo, float *co, int64_t *m_out,
                                 double *lower_bound, double *lb_trace)
 {
-    if (k_iters < 0 || !m_out) return ERR_ARG;
+    if (k_iters < 0 || !m_out || max_cycle_len < 3 || max_cycle_len > MAX_CYCLE_LEN || !cycles || !n_cycles) return ERR_ARG;
     int32_t *ci = (int32_t *)xmalloc((size_t)m * 4), *cj = (int32_t *)xmalloc((size_t)m * 4);
     float *cc = (float *)xmalloc((size_t)m * 4);
     if (!ci || !cj || !cc) return ERR_OOM;
     int64_t mc = 0;
     int st = rama_oracle_canonicalise(n, m, i, j, c, ci, cj, cc, &mc);
     if (st != OK) { free(ci); free(cj); free(cc); return st; }
-    int64_t room = mc + n4 + 2 * n5, Tmax = n3 + 2 * n4 + 3 * n5;
+    int64_t room = mc, Tmax = 0;
+    for (int L = 3; L <= max_cycle_len; ++L) {
+        if (n_cycles[L - 3] < 0) { free(ci); free(cj); free(cc); return ERR_ARG; }
+        room += (L - 3) * n_cycles[L - 3];
+        Tmax += (L - 2) * n_cycles[L - 3];
+    }
     int32_t *ia = (int32_t *)xmalloc((size_t)room * 4), *ja = (int32_t *)xmalloc((size_t)room * 4);
     float *ca = (float *)xmalloc((size_t)room * 4);
     int32_t *tn = (int32_t *)xmalloc((size_t)Tmax * 12), *te = (int32_t *)xmalloc((size_t)Tmax * 12);
     if (!ia || !ja || !ca || !tn || !te) return ERR_OOM;
     int64_t ma = 0, T = 0;
-    st = rama_oracle_triangulate(n, mc, ci, cj, cc, cycles3, n3, cycles4, n4, cycles5, n5, ia, ja, ca, &ma, tn, te, &T);
+    st = rama_oracle_triangulate(n, mc, ci, cj, cc, max_cycle_len, cycles, n_cycles, ia, ja, ca, &ma, tn, te, &T);
     free(ci); free(cj); free(cc);
     if (st == OK && ma > edge_cap) { *m_out = ma; st = ERR_CAP; }
     if (st != OK) { free(ia); free(ja); free(ca); free(tn); free(te); return st; }
@@ -833,10 +887,12 @@ double rama_oracle_multicut_cost(int64_t m, const int32_t *i, const int32_t *j, 
 /* k_r message-passing iterations, contract on the reparametrised costs, compose f.  Stop when */
 /* the contraction set is empty.  The lower bound is the one recorded on the original graph    */
 /* (round 1).  labels[v] = smallest original node id in v's cluster.                           */
-/* stats (optional, int64[8]): rounds, clusters, C3, C4, C5, |T|, |E'| of round 1, final edges */
+/* shortest_only: the separation keeps, per repulsive edge, only its shortest cycles (step a1). */
+/* stats (optional, int64[5+N_LISTS]): rounds, clusters, |T|, |E'| of round 1, final edges,     */
+/* then the number of 3-,4-,..,MAX_CYCLE_LEN-cycles of round 1                                 */
 /* ------------------------------------------------------------------------------------------ */
 int rama_oracle_solve(int32_t n, int64_t m, const int32_t *i, const int32_t *j, const float *c,
-                      int32_t max_cycle_len_first, int32_t max_cycle_len_later,
+                      int32_t max_cycle_len_first, int32_t max_cycle_len_later, int32_t shortest_only,
                       int32_t mp_iters_first, int32_t mp_iters_later,
                       int32_t matching_rounds_cap, float tau, float forest_ratio, int32_t max_rounds,
                       int32_t *labels, double *primal_cost, double *lower_bound, int64_t *stats)
@@ -854,35 +910,36 @@ int rama_oracle_solve(int32_t n, int64_t m, const int32_t *i, const int32_t *j, 
     for (int32_t v = 0; v < n; ++v) f[v] = v;
     double lb = 0.0;
     int have_lb = 0;
-    int64_t st_rounds = 0, st_c[3] = { 0, 0, 0 }, st_T = 0, st_ma = 0;
+    int64_t st_rounds = 0, st_c[N_LISTS] = { 0 }, st_T = 0, st_ma = 0;
+    if (max_cycle_len_first > MAX_CYCLE_LEN || max_cycle_len_later > MAX_CYCLE_LEN) { st = ERR_ARG; goto fail; }
     for (int32_t round = 1; max_rounds <= 0 || round <= max_rounds; ++round) {
         int32_t Lmax = round == 1 ? max_cycle_len_first : max_cycle_len_later;
         int32_t k = round == 1 ? mp_iters_first : mp_iters_later;
-        int64_t cnt[3] = { 0, 0, 0 };
-        int32_t *cyc[3] = { NULL, NULL, NULL };
+        int64_t cnt[N_LISTS] = { 0 }, total = 0, chords = 0;
+        int32_t *cyc[N_LISTS] = { NULL };
         if (Lmax >= 3 && k > 0) {
-            st = rama_oracle_find_conflicted_cycles(ncur, mcur, gi, gj, gc, Lmax, 0, 0, 0, NULL, NULL, NULL, cnt);
+            st = rama_oracle_find_conflicted_cycles(ncur, mcur, gi, gj, gc, Lmax, shortest_only, NULL, NULL, cnt);
             if (st != OK && st != ERR_CAP) goto fail;
-            for (int L = 3; L <= 5; ++L) cyc[L - 3] = (int32_t *)xmalloc((size_t)cnt[L - 3] * L * 4);
-            st = rama_oracle_find_conflicted_cycles(ncur, mcur, gi, gj, gc, Lmax, cnt[0], cnt[1], cnt[2],
-                                                    cyc[0], cyc[1], cyc[2], cnt);
+            for (int L = 3; L <= Lmax; ++L) cyc[L - 3] = (int32_t *)xmalloc((size_t)cnt[L - 3] * L * 4);
+            st = rama_oracle_find_conflicted_cycles(ncur, mcur, gi, gj, gc, Lmax, shortest_only, cnt, cyc, cnt);
             if (st != OK) goto fail;
+            for (int L = 3; L <= Lmax; ++L) { total += cnt[L - 3]; chords += (L - 3) * cnt[L - 3]; }
         }
-        if (round == 1) { st_c[0] = cnt[0]; st_c[1] = cnt[1]; st_c[2] = cnt[2]; }
-        if (cnt[0] + cnt[1] + cnt[2] > 0) {
-            int64_t room = mcur + cnt[1] + 2 * cnt[2], ma = 0;
+        if (round == 1) for (int q = 0; q < N_LISTS; ++q) st_c[q] = cnt[q];
+        if (total > 0) {
+            int64_t room = mcur + chords, ma = 0;
             int32_t *ai = (int32_t *)xmalloc((size_t)room * 4), *aj = (int32_t *)xmalloc((size_t)room * 4);
             float *ac = (float *)xmalloc((size_t)room * 4);
             double lbr = 0.0;
             if (!ai || !aj || !ac) { st = ERR_OOM; goto fail; }
-            st = rama_oracle_message_passing(ncur, mcur, gi, gj, gc, cyc[0], cnt[0], cyc[1], cnt[1], cyc[2], cnt[2],
+            st = rama_oracle_message_passing(ncur, mcur, gi, gj, gc, Lmax, (const int32_t *const *)cyc, cnt,
                                              k, room, ai, aj, ac, &ma, &lbr, NULL);
             if (st != OK) goto fail;
             if (round == 1) { lb = lbr; have_lb = 1; st_ma = ma; }
             free(gi); free(gj); free(gc);
             gi = ai; gj = aj; gc = ac; mcur = ma;
         }
-        for (int L = 0; L < 3; ++L) free(cyc[L]);
+        for (int L = 0; L < N_LISTS; ++L) free(cyc[L]);
         if (round == 1 && !have_lb) {
             for (int64_t e = 0; e < mcur; ++e) if (gc[e] < 0) lb += (double)gc[e];
             have_lb = 1; st_ma = mcur;
@@ -911,8 +968,8 @@ int rama_oracle_solve(int32_t n, int64_t m, const int32_t *i, const int32_t *j, 
     if (primal_cost) *primal_cost = rama_oracle_multicut_cost(m, i, j, c, labels);
     if (lower_bound) *lower_bound = lb;
     if (stats) {
-        stats[0] = st_rounds; stats[1] = ncur; stats[2] = st_c[0]; stats[3] = st_c[1]; stats[4] = st_c[2];
-        stats[5] = st_T; stats[6] = st_ma; stats[7] = mcur;
+        stats[0] = st_rounds; stats[1] = ncur; stats[2] = st_T; stats[3] = st_ma; stats[4] = mcur;
+        for (int q = 0; q < N_LISTS; ++q) stats[5 + q] = st_c[q];
     }
     st = OK;
 fail:

@@ -54,7 +54,7 @@ def conflicted_cycles(n, i, j, c, max_len):
         cost[key] = cost.get(key, 0.0) + float(w)
     def w(a, b):
         return cost.get((min(a, b), max(a, b)))
-    out = {L: set() for L in (3, 4, 5)}
+    out = {L: set() for L in range(3, max(max_len, 5) + 1)}
     for L in range(3, max_len + 1):
         for tup in itertools.permutations(range(n), L):
             if tup[0] >= tup[-1]:
@@ -104,3 +104,18 @@ def forest_path(n, forest_edges, a, b):
                 seen.add(w)
                 stack.append((w, path + [k]))
     return None
+
+
+def hop_distance(n, i, j, c, src, dst):
+    """Hop distance src -> dst using attractive edges only (scipy's breadth-first search); inf if none."""
+    import scipy.sparse as sp
+    from scipy.sparse.csgraph import shortest_path
+    cost = {}
+    for a, b, w in zip(i, j, c):
+        a, b = int(a), int(b)
+        if a != b:
+            key = (min(a, b), max(a, b))
+            cost[key] = cost.get(key, 0.0) + float(w)
+    pos = [k for k, w in cost.items() if w > 0]
+    A = sp.coo_matrix((np.ones(len(pos)), ([k[0] for k in pos], [k[1] for k in pos])), shape=(n, n)).tocsr()
+    return float(shortest_path(A, directed=False, unweighted=True, indices=[src])[0, dst])

@@ -303,3 +303,23 @@ def test_degenerate_inputs(rama):
     # the context stays usable after an error
     r = rama.solve(3, i, j, np.array([1.0, 2.0], np.float32))
     assert np_(r["labels"]).tolist() == [0, 0, 0]
+
+
+def test_profile_hooks_and_workspace(rama):
+    g = CASES["grid3d_24"]
+    rama.profile_enable(True)
+    rama.solve(g["n_nodes"], g["i"], g["j"], g["c"])
+    prof = rama.profile_get()
+    rama.profile_enable(False)
+    names = {k["name"] for k in prof}
+    assert {"k_triangle_update", "k_edge_update", "k_count_cycles", "k_propose", "k_reduce_runs"} <= names
+    assert any(n.startswith("k_rs_scatter<") for n in names) and any(n.startswith("k_scan_apply<") for n in names)
+    for k in prof:
+        assert k["launches"] > 0 and k["ms"] >= 0.0 and k["bytes"] >= 0.0
+    # a name filter restricts the timers
+    rama.profile_enable(True, only="k_rs_scatter")
+    rama.solve(g["n_nodes"], g["i"], g["j"], g["c"])
+    only = rama.profile_get()
+    rama.profile_enable(False)
+    assert only and all(k["name"].startswith("k_rs_scatter") for k in only)
+    assert rama.workspace_bytes() > 0

@@ -70,8 +70,8 @@ def test_canonicalise_rejects_bad_graph(oracle32):
 # --------------------------------------------------------------------------------------------
 # a1 conflicted cycles: brute force over all vertex tuples + hand cases
 # --------------------------------------------------------------------------------------------
-def as_sets(cycles):
-    return {L: set(map(tuple, cycles[L - 3].tolist())) for L in (3, 4, 5)}
+def as_sets(cycles, upto=5):
+    return {L: (set(map(tuple, cycles[L - 3].tolist())) if L - 3 < len(cycles) else set()) for L in range(3, upto + 1)}
 
 
 @pytest.mark.parametrize("seed", range(12))
@@ -81,11 +81,39 @@ def test_cycles_match_brute_force(oracle32, seed):
     g = inputs.random_graph(n, int(rng.uniform(0.4, 0.9) * n * (n - 1) / 2), 100 + seed)
     # bias towards attractive edges so that longer cycles exist
     c = np.where(rng.random(g["c"].size) < 0.7, np.abs(g["c"]), -np.abs(g["c"])).astype(np.float32)
-    for lmax in (3, 4, 5):
-        got = as_sets(oracle32.find_conflicted_cycles(n, g["i"], g["j"], c, lmax))
+    for lmax in (3, 4, 5, 6, 7):
+        got = as_sets(oracle32.find_conflicted_cycles(n, g["i"], g["j"], c, lmax), 7)
         want = bf.conflicted_cycles(n, g["i"], g["j"], c, lmax)
-        for L in (3, 4, 5):
+        for L in (3, 4, 5, 6, 7):
             assert got[L] == (want[L] if L <= lmax else set()), (seed, lmax, L)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_shortest_only_keeps_exactly_the_shortest_cycles(oracle32, seed):
+    """Separation Lemma (Sec. 3.2.2) read literally: per repulsive edge only the cycles along its
+    shortest attractive paths.  Pinned two ways: by filtering the brute-force set of all cycles,
+    and by scipy's breadth-first hop distance between the endpoints of the repulsive edge."""
+    rng = np.random.default_rng(900 + seed)
+    n = int(rng.integers(6, 9))
+    g = inputs.random_graph(n, int(rng.uniform(0.3, 0.7) * n * (n - 1) / 2), 900 + seed)
+    c = np.where(rng.random(g["c"].size) < 0.7, np.abs(g["c"]), -np.abs(g["c"])).astype(np.float32)
+    for lmax in (4, 5, 7):
+        every = bf.conflicted_cycles(n, g["i"], g["j"], c, lmax)
+        shortest = {}
+        for L in range(3, lmax + 1):
+            for t in every[L]:
+                shortest.setdefault((t[0], t[-1]), L)
+        got = as_sets(oracle32.find_conflicted_cycles(n, g["i"], g["j"], c, lmax, shortest_only=True), 7)
+        for L in range(3, 8):
+            want = {t for t in every.get(L, set()) if shortest[(t[0], t[-1])] == L} if L <= lmax else set()
+            assert got[L] == want, (seed, lmax, L)
+            for t in got[L]:
+                assert bf.hop_distance(n, g["i"], g["j"], c, t[0], t[-1]) == L - 1
+        # repulsive edges without any cycle: their endpoints are farther apart than lmax-1 attractive hops
+        ci, cj, cc = oracle32.canonicalise(n, g["i"], g["j"], c)
+        for a, b, w in zip(ci.tolist(), cj.tolist(), cc.tolist()):
+            if w < 0 and (a, b) not in shortest:
+                assert bf.hop_distance(n, g["i"], g["j"], c, a, b) > lmax - 1
 
 
 def test_cycles_messy_input_matches_brute_force(oracle32):
@@ -104,22 +132,36 @@ def ring(L, neg_at, val=1.0):
     return i, j, c
 
 
-@pytest.mark.parametrize("L", [3, 4, 5])
+@pytest.mark.parametrize("L", [3, 4, 5, 6, 7])
 def test_single_ring_cases(oracle32, L):
     i, j, c = ring(L, [L - 1])            # edge (L-1, 0) repulsive
-    cyc = oracle32.find_conflicted_cycles(L, i, j, c, 5)
-    assert [x.shape[0] for x in cyc] == [int(L == 3), int(L == 4), int(L == 5)]
-    assert cyc[L - 3][0].tolist() == list(range(L))   # v0=0 < v_{L-1}=L-1, path 0,1,..,L-1
+    for so in (False, True):
+        cyc = oracle32.find_conflicted_cycles(L, i, j, c, 7, shortest_only=so)
+        assert [x.shape[0] for x in cyc] == [int(L == q) for q in (3, 4, 5, 6, 7)]
+        assert cyc[L - 3][0].tolist() == list(range(L))   # v0=0 < v_{L-1}=L-1, path 0,1,..,L-1
     for neg in ([], [0, 2] if L > 3 else [0, 1]):
         i, j, c = ring(L, neg)
-        assert sum(x.shape[0] for x in oracle32.find_conflicted_cycles(L, i, j, c, 5)) == 0
-    # a 6-ring is out of reach of length 5
-    i, j, c = ring(6, [5])
-    assert sum(x.shape[0] for x in oracle32.find_conflicted_cycles(6, i, j, c, 5)) == 0
+        assert sum(x.shape[0] for x in oracle32.find_conflicted_cycles(L, i, j, c, 7)) == 0
+    # an L-ring is out of reach of length L-1
+    if L > 3:
+        i, j, c = ring(L, [L - 1])
+        assert sum(x.shape[0] for x in oracle32.find_conflicted_cycles(L, i, j, c, L - 1)) == 0
     # zero-cost edge is neither attractive nor repulsive: it breaks the path and is no conflict
     i, j, c = ring(L, [L - 1])
     c[0] = 0.0
-    assert sum(x.shape[0] for x in oracle32.find_conflicted_cycles(L, i, j, c, 5)) == 0
+    assert sum(x.shape[0] for x in oracle32.find_conflicted_cycles(L, i, j, c, 7)) == 0
+
+
+def test_shortest_only_ring_with_shortcut(oracle32):
+    """A 6-ring whose repulsive edge also closes a 4-cycle through a shortcut: the plain search
+    reports both cycles, the shortest-only search just the 4-cycle."""
+    i, j, c = ring(6, [5])                 # path 0-1-2-3-4-5, (0,5) repulsive
+    i, j, c = np.append(i, 1).astype(np.int32), np.append(j, 4).astype(np.int32), np.append(c, 1.0).astype(np.float32)
+    every = oracle32.find_conflicted_cycles(6, i, j, c, 6)
+    assert [x.shape[0] for x in every] == [0, 1, 0, 1]
+    assert every[1][0].tolist() == [0, 1, 4, 5] and every[3][0].tolist() == [0, 1, 2, 3, 4, 5]
+    short = oracle32.find_conflicted_cycles(6, i, j, c, 6, shortest_only=True)
+    assert [x.shape[0] for x in short] == [0, 1, 0, 0] and short[1][0].tolist() == [0, 1, 4, 5]
 
 
 def test_grid_is_bipartite_and_cycles_are_unit_squares(oracle32):
@@ -144,8 +186,9 @@ def test_grid_is_bipartite_and_cycles_are_unit_squares(oracle32):
 def test_cycle_list_order(oracle32):
     g = inputs.random_graph(9, 30, 5)
     c = np.where(np.arange(g["c"].size) % 4 == 0, -np.abs(g["c"]), np.abs(g["c"])).astype(np.float32)
-    for L, cyc in zip((3, 4, 5), oracle32.find_conflicted_cycles(9, g["i"], g["j"], c, 5)):
-        order = {3: [0, 2, 1], 4: [0, 3, 1, 2], 5: [0, 4, 1, 2, 3]}[L]
+    for L, cyc in zip((3, 4, 5, 6, 7), oracle32.find_conflicted_cycles(9, g["i"], g["j"], c, 7)):
+        order = [0, L - 1] + list(range(1, L - 1))
+        assert cyc.shape[0] > 0
         keys = [tuple(int(r[q]) for q in order) for r in cyc]
         assert keys == sorted(keys) and len(set(keys)) == len(keys)
         assert np.all(cyc[:, 0] < cyc[:, -1])
@@ -161,11 +204,11 @@ def test_triangulation_invariants(oracle32, seed):
     g = inputs.random_graph(n, 26, 200 + seed)
     c = np.where(rng.random(g["c"].size) < 0.75, np.abs(g["c"]), -np.abs(g["c"])).astype(np.float32)
     i, j, c = oracle32.canonicalise(n, g["i"], g["j"], c)
-    cyc = oracle32.find_conflicted_cycles(n, i, j, c, 5)
+    lmax = 5 + seed % 3
+    cyc = oracle32.find_conflicted_cycles(n, i, j, c, lmax)
     ia, ja, ca, tn, te = oracle32.triangulate(n, i, j, c, cyc)
-    n3, n4, n5 = (x.shape[0] for x in cyc)
-    assert tn.shape[0] <= n3 + 2 * n4 + 3 * n5
-    assert ia.size <= i.size + n4 + 2 * n5
+    assert tn.shape[0] <= sum((k + 1) * x.shape[0] for k, x in enumerate(cyc))
+    assert ia.size <= i.size + sum(k * x.shape[0] for k, x in enumerate(cyc))
     # augmented list canonical, old edges keep their cost, chords have cost 0
     key = ia.astype(np.int64) * n + ja
     assert np.all(ia < ja) and np.all(np.diff(key) > 0)
@@ -181,10 +224,14 @@ def test_triangulation_invariants(oracle32, seed):
         assert (ia[e0], ja[e0]) == (u, v) and (ia[e1], ja[e1]) == (u, w) and (ia[e2], ja[e2]) == (v, w)
     # every cycle is covered: each of its L-2 fan triangles is present
     ts = set(tl)
-    for L, cl in zip((3, 4, 5), cyc):
+    for L, cl in zip(range(3, lmax + 1), cyc):
         for r in cl.tolist():
             for mm in range(1, L - 1):
                 assert tuple(sorted((r[0], r[mm], r[mm + 1]))) in ts
+    # and nothing else: every triangle is a fan triangle of some cycle
+    fans = {tuple(sorted((r[0], r[mm], r[mm + 1]))) for L, cl in zip(range(3, lmax + 1), cyc)
+            for r in cl.tolist() for mm in range(1, L - 1)}
+    assert ts == fans
 
 
 # --------------------------------------------------------------------------------------------
@@ -296,12 +343,12 @@ def test_single_conflicted_triangle_is_solved_exactly(oracle64):
         assert abs(res["lower_bound"] - opt) < 1e-6
 
 
-@pytest.mark.parametrize("L", [4, 5])
+@pytest.mark.parametrize("L", [4, 5, 6, 7])
 def test_single_ring_bound(oracle64, L):
     i, j, c = ring(L, [L - 1])
     c = c * np.linspace(1.0, 2.0, L).astype(np.float32)
     c[L - 1] = -3.0
-    cyc = oracle64.find_conflicted_cycles(L, i, j, c, 5)
+    cyc = oracle64.find_conflicted_cycles(L, i, j, c, 7)
     res = oracle64.message_passing(L, i, j, c, cyc, 200, trace=True)
     opt, _ = bf.optimal_multicut(L, i, j, c)
     assert abs(opt - min(0.0, float(c[:L - 1].min()) - 3.0)) < 1e-6
@@ -492,6 +539,26 @@ def test_solve_sandwich_small(oracle32, oracle64, seed):
         # labels are canonical: the label of a cluster is its smallest node id
         for v in range(n):
             assert r["labels"][v] == np.where(r["labels"] == r["labels"][v])[0].min()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_solve_sandwich_longer_and_shortest_cycles(oracle32, seed):
+    """Any set of cycle inequalities gives a valid relaxation: the bound stays below the optimum and
+    the primal above it with cycles up to 7 and with the shortest-only separation; on the same
+    graph more cycles (5 -> 7) never loosen the bound of the converged dual by more than rounding."""
+    g = small_random(840 + seed)
+    n = g["n_nodes"]
+    opt, _ = bf.optimal_multicut(n, g["i"], g["j"], g["c"])
+    for kw in (dict(max_cycle_len_first=7, max_cycle_len_later=7), dict(shortest_only=True),
+               dict(max_cycle_len_first=7, max_cycle_len_later=4, shortest_only=True)):
+        r = oracle32.solve(n, g["i"], g["j"], g["c"], **kw)
+        assert r["lower_bound"] <= opt + 1e-4 * (1 + abs(opt))
+        assert opt <= r["primal"] + 1e-4 * (1 + abs(opt))
+        assert abs(r["primal"] - bf.multicut_cost(g["i"], g["j"], g["c"], r["labels"])) < 1e-9
+    # shortest-only finds a subset of the cycles
+    a = oracle32.solve(n, g["i"], g["j"], g["c"], max_cycle_len_first=7)["n_cycles_first"]
+    b = oracle32.solve(n, g["i"], g["j"], g["c"], max_cycle_len_first=7, shortest_only=True)["n_cycles_first"]
+    assert all(y <= x for x, y in zip(a, b))
 
 
 def test_solve_cfg1_recovers_planted_blocks(oracle32):
