@@ -43,9 +43,13 @@ extern "C" {
 
 typedef struct rama_ctx rama_ctx; /* opaque: device, stream, cached workspace, last error */
 
+/* Longest conflicted cycle the separation can look for.  The paper stops at 5 (Sec. 4) and
+ * lists longer cycles as future work (Sec. 5); 6 and 7 come from the same search. */
+#define RAMA_MAX_CYCLE_LEN 7
+
 typedef enum {
     RAMA_OK = 0,
-    RAMA_ERR_INVALID_ARG = -1, /* null pointer, negative size, cycle length not in {3,4,5}, ... */
+    RAMA_ERR_INVALID_ARG = -1, /* null pointer, negative size, cycle length out of range, ... */
     RAMA_ERR_BAD_GRAPH = -2,   /* endpoint out of range, non-finite cost, a cycle that is not in the graph */
     RAMA_ERR_CAPACITY = -3,    /* a caller buffer is too small (needed sizes are written) or a count reaches 2^31 */
     RAMA_ERR_OOM = -4,         /* hipMalloc failed */
@@ -64,13 +68,14 @@ typedef struct {
     float forest_ratio;           /* if the matching joins fewer than forest_ratio*|V| pairs, S is the spanning
                                      forest without conflicts instead; 0.1 (<= 0: matching only) */
     int32_t max_rounds;           /* stop after this many rounds; <=0: until no candidate edge is left */
+    int32_t shortest_cycles_only; /* != 0: per repulsive edge keep only its shortest conflicted cycles; 0 */
 } rama_params;
 
 /* What rama_solve did (all host memory). */
 typedef struct {
     int32_t rounds;             /* rounds of the outer loop that ran */
     int32_t n_clusters;         /* clusters in the result */
-    int64_t n_cycles_first[3];  /* conflicted 3-, 4-, 5-cycles found on the original graph */
+    int64_t n_cycles_first[RAMA_MAX_CYCLE_LEN - 2]; /* conflicted 3-, 4-, .. cycles found on the original graph */
     int64_t n_triangles_first;  /* triangles after triangulation, first round */
     int64_t n_edges_aug_first;  /* edges after adding chords, first round */
     int64_t n_edges_final;      /* edges of the last contracted graph */
@@ -107,27 +112,34 @@ rama_status rama_profile_get(const rama_ctx *ctx, int32_t index, const char **na
 /*
  * Conflicted-cycle separation (Sec. 3.2.2, definition "Conflicted cycles", and the appendix
  * algorithm "Parallel Conf. 5-Cycles"): every simple cycle of length L in {3,..,max_cycle_len}
- * with exactly one repulsive edge and L-1 attractive edges.
+ * with exactly one repulsive edge and L-1 attractive edges.  The paper separates up to length 5
+ * and names longer cycles as an open improvement (Sec. 5); lengths up to RAMA_MAX_CYCLE_LEN are
+ * found by the same depth-first walk.
  *
  * A cycle is stored as the node tuple (v0,...,v_{L-1}) where (v0,v_{L-1}) is its repulsive
  * edge, v0 < v_{L-1}, and v0,v1,...,v_{L-1} is the attractive path.  Each list is ordered by
  * (v0, v_{L-1}, v1, ..., v_{L-2}): grouped by repulsive edge, then lexicographic along the path.
+ * List q (q = 0 .. max_cycle_len-3) holds the cycles of length q+3.
  *
  *   i, j, c            device, [n_edges]
- *   max_cycle_len      3, 4 or 5
- *   cap3, cap4, cap5   capacities of the output lists, in cycles
- *   cycles3/4/5        device, [3*cap3], [4*cap4], [5*cap5]; may be NULL when its cap is 0
- *   n_cycles_out       host, [3]: number of 3-, 4-, 5-cycles found (always written on
- *                      RAMA_OK and RAMA_ERR_CAPACITY)
+ *   max_cycle_len      3 .. RAMA_MAX_CYCLE_LEN
+ *   shortest_only      != 0: the separation lemma of Sec. 3.2.2 taken literally -- per repulsive
+ *                      edge only the cycles along its shortest attractive paths (hop count) are
+ *                      reported, all of them, and none if that length exceeds max_cycle_len
+ *   cap                host, [max_cycle_len-2]: capacity of each list, in cycles; NULL = all 0
+ *   cycles             host array of max_cycle_len-2 device pointers, list q has room for
+ *                      (q+3)*cap[q] int32; an entry may be NULL when its cap is 0; the array
+ *                      itself may be NULL when every cap is 0
+ *   n_cycles_out       host, [max_cycle_len-2]: number of cycles found per length (always written
+ *                      on RAMA_OK and RAMA_ERR_CAPACITY)
  * RAMA_ERR_CAPACITY if any list does not fit; then nothing is written to the lists, and
- * calling again with the reported counts succeeds (calling with all caps 0 is the way to
- * size the buffers).
+ * calling again with the reported counts succeeds (calling with cap = NULL is the way to
+ * size the buffers).  Also RAMA_ERR_CAPACITY if a list would reach 2^31 entries.
  */
 rama_status rama_find_conflicted_cycles(rama_ctx *ctx, int32_t n_nodes, int64_t n_edges,
                                         const int32_t *i, const int32_t *j, const float *c,
-                                        int32_t max_cycle_len, int64_t cap3, int64_t cap4, int64_t cap5,
-                                        int32_t *cycles3, int32_t *cycles4, int32_t *cycles5,
-                                        int64_t *n_cycles_out);
+                                        int32_t max_cycle_len, int32_t shortest_only, const int64_t *cap,
+                                        int32_t *const *cycles, int64_t *n_cycles_out);
 
 /*
  * Dual update of one round (Sec. 3.2.1 Lagrange decomposition, eq. 5 and 6; Sec. 3.2.3,
@@ -139,10 +151,12 @@ rama_status rama_find_conflicted_cycles(rama_ctx *ctx, int32_t n_nodes, int64_t 
  * triangles {v0,v_m,v_{m+1}}, m=1..L-2; a chord (v0,v_m) that is not yet an edge is added
  * with cost 0.  The triangle set is the sorted set of distinct node triples.
  *
- *   cyclesL, nL        device lists in the format of rama_find_conflicted_cycles (any order);
+ *   max_cycle_len      2 .. RAMA_MAX_CYCLE_LEN: max_cycle_len-2 lists follow (2: none)
+ *   cycles, n_cycles   host arrays [max_cycle_len-2]: device list q holds n_cycles[q] cycles of
+ *                      length q+3 in the format of rama_find_conflicted_cycles (any order);
  *                      every cycle edge must be an edge of the graph, nodes distinct
  *   k_iters            >= 0
- *   edge_cap           capacity of i_out/j_out/c_out; n_edges + n4 + 2*n5 always suffices
+ *   edge_cap           capacity of i_out/j_out/c_out; n_edges + sum_q q*n_cycles[q] always suffices
  *   i_out,j_out,c_out  device: canonical edge list incl. new chords, c_out = reduced costs c^lambda (eq. 6a)
  *   n_edges_out        host: number of edges written (needed size on RAMA_ERR_CAPACITY)
  *   lower_bound        host, optional: LB(lambda) of eq. 5 after the last iteration
@@ -150,8 +164,8 @@ rama_status rama_find_conflicted_cycles(rama_ctx *ctx, int32_t n_nodes, int64_t 
  */
 rama_status rama_message_passing(rama_ctx *ctx, int32_t n_nodes, int64_t n_edges,
                                  const int32_t *i, const int32_t *j, const float *c,
-                                 const int32_t *cycles3, int64_t n3, const int32_t *cycles4, int64_t n4,
-                                 const int32_t *cycles5, int64_t n5, int32_t k_iters, int64_t edge_cap,
+                                 int32_t max_cycle_len, const int32_t *const *cycles, const int64_t *n_cycles,
+                                 int32_t k_iters, int64_t edge_cap,
                                  int32_t *i_out, int32_t *j_out, float *c_out, int64_t *n_edges_out,
                                  double *lower_bound, double *lb_trace);
 

@@ -20,18 +20,21 @@ EXPORTS = [
 ]
 
 
+MAX_CYCLE_LEN = 7   # RAMA_MAX_CYCLE_LEN of include/rama.h
+
+
 class RamaParams(C.Structure):
     _fields_ = [
         ("max_cycle_len_first", C.c_int32), ("max_cycle_len_later", C.c_int32),
         ("mp_iters_first", C.c_int32), ("mp_iters_later", C.c_int32),
         ("matching_rounds_cap", C.c_int32), ("contract_threshold", C.c_float),
-        ("forest_ratio", C.c_float), ("max_rounds", C.c_int32),
+        ("forest_ratio", C.c_float), ("max_rounds", C.c_int32), ("shortest_cycles_only", C.c_int32),
     ]
 
 
 class RamaStats(C.Structure):
     _fields_ = [
-        ("rounds", C.c_int32), ("n_clusters", C.c_int32), ("n_cycles_first", C.c_int64 * 3),
+        ("rounds", C.c_int32), ("n_clusters", C.c_int32), ("n_cycles_first", C.c_int64 * (MAX_CYCLE_LEN - 2)),
         ("n_triangles_first", C.c_int64), ("n_edges_aug_first", C.c_int64), ("n_edges_final", C.c_int64),
         ("ms_total", C.c_double), ("ms_cycles", C.c_double), ("ms_dual", C.c_double),
         ("ms_contract", C.c_double), ("ms_other", C.c_double),
@@ -69,10 +72,10 @@ def load_library():
     lib.rama_params_default.restype = None
     lib.rama_workspace_bytes.argtypes = [vp]
     lib.rama_workspace_bytes.restype = i64
-    lib.rama_find_conflicted_cycles.argtypes = [vp, i32, i64, vp, vp, vp, i32, i64, i64, i64, vp, vp, vp,
+    lib.rama_find_conflicted_cycles.argtypes = [vp, i32, i64, vp, vp, vp, i32, i32, C.POINTER(i64), C.POINTER(vp),
                                                 C.POINTER(i64)]
-    lib.rama_message_passing.argtypes = [vp, i32, i64, vp, vp, vp, vp, i64, vp, i64, vp, i64, i32, i64, vp, vp, vp,
-                                         C.POINTER(i64), C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    lib.rama_message_passing.argtypes = [vp, i32, i64, vp, vp, vp, i32, C.POINTER(vp), C.POINTER(i64), i32, i64,
+                                         vp, vp, vp, C.POINTER(i64), C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.rama_contract.argtypes = [vp, i32, i64, vp, vp, vp, C.POINTER(RamaParams), i32, vp, vp, vp, vp, vp,
                                   C.POINTER(i32), C.POINTER(i64)]
     lib.rama_solve.argtypes = [vp, i32, i64, vp, vp, vp, C.POINTER(RamaParams), vp, C.POINTER(C.c_double),
@@ -171,35 +174,43 @@ class Rama:
         return out
 
     # -- entry points ---------------------------------------------------------------------------
-    def find_conflicted_cycles(self, n_nodes, i, j, c, max_cycle_len=5):
+    def find_conflicted_cycles(self, n_nodes, i, j, c, max_cycle_len=5, shortest_only=False):
+        """max_cycle_len-2 device tensors; entry L-3 is [n_L, L], the conflicted L-cycles."""
         t = self.torch
         i, j, c = self._graph(i, j, c)
-        cnt = (C.c_int64 * 3)()
+        nl = max_cycle_len - 2
+        if nl < 1 or max_cycle_len > MAX_CYCLE_LEN:
+            raise ValueError("max_cycle_len out of range")
+        cnt = (C.c_int64 * nl)()
         st = self.lib.rama_find_conflicted_cycles(self.ctx, n_nodes, i.numel(), i.data_ptr(), j.data_ptr(),
-                                                  c.data_ptr(), max_cycle_len, 0, 0, 0, None, None, None, cnt)
+                                                  c.data_ptr(), max_cycle_len, int(shortest_only), None, None, cnt)
         if st not in (RAMA_OK, RAMA_ERR_CAPACITY):
             self._check(st, "rama_find_conflicted_cycles")
-        outs = [self._empty(cnt[k] * (k + 3), t.int32) for k in range(3)]
-        want = [cnt[0], cnt[1], cnt[2]]
+        want = [cnt[k] for k in range(nl)]
+        outs = [self._empty(want[k] * (k + 3), t.int32) for k in range(nl)]
+        cap = (C.c_int64 * nl)(*want)
+        ptrs = (C.c_void_p * nl)(*[o.data_ptr() for o in outs])
         st = self.lib.rama_find_conflicted_cycles(self.ctx, n_nodes, i.numel(), i.data_ptr(), j.data_ptr(),
-                                                  c.data_ptr(), max_cycle_len, want[0], want[1], want[2],
-                                                  outs[0].data_ptr(), outs[1].data_ptr(), outs[2].data_ptr(), cnt)
+                                                  c.data_ptr(), max_cycle_len, int(shortest_only), cap, ptrs, cnt)
         self._check(st, "rama_find_conflicted_cycles")
-        return [outs[k][: want[k] * (k + 3)].view(-1, k + 3) for k in range(3)]
+        return [outs[k][: want[k] * (k + 3)].view(-1, k + 3) for k in range(nl)]
 
     def message_passing(self, n_nodes, i, j, c, cycles, k_iters, trace=False):
+        """cycles: list whose entry q holds the (q+3)-cycles, as returned by find_conflicted_cycles."""
         t = self.torch
         i, j, c = self._graph(i, j, c)
         cyc = [_dev(t.as_tensor(x, device=self.device).reshape(-1), t.int32, t) for x in cycles]
-        n3, n4, n5 = cyc[0].numel() // 3, cyc[1].numel() // 4, cyc[2].numel() // 5
-        cap = i.numel() + n4 + 2 * n5
+        nl = len(cyc)
+        ncyc = [cyc[q].numel() // (q + 3) for q in range(nl)]
+        cap = i.numel() + sum(q * ncyc[q] for q in range(nl))
         io, jo, co = self._empty(cap, t.int32), self._empty(cap, t.int32), self._empty(cap, t.float32)
         mo, lb = C.c_int64(0), C.c_double(0.0)
         tr = (C.c_double * (k_iters + 1))() if trace else None
+        ptrs = (C.c_void_p * max(nl, 1))(*[x.data_ptr() for x in cyc])
+        cnts = (C.c_int64 * max(nl, 1))(*ncyc)
         st = self.lib.rama_message_passing(self.ctx, n_nodes, i.numel(), i.data_ptr(), j.data_ptr(), c.data_ptr(),
-                                           cyc[0].data_ptr(), n3, cyc[1].data_ptr(), n4, cyc[2].data_ptr(), n5,
-                                           k_iters, cap, io.data_ptr(), jo.data_ptr(), co.data_ptr(),
-                                           C.byref(mo), C.byref(lb), tr)
+                                           nl + 2, ptrs, cnts, k_iters, cap, io.data_ptr(), jo.data_ptr(),
+                                           co.data_ptr(), C.byref(mo), C.byref(lb), tr)
         self._check(st, "rama_message_passing")
         k = mo.value
         return dict(i=io[:k], j=jo[:k], c=co[:k], lower_bound=lb.value,

@@ -107,21 +107,24 @@ rama_status solve_impl(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const i
         const int k = round == 1 ? P.mp_iters_first : P.mp_iters_later;
         double t0 = now_ms();
         CycleLists cyc;
-        if (lmax >= 3 && k > 0) RAMA_TRY(find_cycles(ctx, g, lmax, false, cyc));
+        if (lmax >= 3 && k > 0) RAMA_TRY(find_cycles(ctx, g, lmax, P.shortest_cycles_only != 0, false, cyc));
         RAMA_TRY(finish(ctx, RAMA_OK));
         double t1 = now_ms();
         t_cyc += t1 - t0;
-        if (round == 1) for (int q = 0; q < 3; ++q) S.n_cycles_first[q] = cyc.n[q];
-        if (cyc.n[0] + cyc.n[1] + cyc.n[2] > 0) {
+        int64_t n_cyc = 0;
+        const int32_t *lists[kCycleLists];
+        for (int q = 0; q < kCycleLists; ++q) { n_cyc += cyc.n[q]; lists[q] = cyc.v[q].get(); }
+        if (round == 1) for (int q = 0; q < kCycleLists; ++q) S.n_cycles_first[q] = cyc.n[q];
+        if (n_cyc > 0) {
             Graph aug;
             DualInfo info;
             double lbr = 0.0;
-            RAMA_TRY(dual_update(ctx, g, cyc.v[0].get(), cyc.n[0], cyc.v[1].get(), cyc.n[1], cyc.v[2].get(), cyc.n[2],
-                                 false, k, aug, round == 1 ? &lbr : nullptr, nullptr, &info));
+            RAMA_TRY(dual_update(ctx, g, kCycleLists, lists, cyc.n, false, k, aug, round == 1 ? &lbr : nullptr, nullptr,
+                                 &info));
             if (round == 1) { lb = lbr; have_lb = true; S.n_triangles_first = info.n_triangles; }
             g = std::move(aug);
         }
-        for (int q = 0; q < 3; ++q) cyc.v[q].reset();
+        for (int q = 0; q < kCycleLists; ++q) cyc.v[q].reset();
         if (round == 1) {
             if (!have_lb) { RAMA_TRY(negative_cost_sum(ctx, g.c.get(), g.m, &lb)); have_lb = true; }
             S.n_edges_aug_first = g.m;
@@ -148,8 +151,9 @@ rama_status solve_impl(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const i
         const double t3 = now_ms();
         t_con += t3 - t2;
         if (trace)
-            fprintf(stderr, "round %2d: cycles %lld/%lld/%lld  |S| %lld  -> nodes %d edges %lld   ms: cycles %.3f dual %.3f contract %.3f\n",
-                    round, (long long)cyc.n[0], (long long)cyc.n[1], (long long)cyc.n[2], (long long)ns, n_cur,
+            fprintf(stderr, "round %2d: cycles %lld/%lld/%lld/%lld/%lld  |S| %lld  -> nodes %d edges %lld   ms: cycles %.3f dual %.3f contract %.3f\n",
+                    round, (long long)cyc.n[0], (long long)cyc.n[1], (long long)cyc.n[2], (long long)cyc.n[3],
+                    (long long)cyc.n[4], (long long)ns, n_cur,
                     (long long)g.m, t1 - t0, t2 - t1, t3 - t2);
         if (ns == 0) break;
     }
@@ -235,6 +239,7 @@ void rama_params_default(rama_params *p)
     p->contract_threshold = 0.0f;
     p->forest_ratio = 0.1f;
     p->max_rounds = 0;
+    p->shortest_cycles_only = 0;
 }
 
 int64_t rama_workspace_bytes(const rama_ctx *ctx) { return ctx ? (int64_t)ctx->pool.total() : 0; }
@@ -265,47 +270,57 @@ rama_status rama_profile_get(const rama_ctx *ctx, int32_t index, const char **na
 }
 
 rama_status rama_find_conflicted_cycles(rama_ctx *ctx, int32_t n_nodes, int64_t n_edges, const int32_t *i,
-                                        const int32_t *j, const float *c, int32_t max_cycle_len, int64_t cap3,
-                                        int64_t cap4, int64_t cap5, int32_t *cycles3, int32_t *cycles4,
-                                        int32_t *cycles5, int64_t *n_cycles_out)
+                                        const int32_t *j, const float *c, int32_t max_cycle_len, int32_t shortest_only,
+                                        const int64_t *cap, int32_t *const *cycles, int64_t *n_cycles_out)
 {
     if (!ctx) return RAMA_ERR_INVALID_ARG;
-    if (bad_graph_args(n_nodes, n_edges, i, j, c) || !n_cycles_out || max_cycle_len < 3 || max_cycle_len > 5 ||
-        cap3 < 0 || cap4 < 0 || cap5 < 0 || (cap3 > 0 && !cycles3) || (cap4 > 0 && !cycles4) || (cap5 > 0 && !cycles5))
+    if (bad_graph_args(n_nodes, n_edges, i, j, c) || !n_cycles_out || max_cycle_len < 3 || max_cycle_len > kMaxCycleLen)
         return fail(*ctx, RAMA_ERR_INVALID_ARG, "rama_find_conflicted_cycles: bad arguments");
+    const int lists = max_cycle_len - 2;
+    for (int q = 0; q < lists; ++q) {
+        const int64_t cq = cap ? cap[q] : 0;
+        if (cq < 0 || (cq > 0 && (!cycles || !cycles[q])))
+            return fail(*ctx, RAMA_ERR_INVALID_ARG, "rama_find_conflicted_cycles: bad capacities or null list");
+    }
     auto body = [&]() -> rama_status {
         Graph g;
         RAMA_TRY(canonicalise(*ctx, n_nodes, n_edges, i, j, c, g));
         CycleLists cnt;
-        RAMA_TRY(find_cycles(*ctx, g, max_cycle_len, true, cnt));
-        for (int q = 0; q < 3; ++q) n_cycles_out[q] = cnt.n[q];
-        if (cnt.n[0] > cap3 || cnt.n[1] > cap4 || cnt.n[2] > cap5)
+        RAMA_TRY(find_cycles(*ctx, g, max_cycle_len, shortest_only != 0, true, cnt));
+        bool fits = true;
+        int64_t total = 0;
+        for (int q = 0; q < lists; ++q) {
+            n_cycles_out[q] = cnt.n[q];
+            total += cnt.n[q];
+            if (cnt.n[q] > (cap ? cap[q] : 0)) fits = false;
+        }
+        if (!fits)
             return fail(*ctx, RAMA_ERR_CAPACITY, "cycle output lists are too small; needed sizes written to n_cycles_out");
-        if (cnt.n[0] + cnt.n[1] + cnt.n[2] == 0) return RAMA_OK;
+        if (total == 0) return RAMA_OK;
         CycleLists cyc;
-        RAMA_TRY(find_cycles(*ctx, g, max_cycle_len, false, cyc));
-        int32_t *dst[3] = {cycles3, cycles4, cycles5};
-        for (int q = 0; q < 3; ++q)
-            RAMA_TRY(copy_out(*ctx, dst[q], cyc.v[q].get(), (size_t)cyc.n[q] * (q + 3) * 4));
+        RAMA_TRY(find_cycles(*ctx, g, max_cycle_len, shortest_only != 0, false, cyc));
+        for (int q = 0; q < lists; ++q)
+            if (cyc.n[q] > 0) RAMA_TRY(copy_out(*ctx, cycles[q], cyc.v[q].get(), (size_t)cyc.n[q] * (q + 3) * 4));
         return finish(*ctx, RAMA_OK);
     };
     return finish(*ctx, body());
 }
 
 rama_status rama_message_passing(rama_ctx *ctx, int32_t n_nodes, int64_t n_edges, const int32_t *i, const int32_t *j,
-                                 const float *c, const int32_t *cycles3, int64_t n3, const int32_t *cycles4,
-                                 int64_t n4, const int32_t *cycles5, int64_t n5, int32_t k_iters, int64_t edge_cap,
+                                 const float *c, int32_t max_cycle_len, const int32_t *const *cycles,
+                                 const int64_t *n_cycles, int32_t k_iters, int64_t edge_cap,
                                  int32_t *i_out, int32_t *j_out, float *c_out, int64_t *n_edges_out,
                                  double *lower_bound, double *lb_trace)
 {
     if (!ctx) return RAMA_ERR_INVALID_ARG;
-    if (bad_graph_args(n_nodes, n_edges, i, j, c) || !n_edges_out || k_iters < 0 || edge_cap < 0 || n3 < 0 || n4 < 0 ||
-        n5 < 0 || (edge_cap > 0 && (!i_out || !j_out || !c_out)))
+    if (bad_graph_args(n_nodes, n_edges, i, j, c) || !n_edges_out || k_iters < 0 || edge_cap < 0 ||
+        max_cycle_len < 2 || max_cycle_len > kMaxCycleLen || (max_cycle_len > 2 && (!cycles || !n_cycles)) ||
+        (edge_cap > 0 && (!i_out || !j_out || !c_out)))
         return fail(*ctx, RAMA_ERR_INVALID_ARG, "rama_message_passing: bad arguments");
     auto body = [&]() -> rama_status {
         Graph g, out;
         RAMA_TRY(canonicalise(*ctx, n_nodes, n_edges, i, j, c, g));
-        RAMA_TRY(dual_update(*ctx, g, cycles3, n3, cycles4, n4, cycles5, n5, true, k_iters, out, lower_bound, lb_trace,
+        RAMA_TRY(dual_update(*ctx, g, max_cycle_len - 2, cycles, n_cycles, true, k_iters, out, lower_bound, lb_trace,
                              nullptr));
         *n_edges_out = out.m;
         if (out.m > edge_cap)
@@ -378,6 +393,8 @@ rama_status rama_solve(rama_ctx *ctx, int32_t n_nodes, int64_t n_edges, const in
     if (!ctx) return RAMA_ERR_INVALID_ARG;
     if (bad_graph_args(n_nodes, n_edges, i, j, c) || !params || (n_nodes > 0 && !labels))
         return fail(*ctx, RAMA_ERR_INVALID_ARG, "rama_solve: bad arguments");
+    if (params->max_cycle_len_first > RAMA_MAX_CYCLE_LEN || params->max_cycle_len_later > RAMA_MAX_CYCLE_LEN)
+        return fail(*ctx, RAMA_ERR_INVALID_ARG, "rama_solve: cycle length beyond RAMA_MAX_CYCLE_LEN");
     return finish(*ctx, solve_impl(*ctx, n_nodes, n_edges, i, j, c, *params, labels, primal_cost, lower_bound, stats));
 }
 

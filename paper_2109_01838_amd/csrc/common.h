@@ -277,9 +277,12 @@ struct Graph {
     Buf<float> c;
 };
 
+constexpr int kMaxCycleLen = RAMA_MAX_CYCLE_LEN;
+constexpr int kCycleLists = kMaxCycleLen - 2;   // list k holds the (k+3)-cycles
+
 struct CycleLists {
-    int64_t n[3] = {0, 0, 0};
-    Buf<int32_t> v[3];  // [L*n[L-3]]
+    int64_t n[kCycleLists] = {};
+    Buf<int32_t> v[kCycleLists];  // [L*n[L-3]]
 };
 
 // ---- stage entry points on canonical device graphs (defined in the stage files) ----
@@ -287,16 +290,18 @@ struct CycleLists {
 // a0: any edge list -> canonical graph
 rama_status canonicalise(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const int32_t *j, const float *c, Graph &out);
 
-// a1: conflicted cycles of lengths 3..max_len.  With count_only the lists stay empty.
-rama_status find_cycles(Ctx &ctx, const Graph &g, int max_len, bool count_only, CycleLists &out);
+// a1: conflicted cycles of lengths 3..max_len; shortest_only keeps, per repulsive edge, only the
+// cycles of its smallest length.  With count_only the lists stay empty.
+rama_status find_cycles(Ctx &ctx, const Graph &g, int max_len, bool shortest_only, bool count_only, CycleLists &out);
 
 // a2+a3: triangulate, k iterations of message passing; `out` = augmented graph with reduced costs
 struct DualInfo {
     int64_t n_triangles = 0;
 };
-rama_status dual_update(Ctx &ctx, const Graph &g, const int32_t *c3, int64_t n3, const int32_t *c4, int64_t n4,
-                        const int32_t *c5, int64_t n5, bool validate_cycles, int k_iters, Graph &out,
-                        double *lower_bound, double *lb_trace, DualInfo *info);
+// cycles[k] / n_cycles[k]: device list and number of the (k+3)-cycles, k < lists
+rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *const *cycles, const int64_t *n_cycles,
+                        bool validate_cycles, int k_iters, Graph &out, double *lower_bound, double *lb_trace,
+                        DualInfo *info);
 
 // a4..a6: one primal update.  fmap[n] -> [0,n_new); n_matched = |S|.  If |S|==0 nothing else is produced.
 rama_status contract_once(Ctx &ctx, const Graph &g, float tau, int rounds_cap, float forest_ratio, Buf<int32_t> &fmap,

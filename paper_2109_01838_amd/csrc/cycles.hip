@@ -127,107 +127,259 @@ struct EndRow {
     }
 };
 
-// Depth-first walk v0 -> v1 -> v2 -> v3 along N+, closing on N+(vL) at every depth:
-//   v1 in N+(vL)                      -> 3-cycle (v0,v1,vL)
-//   v2 in N+(vL)                      -> 4-cycle (v0,v1,v2,vL)
-//   v3 in N+(vL), v3 != v1            -> 5-cycle (v0,v1,v2,v3,vL)   (the appendix algorithm's
-//                                        pairs (v1,v3) with common neighbour v2, visited path-first)
-// vL and v0 are never in N+(vL) / N+(v0) of a repulsive edge, which settles the other
-// distinctness conditions.  Rows are ascending, so every list comes out in path order.
-template <typename Emit>
+// Depth-first walk v0 -> v1 -> v2 -> ... along N+, closing on N+(vL) at every depth: a node v_K
+// reached over K attractive hops that lies in N+(vL) closes the (K+2)-cycle (v0,..,v_K,vL).  For
+// length 5 these are the appendix algorithm's pairs (v1,v3) with common neighbour v2, visited
+// path-first.  vL and v0 are never in N+(vL) / N+(v0) of a repulsive edge and a row never holds its
+// own node, so a closing node only has to differ from the inner path nodes; a node the walk
+// continues through must also differ from v0 and vL.  Rows are ascending, so every list comes out
+// in path order.  The recursion is over a compile-time depth: it unrolls into nested loops with
+// the path in registers.
+template <int K, int MAXL, typename Emit>
+__device__ __forceinline__ void extend_path(const Adj &g, const EndRow &end, int32_t vl, int max_len,
+                                            int32_t (&path)[MAXL], Emit &emit)
+{
+    const int32_t tail = path[K - 1];
+    const int32_t r0 = g.ptr[tail], r1 = g.ptr[tail + 1];
+    for (int32_t p = r0; p < r1; ++p) {
+        const int32_t v = g.nb[p];
+        bool inner = false;
+#pragma unroll
+        for (int q = 1; q < K - 1; ++q) inner |= (path[q] == v);
+        if (inner) continue;
+        if (end.has(v)) { path[K] = v; emit.template cycle<K + 2>(path); }
+        if constexpr (K + 3 <= MAXL) {
+            if (K + 3 > max_len || v == vl || v == path[0]) continue;
+            path[K] = v;
+            extend_path<K + 1, MAXL>(g, end, vl, max_len, path, emit);
+        }
+    }
+}
+
+template <int MAXL, typename Emit>
 __device__ __forceinline__ void enumerate_cycles(const Adj &g, int32_t v0, int32_t vl, int max_len, Emit &emit)
 {
+    int32_t path[MAXL];
+    path[0] = v0;
     if (max_len <= 3) {
-        intersect_rows(g, v0, vl, [&](int32_t v1) { emit.c3(v1); });
+        intersect_rows(g, v0, vl, [&](int32_t v1) { path[1] = v1; emit.template cycle<3>(path); });
         return;
     }
     EndRow end;
     end.load(g, vl);
     if (end.b0 == end.b1) return;
-    const int32_t r0 = g.ptr[v0], r0e = g.ptr[v0 + 1];
-    for (int32_t p = r0; p < r0e; ++p) {
-        const int32_t v1 = g.nb[p];
-        if (end.has(v1)) emit.c3(v1);
-        const int32_t r1 = g.ptr[v1], r1e = g.ptr[v1 + 1];
-        for (int32_t q = r1; q < r1e; ++q) {
-            const int32_t v2 = g.nb[q];
-            if (v2 == v0) continue;
-            if (end.has(v2)) emit.c4(v1, v2);
-            if (max_len < 5 || v2 == vl) continue;
-            const int32_t r2 = g.ptr[v2], r2e = g.ptr[v2 + 1];
-            for (int32_t t = r2; t < r2e; ++t) {
-                const int32_t v3 = g.nb[t];
-                if (v3 != v1 && end.has(v3)) emit.c5(v1, v2, v3);
-            }
-        }
-    }
+    extend_path<1, MAXL>(g, end, vl, max_len, path, emit);
 }
 
+template <int MAXL>
 struct CountEmit {
-    uint32_t n3 = 0, n4 = 0, n5 = 0;
-    __device__ __forceinline__ void c3(int32_t) { ++n3; }
-    __device__ __forceinline__ void c4(int32_t, int32_t) { ++n4; }
-    __device__ __forceinline__ void c5(int32_t, int32_t, int32_t) { ++n5; }
-};
-
-struct FillEmit {
-    int32_t v0, vl;
-    int32_t *o3, *o4, *o5;
-    __device__ __forceinline__ void c3(int32_t v1) { o3[0] = v0; o3[1] = v1; o3[2] = vl; o3 += 3; }
-    __device__ __forceinline__ void c4(int32_t v1, int32_t v2) { o4[0] = v0; o4[1] = v1; o4[2] = v2; o4[3] = vl; o4 += 4; }
-    __device__ __forceinline__ void c5(int32_t v1, int32_t v2, int32_t v3)
+    uint32_t n[MAXL - 2];
+    __device__ __forceinline__ void clear()
     {
-        o5[0] = v0; o5[1] = v1; o5[2] = v2; o5[3] = v3; o5[4] = vl; o5 += 5;
+#pragma unroll
+        for (int k = 0; k < MAXL - 2; ++k) n[k] = 0;
+    }
+    template <int L>
+    __device__ __forceinline__ void cycle(const int32_t (&)[MAXL])
+    {
+        if constexpr (MAXL > 5) n[L - 3] += (n[L - 3] != 0xffffffffu);   // saturates; the host reports it
+        else ++n[L - 3];
     }
 };
 
+template <int MAXL>
+struct FillEmit {
+    int32_t vl;
+    int32_t *o[MAXL - 2];
+    template <int L>
+    __device__ __forceinline__ void cycle(const int32_t (&path)[MAXL])
+    {
+        int32_t *w = o[L - 3];
+#pragma unroll
+        for (int q = 0; q < L - 1; ++q) w[q] = path[q];
+        w[L - 1] = vl;
+        o[L - 3] = w + L;
+    }
+};
+
+// per-list arrays of one repulsive-edge table: list k (the (k+3)-cycles) starts at k*stride
+template <typename T, int N>
+struct ListPtrs {
+    T *p[N];
+};
+
+// counts per repulsive edge and length.  shortest_only: deepen the walk one length at a time
+// and stop at the first length that closes a cycle (the hop distance in (V,E+) plus one); only
+// that length's count is kept.
+template <int MAXL>
 __global__ __launch_bounds__(kBlock) void k_count_cycles(size_t nr, const int32_t *ri, const int32_t *rj, Adj g,
-                                                         int max_len, uint32_t *c3, uint32_t *c4, uint32_t *c5)
+                                                         int max_len, int shortest_only,
+                                                         ListPtrs<uint32_t, MAXL - 2> cnt)
 {
     size_t r = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (r >= nr) return;
-    CountEmit em;
-    enumerate_cycles(g, ri[r], rj[r], max_len, em);
-    c3[r] = em.n3; c4[r] = em.n4; c5[r] = em.n5;
+    CountEmit<MAXL> em;
+    em.clear();
+    if (!shortest_only) {
+        enumerate_cycles<MAXL>(g, ri[r], rj[r], max_len, em);
+    } else {
+        for (int L = 3; L <= max_len; ++L) {
+            em.clear();
+            enumerate_cycles<MAXL>(g, ri[r], rj[r], L, em);
+            if (em.n[L - 3]) break;
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < MAXL - 2; ++k)
+        if (k + 3 <= max_len) cnt.p[k][r] = em.n[k];
 }
 
+template <int MAXL>
 struct HasCycles {
-    static constexpr int bytes = 12;   // bytes read per item
-    static constexpr const char *tag = "HasCycles";
-    const uint32_t *c3, *c4, *c5;
-    __device__ __forceinline__ uint32_t operator()(size_t r) const { return (c3[r] | c4[r] | c5[r]) ? 1u : 0u; }
+    static constexpr int bytes = 4 * (MAXL - 2);   // bytes read per item
+    static constexpr const char *tag = MAXL > 5 ? "HasCycles7" : "HasCycles";
+    ListPtrs<uint32_t, MAXL - 2> cnt;
+    int lists;
+    __device__ __forceinline__ uint32_t operator()(size_t r) const
+    {
+        uint32_t any = 0;
+#pragma unroll
+        for (int k = 0; k < MAXL - 2; ++k)
+            if (k < lists) any |= cnt.p[k][r];
+        return any ? 1u : 0u;
+    }
 };
 
-__global__ __launch_bounds__(kBlock) void k_collect_hits(size_t nr, const uint32_t *c3, const uint32_t *c4,
-                                                         const uint32_t *c5, const uint32_t *pos, uint32_t *hit)
+template <int MAXL>
+__global__ __launch_bounds__(kBlock) void k_collect_hits(size_t nr, HasCycles<MAXL> has, const uint32_t *pos,
+                                                         uint32_t *hit)
 {
     size_t r = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    if (r < nr && (c3[r] | c4[r] | c5[r])) hit[pos[r]] = (uint32_t)r;
+    if (r < nr && has(r)) hit[pos[r]] = (uint32_t)r;
+}
+
+// a count that saturated: flag[0] = 1
+template <int MAXL>
+__global__ __launch_bounds__(kBlock) void k_check_saturated(size_t nr, ListPtrs<uint32_t, MAXL - 2> cnt, int lists,
+                                                            int32_t *flag)
+{
+    size_t r = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (r >= nr) return;
+    bool sat = false;
+#pragma unroll
+    for (int k = 0; k < MAXL - 2; ++k)
+        if (k < lists) sat |= (cnt.p[k][r] == 0xffffffffu);
+    if (sat) *flag = 1;
 }
 
 // second walk, only over the repulsive edges that have cycles and only as deep as their
 // longest cycle; writes every list at the offsets of the scan
+template <int MAXL>
 __global__ __launch_bounds__(kBlock) void k_fill_cycles(size_t nh, const uint32_t *hit, const int32_t *ri,
-                                                        const int32_t *rj, Adj g, const uint32_t *c4,
-                                                        const uint32_t *c5, const uint64_t *off3, const uint64_t *off4,
-                                                        const uint64_t *off5, int32_t *out3, int32_t *out4,
-                                                        int32_t *out5)
+                                                        const int32_t *rj, Adj g, int lists,
+                                                        ListPtrs<uint32_t, MAXL - 2> cnt,
+                                                        ListPtrs<uint64_t, MAXL - 2> off,
+                                                        ListPtrs<int32_t, MAXL - 2> out)
 {
     size_t h = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (h >= nh) return;
     const uint32_t r = hit[h];
-    const int depth = c5[r] ? 5 : (c4[r] ? 4 : 3);
-    FillEmit em{ri[r], rj[r], out3 + 3 * off3[r], out4 + 4 * off4[r], out5 + 5 * off5[r]};
-    enumerate_cycles(g, em.v0, em.vl, depth, em);
+    int depth = 3;
+    FillEmit<MAXL> em;
+    em.vl = rj[r];
+#pragma unroll
+    for (int k = 0; k < MAXL - 2; ++k) {
+        em.o[k] = nullptr;
+        if (k < lists) {
+            if (cnt.p[k][r]) depth = k + 3;
+            em.o[k] = out.p[k] + (size_t)(k + 3) * off.p[k][r];
+        }
+    }
+    enumerate_cycles<MAXL>(g, ri[r], em.vl, depth, em);
+}
+
+// count, scan, fill for walks of at most MAXL nodes
+template <int MAXL>
+rama_status count_and_fill(Ctx &ctx, size_t mr, const int32_t *ri, const int32_t *rj, Adj adj, int32_t n, size_t mp,
+                           int max_len, bool shortest_only, bool count_only, CycleLists &out)
+{
+    constexpr int NL = MAXL - 2;
+    const int lists = max_len - 2;
+    Buf<uint32_t> cnt[NL];
+    Buf<uint64_t> off[NL];
+    ListPtrs<uint32_t, NL> cp;
+    ListPtrs<uint64_t, NL> op;
+    ListPtrs<int32_t, NL> vp;
+    for (int k = 0; k < NL; ++k) {
+        cp.p[k] = nullptr; op.p[k] = nullptr; vp.p[k] = nullptr;
+        if (k >= lists) continue;
+        RAMA_TRY(cnt[k].alloc(ctx, mr));
+        RAMA_TRY(off[k].alloc(ctx, mr + 1));
+        cp.p[k] = cnt[k].get(); op.p[k] = off[k].get();
+    }
+    {
+        ProfScope ps_(ctx, "k_count_cycles", (double)(mr * (8 + 4 * (size_t)lists) + ((size_t)n + 1) * 4 + mp * 8));
+        k_count_cycles<MAXL><<<grid_for(mr), kBlock, 0, ctx.stream>>>(mr, ri, rj, adj, max_len, shortest_only ? 1 : 0, cp);
+    }
+    LAUNCH_TRY(ctx, "count_cycles");
+    if (MAXL > 5) {
+        Buf<int32_t> flag;
+        RAMA_TRY(flag.alloc(ctx, 1));
+        RAMA_TRY(fill<int32_t>(ctx, flag.get(), 0, 1));
+        {
+            ProfScope ps_(ctx, "k_check_saturated", (double)(mr * 4 * (size_t)lists));
+            k_check_saturated<MAXL><<<grid_for(mr), kBlock, 0, ctx.stream>>>(mr, cp, lists, flag.get());
+        }
+        LAUNCH_TRY(ctx, "check_saturated");
+        int32_t sat = 0;
+        RAMA_TRY(read_back(ctx, &sat, flag.get(), 4));
+        if (sat) return fail(ctx, RAMA_ERR_CAPACITY, "a repulsive edge closes 2^32 or more cycles of one length");
+    }
+    uint64_t tot[NL], all = 0;
+    for (int k = 0; k < lists; ++k) {
+        RAMA_TRY((exclusive_scan<uint64_t>(ctx, PtrInput<uint32_t>{cnt[k].get()}, off[k].get(), mr)));
+        RAMA_TRY(read_back(ctx, &tot[k], off[k].get() + mr, 8));
+        out.n[k] = (int64_t)tot[k];
+        all += tot[k];
+    }
+    if (count_only) return RAMA_OK;
+    double list_bytes = 0.0;
+    for (int k = 0; k < lists; ++k) {
+        if ((uint64_t)(k + 3) * tot[k] >= (uint64_t(1) << 31))
+            return fail(ctx, RAMA_ERR_CAPACITY, "cycle list reaches 2^31 entries");
+        RAMA_TRY(out.v[k].alloc(ctx, (size_t)(k + 3) * tot[k]));
+        vp.p[k] = out.v[k].get();
+        list_bytes += 4.0 * (k + 3) * (double)tot[k];
+    }
+    if (all == 0) return RAMA_OK;
+    Buf<uint32_t> hpos, hit;
+    RAMA_TRY(hpos.alloc(ctx, mr + 1));
+    HasCycles<MAXL> has{cp, lists};
+    RAMA_TRY((exclusive_scan<uint32_t>(ctx, has, hpos.get(), mr)));
+    uint32_t nh = 0;
+    RAMA_TRY(read_back(ctx, &nh, hpos.get() + mr, 4));
+    RAMA_TRY(hit.alloc(ctx, nh));
+    {
+        ProfScope ps_(ctx, "k_collect_hits", (double)(mr * (4 + 4 * (size_t)lists) + (size_t)nh * 4));
+        k_collect_hits<MAXL><<<grid_for(mr), kBlock, 0, ctx.stream>>>(mr, has, hpos.get(), hit.get());
+    }
+    LAUNCH_TRY(ctx, "collect_hits");
+    {
+        ProfScope ps_(ctx, "k_fill_cycles", (double)((size_t)nh * (12 + 12 * (size_t)lists) + ((size_t)n + 1) * 4 + mp * 8) + list_bytes);
+        k_fill_cycles<MAXL><<<grid_for(nh), kBlock, 0, ctx.stream>>>(nh, hit.get(), ri, rj, adj, lists, cp, op, vp);
+    }
+    LAUNCH_TRY(ctx, "fill_cycles");
+    return RAMA_OK;
 }
 
 }  // namespace
 
-rama_status find_cycles(Ctx &ctx, const Graph &g, int max_len, bool count_only, CycleLists &out)
+rama_status find_cycles(Ctx &ctx, const Graph &g, int max_len, bool shortest_only, bool count_only, CycleLists &out)
 {
-    for (int k = 0; k < 3; ++k) { out.n[k] = 0; out.v[k].reset(); }
+    for (int k = 0; k < kCycleLists; ++k) { out.n[k] = 0; out.v[k].reset(); }
     const size_t m = (size_t)g.m;
     if (m == 0 || max_len < 3) return RAMA_OK;
+    if (max_len > kMaxCycleLen) return fail(ctx, RAMA_ERR_INVALID_ARG, "cycle length beyond the supported maximum");
     // sign partition
     Buf<uint32_t> ppos, npos;
     RAMA_TRY(ppos.alloc(ctx, m + 1));
@@ -278,52 +430,10 @@ rama_status find_cycles(Ctx &ctx, const Graph &g, int max_len, bool count_only, 
     LAUNCH_TRY(ctx, "fill_adj");
     pi.reset(); pj.reset(); lkey.reset(); lval.reset(); up_ptr.reset(); low_ptr.reset();
     Adj adj{rowptr.get(), nb.get()};
-    // count, scan, fill
-    Buf<uint32_t> cnt[3];
-    Buf<uint64_t> off[3];
-    for (int k = 0; k < 3; ++k) {
-        RAMA_TRY(cnt[k].alloc(ctx, mr));
-        RAMA_TRY(off[k].alloc(ctx, (size_t)mr + 1));
-    }
-    {
-        ProfScope ps_(ctx, "k_count_cycles", (double)((size_t)mr * 20 + ((size_t)n + 1) * 4 + (size_t)mp * 8));
-        k_count_cycles<<<grid_for(mr), kBlock, 0, ctx.stream>>>(mr, ri.get(), rj.get(), adj, max_len, cnt[0].get(),
-                                                           cnt[1].get(), cnt[2].get());
-    }
-    LAUNCH_TRY(ctx, "count_cycles");
-    uint64_t tot[3];
-    for (int k = 0; k < 3; ++k) {
-        RAMA_TRY((exclusive_scan<uint64_t>(ctx, PtrInput<uint32_t>{cnt[k].get()}, off[k].get(), (size_t)mr)));
-        RAMA_TRY(read_back(ctx, &tot[k], off[k].get() + mr, 8));
-        out.n[k] = (int64_t)tot[k];
-    }
-    if (count_only) return RAMA_OK;
-    for (int k = 0; k < 3; ++k) {
-        if ((uint64_t)(k + 3) * tot[k] >= (uint64_t(1) << 31))
-            return fail(ctx, RAMA_ERR_CAPACITY, "cycle list reaches 2^31 entries");
-        RAMA_TRY(out.v[k].alloc(ctx, (size_t)(k + 3) * tot[k]));
-    }
-    if (tot[0] + tot[1] + tot[2] == 0) return RAMA_OK;
-    Buf<uint32_t> hpos, hit;
-    RAMA_TRY(hpos.alloc(ctx, (size_t)mr + 1));
-    RAMA_TRY((exclusive_scan<uint32_t>(ctx, HasCycles{cnt[0].get(), cnt[1].get(), cnt[2].get()}, hpos.get(), (size_t)mr)));
-    uint32_t nh = 0;
-    RAMA_TRY(read_back(ctx, &nh, hpos.get() + mr, 4));
-    RAMA_TRY(hit.alloc(ctx, nh));
-    {
-        ProfScope ps_(ctx, "k_collect_hits", (double)((size_t)mr * 16 + (size_t)nh * 4));
-        k_collect_hits<<<grid_for(mr), kBlock, 0, ctx.stream>>>(mr, cnt[0].get(), cnt[1].get(), cnt[2].get(), hpos.get(),
-                                                               hit.get());
-    }
-    LAUNCH_TRY(ctx, "collect_hits");
-    {
-        ProfScope ps_(ctx, "k_fill_cycles", (double)((size_t)nh * 44 + ((size_t)n + 1) * 4 + (size_t)mp * 8 + 12.0 * tot[0] + 16.0 * tot[1] + 20.0 * tot[2]));
-        k_fill_cycles<<<grid_for(nh), kBlock, 0, ctx.stream>>>(nh, hit.get(), ri.get(), rj.get(), adj, cnt[1].get(),
-                                                              cnt[2].get(), off[0].get(), off[1].get(), off[2].get(),
-                                                              out.v[0].get(), out.v[1].get(), out.v[2].get());
-    }
-    LAUNCH_TRY(ctx, "fill_cycles");
-    return RAMA_OK;
+    if (max_len <= 5)
+        return count_and_fill<5>(ctx, (size_t)mr, ri.get(), rj.get(), adj, n, (size_t)mp, max_len, shortest_only, count_only, out);
+    return count_and_fill<kMaxCycleLen>(ctx, (size_t)mr, ri.get(), rj.get(), adj, n, (size_t)mp, max_len, shortest_only,
+                                        count_only, out);
 }
 
 }  // namespace rama

@@ -27,42 +27,41 @@ namespace {
 // cycle access: one flat index space over the fan pieces of all cycles
 // ---------------------------------------------------------------------------------------------
 struct CycleSet {
-    const int32_t *c3, *c4, *c5;
-    int64_t n3, n4, n5;
+    const int32_t *c[kCycleLists];   // list k: the (k+3)-cycles
+    size_t cyc_end[kCycleLists];     // running totals over the lists: cycles,
+    size_t fan_end[kCycleLists];     // fan triangles (k+1 per cycle)
+    size_t chord_end[kCycleLists];   // and chords (k per cycle)
 };
 
-// q-th chord: 4-cycles give one (v0,v2), 5-cycles two (v0,v2),(v0,v3)
+// q-th chord: an L-cycle gives the L-3 chords (v0,v_m), m = 2..L-2
 __device__ __forceinline__ void chord_of(const CycleSet &s, size_t q, int32_t &a, int32_t &b)
 {
-    if (q < (size_t)s.n4) {
-        const int32_t *v = s.c4 + 4 * q;
-        a = v[0]; b = v[2];
-    } else {
-        size_t r = q - (size_t)s.n4;
-        const int32_t *v = s.c5 + 5 * (r >> 1);
-        a = v[0]; b = v[2 + (r & 1)];
+    a = b = 0;
+#pragma unroll
+    for (int k = 1; k < kCycleLists; ++k) {
+        if (q < s.chord_end[k]) {
+            const size_t r = q - s.chord_end[k - 1];
+            const int32_t *v = s.c[k] + (size_t)(k + 3) * (r / k);
+            a = v[0]; b = v[2 + (int)(r % k)];
+            return;
+        }
     }
 }
 
-// q-th fan triangle (unsorted nodes)
+// q-th fan triangle (unsorted nodes): an L-cycle gives {v0,v_m,v_{m+1}}, m = 1..L-2
 __device__ __forceinline__ void fan_triangle(const CycleSet &s, size_t q, int32_t &a, int32_t &b, int32_t &c)
 {
-    if (q < (size_t)s.n3) {
-        const int32_t *v = s.c3 + 3 * q;
-        a = v[0]; b = v[1]; c = v[2];
-        return;
+    a = b = c = 0;
+#pragma unroll
+    for (int k = 0; k < kCycleLists; ++k) {
+        if (q < s.fan_end[k]) {
+            const size_t r = q - (k ? s.fan_end[k - 1] : 0);
+            const int32_t *v = s.c[k] + (size_t)(k + 3) * (r / (k + 1));
+            const int mm = 1 + (int)(r % (k + 1));
+            a = v[0]; b = v[mm]; c = v[mm + 1];
+            return;
+        }
     }
-    q -= (size_t)s.n3;
-    if (q < 2 * (size_t)s.n4) {
-        const int32_t *v = s.c4 + 4 * (q >> 1);
-        int mm = 1 + (int)(q & 1);
-        a = v[0]; b = v[mm]; c = v[mm + 1];
-        return;
-    }
-    q -= 2 * (size_t)s.n4;
-    const int32_t *v = s.c5 + 5 * (q / 3);
-    int mm = 1 + (int)(q % 3);
-    a = v[0]; b = v[mm]; c = v[mm + 1];
 }
 
 __device__ __forceinline__ void sort3(int32_t &a, int32_t &b, int32_t &c)
@@ -78,14 +77,13 @@ __global__ __launch_bounds__(kBlock) void k_validate_cycles(CycleSet s, int32_t 
                                                             const int32_t *j, int32_t *flag)
 {
     size_t q = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    size_t total = (size_t)(s.n3 + s.n4 + s.n5);
-    if (q >= total) return;
-    const int32_t *v;
-    int L;
-    if (q < (size_t)s.n3) { v = s.c3 + 3 * q; L = 3; }
-    else if (q < (size_t)(s.n3 + s.n4)) { v = s.c4 + 4 * (q - s.n3); L = 4; }
-    else { v = s.c5 + 5 * (q - s.n3 - s.n4); L = 5; }
-    int32_t x[5];
+    if (q >= s.cyc_end[kCycleLists - 1]) return;
+    const int32_t *v = nullptr;
+    int L = 0;
+#pragma unroll
+    for (int k = kCycleLists - 1; k >= 0; --k)
+        if (q < s.cyc_end[k]) { v = s.c[k] + (size_t)(k + 3) * (q - (k ? s.cyc_end[k - 1] : 0)); L = k + 3; }
+    int32_t x[kMaxCycleLen];
     bool bad = false;
     for (int a = 0; a < L; ++a) {
         x[a] = v[a];
@@ -354,16 +352,29 @@ rama_status copy_graph(Ctx &ctx, const Graph &g, Graph &out)
 
 }  // namespace
 
-rama_status dual_update(Ctx &ctx, const Graph &g, const int32_t *c3, int64_t n3, const int32_t *c4, int64_t n4,
-                        const int32_t *c5, int64_t n5, bool validate_cycles, int k_iters, Graph &out,
-                        double *lower_bound, double *lb_trace, DualInfo *info)
+rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *const *cycles, const int64_t *n_cycles,
+                        bool validate_cycles, int k_iters, Graph &out, double *lower_bound, double *lb_trace,
+                        DualInfo *info)
 {
-    if (n3 < 0 || n4 < 0 || n5 < 0 || k_iters < 0) return fail(ctx, RAMA_ERR_INVALID_ARG, "message passing: negative count");
-    if ((n3 > 0 && !c3) || (n4 > 0 && !c4) || (n5 > 0 && !c5))
-        return fail(ctx, RAMA_ERR_INVALID_ARG, "message passing: null cycle list");
+    if (lists < 0 || lists > kCycleLists || k_iters < 0 || (lists > 0 && (!cycles || !n_cycles)))
+        return fail(ctx, RAMA_ERR_INVALID_ARG, "message passing: bad cycle lists or iteration count");
+    CycleSet cs;
+    size_t ncyc = 0, nfan = 0, nch = 0;
+    double cycle_bytes = 0.0;
+    for (int k = 0; k < kCycleLists; ++k) {
+        cs.c[k] = nullptr;
+        if (k < lists) {
+            if (n_cycles[k] < 0) return fail(ctx, RAMA_ERR_INVALID_ARG, "message passing: negative count");
+            if (n_cycles[k] > 0 && !cycles[k]) return fail(ctx, RAMA_ERR_INVALID_ARG, "message passing: null cycle list");
+            cs.c[k] = cycles[k];
+            ncyc += (size_t)n_cycles[k];
+            nfan += (size_t)(k + 1) * (size_t)n_cycles[k];
+            nch += (size_t)k * (size_t)n_cycles[k];
+            cycle_bytes += 4.0 * (k + 3) * (double)n_cycles[k];
+        }
+        cs.cyc_end[k] = ncyc; cs.fan_end[k] = nfan; cs.chord_end[k] = nch;
+    }
     const size_t m = (size_t)g.m;
-    const size_t nfan = (size_t)n3 + 2 * (size_t)n4 + 3 * (size_t)n5;
-    const size_t nch = (size_t)n4 + 2 * (size_t)n5;
     if (3 * nfan >= (size_t(1) << 31) || m + nch >= (size_t(1) << 31))
         return fail(ctx, RAMA_ERR_CAPACITY, "triangle slots or augmented edges reach 2^31");
     if (info) info->n_triangles = 0;
@@ -380,7 +391,6 @@ rama_status dual_update(Ctx &ctx, const Graph &g, const int32_t *c3, int64_t n3,
     }
     const int32_t n = g.n;
     const int nbits = bits_for((uint64_t)n);
-    CycleSet cs{c3, c4, c5, n3, n4, n5};
     Buf<int32_t> flag;
     RAMA_TRY(flag.alloc(ctx, 1));
     RAMA_TRY(fill<int32_t>(ctx, flag.get(), 0, 1));
@@ -390,9 +400,8 @@ rama_status dual_update(Ctx &ctx, const Graph &g, const int32_t *c3, int64_t n3,
     RAMA_TRY((row_bounds<int32_t, int32_t>(ctx, g.i.get(), m, n, rowptr.get())));
     if (validate_cycles) {
         {
-            ProfScope ps_(ctx, "k_validate_cycles", (double)(12.0 * n3 + 16.0 * n4 + 20.0 * n5));
-            k_validate_cycles<<<grid_for((size_t)(n3 + n4 + n5)), kBlock, 0, ctx.stream>>>(cs, n, rowptr.get(), g.j.get(),
-                                                                                     flag.get());
+            ProfScope ps_(ctx, "k_validate_cycles", cycle_bytes);
+            k_validate_cycles<<<grid_for(ncyc), kBlock, 0, ctx.stream>>>(cs, n, rowptr.get(), g.j.get(), flag.get());
         }
         LAUNCH_TRY(ctx, "validate_cycles");
         int32_t hf = 0;

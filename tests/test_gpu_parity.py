@@ -67,8 +67,43 @@ def test_cycles_bit_exact(rama, oracle32, name, lmax):
         g = dict(g, i=g["i"][:2500], j=g["j"][:2500], c=g["c"][:2500])
     want = oracle32.find_conflicted_cycles(g["n_nodes"], g["i"], g["j"], g["c"], lmax)
     got = rama.find_conflicted_cycles(g["n_nodes"], g["i"], g["j"], g["c"], lmax)
-    for L in range(3):
+    assert len(got) == len(want) == lmax - 2
+    for L in range(lmax - 2):
         assert np.array_equal(np_(got[L]), want[L]), (name, lmax, L + 3, got[L].shape, want[L].shape)
+
+
+# cycles of length 6 and 7 (named as future work in Sec. 5) and the shortest-only separation; the
+# cases are the ones whose plain enumeration the oracle finishes in seconds
+LONG_CASES = [("cfg1", 7), ("grid3d_24", 7), ("random_sparse", 7), ("knn_20000", 7), ("knn_20000", 6),
+              ("grid2d_longrange_96", 6), ("messy", 6)]
+
+
+@pytest.mark.parametrize("name,lmax", LONG_CASES)
+def test_longer_cycles_bit_exact(rama, oracle32, name, lmax):
+    g = CASES[name]
+    want = oracle32.find_conflicted_cycles(g["n_nodes"], g["i"], g["j"], g["c"], lmax)
+    got = rama.find_conflicted_cycles(g["n_nodes"], g["i"], g["j"], g["c"], lmax)
+    assert len(got) == lmax - 2
+    for L in range(lmax - 2):
+        assert np.array_equal(np_(got[L]), want[L]), (name, lmax, L + 3, got[L].shape, want[L].shape)
+    print(name, lmax, [x.shape[0] for x in want])
+
+
+@pytest.mark.parametrize("name", list(CASES))
+@pytest.mark.parametrize("lmax", [3, 4, 5, 7])
+def test_shortest_only_cycles_bit_exact(rama, oracle32, name, lmax):
+    g = CASES[name]
+    if name in ("random_dense", "messy") and lmax == 7:
+        g = dict(g, i=g["i"][:1500], j=g["j"][:1500], c=g["c"][:1500])
+    want = oracle32.find_conflicted_cycles(g["n_nodes"], g["i"], g["j"], g["c"], lmax, shortest_only=True)
+    got = rama.find_conflicted_cycles(g["n_nodes"], g["i"], g["j"], g["c"], lmax, shortest_only=True)
+    for L in range(lmax - 2):
+        assert np.array_equal(np_(got[L]), want[L]), (name, lmax, L + 3, got[L].shape, want[L].shape)
+    # every repulsive edge appears with one length only
+    seen = {}
+    for L, x in enumerate(np_(q) for q in got):
+        for a, b in set(zip(x[:, 0].tolist(), x[:, -1].tolist())):
+            assert seen.setdefault((a, b), L) == L
 
 
 def test_cycles_capacity_protocol(rama):
@@ -77,18 +112,29 @@ def test_cycles_capacity_protocol(rama):
     from paper_2109_01838_amd import binding
     g = CASES["cfg1"]
     i, j, c = (torch.as_tensor(g[k], device="cuda") for k in ("i", "j", "c"))
-    cnt = (C.c_int64 * 3)()
-    st = rama.lib.rama_find_conflicted_cycles(rama.ctx, g["n_nodes"], i.numel(), i.data_ptr(), j.data_ptr(),
-                                              c.data_ptr(), 5, 0, 0, 0, None, None, None, cnt)
-    assert st == binding.RAMA_ERR_CAPACITY and cnt[1] > 0
+    cnt = (C.c_int64 * 5)()
+    args = (rama.ctx, g["n_nodes"], i.numel(), i.data_ptr(), j.data_ptr(), c.data_ptr())
+    st = rama.lib.rama_find_conflicted_cycles(*args, 5, 0, None, None, cnt)
+    assert st == binding.RAMA_ERR_CAPACITY and cnt[1] > 0 and cnt[0] == 0 and cnt[2] == 0
     buf = torch.full((4 * (cnt[1] - 1) + 1,), -7, dtype=torch.int32, device="cuda")
-    st = rama.lib.rama_find_conflicted_cycles(rama.ctx, g["n_nodes"], i.numel(), i.data_ptr(), j.data_ptr(),
-                                              c.data_ptr(), 5, 0, cnt[1] - 1, 0, None, buf.data_ptr(), None, cnt)
+    cap = (C.c_int64 * 3)(0, cnt[1] - 1, 0)
+    ptrs = (C.c_void_p * 3)(None, buf.data_ptr(), None)
+    st = rama.lib.rama_find_conflicted_cycles(*args, 5, 0, cap, ptrs, cnt)
     assert st == binding.RAMA_ERR_CAPACITY
     assert bool((buf == -7).all())          # nothing written on capacity failure
-    st = rama.lib.rama_find_conflicted_cycles(rama.ctx, g["n_nodes"], i.numel(), i.data_ptr(), j.data_ptr(),
-                                              c.data_ptr(), 6, 0, 0, 0, None, None, None, cnt)
-    assert st == binding.RAMA_ERR_INVALID_ARG
+    cap[1] = cnt[1]
+    buf = torch.full((4 * cnt[1] + 1,), -7, dtype=torch.int32, device="cuda")
+    ptrs[1] = buf.data_ptr()
+    st = rama.lib.rama_find_conflicted_cycles(*args, 5, 0, cap, ptrs, cnt)
+    assert st == binding.RAMA_OK and int(buf[-1]) == -7 and bool((buf[:-1] >= 0).all())
+    for bad_len in (2, binding.MAX_CYCLE_LEN + 1):
+        st = rama.lib.rama_find_conflicted_cycles(*args, bad_len, 0, None, None, cnt)
+        assert st == binding.RAMA_ERR_INVALID_ARG
+    cap[1] = -1
+    assert rama.lib.rama_find_conflicted_cycles(*args, 5, 0, cap, ptrs, cnt) == binding.RAMA_ERR_INVALID_ARG
+    cap[1] = 5
+    ptrs[1] = None
+    assert rama.lib.rama_find_conflicted_cycles(*args, 5, 0, cap, ptrs, cnt) == binding.RAMA_ERR_INVALID_ARG
 
 
 # --------------------------------------------------------------------------------------------
@@ -112,6 +158,20 @@ def test_message_passing_parity(rama, oracle32, name, k):
     # the arithmetic is ordered identically on both sides, so in practice the match is exact
     print(name, k, "max |dc| =", float(np.abs(np_(got["c"]) - want["c"]).max()) if want["c"].size else 0.0,
           "bit-exact:", bool(np.array_equal(np_(got["c"]), want["c"])))
+
+
+@pytest.mark.parametrize("name,lmax", LONG_CASES)
+@pytest.mark.parametrize("shortest", [False, True])
+def test_message_passing_parity_longer_cycles(rama, oracle32, name, lmax, shortest):
+    g = CASES[name]
+    n = g["n_nodes"]
+    cyc = oracle32.find_conflicted_cycles(n, g["i"], g["j"], g["c"], lmax, shortest_only=shortest)
+    want = oracle32.message_passing(n, g["i"], g["j"], g["c"], cyc, 5, trace=True)
+    got = rama.message_passing(n, g["i"], g["j"], g["c"], cyc, 5, trace=True)
+    assert np.array_equal(np_(got["i"]), want["i"]) and np.array_equal(np_(got["j"]), want["j"])
+    assert rel_close(np_(got["c"]), want["c"])
+    assert rel_close(got["lb_trace"], want["lb_trace"])
+    print(name, lmax, shortest, "edges", want["i"].size, "bit-exact:", bool(np.array_equal(np_(got["c"]), want["c"])))
 
 
 def test_message_passing_cycle_order_is_irrelevant(rama, oracle32):
@@ -245,7 +305,8 @@ def test_solve_end_to_end(rama, oracle32, name):
           want["rounds"], "primal", got["primal"], want["primal"], "LB", got["lower_bound"], want["lower_bound"])
 
 
-@pytest.mark.parametrize("variant", ["P", "PD+", "D", "PD-matching-only", "PD-forest-always"])
+@pytest.mark.parametrize("variant", ["P", "PD+", "D", "PD-matching-only", "PD-forest-always", "PD-shortest",
+                                     "PD-7-then-4", "PD-7-shortest"])
 def test_solver_variants(rama, oracle32, variant):
     from paper_2109_01838_amd import default_params
     g = CASES["knn_20000"]
@@ -254,9 +315,17 @@ def test_solver_variants(rama, oracle32, variant):
           "PD+": dict(max_cycle_len_later=5),
           "D": dict(max_rounds=1),
           "PD-matching-only": dict(forest_ratio=0.0),
-          "PD-forest-always": dict(forest_ratio=1.0)}[variant]
+          "PD-forest-always": dict(forest_ratio=1.0),
+          "PD-shortest": dict(shortest_only=True),
+          "PD-7-then-4": dict(max_cycle_len_first=7, max_cycle_len_later=4),
+          "PD-7-shortest": dict(max_cycle_len_first=7, max_cycle_len_later=7, shortest_only=True)}[variant]
     want = oracle32.solve(n, g["i"], g["j"], g["c"], **kw)
+    kw = {("shortest_cycles_only" if key == "shortest_only" else key): int(v) if key == "shortest_only" else v
+          for key, v in kw.items()}
     got = rama.solve(n, g["i"], g["j"], g["c"], default_params(**kw))
+    assert got["n_cycles_first"] == want["n_cycles_first"]
+    print(variant, "cycles", got["n_cycles_first"], "labels identical:", bool(np.array_equal(np_(got["labels"]), want["labels"])),
+          "primal", got["primal"], want["primal"], "LB", got["lower_bound"], want["lower_bound"])
     assert abs(got["lower_bound"] - want["lower_bound"]) <= REL * max(1.0, abs(want["lower_bound"]))
     assert abs(got["primal"] - want["primal"]) <= 5e-3 * max(1.0, abs(want["primal"]))
 

@@ -32,8 +32,32 @@ def test_params_default_and_struct_layout():
     assert (p.max_cycle_len_first, p.max_cycle_len_later, p.mp_iters_first, p.mp_iters_later) == (5, 3, 10, 5)
     assert p.matching_rounds_cap == 32 and p.contract_threshold == 0.0 and p.max_rounds == 0
     assert abs(p.forest_ratio - 0.1) < 1e-7
-    assert C.sizeof(binding.RamaParams) == 32
-    assert C.sizeof(binding.RamaStats) == 96
+    assert p.shortest_cycles_only == 0
+    assert C.sizeof(binding.RamaParams) == 36
+    assert C.sizeof(binding.RamaStats) == 112
+
+
+def test_binding_structs_match_the_header(tmp_path):
+    """sizeof / offsetof of every field as a C compiler sees include/rama.h vs the ctypes mirrors."""
+    import subprocess
+    from paper_2109_01838_amd import binding
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "rama.h"', 'int main(void) {',
+             'printf("%d\\n", RAMA_MAX_CYCLE_LEN);']
+    for cname, cls in (("rama_params", binding.RamaParams), ("rama_stats", binding.RamaStats)):
+        lines.append(f'printf("%zu\\n", sizeof({cname}));')
+        for field, _ in cls._fields_:
+            lines.append(f'printf("%zu\\n", offsetof({cname}, {field}));')
+    lines += ['return 0; }']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), "-o", str(exe), str(src)], check=True)
+    got = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    want = [binding.MAX_CYCLE_LEN]
+    for cls in (binding.RamaParams, binding.RamaStats):
+        want.append(C.sizeof(cls))
+        want += [getattr(cls, field).offset for field, _ in cls._fields_]
+    assert got == want
 
 
 def test_no_cpu_fallback_without_gpu():
