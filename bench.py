@@ -32,14 +32,15 @@ def make_workload(name):
     return inputs.make(name)
 
 
-def cpu_baseline(side):
+def cpu_baseline(side, cycle_len, shortest_only):
     """The CPU oracle, as it stands, on a cube of cfg5's recipe small enough for ~10-30 s of CPU work."""
     import oracle
     from paper_2109_01838_amd import inputs
     g = inputs.cfg5_crop(side)
     o = oracle.Oracle("f32")
     t0 = time.perf_counter()
-    r = o.solve(g["n_nodes"], g["i"], g["j"], g["c"])
+    r = o.solve(g["n_nodes"], g["i"], g["j"], g["c"], max_cycle_len_first=cycle_len[0],
+                max_cycle_len_later=cycle_len[1], shortest_only=shortest_only)
     dt = time.perf_counter() - t0
     return {"value": g["i"].size / dt, "unit": "edges/s", "cores": 1, "kind": "oracle",
             "sample": f"cfg5 recipe on a {side}^3 crop ({g['i'].size} edges), full solve, {dt:.1f} s, "
@@ -56,6 +57,10 @@ def main():
     ap.add_argument("--cpu-side", type=int, default=128, help="cube side of the oracle's timed sample (0 = skip)")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event timers")
     ap.add_argument("--max-rounds", type=int, default=0, help="stop the solver after this many rounds (0 = run to the end)")
+    ap.add_argument("--cycle-len", type=int, nargs=2, default=[5, 3], metavar=("FIRST", "LATER"),
+                    help="longest conflicted cycle separated in the first / later rounds (default: solver PD, 5 3)")
+    ap.add_argument("--shortest-only", action="store_true",
+                    help="per repulsive edge separate only its shortest conflicted cycles")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain 1 GiB device copy three times (reference reading for rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE runs)")
@@ -72,7 +77,11 @@ def main():
     dev = torch.device("cuda:0")
     i, j, c = (torch.as_tensor(g[k]).to(dev) for k in ("i", "j", "c"))
     rama = Rama("cuda:0")
-    params = default_params(max_rounds=args.max_rounds)
+    solver_name = ("PD" if args.cycle_len == [5, 3] and not args.shortest_only else "PD variant") + \
+        f" (cycles<={args.cycle_len[0]} then <={args.cycle_len[1]}" + (", shortest only" if args.shortest_only else "") + \
+        ", k=10 then 5)"
+    params = default_params(max_rounds=args.max_rounds, max_cycle_len_first=args.cycle_len[0],
+                            max_cycle_len_later=args.cycle_len[1], shortest_cycles_only=int(args.shortest_only))
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB read + 1 GiB written per copy
         dst = torch.empty_like(src)
@@ -137,7 +146,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": g["name"], "n_nodes": n, "n_edges": m, "solver": "PD (cycles<=5 then <=3, k=10 then 5)"},
+        "config": {"workload": g["name"], "n_nodes": n, "n_edges": m, "solver": solver_name},
         "solve_seconds": ms / 1e3, "primal": res["primal"], "lower_bound": res["lower_bound"], "gap": gap,
         "rounds": res["rounds"], "n_clusters": res["n_clusters"], "n_cycles_first": res["n_cycles_first"],
         "n_triangles_first": res["n_triangles_first"], "stage_ms_last_step": res["ms"],
@@ -149,7 +158,7 @@ def main():
                            "GBps": round(k["GBps"], 1), "frac_hbm": round(k["GBps"] / HBM_PEAK_GBS, 4),
                            "share": round(k["share"], 4)} for k in kernels[:16]]
     del labels
-    out["cpu_baseline"] = cpu_baseline(args.cpu_side) if args.cpu_side > 0 else None
+    out["cpu_baseline"] = cpu_baseline(args.cpu_side, args.cycle_len, args.shortest_only) if args.cpu_side > 0 else None
     print(json.dumps(out))
 
 

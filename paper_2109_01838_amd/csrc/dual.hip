@@ -28,36 +28,36 @@ namespace {
 // ---------------------------------------------------------------------------------------------
 struct CycleSet {
     const int32_t *c[kCycleLists];   // list k: the (k+3)-cycles
-    size_t cyc_end[kCycleLists];     // running totals over the lists: cycles,
-    size_t fan_end[kCycleLists];     // fan triangles (k+1 per cycle)
-    size_t chord_end[kCycleLists];   // and chords (k per cycle)
+    uint32_t cyc_end[kCycleLists];   // running totals over the lists (all below 2^31): cycles,
+    uint32_t fan_end[kCycleLists];   // fan triangles (k+1 per cycle)
+    uint32_t chord_end[kCycleLists]; // and chords (k per cycle)
 };
 
 // q-th chord: an L-cycle gives the L-3 chords (v0,v_m), m = 2..L-2
-__device__ __forceinline__ void chord_of(const CycleSet &s, size_t q, int32_t &a, int32_t &b)
+__device__ __forceinline__ void chord_of(const CycleSet &s, uint32_t q, int32_t &a, int32_t &b)
 {
     a = b = 0;
 #pragma unroll
     for (int k = 1; k < kCycleLists; ++k) {
         if (q < s.chord_end[k]) {
-            const size_t r = q - s.chord_end[k - 1];
-            const int32_t *v = s.c[k] + (size_t)(k + 3) * (r / k);
-            a = v[0]; b = v[2 + (int)(r % k)];
+            const uint32_t r = q - s.chord_end[k - 1], cyc = r / (uint32_t)k;
+            const int32_t *v = s.c[k] + (uint32_t)(k + 3) * cyc;
+            a = v[0]; b = v[2 + (r - cyc * (uint32_t)k)];
             return;
         }
     }
 }
 
 // q-th fan triangle (unsorted nodes): an L-cycle gives {v0,v_m,v_{m+1}}, m = 1..L-2
-__device__ __forceinline__ void fan_triangle(const CycleSet &s, size_t q, int32_t &a, int32_t &b, int32_t &c)
+__device__ __forceinline__ void fan_triangle(const CycleSet &s, uint32_t q, int32_t &a, int32_t &b, int32_t &c)
 {
     a = b = c = 0;
 #pragma unroll
     for (int k = 0; k < kCycleLists; ++k) {
         if (q < s.fan_end[k]) {
-            const size_t r = q - (k ? s.fan_end[k - 1] : 0);
-            const int32_t *v = s.c[k] + (size_t)(k + 3) * (r / (k + 1));
-            const int mm = 1 + (int)(r % (k + 1));
+            const uint32_t r = q - (k ? s.fan_end[k - 1] : 0u), cyc = r / (uint32_t)(k + 1);
+            const int32_t *v = s.c[k] + (uint32_t)(k + 3) * cyc;   // list sizes stay below 2^31 entries
+            const uint32_t mm = 1u + (r - cyc * (uint32_t)(k + 1));
             a = v[0]; b = v[mm]; c = v[mm + 1];
             return;
         }
@@ -82,7 +82,7 @@ __global__ __launch_bounds__(kBlock) void k_validate_cycles(CycleSet s, int32_t 
     int L = 0;
 #pragma unroll
     for (int k = kCycleLists - 1; k >= 0; --k)
-        if (q < s.cyc_end[k]) { v = s.c[k] + (size_t)(k + 3) * (q - (k ? s.cyc_end[k - 1] : 0)); L = k + 3; }
+        if (q < s.cyc_end[k]) { v = s.c[k] + (size_t)(k + 3) * ((uint32_t)q - (k ? s.cyc_end[k - 1] : 0u)); L = k + 3; }
     int32_t x[kMaxCycleLen];
     bool bad = false;
     for (int a = 0; a < L; ++a) {
@@ -103,7 +103,7 @@ __global__ __launch_bounds__(kBlock) void k_chord_keys(CycleSet s, size_t nch, i
     size_t q = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (q >= nch) return;
     int32_t a, b;
-    chord_of(s, q, a, b);
+    chord_of(s, (uint32_t)q, a, b);
     key[q] = ((uint64_t)(uint32_t)min(a, b) << nbits) | (uint32_t)max(a, b);
 }
 
@@ -183,7 +183,7 @@ __global__ __launch_bounds__(kBlock) void k_triangle_keys(CycleSet s, size_t nt,
     size_t q = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (q >= nt) return;
     int32_t a, b, c;
-    fan_triangle(s, q, a, b, c);
+    fan_triangle(s, (uint32_t)q, a, b, c);
     sort3(a, b, c);
     int32_t e0 = find_edge_in_row(rowptr, j, a, b);
     int32_t e1 = find_edge_in_row(rowptr, j, a, c);
@@ -372,7 +372,8 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
             nch += (size_t)k * (size_t)n_cycles[k];
             cycle_bytes += 4.0 * (k + 3) * (double)n_cycles[k];
         }
-        cs.cyc_end[k] = ncyc; cs.fan_end[k] = nfan; cs.chord_end[k] = nch;
+        if (3 * nfan >= (size_t(1) << 31)) return fail(ctx, RAMA_ERR_CAPACITY, "triangle slots reach 2^31");
+        cs.cyc_end[k] = (uint32_t)ncyc; cs.fan_end[k] = (uint32_t)nfan; cs.chord_end[k] = (uint32_t)nch;
     }
     const size_t m = (size_t)g.m;
     if (3 * nfan >= (size_t(1) << 31) || m + nch >= (size_t(1) << 31))
