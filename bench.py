@@ -61,6 +61,7 @@ def main():
                     help="longest conflicted cycle separated in the first / later rounds (default: solver PD, 5 3)")
     ap.add_argument("--shortest-only", action="store_true",
                     help="per repulsive edge separate only its shortest conflicted cycles")
+    ap.add_argument("--kernels", type=int, default=16, help="how many kernels the per-kernel table lists")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain 1 GiB device copy three times (reference reading for rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE runs)")
@@ -156,7 +157,7 @@ def main():
     if kernels:
         out["kernels"] = [{"name": k["name"], "launches": k["launches"], "ms_per_step": k["ms"],
                            "GBps": round(k["GBps"], 1), "frac_hbm": round(k["GBps"] / HBM_PEAK_GBS, 4),
-                           "share": round(k["share"], 4)} for k in kernels[:16]]
+                           "share": round(k["share"], 4)} for k in kernels[:args.kernels]]
     del labels
     out["cpu_baseline"] = cpu_baseline(args.cpu_side, args.cycle_len, args.shortest_only) if args.cpu_side > 0 else None
     print(json.dumps(out))

@@ -236,7 +236,7 @@ __global__ __launch_bounds__(kBlock) void k_count_cycles(size_t nr, const int32_
 
 template <int MAXL>
 struct HasCycles {
-    static constexpr int bytes = 4 * (MAXL - 2);   // bytes read per item
+    static constexpr int bytes = 4;   // bytes read per item: at least one count (one per list searched)
     static constexpr const char *tag = MAXL > 5 ? "HasCycles7" : "HasCycles";
     ListPtrs<uint32_t, MAXL - 2> cnt;
     int lists;

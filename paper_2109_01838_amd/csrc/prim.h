@@ -28,6 +28,26 @@ __device__ __forceinline__ T wave_inclusive_scan(T v)
     return v;
 }
 
+// 32-bit integers: the same scan on the data-parallel-primitive path of the vector ALU instead of
+// the LDS crossbar -- shifts by 1, 2, 4, 8 inside each row of 16 lanes, then lane 15 of rows 0 and
+// 2 is broadcast into rows 1 and 3, then lane 31 into rows 2 and 3.  Lanes without a source add 0.
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v)
+{
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, false);   // row_shr:1
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, false);   // row_shr:2
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, false);   // row_shr:4
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, false);   // row_shr:8
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, false);   // row_bcast:15 -> rows 1, 3
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false);   // row_bcast:31 -> rows 2, 3
+    return v;
+}
+__device__ __forceinline__ int32_t wave_inclusive_scan(int32_t v) { return (int32_t)wave_inclusive_scan((uint32_t)v); }
+
+// value of lane 63, the same in every lane
+template <typename T>
+__device__ __forceinline__ T wave_last(T v) { return __shfl(v, 63, 64); }
+__device__ __forceinline__ uint32_t wave_last(uint32_t v) { return (uint32_t)__builtin_amdgcn_readlane((int)v, 63); }
+
 template <typename T>
 __device__ __forceinline__ T wave_sum(T v)
 {
@@ -73,8 +93,12 @@ __device__ __forceinline__ T block_sum(T v)
 // ------------------------------------------------------------------------------------------
 // exclusive scan of f(0..n-1) into out[0..n] (out[n] = total)
 // ------------------------------------------------------------------------------------------
+// A workgroup owns a tile of 2048 consecutive items, each of its four waves 512 of them, taken
+// 64 at a time: lane l of the wave reads item 64*q + l in step q, so every access is one
+// contiguous 256-byte (or 512-byte) piece per wave.
 constexpr int kScanItems = 8;
 constexpr int kScanTile = kBlock * kScanItems;
+constexpr int kScanWaveItems = 64 * kScanItems;
 
 template <typename T>
 struct PtrInput {
@@ -97,11 +121,13 @@ inline const char *kernel_name(const char *kernel)
 template <typename TO, typename F>
 __global__ __launch_bounds__(kBlock) void k_scan_reduce(F f, TO *block_sums, size_t n)
 {
-    size_t base = (size_t)blockIdx.x * kScanTile + (size_t)threadIdx.x * kScanItems;
+    const size_t base = (size_t)blockIdx.x * kScanTile + threadIdx.x;
     TO s = 0;
 #pragma unroll
-    for (int q = 0; q < kScanItems; ++q)
-        if (base + q < n) s += (TO)f(base + q);
+    for (int q = 0; q < kScanItems; ++q) {
+        const size_t k = base + (size_t)q * kBlock;
+        if (k < n) s += (TO)f(k);
+    }
     TO tot = block_sum(s);
     if (threadIdx.x == 0) block_sums[blockIdx.x] = tot;
 }
@@ -109,23 +135,34 @@ __global__ __launch_bounds__(kBlock) void k_scan_reduce(F f, TO *block_sums, siz
 template <typename TO, typename F>
 __global__ __launch_bounds__(kBlock) void k_scan_apply(F f, TO *out, const TO *block_offsets, size_t n)
 {
-    size_t base = (size_t)blockIdx.x * kScanTile + (size_t)threadIdx.x * kScanItems;
+    __shared__ TO wave_tot[4];
+    const int w = threadIdx.x >> 6;
+    const size_t base = (size_t)blockIdx.x * kScanTile + (size_t)w * kScanWaveItems + lane_id();
     TO v[kScanItems];
-    TO s = 0;
 #pragma unroll
     for (int q = 0; q < kScanItems; ++q) {
-        v[q] = (base + q < n) ? (TO)f(base + q) : (TO)0;
-        s += v[q];
+        const size_t k = base + (size_t)q * 64;
+        v[q] = (k < n) ? (TO)f(k) : (TO)0;
     }
-    TO tot;
-    TO inc = block_inclusive_scan(s, &tot);
-    TO run = inc - s + (block_offsets ? block_offsets[blockIdx.x] : (TO)0);
+    TO carry = 0;   // sum of the wave's items before step q
 #pragma unroll
     for (int q = 0; q < kScanItems; ++q) {
-        if (base + q < n) out[base + q] = run;
-        run += v[q];
+        const TO inc = wave_inclusive_scan(v[q]);
+        v[q] = inc - v[q] + carry;
+        carry += wave_last(inc);
     }
-    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == kBlock - 1) out[n] = run;
+    if (lane_id() == 0) wave_tot[w] = carry;
+    __syncthreads();
+    TO pre = block_offsets ? block_offsets[blockIdx.x] : (TO)0;
+#pragma unroll
+    for (int k = 0; k < 3; ++k)
+        if (k < w) pre += wave_tot[k];
+#pragma unroll
+    for (int q = 0; q < kScanItems; ++q) {
+        const size_t k = base + (size_t)q * 64;
+        if (k < n) out[k] = v[q] + pre;
+    }
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == kBlock - 1) out[n] = pre + carry;
 }
 
 template <typename TO>
