@@ -103,13 +103,16 @@ __global__ __launch_bounds__(kBlock) void k_advance(size_t na, const uint32_t *a
                                                     const float *c, const int32_t *mate, uint32_t *act_next,
                                                     unsigned long long *best_next, uint32_t *counter)
 {
-    __shared__ uint32_t s_base;
-    const size_t tile = (size_t)blockIdx.x * (kBlock * kAdvItems);
-    uint32_t e[kAdvItems];
-    uint32_t keep = 0, cnt = 0;
+    __shared__ uint32_t s_base, s_wave[4];
+    // a wave owns 512 consecutive candidates and takes them 64 at a time, lane l the l-th: loads are
+    // contiguous and neighbouring lanes hold neighbouring edges, which the proposals combine
+    const int w = threadIdx.x >> 6, lane = lane_id();
+    const size_t base = (size_t)blockIdx.x * (kBlock * kAdvItems) + (size_t)w * (64 * kAdvItems) + lane;
+    uint32_t e[kAdvItems], where[kAdvItems];
+    uint32_t keep = 0, cnt = 0;   // cnt: survivors of this wave so far (same in every lane)
 #pragma unroll
     for (int q = 0; q < kAdvItems; ++q) {
-        size_t a = tile + (size_t)threadIdx.x * kAdvItems + q;
+        const size_t a = base + (size_t)q * 64;
         e[q] = 0;
         bool ok = false;
         int32_t u = 0, v = 0;
@@ -118,17 +121,26 @@ __global__ __launch_bounds__(kBlock) void k_advance(size_t na, const uint32_t *a
             u = i[e[q]]; v = j[e[q]];
             ok = mate[u] < 0 && mate[v] < 0;
         }
-        if (ok) { keep |= 1u << q; ++cnt; }
+        const unsigned long long vote = __ballot(ok);
+        where[q] = cnt + (uint32_t)__popcll(vote & ((1ull << lane) - 1ull));
+        cnt += (uint32_t)__popcll(vote);
+        if (ok) keep |= 1u << q;
         propose_edge(ok, u, v, ok ? edge_rank(c[e[q]], e[q]) : 0ull, best_next);
     }
-    uint32_t total;
-    uint32_t off = block_inclusive_scan(cnt, &total) - cnt;
-    if (threadIdx.x == 0) s_base = total ? atomicAdd(counter, total) : 0u;
+    if (lane == 0) s_wave[w] = cnt;
     __syncthreads();
-    off += s_base;
+    if (threadIdx.x == 0) {
+        const uint32_t total = s_wave[0] + s_wave[1] + s_wave[2] + s_wave[3];
+        s_base = total ? atomicAdd(counter, total) : 0u;
+    }
+    __syncthreads();
+    uint32_t off = s_base;
+#pragma unroll
+    for (int k = 0; k < 3; ++k)
+        if (k < w) off += s_wave[k];
 #pragma unroll
     for (int q = 0; q < kAdvItems; ++q)
-        if (keep & (1u << q)) act_next[off++] = e[q];
+        if (keep & (1u << q)) act_next[off + where[q]] = e[q];
 }
 
 struct MatchedLow {
