@@ -226,7 +226,10 @@ __global__ __launch_bounds__(kBlock) void k_count_cycles(size_t nr, const int32_
         for (int L = 3; L <= max_len; ++L) {
             em.clear();
             enumerate_cycles<MAXL>(g, ri[r], rj[r], L, em);
-            if (em.n[L - 3]) break;
+            uint32_t any = 0;   // only length L can have closed: shorter ones were tried before
+#pragma unroll
+            for (int k = 0; k < MAXL - 2; ++k) any |= em.n[k];
+            if (any) break;
         }
     }
 #pragma unroll

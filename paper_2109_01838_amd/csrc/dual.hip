@@ -297,7 +297,10 @@ __global__ __launch_bounds__(kBlock) void k_triangle_update(size_t T, const int3
     msg[3 * t] = oa; msg[3 * t + 1] = ob; msg[3 * t + 2] = oc;
 }
 
-// one thread per active edge; an edge in no triangle is never touched and keeps its cost
+// one thread per active edge; an edge in no triangle is never touched and keeps its cost.
+// Between iterations only the share travels on (the next triangle update reads nothing else), so
+// c_e itself is stored only when somebody reads it: after the last iteration, or for the bound.
+template <bool STORE_CE>
 __global__ __launch_bounds__(kBlock) void k_edge_update(size_t na, const uint32_t *act_edge, const uint32_t *act_start,
                                                         const uint32_t *slot, const float *msg, float *ce, float *share)
 {
@@ -306,7 +309,7 @@ __global__ __launch_bounds__(kBlock) void k_edge_update(size_t na, const uint32_
     const uint32_t e = act_edge[a], p0 = act_start[a], p1 = act_start[a + 1];
     float acc = 0.0f;
     for (uint32_t p = p0; p < p1; ++p) acc = acc + msg[slot[p]];
-    ce[e] = acc;
+    if (STORE_CE) ce[e] = acc;
     share[e] = acc / (float)(p1 - p0);
 }
 
@@ -561,9 +564,14 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
         }
         LAUNCH_TRY(ctx, "triangle_update");
         {
-            ProfScope ps_(ctx, "k_edge_update", (double)(na * 16 + 3 * T * 8));
-            k_edge_update<<<grid_for(na), kBlock, 0, ctx.stream>>>(na, act_edge.get(), act_start.get(), slot.get(), msg.get(),
-                                                               ce, share.get());
+            const bool store_ce = it == k_iters || lb_trace != nullptr;
+            ProfScope ps_(ctx, "k_edge_update", (double)(na * (store_ce ? 16 : 12) + 3 * T * 8));
+            if (store_ce)
+                k_edge_update<true><<<grid_for(na), kBlock, 0, ctx.stream>>>(na, act_edge.get(), act_start.get(), slot.get(),
+                                                                         msg.get(), ce, share.get());
+            else
+                k_edge_update<false><<<grid_for(na), kBlock, 0, ctx.stream>>>(na, act_edge.get(), act_start.get(), slot.get(),
+                                                                          msg.get(), ce, share.get());
         }
         LAUNCH_TRY(ctx, "edge_update");
         if (lb_trace) {
