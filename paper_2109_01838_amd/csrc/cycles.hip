@@ -17,21 +17,20 @@ namespace rama {
 
 namespace {
 
-struct PosFlag {
+// both sign counters in one scan: attractive edges count in the low word, repulsive ones in the high word
+struct SignFlags {
     static constexpr int bytes = 4;   // bytes read per item
-    static constexpr const char *tag = "PosFlag";
+    static constexpr const char *tag = "SignFlags";
     const float *c;
-    __device__ __forceinline__ uint32_t operator()(size_t e) const { return c[e] > 0.0f ? 1u : 0u; }
-};
-struct NegFlag {
-    static constexpr int bytes = 4;   // bytes read per item
-    static constexpr const char *tag = "NegFlag";
-    const float *c;
-    __device__ __forceinline__ uint32_t operator()(size_t e) const { return c[e] < 0.0f ? 1u : 0u; }
+    __device__ __forceinline__ uint64_t operator()(size_t e) const
+    {
+        const float w = c[e];
+        return w > 0.0f ? 1ull : (w < 0.0f ? (1ull << 32) : 0ull);
+    }
 };
 
 __global__ __launch_bounds__(kBlock) void k_split_sign(size_t m, const int32_t *i, const int32_t *j, const float *c,
-                                                       const uint32_t *ppos, const uint32_t *npos, int32_t *pi,
+                                                       const uint64_t *spos, int32_t *pi,
                                                        int32_t *pj, uint32_t *lkey, uint32_t *lval, int32_t *ri,
                                                        int32_t *rj)
 {
@@ -39,11 +38,11 @@ __global__ __launch_bounds__(kBlock) void k_split_sign(size_t m, const int32_t *
     if (e >= m) return;
     float w = c[e];
     if (w > 0.0f) {
-        uint32_t p = ppos[e];
+        uint32_t p = (uint32_t)spos[e];
         pi[p] = i[e]; pj[p] = j[e];
         lkey[p] = (uint32_t)j[e]; lval[p] = (uint32_t)i[e];
     } else if (w < 0.0f) {
-        uint32_t p = npos[e];
+        uint32_t p = (uint32_t)(spos[e] >> 32);
         ri[p] = i[e]; rj[p] = j[e];
     }
 }
@@ -384,14 +383,12 @@ rama_status find_cycles(Ctx &ctx, const Graph &g, int max_len, bool shortest_onl
     if (m == 0 || max_len < 3) return RAMA_OK;
     if (max_len > kMaxCycleLen) return fail(ctx, RAMA_ERR_INVALID_ARG, "cycle length beyond the supported maximum");
     // sign partition
-    Buf<uint32_t> ppos, npos;
-    RAMA_TRY(ppos.alloc(ctx, m + 1));
-    RAMA_TRY(npos.alloc(ctx, m + 1));
-    RAMA_TRY((exclusive_scan<uint32_t>(ctx, PosFlag{g.c.get()}, ppos.get(), m)));
-    RAMA_TRY((exclusive_scan<uint32_t>(ctx, NegFlag{g.c.get()}, npos.get(), m)));
-    uint32_t mp = 0, mr = 0;
-    RAMA_TRY(read_back(ctx, &mp, ppos.get() + m, 4));
-    RAMA_TRY(read_back(ctx, &mr, npos.get() + m, 4));
+    Buf<uint64_t> spos;
+    RAMA_TRY(spos.alloc(ctx, m + 1));
+    RAMA_TRY((exclusive_scan<uint64_t>(ctx, SignFlags{g.c.get()}, spos.get(), m)));
+    uint64_t both = 0;
+    RAMA_TRY(read_back(ctx, &both, spos.get() + m, 8));
+    const uint32_t mp = (uint32_t)both, mr = (uint32_t)(both >> 32);
     if (mp == 0 || mr == 0) return RAMA_OK;
     if ((uint64_t)2 * mp >= (uint64_t(1) << 31)) return fail(ctx, RAMA_ERR_CAPACITY, "positive adjacency reaches 2^31 entries");
     Buf<int32_t> pi, pj, ri, rj;
@@ -404,12 +401,11 @@ rama_status find_cycles(Ctx &ctx, const Graph &g, int max_len, bool shortest_onl
     RAMA_TRY(rj.alloc(ctx, mr));
     {
         ProfScope ps_(ctx, "k_split_sign", (double)(m * 20 + (size_t)mp * 16 + (size_t)mr * 8));
-        k_split_sign<<<grid_for(m), kBlock, 0, ctx.stream>>>(m, g.i.get(), g.j.get(), g.c.get(), ppos.get(), npos.get(),
-                                                         pi.get(), pj.get(), lkey.get(), lval.get(), ri.get(), rj.get());
+        k_split_sign<<<grid_for(m), kBlock, 0, ctx.stream>>>(m, g.i.get(), g.j.get(), g.c.get(), spos.get(), pi.get(),
+                                                         pj.get(), lkey.get(), lval.get(), ri.get(), rj.get());
     }
     LAUNCH_TRY(ctx, "split_sign");
-    ppos.reset();
-    npos.reset();
+    spos.reset();
     // positive CSR
     const int32_t n = g.n;
     Buf<int32_t> up_ptr, low_ptr, rowptr, nb;
