@@ -174,6 +174,36 @@ class Oracle:
         k = mo.value
         return dict(i=io[:k].copy(), j=jo[:k].copy(), c=co[:k].copy(), lower_bound=lb.value, lb_trace=tr)
 
+    def dual_rounds(self, n, i, j, c, max_cycle_len=5, k_iters=10, dual_rounds=1, shortest_only=False,
+                    want_triangles=False):
+        """Separation + k message-passing iterations, repeated dual_rounds times on the same graph."""
+        i, j, c = _i32(i), _i32(j), _f32(c)
+        lb = C.c_double(0.0)
+        tr = np.zeros(dual_rounds + 1, np.float64)
+        room = max(i.size, 1)
+        tcap = 0
+        while True:     # the sizes are only known afterwards: grow and repeat on a capacity miss
+            io, jo, co = np.empty(room, np.int32), np.empty(room, np.int32), np.empty(room, np.float32)
+            tn, ct = np.empty((max(tcap, 1), 3), np.int32), np.empty((max(tcap, 1), 3), np.float32)
+            mo, nt = C.c_int64(0), C.c_int64(0)
+            st = self.lib.rama_oracle_dual_rounds(
+                C.c_int32(n), C.c_int64(i.size), _ptr(i), _ptr(j), _ptr(c), C.c_int32(max_cycle_len),
+                C.c_int32(int(shortest_only)), C.c_int32(k_iters), C.c_int32(dual_rounds), C.c_int64(room),
+                _ptr(io), _ptr(jo), _ptr(co), C.byref(mo), C.byref(lb), _ptr(tr),
+                C.c_int64(tcap), _ptr(tn), _ptr(ct), C.byref(nt))
+            if st == ERR_CAP or (st == OK and want_triangles and nt.value > tcap):
+                room, tcap = max(room, mo.value), nt.value if want_triangles else 0
+                continue
+            if st != OK:
+                raise OracleError(st, "dual_rounds")
+            break
+        k = mo.value
+        out = dict(i=io[:k].copy(), j=jo[:k].copy(), c=co[:k].copy(), lower_bound=lb.value, lb_trace=tr,
+                   n_triangles=nt.value)
+        if want_triangles:
+            out["tri_nodes"], out["ct"] = tn[:nt.value].copy(), ct[:nt.value].copy()
+        return out
+
     # -- a4 / a5 / a6 -------------------------------------------------------------------------
     def matching(self, n, i, j, c, tau=0.0, rounds_cap=32):
         """Input must be canonical.  Returns mate[n]."""
@@ -244,7 +274,7 @@ class Oracle:
 
     def solve(self, n, i, j, c, max_cycle_len_first=5, max_cycle_len_later=3, mp_iters_first=10,
               mp_iters_later=5, matching_rounds_cap=32, tau=0.0, max_rounds=0, forest_ratio=0.1,
-              shortest_only=False):
+              shortest_only=False, dual_rounds=1):
         i, j, c = _i32(i), _i32(j), _f32(c)
         labels = np.empty(n, np.int32)
         primal, lb = C.c_double(0.0), C.c_double(0.0)
@@ -252,7 +282,7 @@ class Oracle:
         st = self.lib.rama_oracle_solve(
             C.c_int32(n), C.c_int64(i.size), _ptr(i), _ptr(j), _ptr(c),
             C.c_int32(max_cycle_len_first), C.c_int32(max_cycle_len_later), C.c_int32(int(shortest_only)),
-            C.c_int32(mp_iters_first), C.c_int32(mp_iters_later),
+            C.c_int32(dual_rounds), C.c_int32(mp_iters_first), C.c_int32(mp_iters_later),
             C.c_int32(matching_rounds_cap), C.c_float(tau), C.c_float(forest_ratio), C.c_int32(max_rounds),
             _ptr(labels), C.byref(primal), C.byref(lb), stats)
         if st != OK:

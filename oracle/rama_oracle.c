@@ -20,7 +20,9 @@
  * brute-force optimal multicuts, brute-force cycle enumeration (lengths 3..7; the
  * shortest-only filter against that set and against scipy's hop distances), dense K^T A K,
  * scipy connected components / duplicate summation, closed-form min-marginals,
- * monotone lower bound, zero min-marginals after a triangle update.
+ * monotone lower bound, zero min-marginals after a triangle update; for the dual rounds:
+ * every multicut keeps its cost under the reparametrisation (edges + kept triangles), the
+ * bound grows from round to round and stays below the brute-force optimum.
  * Parity unpinned: the *choice* of triangulation (fan from the repulsive edge's
  * smaller endpoint) and the matching's tie-break order are readings of passages
  * on which the paper is silent; only their invariants are pinned.
@@ -450,7 +452,8 @@ typedef struct {
     int64_t *slot;       /* 3T */
 } mp_state;
 
-static int mp_init(mp_state *s, int64_t m, const float *c, int64_t T, const int32_t *tri_edge)
+/* ct0: triangle costs to start from (3T values), NULL = all zero (no multipliers yet) */
+static int mp_init(mp_state *s, int64_t m, const float *c, int64_t T, const int32_t *tri_edge, const real *ct0)
 {
     s->m = m; s->T = T; s->tri_edge = tri_edge;
     s->ce = (real *)xmalloc((size_t)m * sizeof(real));
@@ -458,6 +461,7 @@ static int mp_init(mp_state *s, int64_t m, const float *c, int64_t T, const int3
     s->slot_ptr = (int64_t *)calloc((size_t)m + 2, sizeof(int64_t));
     s->slot = (int64_t *)xmalloc((size_t)(3 * T) * sizeof(int64_t));
     if (!s->ce || !s->ct || !s->slot_ptr || !s->slot) return ERR_OOM;
+    if (ct0) for (int64_t q = 0; q < 3 * T; ++q) s->ct[q] = ct0[q];
     for (int64_t e = 0; e < m; ++e) s->ce[e] = (real)c[e];
     for (int64_t q = 0; q < 3 * T; ++q) s->slot_ptr[tri_edge[q] + 1]++;
     for (int64_t e = 0; e < m; ++e) s->slot_ptr[e + 1] += s->slot_ptr[e];
@@ -524,7 +528,7 @@ static double mp_lower_bound(const mp_state *s)
 int rama_oracle_mp_half_step(int64_t m, float *ce, int64_t T, const int32_t *tri_edge, float *ct, int32_t which)
 {
     mp_state s;
-    int st = mp_init(&s, m, ce, T, tri_edge);
+    int st = mp_init(&s, m, ce, T, tri_edge, NULL);
     if (st != OK) return st;
     for (int64_t q = 0; q < 3 * T; ++q) s.ct[q] = (real)ct[q];
     if (which == 0) mp_edges_to_triangles(&s);
@@ -583,7 +587,7 @@ int rama_oracle_message_passing(int32_t n, int64_t m, const int32_t *i, const in
     if (st == OK && ma > edge_cap) { *m_out = ma; st = ERR_CAP; }
     if (st != OK) { free(ia); free(ja); free(ca); free(tn); free(te); return st; }
     mp_state s;
-    st = mp_init(&s, ma, ca, T, te);
+    st = mp_init(&s, ma, ca, T, te, NULL);
     if (st != OK) return st;
     real *msg = (real *)xmalloc((size_t)(3 * T) * sizeof(real));
     if (!msg) return ERR_OOM;
@@ -599,6 +603,148 @@ int rama_oracle_message_passing(int32_t n, int64_t m, const int32_t *i, const in
     free(msg); mp_free(&s);
     free(ia); free(ja); free(ca); free(tn); free(te);
     return OK;
+}
+
+/* ------------------------------------------------------------------------------------------ */
+/* Dual rounds on one graph.  One round = separate the conflicted cycles of the current         */
+/* reparametrised costs (step a1), add their triangles to the triangle set, k iterations of     */
+/* message passing over the whole set.  With one round this is the dual part of a round of      */
+/* Alg. "Primal-Dual Multicut".  More rounds re-separate on the same graph, the cutting-plane   */
+/* loop that Sec. 5 points to when it asks for better separation: triangles found earlier stay  */
+/* in the relaxation and keep their costs c_t (dropping them would give back what their         */
+/* multipliers gained), new ones start at zero, so LB never decreases from round to round.      */
+/* The loop ends early when a separation finds nothing.                                         */
+/* In/out: a canonical graph (*gi,*gj,*gc of *m edges, malloc'd; replaced by the augmented      */
+/* graph with reparametrised costs).  Out: lb (after the last round run; the sum of negative    */
+/* costs if none ran), lb_trace[0..rounds] (optional; [0] before the first round, entries of    */
+/* rounds that did not run repeat the last value), cycles_first[N_LISTS] (optional, first       */
+/* round), and optionally the final triangle set: *tri_nodes_out (3T, sorted triples), *ct_out  */
+/* (3T), *T_out.                                                                                */
+/* ------------------------------------------------------------------------------------------ */
+static int tri_triple_cmp(const int32_t *a, const int32_t *b)
+{
+    for (int q = 0; q < 3; ++q) if (a[q] != b[q]) return a[q] < b[q] ? -1 : 1;
+    return 0;
+}
+
+static int dual_block(int32_t n, int64_t *m, int32_t **gi, int32_t **gj, float **gc,
+                      int32_t max_cycle_len, int32_t shortest_only, int32_t k_iters, int32_t rounds,
+                      double *lb, double *lb_trace, int64_t *cycles_first,
+                      int32_t **tri_nodes_out, real **ct_out, int64_t *T_out)
+{
+    int st = OK;
+    int64_t T = 0;
+    int32_t *tn = NULL;      /* triangle set so far: sorted node triples */
+    real *ct = NULL;         /* their costs */
+    double cur = 0.0;
+    for (int64_t e = 0; e < *m; ++e) if ((*gc)[e] < 0) cur += (double)(*gc)[e];
+    if (lb_trace) lb_trace[0] = cur;
+    if (cycles_first) for (int q = 0; q < N_LISTS; ++q) cycles_first[q] = 0;
+    int32_t done = 0;
+    for (int32_t d = 1; d <= rounds && max_cycle_len >= 3; ++d) {
+        int64_t cnt[N_LISTS] = { 0 }, total = 0, chords = 0, fans = 0;
+        int32_t *cyc[N_LISTS] = { NULL };
+        st = rama_oracle_find_conflicted_cycles(n, *m, *gi, *gj, *gc, max_cycle_len, shortest_only, NULL, NULL, cnt);
+        if (st != OK && st != ERR_CAP) break;
+        for (int L = 3; L <= max_cycle_len; ++L) {
+            /* room for the old triangles behind the new 3-cycles: they re-enter as 3-cycles */
+            cyc[L - 3] = (int32_t *)xmalloc((size_t)(cnt[L - 3] + (L == 3 ? T : 0)) * L * 4);
+            if (!cyc[L - 3]) return ERR_OOM;
+        }
+        st = rama_oracle_find_conflicted_cycles(n, *m, *gi, *gj, *gc, max_cycle_len, shortest_only, cnt, cyc, cnt);
+        if (st != OK) break;
+        for (int L = 3; L <= max_cycle_len; ++L) { total += cnt[L - 3]; chords += (L - 3) * cnt[L - 3]; fans += (L - 2) * cnt[L - 3]; }
+        if (d == 1 && cycles_first) for (int q = 0; q < N_LISTS; ++q) cycles_first[q] = cnt[q];
+        if (total == 0) { for (int L = 0; L < N_LISTS; ++L) free(cyc[L]); break; }
+        if (T > 0) memcpy(cyc[0] + 3 * cnt[0], tn, (size_t)T * 12);
+        int64_t with_old[N_LISTS];
+        for (int q = 0; q < N_LISTS; ++q) with_old[q] = cnt[q];
+        with_old[0] += T;
+        int64_t room = *m + chords, ma = 0, Tn = 0;
+        int32_t *ia = (int32_t *)xmalloc((size_t)room * 4), *ja = (int32_t *)xmalloc((size_t)room * 4);
+        float *ca = (float *)xmalloc((size_t)room * 4);
+        int32_t *tnn = (int32_t *)xmalloc((size_t)(fans + T) * 12), *te = (int32_t *)xmalloc((size_t)(fans + T) * 12);
+        if (!ia || !ja || !ca || !tnn || !te) return ERR_OOM;
+        st = rama_oracle_triangulate(n, *m, *gi, *gj, *gc, max_cycle_len, (const int32_t *const *)cyc, with_old,
+                                     ia, ja, ca, &ma, tnn, te, &Tn);
+        for (int L = 0; L < N_LISTS; ++L) free(cyc[L]);
+        if (st != OK) break;
+        /* old triangles keep their costs: both lists are sorted triples, the old one a subset */
+        real *ctn = (real *)calloc((size_t)(3 * Tn) + 1, sizeof(real));
+        if (!ctn) return ERR_OOM;
+        int64_t q = 0;
+        for (int64_t t = 0; t < T; ++t) {
+            while (q < Tn && tri_triple_cmp(tnn + 3 * q, tn + 3 * t) < 0) ++q;
+            if (q >= Tn || tri_triple_cmp(tnn + 3 * q, tn + 3 * t) != 0) return ERR_GRAPH;
+            for (int sl = 0; sl < 3; ++sl) ctn[3 * q + sl] = ct[3 * t + sl];
+        }
+        mp_state s;
+        st = mp_init(&s, ma, ca, Tn, te, ctn);
+        free(ctn);
+        if (st != OK) break;
+        real *msg = (real *)xmalloc((size_t)(3 * Tn) * sizeof(real));
+        if (!msg) return ERR_OOM;
+        for (int32_t it = 1; it <= k_iters; ++it) {
+            mp_edges_to_triangles(&s);
+            mp_triangles_to_edges(&s, msg);
+        }
+        free(msg);
+        cur = mp_lower_bound(&s);
+        for (int64_t e = 0; e < ma; ++e) ca[e] = (float)s.ce[e];
+        free(tn); free(ct);
+        tn = tnn; T = Tn;
+        ct = (real *)xmalloc((size_t)(3 * Tn) * sizeof(real));
+        if (!ct) return ERR_OOM;
+        memcpy(ct, s.ct, (size_t)(3 * Tn) * sizeof(real));
+        mp_free(&s);
+        free(te);
+        free(*gi); free(*gj); free(*gc);
+        *gi = ia; *gj = ja; *gc = ca; *m = ma;
+        done = d;
+        if (lb_trace) lb_trace[d] = cur;
+    }
+    if (lb_trace) for (int32_t d = done + 1; d <= rounds; ++d) lb_trace[d] = cur;
+    if (lb) *lb = cur;
+    if (T_out) *T_out = T;
+    if (tri_nodes_out) *tri_nodes_out = tn; else free(tn);
+    if (ct_out) *ct_out = ct; else free(ct);
+    return st == ERR_CAP ? OK : st;
+}
+
+/* The dual block on its own: any edge list in, augmented canonical graph with reparametrised costs
+ * out (capacity edge_cap), LB after the last round, optional trace lb_trace[0..dual_rounds], and
+ * optionally the final triangles (tri_nodes: 3*tri_cap int32, ct: 3*tri_cap float; n_tri_out always
+ * gets the count, nothing is copied if tri_cap is too small). */
+int rama_oracle_dual_rounds(int32_t n, int64_t m, const int32_t *i, const int32_t *j, const float *c,
+                            int32_t max_cycle_len, int32_t shortest_only, int32_t k_iters, int32_t dual_rounds,
+                            int64_t edge_cap, int32_t *io, int32_t *jo, float *co, int64_t *m_out,
+                            double *lower_bound, double *lb_trace,
+                            int64_t tri_cap, int32_t *tri_nodes, float *ct, int64_t *n_tri_out)
+{
+    if (!m_out || k_iters < 0 || dual_rounds < 0 || max_cycle_len > MAX_CYCLE_LEN) return ERR_ARG;
+    size_t mm = (size_t)(m > 0 ? m : 1);
+    int32_t *gi = (int32_t *)xmalloc(mm * 4), *gj = (int32_t *)xmalloc(mm * 4);
+    float *gc = (float *)xmalloc(mm * 4);
+    if (!gi || !gj || !gc) return ERR_OOM;
+    int64_t mc = 0, T = 0;
+    int st = rama_oracle_canonicalise(n, m, i, j, c, gi, gj, gc, &mc);
+    int32_t *tn = NULL;
+    real *ctr = NULL;
+    if (st == OK) st = dual_block(n, &mc, &gi, &gj, &gc, max_cycle_len, shortest_only, k_iters, dual_rounds,
+                                  lower_bound, lb_trace, NULL, &tn, &ctr, &T);
+    if (st == OK) {
+        *m_out = mc;
+        if (n_tri_out) *n_tri_out = T;
+        if (mc > edge_cap) st = ERR_CAP;
+        else {
+            for (int64_t e = 0; e < mc; ++e) { io[e] = gi[e]; jo[e] = gj[e]; co[e] = gc[e]; }
+            if (tri_nodes && ct && T <= tri_cap)
+                for (int64_t q = 0; q < 3 * T; ++q) { tri_nodes[q] = tn[q]; ct[q] = (float)ctr[q]; }
+        }
+    }
+    free(tn); free(ctr);
+    free(gi); free(gj); free(gc);
+    return st;
 }
 
 /* ------------------------------------------------------------------------------------------ */
@@ -888,12 +1034,14 @@ double rama_oracle_multicut_cost(int64_t m, const int32_t *i, const int32_t *j, 
 /* the contraction set is empty.  The lower bound is the one recorded on the original graph    */
 /* (round 1).  labels[v] = smallest original node id in v's cluster.                           */
 /* shortest_only: the separation keeps, per repulsive edge, only its shortest cycles (step a1). */
+/* dual_rounds: separation + k message-passing iterations are repeated that many times on the  */
+/* graph of a round before it is contracted (1 = the paper's loop; see dual_block).            */
 /* stats (optional, int64[5+N_LISTS]): rounds, clusters, |T|, |E'| of round 1, final edges,     */
 /* then the number of 3-,4-,..,MAX_CYCLE_LEN-cycles of round 1                                 */
 /* ------------------------------------------------------------------------------------------ */
 int rama_oracle_solve(int32_t n, int64_t m, const int32_t *i, const int32_t *j, const float *c,
                       int32_t max_cycle_len_first, int32_t max_cycle_len_later, int32_t shortest_only,
-                      int32_t mp_iters_first, int32_t mp_iters_later,
+                      int32_t dual_rounds, int32_t mp_iters_first, int32_t mp_iters_later,
                       int32_t matching_rounds_cap, float tau, float forest_ratio, int32_t max_rounds,
                       int32_t *labels, double *primal_cost, double *lower_bound, int64_t *stats)
 {
@@ -915,31 +1063,14 @@ int rama_oracle_solve(int32_t n, int64_t m, const int32_t *i, const int32_t *j, 
     for (int32_t round = 1; max_rounds <= 0 || round <= max_rounds; ++round) {
         int32_t Lmax = round == 1 ? max_cycle_len_first : max_cycle_len_later;
         int32_t k = round == 1 ? mp_iters_first : mp_iters_later;
-        int64_t cnt[N_LISTS] = { 0 }, total = 0, chords = 0;
-        int32_t *cyc[N_LISTS] = { NULL };
         if (Lmax >= 3 && k > 0) {
-            st = rama_oracle_find_conflicted_cycles(ncur, mcur, gi, gj, gc, Lmax, shortest_only, NULL, NULL, cnt);
-            if (st != OK && st != ERR_CAP) goto fail;
-            for (int L = 3; L <= Lmax; ++L) cyc[L - 3] = (int32_t *)xmalloc((size_t)cnt[L - 3] * L * 4);
-            st = rama_oracle_find_conflicted_cycles(ncur, mcur, gi, gj, gc, Lmax, shortest_only, cnt, cyc, cnt);
-            if (st != OK) goto fail;
-            for (int L = 3; L <= Lmax; ++L) { total += cnt[L - 3]; chords += (L - 3) * cnt[L - 3]; }
-        }
-        if (round == 1) for (int q = 0; q < N_LISTS; ++q) st_c[q] = cnt[q];
-        if (total > 0) {
-            int64_t room = mcur + chords, ma = 0;
-            int32_t *ai = (int32_t *)xmalloc((size_t)room * 4), *aj = (int32_t *)xmalloc((size_t)room * 4);
-            float *ac = (float *)xmalloc((size_t)room * 4);
+            /* dual part: separation + message passing, dual_rounds times on this graph */
             double lbr = 0.0;
-            if (!ai || !aj || !ac) { st = ERR_OOM; goto fail; }
-            st = rama_oracle_message_passing(ncur, mcur, gi, gj, gc, Lmax, (const int32_t *const *)cyc, cnt,
-                                             k, room, ai, aj, ac, &ma, &lbr, NULL);
+            st = dual_block(ncur, &mcur, &gi, &gj, &gc, Lmax, shortest_only, k, dual_rounds, &lbr, NULL,
+                            round == 1 ? st_c : NULL, NULL, NULL, round == 1 ? &st_T : NULL);
             if (st != OK) goto fail;
-            if (round == 1) { lb = lbr; have_lb = 1; st_ma = ma; }
-            free(gi); free(gj); free(gc);
-            gi = ai; gj = aj; gc = ac; mcur = ma;
+            if (round == 1) { lb = lbr; have_lb = 1; st_ma = mcur; }
         }
-        for (int L = 0; L < N_LISTS; ++L) free(cyc[L]);
         if (round == 1 && !have_lb) {
             for (int64_t e = 0; e < mcur; ++e) if (gc[e] < 0) lb += (double)gc[e];
             have_lb = 1; st_ma = mcur;

@@ -1,6 +1,7 @@
 """Pins for the CPU oracle: every step is checked against something other than itself --
 the paper's worked example, brute force from the definitions, library routines and invariants
 the paper proves.  CPU only."""
+import itertools
 import os
 
 import numpy as np
@@ -669,3 +670,69 @@ def test_solve_with_forest_sandwich(oracle32, seed):
     for fr in (0.0, 0.1, 1.0):
         r = oracle32.solve(n, g["i"], g["j"], g["c"], forest_ratio=fr)
         assert r["lower_bound"] <= opt + 1e-4 * (1 + abs(opt)) <= r["primal"] + 2e-4 * (1 + abs(opt))
+
+
+# --------------------------------------------------------------------------------------------
+# dual rounds on one graph (re-separation between message-passing blocks)
+# --------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("seed", range(8))
+def test_dual_rounds_bound_is_monotone_and_valid(oracle32, oracle64, seed):
+    """Every dual round keeps a valid relaxation: LB never decreases from round to round and never
+    exceeds the brute-force optimum; one round is exactly separation + message passing."""
+    g = small_random(1200 + seed, n=8, density=0.8)
+    n = g["n_nodes"]
+    opt, _ = bf.optimal_multicut(n, g["i"], g["j"], g["c"])
+    for o in (oracle32, oracle64):
+        for lmax in (3, 5, 7):
+            r = o.dual_rounds(n, g["i"], g["j"], g["c"], lmax, 10, 4)
+            tr = r["lb_trace"]
+            assert abs(tr[0] - float(np.minimum(o.canonicalise(n, g["i"], g["j"], g["c"])[2], 0).astype(np.float64).sum())) < 1e-6
+            assert np.all(np.diff(tr) >= -1e-5 * (1 + np.abs(tr[:-1])))
+            assert tr[-1] <= opt + 1e-4 * (1 + abs(opt)) and r["lower_bound"] == tr[-1]
+            one = o.dual_rounds(n, g["i"], g["j"], g["c"], lmax, 10, 1)
+            cyc = o.find_conflicted_cycles(n, g["i"], g["j"], g["c"], lmax)
+            mp = o.message_passing(n, g["i"], g["j"], g["c"], cyc, 10)
+            assert np.array_equal(one["i"], mp["i"]) and np.array_equal(one["j"], mp["j"])
+            assert np.array_equal(one["c"], mp["c"]) and one["lower_bound"] == mp["lower_bound"]
+            assert one["lb_trace"][1] == tr[1]
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_dual_rounds_reparametrisation_keeps_every_multicut_cost(oracle64, seed):
+    """Reparametrisation moves cost between edges and triangles without changing the cost of any
+    multicut: sum_e c_e y_e == sum_e c^lambda_e y_e + sum_t <c^lambda_t, y_t> for every partition.
+    A triangle that lost its cost between rounds, or got another triangle's, breaks this."""
+    g = small_random(1300 + seed, n=7, density=0.8)
+    n = g["n_nodes"]
+    ci, cj, cc = oracle64.canonicalise(n, g["i"], g["j"], g["c"])
+    for rounds in (1, 2, 3):
+        r = oracle64.dual_rounds(n, g["i"], g["j"], g["c"], 5, 7, rounds, want_triangles=True)
+        tn, ct = r["tri_nodes"], r["ct"].astype(np.float64)
+        if rounds > 1:
+            assert prev <= set(map(tuple, tn.tolist()))          # triangles found earlier stay
+        prev = set(map(tuple, tn.tolist()))
+        assert np.all(tn[:, 0] < tn[:, 1]) and np.all(tn[:, 1] < tn[:, 2])
+        assert sorted(prev) == list(map(tuple, tn.tolist())) and len(prev) == tn.shape[0]
+        scale = float(np.abs(cc).sum()) + 1.0
+        for lab in itertools.islice(bf.set_partitions(n), 0, 400):
+            lab = np.asarray(lab)
+            orig = float(cc.astype(np.float64)[lab[ci] != lab[cj]].sum())
+            cut = lab[r["i"]] != lab[r["j"]]
+            rep = float(r["c"].astype(np.float64)[cut].sum())
+            y = np.stack([lab[tn[:, 0]] != lab[tn[:, 1]], lab[tn[:, 0]] != lab[tn[:, 2]],
+                          lab[tn[:, 1]] != lab[tn[:, 2]]], axis=1)
+            rep += float((ct * y).sum())
+            assert abs(orig - rep) <= 2e-5 * scale, (rounds, lab)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_solve_sandwich_with_dual_rounds(oracle32, seed):
+    g = small_random(1400 + seed)
+    n = g["n_nodes"]
+    opt, _ = bf.optimal_multicut(n, g["i"], g["j"], g["c"])
+    base = oracle32.solve(n, g["i"], g["j"], g["c"])
+    for rounds in (2, 3):
+        r = oracle32.solve(n, g["i"], g["j"], g["c"], dual_rounds=rounds)
+        assert r["lower_bound"] <= opt + 1e-4 * (1 + abs(opt)) <= r["primal"] + 2e-4 * (1 + abs(opt))
+        assert r["lower_bound"] >= base["lower_bound"] - 1e-4 * (1 + abs(opt))   # more rounds, no looser bound
+        assert abs(r["primal"] - bf.multicut_cost(g["i"], g["j"], g["c"], r["labels"])) < 1e-9
