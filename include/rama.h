@@ -69,6 +69,8 @@ typedef struct {
                                      forest without conflicts instead; 0.1 (<= 0: matching only) */
     int32_t max_rounds;           /* stop after this many rounds; <=0: until no candidate edge is left */
     int32_t shortest_cycles_only; /* != 0: per repulsive edge keep only its shortest conflicted cycles; 0 */
+    int32_t dual_rounds;          /* separation + k message-passing iterations are repeated this often on the
+                                     graph of a round before it is contracted, see rama_dual_rounds; 1 */
 } rama_params;
 
 /* What rama_solve did (all host memory). */
@@ -168,6 +170,30 @@ rama_status rama_message_passing(rama_ctx *ctx, int32_t n_nodes, int64_t n_edges
                                  int32_t k_iters, int64_t edge_cap,
                                  int32_t *i_out, int32_t *j_out, float *c_out, int64_t *n_edges_out,
                                  double *lower_bound, double *lb_trace);
+
+/*
+ * The dual part of a round, repeated on one graph (Sec. 3.2; with dual_rounds = 1 it is the
+ * separation and the inner loop of algorithm "Primal-Dual Multicut" in one call; more rounds are
+ * the cutting-plane loop behind the better separation that Sec. 5 asks for): each round separates
+ * the conflicted cycles of the *current* reparametrised costs, adds their triangles to the triangle
+ * set -- triangles found in earlier rounds stay and keep their costs c_t, new ones start at zero --
+ * and runs k_iters message-passing iterations over the whole set.  LB(lambda) never decreases from
+ * round to round.  The loop ends early when a separation finds no cycle.
+ *
+ *   params             used: max_cycle_len_first (cycle length of every round), mp_iters_first
+ *                      (k_iters), shortest_cycles_only, dual_rounds (>= 0)
+ *   edge_cap, i_out, j_out, c_out, n_edges_out   as in rama_message_passing; the needed size is
+ *                      not known beforehand: on RAMA_ERR_CAPACITY it is written to n_edges_out
+ *   lower_bound        host, optional: LB(lambda) after the last round (the sum of the negative costs
+ *                      if no round found a cycle)
+ *   lb_trace           host, optional, [dual_rounds+1]: LB before the first and after every round
+ *                      (rounds that did not run repeat the last value)
+ *   n_triangles_out    host, optional: size of the triangle set at the end
+ */
+rama_status rama_dual_rounds(rama_ctx *ctx, int32_t n_nodes, int64_t n_edges,
+                             const int32_t *i, const int32_t *j, const float *c, const rama_params *params,
+                             int64_t edge_cap, int32_t *i_out, int32_t *j_out, float *c_out, int64_t *n_edges_out,
+                             double *lower_bound, double *lb_trace, int64_t *n_triangles_out);
 
 /*
  * Primal update (Sec. 3.1: Lemma 1, Lemma 3, algorithm "Parallel-Edge-Contraction", "Finding

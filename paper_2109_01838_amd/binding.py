@@ -16,7 +16,7 @@ RAMA_OK, RAMA_ERR_INVALID_ARG, RAMA_ERR_BAD_GRAPH, RAMA_ERR_CAPACITY, RAMA_ERR_O
 EXPORTS = [
     "rama_create", "rama_destroy", "rama_last_error", "rama_params_default", "rama_workspace_bytes",
     "rama_profile_enable", "rama_profile_count", "rama_profile_get",
-    "rama_find_conflicted_cycles", "rama_message_passing", "rama_contract", "rama_solve",
+    "rama_find_conflicted_cycles", "rama_message_passing", "rama_dual_rounds", "rama_contract", "rama_solve",
 ]
 
 
@@ -29,6 +29,7 @@ class RamaParams(C.Structure):
         ("mp_iters_first", C.c_int32), ("mp_iters_later", C.c_int32),
         ("matching_rounds_cap", C.c_int32), ("contract_threshold", C.c_float),
         ("forest_ratio", C.c_float), ("max_rounds", C.c_int32), ("shortest_cycles_only", C.c_int32),
+        ("dual_rounds", C.c_int32),
     ]
 
 
@@ -76,6 +77,8 @@ def load_library():
                                                 C.POINTER(i64)]
     lib.rama_message_passing.argtypes = [vp, i32, i64, vp, vp, vp, i32, C.POINTER(vp), C.POINTER(i64), i32, i64,
                                          vp, vp, vp, C.POINTER(i64), C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    lib.rama_dual_rounds.argtypes = [vp, i32, i64, vp, vp, vp, C.POINTER(RamaParams), i64, vp, vp, vp, C.POINTER(i64),
+                                     C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(i64)]
     lib.rama_contract.argtypes = [vp, i32, i64, vp, vp, vp, C.POINTER(RamaParams), i32, vp, vp, vp, vp, vp,
                                   C.POINTER(i32), C.POINTER(i64)]
     lib.rama_solve.argtypes = [vp, i32, i64, vp, vp, vp, C.POINTER(RamaParams), vp, C.POINTER(C.c_double),
@@ -215,6 +218,28 @@ class Rama:
         k = mo.value
         return dict(i=io[:k], j=jo[:k], c=co[:k], lower_bound=lb.value,
                     lb_trace=None if tr is None else list(tr))
+
+    def dual_rounds(self, n_nodes, i, j, c, params=None):
+        """Separation + message passing, params.dual_rounds times on the same graph (cycle length
+        params.max_cycle_len_first, params.mp_iters_first iterations per round)."""
+        t = self.torch
+        i, j, c = self._graph(i, j, c)
+        params = params or default_params()
+        mo, nt, lb = C.c_int64(0), C.c_int64(0), C.c_double(0.0)
+        tr = (C.c_double * (params.dual_rounds + 1))()
+        cap = i.numel()
+        while True:     # the number of chords is only known afterwards: grow and repeat on a capacity miss
+            io, jo, co = self._empty(cap, t.int32), self._empty(cap, t.int32), self._empty(cap, t.float32)
+            st = self.lib.rama_dual_rounds(self.ctx, n_nodes, i.numel(), i.data_ptr(), j.data_ptr(), c.data_ptr(),
+                                           C.byref(params), cap, io.data_ptr(), jo.data_ptr(), co.data_ptr(),
+                                           C.byref(mo), C.byref(lb), tr, C.byref(nt))
+            if st == RAMA_ERR_CAPACITY and mo.value > cap:
+                cap = mo.value
+                continue
+            self._check(st, "rama_dual_rounds")
+            break
+        k = mo.value
+        return dict(i=io[:k], j=jo[:k], c=co[:k], lower_bound=lb.value, lb_trace=list(tr), n_triangles=nt.value)
 
     def contract(self, n_nodes, i, j, c, params=None, repeat=1, want_diag=True):
         t = self.torch

@@ -3,6 +3,8 @@
 #include <chrono>
 #include <cstdlib>
 
+#include <vector>
+
 #include "prim.h"
 
 using namespace rama;
@@ -75,6 +77,47 @@ bool bad_graph_args(int32_t n, int64_t m, const void *i, const void *j, const vo
     return n < 0 || m < 0 || (m > 0 && (!i || !j || !c));
 }
 
+// Dual part of a round on graph g (replaced by the augmented graph with reparametrised costs):
+// `rounds` times { separate, add triangles to the kept set, k iterations }.  lb: after the last round
+// that ran (untouched if none ran: *ran stays false).  trace: optional [rounds+1].
+rama_status dual_block(Ctx &ctx, Graph &g, int lmax, bool shortest_only, int k, int rounds, double *lb, bool *ran,
+                       double *trace, int64_t *cycles_first, int64_t *n_triangles)
+{
+    *ran = false;
+    if (n_triangles) *n_triangles = 0;
+    DualState state;
+    double cur = 0.0;
+    if (trace) {
+        RAMA_TRY(negative_cost_sum(ctx, g.c.get(), g.m, &cur));
+        trace[0] = cur;
+    }
+    int done = 0;
+    for (int d = 1; d <= rounds && lmax >= 3; ++d) {
+        CycleLists cyc;
+        RAMA_TRY(find_cycles(ctx, g, lmax, shortest_only, false, cyc));
+        int64_t n_cyc = 0;
+        const int32_t *lists[kCycleLists];
+        for (int q = 0; q < kCycleLists; ++q) { n_cyc += cyc.n[q]; lists[q] = cyc.v[q].get(); }
+        if (d == 1 && cycles_first) for (int q = 0; q < kCycleLists; ++q) cycles_first[q] = cyc.n[q];
+        if (n_cyc == 0) break;
+        Graph aug;
+        DualInfo info;
+        DualState next;
+        const bool more = d < rounds;   // the last round's triangles are not needed afterwards
+        RAMA_TRY(dual_update(ctx, g, kCycleLists, lists, cyc.n, false, k, aug, (lb || trace) ? &cur : nullptr, nullptr, &info,
+                             state.T > 0 ? &state : nullptr, more ? &next : nullptr));
+        g = std::move(aug);
+        state = std::move(next);
+        if (n_triangles) *n_triangles = info.n_triangles;
+        *ran = true;
+        done = d;
+        if (trace) trace[d] = cur;
+    }
+    if (trace) for (int d = done + 1; d <= rounds; ++d) trace[d] = cur;
+    if (*ran && lb) *lb = cur;
+    return RAMA_OK;
+}
+
 rama_status solve_impl(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const int32_t *j, const float *c,
                        const rama_params &P, int32_t *labels, double *primal, double *lower_bound, rama_stats *stats)
 {
@@ -106,25 +149,41 @@ rama_status solve_impl(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const i
         const int lmax = round == 1 ? P.max_cycle_len_first : P.max_cycle_len_later;
         const int k = round == 1 ? P.mp_iters_first : P.mp_iters_later;
         double t0 = now_ms();
-        CycleLists cyc;
-        if (lmax >= 3 && k > 0) RAMA_TRY(find_cycles(ctx, g, lmax, P.shortest_cycles_only != 0, false, cyc));
-        RAMA_TRY(finish(ctx, RAMA_OK));
-        double t1 = now_ms();
-        t_cyc += t1 - t0;
-        int64_t n_cyc = 0;
-        const int32_t *lists[kCycleLists];
-        for (int q = 0; q < kCycleLists; ++q) { n_cyc += cyc.n[q]; lists[q] = cyc.v[q].get(); }
-        if (round == 1) for (int q = 0; q < kCycleLists; ++q) S.n_cycles_first[q] = cyc.n[q];
-        if (n_cyc > 0) {
-            Graph aug;
-            DualInfo info;
-            double lbr = 0.0;
-            RAMA_TRY(dual_update(ctx, g, kCycleLists, lists, cyc.n, false, k, aug, round == 1 ? &lbr : nullptr, nullptr,
-                                 &info));
-            if (round == 1) { lb = lbr; have_lb = true; S.n_triangles_first = info.n_triangles; }
-            g = std::move(aug);
+        int64_t cycles_this[kCycleLists] = {};
+        bool ran = false;
+        double lbr = 0.0;
+        int64_t ntri = 0;
+        double t1 = t0;
+        if (lmax >= 3 && k > 0) {
+            if (P.dual_rounds == 1) {
+                CycleLists cyc;
+                RAMA_TRY(find_cycles(ctx, g, lmax, P.shortest_cycles_only != 0, false, cyc));
+                RAMA_TRY(finish(ctx, RAMA_OK));
+                t1 = now_ms();
+                int64_t n_cyc = 0;
+                const int32_t *lists[kCycleLists];
+                for (int q = 0; q < kCycleLists; ++q) { n_cyc += cyc.n[q]; lists[q] = cyc.v[q].get(); cycles_this[q] = cyc.n[q]; }
+                if (n_cyc > 0) {
+                    Graph aug;
+                    DualInfo info;
+                    RAMA_TRY(dual_update(ctx, g, kCycleLists, lists, cyc.n, false, k, aug, round == 1 ? &lbr : nullptr,
+                                         nullptr, &info));
+                    ntri = info.n_triangles;
+                    ran = true;
+                    g = std::move(aug);
+                }
+            } else {
+                RAMA_TRY(dual_block(ctx, g, lmax, P.shortest_cycles_only != 0, k, P.dual_rounds, round == 1 ? &lbr : nullptr,
+                                    &ran, nullptr, cycles_this, &ntri));
+                RAMA_TRY(finish(ctx, RAMA_OK));
+                t1 = now_ms();   // separations and message-passing blocks interleave: the stage clock books all as cycles
+            }
         }
-        for (int q = 0; q < kCycleLists; ++q) cyc.v[q].reset();
+        t_cyc += t1 - t0;
+        if (round == 1) {
+            for (int q = 0; q < kCycleLists; ++q) S.n_cycles_first[q] = cycles_this[q];
+            if (ran) { lb = lbr; have_lb = true; S.n_triangles_first = ntri; }
+        }
         if (round == 1) {
             if (!have_lb) { RAMA_TRY(negative_cost_sum(ctx, g.c.get(), g.m, &lb)); have_lb = true; }
             S.n_edges_aug_first = g.m;
@@ -152,8 +211,8 @@ rama_status solve_impl(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const i
         t_con += t3 - t2;
         if (trace)
             fprintf(stderr, "round %2d: cycles %lld/%lld/%lld/%lld/%lld  |S| %lld  -> nodes %d edges %lld   ms: cycles %.3f dual %.3f contract %.3f\n",
-                    round, (long long)cyc.n[0], (long long)cyc.n[1], (long long)cyc.n[2], (long long)cyc.n[3],
-                    (long long)cyc.n[4], (long long)ns, n_cur,
+                    round, (long long)cycles_this[0], (long long)cycles_this[1], (long long)cycles_this[2],
+                    (long long)cycles_this[3], (long long)cycles_this[4], (long long)ns, n_cur,
                     (long long)g.m, t1 - t0, t2 - t1, t3 - t2);
         if (ns == 0) break;
     }
@@ -240,6 +299,7 @@ void rama_params_default(rama_params *p)
     p->forest_ratio = 0.1f;
     p->max_rounds = 0;
     p->shortest_cycles_only = 0;
+    p->dual_rounds = 1;
 }
 
 int64_t rama_workspace_bytes(const rama_ctx *ctx) { return ctx ? (int64_t)ctx->pool.total() : 0; }
@@ -386,6 +446,39 @@ rama_status rama_contract(rama_ctx *ctx, int32_t n_nodes, int64_t n_edges, const
     return finish(*ctx, body());
 }
 
+rama_status rama_dual_rounds(rama_ctx *ctx, int32_t n_nodes, int64_t n_edges, const int32_t *i, const int32_t *j,
+                             const float *c, const rama_params *params, int64_t edge_cap, int32_t *i_out,
+                             int32_t *j_out, float *c_out, int64_t *n_edges_out, double *lower_bound, double *lb_trace,
+                             int64_t *n_triangles_out)
+{
+    if (!ctx) return RAMA_ERR_INVALID_ARG;
+    if (bad_graph_args(n_nodes, n_edges, i, j, c) || !params || !n_edges_out || edge_cap < 0 ||
+        (edge_cap > 0 && (!i_out || !j_out || !c_out)) || params->dual_rounds < 0 || params->mp_iters_first < 0 ||
+        params->max_cycle_len_first > RAMA_MAX_CYCLE_LEN)
+        return fail(*ctx, RAMA_ERR_INVALID_ARG, "rama_dual_rounds: bad arguments");
+    auto body = [&]() -> rama_status {
+        Graph g;
+        RAMA_TRY(canonicalise(*ctx, n_nodes, n_edges, i, j, c, g));
+        std::vector<double> trace((size_t)params->dual_rounds + 1, 0.0);
+        double lb = 0.0;
+        bool ran = false;
+        int64_t ntri = 0;
+        RAMA_TRY(dual_block(*ctx, g, params->max_cycle_len_first, params->shortest_cycles_only != 0, params->mp_iters_first,
+                            params->dual_rounds, &lb, &ran, trace.data(), nullptr, &ntri));
+        if (lower_bound) *lower_bound = trace[(size_t)params->dual_rounds];
+        if (lb_trace) for (size_t d = 0; d < trace.size(); ++d) lb_trace[d] = trace[d];
+        if (n_triangles_out) *n_triangles_out = ntri;
+        *n_edges_out = g.m;
+        if (g.m > edge_cap)
+            return fail(*ctx, RAMA_ERR_CAPACITY, "edge output buffers are too small; needed size written to n_edges_out");
+        RAMA_TRY(copy_out(*ctx, i_out, g.i.get(), (size_t)g.m * 4));
+        RAMA_TRY(copy_out(*ctx, j_out, g.j.get(), (size_t)g.m * 4));
+        RAMA_TRY(copy_out(*ctx, c_out, g.c.get(), (size_t)g.m * 4));
+        return finish(*ctx, RAMA_OK);
+    };
+    return finish(*ctx, body());
+}
+
 rama_status rama_solve(rama_ctx *ctx, int32_t n_nodes, int64_t n_edges, const int32_t *i, const int32_t *j,
                        const float *c, const rama_params *params, int32_t *labels, double *primal_cost,
                        double *lower_bound, rama_stats *stats)
@@ -395,6 +488,7 @@ rama_status rama_solve(rama_ctx *ctx, int32_t n_nodes, int64_t n_edges, const in
         return fail(*ctx, RAMA_ERR_INVALID_ARG, "rama_solve: bad arguments");
     if (params->max_cycle_len_first > RAMA_MAX_CYCLE_LEN || params->max_cycle_len_later > RAMA_MAX_CYCLE_LEN)
         return fail(*ctx, RAMA_ERR_INVALID_ARG, "rama_solve: cycle length beyond RAMA_MAX_CYCLE_LEN");
+    if (params->dual_rounds < 1) return fail(*ctx, RAMA_ERR_INVALID_ARG, "rama_solve: dual_rounds must be at least 1");
     return finish(*ctx, solve_impl(*ctx, n_nodes, n_edges, i, j, c, *params, labels, primal_cost, lower_bound, stats));
 }
 

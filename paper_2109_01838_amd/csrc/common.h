@@ -298,10 +298,18 @@ rama_status find_cycles(Ctx &ctx, const Graph &g, int max_len, bool shortest_onl
 struct DualInfo {
     int64_t n_triangles = 0;
 };
-// cycles[k] / n_cycles[k]: device list and number of the (k+3)-cycles, k < lists
+// triangles of a graph with their costs c_t, handed from one dual round on a graph to the next
+struct DualState {
+    size_t T = 0;
+    Buf<int32_t> tri_nodes;   // [3T] sorted node triples u<v<w
+    Buf<float> ct;            // [3T]
+};
+// cycles[k] / n_cycles[k]: device list and number of the (k+3)-cycles, k < lists.  The triangles of
+// `prev` (optional) stay in the relaxation with their costs; `next` (optional) receives the
+// triangle set and costs after the last iteration.
 rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *const *cycles, const int64_t *n_cycles,
                         bool validate_cycles, int k_iters, Graph &out, double *lower_bound, double *lb_trace,
-                        DualInfo *info);
+                        DualInfo *info, const DualState *prev = nullptr, DualState *next = nullptr);
 
 // a4..a6: one primal update.  fmap[n] -> [0,n_new); n_matched = |S|.  If |S|==0 nothing else is produced.
 rama_status contract_once(Ctx &ctx, const Graph &g, float tau, int rounds_cap, float forest_ratio, Buf<int32_t> &fmap,

@@ -26,11 +26,15 @@ namespace {
 // ---------------------------------------------------------------------------------------------
 // cycle access: one flat index space over the fan pieces of all cycles
 // ---------------------------------------------------------------------------------------------
+// list k < kCycleLists: the (k+3)-cycles; list kCycleLists: triangles kept from earlier dual rounds
+// on this graph (sorted node triples), which re-enter as 3-cycles
+constexpr int kCycleSets = kCycleLists + 1;
+__host__ __device__ constexpr int set_len(int k) { return k < kCycleLists ? k + 3 : 3; }
 struct CycleSet {
-    const int32_t *c[kCycleLists];   // list k: the (k+3)-cycles
-    uint32_t cyc_end[kCycleLists];   // running totals over the lists (all below 2^31): cycles,
-    uint32_t fan_end[kCycleLists];   // fan triangles (k+1 per cycle)
-    uint32_t chord_end[kCycleLists]; // and chords (k per cycle)
+    const int32_t *c[kCycleSets];
+    uint32_t cyc_end[kCycleSets];    // running totals over the lists (all below 2^31): cycles,
+    uint32_t fan_end[kCycleSets];    // fan triangles (L-2 per cycle)
+    uint32_t chord_end[kCycleSets];  // and chords (L-3 per cycle)
 };
 
 // q-th chord: an L-cycle gives the L-3 chords (v0,v_m), m = 2..L-2
@@ -38,7 +42,7 @@ __device__ __forceinline__ void chord_of(const CycleSet &s, uint32_t q, int32_t 
 {
     a = b = 0;
 #pragma unroll
-    for (int k = 1; k < kCycleLists; ++k) {
+    for (int k = 1; k < kCycleLists; ++k) {   // 3-cycles and kept triangles have no chords
         if (q < s.chord_end[k]) {
             const uint32_t r = q - s.chord_end[k - 1], cyc = r / (uint32_t)k;
             const int32_t *v = s.c[k] + (uint32_t)(k + 3) * cyc;
@@ -53,11 +57,12 @@ __device__ __forceinline__ void fan_triangle(const CycleSet &s, uint32_t q, int3
 {
     a = b = c = 0;
 #pragma unroll
-    for (int k = 0; k < kCycleLists; ++k) {
+    for (int k = 0; k < kCycleSets; ++k) {
         if (q < s.fan_end[k]) {
-            const uint32_t r = q - (k ? s.fan_end[k - 1] : 0u), cyc = r / (uint32_t)(k + 1);
-            const int32_t *v = s.c[k] + (uint32_t)(k + 3) * cyc;   // list sizes stay below 2^31 entries
-            const uint32_t mm = 1u + (r - cyc * (uint32_t)(k + 1));
+            const uint32_t per = (uint32_t)(set_len(k) - 2);   // a constant once the loop is unrolled
+            const uint32_t r = q - (k ? s.fan_end[k - 1] : 0u), cyc = r / per;
+            const int32_t *v = s.c[k] + (uint32_t)set_len(k) * cyc;   // list sizes stay below 2^31 entries
+            const uint32_t mm = 1u + (r - cyc * per);
             a = v[0]; b = v[mm]; c = v[mm + 1];
             return;
         }
@@ -77,12 +82,12 @@ __global__ __launch_bounds__(kBlock) void k_validate_cycles(CycleSet s, int32_t 
                                                             const int32_t *j, int32_t *flag)
 {
     size_t q = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    if (q >= s.cyc_end[kCycleLists - 1]) return;
+    if (q >= s.cyc_end[kCycleSets - 1]) return;
     const int32_t *v = nullptr;
     int L = 0;
 #pragma unroll
-    for (int k = kCycleLists - 1; k >= 0; --k)
-        if (q < s.cyc_end[k]) { v = s.c[k] + (size_t)(k + 3) * ((uint32_t)q - (k ? s.cyc_end[k - 1] : 0u)); L = k + 3; }
+    for (int k = kCycleSets - 1; k >= 0; --k)
+        if (q < s.cyc_end[k]) { v = s.c[k] + (size_t)set_len(k) * ((uint32_t)q - (k ? s.cyc_end[k - 1] : 0u)); L = set_len(k); }
     int32_t x[kMaxCycleLen];
     bool bad = false;
     for (int a = 0; a < L; ++a) {
@@ -221,6 +226,38 @@ __global__ __launch_bounds__(kBlock) void k_triangle_edges(size_t nt, const KT *
     sval[3 * t + 0] = (uint32_t)(3 * t); sval[3 * t + 1] = (uint32_t)(3 * t + 1); sval[3 * t + 2] = (uint32_t)(3 * t + 2);
 }
 
+// Triangles kept from an earlier dual round take their costs along: `origin` is the fan index each
+// sorted key came from, the kept triangles occupy the fan indices [kept_begin, kept_end) in their
+// old order, and the run a key lies in is the triangle's new index.
+template <typename KT>
+__global__ __launch_bounds__(kBlock) void k_carry_costs(size_t nt, const uint32_t *origin, const uint32_t *pos,
+                                                        uint32_t kept_begin, uint32_t kept_end, const float *ct_old,
+                                                        float *ct)
+{
+    size_t q = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (q >= nt) return;
+    const uint32_t o = origin[q];
+    if (o < kept_begin || o >= kept_end) return;
+    const size_t t = pos[q + 1] - 1, old = o - kept_begin;
+    ct[3 * t] = ct_old[3 * old]; ct[3 * t + 1] = ct_old[3 * old + 1]; ct[3 * t + 2] = ct_old[3 * old + 2];
+}
+
+__global__ __launch_bounds__(kBlock) void k_iota_u32(size_t n, uint32_t *p)
+{
+    size_t k = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (k < n) p[k] = (uint32_t)k;
+}
+
+// node triple (u,v,w) of every triangle from its edges (u,v) and (u,w)
+__global__ __launch_bounds__(kBlock) void k_triangle_nodes(size_t T, const int32_t *tri_edge, const int32_t *i,
+                                                           const int32_t *j, int32_t *nodes)
+{
+    size_t t = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (t >= T) return;
+    const int32_t e0 = tri_edge[3 * t], e1 = tri_edge[3 * t + 1];
+    nodes[3 * t] = i[e0]; nodes[3 * t + 1] = j[e0]; nodes[3 * t + 2] = j[e1];
+}
+
 // ---------------------------------------------------------------------------------------------
 // message passing
 // ---------------------------------------------------------------------------------------------
@@ -357,16 +394,21 @@ rama_status copy_graph(Ctx &ctx, const Graph &g, Graph &out)
 
 rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *const *cycles, const int64_t *n_cycles,
                         bool validate_cycles, int k_iters, Graph &out, double *lower_bound, double *lb_trace,
-                        DualInfo *info)
+                        DualInfo *info, const DualState *prev, DualState *next)
 {
     if (lists < 0 || lists > kCycleLists || k_iters < 0 || (lists > 0 && (!cycles || !n_cycles)))
         return fail(ctx, RAMA_ERR_INVALID_ARG, "message passing: bad cycle lists or iteration count");
     CycleSet cs;
     size_t ncyc = 0, nfan = 0, nch = 0;
     double cycle_bytes = 0.0;
-    for (int k = 0; k < kCycleLists; ++k) {
+    const size_t T_kept = prev ? prev->T : 0;
+    for (int k = 0; k < kCycleSets; ++k) {
         cs.c[k] = nullptr;
-        if (k < lists) {
+        if (k == kCycleLists) {
+            cs.c[k] = prev ? prev->tri_nodes.get() : nullptr;
+            ncyc += T_kept;
+            nfan += T_kept;
+        } else if (k < lists) {
             if (n_cycles[k] < 0) return fail(ctx, RAMA_ERR_INVALID_ARG, "message passing: negative count");
             if (n_cycles[k] > 0 && !cycles[k]) return fail(ctx, RAMA_ERR_INVALID_ARG, "message passing: null cycle list");
             cs.c[k] = cycles[k];
@@ -486,9 +528,11 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
     Buf<int32_t> tri_edge;
     Buf<uint32_t> skey, slot;
     size_t T = 0;
+    Buf<float> ct;
     auto triangles = [&](auto key_tag) -> rama_status {
         using KT = decltype(key_tag);
         Buf<KT> tkey;
+        Buf<uint32_t> origin;
         RAMA_TRY(tkey.alloc(ctx, nfan));
         {
             ProfScope ps_(ctx, "k_triangle_keys", (double)(nfan * (12 + sizeof(KT))));
@@ -496,11 +540,30 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
                                                                           tkey.get(), flag.get());
         }
         LAUNCH_TRY(ctx, "triangle_keys");
-        RAMA_TRY((radix_sort_keys<KT>(ctx, tkey, nfan, kbits)));
+        if (T_kept > 0) {   // the sort also has to tell where the kept triangles end up
+            RAMA_TRY(origin.alloc(ctx, nfan));
+            {
+                ProfScope ps_(ctx, "k_iota", (double)(nfan * 4));
+                k_iota_u32<<<grid_for(nfan), kBlock, 0, ctx.stream>>>(nfan, origin.get());
+            }
+            LAUNCH_TRY(ctx, "iota");
+            RAMA_TRY((radix_sort_pairs<KT, uint32_t>(ctx, tkey, origin, nfan, kbits)));
+        } else {
+            RAMA_TRY((radix_sort_keys<KT>(ctx, tkey, nfan, kbits)));
+        }
         RAMA_TRY((exclusive_scan<uint32_t>(ctx, HeadFlagT<KT>{tkey.get()}, tpos.get(), nfan)));
         uint32_t T32 = 0;
         RAMA_TRY(read_back(ctx, &T32, tpos.get() + nfan, 4));
         T = T32;
+        RAMA_TRY(ct.alloc(ctx, 3 * T));
+        RAMA_TRY(fill<float>(ctx, ct.get(), 0.0f, 3 * T));
+        if (T_kept > 0) {
+            ProfScope ps_(ctx, "k_carry_costs", (double)(nfan * 8 + T_kept * 24));
+            k_carry_costs<KT><<<grid_for(nfan), kBlock, 0, ctx.stream>>>(nfan, origin.get(), tpos.get(),
+                                                                        cs.fan_end[kCycleLists - 1], cs.fan_end[kCycleLists],
+                                                                        prev->ct.get(), ct.get());
+            LAUNCH_TRY(ctx, "carry_costs");
+        }
         RAMA_TRY(tri_edge.alloc(ctx, 3 * T));
         RAMA_TRY(skey.alloc(ctx, 3 * T));
         RAMA_TRY(slot.alloc(ctx, 3 * T));
@@ -542,11 +605,9 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
     skey.reset();
     rowptr.reset();
     // ---- iterations ----------------------------------------------------------------------------
-    Buf<float> share, ct, msg;
+    Buf<float> share, msg;
     RAMA_TRY(share.alloc(ctx, ma));
-    RAMA_TRY(ct.alloc(ctx, 3 * T));
     RAMA_TRY(msg.alloc(ctx, 3 * T));
-    RAMA_TRY(fill<float>(ctx, ct.get(), 0.0f, 3 * T));
     float *ce = aug.c.get();
     {
         ProfScope ps_(ctx, "k_edge_init", (double)(na * 16));
@@ -585,6 +646,17 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
             RAMA_TRY(lower_bound_now(ctx, ce, ma, ct.get(), T, lb_dev.get()));
             RAMA_TRY(read_back(ctx, lower_bound, lb_dev.get(), 8));
         }
+    }
+    if (next) {
+        next->T = T;
+        RAMA_TRY(next->tri_nodes.alloc(ctx, 3 * T));
+        {
+            ProfScope ps_(ctx, "k_triangle_nodes", (double)(T * 36));
+            k_triangle_nodes<<<grid_for(T), kBlock, 0, ctx.stream>>>(T, tri_edge.get(), aug.i.get(), aug.j.get(),
+                                                                  next->tri_nodes.get());
+        }
+        LAUNCH_TRY(ctx, "triangle_nodes");
+        next->ct = std::move(ct);
     }
     out.n = aug.n; out.m = aug.m;
     out.i = std::move(aug.i); out.j = std::move(aug.j); out.c = std::move(aug.c);

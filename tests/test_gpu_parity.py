@@ -174,6 +174,43 @@ def test_message_passing_parity_longer_cycles(rama, oracle32, name, lmax, shorte
     print(name, lmax, shortest, "edges", want["i"].size, "bit-exact:", bool(np.array_equal(np_(got["c"]), want["c"])))
 
 
+# dual rounds on one graph: the triangle set and its costs persist from round to round
+DUAL_CASES = [(name, L, R) for name in CASES for (L, R) in ((3, 3), (4, 2), (5, 2))
+              if not (name in ("random_dense", "messy") and L > 3) and not (name == "grid2d_longrange_96" and L == 5)]
+
+
+@pytest.mark.parametrize("name,lmax,rounds", DUAL_CASES)
+def test_dual_rounds_parity(rama, oracle32, name, lmax, rounds):
+    from paper_2109_01838_amd import default_params
+    g = CASES[name]
+    n = g["n_nodes"]
+    want = oracle32.dual_rounds(n, g["i"], g["j"], g["c"], lmax, 5, rounds)
+    got = rama.dual_rounds(n, g["i"], g["j"], g["c"],
+                           default_params(max_cycle_len_first=lmax, mp_iters_first=5, dual_rounds=rounds))
+    assert np.array_equal(np_(got["i"]), want["i"]) and np.array_equal(np_(got["j"]), want["j"])
+    assert rel_close(np_(got["c"]), want["c"])
+    assert rel_close(got["lb_trace"], want["lb_trace"])
+    assert abs(got["lower_bound"] - want["lower_bound"]) <= REL * max(1.0, abs(want["lower_bound"]))
+    assert got["n_triangles"] == want["n_triangles"]
+    tr = np.asarray(got["lb_trace"])
+    assert np.all(np.diff(tr) >= -1e-5 * (1.0 + np.abs(tr[:-1])))
+    print(name, lmax, rounds, "LB", list(tr), "triangles", got["n_triangles"], "bit-exact:",
+          bool(np.array_equal(np_(got["c"]), want["c"])))
+
+
+def test_dual_rounds_one_round_is_separation_plus_message_passing(rama):
+    from paper_2109_01838_amd import default_params
+    g = CASES["knn_20000"]
+    n = g["n_nodes"]
+    cyc = rama.find_conflicted_cycles(n, g["i"], g["j"], g["c"], 5)
+    mp = rama.message_passing(n, g["i"], g["j"], g["c"], cyc, 10)
+    one = rama.dual_rounds(n, g["i"], g["j"], g["c"], default_params(dual_rounds=1))
+    assert np.array_equal(np_(one["c"]), np_(mp["c"])) and one["lower_bound"] == mp["lower_bound"]
+    zero = rama.dual_rounds(n, g["i"], g["j"], g["c"], default_params(dual_rounds=0))
+    assert zero["lb_trace"] == [zero["lower_bound"]] and zero["n_triangles"] == 0
+    assert abs(zero["lower_bound"] - float(np.minimum(g["c"], 0).astype(np.float64).sum())) <= 1e-9 * abs(zero["lower_bound"])
+
+
 def test_message_passing_cycle_order_is_irrelevant(rama, oracle32):
     g = CASES["knn_20000"]
     n = g["n_nodes"]
@@ -306,7 +343,7 @@ def test_solve_end_to_end(rama, oracle32, name):
 
 
 @pytest.mark.parametrize("variant", ["P", "PD+", "D", "PD-matching-only", "PD-forest-always", "PD-shortest",
-                                     "PD-7-then-4", "PD-7-shortest"])
+                                     "PD-7-then-4", "PD-7-shortest", "PD-2-dual-rounds", "D-3-dual-rounds"])
 def test_solver_variants(rama, oracle32, variant):
     from paper_2109_01838_amd import default_params
     g = CASES["knn_20000"]
@@ -318,7 +355,9 @@ def test_solver_variants(rama, oracle32, variant):
           "PD-forest-always": dict(forest_ratio=1.0),
           "PD-shortest": dict(shortest_only=True),
           "PD-7-then-4": dict(max_cycle_len_first=7, max_cycle_len_later=4),
-          "PD-7-shortest": dict(max_cycle_len_first=7, max_cycle_len_later=7, shortest_only=True)}[variant]
+          "PD-7-shortest": dict(max_cycle_len_first=7, max_cycle_len_later=7, shortest_only=True),
+          "PD-2-dual-rounds": dict(dual_rounds=2),
+          "D-3-dual-rounds": dict(max_rounds=1, dual_rounds=3, max_cycle_len_first=4)}[variant]
     want = oracle32.solve(n, g["i"], g["j"], g["c"], **kw)
     kw = {("shortest_cycles_only" if key == "shortest_only" else key): int(v) if key == "shortest_only" else v
           for key, v in kw.items()}

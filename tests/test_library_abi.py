@@ -20,7 +20,7 @@ def test_header_symbols_are_exported():
     lib = binding.load_library()
     names = declared_symbols()
     assert {"rama_create", "rama_destroy", "rama_last_error", "rama_find_conflicted_cycles",
-            "rama_message_passing", "rama_contract", "rama_solve"} <= set(names)
+            "rama_message_passing", "rama_dual_rounds", "rama_contract", "rama_solve"} <= set(names)
     for name in names:
         assert hasattr(lib, name), name
     assert set(names) == set(binding.EXPORTS)
@@ -32,8 +32,8 @@ def test_params_default_and_struct_layout():
     assert (p.max_cycle_len_first, p.max_cycle_len_later, p.mp_iters_first, p.mp_iters_later) == (5, 3, 10, 5)
     assert p.matching_rounds_cap == 32 and p.contract_threshold == 0.0 and p.max_rounds == 0
     assert abs(p.forest_ratio - 0.1) < 1e-7
-    assert p.shortest_cycles_only == 0
-    assert C.sizeof(binding.RamaParams) == 36
+    assert p.shortest_cycles_only == 0 and p.dual_rounds == 1
+    assert C.sizeof(binding.RamaParams) == 40
     assert C.sizeof(binding.RamaStats) == 112
 
 
