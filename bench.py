@@ -32,7 +32,7 @@ def make_workload(name):
     return inputs.make(name)
 
 
-def cpu_baseline(side, cycle_len, shortest_only):
+def cpu_baseline(side, cycle_len, shortest_only, dual_rounds):
     """The CPU oracle, as it stands, on a cube of cfg5's recipe small enough for ~10-30 s of CPU work."""
     import oracle
     from paper_2109_01838_amd import inputs
@@ -40,7 +40,7 @@ def cpu_baseline(side, cycle_len, shortest_only):
     o = oracle.Oracle("f32")
     t0 = time.perf_counter()
     r = o.solve(g["n_nodes"], g["i"], g["j"], g["c"], max_cycle_len_first=cycle_len[0],
-                max_cycle_len_later=cycle_len[1], shortest_only=shortest_only)
+                max_cycle_len_later=cycle_len[1], shortest_only=shortest_only, dual_rounds=dual_rounds)
     dt = time.perf_counter() - t0
     return {"value": g["i"].size / dt, "unit": "edges/s", "cores": 1, "kind": "oracle",
             "sample": f"cfg5 recipe on a {side}^3 crop ({g['i'].size} edges), full solve, {dt:.1f} s, "
@@ -61,6 +61,8 @@ def main():
                     help="longest conflicted cycle separated in the first / later rounds (default: solver PD, 5 3)")
     ap.add_argument("--shortest-only", action="store_true",
                     help="per repulsive edge separate only its shortest conflicted cycles")
+    ap.add_argument("--dual-rounds", type=int, default=1,
+                    help="separation + message-passing blocks per round on the same graph (default 1: the paper's loop)")
     ap.add_argument("--kernels", type=int, default=16, help="how many kernels the per-kernel table lists")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain 1 GiB device copy three times (reference reading for rocprofv3 --pmc "
@@ -78,11 +80,12 @@ def main():
     dev = torch.device("cuda:0")
     i, j, c = (torch.as_tensor(g[k]).to(dev) for k in ("i", "j", "c"))
     rama = Rama("cuda:0")
-    solver_name = ("PD" if args.cycle_len == [5, 3] and not args.shortest_only else "PD variant") + \
+    plain = args.cycle_len == [5, 3] and not args.shortest_only and args.dual_rounds == 1
+    solver_name = ("PD" if plain else "PD variant") + \
         f" (cycles<={args.cycle_len[0]} then <={args.cycle_len[1]}" + (", shortest only" if args.shortest_only else "") + \
-        ", k=10 then 5)"
+        (f", {args.dual_rounds} dual rounds per round" if args.dual_rounds != 1 else "") + ", k=10 then 5)"
     params = default_params(max_rounds=args.max_rounds, max_cycle_len_first=args.cycle_len[0],
-                            max_cycle_len_later=args.cycle_len[1], shortest_cycles_only=int(args.shortest_only))
+                            max_cycle_len_later=args.cycle_len[1], shortest_cycles_only=int(args.shortest_only), dual_rounds=args.dual_rounds)
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB read + 1 GiB written per copy
         dst = torch.empty_like(src)
@@ -159,7 +162,7 @@ def main():
                            "GBps": round(k["GBps"], 1), "frac_hbm": round(k["GBps"] / HBM_PEAK_GBS, 4),
                            "share": round(k["share"], 4)} for k in kernels[:args.kernels]]
     del labels
-    out["cpu_baseline"] = cpu_baseline(args.cpu_side, args.cycle_len, args.shortest_only) if args.cpu_side > 0 else None
+    out["cpu_baseline"] = cpu_baseline(args.cpu_side, args.cycle_len, args.shortest_only, args.dual_rounds) if args.cpu_side > 0 else None
     print(json.dumps(out))
 
 
