@@ -37,34 +37,68 @@ struct CycleSet {
     uint32_t chord_end[kCycleSets];  // and chords (L-3 per cycle)
 };
 
-// q-th chord: an L-cycle gives the L-3 chords (v0,v_m), m = 2..L-2
-__device__ __forceinline__ void chord_of(const CycleSet &s, uint32_t q, int32_t &a, int32_t &b)
+// The list an index falls into is found by a chain of compile-time cases: every access to the
+// set's arrays then has a constant index and the set stays in scalar registers (a loop with an early
+// exit made the compiler copy it to private memory, 128 bytes written per thread).
+template <int K>
+__device__ __forceinline__ void chord_pick(const CycleSet &s, uint32_t q, int32_t &a, int32_t &b)
 {
-    a = b = 0;
-#pragma unroll
-    for (int k = 1; k < kCycleLists; ++k) {   // 3-cycles and kept triangles have no chords
-        if (q < s.chord_end[k]) {
-            const uint32_t r = q - s.chord_end[k - 1], cyc = r / (uint32_t)k;
-            const int32_t *v = s.c[k] + (uint32_t)(k + 3) * cyc;
-            a = v[0]; b = v[2 + (r - cyc * (uint32_t)k)];
-            return;
+    // q-th chord: an L-cycle gives the L-3 chords (v0,v_m), m = 2..L-2; list K has K chords per cycle
+    if constexpr (K >= kCycleLists) {
+        a = b = 0;
+    } else {
+        if (q < s.chord_end[K]) {
+            const uint32_t r = q - s.chord_end[K - 1], cyc = r / (uint32_t)K;
+            const int32_t *v = s.c[K] + (uint32_t)(K + 3) * cyc;
+            a = v[0]; b = v[2 + (r - cyc * (uint32_t)K)];
+        } else {
+            chord_pick<K + 1>(s, q, a, b);
         }
     }
 }
-
-// q-th fan triangle (unsorted nodes): an L-cycle gives {v0,v_m,v_{m+1}}, m = 1..L-2
-__device__ __forceinline__ void fan_triangle(const CycleSet &s, uint32_t q, int32_t &a, int32_t &b, int32_t &c)
+__device__ __forceinline__ void chord_of(const CycleSet &s, uint32_t q, int32_t &a, int32_t &b)
 {
-    a = b = c = 0;
-#pragma unroll
-    for (int k = 0; k < kCycleSets; ++k) {
-        if (q < s.fan_end[k]) {
-            const uint32_t per = (uint32_t)(set_len(k) - 2);   // a constant once the loop is unrolled
-            const uint32_t r = q - (k ? s.fan_end[k - 1] : 0u), cyc = r / per;
-            const int32_t *v = s.c[k] + (uint32_t)set_len(k) * cyc;   // list sizes stay below 2^31 entries
+    chord_pick<1>(s, q, a, b);   // 3-cycles and kept triangles have no chords
+}
+
+template <int K>
+__device__ __forceinline__ void fan_pick(const CycleSet &s, uint32_t q, int32_t &a, int32_t &b, int32_t &c)
+{
+    // q-th fan triangle (unsorted nodes): an L-cycle gives {v0,v_m,v_{m+1}}, m = 1..L-2
+    if constexpr (K >= kCycleSets) {
+        a = b = c = 0;
+    } else {
+        if (q < s.fan_end[K]) {
+            constexpr uint32_t per = (uint32_t)(set_len(K) - 2);
+            uint32_t r = q;
+            if constexpr (K > 0) r -= s.fan_end[K - 1];
+            const uint32_t cyc = r / per;
+            const int32_t *v = s.c[K] + (uint32_t)set_len(K) * cyc;   // list sizes stay below 2^31 entries
             const uint32_t mm = 1u + (r - cyc * per);
             a = v[0]; b = v[mm]; c = v[mm + 1];
-            return;
+        } else {
+            fan_pick<K + 1>(s, q, a, b, c);
+        }
+    }
+}
+__device__ __forceinline__ void fan_triangle(const CycleSet &s, uint32_t q, int32_t &a, int32_t &b, int32_t &c)
+{
+    fan_pick<0>(s, q, a, b, c);
+}
+
+template <int K>
+__device__ __forceinline__ void cycle_pick(const CycleSet &s, uint32_t q, const int32_t *&v, int &L)
+{
+    if constexpr (K >= kCycleSets) {
+        v = nullptr; L = 0;
+    } else {
+        if (q < s.cyc_end[K]) {
+            uint32_t r = q;
+            if constexpr (K > 0) r -= s.cyc_end[K - 1];
+            v = s.c[K] + (size_t)set_len(K) * r;
+            L = set_len(K);
+        } else {
+            cycle_pick<K + 1>(s, q, v, L);
         }
     }
 }
@@ -83,11 +117,9 @@ __global__ __launch_bounds__(kBlock) void k_validate_cycles(CycleSet s, int32_t 
 {
     size_t q = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (q >= s.cyc_end[kCycleSets - 1]) return;
-    const int32_t *v = nullptr;
-    int L = 0;
-#pragma unroll
-    for (int k = kCycleSets - 1; k >= 0; --k)
-        if (q < s.cyc_end[k]) { v = s.c[k] + (size_t)set_len(k) * ((uint32_t)q - (k ? s.cyc_end[k - 1] : 0u)); L = set_len(k); }
+    const int32_t *v;
+    int L;
+    cycle_pick<0>(s, (uint32_t)q, v, L);
     int32_t x[kMaxCycleLen];
     bool bad = false;
     for (int a = 0; a < L; ++a) {

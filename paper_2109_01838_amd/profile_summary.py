@@ -44,14 +44,17 @@ def pmc(path, counter, subs):
 def event_name(rocprof_name):
     """Kernel name as the library's own timers spell it (bench.py's `kernels` table)."""
     n = short(rocprof_name)
-    n = (n.replace("unsigned long", "u64").replace("unsigned int", "u32").replace(", ", ",")
-          .replace(",true>", ">").replace("<u64,u32,false>", "<u64>").replace("<u32,u32,false>", "<u32>"))
+    n = n.replace("unsigned long", "u64").replace("unsigned int", "u32").replace(", ", ",")
+    if n.startswith("k_rs_scatter<"):
+        # <key, value, has values, offsets by local scan>: the timers name key and value types only
+        args = n[len("k_rs_scatter<"):].rstrip(">").split(",")
+        return f"k_rs_scatter<{args[0]},{args[1]}>" if args[2] == "true" else f"k_rs_scatter<{args[0]}>"
     if n.startswith(("k_scan_", "k_sum_partial")) and "<" in n:
         head, args = n.split("<", 1)
         functor = args.rstrip(">").split(",")[-1].split("<")[0].strip()
-        n = f"{head}<{functor}>"
-    if n.startswith("k_rs_hist<"):
-        n = n.replace(">", ">")
+        return f"{head}<{functor}>"
+    if "<" in n and not n.startswith("k_rs_hist<"):
+        return n.split("<", 1)[0]     # plain template arguments (lengths, flags) are not part of the timers' names
     return n
 
 
