@@ -3,6 +3,9 @@
   python -m paper_2109_01838_amd.profile_summary stats  <..._kernel_stats.csv> [n_solves]
   python -m paper_2109_01838_amd.profile_summary pmc    <..._counter_collection.csv> <COUNTER> [kernel substrings..]
   python -m paper_2109_01838_amd.profile_summary traffic <fetch.csv> <write.csv> <fetch_scale> <write_scale> <out.json>
+  python -m paper_2109_01838_amd.profile_summary report  <gpurun_out dir> <profiles dir>
+      (all of the above for bench.py's default workload: expects prof_bench/, pmc_fetch/, pmc_write/ and
+       bench_rocprof.log as the commands in the written files' headers leave them)
 """
 import csv
 import sys
@@ -78,8 +81,67 @@ def traffic_json(fetch_csv, write_csv, fetch_scale, write_scale, out_path):
               sort_keys=True)
 
 
+def capture(fn, *args):
+    import contextlib
+    import io
+    buf = io.StringIO()
+    with contextlib.redirect_stdout(buf):
+        fn(*args)
+    return buf.getvalue()
+
+
+def copy_calibration(path, counter):
+    """The runtime's own device-to-device copies of 1 GiB (bench.py --copy-calibration issues three)."""
+    vals = [float(r["Counter_Value"]) for r in csv.DictReader(open(path))
+            if r.get("Counter_Name") == counter and "copyBuffer" in r["Kernel_Name"]]
+    return [v for v in vals if v > 400000.0][:3]     # the 1 GiB copies, not the small read-backs
+
+
+def report(raw, out):
+    import json
+    import os
+    n_solves = 5      # bench.py default: 1 warm-up + 1 all-kernel-timed + 3 timed solves
+    d = json.loads([l for l in open(os.path.join(raw, "bench_rocprof.log")) if l.startswith("{")][-1])
+    r = d["roofline"]
+    stats_txt = capture(stats, os.path.join(raw, "prof_bench", "bench_kernel_stats.csv"), n_solves)
+    with open(os.path.join(out, "cfg5_solve_kernel_trace.txt"), "w") as f:
+        f.write(f"""# rocprofv3 kernel-trace summary: bench.py default run ({d['config']['workload']}, {d['config']['n_edges']} edges; 1 warm-up + 1 all-kernel-timed + 3 timed solves = {n_solves} solves)
+# command (on the GPU box, $REPO = repository root):
+#   cd /tmp && export TMPDIR=/tmp && rocprofv3 --kernel-trace --stats -d $REPO/gpurun_out/prof_bench -o bench --output-format csv -- python3 $REPO/bench.py > $REPO/gpurun_out/bench_rocprof.log
+# condensed with: python -m paper_2109_01838_amd.profile_summary report gpurun_out profiles
+# bench.py's own HIP-event figures for the dominant kernel in the same run:
+#   {r['kernel']} avg_launch_ms {r['avg_launch_ms']:.5f} launches_per_step {r['launches_per_step']} achieved GB/s {r['achieved']:.1f} frac {r['frac']:.4f}
+#   ms_per_step {d['ms_per_step']:.2f} edges/s {d['value']:.0f} (under the profiler)
+
+""")
+        f.write("\n".join(stats_txt.splitlines()[:28]) + "\n")
+    fetch = os.path.join(raw, "pmc_fetch", "fetch_counter_collection.csv")
+    write = os.path.join(raw, "pmc_write", "write_counter_collection.csv")
+    cf, cw = copy_calibration(fetch, "FETCH_SIZE"), copy_calibration(write, "WRITE_SIZE")
+    kib = 1048576.0
+    fs, ws = round(kib / (sum(cf) / len(cf)), 2), round(kib / (sum(cw) / len(cw)), 2)
+    traffic_json(fetch, write, fs, ws, os.path.join(out, "cfg5_solve_hbm_traffic.json"))
+    with open(os.path.join(out, "cfg5_solve_hbm_traffic.txt"), "w") as f:
+        f.write(f"""# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch), two separate runs, {d['config']['workload']}, one solve each
+# commands (on the GPU box, $REPO = repository root):
+#   rocprofv3 --pmc FETCH_SIZE -d $REPO/gpurun_out/pmc_fetch -o fetch --output-format csv -- python3 $REPO/bench.py --steps 1 --warmup 0 --no-profile --cpu-side 0 --copy-calibration
+#   rocprofv3 --pmc WRITE_SIZE -d $REPO/gpurun_out/pmc_write -o write --output-format csv -- python3 $REPO/bench.py --steps 1 --warmup 0 --no-profile --cpu-side 0 --copy-calibration
+# condensed with: python -m paper_2109_01838_amd.profile_summary report gpurun_out profiles
+# calibration: a plain 1 GiB -> 1 GiB device copy (1048576 KiB read, 1048576 KiB written) reads
+#   FETCH_SIZE {', '.join(f'{v:.1f}' for v in cf)}
+#   WRITE_SIZE {', '.join(f'{v:.1f}' for v in cw)}
+# => actual KiB read = {fs} x FETCH_SIZE, actual KiB written = {ws} x WRITE_SIZE
+# per-kernel bytes per launch (scaled) are in cfg5_solve_hbm_traffic.json
+
+""")
+        f.write("\n".join(capture(pmc, fetch, "FETCH_SIZE", ["k_"]).splitlines()[:25]) + "\n\n")
+        f.write("\n".join(capture(pmc, write, "WRITE_SIZE", ["k_"]).splitlines()[:25]) + "\n")
+
+
 if __name__ == "__main__":
-    if sys.argv[1] == "traffic":
+    if sys.argv[1] == "report":
+        report(sys.argv[2], sys.argv[3])
+    elif sys.argv[1] == "traffic":
         traffic_json(sys.argv[2], sys.argv[3], float(sys.argv[4]), float(sys.argv[5]), sys.argv[6])
     elif sys.argv[1] == "stats":
         stats(sys.argv[2], int(sys.argv[3]) if len(sys.argv) > 3 else 1)
