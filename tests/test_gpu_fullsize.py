@@ -154,3 +154,61 @@ def test_fullsize_solve_properties(big, dev):
     assert r["primal"] <= 0.9 * planted
     r2 = rama.solve(n, t["i"], t["j"], t["c"])
     assert r2["primal"] == r["primal"] and r2["lower_bound"] == r["lower_bound"]   # deterministic
+
+
+def test_fullsize_shortest_longer_cycles_sampled_windows(big, dev, oracle32):
+    """Separation up to length 7, shortest cycles only, at full size: global properties and windows
+    the oracle recomputes.  A cycle of length L with its repulsive edge >= 3 steps inside a window
+    cannot leave it (L <= 7: at most 3 steps away from either endpoint), and neither can a shorter
+    path that would rule it out."""
+    rama, t = dev
+    n = big["n_nodes"]
+    cyc = [x.cpu().numpy() for x in rama.find_conflicted_cycles(n, t["i"], t["j"], t["c"], 7, shortest_only=True)]
+    assert [x.shape[1] for x in cyc] == [3, 4, 5, 6, 7]
+    assert cyc[0].shape[0] == 0 and cyc[2].shape[0] == 0 and cyc[4].shape[0] == 0      # bipartite
+    assert cyc[1].shape[0] > 10_000_000 and cyc[3].shape[0] > 1_000_000
+    for x in (cyc[1], cyc[3]):
+        assert np.all(x[:, 0] < x[:, -1])
+        key = x[:, 0].astype(np.int64) * n + x[:, -1]
+        assert np.all(np.diff(key) >= 0)
+    # no repulsive edge has both a 4-cycle and a 6-cycle
+    k4 = np.unique(cyc[1][:, 0].astype(np.int64) * n + cyc[1][:, -1])
+    k6 = np.unique(cyc[3][:, 0].astype(np.int64) * n + cyc[3][:, -1])
+    assert np.intersect1d(k4, k6).size == 0
+    rng = np.random.default_rng(3)
+    w = 10
+    for _ in range(4):
+        z0, y0, x0 = (int(v) for v in rng.integers(0, SIDE - w, 3))
+        glob, li, lj, c = window_graph(big, z0, y0, x0, w)
+        want = oracle32.find_conflicted_cycles(glob.size, li, lj, c, 7, shortest_only=True)
+        for q in (1, 3):
+            wq = glob[want[q]]
+            keep_w = interior_mask(wq[:, 0], z0, y0, x0, w, 3) & interior_mask(wq[:, -1], z0, y0, x0, w, 3)
+            keep_g = interior_mask(cyc[q][:, 0], z0, y0, x0, w, 3) & interior_mask(cyc[q][:, -1], z0, y0, x0, w, 3)
+            a = sorted(map(tuple, wq[keep_w].tolist()))
+            b = sorted(map(tuple, cyc[q][keep_g].tolist()))
+            assert a == b and (q == 3 or len(a) > 0)
+
+
+def test_fullsize_dual_rounds_properties(big, dev):
+    from paper_2109_01838_amd import default_params
+    rama, t = dev
+    n = big["n_nodes"]
+    one = rama.dual_rounds(n, t["i"], t["j"], t["c"], default_params(dual_rounds=1))
+    two = rama.dual_rounds(n, t["i"], t["j"], t["c"], default_params(dual_rounds=2))
+    tr = np.asarray(two["lb_trace"])
+    assert abs(tr[0] - float(np.minimum(big["c"], 0).astype(np.float64).sum())) <= 1e-9 * abs(tr[0])
+    assert np.all(np.diff(tr) >= 0.0) and tr[1] == one["lb_trace"][1]       # round 1 is the same computation
+    assert two["n_triangles"] > one["n_triangles"] > 0
+    i2, j2 = two["i"].cpu().numpy(), two["j"].cpu().numpy()
+    key2 = i2.astype(np.int64) * n + j2
+    assert np.all(i2 < j2) and np.all(np.diff(key2) > 0)
+    key1 = one["i"].cpu().numpy().astype(np.int64) * n + one["j"].cpu().numpy()
+    assert np.all(np.isin(key1[:: 1009], key2))                             # chords of round 1 stay
+    # a solve with two dual rounds per round: valid labels, bound below primal, tighter than one round
+    base = rama.solve(n, t["i"], t["j"], t["c"])
+    r = rama.solve(n, t["i"], t["j"], t["c"], default_params(dual_rounds=2))
+    labels = r["labels"].cpu().numpy()
+    cut = labels[big["i"]] != labels[big["j"]]
+    assert abs(float(big["c"][cut].astype(np.float64).sum()) - r["primal"]) <= 1e-9 * abs(r["primal"])
+    assert base["lower_bound"] < r["lower_bound"] <= r["primal"]
