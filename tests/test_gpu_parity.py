@@ -35,7 +35,7 @@ def signed(g, seed, pos=0.7):
 
 
 def cases():
-    """name -> instance; sizes span several 4096-key sort tiles and 2048-item scan tiles with ragged tails."""
+    """name -> instance; sizes span several sort tiles (5120 or 6144 keys), on both sides of the 32-tile switch between the two offset schemes, and several 2048-item scan tiles, with ragged tails."""
     out = {}
     out["cfg1"] = inputs.cfg1()
     out["grid2d_longrange_96"] = inputs.cfg2(h=96, w=96, n_seeds=20)
