@@ -170,6 +170,29 @@ __device__ __forceinline__ void enumerate_cycles(const Adj &g, int32_t v0, int32
     extend_path<1, MAXL>(g, end, vl, max_len, path, emit);
 }
 
+// the walk below one given first hop v1 (what the walk from v0 does for each entry of its row)
+template <int MAXL, typename Emit>
+__device__ __forceinline__ void walk_from_first(const Adj &g, const EndRow &end, int32_t v0, int32_t v1, int32_t vl,
+                                                int max_len, Emit &emit)
+{
+    int32_t path[MAXL];
+    path[0] = v0; path[1] = v1;
+    if (end.has(v1)) emit.template cycle<3>(path);
+    if constexpr (MAXL >= 4)
+        if (max_len >= 4) extend_path<2, MAXL>(g, end, vl, max_len, path, emit);
+}
+
+// A repulsive edge whose first endpoint has a long attractive row is "heavy": one thread would walk
+// the whole row alone while its wave waits.  The per-thread kernels put such edges on a list
+// instead, and a second kernel gives each listed edge to a whole wave, one first hop per lane.
+// (Walks of length 3 are row intersections and stay with the per-thread kernels.)
+constexpr int kHeavyRow = 128;
+constexpr unsigned kHeavyGroups = 512;
+__device__ __forceinline__ bool heavy_edge(const Adj &g, int32_t v0, int max_len)
+{
+    return max_len >= 4 && g.ptr[v0 + 1] - g.ptr[v0] > kHeavyRow;
+}
+
 template <int MAXL>
 struct CountEmit {
     uint32_t n[MAXL - 2];
@@ -213,10 +236,20 @@ struct ListPtrs {
 template <int MAXL>
 __global__ __launch_bounds__(kBlock) void k_count_cycles(size_t nr, const int32_t *ri, const int32_t *rj, Adj g,
                                                          int max_len, int shortest_only,
-                                                         ListPtrs<uint32_t, MAXL - 2> cnt)
+                                                         ListPtrs<uint32_t, MAXL - 2> cnt, uint32_t *heavy,
+                                                         uint32_t *n_heavy)
 {
     size_t r = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    if (r >= nr) return;
+    const bool is_heavy = r < nr && heavy_edge(g, ri[r], max_len);
+    const unsigned long long vote = __ballot(is_heavy);
+    if (vote) {   // the wave's heavy edges join the list with one atomic
+        const int lane = (int)(threadIdx.x & 63);
+        uint32_t base = 0;
+        if (lane == __ffsll((long long)vote) - 1) base = atomicAdd(n_heavy, (uint32_t)__popcll(vote));
+        base = (uint32_t)__shfl((int)base, __ffsll((long long)vote) - 1, 64);
+        if (is_heavy) heavy[base + (uint32_t)__popcll(vote & ((1ull << lane) - 1ull))] = (uint32_t)r;
+    }
+    if (r >= nr || is_heavy) return;
     CountEmit<MAXL> em;
     em.clear();
     if (!shortest_only) {
@@ -234,6 +267,42 @@ __global__ __launch_bounds__(kBlock) void k_count_cycles(size_t nr, const int32_
 #pragma unroll
     for (int k = 0; k < MAXL - 2; ++k)
         if (k + 3 <= max_len) cnt.p[k][r] = em.n[k];
+}
+
+// counts of the listed heavy edges: a wave per edge, lane l takes the first hops l, l+64, ...
+template <int MAXL>
+__global__ __launch_bounds__(kBlock) void k_count_cycles_heavy(const uint32_t *heavy, const uint32_t *n_heavy,
+                                                               const int32_t *ri, const int32_t *rj, Adj g, int max_len,
+                                                               int shortest_only, ListPtrs<uint32_t, MAXL - 2> cnt)
+{
+    const uint32_t nh = *n_heavy;
+    const int lane = (int)(threadIdx.x & 63);
+    for (uint32_t h = blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6); h < nh; h += gridDim.x * (kBlock / 64)) {
+        const uint32_t r = heavy[h];
+        const int32_t v0 = ri[r], vl = rj[r];
+        EndRow end;
+        end.load(g, vl);
+        const int32_t r0 = g.ptr[v0], r1 = g.ptr[v0 + 1];
+        unsigned long long tot[MAXL - 2];
+        for (int L = shortest_only ? 3 : max_len; L <= max_len; ++L) {
+            CountEmit<MAXL> em;
+            em.clear();
+            if (end.b0 != end.b1)
+                for (int32_t p = r0 + lane; p < r1; p += 64) walk_from_first<MAXL>(g, end, v0, g.nb[p], vl, L, em);
+            unsigned long long any = 0;
+#pragma unroll
+            for (int k = 0; k < MAXL - 2; ++k) {
+                tot[k] = wave_sum((unsigned long long)em.n[k]);
+                any |= tot[k];
+            }
+            if (any) break;   // plain search: single pass at full depth; shortest only: first length that closes
+        }
+        if (lane == 0) {
+#pragma unroll
+            for (int k = 0; k < MAXL - 2; ++k)
+                if (k + 3 <= max_len) cnt.p[k][r] = tot[k] > 0xffffffffull ? 0xffffffffu : (uint32_t)tot[k];
+        }
+    }
 }
 
 template <int MAXL>
@@ -278,7 +347,7 @@ __global__ __launch_bounds__(kBlock) void k_check_saturated(size_t nr, ListPtrs<
 // longest cycle; writes every list at the offsets of the scan
 template <int MAXL>
 __global__ __launch_bounds__(kBlock) void k_fill_cycles(size_t nh, const uint32_t *hit, const int32_t *ri,
-                                                        const int32_t *rj, Adj g, int lists,
+                                                        const int32_t *rj, Adj g, int lists, int max_len,
                                                         ListPtrs<uint32_t, MAXL - 2> cnt,
                                                         ListPtrs<uint64_t, MAXL - 2> off,
                                                         ListPtrs<int32_t, MAXL - 2> out)
@@ -286,6 +355,7 @@ __global__ __launch_bounds__(kBlock) void k_fill_cycles(size_t nh, const uint32_
     size_t h = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (h >= nh) return;
     const uint32_t r = hit[h];
+    if (heavy_edge(g, ri[r], max_len)) return;   // written by k_fill_cycles_heavy
     int depth = 3;
     FillEmit<MAXL> em;
     em.vl = rj[r];
@@ -298,6 +368,56 @@ __global__ __launch_bounds__(kBlock) void k_fill_cycles(size_t nh, const uint32_
         }
     }
     enumerate_cycles<MAXL>(g, ri[r], em.vl, depth, em);
+}
+
+// cycles of the listed heavy edges: per round of 64 first hops every lane counts what its hop
+// closes, a wave scan turns the counts into places, and the lane walks again and writes
+template <int MAXL>
+__global__ __launch_bounds__(kBlock) void k_fill_cycles_heavy(const uint32_t *heavy, const uint32_t *n_heavy,
+                                                              const int32_t *ri, const int32_t *rj, Adj g, int lists,
+                                                              ListPtrs<uint32_t, MAXL - 2> cnt,
+                                                              ListPtrs<uint64_t, MAXL - 2> off,
+                                                              ListPtrs<int32_t, MAXL - 2> out)
+{
+    const uint32_t nh = *n_heavy;
+    const int lane = (int)(threadIdx.x & 63);
+    for (uint32_t h = blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6); h < nh; h += gridDim.x * (kBlock / 64)) {
+        const uint32_t r = heavy[h];
+        int depth = 0;
+        size_t place[MAXL - 2];   // cycles of this edge already written, per length
+#pragma unroll
+        for (int k = 0; k < MAXL - 2; ++k) {
+            place[k] = 0;
+            if (k < lists) {
+                if (cnt.p[k][r]) depth = k + 3;
+                place[k] = off.p[k][r];
+            }
+        }
+        if (depth == 0) continue;
+        const int32_t v0 = ri[r], vl = rj[r];
+        EndRow end;
+        end.load(g, vl);
+        const int32_t r0 = g.ptr[v0], r1 = g.ptr[v0 + 1];
+        for (int32_t p0 = r0; p0 < r1; p0 += 64) {
+            const int32_t p = p0 + lane;
+            const int32_t v1 = p < r1 ? g.nb[p] : -1;
+            CountEmit<MAXL> em;
+            em.clear();
+            if (v1 >= 0) walk_from_first<MAXL>(g, end, v0, v1, vl, depth, em);
+            FillEmit<MAXL> fe;
+            fe.vl = vl;
+#pragma unroll
+            for (int k = 0; k < MAXL - 2; ++k) {
+                fe.o[k] = nullptr;
+                if (k < lists) {
+                    const uint32_t inc = wave_inclusive_scan(em.n[k]);
+                    fe.o[k] = out.p[k] + (size_t)(k + 3) * (place[k] + (inc - em.n[k]));
+                    place[k] += wave_last(inc);
+                }
+            }
+            if (v1 >= 0) walk_from_first<MAXL>(g, end, v0, v1, vl, depth, fe);
+        }
+    }
 }
 
 // count, scan, fill for walks of at most MAXL nodes
@@ -319,11 +439,25 @@ rama_status count_and_fill(Ctx &ctx, size_t mr, const int32_t *ri, const int32_t
         RAMA_TRY(off[k].alloc(ctx, mr + 1));
         cp.p[k] = cnt[k].get(); op.p[k] = off[k].get();
     }
+    // heavy edges (only possible for max_len >= 4): listed by the first kernel, counted by the second,
+    // which ends at once when the list is empty
+    const bool may_be_heavy = max_len >= 4;
+    Buf<uint32_t> heavy, n_heavy;
+    RAMA_TRY(heavy.alloc(ctx, may_be_heavy ? mr : 1));
+    RAMA_TRY(n_heavy.alloc(ctx, 1));
+    RAMA_TRY(fill<uint32_t>(ctx, n_heavy.get(), 0u, 1));
     {
         ProfScope ps_(ctx, "k_count_cycles", (double)(mr * (8 + 4 * (size_t)lists) + ((size_t)n + 1) * 4 + mp * 8));
-        k_count_cycles<MAXL><<<grid_for(mr), kBlock, 0, ctx.stream>>>(mr, ri, rj, adj, max_len, shortest_only ? 1 : 0, cp);
+        k_count_cycles<MAXL><<<grid_for(mr), kBlock, 0, ctx.stream>>>(mr, ri, rj, adj, max_len, shortest_only ? 1 : 0, cp,
+                                                                     heavy.get(), n_heavy.get());
     }
     LAUNCH_TRY(ctx, "count_cycles");
+    if (may_be_heavy) {
+        ProfScope ps_(ctx, "k_count_cycles_heavy", 0.0);
+        k_count_cycles_heavy<MAXL><<<kHeavyGroups, kBlock, 0, ctx.stream>>>(heavy.get(), n_heavy.get(), ri, rj, adj, max_len,
+                                                                          shortest_only ? 1 : 0, cp);
+        LAUNCH_TRY(ctx, "count_cycles_heavy");
+    }
     if (MAXL > 5) {
         Buf<int32_t> flag;
         RAMA_TRY(flag.alloc(ctx, 1));
@@ -368,9 +502,15 @@ rama_status count_and_fill(Ctx &ctx, size_t mr, const int32_t *ri, const int32_t
     LAUNCH_TRY(ctx, "collect_hits");
     {
         ProfScope ps_(ctx, "k_fill_cycles", (double)((size_t)nh * (12 + 12 * (size_t)lists) + ((size_t)n + 1) * 4 + mp * 8) + list_bytes);
-        k_fill_cycles<MAXL><<<grid_for(nh), kBlock, 0, ctx.stream>>>(nh, hit.get(), ri, rj, adj, lists, cp, op, vp);
+        k_fill_cycles<MAXL><<<grid_for(nh), kBlock, 0, ctx.stream>>>(nh, hit.get(), ri, rj, adj, lists, max_len, cp, op, vp);
     }
     LAUNCH_TRY(ctx, "fill_cycles");
+    if (may_be_heavy) {
+        ProfScope ps_(ctx, "k_fill_cycles_heavy", 0.0);
+        k_fill_cycles_heavy<MAXL><<<kHeavyGroups, kBlock, 0, ctx.stream>>>(heavy.get(), n_heavy.get(), ri, rj, adj, lists, cp,
+                                                                         op, vp);
+        LAUNCH_TRY(ctx, "fill_cycles_heavy");
+    }
     return RAMA_OK;
 }
 

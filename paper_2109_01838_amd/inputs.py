@@ -164,6 +164,26 @@ def make(name, **kw):
     return {"cfg1": cfg1, "cfg2": cfg2, "cfg3": cfg3, "cfg4": cfg4, "cfg5": cfg5}[name](**kw)
 
 
+def hub_graph(n_nodes=4000, hubs=(0, 1, 2000, 3999), hub_degree=700, n_background=9000, seed=0, p_attractive=0.85):
+    """Skewed degrees: a sparse random background plus a few hubs joined to hub_degree random nodes each
+    (and to each other); N(0,1) magnitudes, attractive with probability p_attractive."""
+    rng = np.random.default_rng(seed)
+    a = rng.integers(0, n_nodes, n_background)
+    b = rng.integers(0, n_nodes, n_background)
+    for h in hubs:
+        others = rng.choice(n_nodes, hub_degree, replace=False)
+        a = np.concatenate([a, np.full(hub_degree, h)])
+        b = np.concatenate([b, others])
+    hh = np.array([(x, y) for x in hubs for y in hubs if x < y])
+    a, b = np.concatenate([a, hh[:, 0]]), np.concatenate([b, hh[:, 1]])
+    lo, hi = np.minimum(a, b), np.maximum(a, b)
+    key = np.unique(lo[lo != hi].astype(np.int64) * n_nodes + hi[lo != hi])
+    i, j = (key // n_nodes).astype(np.int32), (key % n_nodes).astype(np.int32)
+    mag = np.abs(rng.normal(0.0, 1.0, i.size)) + 0.05
+    c = np.where(rng.random(i.size) < p_attractive, mag, -mag).astype(np.float32)
+    return dict(name=f"hubs_{n_nodes}", n_nodes=int(n_nodes), i=i, j=j, c=c)
+
+
 def random_graph(n_nodes, n_edges, seed, scale=1.0, allow_messy=False):
     """Small random graph with N(0, scale) costs.  With allow_messy the edge list also
     contains self-loops, antiparallel duplicates and exact-zero costs (boundary hygiene tests)."""

@@ -106,6 +106,38 @@ def test_shortest_only_cycles_bit_exact(rama, oracle32, name, lmax):
             assert seen.setdefault((a, b), L) == L
 
 
+# skewed degrees: repulsive edges at hubs (attractive rows of ~600 entries) take the wave-per-edge path
+@pytest.fixture(scope="module")
+def hubs():
+    return inputs.hub_graph()
+
+
+@pytest.mark.parametrize("lmax,shortest", [(3, False), (4, False), (5, False), (4, True), (5, True), (7, True)])
+def test_heavy_rows_cycles_bit_exact(rama, oracle32, hubs, lmax, shortest):
+    g = hubs
+    deg = np.bincount(np.concatenate([g["i"][g["c"] > 0], g["j"][g["c"] > 0]]), minlength=g["n_nodes"])
+    assert deg.max() > 500 and np.median(deg) < 10
+    want = oracle32.find_conflicted_cycles(g["n_nodes"], g["i"], g["j"], g["c"], lmax, shortest_only=shortest)
+    got = rama.find_conflicted_cycles(g["n_nodes"], g["i"], g["j"], g["c"], lmax, shortest_only=shortest)
+    for L in range(lmax - 2):
+        assert np.array_equal(np_(got[L]), want[L]), (lmax, shortest, L + 3, got[L].shape, want[L].shape)
+    # the hubs' own repulsive edges are among the results
+    heavy = set(np.where(deg > 128)[0].tolist())
+    assert any(int(v) in heavy for L in range(lmax - 2) for v in np.unique(want[L][:, 0]))
+    print(lmax, shortest, [x.shape[0] for x in want])
+
+
+def test_heavy_rows_solve(rama, oracle32, hubs):
+    g = hubs
+    n = g["n_nodes"]
+    want = oracle32.solve(n, g["i"], g["j"], g["c"])
+    got = rama.solve(n, g["i"], g["j"], g["c"])
+    assert got["n_cycles_first"] == want["n_cycles_first"]
+    assert abs(got["lower_bound"] - want["lower_bound"]) <= REL * max(1.0, abs(want["lower_bound"]))
+    assert abs(got["primal"] - want["primal"]) <= 5e-3 * max(1.0, abs(want["primal"]))
+    print("hubs: labels identical:", bool(np.array_equal(np_(got["labels"]), want["labels"])), got["primal"], want["primal"])
+
+
 def test_cycles_capacity_protocol(rama):
     import ctypes as C
     import torch
