@@ -3,7 +3,7 @@
   python -m paper_2109_01838_amd.profile_summary stats  <..._kernel_stats.csv> [n_solves]
   python -m paper_2109_01838_amd.profile_summary pmc    <..._counter_collection.csv> <COUNTER> [kernel substrings..]
   python -m paper_2109_01838_amd.profile_summary traffic <fetch.csv> <write.csv> <fetch_scale> <write_scale> <out.json>
-  python -m paper_2109_01838_amd.profile_summary report  <gpurun_out dir> <profiles dir>
+  python -m paper_2109_01838_amd.profile_summary report  <raw output dir> <profiles dir>
       (all of the above for bench.py's default workload: expects prof_bench/, pmc_fetch/, pmc_write/ and
        bench_rocprof.log as the commands in the written files' headers leave them)
 """
@@ -106,9 +106,9 @@ def report(raw, out):
     stats_txt = capture(stats, os.path.join(raw, "prof_bench", "bench_kernel_stats.csv"), n_solves)
     with open(os.path.join(out, "cfg5_solve_kernel_trace.txt"), "w") as f:
         f.write(f"""# rocprofv3 kernel-trace summary: bench.py default run ({d['config']['workload']}, {d['config']['n_edges']} edges; 1 warm-up + 1 all-kernel-timed + 3 timed solves = {n_solves} solves)
-# command (on the GPU box, $REPO = repository root):
-#   cd /tmp && export TMPDIR=/tmp && rocprofv3 --kernel-trace --stats -d $REPO/gpurun_out/prof_bench -o bench --output-format csv -- python3 $REPO/bench.py > $REPO/gpurun_out/bench_rocprof.log
-# condensed with: python -m paper_2109_01838_amd.profile_summary report gpurun_out profiles
+# command (on the GPU box; $REPO = repository root, $OUT = any scratch directory):
+#   cd /tmp && export TMPDIR=/tmp && rocprofv3 --kernel-trace --stats -d $OUT/prof_bench -o bench --output-format csv -- python3 $REPO/bench.py > $OUT/bench_rocprof.log
+# condensed with: python -m paper_2109_01838_amd.profile_summary report $OUT profiles
 # bench.py's own HIP-event figures for the dominant kernel in the same run:
 #   {r['kernel']} avg_launch_ms {r['avg_launch_ms']:.5f} launches_per_step {r['launches_per_step']} achieved GB/s {r['achieved']:.1f} frac {r['frac']:.4f}
 #   ms_per_step {d['ms_per_step']:.2f} edges/s {d['value']:.0f} (under the profiler)
@@ -123,10 +123,10 @@ def report(raw, out):
     traffic_json(fetch, write, fs, ws, os.path.join(out, "cfg5_solve_hbm_traffic.json"))
     with open(os.path.join(out, "cfg5_solve_hbm_traffic.txt"), "w") as f:
         f.write(f"""# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch), two separate runs, {d['config']['workload']}, one solve each
-# commands (on the GPU box, $REPO = repository root):
-#   rocprofv3 --pmc FETCH_SIZE -d $REPO/gpurun_out/pmc_fetch -o fetch --output-format csv -- python3 $REPO/bench.py --steps 1 --warmup 0 --no-profile --cpu-side 0 --copy-calibration
-#   rocprofv3 --pmc WRITE_SIZE -d $REPO/gpurun_out/pmc_write -o write --output-format csv -- python3 $REPO/bench.py --steps 1 --warmup 0 --no-profile --cpu-side 0 --copy-calibration
-# condensed with: python -m paper_2109_01838_amd.profile_summary report gpurun_out profiles
+# commands (on the GPU box; $REPO = repository root, $OUT = any scratch directory):
+#   rocprofv3 --pmc FETCH_SIZE -d $OUT/pmc_fetch -o fetch --output-format csv -- python3 $REPO/bench.py --steps 1 --warmup 0 --no-profile --cpu-side 0 --copy-calibration
+#   rocprofv3 --pmc WRITE_SIZE -d $OUT/pmc_write -o write --output-format csv -- python3 $REPO/bench.py --steps 1 --warmup 0 --no-profile --cpu-side 0 --copy-calibration
+# condensed with: python -m paper_2109_01838_amd.profile_summary report $OUT profiles
 # calibration: a plain 1 GiB -> 1 GiB device copy (1048576 KiB read, 1048576 KiB written) reads
 #   FETCH_SIZE {', '.join(f'{v:.1f}' for v in cf)}
 #   WRITE_SIZE {', '.join(f'{v:.1f}' for v in cw)}
