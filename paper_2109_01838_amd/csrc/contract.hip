@@ -591,7 +591,8 @@ static rama_status forest_set(Ctx &ctx, const Graph &g, float tau, Buf<int32_t> 
     LAUNCH_TRY(ctx, "root_init");
     const int levels_per_check = 8;
     for (int32_t lvl = 0;; lvl += levels_per_check) {
-        if ((size_t)lvl > n) return fail(ctx, RAMA_ERR_HIP, "forest rooting did not converge");
+        // a tree is at most n-1 levels deep; the sweep after the deepest level reports no change
+        if ((size_t)lvl > n + levels_per_check) return fail(ctx, RAMA_ERR_HIP, "forest rooting did not converge");
         RAMA_TRY(fill<int32_t>(ctx, changed.get(), 0, 1));
         for (int q = 0; q < levels_per_check; ++q) {
             ProfScope ps_(ctx, "k_root_level", (double)((size_t)nf * 20));

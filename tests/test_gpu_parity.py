@@ -310,17 +310,20 @@ def test_contract_forest_parity(rama, oracle32, name, repeat):
         assert not np.any((mp["c"] < 0) & (mp_[mp["i"]] == mp_[mp["j"]]))
 
 
-def test_forest_deep_tree(rama, oracle32):
-    # a long attractive path with a few repulsive chords: trees of depth ~ thousands of levels
-    n = 6000
+@pytest.mark.parametrize("n", [9, 26, 30, 31, 32, 33, 41, 6000])
+def test_forest_deep_tree(rama, oracle32, n):
+    # a long attractive path with a few repulsive chords: one tree as deep as the graph has nodes (the
+    # small sizes put the deepest level on either side of the rooting loop's check interval)
     i = np.arange(n - 1, dtype=np.int32)
     j = i + 1
     rng = np.random.default_rng(3)
     c = rng.uniform(0.5, 1.5, n - 1).astype(np.float32)
-    ci = rng.integers(0, n - 200, 40).astype(np.int32)
-    cj = (ci + rng.integers(2, 200, 40)).astype(np.int32)
+    k = max(1, min(40, n // 8))
+    span = max(3, min(200, n // 2))
+    ci = rng.integers(0, n - span, k).astype(np.int32)
+    cj = (ci + rng.integers(2, span, k)).astype(np.int32)
     ii, jj = np.concatenate([i, ci]), np.concatenate([j, cj])
-    cc = np.concatenate([c, -np.ones(40, np.float32)])
+    cc = np.concatenate([c, -np.ones(k, np.float32)])
     from paper_2109_01838_amd import default_params
     want = oracle32.contract(n, ii, jj, cc, repeat=1, forest_ratio=1.0)
     got = rama.contract(n, ii, jj, cc, params=default_params(forest_ratio=1.0), repeat=1)
@@ -463,3 +466,44 @@ def test_profile_hooks_and_workspace(rama):
     rama.profile_enable(False)
     assert only and all(k["name"].startswith("k_rs_scatter") for k in only)
     assert rama.workspace_bytes() > 0
+
+
+def test_random_sweep_of_small_instances_and_parameters(rama, oracle32):
+    """Seeded sweep: small random / grid instances with random solver parameters (cycle lengths,
+    iteration counts, forest switch, round limit, dual rounds, shortest-only).  Labels, cycle counts,
+    rounds and bounds must agree with the oracle on every one.  (Such a sweep found a rooting loop
+    that gave up one check too early on trees about as deep as the graph has nodes.)"""
+    from paper_2109_01838_amd import default_params
+    rng = np.random.default_rng(7)
+    bad = []
+    for it in range(160):
+        kind = int(rng.integers(0, 4))
+        seed = int(rng.integers(0, 1 << 30))
+        if kind == 0:
+            g = inputs.random_graph(int(rng.integers(2, 60)), int(rng.integers(1, 400)), seed, allow_messy=bool(rng.integers(0, 2)))
+        elif kind == 1:
+            n = int(rng.integers(50, 2000))
+            g = inputs.random_graph(n, int(n * rng.uniform(1.0, 3.0)), seed)
+            g = signed(g, seed, float(rng.uniform(0.5, 0.95)))
+        elif kind == 2:
+            g = inputs.cfg5_crop(int(rng.integers(3, 12)), seed=seed % 1000)
+        else:
+            g = inputs.cfg2(seed=seed % 1000, h=int(rng.integers(10, 30)), w=int(rng.integers(10, 30)), n_seeds=int(rng.integers(2, 12)))
+        n = g["n_nodes"]
+        shortest = bool(rng.integers(0, 2))
+        kw = dict(max_cycle_len_first=int(rng.choice([0, 3, 4, 5, 6])), max_cycle_len_later=int(rng.choice([0, 3, 4])),
+                  mp_iters_first=int(rng.integers(0, 8)), mp_iters_later=int(rng.integers(0, 5)),
+                  forest_ratio=float(rng.choice([0.0, 0.1, 0.5, 1.0])), max_rounds=int(rng.choice([0, 0, 0, 1, 2, 3])),
+                  dual_rounds=int(rng.choice([1, 1, 2, 3])))
+        if kw["dual_rounds"] > 1 or (kind == 3 and not shortest):   # keeps the oracle's enumeration in seconds
+            kw["max_cycle_len_first"] = min(kw["max_cycle_len_first"], 4 if kw["dual_rounds"] > 1 else 5)
+            kw["max_cycle_len_later"] = min(kw["max_cycle_len_later"], 3)
+        want = oracle32.solve(n, g["i"], g["j"], g["c"], shortest_only=shortest, **kw)
+        got = rama.solve(n, g["i"], g["j"], g["c"], default_params(shortest_cycles_only=int(shortest), **kw))
+        ok = (np.array_equal(np_(got["labels"]), want["labels"]) and got["n_cycles_first"] == want["n_cycles_first"]
+              and got["rounds"] == want["rounds"]
+              and abs(got["lower_bound"] - want["lower_bound"]) <= REL * max(1.0, abs(want["lower_bound"]))
+              and abs(got["primal"] - want["primal"]) <= 5e-3 * max(1.0, abs(want["primal"])))
+        if not ok:
+            bad.append((it, kind, seed, n, kw, shortest))
+    assert not bad, bad
