@@ -306,6 +306,13 @@ static_assert(kRadix >= kBlock && kRadix % kBlock == 0, "radix must be a multipl
 // histogram) were also measured: the scatter kernels ran 25-50 % slower while they waited on the
 // agent-scope status words, the all-digit histogram is bound by its LDS atomics, and the whole
 // solve took 11 % longer than with histogram + scan + scatter per pass.
+// Where one pass over 9.8e7 (64-bit key, value) pairs spends its time (one 8-bit pass, measured with
+// keys built for the purpose): the scatter kernel takes 0.78 ms on uniformly random digits, 0.57 ms
+// when every key has the same digit (the output is then one sequential stream), and 0.47 ms for a
+// 4-bit digit with sequential output -- so roughly 0.37 ms is moving the 24 bytes per key (6.3 TB/s),
+// 0.2 ms the ballot ranking (about 26 us per digit bit) and 0.2 ms the cost of writing 256 separate
+// pieces of ~24 keys per tile.  Computing all rows' ballots before touching the counters, or
+// skipping the ballots for rows with a single digit, changed nothing measurable.
 template <typename K>
 struct alignas(16) KeyVec {
     K k[16 / sizeof(K)];
