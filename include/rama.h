@@ -82,7 +82,8 @@ typedef struct {
     int64_t n_edges_aug_first;  /* edges after adding chords, first round */
     int64_t n_edges_final;      /* edges of the last contracted graph */
     double ms_total;            /* wall time of the call */
-    double ms_cycles, ms_dual, ms_contract, ms_other; /* host-clock split by stage */
+    double ms_cycles, ms_dual, ms_contract, ms_other; /* host-clock split by stage; with dual_rounds > 1
+                                   separation and message passing interleave and are both booked as ms_cycles */
 } rama_stats;
 
 /* Create a context on the current HIP device.  `hip_stream` is a hipStream_t (may be NULL
