@@ -507,3 +507,31 @@ def test_random_sweep_of_small_instances_and_parameters(rama, oracle32):
         if not ok:
             bad.append((it, kind, seed, n, kw, shortest))
     assert not bad, bad
+
+
+def test_context_on_a_side_stream_and_two_contexts(rama):
+    """A context bound to a non-default stream (default priority) gives the same result as the
+    default-stream context, also when the two are used in turn."""
+    import torch
+    from paper_2109_01838_amd import Rama
+    g = CASES["grid3d_24"]
+    n = g["n_nodes"]
+    base = rama.solve(n, g["i"], g["j"], g["c"])
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        other = Rama("cuda:0")
+        assert other.stream.cuda_stream == side.cuda_stream and other.stream.cuda_stream != rama.stream.cuda_stream
+        a = other.solve(n, g["i"], g["j"], g["c"])
+        cyc = other.find_conflicted_cycles(n, g["i"], g["j"], g["c"], 5)
+    side.synchronize()
+    b = rama.solve(n, g["i"], g["j"], g["c"])
+    with torch.cuda.stream(side):
+        a2 = other.solve(n, g["i"], g["j"], g["c"])
+    side.synchronize()
+    for r in (a, b, a2):
+        assert np.array_equal(np_(r["labels"]), np_(base["labels"])) and r["primal"] == base["primal"]
+        assert r["lower_bound"] == base["lower_bound"]
+    want = rama.find_conflicted_cycles(n, g["i"], g["j"], g["c"], 5)
+    assert all(np.array_equal(np_(x), np_(y)) for x, y in zip(cyc, want))
+    other.close()
