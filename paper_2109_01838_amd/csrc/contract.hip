@@ -39,11 +39,15 @@ struct CandFlag {
     __device__ __forceinline__ uint32_t operator()(size_t e) const { return c[e] > tau ? 1u : 0u; }
 };
 
-__global__ __launch_bounds__(kBlock) void k_collect(size_t m, const float *c, float tau, const uint32_t *pos, uint32_t *act)
-{
-    size_t e = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    if (e < m && c[e] > tau) act[pos[e]] = (uint32_t)e;
-}
+// consumer of the scan over CandFlag: the list of candidate edges
+struct CollectEmit {
+    static constexpr const char *tag = "Collect";
+    uint32_t *act;
+    __device__ __forceinline__ void operator()(size_t e, uint32_t cand, uint32_t p) const
+    {
+        if (cand) act[p] = (uint32_t)e;
+    }
+};
 
 // Both endpoints of a candidate edge learn its rank.  The candidate list of the first round is
 // in canonical order, so neighbouring lanes often share the first endpoint: those lanes combine
@@ -150,13 +154,16 @@ struct MatchedLow {
     __device__ __forceinline__ uint32_t operator()(size_t v) const { return mate[v] > (int32_t)v ? 1u : 0u; }
 };
 
-__global__ __launch_bounds__(kBlock) void k_emit_pairs(size_t n, const int32_t *mate, const uint32_t *pos, int32_t *si,
-                                                       int32_t *sj)
-{
-    size_t v = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    if (v >= n) return;
-    if (mate[v] > (int32_t)v) { si[pos[v]] = (int32_t)v; sj[pos[v]] = mate[v]; }
-}
+// consumer of the scan over MatchedLow: the matched pairs as an edge list
+struct EmitPairs {
+    static constexpr const char *tag = "EmitPairs";
+    const int32_t *mate;
+    int32_t *si, *sj;
+    __device__ __forceinline__ void operator()(size_t v, uint32_t low, uint32_t p) const
+    {
+        if (low) { si[p] = (int32_t)v; sj[p] = mate[v]; }
+    }
+};
 
 // ---- connected components of (V,S) -------------------------------------------------------------
 __global__ __launch_bounds__(kBlock) void k_iota(size_t n, int32_t *p)
@@ -234,17 +241,22 @@ struct NotLoopKey {
     const uint64_t *raw;
     __device__ __forceinline__ uint32_t operator()(size_t e) const { return raw[e] != kLoopKey ? 1u : 0u; }
 };
-__global__ __launch_bounds__(kBlock) void k_compact_keys(size_t m, const uint64_t *raw, const float *c,
-                                                         const uint32_t *pos, int dbits, uint64_t *key, uint32_t *val)
-{
-    size_t e = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    if (e >= m) return;
-    uint64_t k = raw[e];
-    if (k == kLoopKey) return;
-    uint32_t p = pos[e];
-    key[p] = ((k >> 32) << dbits) | (k & 0xFFFFFFFFull);
-    val[p] = __float_as_uint(c[e]);
-}
+// consumer of the scan over NotLoopKey: edge e that survives goes to place p
+struct CompactKeysEmit {
+    static constexpr const char *tag = "CompactKeys";
+    const uint64_t *raw;
+    const float *c;
+    int dbits;
+    uint64_t *key;
+    uint32_t *val;
+    __device__ __forceinline__ void operator()(size_t e, uint32_t keep, uint32_t p) const
+    {
+        if (!keep) return;
+        const uint64_t k = raw[e];
+        key[p] = ((k >> 32) << dbits) | (k & 0xFFFFFFFFull);
+        val[p] = __float_as_uint(c[e]);
+    }
+};
 
 __global__ __launch_bounds__(kBlock) void k_inner(size_t m, const int32_t *i, const int32_t *j, const float *c,
                                                   const int32_t *fmap, const uint32_t *pos, uint32_t *key, uint32_t *val)
@@ -433,26 +445,27 @@ __global__ __launch_bounds__(kBlock) void k_mark_conflicts(size_t m, const int32
 }  // namespace
 
 // handshake matching; mate[v] = partner or -1; returns |S| in n_matched
-static rama_status matching(Ctx &ctx, const Graph &g, float tau, int rounds_cap, Buf<int32_t> &mate, int64_t &n_matched)
+static rama_status matching(Ctx &ctx, const Graph &g, float tau, int rounds_cap, Buf<int32_t> &mate, int64_t &n_matched,
+                            ScanPlan<uint32_t> &pairs)
 {
     const size_t m = (size_t)g.m, n = (size_t)g.n;
     n_matched = 0;
+    pairs.n = 0;
     RAMA_TRY(mate.alloc(ctx, n > 0 ? n : 1));
     RAMA_TRY(fill<int32_t>(ctx, mate.get(), -1, n));
     if (m == 0) return RAMA_OK;
-    Buf<uint32_t> pos, act, act2;
-    RAMA_TRY(pos.alloc(ctx, m + 1));
-    RAMA_TRY((exclusive_scan<uint32_t>(ctx, CandFlag{g.c.get(), tau}, pos.get(), m)));
+    Buf<uint32_t> act, act2;
     uint32_t na = 0;
-    RAMA_TRY(read_back(ctx, &na, pos.get() + m, 4));
-    if (na == 0) return RAMA_OK;
-    RAMA_TRY(act.alloc(ctx, na));
-    RAMA_TRY(act2.alloc(ctx, na));
     {
-        ProfScope ps_(ctx, "k_collect", (double)(m * 8 + (size_t)na * 4));
-        k_collect<<<grid_for(m), kBlock, 0, ctx.stream>>>(m, g.c.get(), tau, pos.get(), act.get());
+        ScanPlan<uint32_t> cand;
+        RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, m, 0, cand)));
+        RAMA_TRY((scan_totals<uint32_t>(ctx, CandFlag{g.c.get(), tau}, cand)));
+        na = cand.total;
+        if (na == 0) return RAMA_OK;
+        RAMA_TRY(act.alloc(ctx, na));
+        RAMA_TRY(act2.alloc(ctx, na));
+        RAMA_TRY((scan_emit<uint32_t>(ctx, CandFlag{g.c.get(), tau}, CollectEmit{act.get()}, cand, (double)((size_t)na * 4))));
     }
-    LAUNCH_TRY(ctx, "collect");
     Buf<unsigned long long> best, best_next;     // rank words of the current and of the next round
     RAMA_TRY(best.alloc(ctx, n));
     RAMA_TRY(best_next.alloc(ctx, n));
@@ -485,12 +498,10 @@ static rama_status matching(Ctx &ctx, const Graph &g, float tau, int rounds_cap,
         best.swap(best_next);
         na = nn;
     }
-    Buf<uint32_t> npos;
-    RAMA_TRY(npos.alloc(ctx, n + 1));
-    RAMA_TRY((exclusive_scan<uint32_t>(ctx, MatchedLow{mate.get()}, npos.get(), n)));
-    uint32_t ns = 0;
-    RAMA_TRY(read_back(ctx, &ns, npos.get() + n, 4));
-    n_matched = ns;
+    // number of pairs; the plan is kept for the caller, who lists the pairs with it
+    RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, n, 0, pairs)));
+    RAMA_TRY((scan_totals<uint32_t>(ctx, MatchedLow{mate.get()}, pairs)));
+    n_matched = pairs.total;
     return RAMA_OK;
 }
 
@@ -501,17 +512,17 @@ static rama_status forest_set(Ctx &ctx, const Graph &g, float tau, Buf<int32_t> 
     n_set = 0;
     Buf<uint32_t> pos, act, act2, counters;
     RAMA_TRY(pos.alloc(ctx, m + 1));
-    RAMA_TRY((exclusive_scan<uint32_t>(ctx, CandFlag{g.c.get(), tau}, pos.get(), m)));
     uint32_t na = 0;
-    RAMA_TRY(read_back(ctx, &na, pos.get() + m, 4));
-    if (na == 0) return RAMA_OK;
-    RAMA_TRY(act.alloc(ctx, na));
-    RAMA_TRY(act2.alloc(ctx, na));
     {
-        ProfScope ps_(ctx, "k_collect", (double)(m * 8 + (size_t)na * 4));
-        k_collect<<<grid_for(m), kBlock, 0, ctx.stream>>>(m, g.c.get(), tau, pos.get(), act.get());
+        ScanPlan<uint32_t> cand;
+        RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, m, 0, cand)));
+        RAMA_TRY((scan_totals<uint32_t>(ctx, CandFlag{g.c.get(), tau}, cand)));
+        na = cand.total;
+        if (na == 0) return RAMA_OK;
+        RAMA_TRY(act.alloc(ctx, na));
+        RAMA_TRY(act2.alloc(ctx, na));
+        RAMA_TRY((scan_emit<uint32_t>(ctx, CandFlag{g.c.get(), tau}, CollectEmit{act.get()}, cand, (double)((size_t)na * 4))));
     }
-    LAUNCH_TRY(ctx, "collect");
     Buf<unsigned long long> best;
     Buf<int32_t> comp, hook;
     Buf<uint8_t> in_forest, removed;
@@ -664,21 +675,18 @@ static rama_status contract_edges(Ctx &ctx, const Graph &g, const int32_t *fmap,
     out.n = n_new;
     out.m = 0;
     const int nbits = bits_for((uint64_t)n_new);
-    Buf<uint32_t> pos;
+    ScanPlan<uint32_t> keep;   // the extra word behind the total: largest hi-lo
     Buf<uint64_t> raw;
-    RAMA_TRY(pos.alloc(ctx, m + 2));                       // pos[m] = kept edges, pos[m+1] = largest hi-lo
+    RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, m, 1, keep)));
     RAMA_TRY(raw.alloc(ctx, m));
-    RAMA_TRY(fill<uint32_t>(ctx, pos.get() + m + 1, 0u, 1));
     {
         ProfScope ps_(ctx, "k_relabel_keys", (double)(m * 24));
-        k_relabel_keys<<<grid_for(m), kBlock, 0, ctx.stream>>>(m, g.i.get(), g.j.get(), fmap, raw.get(), pos.get() + m + 1);
+        k_relabel_keys<<<grid_for(m), kBlock, 0, ctx.stream>>>(m, g.i.get(), g.j.get(), fmap, raw.get(), keep.extra_ptr());
     }
     LAUNCH_TRY(ctx, "relabel_keys");
-    RAMA_TRY((exclusive_scan<uint32_t>(ctx, NotLoopKey{raw.get()}, pos.get(), m)));
-    uint32_t tail[2] = {0, 0};
-    RAMA_TRY(read_back(ctx, tail, pos.get() + m, 8));
-    const uint32_t kept = tail[0];
-    const int dbits = bits_for((uint64_t)tail[1] + 1);
+    RAMA_TRY((scan_totals<uint32_t>(ctx, NotLoopKey{raw.get()}, keep)));
+    const uint32_t kept = keep.total;
+    const int dbits = bits_for((uint64_t)keep.extra_value[0] + 1);
     if (kept == 0) {
         RAMA_TRY(out.i.alloc(ctx, 1));
         RAMA_TRY(out.j.alloc(ctx, 1));
@@ -689,29 +697,21 @@ static rama_status contract_edges(Ctx &ctx, const Graph &g, const int32_t *fmap,
     Buf<uint32_t> val;
     RAMA_TRY(key.alloc(ctx, kept));
     RAMA_TRY(val.alloc(ctx, kept));
-    {
-        ProfScope ps_(ctx, "k_compact_keys", (double)(m * 16 + (size_t)kept * 12));
-        k_compact_keys<<<grid_for(m), kBlock, 0, ctx.stream>>>(m, raw.get(), g.c.get(), pos.get(), dbits, key.get(),
-                                                               val.get());
-    }
-    LAUNCH_TRY(ctx, "compact_keys");
-    pos.reset();
+    RAMA_TRY((scan_emit<uint32_t>(ctx, NotLoopKey{raw.get()}, CompactKeysEmit{raw.get(), g.c.get(), dbits, key.get(), val.get()},
+                                  keep, (double)(m * 4 + (size_t)kept * 12))));
+    keep.offs.reset();
     raw.reset();
     RAMA_TRY((radix_sort_pairs<uint64_t, uint32_t>(ctx, key, val, kept, nbits + dbits)));
-    Buf<uint32_t> opos;
-    RAMA_TRY(opos.alloc(ctx, (size_t)kept + 1));
-    RAMA_TRY((exclusive_scan<uint32_t>(ctx, HeadFlag{key.get()}, opos.get(), (size_t)kept)));
-    uint32_t uniq = 0;
-    RAMA_TRY(read_back(ctx, &uniq, opos.get() + kept, 4));
+    ScanPlan<uint32_t> runs;
+    RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, kept, 0, runs)));
+    RAMA_TRY((scan_totals<uint32_t>(ctx, HeadFlag{key.get()}, runs)));
+    const uint32_t uniq = runs.total;
     RAMA_TRY(out.i.alloc(ctx, uniq));
     RAMA_TRY(out.j.alloc(ctx, uniq));
     RAMA_TRY(out.c.alloc(ctx, uniq));
-    {
-        ProfScope ps_(ctx, "k_reduce_runs", (double)((size_t)kept * 16 + (size_t)uniq * 12));
-        k_reduce_runs<<<grid_for(kept), kBlock, 0, ctx.stream>>>(kept, key.get(), val.get(), opos.get(), dbits, out.i.get(),
-                                                            out.j.get(), out.c.get());
-    }
-    LAUNCH_TRY(ctx, "reduce_runs");
+    RAMA_TRY((scan_emit<uint32_t>(ctx, HeadFlag{key.get()},
+                                  ReduceRunsEmit{kept, key.get(), val.get(), dbits, out.i.get(), out.j.get(), out.c.get()}, runs,
+                                  (double)((size_t)kept * 4 + (size_t)uniq * 12))));
     out.m = uniq;
     return RAMA_OK;
 }
@@ -721,7 +721,8 @@ rama_status contract_once(Ctx &ctx, const Graph &g, float tau, int rounds_cap, f
 {
     const size_t n = (size_t)g.n;
     Buf<int32_t> mate;
-    RAMA_TRY(matching(ctx, g, tau, rounds_cap, mate, n_matched));
+    ScanPlan<uint32_t> pairs;
+    RAMA_TRY(matching(ctx, g, tau, rounds_cap, mate, n_matched, pairs));
     n_new = g.n;
     if (n_matched == 0) return RAMA_OK;
     Buf<uint32_t> npos;
@@ -733,14 +734,10 @@ rama_status contract_once(Ctx &ctx, const Graph &g, float tau, int rounds_cap, f
         RAMA_TRY(forest_set(ctx, g, tau, si, sj, n_matched));
         if (n_matched == 0) return RAMA_OK;
     } else {
-        RAMA_TRY((exclusive_scan<uint32_t>(ctx, MatchedLow{mate.get()}, npos.get(), n)));
         RAMA_TRY(si.alloc(ctx, (size_t)n_matched));
         RAMA_TRY(sj.alloc(ctx, (size_t)n_matched));
-        {
-            ProfScope ps_(ctx, "k_emit_pairs", (double)(n * 8 + (size_t)n_matched * 8));
-            k_emit_pairs<<<grid_for(n), kBlock, 0, ctx.stream>>>(n, mate.get(), npos.get(), si.get(), sj.get());
-        }
-        LAUNCH_TRY(ctx, "emit_pairs");
+        RAMA_TRY((scan_emit<uint32_t>(ctx, MatchedLow{mate.get()}, EmitPairs{mate.get(), si.get(), sj.get()}, pairs,
+                                      (double)(n * 4 + (size_t)n_matched * 8))));
     }
     const size_t ns = (size_t)n_matched;
     RAMA_TRY(components(ctx, n, ns, si.get(), sj.get(), rep));

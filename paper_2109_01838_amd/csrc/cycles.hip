@@ -29,23 +29,29 @@ struct SignFlags {
     }
 };
 
-__global__ __launch_bounds__(kBlock) void k_split_sign(size_t m, const int32_t *i, const int32_t *j, const float *c,
-                                                       const uint64_t *spos, int32_t *pi,
-                                                       int32_t *pj, uint32_t *lkey, uint32_t *lval, int32_t *ri,
-                                                       int32_t *rj)
-{
-    size_t e = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    if (e >= m) return;
-    float w = c[e];
-    if (w > 0.0f) {
-        uint32_t p = (uint32_t)spos[e];
-        pi[p] = i[e]; pj[p] = j[e];
-        lkey[p] = (uint32_t)j[e]; lval[p] = (uint32_t)i[e];
-    } else if (w < 0.0f) {
-        uint32_t p = (uint32_t)(spos[e] >> 32);
-        ri[p] = i[e]; rj[p] = j[e];
+// consumer of the scan over SignFlags: an attractive edge goes to place low(prefix) of the attractive
+// lists (also as the pair (j,i) that the lower half of the adjacency is sorted from), a repulsive one
+// to place high(prefix) of the repulsive list
+struct SplitSignEmit {
+    static constexpr const char *tag = "SplitSign";
+    const int32_t *i, *j;
+    int32_t *pi, *pj;
+    uint32_t *lkey, *lval;
+    int32_t *ri, *rj;
+    __device__ __forceinline__ void operator()(size_t e, uint64_t sign, uint64_t prefix) const
+    {
+        if (sign == 0) return;
+        const int32_t a = i[e], b = j[e];
+        if (sign == 1ull) {
+            const uint32_t p = (uint32_t)prefix;
+            pi[p] = a; pj[p] = b;
+            lkey[p] = (uint32_t)b; lval[p] = (uint32_t)a;
+        } else {
+            const uint32_t p = (uint32_t)(prefix >> 32);
+            ri[p] = a; rj[p] = b;
+        }
     }
-}
+};
 
 __global__ __launch_bounds__(kBlock) void k_add_ptr(int32_t n, const int32_t *a, const int32_t *b, int32_t *out)
 {
@@ -321,13 +327,15 @@ struct HasCycles {
     }
 };
 
-template <int MAXL>
-__global__ __launch_bounds__(kBlock) void k_collect_hits(size_t nr, HasCycles<MAXL> has, const uint32_t *pos,
-                                                         uint32_t *hit)
-{
-    size_t r = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    if (r < nr && has(r)) hit[pos[r]] = (uint32_t)r;
-}
+// consumer of the scan over HasCycles: the repulsive edges that close a cycle
+struct CollectHitsEmit {
+    static constexpr const char *tag = "CollectHits";
+    uint32_t *hit;
+    __device__ __forceinline__ void operator()(size_t r, uint32_t any, uint32_t p) const
+    {
+        if (any) hit[p] = (uint32_t)r;
+    }
+};
 
 // a count that saturated: flag[0] = 1
 template <int MAXL>
@@ -488,18 +496,17 @@ rama_status count_and_fill(Ctx &ctx, size_t mr, const int32_t *ri, const int32_t
         list_bytes += 4.0 * (k + 3) * (double)tot[k];
     }
     if (all == 0) return RAMA_OK;
-    Buf<uint32_t> hpos, hit;
-    RAMA_TRY(hpos.alloc(ctx, mr + 1));
-    HasCycles<MAXL> has{cp, lists};
-    RAMA_TRY((exclusive_scan<uint32_t>(ctx, has, hpos.get(), mr)));
+    Buf<uint32_t> hit;
     uint32_t nh = 0;
-    RAMA_TRY(read_back(ctx, &nh, hpos.get() + mr, 4));
-    RAMA_TRY(hit.alloc(ctx, nh));
     {
-        ProfScope ps_(ctx, "k_collect_hits", (double)(mr * (4 + 4 * (size_t)lists) + (size_t)nh * 4));
-        k_collect_hits<MAXL><<<grid_for(mr), kBlock, 0, ctx.stream>>>(mr, has, hpos.get(), hit.get());
+        HasCycles<MAXL> has{cp, lists};
+        ScanPlan<uint32_t> hits;
+        RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, mr, 0, hits)));
+        RAMA_TRY((scan_totals<uint32_t>(ctx, has, hits)));
+        nh = hits.total;
+        RAMA_TRY(hit.alloc(ctx, nh));
+        RAMA_TRY((scan_emit<uint32_t>(ctx, has, CollectHitsEmit{hit.get()}, hits, (double)((size_t)nh * 4))));
     }
-    LAUNCH_TRY(ctx, "collect_hits");
     {
         ProfScope ps_(ctx, "k_fill_cycles", (double)((size_t)nh * (12 + 12 * (size_t)lists) + ((size_t)n + 1) * 4 + mp * 8) + list_bytes);
         k_fill_cycles<MAXL><<<grid_for(nh), kBlock, 0, ctx.stream>>>(nh, hit.get(), ri, rj, adj, lists, max_len, cp, op, vp);
@@ -523,12 +530,10 @@ rama_status find_cycles(Ctx &ctx, const Graph &g, int max_len, bool shortest_onl
     if (m == 0 || max_len < 3) return RAMA_OK;
     if (max_len > kMaxCycleLen) return fail(ctx, RAMA_ERR_INVALID_ARG, "cycle length beyond the supported maximum");
     // sign partition
-    Buf<uint64_t> spos;
-    RAMA_TRY(spos.alloc(ctx, m + 1));
-    RAMA_TRY((exclusive_scan<uint64_t>(ctx, SignFlags{g.c.get()}, spos.get(), m)));
-    uint64_t both = 0;
-    RAMA_TRY(read_back(ctx, &both, spos.get() + m, 8));
-    const uint32_t mp = (uint32_t)both, mr = (uint32_t)(both >> 32);
+    ScanPlan<uint64_t> signs;
+    RAMA_TRY((scan_plan_alloc<uint64_t>(ctx, m, 0, signs)));
+    RAMA_TRY((scan_totals<uint64_t>(ctx, SignFlags{g.c.get()}, signs)));
+    const uint32_t mp = (uint32_t)signs.total, mr = (uint32_t)(signs.total >> 32);
     if (mp == 0 || mr == 0) return RAMA_OK;
     if ((uint64_t)2 * mp >= (uint64_t(1) << 31)) return fail(ctx, RAMA_ERR_CAPACITY, "positive adjacency reaches 2^31 entries");
     Buf<int32_t> pi, pj, ri, rj;
@@ -539,13 +544,10 @@ rama_status find_cycles(Ctx &ctx, const Graph &g, int max_len, bool shortest_onl
     RAMA_TRY(lval.alloc(ctx, mp));
     RAMA_TRY(ri.alloc(ctx, mr));
     RAMA_TRY(rj.alloc(ctx, mr));
-    {
-        ProfScope ps_(ctx, "k_split_sign", (double)(m * 20 + (size_t)mp * 16 + (size_t)mr * 8));
-        k_split_sign<<<grid_for(m), kBlock, 0, ctx.stream>>>(m, g.i.get(), g.j.get(), g.c.get(), spos.get(), pi.get(),
-                                                         pj.get(), lkey.get(), lval.get(), ri.get(), rj.get());
-    }
-    LAUNCH_TRY(ctx, "split_sign");
-    spos.reset();
+    RAMA_TRY((scan_emit<uint64_t>(ctx, SignFlags{g.c.get()},
+                                  SplitSignEmit{g.i.get(), g.j.get(), pi.get(), pj.get(), lkey.get(), lval.get(), ri.get(), rj.get()},
+                                  signs, (double)(m * 8 + (size_t)mp * 16 + (size_t)mr * 8))));
+    signs.offs.reset();
     // positive CSR
     const int32_t n = g.n;
     Buf<int32_t> up_ptr, low_ptr, rowptr, nb;

@@ -301,16 +301,21 @@ struct HeadFlag32 {
     __device__ __forceinline__ uint32_t operator()(size_t p) const { return (p == 0 || key[p] != key[p - 1]) ? 1u : 0u; }
 };
 
-__global__ __launch_bounds__(kBlock) void k_active_edges(size_t ns, const uint32_t *skey, const uint32_t *pos,
-                                                         uint32_t *act_edge, uint32_t *act_start)
-{
-    size_t p = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    if (p >= ns) return;
-    if (p == 0) act_start[pos[ns]] = (uint32_t)ns;
-    if (pos[p] == pos[p + 1]) return;
-    act_edge[pos[p]] = skey[p];
-    act_start[pos[p]] = (uint32_t)p;
-}
+// consumer of the scan over HeadFlag32: run number a of the sorted slot list starts at p and belongs
+// to edge skey[p]; the entry behind the last run closes it
+struct ActiveEdgesEmit {
+    static constexpr const char *tag = "ActiveEdges";
+    const uint32_t *skey;
+    uint32_t ns, na;
+    uint32_t *act_edge, *act_start;
+    __device__ __forceinline__ void operator()(size_t p, uint32_t head, uint32_t a) const
+    {
+        if (p == 0) act_start[na] = ns;
+        if (!head) return;
+        act_edge[a] = skey[p];
+        act_start[a] = (uint32_t)p;
+    }
+};
 
 __global__ __launch_bounds__(kBlock) void k_edge_init(size_t na, const uint32_t *act_edge, const uint32_t *act_start,
                                                       const float *ce, float *share)
@@ -619,21 +624,19 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
     }
     // ---- incidence: slots of every edge in ascending triangle order ----------------------------
     RAMA_TRY((radix_sort_pairs<uint32_t, uint32_t>(ctx, skey, slot, 3 * T, bits_for((uint64_t)ma))));
-    Buf<uint32_t> apos, act_edge, act_start;
-    RAMA_TRY(apos.alloc(ctx, 3 * T + 1));
-    RAMA_TRY((exclusive_scan<uint32_t>(ctx, HeadFlag32{skey.get()}, apos.get(), 3 * T)));
-    uint32_t na32 = 0;
-    RAMA_TRY(read_back(ctx, &na32, apos.get() + 3 * T, 4));
-    const size_t na = na32;
-    RAMA_TRY(act_edge.alloc(ctx, na));
-    RAMA_TRY(act_start.alloc(ctx, na + 1));
+    Buf<uint32_t> act_edge, act_start;
+    size_t na = 0;
     {
-        ProfScope ps_(ctx, "k_active_edges", (double)(3 * T * 8 + na * 8));
-        k_active_edges<<<grid_for(3 * T), kBlock, 0, ctx.stream>>>(3 * T, skey.get(), apos.get(), act_edge.get(),
-                                                             act_start.get());
+        ScanPlan<uint32_t> heads;
+        RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, 3 * T, 0, heads)));
+        RAMA_TRY((scan_totals<uint32_t>(ctx, HeadFlag32{skey.get()}, heads)));
+        na = heads.total;
+        RAMA_TRY(act_edge.alloc(ctx, na));
+        RAMA_TRY(act_start.alloc(ctx, na + 1));
+        RAMA_TRY((scan_emit<uint32_t>(ctx, HeadFlag32{skey.get()},
+                                      ActiveEdgesEmit{skey.get(), (uint32_t)(3 * T), (uint32_t)na, act_edge.get(), act_start.get()},
+                                      heads, (double)(na * 8))));
     }
-    LAUNCH_TRY(ctx, "active_edges");
-    apos.reset();
     skey.reset();
     rowptr.reset();
     // ---- iterations ----------------------------------------------------------------------------

@@ -39,18 +39,22 @@ struct NotLoop {
     __device__ __forceinline__ uint32_t operator()(size_t e) const { return i[e] != j[e] ? 1u : 0u; }
 };
 
-__global__ __launch_bounds__(kBlock) void k_pack_edges(size_t m, const int32_t *i, const int32_t *j, const float *c,
-                                                       const uint32_t *pos, int dbits, uint64_t *key, uint32_t *val)
-{
-    size_t e = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    if (e >= m) return;
-    int32_t a = i[e], b = j[e];
-    if (a == b) return;
-    uint32_t lo = (uint32_t)min(a, b), hi = (uint32_t)max(a, b);
-    uint32_t p = pos[e];
-    key[p] = edge_key(lo, hi, dbits);
-    val[p] = __float_as_uint(c[e]);
-}
+// consumer of the scan over NotLoop: edge e that is no self-loop goes to place p
+struct PackEdgesEmit {
+    static constexpr const char *tag = "PackEdges";
+    const int32_t *i, *j;
+    const float *c;
+    int dbits;
+    uint64_t *key;
+    uint32_t *val;
+    __device__ __forceinline__ void operator()(size_t e, uint32_t keep, uint32_t p) const
+    {
+        if (!keep) return;
+        const int32_t a = i[e], b = j[e];
+        key[p] = edge_key((uint32_t)min(a, b), (uint32_t)max(a, b), dbits);
+        val[p] = __float_as_uint(c[e]);
+    }
+};
 
 struct HeadFlag {
     static constexpr int bytes = 8;   // bytes read per item
@@ -95,11 +99,10 @@ rama_status canonicalise(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const
         return RAMA_OK;
     }
     const int nbits = bits_for((uint64_t)n), dbits = bits_for((uint64_t)hf[2] + 1);
-    Buf<uint32_t> pos;
-    RAMA_TRY(pos.alloc(ctx, (size_t)m + 1));
-    RAMA_TRY((exclusive_scan<uint32_t>(ctx, NotLoop{i, j}, pos.get(), (size_t)m)));
-    uint32_t kept = 0;
-    RAMA_TRY(read_back(ctx, &kept, pos.get() + m, 4));
+    ScanPlan<uint32_t> keep;
+    RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, (size_t)m, 0, keep)));
+    RAMA_TRY((scan_totals<uint32_t>(ctx, NotLoop{i, j}, keep)));
+    const uint32_t kept = keep.total;
     if (kept == 0) {
         RAMA_TRY(out.i.alloc(ctx, 1));
         RAMA_TRY(out.j.alloc(ctx, 1));
@@ -110,27 +113,20 @@ rama_status canonicalise(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const
     Buf<uint32_t> val;
     RAMA_TRY(key.alloc(ctx, kept));
     RAMA_TRY(val.alloc(ctx, kept));
-    {
-        ProfScope ps_(ctx, "k_pack_edges", (double)((size_t)m * 16 + (size_t)kept * 12));
-        k_pack_edges<<<grid_for(m), kBlock, 0, ctx.stream>>>((size_t)m, i, j, c, pos.get(), dbits, key.get(), val.get());
-    }
-    LAUNCH_TRY(ctx, "pack_edges");
-    pos.reset();
+    RAMA_TRY((scan_emit<uint32_t>(ctx, NotLoop{i, j}, PackEdgesEmit{i, j, c, dbits, key.get(), val.get()}, keep,
+                                  (double)((size_t)m * 4 + (size_t)kept * 12))));
+    keep.offs.reset();
     RAMA_TRY((radix_sort_pairs<uint64_t, uint32_t>(ctx, key, val, kept, nbits + dbits)));
-    Buf<uint32_t> opos;
-    RAMA_TRY(opos.alloc(ctx, (size_t)kept + 1));
-    RAMA_TRY((exclusive_scan<uint32_t>(ctx, HeadFlag{key.get()}, opos.get(), (size_t)kept)));
-    uint32_t uniq = 0;
-    RAMA_TRY(read_back(ctx, &uniq, opos.get() + kept, 4));
+    ScanPlan<uint32_t> runs;
+    RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, kept, 0, runs)));
+    RAMA_TRY((scan_totals<uint32_t>(ctx, HeadFlag{key.get()}, runs)));
+    const uint32_t uniq = runs.total;
     RAMA_TRY(out.i.alloc(ctx, uniq));
     RAMA_TRY(out.j.alloc(ctx, uniq));
     RAMA_TRY(out.c.alloc(ctx, uniq));
-    {
-        ProfScope ps_(ctx, "k_reduce_runs", (double)((size_t)kept * 16 + (size_t)uniq * 12));
-        k_reduce_runs<<<grid_for(kept), kBlock, 0, ctx.stream>>>(kept, key.get(), val.get(), opos.get(), dbits, out.i.get(),
-                                                            out.j.get(), out.c.get());
-    }
-    LAUNCH_TRY(ctx, "reduce_runs");
+    RAMA_TRY((scan_emit<uint32_t>(ctx, HeadFlag{key.get()},
+                                  ReduceRunsEmit{kept, key.get(), val.get(), dbits, out.i.get(), out.j.get(), out.c.get()}, runs,
+                                  (double)((size_t)kept * 4 + (size_t)uniq * 12))));
     out.m = uniq;
     return RAMA_OK;
 }

@@ -11,6 +11,9 @@
 
 namespace rama {
 
+template <typename T>
+rama_status fill(Ctx &ctx, T *p, T v, size_t n);   // defined with the reductions below
+
 // ------------------------------------------------------------------------------------------
 // wave / block helpers
 // ------------------------------------------------------------------------------------------
@@ -237,6 +240,113 @@ rama_status exclusive_scan(Ctx &ctx, F f, TO *out, size_t n)
         k_scan_apply<TO, F><<<nb, kBlock, 0, ctx.stream>>>(f, out, offs.get(), n);
     }
     LAUNCH_TRY(ctx, "scan_apply");
+    return RAMA_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Scan with a consumer instead of an output array.  scan_totals runs the reduce step and the scan of
+// the tile sums and reads the total back (the caller sizes its outputs with it); scan_emit then
+// recomputes f and hands every item k its value and exclusive prefix: emit(k, f(k), prefix).  The
+// array of prefixes is never stored and the consumer does not re-read what the scan already had in
+// registers.  `extra` words behind the total belong to the caller (e.g. a maximum a producer kernel
+// left there) and come back with the same read.
+// ------------------------------------------------------------------------------------------
+template <typename TO>
+struct ScanPlan {
+    Buf<TO> offs;   // [nb] tile offsets, [nb] total, then the caller's extra words
+    Buf<TO> sums;
+    unsigned nb = 0;
+    size_t n = 0;
+    int extra = 0;
+    TO total = 0;
+    TO extra_value[2] = {0, 0};
+    TO *extra_ptr() { return offs.get() + nb + 1; }
+};
+
+template <typename TO>
+rama_status scan_plan_alloc(Ctx &ctx, size_t n, int extra, ScanPlan<TO> &plan)
+{
+    plan.n = n;
+    plan.nb = grid_for(n, kScanTile);
+    plan.extra = extra;
+    RAMA_TRY(plan.offs.alloc(ctx, (size_t)plan.nb + 1 + 2));
+    RAMA_TRY(plan.sums.alloc(ctx, plan.nb > 0 ? plan.nb : 1));
+    return fill<TO>(ctx, plan.offs.get() + plan.nb, (TO)0, 3);
+}
+
+template <typename TO, typename F>
+rama_status scan_totals(Ctx &ctx, F f, ScanPlan<TO> &plan)
+{
+    plan.total = 0;
+    const unsigned nb = plan.nb;
+    if (plan.n > 0) {
+        {
+            ProfScope ps_(ctx, kernel_name<F>("k_scan_reduce"), (double)(plan.n * F::bytes));
+            k_scan_reduce<TO, F><<<nb, kBlock, 0, ctx.stream>>>(f, plan.sums.get(), plan.n);
+        }
+        LAUNCH_TRY(ctx, "scan_reduce");
+        if (nb <= kScanMidMax) {
+            // k_scan_mid stores the total behind the offsets: keep the caller's extra words, which sit
+            // one further on, out of its way
+            ProfScope ps_(ctx, "k_scan_mid", (double)((size_t)nb * 2 * sizeof(TO)));
+            k_scan_mid<TO><<<1, kBlock, 0, ctx.stream>>>(plan.sums.get(), plan.offs.get(), nb);
+            LAUNCH_TRY(ctx, "scan_mid");
+        } else {
+            // the nested scan writes nb+1 words (offsets and total), nothing beyond
+            RAMA_TRY((exclusive_scan<TO, PtrInput<TO>>(ctx, PtrInput<TO>{plan.sums.get()}, plan.offs.get(), nb)));
+        }
+    }
+    TO back[3] = {0, 0, 0};
+    RAMA_TRY(read_back(ctx, back, plan.offs.get() + nb, (size_t)(1 + plan.extra) * sizeof(TO)));
+    plan.total = back[0];
+    plan.extra_value[0] = back[1];
+    plan.extra_value[1] = back[2];
+    plan.sums.reset();
+    return RAMA_OK;
+}
+
+template <typename TO, typename F, typename E>
+__global__ __launch_bounds__(kBlock) void k_scan_emit(F f, E emit, const TO *block_offsets, size_t n)
+{
+    __shared__ TO wave_tot[4];
+    const int w = threadIdx.x >> 6;
+    const size_t base = (size_t)blockIdx.x * kScanTile + (size_t)w * kScanWaveItems + lane_id();
+    TO x[kScanItems], v[kScanItems];
+#pragma unroll
+    for (int q = 0; q < kScanItems; ++q) {
+        const size_t k = base + (size_t)q * 64;
+        x[q] = (k < n) ? (TO)f(k) : (TO)0;
+    }
+    TO carry = 0;
+#pragma unroll
+    for (int q = 0; q < kScanItems; ++q) {
+        const TO inc = wave_inclusive_scan(x[q]);
+        v[q] = inc - x[q] + carry;
+        carry += wave_last(inc);
+    }
+    if (lane_id() == 0) wave_tot[w] = carry;
+    __syncthreads();
+    TO pre = block_offsets[blockIdx.x];
+#pragma unroll
+    for (int k = 0; k < 3; ++k)
+        if (k < w) pre += wave_tot[k];
+#pragma unroll
+    for (int q = 0; q < kScanItems; ++q) {
+        const size_t k = base + (size_t)q * 64;
+        if (k < n) emit(k, x[q], v[q] + pre);
+    }
+}
+
+// `bytes`: what the consumer moves per launch beyond reading f's input (for the timers)
+template <typename TO, typename F, typename E>
+rama_status scan_emit(Ctx &ctx, F f, E emit, const ScanPlan<TO> &plan, double bytes)
+{
+    if (plan.n == 0) return RAMA_OK;
+    {
+        ProfScope ps_(ctx, kernel_name<E>("k_scan_emit"), (double)(plan.n * F::bytes) + bytes);
+        k_scan_emit<TO, F, E><<<plan.nb, kBlock, 0, ctx.stream>>>(f, emit, plan.offs.get(), plan.n);
+    }
+    LAUNCH_TRY(ctx, "scan_emit");
     return RAMA_OK;
 }
 
@@ -661,24 +771,28 @@ __device__ __forceinline__ void block_max_into(uint32_t v, uint32_t *out)
     }
 }
 
-// Sums runs of equal keys in order of appearance (one thread per run, sequential adds) and
-// writes endpoint pair + cost of run r at position pos[first element of r].
-static __global__ __launch_bounds__(kBlock) void k_reduce_runs(size_t m, const uint64_t *key, const uint32_t *val,
-                                                        const uint32_t *pos, int dbits, int32_t *io, int32_t *jo,
-                                                        float *co)
-{
-    size_t e = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    if (e >= m) return;
-    uint64_t k = key[e];
-    if (e > 0 && key[e - 1] == k) return;
-    float acc = __uint_as_float(val[e]);
-    for (size_t f = e + 1; f < m && key[f] == k; ++f) acc = acc + __uint_as_float(val[f]);
-    uint32_t p = pos[e];
-    const uint32_t lo = (uint32_t)(k >> dbits);
-    io[p] = (int32_t)lo;
-    jo[p] = (int32_t)(lo + (uint32_t)(k & ((1ull << dbits) - 1ull)));
-    co[p] = acc;
-}
+// Sums runs of equal keys in order of appearance (one thread per run, sequential adds): consumer of
+// the scan over the run heads; run number p writes its endpoint pair and cost at place p.
+struct ReduceRunsEmit {
+    static constexpr const char *tag = "ReduceRuns";
+    size_t m;
+    const uint64_t *key;
+    const uint32_t *val;
+    int dbits;
+    int32_t *io, *jo;
+    float *co;
+    __device__ __forceinline__ void operator()(size_t e, uint32_t head, uint32_t p) const
+    {
+        if (!head) return;
+        const uint64_t k = key[e];
+        float acc = __uint_as_float(val[e]);
+        for (size_t f = e + 1; f < m && key[f] == k; ++f) acc = acc + __uint_as_float(val[f]);
+        const uint32_t lo = (uint32_t)(k >> dbits);
+        io[p] = (int32_t)lo;
+        jo[p] = (int32_t)(lo + (uint32_t)(k & ((1ull << dbits) - 1ull)));
+        co[p] = acc;
+    }
+};
 
 // position of the canonical edge (u,v), u<v, in rows given by rowptr over i (upper CSR) or -1
 __device__ __forceinline__ int32_t find_edge_in_row(const int32_t *rowptr, const int32_t *j, int32_t u, int32_t v)
