@@ -236,43 +236,45 @@ struct HeadFlagT {
     __device__ __forceinline__ uint32_t operator()(size_t e) const { return (e == 0 || key[e] != key[e - 1]) ? 1u : 0u; }
 };
 
-// unique triangles -> their three edge ids, and the (edge, slot) pairs for the incidence sort
+// Consumer of the scan over the heads of the sorted triangle keys.  The head of run t is triangle t:
+// it writes its three edge ids and the (edge, slot) pairs for the incidence sort.  Triangles kept from
+// an earlier dual round take their costs along: `origin` (optional) is the fan index each sorted key
+// came from, the kept triangles occupy the fan indices [kept_begin, kept_end) in their old order, and
+// the run a key lies in is the triangle's new index.
 template <typename KT>
-__global__ __launch_bounds__(kBlock) void k_triangle_edges(size_t nt, const KT *key, const uint32_t *pos,
-                                                           const int32_t *rowptr, const int32_t *j, int dbits,
-                                                           int32_t *tri_edge, uint32_t *skey, uint32_t *sval,
-                                                           int32_t *flag)
-{
-    size_t q = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    if (q >= nt) return;
-    if (pos[q] == pos[q + 1]) return;
-    KT k = key[q];
-    int32_t e0 = (int32_t)(k >> dbits);
-    int32_t e1 = e0 + (int32_t)(k & (((KT)1 << dbits) - 1));
-    int32_t v = j[e0], w = j[e1];
-    int32_t e2 = find_edge_in_row(rowptr, j, v, w);
-    if (e2 < 0) { *flag = 1; e2 = 0; }
-    size_t t = pos[q];
-    tri_edge[3 * t + 0] = e0; tri_edge[3 * t + 1] = e1; tri_edge[3 * t + 2] = e2;
-    skey[3 * t + 0] = (uint32_t)e0; skey[3 * t + 1] = (uint32_t)e1; skey[3 * t + 2] = (uint32_t)e2;
-    sval[3 * t + 0] = (uint32_t)(3 * t); sval[3 * t + 1] = (uint32_t)(3 * t + 1); sval[3 * t + 2] = (uint32_t)(3 * t + 2);
-}
-
-// Triangles kept from an earlier dual round take their costs along: `origin` is the fan index each
-// sorted key came from, the kept triangles occupy the fan indices [kept_begin, kept_end) in their
-// old order, and the run a key lies in is the triangle's new index.
-template <typename KT>
-__global__ __launch_bounds__(kBlock) void k_carry_costs(size_t nt, const uint32_t *origin, const uint32_t *pos,
-                                                        uint32_t kept_begin, uint32_t kept_end, const float *ct_old,
-                                                        float *ct)
-{
-    size_t q = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    if (q >= nt) return;
-    const uint32_t o = origin[q];
-    if (o < kept_begin || o >= kept_end) return;
-    const size_t t = pos[q + 1] - 1, old = o - kept_begin;
-    ct[3 * t] = ct_old[3 * old]; ct[3 * t + 1] = ct_old[3 * old + 1]; ct[3 * t + 2] = ct_old[3 * old + 2];
-}
+struct TrianglesEmit {
+    static constexpr const char *tag = sizeof(KT) == 8 ? "Triangles64" : "Triangles";
+    const KT *key;
+    const int32_t *rowptr, *j;
+    int dbits;
+    int32_t *tri_edge;
+    uint32_t *skey, *sval;
+    int32_t *flag;
+    const uint32_t *origin;
+    uint32_t kept_begin, kept_end;
+    const float *ct_old;
+    float *ct;
+    __device__ __forceinline__ void operator()(size_t q, uint32_t head, uint32_t runs_before) const
+    {
+        const size_t t = (size_t)runs_before + head - 1;   // the run q lies in (the first key is a head)
+        if (origin) {
+            const uint32_t o = origin[q];
+            if (o >= kept_begin && o < kept_end) {
+                const size_t old = o - kept_begin;
+                ct[3 * t] = ct_old[3 * old]; ct[3 * t + 1] = ct_old[3 * old + 1]; ct[3 * t + 2] = ct_old[3 * old + 2];
+            }
+        }
+        if (!head) return;
+        const KT k = key[q];
+        const int32_t e0 = (int32_t)(k >> dbits);
+        const int32_t e1 = e0 + (int32_t)(k & (((KT)1 << dbits) - 1));
+        int32_t e2 = find_edge_in_row(rowptr, j, j[e0], j[e1]);
+        if (e2 < 0) { *flag = 1; e2 = 0; }
+        tri_edge[3 * t + 0] = e0; tri_edge[3 * t + 1] = e1; tri_edge[3 * t + 2] = e2;
+        skey[3 * t + 0] = (uint32_t)e0; skey[3 * t + 1] = (uint32_t)e1; skey[3 * t + 2] = (uint32_t)e2;
+        sval[3 * t + 0] = (uint32_t)(3 * t); sval[3 * t + 1] = (uint32_t)(3 * t + 1); sval[3 * t + 2] = (uint32_t)(3 * t + 2);
+    }
+};
 
 __global__ __launch_bounds__(kBlock) void k_iota_u32(size_t n, uint32_t *p)
 {
@@ -560,8 +562,6 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
     RAMA_TRY(read_back(ctx, &hmax, maxrow.get(), 4));
     const int dbits = bits_for((uint64_t)hmax + 1);
     const int kbits = bits_for((uint64_t)ma) + dbits;
-    Buf<uint32_t> tpos;
-    RAMA_TRY(tpos.alloc(ctx, nfan + 1));
     Buf<int32_t> tri_edge;
     Buf<uint32_t> skey, slot;
     size_t T = 0;
@@ -588,35 +588,24 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
         } else {
             RAMA_TRY((radix_sort_keys<KT>(ctx, tkey, nfan, kbits)));
         }
-        RAMA_TRY((exclusive_scan<uint32_t>(ctx, HeadFlagT<KT>{tkey.get()}, tpos.get(), nfan)));
-        uint32_t T32 = 0;
-        RAMA_TRY(read_back(ctx, &T32, tpos.get() + nfan, 4));
-        T = T32;
+        ScanPlan<uint32_t> heads;
+        RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, nfan, 0, heads)));
+        RAMA_TRY((scan_totals<uint32_t>(ctx, HeadFlagT<KT>{tkey.get()}, heads)));
+        T = heads.total;
         RAMA_TRY(ct.alloc(ctx, 3 * T));
         RAMA_TRY(fill<float>(ctx, ct.get(), 0.0f, 3 * T));
-        if (T_kept > 0) {
-            ProfScope ps_(ctx, "k_carry_costs", (double)(nfan * 8 + T_kept * 24));
-            k_carry_costs<KT><<<grid_for(nfan), kBlock, 0, ctx.stream>>>(nfan, origin.get(), tpos.get(),
-                                                                        cs.fan_end[kCycleLists - 1], cs.fan_end[kCycleLists],
-                                                                        prev->ct.get(), ct.get());
-            LAUNCH_TRY(ctx, "carry_costs");
-        }
         RAMA_TRY(tri_edge.alloc(ctx, 3 * T));
         RAMA_TRY(skey.alloc(ctx, 3 * T));
         RAMA_TRY(slot.alloc(ctx, 3 * T));
-        {
-            ProfScope ps_(ctx, "k_triangle_edges", (double)(nfan * (4 + sizeof(KT)) + T * 44));
-            k_triangle_edges<KT><<<grid_for(nfan), kBlock, 0, ctx.stream>>>(nfan, tkey.get(), tpos.get(), rowptr.get(),
-                                                                           aug.j.get(), dbits, tri_edge.get(),
-                                                                           skey.get(), slot.get(), flag.get());
-        }
-        LAUNCH_TRY(ctx, "triangle_edges");
+        TrianglesEmit<KT> te{tkey.get(), rowptr.get(), aug.j.get(), dbits, tri_edge.get(), skey.get(), slot.get(), flag.get(),
+                             T_kept > 0 ? origin.get() : nullptr, cs.fan_end[kCycleLists - 1], cs.fan_end[kCycleLists],
+                             T_kept > 0 ? prev->ct.get() : nullptr, ct.get()};
+        RAMA_TRY((scan_emit<uint32_t>(ctx, HeadFlagT<KT>{tkey.get()}, te, heads, (double)(T * 44 + T_kept * 24))));
         return RAMA_OK;
     };
     if (kbits <= 32) RAMA_TRY(triangles(uint32_t{}));
     else RAMA_TRY(triangles(uint64_t{}));
     if (info) info->n_triangles = (int64_t)T;
-    tpos.reset();
     {
         int32_t hf = 0;
         RAMA_TRY(read_back(ctx, &hf, flag.get(), 4));

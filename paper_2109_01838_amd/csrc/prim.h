@@ -271,7 +271,9 @@ rama_status scan_plan_alloc(Ctx &ctx, size_t n, int extra, ScanPlan<TO> &plan)
     plan.extra = extra;
     RAMA_TRY(plan.offs.alloc(ctx, (size_t)plan.nb + 1 + 2));
     RAMA_TRY(plan.sums.alloc(ctx, plan.nb > 0 ? plan.nb : 1));
-    return fill<TO>(ctx, plan.offs.get() + plan.nb, (TO)0, 3);
+    // the total is always written by the scan of the tile sums; only the caller's words start at zero
+    if (extra > 0) return fill<TO>(ctx, plan.extra_ptr(), (TO)0, (size_t)extra);
+    return RAMA_OK;
 }
 
 template <typename TO, typename F>
@@ -297,7 +299,8 @@ rama_status scan_totals(Ctx &ctx, F f, ScanPlan<TO> &plan)
         }
     }
     TO back[3] = {0, 0, 0};
-    RAMA_TRY(read_back(ctx, back, plan.offs.get() + nb, (size_t)(1 + plan.extra) * sizeof(TO)));
+    if (plan.n > 0) RAMA_TRY(read_back(ctx, back, plan.offs.get() + nb, (size_t)(1 + plan.extra) * sizeof(TO)));
+    else if (plan.extra > 0) RAMA_TRY(read_back(ctx, back + 1, plan.extra_ptr(), (size_t)plan.extra * sizeof(TO)));
     plan.total = back[0];
     plan.extra_value[0] = back[1];
     plan.extra_value[1] = back[2];
