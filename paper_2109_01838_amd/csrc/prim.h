@@ -362,18 +362,35 @@ rama_status scan_emit(Ctx &ctx, F f, E emit, const ScanPlan<TO> &plan, double by
 // ------------------------------------------------------------------------------------------
 constexpr int kRowGapInline = 32;
 
+// four positions per thread, read as one 16-byte vector (keys are 4 bytes wide)
 template <typename K, typename P>
 __global__ __launch_bounds__(kBlock) void k_row_bounds_mark(const K *keys, size_t m, int64_t n, P *ptr)
 {
-    size_t e = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    if (e > m) return;
-    int64_t prev = (e == 0) ? -1 : (int64_t)keys[e - 1];
-    int64_t cur = (e == m) ? n : (int64_t)keys[e];
-    if (cur == prev) return;
-    if (cur - prev <= kRowGapInline)
-        for (int64_t v = prev + 1; v <= cur; ++v) ptr[v] = (P)e;
-    else
-        ptr[cur] = (P)e;
+    static_assert(sizeof(K) == 4, "32-bit keys");
+    const size_t e0 = ((size_t)blockIdx.x * kBlock + threadIdx.x) * 4;
+    if (e0 > m) return;
+    K k[4];
+    if (e0 + 4 <= m) {
+        const uint4 v = *reinterpret_cast<const uint4 *>(keys + e0);   // e0 is a multiple of 4, the array 16-byte aligned
+        k[0] = (K)v.x; k[1] = (K)v.y; k[2] = (K)v.z; k[3] = (K)v.w;
+    } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) k[q] = e0 + q < m ? keys[e0 + q] : (K)0;
+    }
+    int64_t prev = (e0 == 0) ? -1 : (int64_t)keys[e0 - 1];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const size_t e = e0 + q;
+        if (e > m) break;
+        const int64_t cur = (e == m) ? n : (int64_t)k[q];
+        if (cur != prev) {
+            if (cur - prev <= kRowGapInline)
+                for (int64_t v = prev + 1; v <= cur; ++v) ptr[v] = (P)e;
+            else
+                ptr[cur] = (P)e;
+        }
+        prev = cur;
+    }
 }
 
 template <typename K, typename P>
@@ -743,7 +760,7 @@ rama_status row_bounds(Ctx &ctx, const K *keys, size_t m, int64_t n, P *ptr)
     RAMA_TRY(fill<P>(ctx, ptr, (P)-1, (size_t)n + 1));
     {
         ProfScope ps_(ctx, "k_row_bounds_mark", (double)(m * sizeof(K) + ((size_t)n + 1) * sizeof(P)));
-        k_row_bounds_mark<K, P><<<grid_for(m + 1), kBlock, 0, ctx.stream>>>(keys, m, n, ptr);
+        k_row_bounds_mark<K, P><<<grid_for(m / 4 + 1), kBlock, 0, ctx.stream>>>(keys, m, n, ptr);
     }
     LAUNCH_TRY(ctx, "row_bounds_mark");
     {
