@@ -393,17 +393,32 @@ __global__ __launch_bounds__(kBlock) void k_row_bounds_mark(const K *keys, size_
     }
 }
 
+// four rows per thread, looked at as one 16-byte vector (row pointers are 4 bytes wide)
 template <typename K, typename P>
 __global__ __launch_bounds__(kBlock) void k_row_bounds_search(const K *keys, size_t m, int64_t n, P *ptr)
 {
-    int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (v > n || ptr[v] != (P)-1) return;
-    size_t lo = 0, hi = m;
-    while (lo < hi) {
-        size_t mid = lo + ((hi - lo) >> 1);
-        if ((int64_t)keys[mid] < v) lo = mid + 1; else hi = mid;
+    static_assert(sizeof(P) == 4, "32-bit row pointers");
+    const int64_t v0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
+    if (v0 > n) return;
+    P cur[4];
+    if (v0 + 3 <= n) {
+        const uint4 w = *reinterpret_cast<const uint4 *>(ptr + v0);
+        cur[0] = (P)w.x; cur[1] = (P)w.y; cur[2] = (P)w.z; cur[3] = (P)w.w;
+    } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) cur[q] = v0 + q <= n ? ptr[v0 + q] : (P)0;
     }
-    ptr[v] = (P)lo;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int64_t v = v0 + q;
+        if (v > n || cur[q] != (P)-1) continue;
+        size_t lo = 0, hi = m;
+        while (lo < hi) {
+            size_t mid = lo + ((hi - lo) >> 1);
+            if ((int64_t)keys[mid] < v) lo = mid + 1; else hi = mid;
+        }
+        ptr[v] = (P)lo;
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -742,13 +757,32 @@ __global__ __launch_bounds__(kBlock) void k_fill(T *p, T v, size_t n)
     size_t k = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (k < n) p[k] = v;
 }
+// 16 bytes per thread; p must be 16-byte aligned
+template <typename T>
+__global__ __launch_bounds__(kBlock) void k_fill_wide(T *p, T v, size_t n)
+{
+    constexpr int kPer = 16 / (int)sizeof(T);
+    struct alignas(16) Vec { T x[kPer]; };
+    size_t k = ((size_t)blockIdx.x * kBlock + threadIdx.x) * kPer;
+    if (k + kPer <= n) {
+        Vec w;
+#pragma unroll
+        for (int q = 0; q < kPer; ++q) w.x[q] = v;
+        *reinterpret_cast<Vec *>(p + k) = w;
+    } else {
+        for (; k < n; ++k) p[k] = v;
+    }
+}
 template <typename T>
 rama_status fill(Ctx &ctx, T *p, T v, size_t n)
 {
     if (n == 0) return RAMA_OK;
+    constexpr int kPer = 16 / (int)sizeof(T);
+    const bool wide = sizeof(T) < 16 && n >= 1024 && (reinterpret_cast<uintptr_t>(p) & 15u) == 0;
     {
         ProfScope ps_(ctx, "k_fill", (double)(n * sizeof(T)));
-        k_fill<T><<<grid_for(n), kBlock, 0, ctx.stream>>>(p, v, n);
+        if (wide) k_fill_wide<T><<<grid_for((n + kPer - 1) / kPer), kBlock, 0, ctx.stream>>>(p, v, n);
+        else k_fill<T><<<grid_for(n), kBlock, 0, ctx.stream>>>(p, v, n);
     }
     LAUNCH_TRY(ctx, "fill");
     return RAMA_OK;
@@ -765,7 +799,7 @@ rama_status row_bounds(Ctx &ctx, const K *keys, size_t m, int64_t n, P *ptr)
     LAUNCH_TRY(ctx, "row_bounds_mark");
     {
         ProfScope ps_(ctx, "k_row_bounds_search", (double)(((size_t)n + 1) * sizeof(P)));
-        k_row_bounds_search<K, P><<<grid_for((size_t)n + 1), kBlock, 0, ctx.stream>>>(keys, m, n, ptr);
+        k_row_bounds_search<K, P><<<grid_for((size_t)n / 4 + 1), kBlock, 0, ctx.stream>>>(keys, m, n, ptr);
     }
     LAUNCH_TRY(ctx, "row_bounds_search");
     return RAMA_OK;
