@@ -72,27 +72,43 @@ __device__ __forceinline__ void propose_edge(bool valid, int32_t u, int32_t v, u
     }
 }
 
-__global__ __launch_bounds__(kBlock) void k_propose(size_t na, const uint32_t *act, const int32_t *i, const int32_t *j,
-                                                    const float *c, unsigned long long *best)
+// The matching keeps its candidates packed -- endpoints and rank word, 16 bytes per candidate in three
+// arrays -- so that a handshake round reads its list contiguously instead of reaching through the edge
+// id into i, j and c of an ever sparser subset of the edges.
+struct Cands {
+    int32_t *u, *v;
+    unsigned long long *r;
+};
+// consumer of the scan over CandFlag: the packed candidate list
+struct PackCandsEmit {
+    static constexpr const char *tag = "PackCands";
+    const int32_t *i, *j;
+    const float *c;
+    Cands out;
+    __device__ __forceinline__ void operator()(size_t e, uint32_t cand, uint32_t p) const
+    {
+        if (!cand) return;
+        out.u[p] = i[e]; out.v[p] = j[e];
+        out.r[p] = edge_rank(c[e], (uint32_t)e);
+    }
+};
+
+__global__ __launch_bounds__(kBlock) void k_propose(size_t na, Cands a, unsigned long long *best)
 {
-    size_t a = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    const bool valid = a < na;
-    uint32_t e = valid ? act[a] : 0u;
-    int32_t u = valid ? i[e] : 0, v = valid ? j[e] : 0;
-    propose_edge(valid, u, v, valid ? edge_rank(c[e], e) : 0ull, best);
+    size_t k = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    const bool valid = k < na;
+    propose_edge(valid, valid ? a.u[k] : 0, valid ? a.v[k] : 0, valid ? a.r[k] : 0ull, best);
 }
 
 // matched edges fix their endpoints; the rank words the next round will use are cleared for the
 // endpoints of every edge still listed (the two rank arrays alternate between rounds)
-__global__ __launch_bounds__(kBlock) void k_accept(size_t na, const uint32_t *act, const int32_t *i, const int32_t *j,
-                                                   const float *c, const unsigned long long *best,
+__global__ __launch_bounds__(kBlock) void k_accept(size_t na, Cands a, const unsigned long long *best,
                                                    unsigned long long *best_next, int32_t *mate)
 {
-    size_t a = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    if (a >= na) return;
-    uint32_t e = act[a];
-    unsigned long long r = edge_rank(c[e], e);
-    int32_t u = i[e], v = j[e];
+    size_t k = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (k >= na) return;
+    const int32_t u = a.u[k], v = a.v[k];
+    const unsigned long long r = a.r[k];
     if (best[u] == r && best[v] == r) { mate[u] = v; mate[v] = u; }
     best_next[u] = 0ull;
     best_next[v] = 0ull;
@@ -103,33 +119,31 @@ __global__ __launch_bounds__(kBlock) void k_accept(size_t na, const uint32_t *ac
 // single atomicAdd; the order of the ranges varies from run to run, which is harmless: proposals
 // (atomicMax) and the accept test do not depend on the order of the list.
 constexpr int kAdvItems = 8;
-__global__ __launch_bounds__(kBlock) void k_advance(size_t na, const uint32_t *act, const int32_t *i, const int32_t *j,
-                                                    const float *c, const int32_t *mate, uint32_t *act_next,
+__global__ __launch_bounds__(kBlock) void k_advance(size_t na, Cands a, const int32_t *mate, Cands next,
                                                     unsigned long long *best_next, uint32_t *counter)
 {
     __shared__ uint32_t s_base, s_wave[4];
-    // a wave owns 512 consecutive candidates and takes them 64 at a time, lane l the l-th: loads are
-    // contiguous and neighbouring lanes hold neighbouring edges, which the proposals combine
     const int w = threadIdx.x >> 6, lane = lane_id();
     const size_t base = (size_t)blockIdx.x * (kBlock * kAdvItems) + (size_t)w * (64 * kAdvItems) + lane;
-    uint32_t e[kAdvItems], where[kAdvItems];
-    uint32_t keep = 0, cnt = 0;   // cnt: survivors of this wave so far (same in every lane)
+    int32_t u[kAdvItems], v[kAdvItems];
+    unsigned long long r[kAdvItems];
+    uint32_t where[kAdvItems];
+    uint32_t keep = 0, cnt = 0;
 #pragma unroll
     for (int q = 0; q < kAdvItems; ++q) {
-        const size_t a = base + (size_t)q * 64;
-        e[q] = 0;
+        const size_t k = base + (size_t)q * 64;
+        u[q] = 0; v[q] = 0; r[q] = 0ull;
         bool ok = false;
-        int32_t u = 0, v = 0;
-        if (a < na) {
-            e[q] = act[a];
-            u = i[e[q]]; v = j[e[q]];
-            ok = mate[u] < 0 && mate[v] < 0;
+        if (k < na) {
+            u[q] = a.u[k]; v[q] = a.v[k];
+            ok = mate[u[q]] < 0 && mate[v[q]] < 0;
+            if (ok) r[q] = a.r[k];
         }
         const unsigned long long vote = __ballot(ok);
         where[q] = cnt + (uint32_t)__popcll(vote & ((1ull << lane) - 1ull));
         cnt += (uint32_t)__popcll(vote);
         if (ok) keep |= 1u << q;
-        propose_edge(ok, u, v, ok ? edge_rank(c[e[q]], e[q]) : 0ull, best_next);
+        propose_edge(ok, u[q], v[q], r[q], best_next);
     }
     if (lane == 0) s_wave[w] = cnt;
     __syncthreads();
@@ -144,7 +158,10 @@ __global__ __launch_bounds__(kBlock) void k_advance(size_t na, const uint32_t *a
         if (k < w) off += s_wave[k];
 #pragma unroll
     for (int q = 0; q < kAdvItems; ++q)
-        if (keep & (1u << q)) act_next[off + where[q]] = e[q];
+        if (keep & (1u << q)) {
+            const uint32_t p = off + where[q];
+            next.u[p] = u[q]; next.v[p] = v[q]; next.r[p] = r[q];
+        }
 }
 
 struct MatchedLow {
@@ -454,7 +471,9 @@ static rama_status matching(Ctx &ctx, const Graph &g, float tau, int rounds_cap,
     RAMA_TRY(mate.alloc(ctx, n > 0 ? n : 1));
     RAMA_TRY(fill<int32_t>(ctx, mate.get(), -1, n));
     if (m == 0) return RAMA_OK;
-    Buf<uint32_t> act, act2;
+    Buf<int32_t> cu[2], cv[2];
+    Buf<unsigned long long> cr[2];
+    Cands cur{}, nxt{};
     uint32_t na = 0;
     {
         ScanPlan<uint32_t> cand;
@@ -462,9 +481,15 @@ static rama_status matching(Ctx &ctx, const Graph &g, float tau, int rounds_cap,
         RAMA_TRY((scan_totals<uint32_t>(ctx, CandFlag{g.c.get(), tau}, cand)));
         na = cand.total;
         if (na == 0) return RAMA_OK;
-        RAMA_TRY(act.alloc(ctx, na));
-        RAMA_TRY(act2.alloc(ctx, na));
-        RAMA_TRY((scan_emit<uint32_t>(ctx, CandFlag{g.c.get(), tau}, CollectEmit{act.get()}, cand, (double)((size_t)na * 4))));
+        for (int k = 0; k < 2; ++k) {
+            RAMA_TRY(cu[k].alloc(ctx, na));
+            RAMA_TRY(cv[k].alloc(ctx, na));
+            RAMA_TRY(cr[k].alloc(ctx, na));
+        }
+        cur = Cands{cu[0].get(), cv[0].get(), cr[0].get()};
+        nxt = Cands{cu[1].get(), cv[1].get(), cr[1].get()};
+        RAMA_TRY((scan_emit<uint32_t>(ctx, CandFlag{g.c.get(), tau}, PackCandsEmit{g.i.get(), g.j.get(), g.c.get(), cur}, cand,
+                                      (double)((size_t)na * 28))));
     }
     Buf<unsigned long long> best, best_next;     // rank words of the current and of the next round
     RAMA_TRY(best.alloc(ctx, n));
@@ -476,25 +501,24 @@ static rama_status matching(Ctx &ctx, const Graph &g, float tau, int rounds_cap,
     RAMA_TRY(fill<uint32_t>(ctx, counters.get(), 0u, (size_t)(rounds_cap > 0 ? rounds_cap : 1)));
     if (rounds_cap > 0) {
         ProfScope ps_(ctx, "k_propose", (double)((size_t)na * 32));
-        k_propose<<<grid_for(na), kBlock, 0, ctx.stream>>>(na, act.get(), g.i.get(), g.j.get(), g.c.get(), best.get());
+        k_propose<<<grid_for(na), kBlock, 0, ctx.stream>>>(na, cur, best.get());
     }
     LAUNCH_TRY(ctx, "propose");
     for (int r = 0; r < rounds_cap && na > 0; ++r) {
         {
             ProfScope ps_(ctx, "k_accept", (double)((size_t)na * 56));
-            k_accept<<<grid_for(na), kBlock, 0, ctx.stream>>>(na, act.get(), g.i.get(), g.j.get(), g.c.get(), best.get(),
-                                                             best_next.get(), mate.get());
+            k_accept<<<grid_for(na), kBlock, 0, ctx.stream>>>(na, cur, best.get(), best_next.get(), mate.get());
         }
         LAUNCH_TRY(ctx, "accept");
         {
             ProfScope ps_(ctx, "k_advance", (double)((size_t)na * 40));
             k_advance<<<grid_for(na, kBlock * kAdvItems), kBlock, 0, ctx.stream>>>(
-                na, act.get(), g.i.get(), g.j.get(), g.c.get(), mate.get(), act2.get(), best_next.get(), counters.get() + r);
+                na, cur, mate.get(), nxt, best_next.get(), counters.get() + r);
         }
         LAUNCH_TRY(ctx, "advance");
         uint32_t nn = 0;
         RAMA_TRY(read_back(ctx, &nn, counters.get() + r, 4));
-        act.swap(act2);
+        Cands t = cur; cur = nxt; nxt = t;
         best.swap(best_next);
         na = nn;
     }
