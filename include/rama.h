@@ -113,6 +113,15 @@ rama_status rama_profile_get(const rama_ctx *ctx, int32_t index, const char **na
                              double *bytes);
 
 /*
+ * Tuning hook (not an operation of the paper).  The library sorts with stable 8-bit radix passes.
+ * An array of at least `n_min` elements is instead sorted by passes over its top key bits followed
+ * by one sort of the remaining bits inside LDS, provided that replaces at least
+ * `min_passes_replaced` passes.  Both ways are the same stable sort, so no result depends on the
+ * setting.  Defaults: 2^21 and 2.  (0, 0) sends every array that way, (INT64_MAX, any) none.
+ */
+rama_status rama_set_sort_split(rama_ctx *ctx, int64_t n_min, int32_t min_passes_replaced);
+
+/*
  * Conflicted-cycle separation (Sec. 3.2.2, definition "Conflicted cycles", and the appendix
  * algorithm "Parallel Conf. 5-Cycles"): every simple cycle of length L in {3,..,max_cycle_len}
  * with exactly one repulsive edge and L-1 attractive edges.  The paper separates up to length 5

@@ -15,7 +15,7 @@ RAMA_OK, RAMA_ERR_INVALID_ARG, RAMA_ERR_BAD_GRAPH, RAMA_ERR_CAPACITY, RAMA_ERR_O
 
 EXPORTS = [
     "rama_create", "rama_destroy", "rama_last_error", "rama_params_default", "rama_workspace_bytes",
-    "rama_profile_enable", "rama_profile_count", "rama_profile_get",
+    "rama_profile_enable", "rama_profile_count", "rama_profile_get", "rama_set_sort_split",
     "rama_find_conflicted_cycles", "rama_message_passing", "rama_dual_rounds", "rama_contract", "rama_solve",
 ]
 
@@ -84,6 +84,7 @@ def load_library():
     lib.rama_solve.argtypes = [vp, i32, i64, vp, vp, vp, C.POINTER(RamaParams), vp, C.POINTER(C.c_double),
                                C.POINTER(C.c_double), C.POINTER(RamaStats)]
     lib.rama_profile_enable.argtypes = [vp, i32, C.c_char_p]
+    lib.rama_set_sort_split.argtypes = [vp, i64, i32]
     lib.rama_profile_count.argtypes = [vp]
     lib.rama_profile_count.restype = i32
     lib.rama_profile_get.argtypes = [vp, i32, C.POINTER(C.c_char_p), C.POINTER(i64), C.POINTER(C.c_double),
@@ -164,6 +165,11 @@ class Rama:
     def profile_enable(self, on=True, only=None):
         self._check(self.lib.rama_profile_enable(self.ctx, 1 if on else 0, only.encode() if only else None),
                     "rama_profile_enable")
+
+    def set_sort_split(self, n_min, min_passes_replaced=2):
+        """Arrays of at least n_min elements take the split sort (top-bit passes + one in-LDS sort)
+        when that replaces at least min_passes_replaced radix passes."""
+        self._check(self.lib.rama_set_sort_split(self.ctx, int(n_min), int(min_passes_replaced)), "rama_set_sort_split")
 
     def profile_get(self):
         """Per-kernel totals since profiling was enabled: name, launches, ms, algorithmic bytes."""

@@ -315,6 +315,14 @@ rama_status rama_profile_enable(rama_ctx *ctx, int32_t on, const char *only)
     return RAMA_OK;
 }
 
+rama_status rama_set_sort_split(rama_ctx *ctx, int64_t n_min, int32_t min_passes_replaced)
+{
+    if (!ctx || n_min < 0 || min_passes_replaced < 0) return RAMA_ERR_INVALID_ARG;
+    ctx->sort_split_min = (size_t)n_min;
+    ctx->sort_split_gain = min_passes_replaced;
+    return RAMA_OK;
+}
+
 int32_t rama_profile_count(const rama_ctx *ctx) { return ctx ? (int32_t)ctx->prof.stats.size() : 0; }
 
 rama_status rama_profile_get(const rama_ctx *ctx, int32_t index, const char **name, int64_t *launches, double *ms,

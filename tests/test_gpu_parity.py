@@ -509,6 +509,80 @@ def test_random_sweep_of_small_instances_and_parameters(rama, oracle32):
     assert not bad, bad
 
 
+# --------------------------------------------------------------------------------------------
+# the split sort (top-bit passes + one in-LDS sort) is the same stable sort as passes over all bits
+# --------------------------------------------------------------------------------------------
+@pytest.fixture(scope="module")
+def rama_split():
+    from paper_2109_01838_amd import Rama
+    r = Rama("cuda:0")
+    r.set_sort_split(0, 0)          # every sort of two or more elements takes the split path
+    yield r
+    r.close()
+
+
+def star_graph(n_leaves, seed):
+    """Node 0 joined to every other node, plus a sparse ring: all edges of the hub share their
+    first endpoint, so the hub's segment exceeds what a workgroup can sort in LDS."""
+    rng = np.random.default_rng(seed)
+    leaves = np.arange(1, n_leaves + 1, dtype=np.int32)
+    i = np.concatenate([np.zeros(n_leaves, np.int32), leaves[:-1]])
+    j = np.concatenate([leaves, leaves[1:]])
+    mag = np.abs(rng.normal(0.0, 1.0, i.size)).astype(np.float32) + 0.05
+    c = np.where(rng.random(i.size) < 0.7, mag, -mag).astype(np.float32)
+    perm = rng.permutation(i.size)
+    return dict(name=f"star_{n_leaves}", n_nodes=n_leaves + 1, i=i[perm], j=j[perm], c=c[perm])
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_split_sort_stagewise(rama_split, oracle32, name):
+    from paper_2109_01838_amd import default_params
+    g = CASES[name]
+    n = g["n_nodes"]
+    lmax = 4 if name == "random_dense" else 5
+    cyc = oracle32.find_conflicted_cycles(n, g["i"], g["j"], g["c"], lmax)
+    got = rama_split.find_conflicted_cycles(n, g["i"], g["j"], g["c"], lmax)
+    for a, b in zip(got, cyc):
+        assert np.array_equal(np_(a), b)
+    want = oracle32.message_passing(n, g["i"], g["j"], g["c"], cyc, 3)
+    mp = rama_split.message_passing(n, g["i"], g["j"], g["c"], cyc, 3)
+    assert np.array_equal(np_(mp["i"]), want["i"]) and np.array_equal(np_(mp["j"]), want["j"])
+    assert rel_close(np_(mp["c"]), want["c"])
+    for forest_ratio in (0.1, 1.0):
+        w = oracle32.contract(n, want["i"], want["j"], want["c"], forest_ratio=forest_ratio)
+        con = rama_split.contract(n, want["i"], want["j"], want["c"], params=default_params(forest_ratio=forest_ratio))
+        assert np.array_equal(np_(con["mapping"]), w["mapping"])
+        assert np.array_equal(np_(con["i"]), w["i"]) and np.array_equal(np_(con["j"]), w["j"])
+        assert rel_close(np_(con["c"]), w["c"])
+
+
+@pytest.mark.parametrize("name", list(CASES) + ["hubs", "star_9", "star_40000"])
+def test_split_sort_solve(rama, rama_split, oracle32, name):
+    """Same labels, bounds and counts from both sort paths (bit for bit: both are the same stable
+    sort), and both agree with the oracle.  star_40000 holds a segment no workgroup can take, which
+    sends the split path back to passes over all bits after its top-bit passes."""
+    g = CASES[name] if name in CASES else (inputs.hub_graph() if name == "hubs" else star_graph(int(name[5:]), 3))
+    n = g["n_nodes"]
+    a = rama.solve(n, g["i"], g["j"], g["c"])
+    b = rama_split.solve(n, g["i"], g["j"], g["c"])
+    want = oracle32.solve(n, g["i"], g["j"], g["c"])
+    assert np.array_equal(np_(a["labels"]), np_(b["labels"]))
+    assert a["primal"] == b["primal"] and a["lower_bound"] == b["lower_bound"]
+    assert a["n_cycles_first"] == b["n_cycles_first"] == want["n_cycles_first"]
+    assert a["rounds"] == b["rounds"]
+    assert np.array_equal(np_(b["labels"]), want["labels"])
+    assert abs(b["lower_bound"] - want["lower_bound"]) <= REL * max(1.0, abs(want["lower_bound"]))
+
+
+def test_split_sort_takes_its_kernels(rama_split):
+    g = CASES["knn_20000"]
+    rama_split.profile_enable(True)
+    rama_split.solve(g["n_nodes"], g["i"], g["j"], g["c"])
+    names = {k["name"] for k in rama_split.profile_get()}
+    rama_split.profile_enable(False)
+    assert "k_seg_bounds" in names and "k_rs_local<u64,u32>" in names and "k_rs_local<u32,u32>" in names
+
+
 def test_context_on_a_side_stream_and_two_contexts(rama):
     """A context bound to a non-default stream (default priority) gives the same result as the
     default-stream context, also when the two are used in turn."""
