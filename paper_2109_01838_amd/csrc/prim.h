@@ -492,6 +492,34 @@ __global__ __launch_bounds__(kBlock) void k_rs_hist(const K *keys, uint32_t *his
     for (uint32_t d = threadIdx.x; d <= mask; d += kBlock) hist[(size_t)d * nb + blockIdx.x] = h[d];
 }
 
+// Offsets of a pass from its [digit][tile] histogram: workgroup d scans row d (keys with digit d in
+// earlier tiles) and stores the row's total behind the table; the scatter kernel adds the keys of
+// smaller digits itself, from the 256 totals.  One launch instead of the three of a general scan.
+static __global__ __launch_bounds__(kBlock) void k_rs_rowscan(const uint32_t *hist, uint32_t *offs, uint32_t nb, uint32_t *totals)
+{
+    const uint32_t *in = hist + (size_t)blockIdx.x * nb;
+    uint32_t *out = offs + (size_t)blockIdx.x * nb;
+    uint32_t carry = 0;
+    for (uint32_t c0 = 0; c0 < nb; c0 += kScanTile) {
+        const uint32_t base = c0 + threadIdx.x * kScanItems;
+        uint32_t v[kScanItems], s = 0;
+#pragma unroll
+        for (int q = 0; q < kScanItems; ++q) {
+            v[q] = (base + q < nb) ? in[base + q] : 0u;
+            s += v[q];
+        }
+        uint32_t tot;
+        uint32_t run = block_inclusive_scan(s, &tot) - s + carry;
+#pragma unroll
+        for (int q = 0; q < kScanItems; ++q) {
+            if (base + q < nb) out[base + q] = run;
+            run += v[q];
+        }
+        carry += tot;
+    }
+    if (threadIdx.x == 0) totals[blockIdx.x] = carry;
+}
+
 __device__ __forceinline__ uint64_t match_digit(uint32_t d, int bits, uint64_t valid)
 {
     uint64_t m = valid;
@@ -509,7 +537,7 @@ __device__ __forceinline__ uint64_t match_digit(uint32_t d, int bits, uint64_t v
 // is written out linearly -- neighbouring lanes hold neighbouring keys of the same digit, so the
 // global stores fall into contiguous runs instead of 64 scattered lines per instruction.
 // With LOCAL_SCAN (few tiles) `offs` is the raw [digit][tile] histogram and every workgroup derives
-// its own global offsets from it, which saves the three scan launches of the pass.
+// its own global offsets from it, which saves the scan launch of the pass.
 constexpr uint32_t kSortLocalScanTiles = 32;
 template <typename K, typename V, bool HAS_V, bool LOCAL_SCAN>
 __global__ __launch_bounds__(kBlock) void k_rs_scatter(const K *kin, const V *vin, K *kout, V *vout,
@@ -583,10 +611,22 @@ __global__ __launch_bounds__(kBlock) void k_rs_scatter(const K *kin, const V *vi
 #pragma unroll
             for (int q = 0; q < kDigitsPerThread; ++q) { goff[q] = dig + before[q]; dig += rowsum[q]; }
         } else {
+            // offs: per digit the keys in earlier tiles, and behind the table the digits' totals
+            const uint32_t *totals = offs + (size_t)kRadix * nb;
+            uint32_t rows = 0, rowsum[kDigitsPerThread];
 #pragma unroll
             for (int q = 0; q < kDigitsPerThread; ++q) {
                 const uint32_t d = (uint32_t)(tid * kDigitsPerThread + q);
-                goff[q] = d <= mask ? offs[(size_t)d * nb + blockIdx.x] : 0u;
+                rowsum[q] = d <= mask ? totals[d] : 0u;
+                rows += rowsum[q];
+            }
+            uint32_t dummy;
+            uint32_t dig = block_inclusive_scan(rows, &dummy) - rows;
+#pragma unroll
+            for (int q = 0; q < kDigitsPerThread; ++q) {
+                const uint32_t d = (uint32_t)(tid * kDigitsPerThread + q);
+                goff[q] = dig + (d <= mask ? offs[(size_t)d * nb + blockIdx.x] : 0u);
+                dig += rowsum[q];
             }
         }
 #pragma unroll
@@ -831,7 +871,11 @@ rama_status radix_passes(Ctx &ctx, K *&ka, V *&va, K *&kb, V *&vb, size_t n, int
             ProfScope ps_(ctx, rs_scatter_name<K, HAS_V>(), (double)(n * (2 * sizeof(K) + (HAS_V ? 8 : 0))));
             k_rs_scatter<K, V, HAS_V, true><<<nb, kBlock, 0, ctx.stream>>>(ka, va, kb, vb, hist, n, shift, bits, nb);
         } else {
-            RAMA_TRY((exclusive_scan<uint32_t, PtrInput<uint32_t>>(ctx, PtrInput<uint32_t>{hist}, offs, (size_t)nb << bits)));
+            {
+                ProfScope ps_(ctx, "k_rs_rowscan", (double)(((size_t)nb << bits) * 8));
+                k_rs_rowscan<<<1u << bits, kBlock, 0, ctx.stream>>>(hist, offs, nb, offs + (size_t)kRadix * nb);
+            }
+            LAUNCH_TRY(ctx, "rs_rowscan");
             ProfScope ps_(ctx, rs_scatter_name<K, HAS_V>(), (double)(n * (2 * sizeof(K) + (HAS_V ? 8 : 0))));
             k_rs_scatter<K, V, HAS_V, false><<<nb, kBlock, 0, ctx.stream>>>(ka, va, kb, vb, offs, n, shift, bits, nb);
         }
@@ -892,7 +936,7 @@ rama_status radix_sort_impl(Ctx &ctx, K *ka, V *va, K *kb, V *vb, size_t n, int 
     const uint32_t nb = grid_for(n, SortTile<K>::size);
     Buf<uint32_t> hist, offs;
     RAMA_TRY(hist.alloc(ctx, (size_t)kRadix * nb));
-    RAMA_TRY(offs.alloc(ctx, (size_t)kRadix * nb + 1));
+    RAMA_TRY(offs.alloc(ctx, (size_t)kRadix * nb + kRadix));
     const int all_passes = (total_bits + kRadixBits - 1) / kRadixBits;
     if (n >= ctx.sort_split_min) {
         // top bits: whole passes, enough of them for segments of a quarter of a workgroup's capacity on

@@ -154,6 +154,22 @@ def test_fullsize_solve_properties(big, dev):
     assert r["primal"] <= 0.9 * planted
     r2 = rama.solve(n, t["i"], t["j"], t["c"])
     assert r2["primal"] == r["primal"] and r2["lower_bound"] == r["lower_bound"]   # deterministic
+    # at this size the long sorts take the split path (top-bit passes + in-LDS sort); with that path
+    # switched off the library sorts by passes over all bits, and nothing may change
+    import torch
+    names = set()
+    rama.profile_enable(True)
+    rama.solve(n, t["i"], t["j"], t["c"])
+    names |= {k["name"] for k in rama.profile_get()}
+    rama.profile_enable(False)
+    assert "k_rs_local<u64,u32>" in names and "k_rs_local<u32,u32>" in names
+    rama.set_sort_split(1 << 62, 2)
+    try:
+        r3 = rama.solve(n, t["i"], t["j"], t["c"])
+    finally:
+        rama.set_sort_split(1 << 21, 2)
+    assert r3["primal"] == r["primal"] and r3["lower_bound"] == r["lower_bound"] and r3["rounds"] == r["rounds"]
+    assert torch.equal(r3["labels"], r["labels"])
 
 
 def test_fullsize_shortest_longer_cycles_sampled_windows(big, dev, oracle32):
