@@ -650,7 +650,7 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
         LAUNCH_TRY(ctx, "triangle_update");
         {
             const bool store_ce = it == k_iters || lb_trace != nullptr;
-            ProfScope ps_(ctx, "k_edge_update", (double)(na * (store_ce ? 16 : 12) + 3 * T * 8));
+            ProfScope ps_(ctx, store_ce ? "k_edge_update<true>" : "k_edge_update<false>", (double)(na * (store_ce ? 16 : 12) + 3 * T * 8));
             if (store_ce)
                 k_edge_update<true><<<grid_for(na), kBlock, 0, ctx.stream>>>(na, act_edge.get(), act_start.get(), slot.get(),
                                                                          msg.get(), ce, share.get());
