@@ -50,7 +50,10 @@ __global__ __launch_bounds__(kBlock) void k_compose(size_t n, int32_t *f, const 
 __global__ __launch_bounds__(kBlock) void k_cluster_min(size_t n, const int32_t *f, int32_t *first)
 {
     size_t v = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    if (v < n) atomicMin(&first[f[v]], (int32_t)v);
+    // nodes ascend with the lanes: a lane whose left neighbour is in the same cluster cannot hold the minimum
+    const int32_t mine = v < n ? f[v] : -1;
+    const int32_t left = __shfl_up(mine, 1, 64);
+    if (v < n && (lane_id() == 0 || left != mine)) atomicMin(&first[mine], (int32_t)v);
 }
 
 __global__ __launch_bounds__(kBlock) void k_labels(size_t n, const int32_t *f, const int32_t *first, int32_t *labels)

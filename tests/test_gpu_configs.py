@@ -1,6 +1,7 @@
 """End-to-end parity on the named configurations the oracle can still solve (cfg2: 512x512 grid
 with long-range edges, 1.56e6 edges; cfg3: 1e6-point 6-NN graph, ~3.5e6 edges) at their full
-sizes: primal within 0.5 %, lower bound within 1e-4 relative, and -- because both sides order
+sizes, and on a 110^3 cube of cfg5's recipe (3.96e6 edges), the smallest of these on which the
+long sorts of both key widths take the split path (top-bit passes + in-LDS sort) by themselves: primal within 0.5 %, lower bound within 1e-4 relative, and -- because both sides order
 their arithmetic identically -- in practice identical labels."""
 import numpy as np
 import pytest
@@ -19,11 +20,16 @@ def rama():
 
 
 @pytest.mark.timeout(600)
-@pytest.mark.parametrize("name", ["cfg2", "cfg3"])
+@pytest.mark.parametrize("name", ["cfg2", "cfg3", "cfg5crop110"])
 def test_named_config_end_to_end(rama, oracle32, name):
-    g = inputs.make(name)
+    g = inputs.cfg5_crop(110, seed=5) if name == "cfg5crop110" else inputs.make(name)
     n = g["n_nodes"]
+    rama.profile_enable(True)
     got = rama.solve(n, g["i"], g["j"], g["c"])
+    kernels = {k["name"] for k in rama.profile_get()}
+    rama.profile_enable(False)
+    if name == "cfg5crop110":
+        assert {"k_rs_local<u64,u32>", "k_rs_local<u32>", "k_seg_bounds"} <= kernels
     print(name, "gpu:", {k: v for k, v in got.items() if k not in ("labels",)}, flush=True)
     want = oracle32.solve(n, g["i"], g["j"], g["c"])
     labels = got["labels"].cpu().numpy()
