@@ -6,7 +6,8 @@
 //         incident candidate" is an integer atomicMax per endpoint -- order independent, hence
 //         deterministic.  An edge both of whose endpoints point at it is matched; rounds repeat
 //         on the shrinking list of edges whose endpoints are both still free (two kernels per
-//         round: accept, then compaction of the survivors fused with their next proposals).
+//         round: accept, then compaction of the survivors fused with their next proposals); the
+//         list carries endpoints and rank word, so a round streams it and touches no edge array.
 //   f'  : connected components of (V,S) by min-label hooking + pointer jumping; a component is
 //         represented by its smallest node; new ids are the ranks of the representatives.
 //   S'  : when the matching joins fewer than forest_ratio*|V| pairs: maximum spanning forest of the
