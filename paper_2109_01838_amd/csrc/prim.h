@@ -845,9 +845,13 @@ __global__ __launch_bounds__(kLocalSortWaves * 64) void k_rs_local(const K *kin,
     }
 }
 
-template <typename K, bool HAS_V>
+template <typename K, bool HAS_V, typename LK>
 inline const char *rs_local_name()
 {
+    if (sizeof(LK) == 8) {      // 64-bit keys inside LDS: the low bits did not fit 32
+        if (HAS_V) return sizeof(K) == 8 ? "k_rs_local<u64,u32,wide>" : "k_rs_local<u32,u32,wide>";
+        return sizeof(K) == 8 ? "k_rs_local<u64,wide>" : "k_rs_local<u32,wide>";
+    }
     if (HAS_V) return sizeof(K) == 8 ? "k_rs_local<u64,u32>" : "k_rs_local<u32,u32>";
     return sizeof(K) == 8 ? "k_rs_local<u64>" : "k_rs_local<u32>";
 }
@@ -912,7 +916,7 @@ rama_status split_sort_tail(Ctx &ctx, K *ka, V *va, K *kb, V *vb, size_t n, int 
     RAMA_TRY(read_back(ctx, &over, oversize, 4));
     if (over) return RAMA_OK;
     {
-        ProfScope ps_(ctx, rs_local_name<K, HAS_V>(), (double)(n * (2 * sizeof(K) + (HAS_V ? 8 : 0))));
+        ProfScope ps_(ctx, rs_local_name<K, HAS_V, LK>(), (double)(n * (2 * sizeof(K) + (HAS_V ? 8 : 0))));
         k_rs_local<K, V, HAS_V, LK><<<nbk, LS::threads, 0, ctx.stream>>>(ka, va, kb, vb, bounds.get(), low_bits);
     }
     LAUNCH_TRY(ctx, "rs_local");

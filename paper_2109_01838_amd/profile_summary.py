@@ -55,7 +55,8 @@ def event_name(rocprof_name):
     if n.startswith("k_rs_local<"):
         # <key, value, has values, key type inside LDS>
         args = n[len("k_rs_local<"):].rstrip(">").split(",")
-        return f"k_rs_local<{args[0]},{args[1]}>" if args[2] == "true" else f"k_rs_local<{args[0]}>"
+        wide = ",wide" if args[3] == "u64" else ""
+        return f"k_rs_local<{args[0]},{args[1]}{wide}>" if args[2] == "true" else f"k_rs_local<{args[0]}{wide}>"
     if n.startswith(("k_scan_", "k_sum_partial")) and "<" in n:
         head, args = n.split("<", 1)
         functor = args.rstrip(">").split(",")[-1].split("<")[0].strip()

@@ -583,6 +583,31 @@ def test_split_sort_takes_its_kernels(rama_split):
     assert "k_seg_bounds" in names and "k_rs_local<u64,u32>" in names and "k_rs_local<u32,u32>" in names
 
 
+def test_split_sort_with_wide_local_keys(rama_split, oracle32):
+    """Few edges over many nodes: one pass over the top bits leaves more than 26 low bits, which do
+    not fit the 32-bit keys of the in-LDS sort, so its 64-bit variant runs."""
+    from paper_2109_01838_amd import default_params
+    g = signed(inputs.random_graph(200000, 400000, 21), 21, 0.75)
+    perm = np.random.default_rng(5).permutation(g["i"].size)     # unsorted input: canonicalising it sorts (key, cost) pairs
+    g = dict(g, i=g["i"][perm], j=g["j"][perm], c=g["c"][perm])
+    n = g["n_nodes"]
+    rama_split.profile_enable(True)
+    got = rama_split.solve(n, g["i"], g["j"], g["c"])
+    names = {k["name"] for k in rama_split.profile_get()}
+    rama_split.profile_enable(False)
+    assert {"k_rs_local<u64,u32,wide>", "k_rs_local<u64,wide>"} <= names
+    want = oracle32.solve(n, g["i"], g["j"], g["c"])
+    assert np.array_equal(np_(got["labels"]), want["labels"])
+    assert got["n_cycles_first"] == want["n_cycles_first"] and got["rounds"] == want["rounds"]
+    assert abs(got["lower_bound"] - want["lower_bound"]) <= REL * max(1.0, abs(want["lower_bound"]))
+    for forest_ratio in (0.1, 1.0):
+        w = oracle32.contract(n, g["i"], g["j"], g["c"], forest_ratio=forest_ratio)
+        con = rama_split.contract(n, g["i"], g["j"], g["c"], params=default_params(forest_ratio=forest_ratio))
+        assert np.array_equal(np_(con["mapping"]), w["mapping"])
+        assert np.array_equal(np_(con["i"]), w["i"]) and np.array_equal(np_(con["j"]), w["j"])
+        assert rel_close(np_(con["c"]), w["c"])
+
+
 def test_context_on_a_side_stream_and_two_contexts(rama):
     """A context bound to a non-default stream (default priority) gives the same result as the
     default-stream context, also when the two are used in turn."""

@@ -59,6 +59,7 @@ def test_profiler_names_map_onto_timer_names():
     assert f("void rama::(anonymous namespace)::k_edge_update<false>(unsigned long)") == "k_edge_update<false>"
     assert f("void rama::k_rs_local<unsigned long, unsigned int, true, unsigned int>(unsigned long const*)") == "k_rs_local<u64,u32>"
     assert f("void rama::k_rs_local<unsigned int, unsigned int, false, unsigned int>(unsigned int const*)") == "k_rs_local<u32>"
+    assert f("void rama::k_rs_local<unsigned long, unsigned int, true, unsigned long>(unsigned long const*)") == "k_rs_local<u64,u32,wide>"
     assert f("rama::(anonymous namespace)::k_triangle_update(unsigned long, int const*)") == "k_triangle_update"
 
 
