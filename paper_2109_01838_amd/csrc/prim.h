@@ -482,7 +482,18 @@ __global__ __launch_bounds__(kBlock) void k_rs_hist(const K *keys, uint32_t *his
         for (int r = 0; r < kVecs; ++r) {
             KeyVec<K> v = src[(size_t)r * kBlock + threadIdx.x];
 #pragma unroll
-            for (int q = 0; q < kPer; ++q) atomicAdd(&h[(uint32_t)(v.k[q] >> shift) & mask], 1u);
+            for (int q = 0; q < kPer; ++q) {
+                // The top digits of nearly sorted keys (edge lists keyed by their first endpoint) are the
+                // same across a wave more often than not, and 64 atomics on one LDS word run one after
+                // the other: such a wave adds its count once.
+                const uint32_t d = (uint32_t)(v.k[q] >> shift) & mask;
+                const uint32_t d0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)d);
+                if (__ballot(d != d0) == 0ull) {
+                    if (lane_id() == 0) atomicAdd(&h[d0], 64u);
+                } else {
+                    atomicAdd(&h[d], 1u);
+                }
+            }
         }
     } else {
         for (size_t idx = tile + threadIdx.x; idx < n; idx += kBlock)
