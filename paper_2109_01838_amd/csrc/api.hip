@@ -108,7 +108,7 @@ rama_status dual_block(Ctx &ctx, Graph &g, int lmax, bool shortest_only, int k, 
         DualState next;
         const bool more = d < rounds;   // the last round's triangles are not needed afterwards
         RAMA_TRY(dual_update(ctx, g, kCycleLists, lists, cyc.n, false, k, aug, (lb || trace) ? &cur : nullptr, nullptr, &info,
-                             state.T > 0 ? &state : nullptr, more ? &next : nullptr));
+                             state.T > 0 ? &state : nullptr, more ? &next : nullptr, &g));
         g = std::move(aug);
         state = std::move(next);
         if (n_triangles) *n_triangles = info.n_triangles;
@@ -170,7 +170,7 @@ rama_status solve_impl(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const i
                     Graph aug;
                     DualInfo info;
                     RAMA_TRY(dual_update(ctx, g, kCycleLists, lists, cyc.n, false, k, aug, round == 1 ? &lbr : nullptr,
-                                         nullptr, &info));
+                                         nullptr, &info, nullptr, nullptr, &g));
                     ntri = info.n_triangles;
                     ran = true;
                     g = std::move(aug);
@@ -392,7 +392,7 @@ rama_status rama_message_passing(rama_ctx *ctx, int32_t n_nodes, int64_t n_edges
         Graph g, out;
         RAMA_TRY(canonicalise(*ctx, n_nodes, n_edges, i, j, c, g));
         RAMA_TRY(dual_update(*ctx, g, max_cycle_len - 2, cycles, n_cycles, true, k_iters, out, lower_bound, lb_trace,
-                             nullptr));
+                             nullptr, nullptr, nullptr, &g));
         *n_edges_out = out.m;
         if (out.m > edge_cap)
             return fail(*ctx, RAMA_ERR_CAPACITY, "edge output buffers are too small; needed size written to n_edges_out");

@@ -311,7 +311,8 @@ struct DualState {
 // triangle set and costs after the last iteration.
 rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *const *cycles, const int64_t *n_cycles,
                         bool validate_cycles, int k_iters, Graph &out, double *lower_bound, double *lb_trace,
-                        DualInfo *info, const DualState *prev = nullptr, DualState *next = nullptr);
+                        DualInfo *info, const DualState *prev = nullptr, DualState *next = nullptr,
+                        Graph *donor = nullptr);
 
 // a4..a6: one primal update.  fmap[n] -> [0,n_new); n_matched = |S|.  If |S|==0 nothing else is produced.
 rama_status contract_once(Ctx &ctx, const Graph &g, float tau, int rounds_cap, float forest_ratio, Buf<int32_t> &fmap,

@@ -433,7 +433,7 @@ rama_status copy_graph(Ctx &ctx, const Graph &g, Graph &out)
 
 rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *const *cycles, const int64_t *n_cycles,
                         bool validate_cycles, int k_iters, Graph &out, double *lower_bound, double *lb_trace,
-                        DualInfo *info, const DualState *prev, DualState *next)
+                        DualInfo *info, const DualState *prev, DualState *next, Graph *donor)
 {
     if (lists < 0 || lists > kCycleLists || k_iters < 0 || (lists > 0 && (!cycles || !n_cycles)))
         return fail(ctx, RAMA_ERR_INVALID_ARG, "message passing: bad cycle lists or iteration count");
@@ -547,7 +547,17 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
             RAMA_TRY((row_bounds<int32_t, int32_t>(ctx, aug.i.get(), (size_t)aug.m, n, rowptr.get())));
         }
     }
-    if (nnew == 0) RAMA_TRY(copy_graph(ctx, g, aug));
+    if (nnew == 0) {
+        // no chord to add: the augmented graph is the input graph.  `donor` (the same graph, owned by a
+        // caller that replaces it by the result anyway) hands its arrays over instead of being copied;
+        // nothing below reads g.
+        if (donor) {
+            aug.n = g.n; aug.m = g.m;
+            aug.i = std::move(donor->i); aug.j = std::move(donor->j); aug.c = std::move(donor->c);
+        } else {
+            RAMA_TRY(copy_graph(ctx, g, aug));
+        }
+    }
     const size_t ma = (size_t)aug.m;
     // ---- triangles -----------------------------------------------------------------------------
     Buf<uint32_t> maxrow;
