@@ -82,11 +82,35 @@ struct Adj {
     const int32_t *nb;
 };
 
-// calls f(x) for every x in row a & row b, ascending: walk the shorter row, search the longer
+// calls f(x) for every x in row a & row b, ascending.  Two short rows are fetched whole -- sixteen
+// independent loads, one memory latency -- and compared in registers; otherwise walk the shorter
+// row and search the longer (a chain of dependent loads, but few rows are long).
+constexpr int kShortRow = 8;
 template <typename F>
 __device__ __forceinline__ void intersect_rows(const Adj &g, int32_t a, int32_t b, F &&f)
 {
     int32_t a0 = g.ptr[a], a1 = g.ptr[a + 1], b0 = g.ptr[b], b1 = g.ptr[b + 1];
+    if (a1 - a0 <= kShortRow && b1 - b0 <= kShortRow) {
+        if (a0 == a1 || b0 == b1) return;
+        // eight entries from each row start with two 16-byte loads (the array is padded by eight
+        // entries; what lies behind the row's end is masked out)
+        int32_t ra[kShortRow], rb[kShortRow];
+        __builtin_memcpy(ra, g.nb + a0, sizeof(ra));
+        __builtin_memcpy(rb, g.nb + b0, sizeof(rb));
+#pragma unroll
+        for (int k = 0; k < kShortRow; ++k) {
+            ra[k] = a0 + k < a1 ? ra[k] : -1;
+            rb[k] = b0 + k < b1 ? rb[k] : -2;
+        }
+#pragma unroll
+        for (int k = 0; k < kShortRow; ++k) {
+            bool hit = false;
+#pragma unroll
+            for (int q = 0; q < kShortRow; ++q) hit |= (ra[k] == rb[q]);
+            if (hit) f(ra[k]);
+        }
+        return;
+    }
     if (a1 - a0 > b1 - b0) { int32_t t = a0; a0 = b0; b0 = t; t = a1; a1 = b1; b1 = t; }
     for (int32_t p = a0; p < a1 && b0 < b1; ++p) {
         int32_t x = g.nb[p];
@@ -554,7 +578,7 @@ rama_status find_cycles(Ctx &ctx, const Graph &g, int max_len, bool shortest_onl
     RAMA_TRY(up_ptr.alloc(ctx, (size_t)n + 1));
     RAMA_TRY(low_ptr.alloc(ctx, (size_t)n + 1));
     RAMA_TRY(rowptr.alloc(ctx, (size_t)n + 1));
-    RAMA_TRY(nb.alloc(ctx, (size_t)2 * mp));
+    RAMA_TRY(nb.alloc(ctx, (size_t)2 * mp + kShortRow));   // padded: short rows are read eight entries at a time
     RAMA_TRY((row_bounds<int32_t, int32_t>(ctx, pi.get(), mp, n, up_ptr.get())));
     RAMA_TRY((radix_sort_pairs<uint32_t, uint32_t>(ctx, lkey, lval, mp, bits_for((uint64_t)n))));
     RAMA_TRY((row_bounds<uint32_t, int32_t>(ctx, lkey.get(), mp, n, low_ptr.get())));
