@@ -479,7 +479,7 @@ rama_status count_and_fill(Ctx &ctx, size_t mr, const int32_t *ri, const int32_t
     RAMA_TRY(n_heavy.alloc(ctx, 1));
     RAMA_TRY(fill<uint32_t>(ctx, n_heavy.get(), 0u, 1));
     {
-        ProfScope ps_(ctx, "k_count_cycles", (double)(mr * (8 + 4 * (size_t)lists) + ((size_t)n + 1) * 4 + mp * 8));
+        ProfScope ps_(ctx, MAXL == 3 ? "k_count_cycles<3>" : MAXL == 5 ? "k_count_cycles<5>" : "k_count_cycles<7>", (double)(mr * (8 + 4 * (size_t)lists) + ((size_t)n + 1) * 4 + mp * 8));
         k_count_cycles<MAXL><<<grid_for(mr), kBlock, 0, ctx.stream>>>(mr, ri, rj, adj, max_len, shortest_only ? 1 : 0, cp,
                                                                      heavy.get(), n_heavy.get());
     }
@@ -532,7 +532,7 @@ rama_status count_and_fill(Ctx &ctx, size_t mr, const int32_t *ri, const int32_t
         RAMA_TRY((scan_emit<uint32_t>(ctx, has, CollectHitsEmit{hit.get()}, hits, (double)((size_t)nh * 4))));
     }
     {
-        ProfScope ps_(ctx, "k_fill_cycles", (double)((size_t)nh * (12 + 12 * (size_t)lists) + ((size_t)n + 1) * 4 + mp * 8) + list_bytes);
+        ProfScope ps_(ctx, MAXL == 3 ? "k_fill_cycles<3>" : MAXL == 5 ? "k_fill_cycles<5>" : "k_fill_cycles<7>", (double)((size_t)nh * (12 + 12 * (size_t)lists) + ((size_t)n + 1) * 4 + mp * 8) + list_bytes);
         k_fill_cycles<MAXL><<<grid_for(nh), kBlock, 0, ctx.stream>>>(nh, hit.get(), ri, rj, adj, lists, max_len, cp, op, vp);
     }
     LAUNCH_TRY(ctx, "fill_cycles");
@@ -595,6 +595,9 @@ rama_status find_cycles(Ctx &ctx, const Graph &g, int max_len, bool shortest_onl
     LAUNCH_TRY(ctx, "fill_adj");
     pi.reset(); pj.reset(); lkey.reset(); lval.reset(); up_ptr.reset(); low_ptr.reset();
     Adj adj{rowptr.get(), nb.get()};
+    // one instantiation per depth class: triangles are row intersections and need no walk state
+    if (max_len <= 3)
+        return count_and_fill<3>(ctx, (size_t)mr, ri.get(), rj.get(), adj, n, (size_t)mp, max_len, shortest_only, count_only, out);
     if (max_len <= 5)
         return count_and_fill<5>(ctx, (size_t)mr, ri.get(), rj.get(), adj, n, (size_t)mp, max_len, shortest_only, count_only, out);
     return count_and_fill<kMaxCycleLen>(ctx, (size_t)mr, ri.get(), rj.get(), adj, n, (size_t)mp, max_len, shortest_only,

@@ -61,7 +61,7 @@ def event_name(rocprof_name):
         head, args = n.split("<", 1)
         functor = args.rstrip(">").split(",")[-1].split("<")[0].strip()
         return f"{head}<{functor}>"
-    if "<" in n and not n.startswith(("k_rs_hist<", "k_edge_update<")):
+    if "<" in n and not n.startswith(("k_rs_hist<", "k_edge_update<", "k_count_cycles<", "k_fill_cycles<")):
         return n.split("<", 1)[0]     # plain template arguments (lengths, flags) are not part of the timers' names
     return n
 

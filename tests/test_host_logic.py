@@ -55,7 +55,7 @@ def test_profiler_names_map_onto_timer_names():
     assert f("void rama::k_rs_hist<unsigned long>(unsigned long const*, unsigned int*)") == "k_rs_hist<u64>"
     assert f("void rama::k_scan_apply<unsigned int, rama::(anonymous namespace)::HeadFlag>(x)") == "k_scan_apply<HeadFlag>"
     assert f("void rama::k_scan_reduce<unsigned long, rama::PtrInput<unsigned int> >(x)") == "k_scan_reduce<PtrInput>"
-    assert f("void rama::(anonymous namespace)::k_count_cycles<5>(unsigned long, int const*)") == "k_count_cycles"
+    assert f("void rama::(anonymous namespace)::k_count_cycles<5>(unsigned long, int const*)") == "k_count_cycles<5>"
     assert f("void rama::(anonymous namespace)::k_edge_update<false>(unsigned long)") == "k_edge_update<false>"
     assert f("void rama::k_rs_local<unsigned long, unsigned int, true, unsigned int>(unsigned long const*)") == "k_rs_local<u64,u32>"
     assert f("void rama::k_rs_local<unsigned int, unsigned int, false, unsigned int>(unsigned int const*)") == "k_rs_local<u32>"
