@@ -172,16 +172,13 @@ struct MatchedLow {
     __device__ __forceinline__ uint32_t operator()(size_t v) const { return mate[v] > (int32_t)v ? 1u : 0u; }
 };
 
-// consumer of the scan over MatchedLow: the matched pairs as an edge list
-struct EmitPairs {
-    static constexpr const char *tag = "EmitPairs";
-    const int32_t *mate;
-    int32_t *si, *sj;
-    __device__ __forceinline__ void operator()(size_t v, uint32_t low, uint32_t p) const
-    {
-        if (low) { si[p] = (int32_t)v; sj[p] = mate[v]; }
-    }
-};
+__global__ __launch_bounds__(kBlock) void k_pair_rep(size_t n, const int32_t *mate, int32_t *rep)
+{
+    size_t v = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (v >= n) return;
+    const int32_t w = mate[v];
+    rep[v] = (w >= 0 && w < (int32_t)v) ? w : (int32_t)v;
+}
 
 // ---- connected components of (V,S) -------------------------------------------------------------
 __global__ __launch_bounds__(kBlock) void k_iota(size_t n, int32_t *p)
@@ -463,12 +460,10 @@ __global__ __launch_bounds__(kBlock) void k_mark_conflicts(size_t m, const int32
 }  // namespace
 
 // handshake matching; mate[v] = partner or -1; returns |S| in n_matched
-static rama_status matching(Ctx &ctx, const Graph &g, float tau, int rounds_cap, Buf<int32_t> &mate, int64_t &n_matched,
-                            ScanPlan<uint32_t> &pairs)
+static rama_status matching(Ctx &ctx, const Graph &g, float tau, int rounds_cap, Buf<int32_t> &mate, int64_t &n_matched)
 {
     const size_t m = (size_t)g.m, n = (size_t)g.n;
     n_matched = 0;
-    pairs.n = 0;
     RAMA_TRY(mate.alloc(ctx, n > 0 ? n : 1));
     RAMA_TRY(fill<int32_t>(ctx, mate.get(), -1, n));
     if (m == 0) return RAMA_OK;
@@ -523,7 +518,8 @@ static rama_status matching(Ctx &ctx, const Graph &g, float tau, int rounds_cap,
         best.swap(best_next);
         na = nn;
     }
-    // number of pairs; the plan is kept for the caller, who lists the pairs with it
+    // number of pairs
+    ScanPlan<uint32_t> pairs;
     RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, n, 0, pairs)));
     RAMA_TRY((scan_totals<uint32_t>(ctx, MatchedLow{mate.get()}, pairs)));
     n_matched = pairs.total;
@@ -746,8 +742,7 @@ rama_status contract_once(Ctx &ctx, const Graph &g, float tau, int rounds_cap, f
 {
     const size_t n = (size_t)g.n;
     Buf<int32_t> mate;
-    ScanPlan<uint32_t> pairs;
-    RAMA_TRY(matching(ctx, g, tau, rounds_cap, mate, n_matched, pairs));
+    RAMA_TRY(matching(ctx, g, tau, rounds_cap, mate, n_matched));
     n_new = g.n;
     if (n_matched == 0) return RAMA_OK;
     Buf<uint32_t> npos;
@@ -758,14 +753,14 @@ rama_status contract_once(Ctx &ctx, const Graph &g, float tau, int rounds_cap, f
         mate.reset();
         RAMA_TRY(forest_set(ctx, g, tau, si, sj, n_matched));
         if (n_matched == 0) return RAMA_OK;
+        RAMA_TRY(components(ctx, n, (size_t)n_matched, si.get(), sj.get(), rep));
     } else {
-        RAMA_TRY(si.alloc(ctx, (size_t)n_matched));
-        RAMA_TRY(sj.alloc(ctx, (size_t)n_matched));
-        RAMA_TRY((scan_emit<uint32_t>(ctx, MatchedLow{mate.get()}, EmitPairs{mate.get(), si.get(), sj.get()}, pairs,
-                                      (double)(n * 4 + (size_t)n_matched * 8))));
+        // the components of a matching are its pairs: the representative (smallest node) is at hand
+        RAMA_TRY(rep.alloc(ctx, n));
+        ProfScope ps_(ctx, "k_pair_rep", (double)(n * 8));
+        k_pair_rep<<<grid_for(n), kBlock, 0, ctx.stream>>>(n, mate.get(), rep.get());
     }
-    const size_t ns = (size_t)n_matched;
-    RAMA_TRY(components(ctx, n, ns, si.get(), sj.get(), rep));
+    LAUNCH_TRY(ctx, "pair_rep");
     RAMA_TRY((exclusive_scan<uint32_t>(ctx, IsRoot{rep.get()}, npos.get(), n)));
     uint32_t nn = 0;
     RAMA_TRY(read_back(ctx, &nn, npos.get() + n, 4));
