@@ -137,13 +137,10 @@ rama_status solve_impl(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const i
     }
     Graph g;
     RAMA_TRY(canonicalise(ctx, n, m, i, j, c, g));
-    Buf<int32_t> f;
-    RAMA_TRY(f.alloc(ctx, (size_t)(n > 0 ? n : 1)));
-    {
-        ProfScope ps_(ctx, "k_iota32", (double)((size_t)n * 4));
-        k_iota32<<<grid_for((size_t)n), kBlock, 0, ctx.stream>>>((size_t)n, f.get());
-    }
-    LAUNCH_TRY(ctx, "iota");
+    // The rounds' node mappings f' are kept and composed at the end, last round first: every
+    // composition then runs over the (shrinking) node set of its own round instead of all n nodes.
+    std::vector<Buf<int32_t>> maps;
+    std::vector<size_t> map_size;
     double lb = 0.0;
     bool have_lb = false;
     int32_t n_cur = n;
@@ -201,11 +198,8 @@ rama_status solve_impl(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const i
         RAMA_TRY(contract_once(ctx, g, P.contract_threshold, P.matching_rounds_cap, P.forest_ratio, fprime, n_new, gn, ns));
         S.rounds = round;
         if (ns > 0) {
-            {
-                ProfScope ps_(ctx, "k_compose", (double)((size_t)n * 12));
-                k_compose<<<grid_for((size_t)n), kBlock, 0, ctx.stream>>>((size_t)n, f.get(), fprime.get());
-            }
-            LAUNCH_TRY(ctx, "compose");
+            maps.push_back(std::move(fprime));
+            map_size.push_back((size_t)n_cur);
             g = std::move(gn);
             n_cur = n_new;
         }
@@ -219,6 +213,21 @@ rama_status solve_impl(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const i
                     (long long)g.m, t1 - t0, t2 - t1, t3 - t2);
         if (ns == 0) break;
     }
+    Buf<int32_t> f;    // original node -> final cluster
+    for (size_t k = maps.size(); k-- > 1;) {
+        ProfScope ps_(ctx, "k_compose", (double)(map_size[k - 1] * 12));
+        k_compose<<<grid_for(map_size[k - 1]), kBlock, 0, ctx.stream>>>(map_size[k - 1], maps[k - 1].get(), maps[k].get());
+    }
+    LAUNCH_TRY(ctx, "compose");
+    if (!maps.empty()) {
+        f = std::move(maps[0]);
+    } else {
+        RAMA_TRY(f.alloc(ctx, (size_t)(n > 0 ? n : 1)));
+        ProfScope ps_(ctx, "k_iota32", (double)((size_t)n * 4));
+        k_iota32<<<grid_for((size_t)n), kBlock, 0, ctx.stream>>>((size_t)n, f.get());
+    }
+    LAUNCH_TRY(ctx, "iota");
+    maps.clear();
     // labels: smallest original node per cluster; primal cost on the caller's costs
     {
         Buf<int32_t> first;
