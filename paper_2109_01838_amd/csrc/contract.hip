@@ -101,27 +101,28 @@ __global__ __launch_bounds__(kBlock) void k_propose(size_t na, Cands a, unsigned
     propose_edge(valid, valid ? a.u[k] : 0, valid ? a.v[k] : 0, valid ? a.r[k] : 0ull, best);
 }
 
-// matched edges fix their endpoints; the rank words the next round will use are cleared for the
-// endpoints of every edge still listed (the two rank arrays alternate between rounds)
-__global__ __launch_bounds__(kBlock) void k_accept(size_t na, Cands a, const unsigned long long *best,
-                                                   unsigned long long *best_next, int32_t *mate)
+// matched edges fix their endpoints
+__global__ __launch_bounds__(kBlock) void k_accept(size_t na, Cands a, const unsigned long long *best, int32_t *mate)
 {
     size_t k = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (k >= na) return;
     const int32_t u = a.u[k], v = a.v[k];
     const unsigned long long r = a.r[k];
     if (best[u] == r && best[v] == r) { mate[u] = v; mate[v] = u; }
-    best_next[u] = 0ull;
-    best_next[v] = 0ull;
 }
 
 // Survivors (both endpoints still free) move to the next list and at once propose for the next
 // round.  Every workgroup compacts 2048 candidates locally and reserves its output range with a
 // single atomicAdd; the order of the ranges varies from run to run, which is harmless: proposals
 // (atomicMax) and the accept test do not depend on the order of the list.
+// Three rank arrays rotate: this round's proposals were read by k_accept, the survivors propose into
+// the second, and they clear their endpoints' words in the third, which takes the proposals of the
+// round after next -- so only survivors pay for clearing, and nobody clears what somebody else
+// is proposing into.
 constexpr int kAdvItems = 8;
 __global__ __launch_bounds__(kBlock) void k_advance(size_t na, Cands a, const int32_t *mate, Cands next,
-                                                    unsigned long long *best_next, uint32_t *counter)
+                                                    unsigned long long *best_next, unsigned long long *best_after,
+                                                    uint32_t *counter)
 {
     __shared__ uint32_t s_base, s_wave[4];
     const int w = threadIdx.x >> 6, lane = lane_id();
@@ -143,7 +144,11 @@ __global__ __launch_bounds__(kBlock) void k_advance(size_t na, Cands a, const in
         const unsigned long long vote = __ballot(ok);
         where[q] = cnt + (uint32_t)__popcll(vote & ((1ull << lane) - 1ull));
         cnt += (uint32_t)__popcll(vote);
-        if (ok) keep |= 1u << q;
+        if (ok) {
+            keep |= 1u << q;
+            best_after[u[q]] = 0ull;
+            best_after[v[q]] = 0ull;
+        }
         propose_edge(ok, u[q], v[q], r[q], best_next);
     }
     if (lane == 0) s_wave[w] = cnt;
@@ -487,9 +492,10 @@ static rama_status matching(Ctx &ctx, const Graph &g, float tau, int rounds_cap,
         RAMA_TRY((scan_emit<uint32_t>(ctx, CandFlag{g.c.get(), tau}, PackCandsEmit{g.i.get(), g.j.get(), g.c.get(), cur}, cand,
                                       (double)((size_t)na * 28))));
     }
-    Buf<unsigned long long> best, best_next;     // rank words of the current and of the next round
+    Buf<unsigned long long> best, best_next, best_after;   // rank words of this round, the next, the one after
     RAMA_TRY(best.alloc(ctx, n));
     RAMA_TRY(best_next.alloc(ctx, n));
+    RAMA_TRY(best_after.alloc(ctx, n));
     RAMA_TRY(fill<unsigned long long>(ctx, best.get(), 0ull, n));
     RAMA_TRY(fill<unsigned long long>(ctx, best_next.get(), 0ull, n));
     Buf<uint32_t> counters;                      // one survivor counter per handshake round
@@ -502,20 +508,21 @@ static rama_status matching(Ctx &ctx, const Graph &g, float tau, int rounds_cap,
     LAUNCH_TRY(ctx, "propose");
     for (int r = 0; r < rounds_cap && na > 0; ++r) {
         {
-            ProfScope ps_(ctx, "k_accept", (double)((size_t)na * 56));
-            k_accept<<<grid_for(na), kBlock, 0, ctx.stream>>>(na, cur, best.get(), best_next.get(), mate.get());
+            ProfScope ps_(ctx, "k_accept", (double)((size_t)na * 40));
+            k_accept<<<grid_for(na), kBlock, 0, ctx.stream>>>(na, cur, best.get(), mate.get());
         }
         LAUNCH_TRY(ctx, "accept");
         {
-            ProfScope ps_(ctx, "k_advance", (double)((size_t)na * 40));
+            ProfScope ps_(ctx, "k_advance", (double)((size_t)na * 56));
             k_advance<<<grid_for(na, kBlock * kAdvItems), kBlock, 0, ctx.stream>>>(
-                na, cur, mate.get(), nxt, best_next.get(), counters.get() + r);
+                na, cur, mate.get(), nxt, best_next.get(), best_after.get(), counters.get() + r);
         }
         LAUNCH_TRY(ctx, "advance");
         uint32_t nn = 0;
         RAMA_TRY(read_back(ctx, &nn, counters.get() + r, 4));
         Cands t = cur; cur = nxt; nxt = t;
-        best.swap(best_next);
+        best.swap(best_next);          // (this, next, after) <- (next, after, this)
+        best_next.swap(best_after);
         na = nn;
     }
     // number of pairs
