@@ -124,23 +124,26 @@ __global__ __launch_bounds__(kBlock) void k_advance(size_t na, Cands a, const in
                                                     unsigned long long *best_next, unsigned long long *best_after,
                                                     uint32_t *counter)
 {
-    __shared__ uint32_t s_base, s_wave[4];
+    __shared__ uint32_t s_base, s_wave[4], s_pairs[4];
     const int w = threadIdx.x >> 6, lane = lane_id();
     const size_t base = (size_t)blockIdx.x * (kBlock * kAdvItems) + (size_t)w * (64 * kAdvItems) + lane;
     int32_t u[kAdvItems], v[kAdvItems];
     unsigned long long r[kAdvItems];
     uint32_t where[kAdvItems];
-    uint32_t keep = 0, cnt = 0;
+    uint32_t keep = 0, cnt = 0, pairs = 0;
 #pragma unroll
     for (int q = 0; q < kAdvItems; ++q) {
         const size_t k = base + (size_t)q * 64;
         u[q] = 0; v[q] = 0; r[q] = 0ull;
-        bool ok = false;
+        bool ok = false, pair = false;
         if (k < na) {
             u[q] = a.u[k]; v[q] = a.v[k];
-            ok = mate[u[q]] < 0 && mate[v[q]] < 0;
+            const int32_t mu = mate[u[q]], mv = mate[v[q]];
+            ok = mu < 0 && mv < 0;
+            pair = mu == v[q];            // this very edge was matched in the round that just ended
             if (ok) r[q] = a.r[k];
         }
+        pairs += (uint32_t)__popcll(__ballot(pair));
         const unsigned long long vote = __ballot(ok);
         where[q] = cnt + (uint32_t)__popcll(vote & ((1ull << lane) - 1ull));
         cnt += (uint32_t)__popcll(vote);
@@ -151,11 +154,13 @@ __global__ __launch_bounds__(kBlock) void k_advance(size_t na, Cands a, const in
         }
         propose_edge(ok, u[q], v[q], r[q], best_next);
     }
-    if (lane == 0) s_wave[w] = cnt;
+    if (lane == 0) { s_wave[w] = cnt; s_pairs[w] = pairs; }
     __syncthreads();
     if (threadIdx.x == 0) {
         const uint32_t total = s_wave[0] + s_wave[1] + s_wave[2] + s_wave[3];
         s_base = total ? atomicAdd(counter, total) : 0u;
+        const uint32_t made = s_pairs[0] + s_pairs[1] + s_pairs[2] + s_pairs[3];
+        if (made) atomicAdd(counter + 1, made);     // counter[1]: pairs made in this handshake round
     }
     __syncthreads();
     uint32_t off = s_base;
@@ -169,13 +174,6 @@ __global__ __launch_bounds__(kBlock) void k_advance(size_t na, Cands a, const in
             next.u[p] = u[q]; next.v[p] = v[q]; next.r[p] = r[q];
         }
 }
-
-struct MatchedLow {
-    static constexpr int bytes = 4;   // bytes read per item
-    static constexpr const char *tag = "MatchedLow";
-    const int32_t *mate;
-    __device__ __forceinline__ uint32_t operator()(size_t v) const { return mate[v] > (int32_t)v ? 1u : 0u; }
-};
 
 __global__ __launch_bounds__(kBlock) void k_pair_rep(size_t n, const int32_t *mate, int32_t *rep)
 {
@@ -498,9 +496,9 @@ static rama_status matching(Ctx &ctx, const Graph &g, float tau, int rounds_cap,
     RAMA_TRY(best_after.alloc(ctx, n));
     RAMA_TRY(fill<unsigned long long>(ctx, best.get(), 0ull, n));
     RAMA_TRY(fill<unsigned long long>(ctx, best_next.get(), 0ull, n));
-    Buf<uint32_t> counters;                      // one survivor counter per handshake round
-    RAMA_TRY(counters.alloc(ctx, (size_t)(rounds_cap > 0 ? rounds_cap : 1)));
-    RAMA_TRY(fill<uint32_t>(ctx, counters.get(), 0u, (size_t)(rounds_cap > 0 ? rounds_cap : 1)));
+    Buf<uint32_t> counters;                      // per handshake round: survivors, pairs made
+    RAMA_TRY(counters.alloc(ctx, (size_t)(rounds_cap > 0 ? 2 * rounds_cap : 2)));
+    RAMA_TRY(fill<uint32_t>(ctx, counters.get(), 0u, (size_t)(rounds_cap > 0 ? 2 * rounds_cap : 2)));
     if (rounds_cap > 0) {
         ProfScope ps_(ctx, "k_propose", (double)((size_t)na * 32));
         k_propose<<<grid_for(na), kBlock, 0, ctx.stream>>>(na, cur, best.get());
@@ -515,21 +513,18 @@ static rama_status matching(Ctx &ctx, const Graph &g, float tau, int rounds_cap,
         {
             ProfScope ps_(ctx, "k_advance", (double)((size_t)na * 56));
             k_advance<<<grid_for(na, kBlock * kAdvItems), kBlock, 0, ctx.stream>>>(
-                na, cur, mate.get(), nxt, best_next.get(), best_after.get(), counters.get() + r);
+                na, cur, mate.get(), nxt, best_next.get(), best_after.get(), counters.get() + 2 * r);
         }
         LAUNCH_TRY(ctx, "advance");
-        uint32_t nn = 0;
-        RAMA_TRY(read_back(ctx, &nn, counters.get() + r, 4));
+        uint32_t back[2] = {0, 0};
+        RAMA_TRY(read_back(ctx, back, counters.get() + 2 * r, 8));
+        const uint32_t nn = back[0];
+        n_matched += back[1];
         Cands t = cur; cur = nxt; nxt = t;
         best.swap(best_next);          // (this, next, after) <- (next, after, this)
         best_next.swap(best_after);
         na = nn;
     }
-    // number of pairs
-    ScanPlan<uint32_t> pairs;
-    RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, n, 0, pairs)));
-    RAMA_TRY((scan_totals<uint32_t>(ctx, MatchedLow{mate.get()}, pairs)));
-    n_matched = pairs.total;
     return RAMA_OK;
 }
 
