@@ -164,14 +164,39 @@ struct EndRow {
 // continues through must also differ from v0 and vL.  Rows are ascending, so every list comes out
 // in path order.  The recursion is over a compile-time depth: it unrolls into nested loops with
 // the path in registers.
+// [r0, r1) is the row of path[K-1]: the level above fetched the bounds while it was still busy with
+// the previous neighbour, so that a level does not start with a load it has to wait for.
 template <int K, int MAXL, typename Emit>
 __device__ __forceinline__ void extend_path(const Adj &g, const EndRow &end, int32_t vl, int max_len,
-                                            int32_t (&path)[MAXL], Emit &emit)
+                                            int32_t (&path)[MAXL], Emit &emit, int32_t r0, int32_t r1)
 {
-    const int32_t tail = path[K - 1];
-    const int32_t r0 = g.ptr[tail], r1 = g.ptr[tail + 1];
+    if (K + 3 > max_len && r1 - r0 <= kShortRow) {
+        // Last level (nothing continues below) and a short row: its entries come in with two 16-byte
+        // loads instead of one dependent load per turn of a loop -- the walk spends most of its time
+        // waiting for exactly these loads.  (The array is padded; entries behind the row's end are skipped.)
+        int32_t row[kShortRow];
+        __builtin_memcpy(row, g.nb + r0, sizeof(row));
+#pragma unroll
+        for (int k = 0; k < kShortRow; ++k) {
+            if (r0 + k < r1) {
+                const int32_t v = row[k];
+                bool inner = false;
+#pragma unroll
+                for (int q = 1; q < K - 1; ++q) inner |= (path[q] == v);
+                if (!inner && end.has(v)) { path[K] = v; emit.template cycle<K + 2>(path); }
+            }
+        }
+        return;
+    }
+    const bool deeper = (K + 3 <= MAXL) && (K + 3 <= max_len);
+    int32_t vn = r0 < r1 ? g.nb[r0] : 0, n0 = 0, n1 = 0;      // the neighbour of the coming turn and its row
+    if (deeper && r0 < r1) { n0 = g.ptr[vn]; n1 = g.ptr[vn + 1]; }
     for (int32_t p = r0; p < r1; ++p) {
-        const int32_t v = g.nb[p];
+        const int32_t v = vn, c0 = n0, c1 = n1;
+        if (p + 1 < r1) {
+            vn = g.nb[p + 1];
+            if (deeper) { n0 = g.ptr[vn]; n1 = g.ptr[vn + 1]; }
+        }
         bool inner = false;
 #pragma unroll
         for (int q = 1; q < K - 1; ++q) inner |= (path[q] == v);
@@ -180,9 +205,16 @@ __device__ __forceinline__ void extend_path(const Adj &g, const EndRow &end, int
         if constexpr (K + 3 <= MAXL) {
             if (K + 3 > max_len || v == vl || v == path[0]) continue;
             path[K] = v;
-            extend_path<K + 1, MAXL>(g, end, vl, max_len, path, emit);
+            extend_path<K + 1, MAXL>(g, end, vl, max_len, path, emit, c0, c1);
         }
     }
+}
+template <int K, int MAXL, typename Emit>
+__device__ __forceinline__ void extend_path(const Adj &g, const EndRow &end, int32_t vl, int max_len,
+                                            int32_t (&path)[MAXL], Emit &emit)
+{
+    const int32_t tail = path[K - 1];
+    extend_path<K, MAXL>(g, end, vl, max_len, path, emit, g.ptr[tail], g.ptr[tail + 1]);
 }
 
 template <int MAXL, typename Emit>
