@@ -22,8 +22,9 @@ class Pool {
 public:
     hipError_t alloc(size_t bytes, void **out)
     {
-        if (bytes == 0) bytes = 256;
-        bytes = (bytes + 255) & ~size_t(255);
+        // every block ends with at least 32 readable bytes of slack: kernels fetch short index rows
+        // with 16-byte loads and may read (never use) up to 28 bytes behind the last element
+        bytes = (bytes + 32 + 255) & ~size_t(255);
         int best = -1;
         for (int k = 0; k < (int)free_.size(); ++k)
             if (free_[k].bytes >= bytes && (best < 0 || free_[k].bytes < free_[best].bytes)) best = k;

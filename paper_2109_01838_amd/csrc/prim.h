@@ -1161,6 +1161,17 @@ struct ReduceRunsEmit {
 __device__ __forceinline__ int32_t find_edge_in_row(const int32_t *rowptr, const int32_t *j, int32_t u, int32_t v)
 {
     int32_t lo = rowptr[u], hi = rowptr[u + 1];
+    if (hi - lo <= 8) {
+        // a short row: eight entries with two 16-byte loads (one wait instead of a chain of probes);
+        // what lies behind the row's end is read but not looked at (device arrays end with slack)
+        int32_t row[8];
+        __builtin_memcpy(row, j + lo, sizeof(row));
+        int32_t pos = -1;
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            if (lo + k < hi && row[k] == v) pos = lo + k;
+        return pos;
+    }
     const int32_t end = hi;
     while (lo < hi) {
         int32_t mid = lo + ((hi - lo) >> 1);
