@@ -82,33 +82,46 @@ struct Adj {
     const int32_t *nb;
 };
 
-// calls f(x) for every x in row a & row b, ascending.  Two short rows are fetched whole -- sixteen
-// independent loads, one memory latency -- and compared in registers; otherwise walk the shorter
-// row and search the longer (a chain of dependent loads, but few rows are long).
+// both rows (at most N entries each) are fetched whole with 16-byte loads -- one wait instead of a
+// chain of dependent probes -- and compared in registers; f is called for the common entries in
+// ascending order.  The array is padded by kWideRow entries; what lies behind a row's end is masked out.
+template <int N, typename F>
+__device__ __forceinline__ void intersect_in_registers(const Adj &g, int32_t a0, int32_t a1, int32_t b0, int32_t b1, F &&f)
+{
+    int32_t ra[N], rb[N];
+    __builtin_memcpy(ra, g.nb + a0, sizeof(ra));
+    __builtin_memcpy(rb, g.nb + b0, sizeof(rb));
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        ra[k] = a0 + k < a1 ? ra[k] : -1;
+        rb[k] = b0 + k < b1 ? rb[k] : -2;
+    }
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        bool hit = false;
+#pragma unroll
+        for (int q = 0; q < N; ++q) hit |= (ra[k] == rb[q]);
+        if (hit) f(ra[k]);
+    }
+}
+
+// calls f(x) for every x in row a & row b, ascending.  Rows of up to kWideRow entries -- nearly all
+// rows of the contracted graphs -- are compared in registers; longer ones: walk the shorter row,
+// bisect the longer (a chain of dependent loads: measured, this fallback used to take half of the
+// triangle search's time when it started at nine entries).
 constexpr int kShortRow = 8;
+constexpr int kWideRow = 16;
 template <typename F>
 __device__ __forceinline__ void intersect_rows(const Adj &g, int32_t a, int32_t b, F &&f)
 {
     int32_t a0 = g.ptr[a], a1 = g.ptr[a + 1], b0 = g.ptr[b], b1 = g.ptr[b + 1];
+    if (a0 == a1 || b0 == b1) return;
     if (a1 - a0 <= kShortRow && b1 - b0 <= kShortRow) {
-        if (a0 == a1 || b0 == b1) return;
-        // eight entries from each row start with two 16-byte loads (the array is padded by eight
-        // entries; what lies behind the row's end is masked out)
-        int32_t ra[kShortRow], rb[kShortRow];
-        __builtin_memcpy(ra, g.nb + a0, sizeof(ra));
-        __builtin_memcpy(rb, g.nb + b0, sizeof(rb));
-#pragma unroll
-        for (int k = 0; k < kShortRow; ++k) {
-            ra[k] = a0 + k < a1 ? ra[k] : -1;
-            rb[k] = b0 + k < b1 ? rb[k] : -2;
-        }
-#pragma unroll
-        for (int k = 0; k < kShortRow; ++k) {
-            bool hit = false;
-#pragma unroll
-            for (int q = 0; q < kShortRow; ++q) hit |= (ra[k] == rb[q]);
-            if (hit) f(ra[k]);
-        }
+        intersect_in_registers<kShortRow>(g, a0, a1, b0, b1, f);
+        return;
+    }
+    if (a1 - a0 <= kWideRow && b1 - b0 <= kWideRow) {
+        intersect_in_registers<kWideRow>(g, a0, a1, b0, b1, f);
         return;
     }
     if (a1 - a0 > b1 - b0) { int32_t t = a0; a0 = b0; b0 = t; t = a1; a1 = b1; b1 = t; }
@@ -610,7 +623,7 @@ rama_status find_cycles(Ctx &ctx, const Graph &g, int max_len, bool shortest_onl
     RAMA_TRY(up_ptr.alloc(ctx, (size_t)n + 1));
     RAMA_TRY(low_ptr.alloc(ctx, (size_t)n + 1));
     RAMA_TRY(rowptr.alloc(ctx, (size_t)n + 1));
-    RAMA_TRY(nb.alloc(ctx, (size_t)2 * mp + kShortRow));   // padded: short rows are read eight entries at a time
+    RAMA_TRY(nb.alloc(ctx, (size_t)2 * mp + kWideRow));   // padded: short rows are read eight entries at a time
     RAMA_TRY((row_bounds<int32_t, int32_t>(ctx, pi.get(), mp, n, up_ptr.get())));
     RAMA_TRY((radix_sort_pairs<uint32_t, uint32_t>(ctx, lkey, lval, mp, bits_for((uint64_t)n))));
     RAMA_TRY((row_bounds<uint32_t, int32_t>(ctx, lkey.get(), mp, n, low_ptr.get())));
