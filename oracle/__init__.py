@@ -6,7 +6,10 @@ this module never imports the product's HIP binding.
 
 Two builds of the same source exist: real=float (decisions taken in the GPU
 path's precision; this is the parity twin) and real=double (used to size the
-floating-point tolerances).
+floating-point tolerances).  With RAMA_ORACLE_SANITIZE=1 in the environment both
+are built with AddressSanitizer + UndefinedBehaviorSanitizer into libraries of
+their own (the process must then have been started with libasan preloaded, see
+tests/test_oracle_sanitized.py).
 """
 from __future__ import annotations
 
@@ -18,9 +21,13 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "rama_oracle.c")
-_LIBS = {"f32": os.path.join(_HERE, "librama_oracle_f32.so"),
-         "f64": os.path.join(_HERE, "librama_oracle_f64.so")}
+SANITIZE = os.environ.get("RAMA_ORACLE_SANITIZE", "0") == "1"
+_SUFFIX = "_san" if SANITIZE else ""
+_LIBS = {"f32": os.path.join(_HERE, f"librama_oracle_f32{_SUFFIX}.so"),
+         "f64": os.path.join(_HERE, f"librama_oracle_f64{_SUFFIX}.so")}
 _CFLAGS = ["-O2", "-ffp-contract=off", "-fno-fast-math", "-std=c11", "-shared", "-fPIC", "-Wall", "-Wextra"]
+if SANITIZE:   # same arithmetic flags; every finding aborts the process
+    _CFLAGS = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer"] + _CFLAGS[1:]
 
 OK, ERR_ARG, ERR_GRAPH, ERR_CAP, ERR_OOM = 0, -1, -2, -3, -4
 MAX_CYCLE_LEN = 7   # longest cycle the C source separates
