@@ -18,8 +18,8 @@
  *     HOST pointers.
  *   - The caller owns every input and output buffer.  Inputs are never modified.  The
  *     library keeps no reference to caller memory after a call returns.  Workspace is
- *     allocated with hipMalloc through the ctx, cached for reuse, and released by
- *     rama_destroy.
+ *     allocated through the ctx -- with the allocator callbacks given to rama_create, else
+ *     with hipMalloc -- cached for reuse, and released by rama_destroy.
  *   - Every call enqueues its kernels on the ctx's stream and synchronises that stream
  *     before it returns (scalar results are on the host when the call returns).
  *   - Any edge list is accepted: either orientation, self-loops (dropped; they can never
@@ -35,6 +35,7 @@
 #ifndef RAMA_H
 #define RAMA_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -52,7 +53,7 @@ typedef enum {
     RAMA_ERR_INVALID_ARG = -1, /* null pointer, negative size, cycle length out of range, ... */
     RAMA_ERR_BAD_GRAPH = -2,   /* endpoint out of range, non-finite cost, a cycle that is not in the graph */
     RAMA_ERR_CAPACITY = -3,    /* a caller buffer is too small (needed sizes are written) or a count reaches 2^31 */
-    RAMA_ERR_OOM = -4,         /* hipMalloc failed */
+    RAMA_ERR_OOM = -4,         /* the workspace allocator (callbacks or hipMalloc) returned no memory */
     RAMA_ERR_HIP = -5          /* any other HIP runtime error */
 } rama_status;
 
@@ -82,13 +83,42 @@ typedef struct {
     int64_t n_edges_aug_first;  /* edges after adding chords, first round */
     int64_t n_edges_final;      /* edges of the last contracted graph */
     double ms_total;            /* wall time of the call */
-    double ms_cycles, ms_dual, ms_contract, ms_other; /* host-clock split by stage; with dual_rounds > 1
-                                   separation and message passing interleave and are both booked as ms_cycles */
+    double ms_cycles, ms_dual, ms_contract, ms_other; /* split by stage: stream time between HIP events recorded at
+                                   the stage boundaries (no extra synchronisation), ms_other = the rest of ms_total; with
+                                   dual_rounds > 1 separation and message passing interleave and are both booked as ms_cycles */
 } rama_stats;
 
+/* One round of the outer loop of rama_solve (all host memory); see rama_round_get. */
+typedef struct {
+    int32_t n_nodes;            /* nodes of the graph the round started from */
+    int32_t used_forest;        /* 1: S came from the spanning forest without conflicts, 0: from the matching */
+    int64_t n_edges;            /* its edges */
+    int64_t n_attractive;       /* edges with c > 0 / c < 0 when the round started; -1 if the round did not separate */
+    int64_t n_repulsive;
+    int64_t n_cycles[RAMA_MAX_CYCLE_LEN - 2]; /* conflicted 3-, 4-, .. cycles separated in this round */
+    int64_t n_triangles;        /* triangles the message passing ran on */
+    int64_t n_edges_aug;        /* edges after adding chords */
+    int64_t n_contracted;       /* |S| */
+    int64_t workspace_peak;     /* largest number of workspace bytes in use at one time during the round */
+    double ms_cycles, ms_dual, ms_contract; /* stream time between stage marks (HIP events) */
+} rama_round_stats;
+
+/* Optional source of device workspace (for instance a framework's caching allocator).  alloc returns
+ * device memory of at least `bytes` bytes, aligned to 256 bytes, on the ctx's device, or NULL when it
+ * has none (the call in progress then ends with RAMA_ERR_OOM and the ctx stays usable); free takes back
+ * a block alloc returned.  Both are called from the thread that calls into the library, only while such
+ * a call runs; blocks are cached by the ctx and go back in rama_destroy (or earlier, when an allocation
+ * fails and the cache is given up before one more attempt). */
+typedef struct {
+    void *(*alloc)(void *user, size_t bytes);
+    void (*free)(void *user, void *ptr);
+    void *user;
+} rama_alloc;
+
 /* Create a context on the current HIP device.  `hip_stream` is a hipStream_t (may be NULL
- * for the default stream) on which all work is enqueued; the caller keeps ownership of it. */
-rama_status rama_create(rama_ctx **out, void *hip_stream);
+ * for the default stream) on which all work is enqueued; the caller keeps ownership of it.
+ * `alloc` (may be NULL: hipMalloc / hipFree) is copied; alloc->alloc must then be non-NULL. */
+rama_status rama_create(rama_ctx **out, void *hip_stream, const rama_alloc *alloc);
 /* Free the workspace and the context.  NULL is allowed. */
 rama_status rama_destroy(rama_ctx *ctx);
 /* Text for the last failure on this ctx; owned by the ctx, valid until the next call. */
@@ -97,6 +127,10 @@ const char *rama_last_error(const rama_ctx *ctx);
 void rama_params_default(rama_params *p);
 /* Bytes of device workspace currently cached by the ctx. */
 int64_t rama_workspace_bytes(const rama_ctx *ctx);
+/* Per-round record of the last rama_solve on this ctx (metrics, not an operation of the paper):
+ * rama_round_count rounds are held, rama_round_get copies round `index` (0-based) to *out. */
+int32_t rama_round_count(const rama_ctx *ctx);
+rama_status rama_round_get(const rama_ctx *ctx, int32_t index, rama_round_stats *out);
 
 /*
  * Measurement hooks (not operations of the paper): per-kernel timers for roofline reports.

@@ -1,5 +1,7 @@
 """Thin ctypes binding of librama_hip.so (include/rama.h).  Argument marshalling only: torch
-supplies device memory and the stream, every step of the method runs inside the library.
+supplies device memory (inputs, outputs and -- through the allocator callbacks of rama_create --
+the library's workspace, which so lives in torch's caching allocator) and the stream; every step
+of the method runs inside the library.
 
 There is no CPU fallback: if the library is missing or no GPU is present the calls raise.
 """
@@ -15,6 +17,7 @@ RAMA_OK, RAMA_ERR_INVALID_ARG, RAMA_ERR_BAD_GRAPH, RAMA_ERR_CAPACITY, RAMA_ERR_O
 
 EXPORTS = [
     "rama_create", "rama_destroy", "rama_last_error", "rama_params_default", "rama_workspace_bytes",
+    "rama_round_count", "rama_round_get",
     "rama_profile_enable", "rama_profile_count", "rama_profile_get", "rama_set_sort_split",
     "rama_find_conflicted_cycles", "rama_message_passing", "rama_dual_rounds", "rama_contract", "rama_solve",
 ]
@@ -42,6 +45,24 @@ class RamaStats(C.Structure):
     ]
 
 
+class RamaRoundStats(C.Structure):
+    _fields_ = [
+        ("n_nodes", C.c_int32), ("used_forest", C.c_int32), ("n_edges", C.c_int64),
+        ("n_attractive", C.c_int64), ("n_repulsive", C.c_int64), ("n_cycles", C.c_int64 * (MAX_CYCLE_LEN - 2)),
+        ("n_triangles", C.c_int64), ("n_edges_aug", C.c_int64), ("n_contracted", C.c_int64),
+        ("workspace_peak", C.c_int64),
+        ("ms_cycles", C.c_double), ("ms_dual", C.c_double), ("ms_contract", C.c_double),
+    ]
+
+
+ALLOC_FN = C.CFUNCTYPE(C.c_void_p, C.c_void_p, C.c_size_t)
+FREE_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_void_p)
+
+
+class RamaAlloc(C.Structure):
+    _fields_ = [("alloc", ALLOC_FN), ("free", FREE_FN), ("user", C.c_void_p)]
+
+
 class RamaError(RuntimeError):
     def __init__(self, status, where, msg):
         super().__init__(f"{where} failed with status {status}: {msg}")
@@ -65,7 +86,10 @@ def load_library():
                            "(or __graft_entry__.build()); there is no CPU fallback")
     lib = C.CDLL(LIB_PATH)
     vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
-    lib.rama_create.argtypes = [C.POINTER(vp), vp]
+    lib.rama_create.argtypes = [C.POINTER(vp), vp, C.POINTER(RamaAlloc)]
+    lib.rama_round_count.argtypes = [vp]
+    lib.rama_round_count.restype = i32
+    lib.rama_round_get.argtypes = [vp, i32, C.POINTER(RamaRoundStats)]
     lib.rama_destroy.argtypes = [vp]
     lib.rama_last_error.argtypes = [vp]
     lib.rama_last_error.restype = C.c_char_p
@@ -90,7 +114,8 @@ def load_library():
     lib.rama_profile_get.argtypes = [vp, i32, C.POINTER(C.c_char_p), C.POINTER(i64), C.POINTER(C.c_double),
                                      C.POINTER(C.c_double)]
     for name in EXPORTS:
-        if name not in ("rama_last_error", "rama_params_default", "rama_workspace_bytes", "rama_profile_count"):
+        if name not in ("rama_last_error", "rama_params_default", "rama_workspace_bytes", "rama_profile_count",
+                        "rama_round_count"):
             getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -115,9 +140,14 @@ def _dev(t, dtype, torch):
 
 
 class Rama:
-    """One library context bound to the current torch device and stream."""
+    """One library context bound to the current torch device and stream.
 
-    def __init__(self, device="cuda:0"):
+    allocator: "torch" (default) -- the library's workspace comes from torch's caching allocator;
+               "hip"             -- the library calls hipMalloc / hipFree itself;
+               (alloc, free)     -- two callables, alloc(nbytes) -> device address (int) or None, free(address)
+    """
+
+    def __init__(self, device="cuda:0", allocator="torch"):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU visible: the HIP path cannot run and there is no CPU fallback")
@@ -127,7 +157,33 @@ class Rama:
         torch.cuda.set_device(self.device)
         self.stream = torch.cuda.current_stream(self.device)
         self.ctx = C.c_void_p()
-        st = self.lib.rama_create(C.byref(self.ctx), C.c_void_p(self.stream.cuda_stream))
+        self._alloc = None
+        if allocator == "torch":
+            dev_index, stream = self.device.index or 0, self.stream
+
+            def t_alloc(nbytes):
+                return torch.cuda.caching_allocator_alloc(int(nbytes), dev_index, stream)
+
+            allocator = (t_alloc, torch.cuda.caching_allocator_delete)
+        if allocator != "hip":
+            py_alloc, py_free = allocator
+
+            def c_alloc(_user, nbytes):     # no exception may cross the C boundary: failure is a null pointer
+                try:
+                    return py_alloc(nbytes) or None
+                except Exception:
+                    return None
+
+            def c_free(_user, ptr):
+                try:
+                    py_free(ptr)
+                except Exception:
+                    pass
+
+            # the callback objects must live as long as the ctx
+            self._alloc = RamaAlloc(ALLOC_FN(c_alloc), FREE_FN(c_free), None)
+        st = self.lib.rama_create(C.byref(self.ctx), C.c_void_p(self.stream.cuda_stream),
+                                  C.byref(self._alloc) if self._alloc is not None else None)
         if st != RAMA_OK:
             raise RamaError(st, "rama_create", "")
 
@@ -161,6 +217,19 @@ class Rama:
 
     def workspace_bytes(self):
         return int(self.lib.rama_workspace_bytes(self.ctx))
+
+    def round_stats(self):
+        """Per-round record of the last solve: sizes, cycles per length, triangles, |S|, stage ms."""
+        out = []
+        for k in range(self.lib.rama_round_count(self.ctx)):
+            r = RamaRoundStats()
+            self._check(self.lib.rama_round_get(self.ctx, k, C.byref(r)), "rama_round_get")
+            out.append(dict(n_nodes=r.n_nodes, n_edges=r.n_edges, n_attractive=r.n_attractive, n_repulsive=r.n_repulsive,
+                            n_cycles=list(r.n_cycles), n_triangles=r.n_triangles, n_edges_aug=r.n_edges_aug,
+                            n_contracted=r.n_contracted, used_forest=bool(r.used_forest),
+                            workspace_peak=r.workspace_peak,
+                            ms=dict(cycles=r.ms_cycles, dual=r.ms_dual, contract=r.ms_contract)))
+        return out
 
     def profile_enable(self, on=True, only=None):
         self._check(self.lib.rama_profile_enable(self.ctx, 1 if on else 0, only.encode() if only else None),

@@ -1,7 +1,6 @@
 // C ABI: argument checks, the four entry points, and the primal-dual loop
 // (paper algorithm "Primal-Dual Multicut").  Host code here only sequences the stage kernels.
 #include <chrono>
-#include <cstdlib>
 
 #include <vector>
 
@@ -121,13 +120,36 @@ rama_status dual_block(Ctx &ctx, Graph &g, int lmax, bool shortest_only, int k, 
     return RAMA_OK;
 }
 
+// stage clock of the solver: marks on the stream (no synchronisation); read when the stream has drained
+struct StageClock {
+    Ctx &ctx;
+    int used = 0;
+    explicit StageClock(Ctx &c) : ctx(c) {}
+    // mark `which` (0: round starts, 1: separation done, 2: message passing done, 3: contraction done) of a round
+    void mark(int round, int which)
+    {
+        const int k = 4 * (round - 1) + which;
+        if (k >= Ctx::kStageEvents || !ctx.stage_ev[k]) return;
+        if (hipEventRecord(ctx.stage_ev[k], ctx.stream) != hipSuccess) { (void)hipGetLastError(); return; }
+        if (k + 1 > used) used = k + 1;
+    }
+    double between(int round, int a, int b) const
+    {
+        const int ka = 4 * (round - 1) + a, kb = 4 * (round - 1) + b;
+        if (kb >= used) return 0.0;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, ctx.stage_ev[ka], ctx.stage_ev[kb]) != hipSuccess) { (void)hipGetLastError(); return 0.0; }
+        return (double)ms;
+    }
+};
+
 rama_status solve_impl(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const int32_t *j, const float *c,
                        const rama_params &P, int32_t *labels, double *primal, double *lower_bound, rama_stats *stats)
 {
     const double t_begin = now_ms();
-    double t_cyc = 0, t_dual = 0, t_con = 0;
     rama_stats S;
     memset(&S, 0, sizeof S);
+    ctx.rounds.clear();
     if (n == 0) {   // no nodes: nothing to label (edges would have been rejected as out of range)
         if (m > 0) return fail(ctx, RAMA_ERR_BAD_GRAPH, "edges given for a graph without nodes");
         if (primal) *primal = 0.0;
@@ -135,6 +157,7 @@ rama_status solve_impl(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const i
         if (stats) *stats = S;
         return RAMA_OK;
     }
+    StageClock clock(ctx);
     Graph g;
     RAMA_TRY(canonicalise(ctx, n, m, i, j, c, g));
     // The rounds' node mappings f' are kept and composed at the end, last round first: every
@@ -144,25 +167,28 @@ rama_status solve_impl(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const i
     double lb = 0.0;
     bool have_lb = false;
     int32_t n_cur = n;
-    const bool trace = getenv("RAMA_TRACE") != nullptr;   // per-round sizes and times on stderr
     for (int round = 1; P.max_rounds <= 0 || round <= P.max_rounds; ++round) {
         const int lmax = round == 1 ? P.max_cycle_len_first : P.max_cycle_len_later;
         const int k = round == 1 ? P.mp_iters_first : P.mp_iters_later;
-        double t0 = now_ms();
-        int64_t cycles_this[kCycleLists] = {};
+        rama_round_stats R;
+        memset(&R, 0, sizeof R);
+        R.n_nodes = n_cur; R.n_edges = g.m; R.n_attractive = -1; R.n_repulsive = -1;
+        ctx.active->reset_peak();
+        clock.mark(round, 0);
         bool ran = false;
         double lbr = 0.0;
         int64_t ntri = 0;
-        double t1 = t0;
+        bool dual_marked = false;
         if (lmax >= 3 && k > 0) {
             if (P.dual_rounds == 1) {
                 CycleLists cyc;
                 RAMA_TRY(find_cycles(ctx, g, lmax, P.shortest_cycles_only != 0, false, cyc));
-                RAMA_TRY(finish(ctx, RAMA_OK));
-                t1 = now_ms();
+                clock.mark(round, 1);
+                dual_marked = true;
+                R.n_attractive = cyc.n_attractive; R.n_repulsive = cyc.n_repulsive;
                 int64_t n_cyc = 0;
                 const int32_t *lists[kCycleLists];
-                for (int q = 0; q < kCycleLists; ++q) { n_cyc += cyc.n[q]; lists[q] = cyc.v[q].get(); cycles_this[q] = cyc.n[q]; }
+                for (int q = 0; q < kCycleLists; ++q) { n_cyc += cyc.n[q]; lists[q] = cyc.v[q].get(); R.n_cycles[q] = cyc.n[q]; }
                 if (n_cyc > 0) {
                     Graph aug;
                     DualInfo info;
@@ -173,29 +199,27 @@ rama_status solve_impl(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const i
                     g = std::move(aug);
                 }
             } else {
+                // separations and message-passing blocks interleave: the stage clock books all as cycles
                 RAMA_TRY(dual_block(ctx, g, lmax, P.shortest_cycles_only != 0, k, P.dual_rounds, round == 1 ? &lbr : nullptr,
-                                    &ran, nullptr, cycles_this, &ntri));
-                RAMA_TRY(finish(ctx, RAMA_OK));
-                t1 = now_ms();   // separations and message-passing blocks interleave: the stage clock books all as cycles
+                                    &ran, nullptr, R.n_cycles, &ntri));
             }
         }
-        t_cyc += t1 - t0;
+        if (!dual_marked) clock.mark(round, 1);
+        R.n_triangles = ntri;
+        R.n_edges_aug = g.m;
         if (round == 1) {
-            for (int q = 0; q < kCycleLists; ++q) S.n_cycles_first[q] = cycles_this[q];
+            for (int q = 0; q < kCycleLists; ++q) S.n_cycles_first[q] = R.n_cycles[q];
             if (ran) { lb = lbr; have_lb = true; S.n_triangles_first = ntri; }
-        }
-        if (round == 1) {
             if (!have_lb) { RAMA_TRY(negative_cost_sum(ctx, g.c.get(), g.m, &lb)); have_lb = true; }
             S.n_edges_aug_first = g.m;
         }
-        RAMA_TRY(finish(ctx, RAMA_OK));
-        double t2 = now_ms();
-        t_dual += t2 - t1;
+        clock.mark(round, 2);
         Buf<int32_t> fprime;
         Graph gn;
         int32_t n_new = n_cur;
         int64_t ns = 0;
-        RAMA_TRY(contract_once(ctx, g, P.contract_threshold, P.matching_rounds_cap, P.forest_ratio, fprime, n_new, gn, ns));
+        bool forest = false;
+        RAMA_TRY(contract_once(ctx, g, P.contract_threshold, P.matching_rounds_cap, P.forest_ratio, fprime, n_new, gn, ns, &forest));
         S.rounds = round;
         if (ns > 0) {
             maps.push_back(std::move(fprime));
@@ -203,14 +227,11 @@ rama_status solve_impl(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const i
             g = std::move(gn);
             n_cur = n_new;
         }
-        RAMA_TRY(finish(ctx, RAMA_OK));
-        const double t3 = now_ms();
-        t_con += t3 - t2;
-        if (trace)
-            fprintf(stderr, "round %2d: cycles %lld/%lld/%lld/%lld/%lld  |S| %lld  -> nodes %d edges %lld   ms: cycles %.3f dual %.3f contract %.3f\n",
-                    round, (long long)cycles_this[0], (long long)cycles_this[1], (long long)cycles_this[2],
-                    (long long)cycles_this[3], (long long)cycles_this[4], (long long)ns, n_cur,
-                    (long long)g.m, t1 - t0, t2 - t1, t3 - t2);
+        clock.mark(round, 3);
+        R.n_contracted = ns;
+        R.used_forest = forest ? 1 : 0;
+        R.workspace_peak = (int64_t)ctx.active->peak_live();
+        ctx.rounds.push_back(R);
         if (ns == 0) break;
     }
     Buf<int32_t> f;    // original node -> final cluster
@@ -257,8 +278,14 @@ rama_status solve_impl(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const i
     S.n_clusters = n_cur;
     S.n_edges_final = g.m;
     S.ms_total = now_ms() - t_begin;
-    S.ms_cycles = t_cyc; S.ms_dual = t_dual; S.ms_contract = t_con;
-    S.ms_other = S.ms_total - t_cyc - t_dual - t_con;
+    for (size_t r = 0; r < ctx.rounds.size(); ++r) {
+        rama_round_stats &R = ctx.rounds[r];
+        R.ms_cycles = clock.between((int)r + 1, 0, 1);
+        R.ms_dual = clock.between((int)r + 1, 1, 2);
+        R.ms_contract = clock.between((int)r + 1, 2, 3);
+        S.ms_cycles += R.ms_cycles; S.ms_dual += R.ms_dual; S.ms_contract += R.ms_contract;
+    }
+    S.ms_other = S.ms_total - S.ms_cycles - S.ms_dual - S.ms_contract;
     if (stats) *stats = S;
     return RAMA_OK;
 }
@@ -267,19 +294,22 @@ rama_status solve_impl(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const i
 
 extern "C" {
 
-rama_status rama_create(rama_ctx **out, void *hip_stream)
+rama_status rama_create(rama_ctx **out, void *hip_stream, const rama_alloc *alloc)
 {
     if (!out) return RAMA_ERR_INVALID_ARG;
     *out = nullptr;
+    if (alloc && !alloc->alloc) return RAMA_ERR_INVALID_ARG;
     rama_ctx *ctx = new (std::nothrow) rama_ctx();
     if (!ctx) return RAMA_ERR_OOM;
     ctx->stream = (hipStream_t)hip_stream;
+    if (alloc) ctx->pool.set_source(alloc->alloc, alloc->free, alloc->user);
     hipError_t e = hipGetDevice(&ctx->device);
     if (e == hipSuccess) e = hipHostMalloc(&ctx->pinned, rama_ctx::kPinnedBytes, hipHostMallocDefault);
+    for (int k = 0; k < rama_ctx::kStageEvents && e == hipSuccess; ++k) e = hipEventCreate(&ctx->stage_ev[k]);
     if (e != hipSuccess) {
         (void)hipGetLastError();
         fprintf(stderr, "rama_create: %s\n", hipGetErrorString(e));
-        delete ctx;
+        rama_destroy(ctx);
         return RAMA_ERR_HIP;
     }
     *out = ctx;
@@ -292,6 +322,8 @@ rama_status rama_destroy(rama_ctx *ctx)
     (void)hipStreamSynchronize(ctx->stream);
     ctx->prof.destroy();
     ctx->pool.destroy();
+    for (hipEvent_t ev : ctx->stage_ev)
+        if (ev) (void)hipEventDestroy(ev);
     if (ctx->pinned) (void)hipHostFree(ctx->pinned);
     delete ctx;
     return RAMA_OK;
@@ -315,6 +347,15 @@ void rama_params_default(rama_params *p)
 }
 
 int64_t rama_workspace_bytes(const rama_ctx *ctx) { return ctx ? (int64_t)ctx->pool.total() : 0; }
+
+int32_t rama_round_count(const rama_ctx *ctx) { return ctx ? (int32_t)ctx->rounds.size() : 0; }
+
+rama_status rama_round_get(const rama_ctx *ctx, int32_t index, rama_round_stats *out)
+{
+    if (!ctx || !out || index < 0 || index >= (int32_t)ctx->rounds.size()) return RAMA_ERR_INVALID_ARG;
+    *out = ctx->rounds[(size_t)index];
+    return RAMA_OK;
+}
 
 rama_status rama_profile_enable(rama_ctx *ctx, int32_t on, const char *only)
 {

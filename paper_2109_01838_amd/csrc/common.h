@@ -18,31 +18,53 @@ constexpr int kBlock = 256;  // threads per workgroup everywhere: four wave64
 
 // Device memory cache.  All work of one ctx is enqueued on one stream, so a block released by
 // an earlier step can be handed to a later step without synchronisation.
+// Blocks come from one of three sources: the caller's allocator callbacks (rama_alloc), hipMalloc,
+// or -- in arena mode -- a fixed piece of device memory that is carved up and never grows.
 class Pool {
 public:
+    // where fresh blocks come from when no cached one fits; both null: hipMalloc / hipFree
+    void set_source(void *(*alloc_fn)(void *, size_t), void (*free_fn)(void *, void *), void *user)
+    {
+        alloc_fn_ = alloc_fn; free_fn_ = free_fn; user_ = user;
+    }
+    // arena mode: every block is a piece of [base, base+bytes); nothing is ever requested from a driver
+    void set_arena(void *base, size_t bytes)
+    {
+        arena_ = (char *)base; arena_bytes_ = bytes;
+        arena_reset();
+    }
+    bool is_arena() const { return arena_ != nullptr; }
+    void arena_reset()
+    {
+        holes_.clear(); used_.clear();
+        if (arena_bytes_ > 0) holes_.push_back({arena_, arena_bytes_});
+        live_ = 0; peak_live_ = 0;
+    }
     hipError_t alloc(size_t bytes, void **out)
     {
         // every block ends with at least 32 readable bytes of slack: kernels fetch short index rows
         // with 16-byte loads and may read (never use) up to 28 bytes behind the last element
         bytes = (bytes + 32 + 255) & ~size_t(255);
+        if (arena_) return arena_alloc(bytes, out);
         int best = -1;
         for (int k = 0; k < (int)free_.size(); ++k)
             if (free_[k].bytes >= bytes && (best < 0 || free_[k].bytes < free_[best].bytes)) best = k;
         if (best >= 0 && free_[best].bytes <= 2 * bytes + (size_t(1) << 20)) {
             *out = free_[best].ptr;
             used_.push_back(free_[best]);
+            went_live(free_[best].bytes);
             free_.erase(free_.begin() + best);
             return hipSuccess;
         }
         void *p = nullptr;
-        hipError_t e = hipMalloc(&p, bytes);
-        if (e != hipSuccess) {  // give cached blocks back to the driver and retry once
-            (void)hipGetLastError();
+        hipError_t e = fresh(&p, bytes);
+        if (e != hipSuccess) {  // give cached blocks back to their source and retry once
             trim();
-            e = hipMalloc(&p, bytes);
+            e = fresh(&p, bytes);
             if (e != hipSuccess) return e;
         }
         total_ += bytes;
+        went_live(bytes);
         used_.push_back({p, bytes});
         *out = p;
         return hipSuccess;
@@ -51,28 +73,88 @@ public:
     {
         for (int k = (int)used_.size() - 1; k >= 0; --k)
             if (used_[k].ptr == p) {
-                free_.push_back(used_[k]);
+                live_ -= used_[k].bytes;
+                if (arena_) arena_release(used_[k]); else free_.push_back(used_[k]);
                 used_.erase(used_.begin() + k);
                 return;
             }
     }
     void trim()
     {
-        for (auto &b : free_) { (void)hipFree(b.ptr); total_ -= b.bytes; }
+        if (arena_) return;
+        for (auto &b : free_) { give_back(b.ptr); total_ -= b.bytes; }
         free_.clear();
     }
     void destroy()
     {
+        if (arena_) { arena_reset(); return; }
         trim();
-        for (auto &b : used_) { (void)hipFree(b.ptr); total_ -= b.bytes; }
+        for (auto &b : used_) { give_back(b.ptr); total_ -= b.bytes; }
         used_.clear();
+        live_ = 0;
     }
-    size_t total() const { return total_; }
+    size_t total() const { return arena_ ? arena_bytes_ : total_; }   // bytes held, cached blocks included
+    size_t live() const { return live_; }                             // bytes handed out right now
+    size_t peak_live() const { return peak_live_; }                   // largest value of live() since reset_peak()
+    void reset_peak() { peak_live_ = live_; }
 
 private:
     struct Blk { void *ptr; size_t bytes; };
-    std::vector<Blk> free_, used_;
-    size_t total_ = 0;
+    void went_live(size_t bytes)
+    {
+        live_ += bytes;
+        if (live_ > peak_live_) peak_live_ = live_;
+    }
+    hipError_t fresh(void **p, size_t bytes)
+    {
+        if (alloc_fn_) {
+            *p = alloc_fn_(user_, bytes);
+            return *p ? hipSuccess : hipErrorOutOfMemory;
+        }
+        hipError_t e = hipMalloc(p, bytes);
+        if (e != hipSuccess) (void)hipGetLastError();
+        return e;
+    }
+    void give_back(void *p)
+    {
+        if (alloc_fn_) { if (free_fn_) free_fn_(user_, p); }
+        else (void)hipFree(p);
+    }
+    // arena: holes_ is sorted by address; first hole that fits is cut from its front
+    hipError_t arena_alloc(size_t bytes, void **out)
+    {
+        for (size_t k = 0; k < holes_.size(); ++k)
+            if (holes_[k].bytes >= bytes) {
+                *out = holes_[k].ptr;
+                used_.push_back({holes_[k].ptr, bytes});
+                if (holes_[k].bytes == bytes) holes_.erase(holes_.begin() + (long)k);
+                else { holes_[k].ptr = (char *)holes_[k].ptr + bytes; holes_[k].bytes -= bytes; }
+                went_live(bytes);
+                return hipSuccess;
+            }
+        return hipErrorOutOfMemory;
+    }
+    void arena_release(const Blk &b)
+    {
+        size_t k = 0;
+        while (k < holes_.size() && holes_[k].ptr < b.ptr) ++k;
+        holes_.insert(holes_.begin() + (long)k, b);
+        if (k + 1 < holes_.size() && (char *)holes_[k].ptr + holes_[k].bytes == holes_[k + 1].ptr) {
+            holes_[k].bytes += holes_[k + 1].bytes;
+            holes_.erase(holes_.begin() + (long)k + 1);
+        }
+        if (k > 0 && (char *)holes_[k - 1].ptr + holes_[k - 1].bytes == holes_[k].ptr) {
+            holes_[k - 1].bytes += holes_[k].bytes;
+            holes_.erase(holes_.begin() + (long)k);
+        }
+    }
+    std::vector<Blk> free_, used_, holes_;
+    size_t total_ = 0, live_ = 0, peak_live_ = 0;
+    void *(*alloc_fn_)(void *, size_t) = nullptr;
+    void (*free_fn_)(void *, void *) = nullptr;
+    void *user_ = nullptr;
+    char *arena_ = nullptr;
+    size_t arena_bytes_ = 0;
 };
 
 // Per-kernel timers: when switched on, every instrumented launch is bracketed by two HIP events
@@ -146,8 +228,13 @@ private:
 struct rama_ctx {
     hipStream_t stream = nullptr;
     int device = 0;
-    rama::Pool pool;
+    rama::Pool pool;                 // the ctx's own cache (caller's allocator or hipMalloc)
+    rama::Pool arena;                // carves up the static scratch array of this device (rama_solve_static)
+    rama::Pool *active = &pool;      // where Buf takes its memory from: `pool`, or `arena` during a call that must not allocate
     rama::Profiler prof;
+    std::vector<rama_round_stats> rounds;   // per-round record of the last rama_solve
+    static constexpr int kStageEvents = 4 * 64;
+    hipEvent_t stage_ev[kStageEvents] = {};  // stage clock of rama_solve: four marks per round, created once
     std::string err;
     void *pinned = nullptr;  // small pinned host block for scalar read-backs
     static constexpr size_t kPinnedBytes = 4096;
@@ -223,17 +310,18 @@ public:
     {
         reset();
         void *p = nullptr;
-        hipError_t e = ctx.pool.alloc(count * sizeof(T), &p);
+        hipError_t e = ctx.active->alloc(count * sizeof(T), &p);
         if (e != hipSuccess) {
             (void)hipGetLastError();
-            return fail(ctx, RAMA_ERR_OOM, "device allocation of " + std::to_string(count * sizeof(T)) + " bytes failed");
+            return fail(ctx, RAMA_ERR_OOM, std::string(ctx.active->is_arena() ? "static scratch exhausted: " : "") +
+                                               "device allocation of " + std::to_string(count * sizeof(T)) + " bytes failed");
         }
-        ctx_ = &ctx; ptr_ = (T *)p; count_ = count;
+        ctx_ = ctx.active; ptr_ = (T *)p; count_ = count;
         return RAMA_OK;
     }
     void reset()
     {
-        if (ptr_) ctx_->pool.release(ptr_);
+        if (ptr_) ctx_->release(ptr_);
         ptr_ = nullptr; count_ = 0; ctx_ = nullptr;
     }
     T *get() const { return ptr_; }
@@ -243,7 +331,7 @@ public:
 
 private:
     void steal(Buf &o) { ctx_ = o.ctx_; ptr_ = o.ptr_; count_ = o.count_; o.ptr_ = nullptr; o.count_ = 0; o.ctx_ = nullptr; }
-    Ctx *ctx_ = nullptr;
+    Pool *ctx_ = nullptr;   // the pool the block came from
     T *ptr_ = nullptr;
     size_t count_ = 0;
 };
@@ -286,6 +374,7 @@ constexpr int kCycleLists = kMaxCycleLen - 2;   // list k holds the (k+3)-cycles
 struct CycleLists {
     int64_t n[kCycleLists] = {};
     Buf<int32_t> v[kCycleLists];  // [L*n[L-3]]
+    int64_t n_attractive = 0, n_repulsive = 0;   // sign split of the searched graph
 };
 
 // ---- stage entry points on canonical device graphs (defined in the stage files) ----
@@ -317,7 +406,7 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
 
 // a4..a6: one primal update.  fmap[n] -> [0,n_new); n_matched = |S|.  If |S|==0 nothing else is produced.
 rama_status contract_once(Ctx &ctx, const Graph &g, float tau, int rounds_cap, float forest_ratio, Buf<int32_t> &fmap,
-                          int32_t &n_new, Graph &out, int64_t &n_matched);
+                          int32_t &n_new, Graph &out, int64_t &n_matched, bool *used_forest = nullptr);
 
 // diagonal of K^T A K for a mapping F on canonical graph g: diag[a] = sum of edges with F(i)=F(j)=a
 rama_status contraction_diagonal(Ctx &ctx, const Graph &g, const int32_t *fmap, int32_t n_new, float *diag);

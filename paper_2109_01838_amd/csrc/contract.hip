@@ -740,9 +740,10 @@ static rama_status contract_edges(Ctx &ctx, const Graph &g, const int32_t *fmap,
 }
 
 rama_status contract_once(Ctx &ctx, const Graph &g, float tau, int rounds_cap, float forest_ratio, Buf<int32_t> &fmap,
-                          int32_t &n_new, Graph &out, int64_t &n_matched)
+                          int32_t &n_new, Graph &out, int64_t &n_matched, bool *used_forest)
 {
     const size_t n = (size_t)g.n;
+    if (used_forest) *used_forest = false;
     Buf<int32_t> mate;
     RAMA_TRY(matching(ctx, g, tau, rounds_cap, mate, n_matched));
     n_new = g.n;
@@ -753,6 +754,7 @@ rama_status contract_once(Ctx &ctx, const Graph &g, float tau, int rounds_cap, f
     // too few pairs: switch to the spanning forest without conflicts (Sec. 3.1, "fewer than 0.1|V|")
     if (forest_ratio > 0.0f && (double)n_matched < (double)forest_ratio * (double)g.n) {
         mate.reset();
+        if (used_forest) *used_forest = true;
         RAMA_TRY(forest_set(ctx, g, tau, si, sj, n_matched));
         if (n_matched == 0) return RAMA_OK;
         RAMA_TRY(components(ctx, n, (size_t)n_matched, si.get(), sj.get(), rep));

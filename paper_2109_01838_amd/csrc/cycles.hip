@@ -279,8 +279,7 @@ struct CountEmit {
     template <int L>
     __device__ __forceinline__ void cycle(const int32_t (&)[MAXL])
     {
-        if constexpr (MAXL > 5) n[L - 3] += (n[L - 3] != 0xffffffffu);   // saturates; the host reports it
-        else ++n[L - 3];
+        n[L - 3] += (n[L - 3] != 0xffffffffu);   // saturates; the host reports it
     }
 };
 
@@ -312,7 +311,7 @@ template <int MAXL>
 __global__ __launch_bounds__(kBlock) void k_count_cycles(size_t nr, const int32_t *ri, const int32_t *rj, Adj g,
                                                          int max_len, int shortest_only,
                                                          ListPtrs<uint32_t, MAXL - 2> cnt, uint32_t *heavy,
-                                                         uint32_t *n_heavy)
+                                                         uint32_t *n_heavy, uint32_t *saturated)
 {
     size_t r = (size_t)blockIdx.x * kBlock + threadIdx.x;
     const bool is_heavy = r < nr && heavy_edge(g, ri[r], max_len);
@@ -339,16 +338,19 @@ __global__ __launch_bounds__(kBlock) void k_count_cycles(size_t nr, const int32_
             if (any) break;
         }
     }
+    bool sat = false;
 #pragma unroll
     for (int k = 0; k < MAXL - 2; ++k)
-        if (k + 3 <= max_len) cnt.p[k][r] = em.n[k];
+        if (k + 3 <= max_len) { cnt.p[k][r] = em.n[k]; sat |= (em.n[k] == 0xffffffffu); }
+    if (sat) *saturated = 1u;   // a count that reached 2^32-1 may have lost cycles: the host turns this into an error
 }
 
 // counts of the listed heavy edges: a wave per edge, lane l takes the first hops l, l+64, ...
 template <int MAXL>
 __global__ __launch_bounds__(kBlock) void k_count_cycles_heavy(const uint32_t *heavy, const uint32_t *n_heavy,
                                                                const int32_t *ri, const int32_t *rj, Adj g, int max_len,
-                                                               int shortest_only, ListPtrs<uint32_t, MAXL - 2> cnt)
+                                                               int shortest_only, ListPtrs<uint32_t, MAXL - 2> cnt,
+                                                               uint32_t *saturated)
 {
     const uint32_t nh = *n_heavy;
     const int lane = (int)(threadIdx.x & 63);
@@ -375,7 +377,10 @@ __global__ __launch_bounds__(kBlock) void k_count_cycles_heavy(const uint32_t *h
         if (lane == 0) {
 #pragma unroll
             for (int k = 0; k < MAXL - 2; ++k)
-                if (k + 3 <= max_len) cnt.p[k][r] = tot[k] > 0xffffffffull ? 0xffffffffu : (uint32_t)tot[k];
+                if (k + 3 <= max_len) {
+                    cnt.p[k][r] = tot[k] >= 0xffffffffull ? 0xffffffffu : (uint32_t)tot[k];
+                    if (tot[k] >= 0xffffffffull) *saturated = 1u;
+                }
         }
     }
 }
@@ -406,18 +411,13 @@ struct CollectHitsEmit {
     }
 };
 
-// a count that saturated: flag[0] = 1
-template <int MAXL>
-__global__ __launch_bounds__(kBlock) void k_check_saturated(size_t nr, ListPtrs<uint32_t, MAXL - 2> cnt, int lists,
-                                                            int32_t *flag)
+// the list totals (last entry of every offset array) and the saturation flag, side by side for one read-back
+template <int NL>
+__global__ void k_cycle_totals(ListPtrs<uint64_t, NL> off, size_t mr, int lists, const uint32_t *saturated, uint64_t *summary)
 {
-    size_t r = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    if (r >= nr) return;
-    bool sat = false;
-#pragma unroll
-    for (int k = 0; k < MAXL - 2; ++k)
-        if (k < lists) sat |= (cnt.p[k][r] == 0xffffffffu);
-    if (sat) *flag = 1;
+    const int k = (int)threadIdx.x;
+    if (k < lists) summary[k] = off.p[k][mr];
+    if (k == NL) summary[NL] = *saturated;
 }
 
 // second walk, only over the repulsive edges that have cycles and only as deep as their
@@ -519,39 +519,34 @@ rama_status count_and_fill(Ctx &ctx, size_t mr, const int32_t *ri, const int32_t
     // heavy edges (only possible for max_len >= 4): listed by the first kernel, counted by the second,
     // which ends at once when the list is empty
     const bool may_be_heavy = max_len >= 4;
-    Buf<uint32_t> heavy, n_heavy;
+    Buf<uint32_t> heavy, n_heavy;   // n_heavy[0]: length of the heavy list, n_heavy[1]: a count saturated
     RAMA_TRY(heavy.alloc(ctx, may_be_heavy ? mr : 1));
-    RAMA_TRY(n_heavy.alloc(ctx, 1));
-    RAMA_TRY(fill<uint32_t>(ctx, n_heavy.get(), 0u, 1));
+    RAMA_TRY(n_heavy.alloc(ctx, 2));
+    RAMA_TRY(fill<uint32_t>(ctx, n_heavy.get(), 0u, 2));
     {
         ProfScope ps_(ctx, MAXL == 3 ? "k_count_cycles<3>" : MAXL == 5 ? "k_count_cycles<5>" : "k_count_cycles<7>", (double)(mr * (8 + 4 * (size_t)lists) + ((size_t)n + 1) * 4 + mp * 8));
         k_count_cycles<MAXL><<<grid_for(mr), kBlock, 0, ctx.stream>>>(mr, ri, rj, adj, max_len, shortest_only ? 1 : 0, cp,
-                                                                     heavy.get(), n_heavy.get());
+                                                                     heavy.get(), n_heavy.get(), n_heavy.get() + 1);
     }
     LAUNCH_TRY(ctx, "count_cycles");
     if (may_be_heavy) {
         ProfScope ps_(ctx, "k_count_cycles_heavy", 0.0);
         k_count_cycles_heavy<MAXL><<<kHeavyGroups, kBlock, 0, ctx.stream>>>(heavy.get(), n_heavy.get(), ri, rj, adj, max_len,
-                                                                          shortest_only ? 1 : 0, cp);
+                                                                          shortest_only ? 1 : 0, cp, n_heavy.get() + 1);
         LAUNCH_TRY(ctx, "count_cycles_heavy");
     }
-    if (MAXL > 5) {
-        Buf<int32_t> flag;
-        RAMA_TRY(flag.alloc(ctx, 1));
-        RAMA_TRY(fill<int32_t>(ctx, flag.get(), 0, 1));
-        {
-            ProfScope ps_(ctx, "k_check_saturated", (double)(mr * 4 * (size_t)lists));
-            k_check_saturated<MAXL><<<grid_for(mr), kBlock, 0, ctx.stream>>>(mr, cp, lists, flag.get());
-        }
-        LAUNCH_TRY(ctx, "check_saturated");
-        int32_t sat = 0;
-        RAMA_TRY(read_back(ctx, &sat, flag.get(), 4));
-        if (sat) return fail(ctx, RAMA_ERR_CAPACITY, "a repulsive edge closes 2^32 or more cycles of one length");
-    }
-    uint64_t tot[NL], all = 0;
-    for (int k = 0; k < lists; ++k) {
+    uint64_t tot[NL + 1], all = 0;
+    for (int k = 0; k < lists; ++k)
         RAMA_TRY((exclusive_scan<uint64_t>(ctx, PtrInput<uint32_t>{cnt[k].get()}, off[k].get(), mr)));
-        RAMA_TRY(read_back(ctx, &tot[k], off[k].get() + mr, 8));
+    {
+        Buf<uint64_t> summary;
+        RAMA_TRY(summary.alloc(ctx, NL + 1));
+        k_cycle_totals<NL><<<1, 64, 0, ctx.stream>>>(op, mr, lists, n_heavy.get() + 1, summary.get());
+        LAUNCH_TRY(ctx, "cycle_totals");
+        RAMA_TRY(read_back(ctx, tot, summary.get(), sizeof(tot)));
+    }
+    if (tot[NL]) return fail(ctx, RAMA_ERR_CAPACITY, "a repulsive edge closes 2^32 - 1 or more cycles of one length");
+    for (int k = 0; k < lists; ++k) {
         out.n[k] = (int64_t)tot[k];
         all += tot[k];
     }
@@ -595,6 +590,7 @@ rama_status count_and_fill(Ctx &ctx, size_t mr, const int32_t *ri, const int32_t
 rama_status find_cycles(Ctx &ctx, const Graph &g, int max_len, bool shortest_only, bool count_only, CycleLists &out)
 {
     for (int k = 0; k < kCycleLists; ++k) { out.n[k] = 0; out.v[k].reset(); }
+    out.n_attractive = 0; out.n_repulsive = 0;
     const size_t m = (size_t)g.m;
     if (m == 0 || max_len < 3) return RAMA_OK;
     if (max_len > kMaxCycleLen) return fail(ctx, RAMA_ERR_INVALID_ARG, "cycle length beyond the supported maximum");
@@ -603,6 +599,7 @@ rama_status find_cycles(Ctx &ctx, const Graph &g, int max_len, bool shortest_onl
     RAMA_TRY((scan_plan_alloc<uint64_t>(ctx, m, 0, signs)));
     RAMA_TRY((scan_totals<uint64_t>(ctx, SignFlags{g.c.get()}, signs)));
     const uint32_t mp = (uint32_t)signs.total, mr = (uint32_t)(signs.total >> 32);
+    out.n_attractive = mp; out.n_repulsive = mr;
     if (mp == 0 || mr == 0) return RAMA_OK;
     if ((uint64_t)2 * mp >= (uint64_t(1) << 31)) return fail(ctx, RAMA_ERR_CAPACITY, "positive adjacency reaches 2^31 entries");
     Buf<int32_t> pi, pj, ri, rj;

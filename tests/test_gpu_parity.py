@@ -634,3 +634,81 @@ def test_context_on_a_side_stream_and_two_contexts(rama):
     want = rama.find_conflicted_cycles(n, g["i"], g["j"], g["c"], 5)
     assert all(np.array_equal(np_(x), np_(y)) for x, y in zip(cyc, want))
     other.close()
+
+
+# --------------------------------------------------------------------------------------------
+# workspace allocator callbacks and per-round records
+# --------------------------------------------------------------------------------------------
+def test_allocator_callbacks_and_injected_out_of_memory(rama):
+    """The workspace comes from the caller's allocator; an allocator that runs dry at its n-th call makes the
+    call in progress end with RAMA_ERR_OOM, everything taken so far goes back, and the ctx stays usable."""
+    import torch
+    from paper_2109_01838_amd import Rama, RamaError, binding
+    g = CASES["grid3d_24"]
+    n = g["n_nodes"]
+    base = rama.solve(n, g["i"], g["j"], g["c"])
+    live, calls, fail_from = {}, [0], [None]
+
+    def alloc(nbytes):
+        calls[0] += 1
+        if fail_from[0] is not None and calls[0] >= fail_from[0]:
+            return None
+        p = torch.cuda.caching_allocator_alloc(int(nbytes), 0)
+        live[p] = nbytes
+        return p
+
+    def free(ptr):
+        assert ptr in live
+        del live[ptr]
+        torch.cuda.caching_allocator_delete(ptr)
+
+    r = Rama("cuda:0", allocator=(alloc, free))
+    a = r.solve(n, g["i"], g["j"], g["c"])
+    assert np.array_equal(np_(a["labels"]), np_(base["labels"])) and a["primal"] == base["primal"]
+    total_calls = calls[0]
+    assert total_calls > 5 and len(live) > 0 and sum(live.values()) == r.workspace_bytes()
+    r.close()
+    assert not live                                  # every block went back through the callback
+    for k in (1, 3, total_calls // 2, total_calls - 1):
+        r = Rama("cuda:0", allocator=(alloc, free))
+        calls[0], fail_from[0] = 0, k
+        with pytest.raises(RamaError) as ei:
+            r.solve(n, g["i"], g["j"], g["c"])
+        assert ei.value.status == binding.RAMA_ERR_OOM, ei.value
+        assert sum(live.values()) == r.workspace_bytes()   # what was in use at the failure is cached, nothing is lost
+        fail_from[0] = None
+        b = r.solve(n, g["i"], g["j"], g["c"])       # same ctx, allocator working again
+        assert np.array_equal(np_(b["labels"]), np_(base["labels"])) and b["lower_bound"] == base["lower_bound"]
+        r.close()
+        assert not live
+    # the library's own hipMalloc path still exists
+    r = Rama("cuda:0", allocator="hip")
+    c = r.solve(n, g["i"], g["j"], g["c"])
+    assert np.array_equal(np_(c["labels"]), np_(base["labels"]))
+    r.close()
+
+
+def test_round_records(rama, oracle32):
+    g = CASES["knn_20000"]
+    n = g["n_nodes"]
+    got = rama.solve(n, g["i"], g["j"], g["c"])
+    rounds = rama.round_stats()
+    assert len(rounds) == got["rounds"] >= 2
+    ic, jc, cc = oracle32.canonicalise(n, g["i"], g["j"], g["c"])
+    first = rounds[0]
+    assert first["n_nodes"] == n and first["n_edges"] == ic.size
+    assert first["n_attractive"] == int((cc > 0).sum()) and first["n_repulsive"] == int((cc < 0).sum())
+    assert first["n_cycles"] == got["n_cycles_first"] and first["n_triangles"] == got["n_triangles_first"]
+    assert first["n_edges_aug"] == got["n_edges_aug_first"]
+    want = oracle32.find_conflicted_cycles(n, g["i"], g["j"], g["c"], 5)
+    assert first["n_cycles"][:3] == [w.shape[0] for w in want]
+    for a, b in zip(rounds, rounds[1:]):
+        assert b["n_nodes"] < a["n_nodes"]
+        assert a["n_contracted"] > 0 and b["n_edges"] <= a["n_edges_aug"]
+        if not a["used_forest"]:
+            assert b["n_nodes"] == a["n_nodes"] - a["n_contracted"]     # a matching joins pairs
+    assert rounds[-1]["n_contracted"] == 0
+    assert all(r["workspace_peak"] > 0 for r in rounds)
+    assert all(r["ms"]["cycles"] >= 0 and r["ms"]["dual"] >= 0 and r["ms"]["contract"] > 0 for r in rounds)
+    s = got["ms"]
+    assert abs(sum(r["ms"]["contract"] for r in rounds) - s["contract"]) < 1e-6 and s["total"] > s["contract"]

@@ -43,7 +43,9 @@ def test_binding_structs_match_the_header(tmp_path):
     from paper_2109_01838_amd import binding
     lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "rama.h"', 'int main(void) {',
              'printf("%d\\n", RAMA_MAX_CYCLE_LEN);']
-    for cname, cls in (("rama_params", binding.RamaParams), ("rama_stats", binding.RamaStats)):
+    classes = (("rama_params", binding.RamaParams), ("rama_stats", binding.RamaStats),
+               ("rama_round_stats", binding.RamaRoundStats), ("rama_alloc", binding.RamaAlloc))
+    for cname, cls in classes:
         lines.append(f'printf("%zu\\n", sizeof({cname}));')
         for field, _ in cls._fields_:
             lines.append(f'printf("%zu\\n", offsetof({cname}, {field}));')
@@ -54,7 +56,7 @@ def test_binding_structs_match_the_header(tmp_path):
     subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), "-o", str(exe), str(src)], check=True)
     got = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
     want = [binding.MAX_CYCLE_LEN]
-    for cls in (binding.RamaParams, binding.RamaStats):
+    for _, cls in classes:
         want.append(C.sizeof(cls))
         want += [getattr(cls, field).offset for field, _ in cls._fields_]
     assert got == want
