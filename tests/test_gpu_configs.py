@@ -1,11 +1,14 @@
-"""End-to-end parity on the named configurations the oracle can still solve (cfg2: 512x512 grid
+"""End-to-end parity on the named configurations (cfg2: 512x512 grid
 with long-range edges, 1.56e6 edges; cfg3: 1e6-point 6-NN graph, ~3.5e6 edges) at their full
 sizes, and on a 110^3 cube of cfg5's recipe (3.96e6 edges), the smallest of these on which the
 long sorts of both key widths take the split path (top-bit passes + in-LDS sort) by themselves: primal within 0.5 %, lower bound within 1e-4 relative, and -- because both sides order
-their arithmetic identically -- in practice identical labels."""
+their arithmetic identically -- in practice identical labels.  cfg4 (256x256x128 grid, 2.5e7 edges)
+takes the oracle minutes, so its result is stored (tests/golden/cfg4_oracle.json, written by the oracle
+alone) and compared here; cfg5 is compared the same way in test_gpu_fullsize.py."""
 import numpy as np
 import pytest
 
+import golden_check
 from paper_2109_01838_amd import inputs
 
 pytestmark = pytest.mark.gpu
@@ -41,3 +44,12 @@ def test_named_config_end_to_end(rama, oracle32, name):
     assert got["lower_bound"] <= got["primal"]
     print(name, "labels identical:", bool(np.array_equal(labels, want["labels"])), "rounds", got["rounds"], want["rounds"],
           "primal", got["primal"], want["primal"])
+
+
+@pytest.mark.timeout(900)
+def test_cfg4_end_to_end_against_stored_oracle_result(rama, oracle32):
+    g = inputs.cfg4()
+    got = rama.solve(g["n_nodes"], g["i"], g["j"], g["c"])
+    golden_check.check_against_golden("cfg4", g, got)
+    labels = got["labels"].cpu().numpy()
+    assert abs(oracle32.multicut_cost(g["i"], g["j"], g["c"], labels) - got["primal"]) <= 1e-6 * abs(got["primal"])
