@@ -280,6 +280,27 @@ rama_status rama_solve(rama_ctx *ctx, int32_t n_nodes, int64_t n_edges,
                        const int32_t *i, const int32_t *j, const float *c, const rama_params *params,
                        int32_t *labels, double *primal_cost, double *lower_bound, rama_stats *stats);
 
+/*
+ * rama_solve for callers that cannot allocate device memory while they run -- code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same result (bit for
+ * bit) as rama_solve, but every byte of device workspace is taken from a static array of
+ * RAMA_STATIC_SCRATCH_BYTES that the library holds on each GPU it runs on from load time to process end,
+ * and the call itself calls no hipMalloc / hipFree, no allocator callback and no allocating library routine.
+ *
+ * Limits: n_nodes <= RAMA_STATIC_MAX_NODES and n_edges <= RAMA_STATIC_MAX_EDGES, else RAMA_ERR_CAPACITY
+ * (nothing is run).  How much workspace a graph inside these limits needs depends on how many conflicted
+ * cycles it has; if the array does not suffice the call returns RAMA_ERR_OOM ("static scratch exhausted").
+ * All calls on one GPU, from any ctx, share that GPU's array: calls that overlap in time on one GPU race.
+ * Nothing is kept in the array between calls.  Per-kernel timers (rama_profile_enable) are not collected
+ * during this call.
+ */
+#define RAMA_STATIC_SCRATCH_BYTES (64u << 20)
+#define RAMA_STATIC_MAX_NODES (1 << 17)
+#define RAMA_STATIC_MAX_EDGES (1 << 18)
+rama_status rama_solve_static(rama_ctx *ctx, int32_t n_nodes, int64_t n_edges,
+                              const int32_t *i, const int32_t *j, const float *c, const rama_params *params,
+                              int32_t *labels, double *primal_cost, double *lower_bound, rama_stats *stats);
+
 #ifdef __cplusplus
 }
 #endif

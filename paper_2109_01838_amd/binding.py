@@ -20,7 +20,9 @@ EXPORTS = [
     "rama_round_count", "rama_round_get",
     "rama_profile_enable", "rama_profile_count", "rama_profile_get", "rama_set_sort_split",
     "rama_find_conflicted_cycles", "rama_message_passing", "rama_dual_rounds", "rama_contract", "rama_solve",
+    "rama_solve_static",
 ]
+STATIC_MAX_NODES, STATIC_MAX_EDGES = 1 << 17, 1 << 18   # RAMA_STATIC_MAX_* of include/rama.h
 
 
 MAX_CYCLE_LEN = 7   # RAMA_MAX_CYCLE_LEN of include/rama.h
@@ -107,6 +109,7 @@ def load_library():
                                   C.POINTER(i32), C.POINTER(i64)]
     lib.rama_solve.argtypes = [vp, i32, i64, vp, vp, vp, C.POINTER(RamaParams), vp, C.POINTER(C.c_double),
                                C.POINTER(C.c_double), C.POINTER(RamaStats)]
+    lib.rama_solve_static.argtypes = lib.rama_solve.argtypes
     lib.rama_profile_enable.argtypes = [vp, i32, C.c_char_p]
     lib.rama_set_sort_split.argtypes = [vp, i64, i32]
     lib.rama_profile_count.argtypes = [vp]
@@ -333,16 +336,20 @@ class Rama:
         return dict(mapping=mapping[:n_nodes], i=io[:k], j=jo[:k], c=co[:k],
                     diag=diag[: nn.value] if want_diag else None, n_nodes=nn.value)
 
-    def solve(self, n_nodes, i, j, c, params=None):
+    def solve(self, n_nodes, i, j, c, params=None, static=False, labels=None):
+        """static=True: rama_solve_static (workspace from the library's static device array, no allocation
+        inside the call; the caller may hand in the labels tensor so that this wrapper allocates nothing either)."""
         t = self.torch
         i, j, c = self._graph(i, j, c)
         params = params or default_params()
-        labels = self._empty(n_nodes, t.int32)
+        if labels is None:
+            labels = self._empty(n_nodes, t.int32)
         primal, lb = C.c_double(0.0), C.c_double(0.0)
         stats = RamaStats()
-        st = self.lib.rama_solve(self.ctx, n_nodes, i.numel(), i.data_ptr(), j.data_ptr(), c.data_ptr(),
-                                 C.byref(params), labels.data_ptr(), C.byref(primal), C.byref(lb), C.byref(stats))
-        self._check(st, "rama_solve")
+        fn, name = (self.lib.rama_solve_static, "rama_solve_static") if static else (self.lib.rama_solve, "rama_solve")
+        st = fn(self.ctx, n_nodes, i.numel(), i.data_ptr(), j.data_ptr(), c.data_ptr(),
+                C.byref(params), labels.data_ptr(), C.byref(primal), C.byref(lb), C.byref(stats))
+        self._check(st, name)
         return dict(labels=labels[:n_nodes], primal=primal.value, lower_bound=lb.value,
                     rounds=stats.rounds, n_clusters=stats.n_clusters,
                     n_cycles_first=list(stats.n_cycles_first), n_triangles_first=stats.n_triangles_first,

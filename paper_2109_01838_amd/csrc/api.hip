@@ -8,6 +8,15 @@
 
 using namespace rama;
 
+// Workspace of rama_solve_static: device memory that exists from the moment the library is loaded, so
+// that the call never has to ask anybody for memory.  In host code the array's name is only a handle;
+// its device address is looked up once per device (rama_create) and kept in g_scratch_ptr.
+static __device__ __align__(256) unsigned char scratch[RAMA_STATIC_SCRATCH_BYTES];
+namespace {
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices] = {};
+}  // namespace
+
 namespace {
 
 double now_ms()
@@ -306,6 +315,15 @@ rama_status rama_create(rama_ctx **out, void *hip_stream, const rama_alloc *allo
     hipError_t e = hipGetDevice(&ctx->device);
     if (e == hipSuccess) e = hipHostMalloc(&ctx->pinned, rama_ctx::kPinnedBytes, hipHostMallocDefault);
     for (int k = 0; k < rama_ctx::kStageEvents && e == hipSuccess; ++k) e = hipEventCreate(&ctx->stage_ev[k]);
+    if (e == hipSuccess && ctx->device >= 0 && ctx->device < kMaxDevices) {
+        // every GPU holds its own copy of the static scratch array at its own address
+        if (!g_scratch_ptr[ctx->device]) {
+            void *p = nullptr;
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e == hipSuccess) g_scratch_ptr[ctx->device] = p;
+        }
+        if (e == hipSuccess) ctx->arena.set_arena(g_scratch_ptr[ctx->device], RAMA_STATIC_SCRATCH_BYTES);
+    }
     if (e != hipSuccess) {
         (void)hipGetLastError();
         fprintf(stderr, "rama_create: %s\n", hipGetErrorString(e));
@@ -551,6 +569,34 @@ rama_status rama_solve(rama_ctx *ctx, int32_t n_nodes, int64_t n_edges, const in
         return fail(*ctx, RAMA_ERR_INVALID_ARG, "rama_solve: cycle length beyond RAMA_MAX_CYCLE_LEN");
     if (params->dual_rounds < 1) return fail(*ctx, RAMA_ERR_INVALID_ARG, "rama_solve: dual_rounds must be at least 1");
     return finish(*ctx, solve_impl(*ctx, n_nodes, n_edges, i, j, c, *params, labels, primal_cost, lower_bound, stats));
+}
+
+rama_status rama_solve_static(rama_ctx *ctx, int32_t n_nodes, int64_t n_edges, const int32_t *i, const int32_t *j,
+                              const float *c, const rama_params *params, int32_t *labels, double *primal_cost,
+                              double *lower_bound, rama_stats *stats)
+{
+    if (!ctx) return RAMA_ERR_INVALID_ARG;
+    if (bad_graph_args(n_nodes, n_edges, i, j, c) || !params || (n_nodes > 0 && !labels))
+        return fail(*ctx, RAMA_ERR_INVALID_ARG, "rama_solve_static: bad arguments");
+    if (params->max_cycle_len_first > RAMA_MAX_CYCLE_LEN || params->max_cycle_len_later > RAMA_MAX_CYCLE_LEN)
+        return fail(*ctx, RAMA_ERR_INVALID_ARG, "rama_solve_static: cycle length beyond RAMA_MAX_CYCLE_LEN");
+    if (params->dual_rounds < 1) return fail(*ctx, RAMA_ERR_INVALID_ARG, "rama_solve_static: dual_rounds must be at least 1");
+    if (n_nodes > RAMA_STATIC_MAX_NODES || n_edges > RAMA_STATIC_MAX_EDGES)
+        return fail(*ctx, RAMA_ERR_CAPACITY,
+                    "rama_solve_static: at most " + std::to_string(RAMA_STATIC_MAX_NODES) + " nodes and " +
+                        std::to_string(RAMA_STATIC_MAX_EDGES) + " edges (got " + std::to_string(n_nodes) + " and " +
+                        std::to_string(n_edges) + "); use rama_solve");
+    if (!ctx->arena.is_arena()) return fail(*ctx, RAMA_ERR_HIP, "rama_solve_static: no static scratch on this device");
+    // every Buf of the solve now comes out of the static array; the per-kernel timers (they create events) stay off
+    const bool prof_was_on = ctx->prof.on;
+    ctx->prof.on = false;
+    ctx->arena.arena_reset();
+    ctx->active = &ctx->arena;
+    rama_status st = finish(*ctx, solve_impl(*ctx, n_nodes, n_edges, i, j, c, *params, labels, primal_cost, lower_bound, stats));
+    ctx->active = &ctx->pool;
+    ctx->arena.arena_reset();
+    ctx->prof.on = prof_was_on;
+    return st;
 }
 
 }  // extern "C"
