@@ -63,6 +63,8 @@ def main():
                     help="per repulsive edge separate only its shortest conflicted cycles")
     ap.add_argument("--dual-rounds", type=int, default=1,
                     help="separation + message-passing blocks per round on the same graph (default 1: the paper's loop)")
+    ap.add_argument("--cycle-search", type=int, default=0, choices=[0, 1, 2, 3],
+                    help="cycles of length 4-5: 0 = default choice, 1 = plain per-thread walk, 2 = cooperative search, 3 = walk whose last level closes from the far endpoint")
     ap.add_argument("--kernels", type=int, default=16, help="how many kernels the per-kernel table lists")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain 1 GiB device copy three times (reference reading for rocprofv3 --pmc "
@@ -80,6 +82,7 @@ def main():
     dev = torch.device("cuda:0")
     i, j, c = (torch.as_tensor(g[k]).to(dev) for k in ("i", "j", "c"))
     rama = Rama("cuda:0")
+    rama.set_cycle_search(args.cycle_search)
     plain = args.cycle_len == [5, 3] and not args.shortest_only and args.dual_rounds == 1
     solver_name = ("PD" if plain else "PD variant") + \
         f" (cycles<={args.cycle_len[0]} then <={args.cycle_len[1]}" + (", shortest only" if args.shortest_only else "") + \

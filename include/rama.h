@@ -156,6 +156,20 @@ rama_status rama_profile_get(const rama_ctx *ctx, int32_t index, const char **na
 rama_status rama_set_sort_split(rama_ctx *ctx, int64_t n_min, int32_t min_passes_replaced);
 
 /*
+ * Tuning hook (not an operation of the paper).  Three searches produce the same cycle lists:
+ *   1  the walk: one thread per repulsive edge (v0,vL) walks v0 -> v1 -> v2 -> .. over attractive edges and
+ *      tests every node it reaches against N+(vL); its last level fetches one row per path;
+ *   3  the same walk, but its last level closes from vL's side as in the appendix algorithm "Parallel Conf.
+ *      5-Cycles" (pairs (v1,v3) of N+(v0) x N+(vL) meeting in a common neighbour): the rows of N+(vL)'s
+ *      entries are fetched once per repulsive edge and held in registers (rows of up to 8 entries);
+ *   2  the cooperative search for lengths 4 and 5: sixteen lanes per repulsive edge, N+(v0), N+(vL) and
+ *      the rows of N+(vL)'s entries staged in LDS (rows of up to 16 entries; edges with longer rows are
+ *      walked as in 3), hits placed by ballots and prefix sums over the sixteen lanes.
+ * mode 0 (default) chooses between 2 and 3 from the sizes of the graph.
+ */
+rama_status rama_set_cycle_search(rama_ctx *ctx, int32_t mode);
+
+/*
  * Conflicted-cycle separation (Sec. 3.2.2, definition "Conflicted cycles", and the appendix
  * algorithm "Parallel Conf. 5-Cycles"): every simple cycle of length L in {3,..,max_cycle_len}
  * with exactly one repulsive edge and L-1 attractive edges.  The paper separates up to length 5

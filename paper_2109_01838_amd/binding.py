@@ -18,7 +18,7 @@ RAMA_OK, RAMA_ERR_INVALID_ARG, RAMA_ERR_BAD_GRAPH, RAMA_ERR_CAPACITY, RAMA_ERR_O
 EXPORTS = [
     "rama_create", "rama_destroy", "rama_last_error", "rama_params_default", "rama_workspace_bytes",
     "rama_round_count", "rama_round_get",
-    "rama_profile_enable", "rama_profile_count", "rama_profile_get", "rama_set_sort_split",
+    "rama_profile_enable", "rama_profile_count", "rama_profile_get", "rama_set_sort_split", "rama_set_cycle_search",
     "rama_find_conflicted_cycles", "rama_message_passing", "rama_dual_rounds", "rama_contract", "rama_solve",
     "rama_solve_static",
 ]
@@ -112,6 +112,7 @@ def load_library():
     lib.rama_solve_static.argtypes = lib.rama_solve.argtypes
     lib.rama_profile_enable.argtypes = [vp, i32, C.c_char_p]
     lib.rama_set_sort_split.argtypes = [vp, i64, i32]
+    lib.rama_set_cycle_search.argtypes = [vp, i32]
     lib.rama_profile_count.argtypes = [vp]
     lib.rama_profile_count.restype = i32
     lib.rama_profile_get.argtypes = [vp, i32, C.POINTER(C.c_char_p), C.POINTER(i64), C.POINTER(C.c_double),
@@ -242,6 +243,11 @@ class Rama:
         """Arrays of at least n_min elements take the split sort (top-bit passes + one in-LDS sort)
         when that replaces at least min_passes_replaced radix passes."""
         self._check(self.lib.rama_set_sort_split(self.ctx, int(n_min), int(min_passes_replaced)), "rama_set_sort_split")
+
+    def set_cycle_search(self, mode):
+        """0: cooperative search for cycles of length 4-5 on graphs with short rows (default), 1: always the
+        per-thread walk, 2: always cooperative.  The lists are the same either way."""
+        self._check(self.lib.rama_set_cycle_search(self.ctx, int(mode)), "rama_set_cycle_search")
 
     def profile_get(self):
         """Per-kernel totals since profiling was enabled: name, launches, ms, algorithmic bytes."""

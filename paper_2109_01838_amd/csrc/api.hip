@@ -394,6 +394,13 @@ rama_status rama_set_sort_split(rama_ctx *ctx, int64_t n_min, int32_t min_passes
     return RAMA_OK;
 }
 
+rama_status rama_set_cycle_search(rama_ctx *ctx, int32_t mode)
+{
+    if (!ctx || mode < 0 || mode > 3) return RAMA_ERR_INVALID_ARG;
+    ctx->cycle_search = mode;
+    return RAMA_OK;
+}
+
 int32_t rama_profile_count(const rama_ctx *ctx) { return ctx ? (int32_t)ctx->prof.stats.size() : 0; }
 
 rama_status rama_profile_get(const rama_ctx *ctx, int32_t index, const char **name, int64_t *launches, double *ms,

@@ -238,6 +238,7 @@ struct rama_ctx {
     std::string err;
     void *pinned = nullptr;  // small pinned host block for scalar read-backs
     static constexpr size_t kPinnedBytes = 4096;
+    int cycle_search = 0;                      // see rama_set_cycle_search
     size_t sort_split_min = size_t(1) << 21;   // arrays at least this long may take the split sort ...
     int sort_split_gain = 2;                   // ... when it replaces at least this many passes
 };

@@ -59,9 +59,23 @@ def rel_close(a, b, rel=REL):
 # --------------------------------------------------------------------------------------------
 # a1 cycles
 # --------------------------------------------------------------------------------------------
+@pytest.fixture
+def search_mode(rama, request):
+    """The ways of finding the cycles of length 4 and more: 1 = the per-thread walk that fetches a row per path
+    at its last level, 3 = the walk whose last level closes from the far endpoint's side, 2 = the cooperative
+    search for lengths 4 and 5 (rows beyond its staged sizes fall back to walk 3 edge by edge)."""
+    rama.set_cycle_search(request.param)
+    yield request.param
+    rama.set_cycle_search(0)
+
+
+BOTH_SEARCHES = pytest.mark.parametrize("search_mode", [1, 2, 3], indirect=True, ids=["walk", "cooperative", "walk-meet"])
+
+
 @pytest.mark.parametrize("name", list(CASES))
 @pytest.mark.parametrize("lmax", [3, 4, 5])
-def test_cycles_bit_exact(rama, oracle32, name, lmax):
+@BOTH_SEARCHES
+def test_cycles_bit_exact(rama, oracle32, name, lmax, search_mode):
     g = CASES[name]
     if name == "random_dense" and lmax == 5:
         g = dict(g, i=g["i"][:2500], j=g["j"][:2500], c=g["c"][:2500])
@@ -79,7 +93,8 @@ LONG_CASES = [("cfg1", 7), ("grid3d_24", 7), ("random_sparse", 7), ("knn_20000",
 
 
 @pytest.mark.parametrize("name,lmax", LONG_CASES)
-def test_longer_cycles_bit_exact(rama, oracle32, name, lmax):
+@BOTH_SEARCHES
+def test_longer_cycles_bit_exact(rama, oracle32, name, lmax, search_mode):
     g = CASES[name]
     want = oracle32.find_conflicted_cycles(g["n_nodes"], g["i"], g["j"], g["c"], lmax)
     got = rama.find_conflicted_cycles(g["n_nodes"], g["i"], g["j"], g["c"], lmax)
@@ -91,7 +106,8 @@ def test_longer_cycles_bit_exact(rama, oracle32, name, lmax):
 
 @pytest.mark.parametrize("name", list(CASES))
 @pytest.mark.parametrize("lmax", [3, 4, 5, 7])
-def test_shortest_only_cycles_bit_exact(rama, oracle32, name, lmax):
+@BOTH_SEARCHES
+def test_shortest_only_cycles_bit_exact(rama, oracle32, name, lmax, search_mode):
     g = CASES[name]
     if name in ("random_dense", "messy") and lmax == 7:
         g = dict(g, i=g["i"][:1500], j=g["j"][:1500], c=g["c"][:1500])
@@ -113,7 +129,8 @@ def hubs():
 
 
 @pytest.mark.parametrize("lmax,shortest", [(3, False), (4, False), (5, False), (4, True), (5, True), (7, True)])
-def test_heavy_rows_cycles_bit_exact(rama, oracle32, hubs, lmax, shortest):
+@BOTH_SEARCHES
+def test_heavy_rows_cycles_bit_exact(rama, oracle32, hubs, lmax, shortest, search_mode):
     g = hubs
     deg = np.bincount(np.concatenate([g["i"][g["c"] > 0], g["j"][g["c"] > 0]]), minlength=g["n_nodes"])
     assert deg.max() > 500 and np.median(deg) < 10
