@@ -137,8 +137,8 @@ rama_status rama_round_get(const rama_ctx *ctx, int32_t index, rama_round_stats 
  * While enabled, every kernel launch of the library is bracketed by two HIP events on the ctx
  * stream and accounted under the kernel's name together with the algorithmic bytes that launch
  * has to move (the launch site computes them from the array sizes).  Enabling resets the
- * accumulators; `only` (may be NULL) restricts the timers to kernels whose name starts with it,
- * which keeps the event overhead out of a timed region.  rama_profile_get returns entry `index` in [0, rama_profile_count): name
+ * accumulators; `only` (may be NULL) restricts the timers to kernels whose name starts with it -- or with
+ * one of several prefixes separated by '|' -- which keeps the event overhead out of a timed region.  rama_profile_get returns entry `index` in [0, rama_profile_count): name
  * (owned by the library), number of launches, summed milliseconds, summed algorithmic bytes.
  */
 rama_status rama_profile_enable(rama_ctx *ctx, int32_t on, const char *only);
@@ -152,6 +152,8 @@ rama_status rama_profile_get(const rama_ctx *ctx, int32_t index, const char **na
  * by one sort of the remaining bits inside LDS, provided that replaces at least
  * `min_passes_replaced` passes.  Both ways are the same stable sort, so no result depends on the
  * setting.  Defaults: 2^21 and 2.  (0, 0) sends every array that way, (INT64_MAX, any) none.
+ * Independently of n_min, an array short enough for one workgroup (8192 keys of up to 32 bits, 4096 wider
+ * ones) is sorted inside LDS by a single launch, unless n_min is INT64_MAX.
  */
 rama_status rama_set_sort_split(rama_ctx *ctx, int64_t n_min, int32_t min_passes_replaced);
 

@@ -314,6 +314,16 @@ rama_status rama_create(rama_ctx **out, void *hip_stream, const rama_alloc *allo
     if (alloc) ctx->pool.set_source(alloc->alloc, alloc->free, alloc->user);
     hipError_t e = hipGetDevice(&ctx->device);
     if (e == hipSuccess) e = hipHostMalloc(&ctx->pinned, rama_ctx::kPinnedBytes, hipHostMallocDefault);
+    if (e == hipSuccess) memset(ctx->pinned, 0, rama_ctx::kPinnedBytes);
+    if (e == hipSuccess) {   // the ticket word of the fused scans: zero at rest
+        void *t = nullptr;
+        e = ctx->pool.alloc(sizeof(uint32_t), &t);
+        if (e == hipSuccess) {
+            ctx->ticket = (uint32_t *)t;
+            e = hipMemsetAsync(t, 0, sizeof(uint32_t), ctx->stream);
+            if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+        }
+    }
     for (int k = 0; k < rama_ctx::kStageEvents && e == hipSuccess; ++k) e = hipEventCreate(&ctx->stage_ev[k]);
     if (e == hipSuccess && ctx->device >= 0 && ctx->device < kMaxDevices) {
         // every GPU holds its own copy of the static scratch array at its own address

@@ -102,8 +102,12 @@ __global__ __launch_bounds__(kBlock) void k_propose(size_t na, Cands a, unsigned
 }
 
 // matched edges fix their endpoints
-__global__ __launch_bounds__(kBlock) void k_accept(size_t na, Cands a, const unsigned long long *best, int32_t *mate)
+// The length of a round's candidate list is read from device memory (*n_list: the count the previous
+// round's compaction left there), so that several handshake rounds can be enqueued without the host
+// looking at the counts in between; the grid is sized from an upper bound and surplus workgroups leave.
+__global__ __launch_bounds__(kBlock) void k_accept(const uint32_t *n_list, Cands a, const unsigned long long *best, int32_t *mate)
 {
+    const size_t na = *n_list;
     size_t k = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (k >= na) return;
     const int32_t u = a.u[k], v = a.v[k];
@@ -120,11 +124,15 @@ __global__ __launch_bounds__(kBlock) void k_accept(size_t na, Cands a, const uns
 // round after next -- so only survivors pay for clearing, and nobody clears what somebody else
 // is proposing into.
 constexpr int kAdvItems = 8;
-__global__ __launch_bounds__(kBlock) void k_advance(size_t na, Cands a, const int32_t *mate, Cands next,
+constexpr uint32_t kMatchBatchMax = 1u << 20;   // candidate lists up to this length run their handshake rounds in batches
+constexpr int kMatchBatch = 4;
+__global__ __launch_bounds__(kBlock) void k_advance(const uint32_t *n_list, Cands a, const int32_t *mate, Cands next,
                                                     unsigned long long *best_next, unsigned long long *best_after,
                                                     uint32_t *counter)
 {
     __shared__ uint32_t s_base, s_wave[4], s_pairs[4];
+    const size_t na = *n_list;
+    if ((size_t)blockIdx.x * (kBlock * kAdvItems) >= na) return;   // the whole workgroup: nothing left of the list here
     const int w = threadIdx.x >> 6, lane = lane_id();
     const size_t base = (size_t)blockIdx.x * (kBlock * kAdvItems) + (size_t)w * (64 * kAdvItems) + lane;
     int32_t u[kAdvItems], v[kAdvItems];
@@ -468,62 +476,69 @@ static rama_status matching(Ctx &ctx, const Graph &g, float tau, int rounds_cap,
     const size_t m = (size_t)g.m, n = (size_t)g.n;
     n_matched = 0;
     RAMA_TRY(mate.alloc(ctx, n > 0 ? n : 1));
-    RAMA_TRY(fill<int32_t>(ctx, mate.get(), -1, n));
-    if (m == 0) return RAMA_OK;
+    MultiFill setup;   // mate = -1, rank words and counters = 0: one launch
+    setup.add(mate.get(), 0xffffffffu, n);
+    if (m == 0) return setup.run(ctx);
     Buf<int32_t> cu[2], cv[2];
     Buf<unsigned long long> cr[2];
     Cands cur{}, nxt{};
     uint32_t na = 0;
-    {
-        ScanPlan<uint32_t> cand;
-        RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, m, 0, cand)));
-        RAMA_TRY((scan_totals<uint32_t>(ctx, CandFlag{g.c.get(), tau}, cand)));
-        na = cand.total;
-        if (na == 0) return RAMA_OK;
-        for (int k = 0; k < 2; ++k) {
-            RAMA_TRY(cu[k].alloc(ctx, na));
-            RAMA_TRY(cv[k].alloc(ctx, na));
-            RAMA_TRY(cr[k].alloc(ctx, na));
-        }
-        cur = Cands{cu[0].get(), cv[0].get(), cr[0].get()};
-        nxt = Cands{cu[1].get(), cv[1].get(), cr[1].get()};
-        RAMA_TRY((scan_emit<uint32_t>(ctx, CandFlag{g.c.get(), tau}, PackCandsEmit{g.i.get(), g.j.get(), g.c.get(), cur}, cand,
-                                      (double)((size_t)na * 28))));
+    ScanPlan<uint32_t> cand;   // its total -- the length of the first list -- stays on the device for the first round
+    RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, m, 0, cand)));
+    RAMA_TRY((scan_totals<uint32_t>(ctx, CandFlag{g.c.get(), tau}, cand)));
+    na = cand.total;
+    if (na == 0) return setup.run(ctx);
+    for (int k = 0; k < 2; ++k) {
+        RAMA_TRY(cu[k].alloc(ctx, na));
+        RAMA_TRY(cv[k].alloc(ctx, na));
+        RAMA_TRY(cr[k].alloc(ctx, na));
     }
+    cur = Cands{cu[0].get(), cv[0].get(), cr[0].get()};
+    nxt = Cands{cu[1].get(), cv[1].get(), cr[1].get()};
+    RAMA_TRY((scan_emit<uint32_t>(ctx, CandFlag{g.c.get(), tau}, PackCandsEmit{g.i.get(), g.j.get(), g.c.get(), cur}, cand,
+                                  (double)((size_t)na * 28))));
     Buf<unsigned long long> best, best_next, best_after;   // rank words of this round, the next, the one after
     RAMA_TRY(best.alloc(ctx, n));
     RAMA_TRY(best_next.alloc(ctx, n));
     RAMA_TRY(best_after.alloc(ctx, n));
-    RAMA_TRY(fill<unsigned long long>(ctx, best.get(), 0ull, n));
-    RAMA_TRY(fill<unsigned long long>(ctx, best_next.get(), 0ull, n));
+    const int cap = rounds_cap > 0 ? rounds_cap : 0;
     Buf<uint32_t> counters;                      // per handshake round: survivors, pairs made
-    RAMA_TRY(counters.alloc(ctx, (size_t)(rounds_cap > 0 ? 2 * rounds_cap : 2)));
-    RAMA_TRY(fill<uint32_t>(ctx, counters.get(), 0u, (size_t)(rounds_cap > 0 ? 2 * rounds_cap : 2)));
-    if (rounds_cap > 0) {
+    RAMA_TRY(counters.alloc(ctx, (size_t)(2 * cap + 2)));
+    setup.add(best.get(), 0u, n);
+    setup.add(best_next.get(), 0u, n);
+    setup.add(counters.get(), 0u, (size_t)(2 * cap + 2));
+    RAMA_TRY(setup.run(ctx));
+    if (cap > 0) {
         ProfScope ps_(ctx, "k_propose", (double)((size_t)na * 32));
         k_propose<<<grid_for(na), kBlock, 0, ctx.stream>>>(na, cur, best.get());
     }
     LAUNCH_TRY(ctx, "propose");
-    for (int r = 0; r < rounds_cap && na > 0; ++r) {
-        {
-            ProfScope ps_(ctx, "k_accept", (double)((size_t)na * 40));
-            k_accept<<<grid_for(na), kBlock, 0, ctx.stream>>>(na, cur, best.get(), mate.get());
+    // Long lists: one round per look at the counts, so that every launch has its exact size.  Short lists
+    // (the launches are empty anyway): a batch of rounds is enqueued on the size of its first list, the counts
+    // come back together; rounds behind the one that emptied the list find a zero count and do nothing.
+    std::vector<uint32_t> back((size_t)(2 * cap + 2), 0u);
+    for (int r = 0; r < cap && na > 0;) {
+        const int batch = na > kMatchBatchMax ? 1 : (cap - r < kMatchBatch ? cap - r : kMatchBatch);
+        for (int b = 0; b < batch; ++b, ++r) {
+            const uint32_t *n_list = r == 0 ? cand.offs.get() + cand.nb : counters.get() + 2 * (r - 1);
+            {
+                ProfScope ps_(ctx, "k_accept", (double)((size_t)na * 40));
+                k_accept<<<grid_for(na), kBlock, 0, ctx.stream>>>(n_list, cur, best.get(), mate.get());
+            }
+            LAUNCH_TRY(ctx, "accept");
+            {
+                ProfScope ps_(ctx, "k_advance", (double)((size_t)na * 56));
+                k_advance<<<grid_for(na, kBlock * kAdvItems), kBlock, 0, ctx.stream>>>(
+                    n_list, cur, mate.get(), nxt, best_next.get(), best_after.get(), counters.get() + 2 * r);
+            }
+            LAUNCH_TRY(ctx, "advance");
+            Cands t = cur; cur = nxt; nxt = t;
+            best.swap(best_next);          // (this, next, after) <- (next, after, this)
+            best_next.swap(best_after);
         }
-        LAUNCH_TRY(ctx, "accept");
-        {
-            ProfScope ps_(ctx, "k_advance", (double)((size_t)na * 56));
-            k_advance<<<grid_for(na, kBlock * kAdvItems), kBlock, 0, ctx.stream>>>(
-                na, cur, mate.get(), nxt, best_next.get(), best_after.get(), counters.get() + 2 * r);
-        }
-        LAUNCH_TRY(ctx, "advance");
-        uint32_t back[2] = {0, 0};
-        RAMA_TRY(read_back(ctx, back, counters.get() + 2 * r, 8));
-        const uint32_t nn = back[0];
-        n_matched += back[1];
-        Cands t = cur; cur = nxt; nxt = t;
-        best.swap(best_next);          // (this, next, after) <- (next, after, this)
-        best_next.swap(best_after);
-        na = nn;
+        RAMA_TRY(read_back(ctx, back.data() + 2 * (r - batch), counters.get() + 2 * (r - batch), (size_t)batch * 8));
+        for (int b = r - batch; b < r; ++b) n_matched += back[(size_t)(2 * b + 1)];
+        na = back[(size_t)(2 * (r - 1))];
     }
     return RAMA_OK;
 }
@@ -751,8 +766,10 @@ rama_status contract_once(Ctx &ctx, const Graph &g, float tau, int rounds_cap, f
     Buf<uint32_t> npos;
     Buf<int32_t> si, sj, rep;
     RAMA_TRY(npos.alloc(ctx, n + 1));
+    bool pairs_only = true;   // S is a matching: every component of (V,S) is a node or a pair
     // too few pairs: switch to the spanning forest without conflicts (Sec. 3.1, "fewer than 0.1|V|")
     if (forest_ratio > 0.0f && (double)n_matched < (double)forest_ratio * (double)g.n) {
+        pairs_only = false;
         mate.reset();
         if (used_forest) *used_forest = true;
         RAMA_TRY(forest_set(ctx, g, tau, si, sj, n_matched));
@@ -766,9 +783,13 @@ rama_status contract_once(Ctx &ctx, const Graph &g, float tau, int rounds_cap, f
     }
     LAUNCH_TRY(ctx, "pair_rep");
     RAMA_TRY((exclusive_scan<uint32_t>(ctx, IsRoot{rep.get()}, npos.get(), n)));
-    uint32_t nn = 0;
-    RAMA_TRY(read_back(ctx, &nn, npos.get() + n, 4));
-    n_new = (int32_t)nn;
+    if (pairs_only) {
+        n_new = (int32_t)((int64_t)g.n - n_matched);   // every pair removes one node: no need to ask the device
+    } else {
+        uint32_t nn = 0;
+        RAMA_TRY(read_back(ctx, &nn, npos.get() + n, 4));
+        n_new = (int32_t)nn;
+    }
     RAMA_TRY(fmap.alloc(ctx, n));
     {
         ProfScope ps_(ctx, "k_number", (double)(n * 12));

@@ -319,6 +319,7 @@ __device__ __forceinline__ void walk_from_first(const Adj &g, const EndRow &end,
 // the whole row alone while its wave waits.  The per-thread kernels put such edges on a list
 // instead, and a second kernel gives each listed edge to a whole wave, one first hop per lane.
 // (Walks of length 3 are row intersections and stay with the per-thread kernels.)
+constexpr size_t kListHitsFrom = size_t(1) << 17;
 constexpr int kHeavyRow = 128;
 constexpr unsigned kHeavyGroups = 512;
 __device__ __forceinline__ bool heavy_edge(const Adj &g, int32_t v0, int max_len)
@@ -535,7 +536,7 @@ __global__ __launch_bounds__(kBlock) void k_fill_cycles(size_t nh, const uint32_
 {
     size_t h = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (h >= nh) return;
-    fill_edge<MAXL, MEET>(hit[h], ri, rj, g, lists, max_len, cnt, off, out);
+    fill_edge<MAXL, MEET>(hit ? hit[h] : (uint32_t)h, ri, rj, g, lists, max_len, cnt, off, out);
 }
 
 template <int MAXL, bool MEET>
@@ -746,8 +747,14 @@ __global__ __launch_bounds__(kBlock) void k_fill_cycles_coop(size_t nh, const ui
     const int gl = (int)(threadIdx.x & (kCoopLanes - 1)), grp = (int)(threadIdx.x / kCoopLanes);
     CoopStage &S = stage[grp];
     const size_t h = (size_t)blockIdx.x * kCoopEdges + grp;
-    const bool valid = h < nh;
-    const uint32_t r = valid ? hit[h] : 0u;
+    bool valid = h < nh;
+    const uint32_t r = valid ? (hit ? hit[h] : (uint32_t)h) : 0u;
+    if (valid && !hit) {   // no list of the edges with cycles was made: look at the counts first
+        uint32_t any = cnt.p[0][r];
+        if (max_len >= 4) any |= cnt.p[1][r];
+        if (max_len >= 5) any |= cnt.p[2][r];
+        valid = any != 0;
+    }
     const CoopEdge E = coop_stage(S, valid, valid ? ri[r] : 0, valid ? rj[r] : 0, g, max_len);
     __syncthreads();
     if (!E.live) return;   // nothing to search, or written by the walking kernels; the whole group leaves
@@ -950,9 +957,13 @@ rama_status count_and_fill(Ctx &ctx, size_t mr, const int32_t *ri, const int32_t
         list_bytes += 4.0 * (k + 3) * (double)tot[k];
     }
     if (all == 0) return RAMA_OK;
+    // The fill pass visits the repulsive edges that have cycles.  Listing them first pays on long lists; a
+    // short one is visited whole (an edge without cycles costs its thread three loads) and the launches and
+    // the count read-back of the listing are saved.
+    const bool list_hits = mr > kListHitsFrom;
     Buf<uint32_t> hit;
-    uint32_t nh = 0;
-    {
+    uint32_t nh = (uint32_t)mr;
+    if (list_hits) {
         HasCycles<MAXL> has{cp, lists};
         ScanPlan<uint32_t> hits;
         RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, mr, 0, hits)));
@@ -971,7 +982,7 @@ rama_status count_and_fill(Ctx &ctx, size_t mr, const int32_t *ri, const int32_t
         if (coop) {
             {
                 ProfScope ps_(ctx, "k_fill_cycles_coop", fill_bytes);
-                k_fill_cycles_coop<<<grid_for(nh, kCoopEdges), kBlock, 0, ctx.stream>>>(nh, hit.get(), ri, rj, adj, max_len, cp, op, vp);
+                k_fill_cycles_coop<<<grid_for(nh, kCoopEdges), kBlock, 0, ctx.stream>>>(nh, list_hits ? hit.get() : nullptr, ri, rj, adj, max_len, cp, op, vp);
             }
             LAUNCH_TRY(ctx, "fill_cycles_coop");
             ProfScope ps_(ctx, "k_fill_cycles_listed", 0.0);
@@ -982,9 +993,9 @@ rama_status count_and_fill(Ctx &ctx, size_t mr, const int32_t *ri, const int32_t
     if (!coop) {
         ProfScope ps_(ctx, MAXL == 3 ? "k_fill_cycles<3>" : MAXL == 5 ? "k_fill_cycles<5>" : "k_fill_cycles<7>", fill_bytes);
         if (meet && long_cycles)
-            k_fill_cycles<MAXL, (MAXL >= 5)><<<grid_for(nh), kBlock, 0, ctx.stream>>>(nh, hit.get(), ri, rj, adj, lists, max_len, cp, op, vp);
+            k_fill_cycles<MAXL, (MAXL >= 5)><<<grid_for(nh), kBlock, 0, ctx.stream>>>(nh, list_hits ? hit.get() : nullptr, ri, rj, adj, lists, max_len, cp, op, vp);
         else
-            k_fill_cycles<MAXL, false><<<grid_for(nh), kBlock, 0, ctx.stream>>>(nh, hit.get(), ri, rj, adj, lists, max_len, cp, op, vp);
+            k_fill_cycles<MAXL, false><<<grid_for(nh), kBlock, 0, ctx.stream>>>(nh, list_hits ? hit.get() : nullptr, ri, rj, adj, lists, max_len, cp, op, vp);
     }
     LAUNCH_TRY(ctx, "fill_cycles");
     if (may_be_heavy) {

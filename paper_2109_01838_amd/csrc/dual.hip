@@ -249,7 +249,8 @@ struct TrianglesEmit {
     int dbits;
     int32_t *tri_edge;
     uint32_t *skey, *sval;
-    int32_t *flag;
+    const int32_t *flag_in;   // raised by the kernel that built the keys
+    int32_t *flag;            // where the host will look: flag_in is carried over
     const uint32_t *origin;
     uint32_t kept_begin, kept_end;
     const float *ct_old;
@@ -257,6 +258,7 @@ struct TrianglesEmit {
     __device__ __forceinline__ void operator()(size_t q, uint32_t head, uint32_t runs_before) const
     {
         const size_t t = (size_t)runs_before + head - 1;   // the run q lies in (the first key is a head)
+        if (q == 0 && *flag_in) *flag = 1;
         if (origin) {
             const uint32_t o = origin[q];
             if (o >= kept_begin && o < kept_end) {
@@ -265,6 +267,7 @@ struct TrianglesEmit {
             }
         }
         if (!head) return;
+        if (!origin) { ct[3 * t] = 0.0f; ct[3 * t + 1] = 0.0f; ct[3 * t + 2] = 0.0f; }   // a new triangle starts at zero
         const KT k = key[q];
         const int32_t e0 = (int32_t)(k >> dbits);
         const int32_t e1 = e0 + (int32_t)(k & (((KT)1 << dbits) - 1));
@@ -518,9 +521,11 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
     }
     const int32_t n = g.n;
     const int nbits = bits_for((uint64_t)n);
-    Buf<int32_t> flag;
-    RAMA_TRY(flag.alloc(ctx, 1));
-    RAMA_TRY(fill<int32_t>(ctx, flag.get(), 0, 1));
+    // "a cycle uses an edge that is not in the graph": raised by the kernels that look edges up, read by the
+    // host together with the next count it waits for anyway
+    Buf<int32_t> flag;   // [0]: the flag, [1]: the longest row of the upper adjacency (filled in further down)
+    RAMA_TRY(flag.alloc(ctx, 2));
+    RAMA_TRY(fill<int32_t>(ctx, flag.get(), 0, 2));
     // rows of the canonical edge list (upper CSR)
     Buf<int32_t> rowptr;
     RAMA_TRY(rowptr.alloc(ctx, (size_t)n + 1));
@@ -602,22 +607,21 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
     }
     const size_t ma = (size_t)aug.m;
     // ---- triangles -----------------------------------------------------------------------------
-    Buf<uint32_t> maxrow;
-    RAMA_TRY(maxrow.alloc(ctx, 1));
-    RAMA_TRY(fill<uint32_t>(ctx, maxrow.get(), 0u, 1));
+    uint32_t *maxrow = (uint32_t *)(flag.get() + 1);
     {
         ProfScope ps_(ctx, "k_max_row", (double)(((size_t)n + 1) * 4));
-        k_max_row<<<grid_for((size_t)n), kBlock, 0, ctx.stream>>>(n, rowptr.get(), maxrow.get());
+        k_max_row<<<grid_for((size_t)n), kBlock, 0, ctx.stream>>>(n, rowptr.get(), maxrow);
     }
     LAUNCH_TRY(ctx, "max_row");
     uint32_t hmax = 0;
-    RAMA_TRY(read_back(ctx, &hmax, maxrow.get(), 4));
+    RAMA_TRY(read_back(ctx, &hmax, maxrow, 4));
     const int dbits = bits_for((uint64_t)hmax + 1);
     const int kbits = bits_for((uint64_t)ma) + dbits;
     Buf<int32_t> tri_edge;
     Buf<uint32_t> skey, slot;
     size_t T = 0;
     Buf<float> ct;
+    ScanPlan<uint32_t> inc_heads;   // scan over the sorted slot list (incidence); its spare word carries the flag to the host
     auto triangles = [&](auto key_tag) -> rama_status {
         using KT = decltype(key_tag);
         Buf<KT> tkey;
@@ -645,12 +649,13 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
         RAMA_TRY((scan_totals<uint32_t>(ctx, HeadFlagT<KT>{tkey.get()}, heads)));
         T = heads.total;
         RAMA_TRY(ct.alloc(ctx, 3 * T));
-        RAMA_TRY(fill<float>(ctx, ct.get(), 0.0f, 3 * T));
+        if (T_kept > 0) RAMA_TRY(fill<float>(ctx, ct.get(), 0.0f, 3 * T));   // otherwise the consumer below zeroes what it creates
         RAMA_TRY(tri_edge.alloc(ctx, 3 * T));
         RAMA_TRY(skey.alloc(ctx, 3 * T));
         RAMA_TRY(slot.alloc(ctx, 3 * T));
+        RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, 3 * T, 1, inc_heads)));
         TrianglesEmit<KT> te{tkey.get(), rowptr.get(), aug.j.get(), dbits, tri_edge.get(), skey.get(), slot.get(), flag.get(),
-                             T_kept > 0 ? origin.get() : nullptr, cs.fan_end[kCycleLists - 1], cs.fan_end[kCycleLists],
+                             (int32_t *)inc_heads.extra_ptr(), T_kept > 0 ? origin.get() : nullptr, cs.fan_end[kCycleLists - 1], cs.fan_end[kCycleLists],
                              T_kept > 0 ? prev->ct.get() : nullptr, ct.get()};
         RAMA_TRY((scan_emit<uint32_t>(ctx, HeadFlagT<KT>{tkey.get()}, te, heads, (double)(T * 44 + T_kept * 24))));
         return RAMA_OK;
@@ -658,19 +663,15 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
     if (kbits <= 32) RAMA_TRY(triangles(uint32_t{}));
     else RAMA_TRY(triangles(uint64_t{}));
     if (info) info->n_triangles = (int64_t)T;
-    {
-        int32_t hf = 0;
-        RAMA_TRY(read_back(ctx, &hf, flag.get(), 4));
-        if (hf) return fail(ctx, RAMA_ERR_BAD_GRAPH, "a cycle uses an edge that is not in the graph");
-    }
     // ---- incidence: slots of every edge in ascending triangle order ----------------------------
+    // (if the flag is up, the edge ids below are placeholders -- all valid indices -- and the result is discarded)
     RAMA_TRY((radix_sort_pairs<uint32_t, uint32_t>(ctx, skey, slot, 3 * T, bits_for((uint64_t)ma))));
     Buf<uint32_t> act_edge, act_start;
     size_t na = 0;
     {
-        ScanPlan<uint32_t> heads;
-        RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, 3 * T, 0, heads)));
+        ScanPlan<uint32_t> &heads = inc_heads;
         RAMA_TRY((scan_totals<uint32_t>(ctx, HeadFlag32{skey.get()}, heads)));
+        if (heads.extra_value[0]) return fail(ctx, RAMA_ERR_BAD_GRAPH, "a cycle uses an edge that is not in the graph");
         na = heads.total;
         RAMA_TRY(act_edge.alloc(ctx, na));
         RAMA_TRY(act_start.alloc(ctx, na + 1));

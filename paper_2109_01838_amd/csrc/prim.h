@@ -94,6 +94,40 @@ __device__ __forceinline__ T block_sum(T v)
 }
 
 // ------------------------------------------------------------------------------------------
+// scalars for the host: the mailbox
+// ------------------------------------------------------------------------------------------
+// closes message `seq`: everything this workgroup stored into mail[1..] before is visible to the host first
+__device__ __forceinline__ void mail_send(uint64_t *mail, uint64_t seq)
+{
+    __threadfence_system();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        *(volatile uint64_t *)mail = seq;
+        __threadfence_system();
+    }
+}
+
+// `words` 4-byte words from device memory into the mailbox
+static __global__ __launch_bounds__(kBlock) void k_publish(const uint32_t *src, unsigned words, uint64_t *mail, uint64_t seq)
+{
+    uint32_t *dst = (uint32_t *)(mail + 1);
+    for (unsigned k = threadIdx.x; k < words; k += kBlock) dst[k] = src[k];
+    mail_send(mail, seq);
+}
+
+// copy `bytes` (a multiple of 4, at most what a message holds) from device memory to the host and wait
+inline rama_status read_back(Ctx &ctx, void *host, const void *dev, size_t bytes)
+{
+    if (bytes % 4 != 0 || bytes > (Ctx::kMailWords - 1) * 8) return read_back_sync(ctx, host, dev, bytes);
+    const uint64_t seq = ++ctx.mail_seq;
+    k_publish<<<1, kBlock, 0, ctx.stream>>>((const uint32_t *)dev, (unsigned)(bytes / 4), mailbox(ctx), seq);
+    LAUNCH_TRY(ctx, "publish");
+    RAMA_TRY(wait_mail(ctx, seq));
+    memcpy(host, (const void *)(mailbox(ctx) + 1), bytes);
+    return RAMA_OK;
+}
+
+// ------------------------------------------------------------------------------------------
 // exclusive scan of f(0..n-1) into out[0..n] (out[n] = total)
 // ------------------------------------------------------------------------------------------
 // A workgroup owns a tile of 2048 consecutive items, each of its four waves 512 of them, taken
@@ -121,8 +155,45 @@ inline const char *kernel_name(const char *kernel)
     return names.back().second.c_str();
 }
 
+// exclusive scan of up to kScanMidMax tile sums by one workgroup, chunk after chunk; out[nb] = total
+constexpr unsigned kScanMidMax = 1u << 13;
+template <typename TO, bool COHERENT>
+__device__ __forceinline__ TO scan_tile_sums(const TO *in, TO *out, unsigned nb)
+{
+    TO carry = 0;
+    for (unsigned c0 = 0; c0 < nb; c0 += kScanTile) {
+        unsigned base = c0 + threadIdx.x * kScanItems;
+        TO v[kScanItems];
+        TO s = 0;
+#pragma unroll
+        for (int q = 0; q < kScanItems; ++q) {
+            // sums written by other workgroups of the same launch are read past the local cache
+            v[q] = (base + q < nb) ? (COHERENT ? __hip_atomic_load(in + base + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                               : in[base + q])
+                                   : (TO)0;
+            s += v[q];
+        }
+        TO tot;
+        TO run = block_inclusive_scan(s, &tot) - s + carry;
+#pragma unroll
+        for (int q = 0; q < kScanItems; ++q) {
+            if (base + q < nb) out[base + q] = run;
+            run += v[q];
+        }
+        carry += tot;
+    }
+    if (threadIdx.x == 0) out[nb] = carry;
+    return carry;
+}
+
+// Tile sums.  With a ticket word the launch also scans them: every workgroup publishes its sum and draws
+// a ticket; the one that draws the last ticket sees all sums, scans them into offs[0..nb] (offs[nb] = total),
+// puts the ticket word back to zero and -- if a mailbox is given -- sends the total and the caller's
+// `extra` words behind it (written by earlier launches) to the host.  One launch instead of two, and the
+// total reaches the host without a copy.
 template <typename TO, typename F>
-__global__ __launch_bounds__(kBlock) void k_scan_reduce(F f, TO *block_sums, size_t n)
+__global__ __launch_bounds__(kBlock) void k_scan_reduce(F f, TO *block_sums, size_t n, TO *offs, uint32_t *ticket,
+                                                        uint64_t *mail, uint64_t seq, int extra)
 {
     const size_t base = (size_t)blockIdx.x * kScanTile + threadIdx.x;
     TO s = 0;
@@ -132,7 +203,28 @@ __global__ __launch_bounds__(kBlock) void k_scan_reduce(F f, TO *block_sums, siz
         if (k < n) s += (TO)f(k);
     }
     TO tot = block_sum(s);
-    if (threadIdx.x == 0) block_sums[blockIdx.x] = tot;
+    if (!ticket) {
+        if (threadIdx.x == 0) block_sums[blockIdx.x] = tot;
+        return;
+    }
+    __shared__ bool last;
+    if (threadIdx.x == 0) {
+        __hip_atomic_store(block_sums + blockIdx.x, tot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __threadfence();
+        last = atomicAdd(ticket, 1u) == gridDim.x - 1;
+    }
+    __syncthreads();
+    if (!last) return;
+    __threadfence();
+    const TO total = scan_tile_sums<TO, true>(block_sums, offs, gridDim.x);
+    if (threadIdx.x == 0) *ticket = 0u;
+    if (mail) {
+        if (threadIdx.x == 0) {
+            mail[1] = (uint64_t)total;
+            for (int e = 0; e < extra; ++e) mail[2 + e] = (uint64_t)offs[gridDim.x + 1 + e];
+        }
+        mail_send(mail, seq);
+    }
 }
 
 template <typename TO, typename F>
@@ -171,33 +263,6 @@ __global__ __launch_bounds__(kBlock) void k_scan_apply(F f, TO *out, const TO *b
 template <typename TO>
 __global__ void k_store_zero(TO *p) { *p = 0; }
 
-// exclusive scan of up to kScanMidMax tile sums by one workgroup, chunk after chunk
-constexpr unsigned kScanMidMax = 1u << 13;
-template <typename TO>
-__global__ __launch_bounds__(kBlock) void k_scan_mid(const TO *in, TO *out, unsigned nb)
-{
-    TO carry = 0;
-    for (unsigned c0 = 0; c0 < nb; c0 += kScanTile) {
-        unsigned base = c0 + threadIdx.x * kScanItems;
-        TO v[kScanItems];
-        TO s = 0;
-#pragma unroll
-        for (int q = 0; q < kScanItems; ++q) {
-            v[q] = (base + q < nb) ? in[base + q] : (TO)0;
-            s += v[q];
-        }
-        TO tot;
-        TO run = block_inclusive_scan(s, &tot) - s + carry;
-#pragma unroll
-        for (int q = 0; q < kScanItems; ++q) {
-            if (base + q < nb) out[base + q] = run;
-            run += v[q];
-        }
-        carry += tot;
-    }
-    if (threadIdx.x == 0) out[nb] = carry;
-}
-
 template <typename TO, typename F>
 rama_status exclusive_scan(Ctx &ctx, F f, TO *out, size_t n)
 {
@@ -221,20 +286,14 @@ rama_status exclusive_scan(Ctx &ctx, F f, TO *out, size_t n)
     Buf<TO> sums, offs;
     RAMA_TRY(sums.alloc(ctx, nb));
     RAMA_TRY(offs.alloc(ctx, (size_t)nb + 1));
+    const bool fused = nb <= kScanMidMax;   // the last workgroup of the reduce launch scans the tile sums
     {
         ProfScope ps_(ctx, kernel_name<F>("k_scan_reduce"), (double)(n * F::bytes));
-        k_scan_reduce<TO, F><<<nb, kBlock, 0, ctx.stream>>>(f, sums.get(), n);
+        k_scan_reduce<TO, F><<<nb, kBlock, 0, ctx.stream>>>(f, sums.get(), n, offs.get(), fused ? ctx.ticket : nullptr,
+                                                           (uint64_t *)nullptr, 0, 0);
     }
     LAUNCH_TRY(ctx, "scan_reduce");
-    if (nb <= kScanMidMax) {   // one workgroup walks all tile sums: three launches in total
-        {
-            ProfScope ps_(ctx, "k_scan_mid", (double)((size_t)nb * 2 * sizeof(TO)));
-            k_scan_mid<TO><<<1, kBlock, 0, ctx.stream>>>(sums.get(), offs.get(), nb);
-        }
-        LAUNCH_TRY(ctx, "scan_mid");
-    } else {
-        RAMA_TRY((exclusive_scan<TO, PtrInput<TO>>(ctx, PtrInput<TO>{sums.get()}, offs.get(), nb)));
-    }
+    if (!fused) RAMA_TRY((exclusive_scan<TO, PtrInput<TO>>(ctx, PtrInput<TO>{sums.get()}, offs.get(), nb)));
     {
         ProfScope ps_(ctx, kernel_name<F>("k_scan_apply"), (double)(n * (F::bytes + sizeof(TO))));
         k_scan_apply<TO, F><<<nb, kBlock, 0, ctx.stream>>>(f, out, offs.get(), n);
@@ -281,26 +340,33 @@ rama_status scan_totals(Ctx &ctx, F f, ScanPlan<TO> &plan)
 {
     plan.total = 0;
     const unsigned nb = plan.nb;
-    if (plan.n > 0) {
+    TO back[3] = {0, 0, 0};
+    if (plan.n > 0 && nb <= kScanMidMax) {
+        // one launch: tile sums, their scan by the last workgroup, total and extra words into the mailbox
+        const uint64_t seq = ++ctx.mail_seq;
         {
             ProfScope ps_(ctx, kernel_name<F>("k_scan_reduce"), (double)(plan.n * F::bytes));
-            k_scan_reduce<TO, F><<<nb, kBlock, 0, ctx.stream>>>(f, plan.sums.get(), plan.n);
+            k_scan_reduce<TO, F><<<nb, kBlock, 0, ctx.stream>>>(f, plan.sums.get(), plan.n, plan.offs.get(), ctx.ticket,
+                                                               mailbox(ctx), seq, plan.extra);
         }
         LAUNCH_TRY(ctx, "scan_reduce");
-        if (nb <= kScanMidMax) {
-            // k_scan_mid stores the total behind the offsets: keep the caller's extra words, which sit
-            // one further on, out of its way
-            ProfScope ps_(ctx, "k_scan_mid", (double)((size_t)nb * 2 * sizeof(TO)));
-            k_scan_mid<TO><<<1, kBlock, 0, ctx.stream>>>(plan.sums.get(), plan.offs.get(), nb);
-            LAUNCH_TRY(ctx, "scan_mid");
-        } else {
-            // the nested scan writes nb+1 words (offsets and total), nothing beyond
-            RAMA_TRY((exclusive_scan<TO, PtrInput<TO>>(ctx, PtrInput<TO>{plan.sums.get()}, plan.offs.get(), nb)));
+        RAMA_TRY(wait_mail(ctx, seq));
+        const volatile uint64_t *m = mailbox(ctx);
+        for (int k = 0; k < 1 + plan.extra; ++k) back[k] = (TO)m[1 + k];
+    } else if (plan.n > 0) {
+        {
+            ProfScope ps_(ctx, kernel_name<F>("k_scan_reduce"), (double)(plan.n * F::bytes));
+            k_scan_reduce<TO, F><<<nb, kBlock, 0, ctx.stream>>>(f, plan.sums.get(), plan.n, (TO *)nullptr, (uint32_t *)nullptr,
+                                                               (uint64_t *)nullptr, 0, 0);
         }
+        LAUNCH_TRY(ctx, "scan_reduce");
+        // the nested scan writes nb+1 words (offsets and total), nothing beyond: the caller's extra words,
+        // which sit one further on, stay as they are
+        RAMA_TRY((exclusive_scan<TO, PtrInput<TO>>(ctx, PtrInput<TO>{plan.sums.get()}, plan.offs.get(), nb)));
+        RAMA_TRY(read_back(ctx, back, plan.offs.get() + nb, (size_t)(1 + plan.extra) * sizeof(TO)));
+    } else if (plan.extra > 0) {
+        RAMA_TRY(read_back(ctx, back + 1, plan.extra_ptr(), (size_t)plan.extra * sizeof(TO)));
     }
-    TO back[3] = {0, 0, 0};
-    if (plan.n > 0) RAMA_TRY(read_back(ctx, back, plan.offs.get() + nb, (size_t)(1 + plan.extra) * sizeof(TO)));
-    else if (plan.extra > 0) RAMA_TRY(read_back(ctx, back + 1, plan.extra_ptr(), (size_t)plan.extra * sizeof(TO)));
     plan.total = back[0];
     plan.extra_value[0] = back[1];
     plan.extra_value[1] = back[2];
@@ -750,7 +816,7 @@ struct LocalSort {
 };
 template <typename K, typename V, bool HAS_V, typename LK>
 __global__ __launch_bounds__(kLocalSortWaves * 64) void k_rs_local(const K *kin, const V *vin, K *kout, V *vout,
-                                                                   const uint32_t *bounds, int low_bits)
+                                                                   const uint32_t *bounds, int low_bits, uint32_t n_all)
 {
     constexpr int NW = kLocalSortWaves;
     constexpr int kItems = LocalSort<LK>::items;
@@ -761,7 +827,8 @@ __global__ __launch_bounds__(kLocalSortWaves * 64) void k_rs_local(const K *kin,
     __shared__ uint32_t wave_tot[4];
     __shared__ LK skey[kCap];
     __shared__ uint32_t sval[HAS_V ? kCap : 1];
-    const uint32_t beg = bounds[blockIdx.x], end = bounds[blockIdx.x + 1];
+    // without a bounds array the (single) workgroup takes the whole array of n_all keys
+    const uint32_t beg = bounds ? bounds[blockIdx.x] : 0u, end = bounds ? bounds[blockIdx.x + 1] : n_all;
     const uint32_t cnt = end - beg;
     if (cnt == 0 || cnt > (uint32_t)kCap) return;      // the caller has ruled the second case out
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -928,7 +995,7 @@ rama_status split_sort_tail(Ctx &ctx, K *ka, V *va, K *kb, V *vb, size_t n, int 
     if (over) return RAMA_OK;
     {
         ProfScope ps_(ctx, rs_local_name<K, HAS_V, LK>(), (double)(n * (2 * sizeof(K) + (HAS_V ? 8 : 0))));
-        k_rs_local<K, V, HAS_V, LK><<<nbk, LS::threads, 0, ctx.stream>>>(ka, va, kb, vb, bounds.get(), low_bits);
+        k_rs_local<K, V, HAS_V, LK><<<nbk, LS::threads, 0, ctx.stream>>>(ka, va, kb, vb, bounds.get(), low_bits, (uint32_t)n);
     }
     LAUNCH_TRY(ctx, "rs_local");
     *done = true;
@@ -948,6 +1015,25 @@ rama_status radix_sort_impl(Ctx &ctx, K *ka, V *va, K *kb, V *vb, size_t n, int 
     *result_in_b = false;
     if (n <= 1 || total_bits <= 0) return RAMA_OK;
     if (n >= (size_t(1) << 32)) return fail(ctx, RAMA_ERR_CAPACITY, "radix sort: more than 2^32 keys");
+    // an array that one workgroup can hold is sorted inside LDS by a single launch
+    if (total_bits < 8 * (int)sizeof(K) && ctx.sort_split_min < (size_t)INT64_MAX) {
+        const bool narrow = total_bits <= 32 && n <= (size_t)LocalSort<uint32_t>::cap;
+        const bool wide = !narrow && n <= (size_t)LocalSort<uint64_t>::cap;
+        if (narrow || wide) {
+            if (narrow) {
+                ProfScope ps_(ctx, rs_local_name<K, HAS_V, uint32_t>(), (double)(n * (2 * sizeof(K) + (HAS_V ? 8 : 0))));
+                k_rs_local<K, V, HAS_V, uint32_t><<<1, LocalSort<uint32_t>::threads, 0, ctx.stream>>>(ka, va, kb, vb, (const uint32_t *)nullptr,
+                                                                                                  total_bits, (uint32_t)n);
+            } else {
+                ProfScope ps_(ctx, rs_local_name<K, HAS_V, uint64_t>(), (double)(n * (2 * sizeof(K) + (HAS_V ? 8 : 0))));
+                k_rs_local<K, V, HAS_V, uint64_t><<<1, LocalSort<uint64_t>::threads, 0, ctx.stream>>>(ka, va, kb, vb, (const uint32_t *)nullptr,
+                                                                                                  total_bits, (uint32_t)n);
+            }
+            LAUNCH_TRY(ctx, "rs_local");
+            *result_in_b = true;
+            return RAMA_OK;
+        }
+    }
     const uint32_t nb = grid_for(n, SortTile<K>::size);
     Buf<uint32_t> hist, offs;
     RAMA_TRY(hist.alloc(ctx, (size_t)kRadix * nb));
@@ -1082,6 +1168,65 @@ __global__ __launch_bounds__(kBlock) void k_fill_wide(T *p, T v, size_t n)
         for (; k < n; ++k) p[k] = v;
     }
 }
+// up to four arrays of 32-bit words filled by one launch (arrays that one step sets up together);
+// every array is 16-byte aligned (pool blocks are) and is written 16 bytes per thread
+struct FillJobs {
+    uint32_t *p[4];
+    uint32_t v[4];
+    size_t end[4];   // running totals of the arrays' lengths in 16-byte pieces
+    size_t words[4];
+};
+static __global__ __launch_bounds__(kBlock) void k_fill_multi(FillJobs jobs)
+{
+    const size_t k = (size_t)blockIdx.x * kBlock + threadIdx.x;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        const size_t first = a ? jobs.end[a - 1] : 0;
+        if (k >= first && k < jobs.end[a]) {
+            const size_t w = (k - first) * 4;
+            uint32_t *p = jobs.p[a] + w;
+            const uint32_t v = jobs.v[a];
+            if (w + 4 <= jobs.words[a]) *reinterpret_cast<uint4 *>(p) = make_uint4(v, v, v, v);
+            else for (size_t q = w; q < jobs.words[a]; ++q) jobs.p[a][q] = v;
+        }
+    }
+}
+class MultiFill {
+public:
+    template <typename T>
+    void add(T *p, uint32_t pattern, size_t count)   // `count` elements of T, every 32-bit word of which becomes `pattern`
+    {
+        static_assert(sizeof(T) % 4 == 0, "whole words");
+        if (count == 0 || n_ >= 4) { overflow_ |= (count != 0); return; }
+        jobs_.p[n_] = reinterpret_cast<uint32_t *>(p);
+        jobs_.v[n_] = pattern;
+        jobs_.words[n_] = count * (sizeof(T) / 4);
+        total_ += (jobs_.words[n_] + 3) / 4;
+        jobs_.end[n_] = total_;
+        bytes_ += (double)(count * sizeof(T));
+        ++n_;
+    }
+    rama_status run(Ctx &ctx)
+    {
+        if (overflow_) return fail(ctx, RAMA_ERR_INVALID_ARG, "more than four arrays in one fill");
+        if (n_ == 0) return RAMA_OK;
+        for (int a = n_; a < 4; ++a) { jobs_.p[a] = nullptr; jobs_.v[a] = 0; jobs_.end[a] = total_; jobs_.words[a] = 0; }
+        {
+            ProfScope ps_(ctx, "k_fill", bytes_);
+            k_fill_multi<<<grid_for(total_), kBlock, 0, ctx.stream>>>(jobs_);
+        }
+        LAUNCH_TRY(ctx, "fill_multi");
+        return RAMA_OK;
+    }
+
+private:
+    FillJobs jobs_{};
+    int n_ = 0;
+    size_t total_ = 0;
+    double bytes_ = 0.0;
+    bool overflow_ = false;
+};
+
 template <typename T>
 rama_status fill(Ctx &ctx, T *p, T v, size_t n)
 {

@@ -61,7 +61,10 @@ def event_name(rocprof_name):
         head, args = n.split("<", 1)
         functor = args.rstrip(">").split(",")[-1].split("<")[0].strip()
         return f"{head}<{functor}>"
-    if "<" in n and not n.startswith(("k_rs_hist<", "k_edge_update<", "k_count_cycles<", "k_fill_cycles<")):
+    if n.startswith(("k_count_cycles<", "k_fill_cycles<")):
+        # <longest walk, last level closes from the far endpoint>: the timers name the walk length only
+        return n.split(",")[0].rstrip(">") + ">"
+    if "<" in n and not n.startswith(("k_rs_hist<", "k_edge_update<")):
         return n.split("<", 1)[0]     # plain template arguments (lengths, flags) are not part of the timers' names
     return n
 
@@ -82,8 +85,8 @@ def traffic_json(fetch_csv, write_csv, fetch_scale, write_scale, out_path):
         if nf and nw and (name.startswith("k_") or name.startswith("__amd")):
             out[name] = {"launches": nf, "read_bytes_per_launch": 1024.0 * fetch_scale * f / nf,
                          "written_bytes_per_launch": 1024.0 * write_scale * w / nw}
-    json.dump({"fetch_scale": fetch_scale, "write_scale": write_scale, "kernels": out}, open(out_path, "w"), indent=1,
-              sort_keys=True)
+    json.dump({"fetch_scale": fetch_scale, "write_scale": write_scale, "solves": 1, "kernels": out}, open(out_path, "w"),
+              indent=1, sort_keys=True)
 
 
 def capture(fn, *args):
@@ -112,7 +115,7 @@ def report(raw, out):
     with open(os.path.join(out, "cfg5_solve_kernel_trace.txt"), "w") as f:
         f.write(f"""# rocprofv3 kernel-trace summary: bench.py default run ({d['config']['workload']}, {d['config']['n_edges']} edges; 1 warm-up + 1 all-kernel-timed + 3 timed solves = {n_solves} solves)
 # command (on the GPU box; $REPO = repository root, $OUT = any scratch directory):
-#   cd /tmp && export TMPDIR=/tmp && rocprofv3 --kernel-trace --stats -d $OUT/prof_bench -o bench --output-format csv -- python3 $REPO/bench.py > $OUT/bench_rocprof.log
+#   cd /tmp && export TMPDIR=/tmp && rocprofv3 --kernel-trace --stats -d $OUT/prof_bench -o bench --output-format csv -- python3 $REPO/bench.py --other-workloads '' --cpu-config none > $OUT/bench_rocprof.log
 # condensed with: python -m paper_2109_01838_amd.profile_summary report $OUT profiles
 # bench.py's own HIP-event figures for the dominant kernel in the same run:
 #   {r['kernel']} avg_launch_ms {r['avg_launch_ms']:.5f} launches_per_step {r['launches_per_step']} achieved GB/s {r['achieved']:.1f} frac {r['frac']:.4f}
@@ -129,8 +132,8 @@ def report(raw, out):
     with open(os.path.join(out, "cfg5_solve_hbm_traffic.txt"), "w") as f:
         f.write(f"""# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch), two separate runs, {d['config']['workload']}, one solve each
 # commands (on the GPU box; $REPO = repository root, $OUT = any scratch directory):
-#   rocprofv3 --pmc FETCH_SIZE -d $OUT/pmc_fetch -o fetch --output-format csv -- python3 $REPO/bench.py --steps 1 --warmup 0 --no-profile --cpu-side 0 --copy-calibration
-#   rocprofv3 --pmc WRITE_SIZE -d $OUT/pmc_write -o write --output-format csv -- python3 $REPO/bench.py --steps 1 --warmup 0 --no-profile --cpu-side 0 --copy-calibration
+#   rocprofv3 --pmc FETCH_SIZE -d $OUT/pmc_fetch -o fetch --output-format csv -- python3 $REPO/bench.py --steps 1 --warmup 0 --no-profile --other-workloads '' --cpu-config none --copy-calibration
+#   rocprofv3 --pmc WRITE_SIZE -d $OUT/pmc_write -o write --output-format csv -- python3 $REPO/bench.py --steps 1 --warmup 0 --no-profile --other-workloads '' --cpu-config none --copy-calibration
 # condensed with: python -m paper_2109_01838_amd.profile_summary report $OUT profiles
 # calibration: a plain 1 GiB -> 1 GiB device copy (1048576 KiB read, 1048576 KiB written) reads
 #   FETCH_SIZE {', '.join(f'{v:.1f}' for v in cf)}

@@ -56,6 +56,10 @@ def test_profiler_names_map_onto_timer_names():
     assert f("void rama::k_scan_apply<unsigned int, rama::(anonymous namespace)::HeadFlag>(x)") == "k_scan_apply<HeadFlag>"
     assert f("void rama::k_scan_reduce<unsigned long, rama::PtrInput<unsigned int> >(x)") == "k_scan_reduce<PtrInput>"
     assert f("void rama::(anonymous namespace)::k_count_cycles<5>(unsigned long, int const*)") == "k_count_cycles<5>"
+    assert f("void rama::(anonymous namespace)::k_count_cycles<5, true>(unsigned long, int const*)") == "k_count_cycles<5>"
+    assert f("void rama::(anonymous namespace)::k_fill_cycles<7, false>(unsigned long)") == "k_fill_cycles<7>"
+    assert f("void rama::(anonymous namespace)::k_count_cycles_listed<5, true>(unsigned int const*)") == "k_count_cycles_listed"
+    assert f("void rama::(anonymous namespace)::k_count_cycles_coop(unsigned long)") == "k_count_cycles_coop"
     assert f("void rama::(anonymous namespace)::k_edge_update<false>(unsigned long)") == "k_edge_update<false>"
     assert f("void rama::k_rs_local<unsigned long, unsigned int, true, unsigned int>(unsigned long const*)") == "k_rs_local<u64,u32>"
     assert f("void rama::k_rs_local<unsigned int, unsigned int, false, unsigned int>(unsigned int const*)") == "k_rs_local<u32>"
