@@ -157,6 +157,7 @@ inline const char *kernel_name(const char *kernel)
 
 // exclusive scan of up to kScanMidMax tile sums by one workgroup, chunk after chunk; out[nb] = total
 constexpr unsigned kScanMidMax = 1u << 13;
+constexpr unsigned kScanFusedMax = 256;   // up to this many tiles (2^19 items) the reduce launch scans its own tile sums
 template <typename TO, bool COHERENT>
 __device__ __forceinline__ TO scan_tile_sums(const TO *in, TO *out, unsigned nb)
 {
@@ -227,6 +228,21 @@ __global__ __launch_bounds__(kBlock) void k_scan_reduce(F f, TO *block_sums, siz
     }
 }
 
+// the scan of the tile sums as a launch of its own (long arrays: the election above would make every
+// workgroup of the reduce launch wait for its sum to be visible, which costs more than a launch)
+template <typename TO>
+__global__ __launch_bounds__(kBlock) void k_scan_mid(const TO *in, TO *out, unsigned nb, uint64_t *mail, uint64_t seq, int extra)
+{
+    const TO total = scan_tile_sums<TO, false>(in, out, nb);
+    if (mail) {
+        if (threadIdx.x == 0) {
+            mail[1] = (uint64_t)total;
+            for (int e = 0; e < extra; ++e) mail[2 + e] = (uint64_t)out[nb + 1 + e];
+        }
+        mail_send(mail, seq);
+    }
+}
+
 template <typename TO, typename F>
 __global__ __launch_bounds__(kBlock) void k_scan_apply(F f, TO *out, const TO *block_offsets, size_t n)
 {
@@ -286,14 +302,20 @@ rama_status exclusive_scan(Ctx &ctx, F f, TO *out, size_t n)
     Buf<TO> sums, offs;
     RAMA_TRY(sums.alloc(ctx, nb));
     RAMA_TRY(offs.alloc(ctx, (size_t)nb + 1));
-    const bool fused = nb <= kScanMidMax;   // the last workgroup of the reduce launch scans the tile sums
+    const bool fused = nb <= kScanFusedMax;   // the last workgroup of the reduce launch scans the tile sums
     {
         ProfScope ps_(ctx, kernel_name<F>("k_scan_reduce"), (double)(n * F::bytes));
         k_scan_reduce<TO, F><<<nb, kBlock, 0, ctx.stream>>>(f, sums.get(), n, offs.get(), fused ? ctx.ticket : nullptr,
                                                            (uint64_t *)nullptr, 0, 0);
     }
     LAUNCH_TRY(ctx, "scan_reduce");
-    if (!fused) RAMA_TRY((exclusive_scan<TO, PtrInput<TO>>(ctx, PtrInput<TO>{sums.get()}, offs.get(), nb)));
+    if (!fused && nb <= kScanMidMax) {
+        ProfScope ps_(ctx, "k_scan_mid", (double)((size_t)nb * 2 * sizeof(TO)));
+        k_scan_mid<TO><<<1, kBlock, 0, ctx.stream>>>(sums.get(), offs.get(), nb, (uint64_t *)nullptr, 0, 0);
+        LAUNCH_TRY(ctx, "scan_mid");
+    } else if (!fused) {
+        RAMA_TRY((exclusive_scan<TO, PtrInput<TO>>(ctx, PtrInput<TO>{sums.get()}, offs.get(), nb)));
+    }
     {
         ProfScope ps_(ctx, kernel_name<F>("k_scan_apply"), (double)(n * (F::bytes + sizeof(TO))));
         k_scan_apply<TO, F><<<nb, kBlock, 0, ctx.stream>>>(f, out, offs.get(), n);
@@ -342,14 +364,21 @@ rama_status scan_totals(Ctx &ctx, F f, ScanPlan<TO> &plan)
     const unsigned nb = plan.nb;
     TO back[3] = {0, 0, 0};
     if (plan.n > 0 && nb <= kScanMidMax) {
-        // one launch: tile sums, their scan by the last workgroup, total and extra words into the mailbox
+        // short arrays, one launch: tile sums, their scan by the last workgroup, total and extra words into the
+        // mailbox; longer arrays: the scan of the tile sums is a launch of its own
         const uint64_t seq = ++ctx.mail_seq;
+        const bool fused = nb <= kScanFusedMax;
         {
             ProfScope ps_(ctx, kernel_name<F>("k_scan_reduce"), (double)(plan.n * F::bytes));
-            k_scan_reduce<TO, F><<<nb, kBlock, 0, ctx.stream>>>(f, plan.sums.get(), plan.n, plan.offs.get(), ctx.ticket,
-                                                               mailbox(ctx), seq, plan.extra);
+            k_scan_reduce<TO, F><<<nb, kBlock, 0, ctx.stream>>>(f, plan.sums.get(), plan.n, plan.offs.get(),
+                                                               fused ? ctx.ticket : nullptr, mailbox(ctx), seq, plan.extra);
         }
         LAUNCH_TRY(ctx, "scan_reduce");
+        if (!fused) {
+            ProfScope ps_(ctx, "k_scan_mid", (double)((size_t)nb * 2 * sizeof(TO)));
+            k_scan_mid<TO><<<1, kBlock, 0, ctx.stream>>>(plan.sums.get(), plan.offs.get(), nb, mailbox(ctx), seq, plan.extra);
+            LAUNCH_TRY(ctx, "scan_mid");
+        }
         RAMA_TRY(wait_mail(ctx, seq));
         const volatile uint64_t *m = mailbox(ctx);
         for (int k = 0; k < 1 + plan.extra; ++k) back[k] = (TO)m[1 + k];
