@@ -3,6 +3,7 @@
   python -m paper_2109_01838_amd.profile_summary stats  <..._kernel_stats.csv> [n_solves]
   python -m paper_2109_01838_amd.profile_summary pmc    <..._counter_collection.csv> <COUNTER> [kernel substrings..]
   python -m paper_2109_01838_amd.profile_summary traffic <fetch.csv> <write.csv> <fetch_scale> <write_scale> <out.json>
+  python -m paper_2109_01838_amd.profile_summary report-workload <raw output dir> <profiles dir> <cfg2|cfg3|..>
   python -m paper_2109_01838_amd.profile_summary report  <raw output dir> <profiles dir>
       (all of the above for bench.py's default workload: expects prof_bench/, pmc_fetch/, pmc_write/ and
        bench_rocprof.log as the commands in the written files' headers leave them)
@@ -146,9 +147,30 @@ def report(raw, out):
         f.write("\n".join(capture(pmc, write, "WRITE_SIZE", ["k_"]).splitlines()[:25]) + "\n")
 
 
+def report_workload(raw, out, workload):
+    """Kernel-trace summary of a bench.py run on another named configuration (expects prof_<workload>/ and
+    bench_<workload>_rocprof.log in `raw`, as the command in the written file's header leaves them)."""
+    import json
+    import os
+    n_solves = 5
+    d = json.loads([l for l in open(os.path.join(raw, f"bench_{workload}_rocprof.log")) if l.startswith("{")][-1])
+    stats_txt = capture(stats, os.path.join(raw, f"prof_{workload}", f"{workload}_kernel_stats.csv"), n_solves)
+    with open(os.path.join(out, f"{workload}_solve_kernel_trace.txt"), "w") as f:
+        f.write(f"""# rocprofv3 kernel-trace summary: bench.py on {d['config']['workload']} ({d['config']['n_edges']} edges; 1 warm-up + 1 all-kernel-timed + 3 timed solves = {n_solves} solves)
+# command (on the GPU box; $REPO = repository root, $OUT = any scratch directory):
+#   cd /tmp && export TMPDIR=/tmp && rocprofv3 --kernel-trace --stats -d $OUT/prof_{workload} -o {workload} --output-format csv -- python3 $REPO/bench.py --workload {workload} --other-workloads '' --cpu-config none > $OUT/bench_{workload}_rocprof.log
+# condensed with: python -m paper_2109_01838_amd.profile_summary report-workload $OUT profiles {workload}
+# bench.py in the same run: ms_per_step {d['ms_per_step']:.2f} (under the profiler), rounds {d['rounds']}, cycles found in round 1 {d['n_cycles_first'][:3]}
+
+""")
+        f.write("\n".join(stats_txt.splitlines()[:34]) + "\n")
+
+
 if __name__ == "__main__":
     if sys.argv[1] == "report":
         report(sys.argv[2], sys.argv[3])
+    elif sys.argv[1] == "report-workload":
+        report_workload(sys.argv[2], sys.argv[3], sys.argv[4])
     elif sys.argv[1] == "traffic":
         traffic_json(sys.argv[2], sys.argv[3], float(sys.argv[4]), float(sys.argv[5]), sys.argv[6])
     elif sys.argv[1] == "stats":
