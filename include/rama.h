@@ -167,7 +167,11 @@ rama_status rama_set_sort_split(rama_ctx *ctx, int64_t n_min, int32_t min_passes
  *   2  the cooperative search for lengths 4 and 5: sixteen lanes per repulsive edge, N+(v0), N+(vL) and
  *      the rows of N+(vL)'s entries staged in LDS (rows of up to 16 entries; edges with longer rows are
  *      walked as in 3), hits placed by ballots and prefix sums over the sixteen lanes.
- * mode 0 (default) chooses between 2 and 3 from the sizes of the graph.
+ * Searches for triangles only (max_cycle_len 3) are row intersections: by one thread per repulsive edge
+ * (modes 1 and 3), or by sixteen lanes per edge that bisect the longer row for sixteen entries of the shorter
+ * one at a time (mode 2).
+ * mode 0 (default) chooses from the sizes of the graph: for lengths 4-5 between 2 and 3, for triangles the
+ * sixteen-lane search when the attractive rows hold more than 12 entries on average.
  */
 rama_status rama_set_cycle_search(rama_ctx *ctx, int32_t mode);
 

@@ -807,6 +807,55 @@ __global__ __launch_bounds__(kBlock) void k_fill_cycles_coop(size_t nh, const ui
     }
 }
 
+// ---- triangles on graphs with long rows ----------------------------------------------------------
+// The contracted graphs of later rounds can be dense (rows of 20-40 attractive neighbours and more).  One
+// thread per repulsive edge then walks its shorter row alone, a dependent bisection of the longer row per
+// entry.  Here sixteen lanes share the edge: they take the shorter row sixteen entries at a time, every lane
+// bisects the longer row for its entry, and a ballot counts -- or, in the fill pass, places -- the common
+// neighbours.  The shorter row is ascending, so the triangles (v0, v1, vL) come out in list order.
+template <bool FILL>
+__global__ __launch_bounds__(kBlock) void k_triangles_group(size_t nr, const uint32_t *hit, const int32_t *ri,
+                                                            const int32_t *rj, Adj g, uint32_t *cnt0, const uint64_t *off0,
+                                                            int32_t *out0)
+{
+    const int gl = (int)(threadIdx.x & (kCoopLanes - 1));
+    const size_t h = (size_t)blockIdx.x * kCoopEdges + threadIdx.x / kCoopLanes;
+    if (h >= nr) return;                                   // the whole group
+    const uint32_t r = hit ? hit[h] : (uint32_t)h;
+    if (FILL && cnt0[r] == 0) return;
+    const int32_t v0 = ri[r], vl = rj[r];
+    int32_t a0 = g.ptr[v0], a1 = g.ptr[v0 + 1], b0 = g.ptr[vl], b1 = g.ptr[vl + 1];
+    if (a1 - a0 > b1 - b0) { int32_t t = a0; a0 = b0; b0 = t; t = a1; a1 = b1; b1 = t; }   // [a0,a1): the shorter row
+    uint32_t found = 0;
+    uint64_t at = FILL ? off0[r] : 0;
+    if (b0 < b1)
+        for (int32_t base = a0; base < a1; base += kCoopLanes) {   // the same number of turns for every lane of the group
+            const int32_t p = base + gl;
+            bool common = false;
+            int32_t x = 0;
+            if (p < a1) {
+                x = g.nb[p];
+                int32_t lo = b0, hi = b1;
+                while (lo < hi) {
+                    const int32_t mid = lo + ((hi - lo) >> 1);
+                    if (g.nb[mid] < x) lo = mid + 1; else hi = mid;
+                }
+                common = lo < b1 && g.nb[lo] == x;
+            }
+            const uint32_t vote = group_ballot(common);
+            if (FILL) {
+                if (common) {
+                    int32_t *o = out0 + 3 * (at + (uint64_t)__popc(vote & ((1u << gl) - 1u)));
+                    o[0] = v0; o[1] = x; o[2] = vl;
+                }
+                at += (uint64_t)__popc(vote);
+            } else {
+                found += (uint32_t)__popc(vote);
+            }
+        }
+    if (!FILL && gl == 0) cnt0[r] = found;
+}
+
 // cycles of the listed heavy edges: per round of 64 first hops every lane counts what its hop
 // closes, a wave scan turns the counts into places, and the lane walks again and writes
 template <int MAXL>
@@ -916,7 +965,15 @@ rama_status count_and_fill(Ctx &ctx, size_t mr, const int32_t *ri, const int32_t
                                                                                      n_heavy.get() + 1);
         }
     }
-    if (!coop) {
+    // triangles only, rows of more than 12 attractive neighbours on average: sixteen lanes per repulsive edge
+    bool wide3 = false;
+    if constexpr (MAXL == 3)
+        wide3 = ctx.cycle_search == 2 || (ctx.cycle_search == 0 && 2 * mp > (size_t)12 * (size_t)n);
+    if (wide3) {
+        ProfScope ps_(ctx, "k_count_triangles_group", search_bytes);
+        k_triangles_group<false><<<grid_for(mr, kCoopEdges), kBlock, 0, ctx.stream>>>(mr, (const uint32_t *)nullptr, ri, rj, adj, cp.p[0],
+                                                                                   (const uint64_t *)nullptr, (int32_t *)nullptr);
+    } else if (!coop) {
         ProfScope ps_(ctx, MAXL == 3 ? "k_count_cycles<3>" : MAXL == 5 ? "k_count_cycles<5>" : "k_count_cycles<7>", search_bytes);
         if (meet)
             k_count_cycles<MAXL, (MAXL >= 5)><<<grid_for(mr), kBlock, 0, ctx.stream>>>(mr, ri, rj, adj, max_len, walk_flags, cp,
@@ -990,7 +1047,11 @@ rama_status count_and_fill(Ctx &ctx, size_t mr, const int32_t *ri, const int32_t
                                                                                     max_len, cp, op, vp);
         }
     }
-    if (!coop) {
+    if (wide3) {
+        ProfScope ps_(ctx, "k_fill_triangles_group", fill_bytes);
+        k_triangles_group<true><<<grid_for(nh, kCoopEdges), kBlock, 0, ctx.stream>>>(nh, list_hits ? hit.get() : nullptr, ri, rj, adj, cp.p[0],
+                                                                                  op.p[0], vp.p[0]);
+    } else if (!coop) {
         ProfScope ps_(ctx, MAXL == 3 ? "k_fill_cycles<3>" : MAXL == 5 ? "k_fill_cycles<5>" : "k_fill_cycles<7>", fill_bytes);
         if (meet && long_cycles)
             k_fill_cycles<MAXL, (MAXL >= 5)><<<grid_for(nh), kBlock, 0, ctx.stream>>>(nh, list_hits ? hit.get() : nullptr, ri, rj, adj, lists, max_len, cp, op, vp);
