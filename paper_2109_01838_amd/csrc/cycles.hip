@@ -475,13 +475,13 @@ struct HasCycles {
     static constexpr int bytes = 4;   // bytes read per item: at least one count (one per list searched)
     static constexpr const char *tag = MAXL > 5 ? "HasCycles7" : "HasCycles";
     ListPtrs<uint32_t, MAXL - 2> cnt;
-    int lists;
+    int live;   // bit mask of the lists that hold any cycle
     __device__ __forceinline__ uint32_t operator()(size_t r) const
     {
         uint32_t any = 0;
 #pragma unroll
         for (int k = 0; k < MAXL - 2; ++k)
-            if (k < lists) any |= cnt.p[k][r];
+            if (live & (1 << k)) any |= cnt.p[k][r];
         return any ? 1u : 0u;
     }
 };
@@ -508,7 +508,7 @@ __global__ void k_cycle_totals(ListPtrs<uint64_t, NL> off, size_t mr, int lists,
 // second walk, only over the repulsive edges that have cycles and only as deep as their
 // longest cycle; writes every list at the offsets of the scan
 template <int MAXL, bool MEET>
-__device__ __forceinline__ void fill_edge(uint32_t r, const int32_t *ri, const int32_t *rj, const Adj &g, int lists,
+__device__ __forceinline__ void fill_edge(uint32_t r, const int32_t *ri, const int32_t *rj, const Adj &g, int live,
                                           int max_len, const ListPtrs<uint32_t, MAXL - 2> &cnt,
                                           const ListPtrs<uint64_t, MAXL - 2> &off, const ListPtrs<int32_t, MAXL - 2> &out)
 {
@@ -519,7 +519,7 @@ __device__ __forceinline__ void fill_edge(uint32_t r, const int32_t *ri, const i
 #pragma unroll
     for (int k = 0; k < MAXL - 2; ++k) {
         em.o[k] = nullptr;
-        if (k < lists) {
+        if (live & (1 << k)) {   // `live`: bit k set iff list k holds any cycle at all (the arrays of empty lists are not touched)
             if (cnt.p[k][r]) depth = k + 3;
             em.o[k] = out.p[k] + (size_t)(k + 3) * off.p[k][r];
         }
@@ -529,26 +529,26 @@ __device__ __forceinline__ void fill_edge(uint32_t r, const int32_t *ri, const i
 
 template <int MAXL, bool MEET>
 __global__ __launch_bounds__(kBlock) void k_fill_cycles(size_t nh, const uint32_t *hit, const int32_t *ri,
-                                                        const int32_t *rj, Adj g, int lists, int max_len,
+                                                        const int32_t *rj, Adj g, int live, int max_len,
                                                         ListPtrs<uint32_t, MAXL - 2> cnt,
                                                         ListPtrs<uint64_t, MAXL - 2> off,
                                                         ListPtrs<int32_t, MAXL - 2> out)
 {
     size_t h = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (h >= nh) return;
-    fill_edge<MAXL, MEET>(hit ? hit[h] : (uint32_t)h, ri, rj, g, lists, max_len, cnt, off, out);
+    fill_edge<MAXL, MEET>(hit ? hit[h] : (uint32_t)h, ri, rj, g, live, max_len, cnt, off, out);
 }
 
 template <int MAXL, bool MEET>
 __global__ __launch_bounds__(kBlock) void k_fill_cycles_listed(const uint32_t *list, const uint32_t *n_list,
-                                                               const int32_t *ri, const int32_t *rj, Adj g, int lists,
+                                                               const int32_t *ri, const int32_t *rj, Adj g, int live,
                                                                int max_len, ListPtrs<uint32_t, MAXL - 2> cnt,
                                                                ListPtrs<uint64_t, MAXL - 2> off,
                                                                ListPtrs<int32_t, MAXL - 2> out)
 {
     const size_t n = *n_list;
     for (size_t q = (size_t)blockIdx.x * kBlock + threadIdx.x; q < n; q += (size_t)gridDim.x * kBlock)
-        fill_edge<MAXL, MEET>(list[q], ri, rj, g, lists, max_len, cnt, off, out);
+        fill_edge<MAXL, MEET>(list[q], ri, rj, g, live, max_len, cnt, off, out);
 }
 
 // ---- cooperative search for cycles of length up to 5 ---------------------------------------------
@@ -739,7 +739,7 @@ __global__ __launch_bounds__(kBlock) void k_count_cycles_coop(size_t nr, const i
 }
 
 __global__ __launch_bounds__(kBlock) void k_fill_cycles_coop(size_t nh, const uint32_t *hit, const int32_t *ri,
-                                                             const int32_t *rj, Adj g, int max_len,
+                                                             const int32_t *rj, Adj g, int max_len, int live,
                                                              ListPtrs<uint32_t, 3> cnt, ListPtrs<uint64_t, 3> off,
                                                              ListPtrs<int32_t, 3> out)
 {
@@ -750,18 +750,19 @@ __global__ __launch_bounds__(kBlock) void k_fill_cycles_coop(size_t nh, const ui
     bool valid = h < nh;
     const uint32_t r = valid ? (hit ? hit[h] : (uint32_t)h) : 0u;
     if (valid && !hit) {   // no list of the edges with cycles was made: look at the counts first
-        uint32_t any = cnt.p[0][r];
-        if (max_len >= 4) any |= cnt.p[1][r];
-        if (max_len >= 5) any |= cnt.p[2][r];
+        uint32_t any = 0;   // `live`: bit k set iff list k holds any cycle at all
+        if (live & 1) any |= cnt.p[0][r];
+        if (live & 2) any |= cnt.p[1][r];
+        if (live & 4) any |= cnt.p[2][r];
         valid = any != 0;
     }
     const CoopEdge E = coop_stage(S, valid, valid ? ri[r] : 0, valid ? rj[r] : 0, g, max_len);
     __syncthreads();
     if (!E.live) return;   // nothing to search, or written by the walking kernels; the whole group leaves
     // a list is written iff the count pass kept cycles of that length (with shortest_only: one length only)
-    const bool want3 = cnt.p[0][r] != 0;
-    const bool want4 = max_len >= 4 && cnt.p[1][r] != 0;
-    const bool want5 = max_len >= 5 && cnt.p[2][r] != 0;
+    const bool want3 = (live & 1) && cnt.p[0][r] != 0;
+    const bool want4 = (live & 2) && cnt.p[1][r] != 0;
+    const bool want5 = (live & 4) && cnt.p[2][r] != 0;
     CoopRegs R;
     R.load(S);
     if (want3) {
@@ -860,7 +861,7 @@ __global__ __launch_bounds__(kBlock) void k_triangles_group(size_t nr, const uin
 // closes, a wave scan turns the counts into places, and the lane walks again and writes
 template <int MAXL>
 __global__ __launch_bounds__(kBlock) void k_fill_cycles_heavy(const uint32_t *heavy, const uint32_t *n_heavy,
-                                                              const int32_t *ri, const int32_t *rj, Adj g, int lists,
+                                                              const int32_t *ri, const int32_t *rj, Adj g, int live,
                                                               ListPtrs<uint32_t, MAXL - 2> cnt,
                                                               ListPtrs<uint64_t, MAXL - 2> off,
                                                               ListPtrs<int32_t, MAXL - 2> out)
@@ -874,7 +875,7 @@ __global__ __launch_bounds__(kBlock) void k_fill_cycles_heavy(const uint32_t *he
 #pragma unroll
         for (int k = 0; k < MAXL - 2; ++k) {
             place[k] = 0;
-            if (k < lists) {
+            if (live & (1 << k)) {
                 if (cnt.p[k][r]) depth = k + 3;
                 place[k] = off.p[k][r];
             }
@@ -895,7 +896,7 @@ __global__ __launch_bounds__(kBlock) void k_fill_cycles_heavy(const uint32_t *he
 #pragma unroll
             for (int k = 0; k < MAXL - 2; ++k) {
                 fe.o[k] = nullptr;
-                if (k < lists) {
+                if (live & (1 << k)) {
                     const uint32_t inc = wave_inclusive_scan(em.n[k]);
                     fe.o[k] = out.p[k] + (size_t)(k + 3) * (place[k] + (inc - em.n[k]));
                     place[k] += wave_last(inc);
@@ -1014,6 +1015,9 @@ rama_status count_and_fill(Ctx &ctx, size_t mr, const int32_t *ri, const int32_t
         list_bytes += 4.0 * (k + 3) * (double)tot[k];
     }
     if (all == 0) return RAMA_OK;
+    int live = 0;   // the lists that hold any cycle: the fill pass leaves the count and offset arrays of the others alone
+    for (int k = 0; k < lists; ++k)
+        if (tot[k]) live |= 1 << k;
     // The fill pass visits the repulsive edges that have cycles.  Listing them first pays on long lists; a
     // short one is visited whole (an edge without cycles costs its thread three loads) and the launches and
     // the count read-back of the listing are saved.
@@ -1021,7 +1025,7 @@ rama_status count_and_fill(Ctx &ctx, size_t mr, const int32_t *ri, const int32_t
     Buf<uint32_t> hit;
     uint32_t nh = (uint32_t)mr;
     if (list_hits) {
-        HasCycles<MAXL> has{cp, lists};
+        HasCycles<MAXL> has{cp, live};
         ScanPlan<uint32_t> hits;
         RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, mr, 0, hits)));
         RAMA_TRY((scan_totals<uint32_t>(ctx, has, hits)));
@@ -1039,11 +1043,11 @@ rama_status count_and_fill(Ctx &ctx, size_t mr, const int32_t *ri, const int32_t
         if (coop) {
             {
                 ProfScope ps_(ctx, "k_fill_cycles_coop", fill_bytes);
-                k_fill_cycles_coop<<<grid_for(nh, kCoopEdges), kBlock, 0, ctx.stream>>>(nh, list_hits ? hit.get() : nullptr, ri, rj, adj, max_len, cp, op, vp);
+                k_fill_cycles_coop<<<grid_for(nh, kCoopEdges), kBlock, 0, ctx.stream>>>(nh, list_hits ? hit.get() : nullptr, ri, rj, adj, max_len, live, cp, op, vp);
             }
             LAUNCH_TRY(ctx, "fill_cycles_coop");
             ProfScope ps_(ctx, "k_fill_cycles_listed", 0.0);
-            k_fill_cycles_listed<MAXL, true><<<kHeavyGroups, kBlock, 0, ctx.stream>>>(spill.get(), n_heavy.get() + 2, ri, rj, adj, lists,
+            k_fill_cycles_listed<MAXL, true><<<kHeavyGroups, kBlock, 0, ctx.stream>>>(spill.get(), n_heavy.get() + 2, ri, rj, adj, live,
                                                                                     max_len, cp, op, vp);
         }
     }
@@ -1054,14 +1058,14 @@ rama_status count_and_fill(Ctx &ctx, size_t mr, const int32_t *ri, const int32_t
     } else if (!coop) {
         ProfScope ps_(ctx, MAXL == 3 ? "k_fill_cycles<3>" : MAXL == 5 ? "k_fill_cycles<5>" : "k_fill_cycles<7>", fill_bytes);
         if (meet && long_cycles)
-            k_fill_cycles<MAXL, (MAXL >= 5)><<<grid_for(nh), kBlock, 0, ctx.stream>>>(nh, list_hits ? hit.get() : nullptr, ri, rj, adj, lists, max_len, cp, op, vp);
+            k_fill_cycles<MAXL, (MAXL >= 5)><<<grid_for(nh), kBlock, 0, ctx.stream>>>(nh, list_hits ? hit.get() : nullptr, ri, rj, adj, live, max_len, cp, op, vp);
         else
-            k_fill_cycles<MAXL, false><<<grid_for(nh), kBlock, 0, ctx.stream>>>(nh, list_hits ? hit.get() : nullptr, ri, rj, adj, lists, max_len, cp, op, vp);
+            k_fill_cycles<MAXL, false><<<grid_for(nh), kBlock, 0, ctx.stream>>>(nh, list_hits ? hit.get() : nullptr, ri, rj, adj, live, max_len, cp, op, vp);
     }
     LAUNCH_TRY(ctx, "fill_cycles");
     if (may_be_heavy) {
         ProfScope ps_(ctx, "k_fill_cycles_heavy", 0.0);
-        k_fill_cycles_heavy<MAXL><<<kHeavyGroups, kBlock, 0, ctx.stream>>>(heavy.get(), n_heavy.get(), ri, rj, adj, lists, cp,
+        k_fill_cycles_heavy<MAXL><<<kHeavyGroups, kBlock, 0, ctx.stream>>>(heavy.get(), n_heavy.get(), ri, rj, adj, live, cp,
                                                                          op, vp);
         LAUNCH_TRY(ctx, "fill_cycles_heavy");
     }
