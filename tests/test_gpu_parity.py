@@ -487,11 +487,13 @@ def test_profile_hooks_and_workspace(rama):
 
 def test_random_sweep_of_small_instances_and_parameters(rama, oracle32):
     """Seeded sweep: small random / grid instances with random solver parameters (cycle lengths,
-    iteration counts, forest switch, round limit, dual rounds, shortest-only).  Labels, cycle counts,
+    iteration counts, forest switch, round limit, dual rounds, shortest-only) and a random choice of the
+    cycle search (0..3) and of the entry point (rama_solve / rama_solve_static).  Labels, cycle counts,
     rounds and bounds must agree with the oracle on every one.  (Such a sweep found a rooting loop
     that gave up one check too early on trees about as deep as the graph has nodes.)"""
     from paper_2109_01838_amd import default_params
     rng = np.random.default_rng(7)
+    mode_rng = np.random.default_rng(8)   # a stream of its own: the instances stay the ones of earlier versions of this test
     bad = []
     for it in range(160):
         kind = int(rng.integers(0, 4))
@@ -516,7 +518,10 @@ def test_random_sweep_of_small_instances_and_parameters(rama, oracle32):
             kw["max_cycle_len_first"] = min(kw["max_cycle_len_first"], 4 if kw["dual_rounds"] > 1 else 5)
             kw["max_cycle_len_later"] = min(kw["max_cycle_len_later"], 3)
         want = oracle32.solve(n, g["i"], g["j"], g["c"], shortest_only=shortest, **kw)
-        got = rama.solve(n, g["i"], g["j"], g["c"], default_params(shortest_cycles_only=int(shortest), **kw))
+        rama.set_cycle_search(int(mode_rng.integers(0, 4)))
+        got = rama.solve(n, g["i"], g["j"], g["c"], default_params(shortest_cycles_only=int(shortest), **kw),
+                         static=bool(mode_rng.integers(0, 3) == 0))
+        rama.set_cycle_search(0)
         ok = (np.array_equal(np_(got["labels"]), want["labels"]) and got["n_cycles_first"] == want["n_cycles_first"]
               and got["rounds"] == want["rounds"]
               and abs(got["lower_bound"] - want["lower_bound"]) <= REL * max(1.0, abs(want["lower_bound"]))
