@@ -135,7 +135,8 @@ rama_status rama_round_get(const rama_ctx *ctx, int32_t index, rama_round_stats 
 /*
  * Measurement hooks (not operations of the paper): per-kernel timers for roofline reports.
  * While enabled, every kernel launch of the library is bracketed by two HIP events on the ctx
- * stream and accounted under the kernel's name together with the algorithmic bytes that launch
+ * stream (the triangle update of the message passing stamps its events from the dispatch itself) and
+ * accounted under the kernel's name together with the algorithmic bytes that launch
  * has to move (the launch site computes them from the array sizes).  Enabling resets the
  * accumulators; `only` (may be NULL) restricts the timers to kernels whose name starts with it -- or with
  * one of several prefixes separated by '|' -- which keeps the event overhead out of a timed region.  rama_profile_get returns entry `index` in [0, rama_profile_count): name

@@ -191,6 +191,14 @@ public:
         pending_.push_back(p);
     }
     void end(hipStream_t s) { (void)hipEventRecord(pending_.back().b, s); }
+    // for a launch that stamps its own start and stop events (hipExtLaunchKernelGGL): the times then come
+    // from the dispatch itself, nothing extra is put into the queue
+    void begin_stamped(const char *name, double bytes, hipEvent_t *a, hipEvent_t *b)
+    {
+        Pending p{id_of(name), get_event(), get_event(), bytes};
+        *a = p.a; *b = p.b;
+        pending_.push_back(p);
+    }
     // call only when the stream has been synchronised
     void collect()
     {
@@ -371,12 +379,12 @@ inline int bits_for(uint64_t n)
 // the mailbox as kernels see it (pinned host memory is mapped at the same address on the device)
 inline uint64_t *mailbox(Ctx &ctx) { return (uint64_t *)((char *)ctx.pinned + 2048); }
 
-// waits until message `seq` is in the mailbox: bounded polling, then the stream synchronisation.  While the
-// per-kernel timers are on every wait is a synchronisation (the timers are collected there).
+// waits until message `seq` is in the mailbox: bounded polling, then the stream synchronisation.  (The
+// per-kernel timers are collected at the synchronisation that ends every call of the library.)
 inline rama_status wait_mail(Ctx &ctx, uint64_t seq)
 {
     volatile uint64_t *m = mailbox(ctx);
-    if (!ctx.prof.on) {
+    {
         // polls as long as it takes the kernels in front of the message; the clock is only there to end the
         // wait if the message never comes (a failed launch, a fault): the synchronisation below then reports it
         const auto t0 = std::chrono::steady_clock::now();

@@ -17,6 +17,8 @@
 //   edge kernel:     one thread per edge that lies in a triangle; adds its messages in ascending
 //                    triangle order (slot list built once per round by a stable sort) and stores
 //                    the next share c_e/N_e.  Work is proportional to the triangles, not the edges.
+#include <hip/hip_ext.h>
+
 #include "prim.h"
 
 namespace rama {
@@ -696,8 +698,12 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
         RAMA_TRY(read_back(ctx, &lb_trace[0], lb_dev.get(), 8));
     }
     for (int it = 1; it <= k_iters; ++it) {
-        {
-            ProfScope ps_(ctx, "k_triangle_update", (double)(T * 60));
+        if (ctx.prof.wants("k_triangle_update")) {   // timed by the dispatch's own start and stop stamps
+            hipEvent_t ea, eb;
+            ctx.prof.begin_stamped("k_triangle_update", (double)(T * 60), &ea, &eb);
+            hipExtLaunchKernelGGL(k_triangle_update, dim3(grid_for(T)), dim3(kBlock), 0, ctx.stream, ea, eb, 0, (size_t)T,
+                                  (const int32_t *)tri_edge.get(), (const float *)share.get(), (float *)ct.get(), (float *)msg.get());
+        } else {
             k_triangle_update<<<grid_for(T), kBlock, 0, ctx.stream>>>(T, tri_edge.get(), share.get(), ct.get(), msg.get());
         }
         LAUNCH_TRY(ctx, "triangle_update");
