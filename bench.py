@@ -166,6 +166,7 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms = 1e3 * dt / args.steps
+    round_records = rama.round_stats()      # of the last timed solve (later solves on this ctx overwrite them)
 
     roofline, roofline_top, solve_traffic = None, None, None
     if dominant is not None:
@@ -239,7 +240,7 @@ def main():
                            "cycles": r["n_cycles"][:3], "triangles": r["n_triangles"], "contracted": r["n_contracted"],
                            "forest": r["used_forest"], "workspace_peak_MiB": round(r["workspace_peak"] / 2**20, 1),
                            "ms": [round(r["ms"][k], 3) for k in ("cycles", "dual", "contract")]}
-                          for r in rama.round_stats()],
+                          for r in round_records],
         "roofline": roofline,
         "roofline_top5": roofline_top,
         "solve_traffic": solve_traffic,
