@@ -188,20 +188,25 @@ __global__ __launch_bounds__(kBlock) void k_emit_chords(size_t nch, const uint64
 }
 
 // merge of the canonical edge list with the (sorted, disjoint) new chords.
-// ins[e] = number of chords placed before graph edge e  (row bounds of `before`)
+// ins[v] = number of chords with before < v, so ins[e + 1] chords come before graph edge e (row bounds of
+// `before`).  A workgroup writes its 256 edges and the chords that sit between them (and in front of its first
+// edge; the last workgroup also those behind the last edge): one contiguous stretch of the output, written
+// at one time.  With chord k handled by thread k instead, every output cache line was written twice, at two
+// far-apart moments (3.0 GB written for a 1.56 GB list at the 320^3 grid).
 __global__ __launch_bounds__(kBlock) void k_merge_edges(size_t m, const int32_t *i, const int32_t *j, const float *c,
-                                                        const int32_t *ins, size_t nnew, const int32_t *ci,
-                                                        const int32_t *cj, const int32_t *before, int32_t *io,
-                                                        int32_t *jo, float *co)
+                                                        const int32_t *ins, const int32_t *ci, const int32_t *cj,
+                                                        const int32_t *before, int32_t *io, int32_t *jo, float *co)
 {
-    size_t e = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    const size_t e0 = (size_t)blockIdx.x * kBlock, e = e0 + threadIdx.x;
+    const size_t e1 = e0 + kBlock < m ? e0 + kBlock : m;
     if (e < m) {
         size_t d = e + (size_t)ins[e + 1];
         io[d] = i[e]; jo[d] = j[e]; co[d] = c[e];
     }
-    if (e < nnew) {
-        size_t d = (size_t)before[e] + e;
-        io[d] = ci[e]; jo[d] = cj[e]; co[d] = 0.0f;
+    const size_t k0 = (size_t)ins[e0], k1 = (size_t)ins[e1 == m ? m + 1 : e1];
+    for (size_t k = k0 + threadIdx.x; k < k1; k += kBlock) {
+        size_t d = (size_t)before[k] + k;
+        io[d] = ci[k]; jo[d] = cj[k]; co[d] = 0.0f;
     }
 }
 
@@ -585,12 +590,11 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
             RAMA_TRY(aug.i.alloc(ctx, (size_t)aug.m));
             RAMA_TRY(aug.j.alloc(ctx, (size_t)aug.m));
             RAMA_TRY(aug.c.alloc(ctx, (size_t)aug.m));
-            size_t span = m > nnew ? m : nnew;
             {
                 ProfScope ps_(ctx, "k_merge_edges", (double)(m * 16 + (size_t)nnew * 12 + (m + nnew) * 12));
-                k_merge_edges<<<grid_for(span), kBlock, 0, ctx.stream>>>(m, g.i.get(), g.j.get(), g.c.get(), ins.get(), nnew,
-                                                                    ci.get(), cj.get(), before.get(), aug.i.get(),
-                                                                    aug.j.get(), aug.c.get());
+                k_merge_edges<<<grid_for(m), kBlock, 0, ctx.stream>>>(m, g.i.get(), g.j.get(), g.c.get(), ins.get(), ci.get(),
+                                                                 cj.get(), before.get(), aug.i.get(), aug.j.get(),
+                                                                 aug.c.get());
             }
             LAUNCH_TRY(ctx, "merge_edges");
             RAMA_TRY((row_bounds<int32_t, int32_t>(ctx, aug.i.get(), (size_t)aug.m, n, rowptr.get())));
