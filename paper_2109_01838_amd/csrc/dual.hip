@@ -254,7 +254,6 @@ struct TrianglesEmit {
     const KT *key;
     const int32_t *rowptr, *j;
     int dbits;
-    int32_t *tri_edge;
     uint32_t *skey, *sval;
     const int32_t *flag_in;   // raised by the kernel that built the keys
     int32_t *flag;            // where the host will look: flag_in is carried over
@@ -280,7 +279,6 @@ struct TrianglesEmit {
         const int32_t e1 = e0 + (int32_t)(k & (((KT)1 << dbits) - 1));
         int32_t e2 = find_edge_in_row(rowptr, j, j[e0], j[e1]);
         if (e2 < 0) { *flag = 1; e2 = 0; }
-        tri_edge[3 * t + 0] = e0; tri_edge[3 * t + 1] = e1; tri_edge[3 * t + 2] = e2;
         skey[3 * t + 0] = (uint32_t)e0; skey[3 * t + 1] = (uint32_t)e1; skey[3 * t + 2] = (uint32_t)e2;
         sval[3 * t + 0] = (uint32_t)(3 * t); sval[3 * t + 1] = (uint32_t)(3 * t + 1); sval[3 * t + 2] = (uint32_t)(3 * t + 2);
     }
@@ -292,13 +290,13 @@ __global__ __launch_bounds__(kBlock) void k_iota_u32(size_t n, uint32_t *p)
     if (k < n) p[k] = (uint32_t)k;
 }
 
-// node triple (u,v,w) of every triangle from its edges (u,v) and (u,w)
-__global__ __launch_bounds__(kBlock) void k_triangle_nodes(size_t T, const int32_t *tri_edge, const int32_t *i,
-                                                           const int32_t *j, int32_t *nodes)
+// node triple (u,v,w) of every triangle from its edges (u,v) and (u,w); tri_act holds their numbers among the active edges
+__global__ __launch_bounds__(kBlock) void k_triangle_nodes(size_t T, const uint32_t *tri_act, const uint32_t *act_edge,
+                                                           const int32_t *i, const int32_t *j, int32_t *nodes)
 {
     size_t t = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (t >= T) return;
-    const int32_t e0 = tri_edge[3 * t], e1 = tri_edge[3 * t + 1];
+    const uint32_t e0 = act_edge[tri_act[3 * t]], e1 = act_edge[tri_act[3 * t + 1]];
     nodes[3 * t] = i[e0]; nodes[3 * t + 1] = j[e0]; nodes[3 * t + 2] = j[e1];
 }
 
@@ -314,15 +312,20 @@ struct HeadFlag32 {
 };
 
 // consumer of the scan over HeadFlag32: run number a of the sorted slot list starts at p and belongs
-// to edge skey[p]; the entry behind the last run closes it
+// to edge skey[p]; the entry behind the last run closes it.  Every slot learns the number of its run:
+// the message passing addresses edges by their number among the active edges, so that the shares it
+// gathers lie densely (on the 320^3 grid one edge in five is active; indexed by edge id the share
+// array cost the triangle update 25 bytes of fetches per triangle beyond the 12 it uses).
 struct ActiveEdgesEmit {
     static constexpr const char *tag = "ActiveEdges";
-    const uint32_t *skey;
+    const uint32_t *skey, *sval;
     uint32_t ns, na;
-    uint32_t *act_edge, *act_start;
-    __device__ __forceinline__ void operator()(size_t p, uint32_t head, uint32_t a) const
+    uint32_t *act_edge, *act_start, *tri_act;
+    __device__ __forceinline__ void operator()(size_t p, uint32_t head, uint32_t before) const
     {
         if (p == 0) act_start[na] = ns;
+        const uint32_t a = before + head - 1u;   // the first slot is a head
+        tri_act[sval[p]] = a;
         if (!head) return;
         act_edge[a] = skey[p];
         act_start[a] = (uint32_t)p;
@@ -334,8 +337,7 @@ __global__ __launch_bounds__(kBlock) void k_edge_init(size_t na, const uint32_t 
 {
     size_t a = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (a >= na) return;
-    uint32_t e = act_edge[a];
-    share[e] = ce[e] / (float)(act_start[a + 1] - act_start[a]);
+    share[a] = ce[act_edge[a]] / (float)(act_start[a + 1] - act_start[a]);
 }
 
 // costs of the four non-trivial labelings of M_T = {000,110,101,011,111}
@@ -360,12 +362,12 @@ __device__ __forceinline__ float min_marginal(float a, float b, float c, int s)
     return fminf(fminf(l.l101, l.l011), l.l111) - fminf(0.0f, l.l110);
 }
 
-__global__ __launch_bounds__(kBlock) void k_triangle_update(size_t T, const int32_t *tri_edge, const float *share,
+__global__ __launch_bounds__(kBlock) void k_triangle_update(size_t T, const uint32_t *tri_act, const float *share,
                                                             float *ct, float *msg)
 {
     size_t t = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (t >= T) return;
-    const int32_t e0 = tri_edge[3 * t], e1 = tri_edge[3 * t + 1], e2 = tri_edge[3 * t + 2];
+    const uint32_t e0 = tri_act[3 * t], e1 = tri_act[3 * t + 1], e2 = tri_act[3 * t + 2];
     // edges -> triangles
     float a = ct[3 * t] + share[e0];
     float b = ct[3 * t + 1] + share[e1];
@@ -434,9 +436,8 @@ __global__ __launch_bounds__(kBlock) void k_edge_update(size_t na, const uint32_
     for (int j = 0; j < kEdgesPerThread; ++j) {
         const size_t a = a0 + (size_t)j * kBlock + threadIdx.x;
         if (a < na) {
-            const uint32_t e = act_edge[a];
-            if (STORE_CE) ce[e] = acc[j];
-            share[e] = acc[j] / (float)(p1[j] - p0[j]);
+            if (STORE_CE) ce[act_edge[a]] = acc[j];
+            share[a] = acc[j] / (float)(p1[j] - p0[j]);
         }
     }
 }
@@ -623,7 +624,7 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
     RAMA_TRY(read_back(ctx, &hmax, maxrow, 4));
     const int dbits = bits_for((uint64_t)hmax + 1);
     const int kbits = bits_for((uint64_t)ma) + dbits;
-    Buf<int32_t> tri_edge;
+    Buf<uint32_t> tri_act;   // per triangle slot: its edge's number among the active edges
     Buf<uint32_t> skey, slot;
     size_t T = 0;
     Buf<float> ct;
@@ -656,14 +657,13 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
         T = heads.total;
         RAMA_TRY(ct.alloc(ctx, 3 * T));
         if (T_kept > 0) RAMA_TRY(fill<float>(ctx, ct.get(), 0.0f, 3 * T));   // otherwise the consumer below zeroes what it creates
-        RAMA_TRY(tri_edge.alloc(ctx, 3 * T));
         RAMA_TRY(skey.alloc(ctx, 3 * T));
         RAMA_TRY(slot.alloc(ctx, 3 * T));
         RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, 3 * T, 1, inc_heads)));
-        TrianglesEmit<KT> te{tkey.get(), rowptr.get(), aug.j.get(), dbits, tri_edge.get(), skey.get(), slot.get(), flag.get(),
+        TrianglesEmit<KT> te{tkey.get(), rowptr.get(), aug.j.get(), dbits, skey.get(), slot.get(), flag.get(),
                              (int32_t *)inc_heads.extra_ptr(), T_kept > 0 ? origin.get() : nullptr, cs.fan_end[kCycleLists - 1], cs.fan_end[kCycleLists],
                              T_kept > 0 ? prev->ct.get() : nullptr, ct.get()};
-        RAMA_TRY((scan_emit<uint32_t>(ctx, HeadFlagT<KT>{tkey.get()}, te, heads, (double)(T * 44 + T_kept * 24))));
+        RAMA_TRY((scan_emit<uint32_t>(ctx, HeadFlagT<KT>{tkey.get()}, te, heads, (double)(T * 32 + T_kept * 24))));
         return RAMA_OK;
     };
     if (kbits <= 32) RAMA_TRY(triangles(uint32_t{}));
@@ -681,15 +681,17 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
         na = heads.total;
         RAMA_TRY(act_edge.alloc(ctx, na));
         RAMA_TRY(act_start.alloc(ctx, na + 1));
+        RAMA_TRY(tri_act.alloc(ctx, 3 * T));
         RAMA_TRY((scan_emit<uint32_t>(ctx, HeadFlag32{skey.get()},
-                                      ActiveEdgesEmit{skey.get(), (uint32_t)(3 * T), (uint32_t)na, act_edge.get(), act_start.get()},
-                                      heads, (double)(na * 8))));
+                                      ActiveEdgesEmit{skey.get(), slot.get(), (uint32_t)(3 * T), (uint32_t)na, act_edge.get(),
+                                                      act_start.get(), tri_act.get()},
+                                      heads, (double)(na * 8 + 3 * T * 8))));
     }
     skey.reset();
     rowptr.reset();
     // ---- iterations ----------------------------------------------------------------------------
     Buf<float> share, msg;
-    RAMA_TRY(share.alloc(ctx, ma));
+    RAMA_TRY(share.alloc(ctx, na));
     RAMA_TRY(msg.alloc(ctx, 3 * T));
     float *ce = aug.c.get();
     {
@@ -706,14 +708,14 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
             hipEvent_t ea, eb;
             ctx.prof.begin_stamped("k_triangle_update", (double)(T * 60), &ea, &eb);
             hipExtLaunchKernelGGL(k_triangle_update, dim3(grid_for(T)), dim3(kBlock), 0, ctx.stream, ea, eb, 0, (size_t)T,
-                                  (const int32_t *)tri_edge.get(), (const float *)share.get(), (float *)ct.get(), (float *)msg.get());
+                                  (const uint32_t *)tri_act.get(), (const float *)share.get(), (float *)ct.get(), (float *)msg.get());
         } else {
-            k_triangle_update<<<grid_for(T), kBlock, 0, ctx.stream>>>(T, tri_edge.get(), share.get(), ct.get(), msg.get());
+            k_triangle_update<<<grid_for(T), kBlock, 0, ctx.stream>>>(T, tri_act.get(), share.get(), ct.get(), msg.get());
         }
         LAUNCH_TRY(ctx, "triangle_update");
         {
             const bool store_ce = it == k_iters || lb_trace != nullptr;
-            ProfScope ps_(ctx, store_ce ? "k_edge_update<true>" : "k_edge_update<false>", (double)(na * (store_ce ? 16 : 12) + 3 * T * 8));
+            ProfScope ps_(ctx, store_ce ? "k_edge_update<true>" : "k_edge_update<false>", (double)(na * (store_ce ? 16 : 8) + 3 * T * 8));
             if (store_ce)
                 k_edge_update<true><<<grid_for(na, kBlock * kEdgesPerThread), kBlock, 0, ctx.stream>>>(na, act_edge.get(), act_start.get(), slot.get(),
                                                                          msg.get(), ce, share.get());
@@ -739,7 +741,7 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
         RAMA_TRY(next->tri_nodes.alloc(ctx, 3 * T));
         {
             ProfScope ps_(ctx, "k_triangle_nodes", (double)(T * 36));
-            k_triangle_nodes<<<grid_for(T), kBlock, 0, ctx.stream>>>(T, tri_edge.get(), aug.i.get(), aug.j.get(),
+            k_triangle_nodes<<<grid_for(T), kBlock, 0, ctx.stream>>>(T, tri_act.get(), act_edge.get(), aug.i.get(), aug.j.get(),
                                                                   next->tri_nodes.get());
         }
         LAUNCH_TRY(ctx, "triangle_nodes");
