@@ -747,9 +747,7 @@ static rama_status contract_edges(Ctx &ctx, const Graph &g, const int32_t *fmap,
     RAMA_TRY(out.i.alloc(ctx, uniq));
     RAMA_TRY(out.j.alloc(ctx, uniq));
     RAMA_TRY(out.c.alloc(ctx, uniq));
-    RAMA_TRY((scan_emit<uint32_t>(ctx, HeadFlag{key.get()},
-                                  ReduceRunsEmit{kept, key.get(), val.get(), dbits, out.i.get(), out.j.get(), out.c.get()}, runs,
-                                  (double)((size_t)kept * 4 + (size_t)uniq * 12))));
+    RAMA_TRY(reduce_runs(ctx, runs, key.get(), val.get(), dbits, out.i.get(), out.j.get(), out.c.get()));
     out.m = uniq;
     return RAMA_OK;
 }

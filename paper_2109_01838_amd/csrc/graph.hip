@@ -124,9 +124,7 @@ rama_status canonicalise(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const
     RAMA_TRY(out.i.alloc(ctx, uniq));
     RAMA_TRY(out.j.alloc(ctx, uniq));
     RAMA_TRY(out.c.alloc(ctx, uniq));
-    RAMA_TRY((scan_emit<uint32_t>(ctx, HeadFlag{key.get()},
-                                  ReduceRunsEmit{kept, key.get(), val.get(), dbits, out.i.get(), out.j.get(), out.c.get()}, runs,
-                                  (double)((size_t)kept * 4 + (size_t)uniq * 12))));
+    RAMA_TRY(reduce_runs(ctx, runs, key.get(), val.get(), dbits, out.i.get(), out.j.get(), out.c.get()));
     out.m = uniq;
     return RAMA_OK;
 }

@@ -1308,28 +1308,75 @@ __device__ __forceinline__ void block_max_into(uint32_t v, uint32_t *out)
     }
 }
 
-// Sums runs of equal keys in order of appearance (one thread per run, sequential adds): consumer of
-// the scan over the run heads; run number p writes its endpoint pair and cost at place p.
-struct ReduceRunsEmit {
-    static constexpr const char *tag = "ReduceRuns";
-    size_t m;
-    const uint64_t *key;
-    const uint32_t *val;
-    int dbits;
-    int32_t *io, *jo;
-    float *co;
-    __device__ __forceinline__ void operator()(size_t e, uint32_t head, uint32_t p) const
-    {
-        if (!head) return;
-        const uint64_t k = key[e];
-        float acc = __uint_as_float(val[e]);
-        for (size_t f = e + 1; f < m && key[f] == k; ++f) acc = acc + __uint_as_float(val[f]);
-        const uint32_t lo = (uint32_t)(k >> dbits);
+// Sums runs of equal keys in order of appearance (one thread per run, sequential adds) and writes run number p
+// -- endpoint pair and cost -- at place p.  The tiling is that of the scan over the run heads (HeadFlag), whose
+// tile offsets come in through `block_offsets`.  A workgroup keeps its 2048 values and head marks in LDS:
+// the heads are found from the keys in registers (the left neighbour's key by a shuffle), and a run is
+// added up from LDS instead of by a chain of dependent fetches of keys and values; only a run that
+// crosses the end of the tile goes on in memory.
+static __global__ __launch_bounds__(kBlock) void k_reduce_runs(size_t m, const uint64_t *key, const uint32_t *val, int dbits,
+                                                        const uint32_t *block_offsets, int32_t *io, int32_t *jo, float *co)
+{
+    __shared__ float s_val[kScanTile];
+    __shared__ uint8_t s_head[kScanTile];
+    __shared__ uint32_t wave_tot[4];
+    const int w = threadIdx.x >> 6, lane = lane_id();
+    const size_t tile0 = (size_t)blockIdx.x * kScanTile;
+    const int local0 = w * kScanWaveItems + lane;
+    uint64_t k[kScanItems];
+    uint32_t x[kScanItems], v[kScanItems];
+#pragma unroll
+    for (int q = 0; q < kScanItems; ++q) {
+        const int local = local0 + q * 64;
+        const size_t e = tile0 + (size_t)local;
+        k[q] = e < m ? key[e] : 0ull;
+        uint64_t left = __shfl_up(k[q], 1, 64);
+        if (lane == 0 && e > 0 && e < m) left = key[e - 1];
+        x[q] = (e < m && (e == 0 || k[q] != left)) ? 1u : 0u;
+        s_val[local] = e < m ? __uint_as_float(val[e]) : 0.0f;
+        s_head[local] = (uint8_t)(e < m ? x[q] : 1u);   // what lies behind the array ends every run
+    }
+    uint32_t carry = 0;
+#pragma unroll
+    for (int q = 0; q < kScanItems; ++q) {
+        const uint32_t inc = wave_inclusive_scan(x[q]);
+        v[q] = inc - x[q] + carry;
+        carry += wave_last(inc);
+    }
+    if (lane == 0) wave_tot[w] = carry;
+    __syncthreads();
+    uint32_t pre = block_offsets[blockIdx.x];
+#pragma unroll
+    for (int j = 0; j < 3; ++j)
+        if (j < w) pre += wave_tot[j];
+#pragma unroll
+    for (int q = 0; q < kScanItems; ++q) {
+        if (!x[q]) continue;
+        int pos = local0 + q * 64;
+        float acc = s_val[pos];
+        for (++pos; pos < kScanTile && !s_head[pos]; ++pos) acc = acc + s_val[pos];
+        if (pos == kScanTile)
+            for (size_t f = tile0 + kScanTile; f < m && key[f] == k[q]; ++f) acc = acc + __uint_as_float(val[f]);
+        const uint32_t p = v[q] + pre;
+        const uint32_t lo = (uint32_t)(k[q] >> dbits);
         io[p] = (int32_t)lo;
-        jo[p] = (int32_t)(lo + (uint32_t)(k & ((1ull << dbits) - 1ull)));
+        jo[p] = (int32_t)(lo + (uint32_t)(k[q] & ((1ull << dbits) - 1ull)));
         co[p] = acc;
     }
-};
+}
+
+// `plan`: the scan over HeadFlag{key} (scan_totals has run); uniq = its total
+inline rama_status reduce_runs(Ctx &ctx, const ScanPlan<uint32_t> &plan, const uint64_t *key, const uint32_t *val, int dbits,
+                               int32_t *io, int32_t *jo, float *co)
+{
+    if (plan.n == 0) return RAMA_OK;
+    {
+        ProfScope ps_(ctx, "k_reduce_runs", (double)(plan.n * 12 + (size_t)plan.total * 12));
+        k_reduce_runs<<<plan.nb, kBlock, 0, ctx.stream>>>(plan.n, key, val, dbits, plan.offs.get(), io, jo, co);
+    }
+    LAUNCH_TRY(ctx, "reduce_runs");
+    return RAMA_OK;
+}
 
 // position of the canonical edge (u,v), u<v, in rows given by rowptr over i (upper CSR) or -1
 __device__ __forceinline__ int32_t find_edge_in_row(const int32_t *rowptr, const int32_t *j, int32_t u, int32_t v)
