@@ -59,8 +59,20 @@ def event_name(rocprof_name):
         wide = ",wide" if args[3] == "u64" else ""
         return f"k_rs_local<{args[0]},{args[1]}{wide}>" if args[2] == "true" else f"k_rs_local<{args[0]}{wide}>"
     if n.startswith(("k_scan_", "k_sum_partial")) and "<" in n:
+        # the timers name the last functor by its tag: the class name without "Emit"; functors templated on a
+        # key type or a length append it where the library does (HeadFlagT<u64> -> HeadFlag64)
         head, args = n.split("<", 1)
-        functor = args.rstrip(">").split(",")[-1].split("<")[0].strip()
+        last = args.strip().rstrip(">").strip().split(",")[-1].strip()
+        functor, _, targ = last.partition("<")
+        targ = targ.strip().rstrip(">").strip()
+        if functor.endswith("Emit"):
+            functor = functor[:-4]
+        if functor == "HeadFlagT":
+            functor = "HeadFlag64" if targ == "u64" else "HeadFlag32"
+        elif functor == "Triangles" and targ == "u64":
+            functor = "Triangles64"
+        elif functor == "HasCycles" and targ == "7":
+            functor = "HasCycles7"
         return f"{head}<{functor}>"
     if n.startswith(("k_count_cycles<", "k_fill_cycles<")):
         # <longest walk, last level closes from the far endpoint>: the timers name the walk length only

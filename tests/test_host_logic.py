@@ -65,6 +65,14 @@ def test_profiler_names_map_onto_timer_names():
     assert f("void rama::k_rs_local<unsigned int, unsigned int, false, unsigned int>(unsigned int const*)") == "k_rs_local<u32>"
     assert f("void rama::k_rs_local<unsigned long, unsigned int, true, unsigned long>(unsigned long const*)") == "k_rs_local<u64,u32,wide>"
     assert f("rama::(anonymous namespace)::k_triangle_update(unsigned long, int const*)") == "k_triangle_update"
+    A = "rama::(anonymous namespace)::"
+    assert f(f"void rama::k_scan_emit<unsigned long, {A}SignFlags, {A}SplitSignEmit>(x)") == "k_scan_emit<SplitSign>"
+    assert f(f"void rama::k_scan_emit<unsigned int, {A}HeadFlagT<unsigned int>, {A}TrianglesEmit<unsigned int> >(x)") == "k_scan_emit<Triangles>"
+    assert f(f"void rama::k_scan_emit<unsigned int, {A}HeadFlagT<unsigned long>, {A}TrianglesEmit<unsigned long> >(x)") == "k_scan_emit<Triangles64>"
+    assert f(f"void rama::k_scan_reduce<unsigned int, {A}HeadFlagT<unsigned long> >(x)") == "k_scan_reduce<HeadFlag64>"
+    assert f(f"void rama::k_scan_reduce<unsigned int, {A}HasCycles<5> >(x)") == "k_scan_reduce<HasCycles>"
+    assert f(f"void rama::k_scan_reduce<unsigned int, {A}HasCycles<7> >(x)") == "k_scan_reduce<HasCycles7>"
+    assert f("rama::k_reduce_runs(unsigned long, unsigned long const*)") == "k_reduce_runs"
 
 
 def test_traffic_summary_scales_and_averages(tmp_path):
