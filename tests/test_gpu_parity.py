@@ -372,6 +372,21 @@ def test_canonicalisation_of_large_shuffled_input(rama, oracle32):
     assert np.array_equal(np_(got["c"]), wc)       # duplicates are added in input order on both sides
 
 
+@pytest.mark.parametrize("n,m", [(3, 20001), (2, 2049), (5, 4096), (40, 70000)])
+def test_canonicalisation_sums_long_runs_in_input_order(rama, oracle32, n, m):
+    # few nodes, many parallel edges: every run of equal pairs is thousands of entries long and crosses
+    # the 2048-entry tiles of the run reduction, some exactly at a tile's end; costs of mixed magnitude
+    # make the float sum depend on the order of the adds
+    rng = np.random.default_rng(n * 1000 + m)
+    i = rng.integers(0, n, m).astype(np.int32)
+    j = ((i + 1 + rng.integers(0, max(n - 1, 1), m)) % n).astype(np.int32)
+    c = (-np.abs(rng.normal(size=m)) * 10.0 ** rng.integers(-3, 4, m) - 1e-3).astype(np.float32)
+    wi, wj, wc = oracle32.canonicalise(n, i, j, c)
+    got = rama.contract(n, i, j, c, repeat=1)
+    assert np.array_equal(np_(got["i"]), wi) and np.array_equal(np_(got["j"]), wj)
+    assert np.array_equal(np_(got["c"]), wc)
+
+
 # --------------------------------------------------------------------------------------------
 # end to end
 # --------------------------------------------------------------------------------------------
