@@ -248,17 +248,28 @@ struct InnerFlag {
 // part of the contraction -- so it is done exactly once: the packed pair of every edge is stored
 // (loops get an all-ones key), the scan and the compaction then stream over the stored keys.
 constexpr uint64_t kLoopKey = ~0ull;
-// raw[e] = (lo, hi-lo) in two 32-bit halves; *maxdiff collects the largest hi-lo
+// raw[e] = (lo, hi-lo) in two 32-bit halves; *maxdiff collects the largest hi-lo.  A workgroup takes one tile of
+// the scan that follows (kScanTile edges) and leaves the number of edges that are no loops in tile_sums: the scan
+// over NotLoopKey then needs no pass of its own to count them.
 __global__ __launch_bounds__(kBlock) void k_relabel_keys(size_t m, const int32_t *i, const int32_t *j,
-                                                         const int32_t *fmap, uint64_t *raw, uint32_t *maxdiff)
+                                                         const int32_t *fmap, uint64_t *raw, uint32_t *maxdiff,
+                                                         uint32_t *tile_sums)
 {
-    size_t e = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    uint32_t diff = 0;
-    if (e < m) {
-        int32_t a = fmap[i[e]], b = fmap[j[e]];
-        diff = (uint32_t)abs(a - b);
-        raw[e] = (a == b) ? kLoopKey : (((uint64_t)(uint32_t)min(a, b) << 32) | diff);
+    const size_t base = (size_t)blockIdx.x * kScanTile + threadIdx.x;
+    uint32_t diff = 0, kept = 0;
+#pragma unroll
+    for (int q = 0; q < kScanItems; ++q) {
+        const size_t e = base + (size_t)q * kBlock;
+        if (e < m) {
+            const int32_t a = fmap[i[e]], b = fmap[j[e]];
+            const uint32_t d = (uint32_t)abs(a - b);
+            diff = d > diff ? d : diff;
+            kept += a != b ? 1u : 0u;
+            raw[e] = (a == b) ? kLoopKey : (((uint64_t)(uint32_t)min(a, b) << 32) | d);
+        }
     }
+    kept = block_sum(kept);
+    if (threadIdx.x == 0) tile_sums[blockIdx.x] = kept;
     block_max_into(diff, maxdiff);
 }
 struct NotLoopKey {
@@ -719,10 +730,11 @@ static rama_status contract_edges(Ctx &ctx, const Graph &g, const int32_t *fmap,
     RAMA_TRY(raw.alloc(ctx, m));
     {
         ProfScope ps_(ctx, "k_relabel_keys", (double)(m * 24));
-        k_relabel_keys<<<grid_for(m), kBlock, 0, ctx.stream>>>(m, g.i.get(), g.j.get(), fmap, raw.get(), keep.extra_ptr());
+        k_relabel_keys<<<keep.nb, kBlock, 0, ctx.stream>>>(m, g.i.get(), g.j.get(), fmap, raw.get(), keep.extra_ptr(),
+                                                           keep.sums.get());
     }
     LAUNCH_TRY(ctx, "relabel_keys");
-    RAMA_TRY((scan_totals<uint32_t>(ctx, NotLoopKey{raw.get()}, keep)));
+    RAMA_TRY((scan_totals<uint32_t>(ctx, NotLoopKey{raw.get()}, keep, true)));   // tile sums: left by k_relabel_keys
     const uint32_t kept = keep.total;
     const int dbits = bits_for((uint64_t)keep.extra_value[0] + 1);
     if (kept == 0) {

@@ -357,8 +357,10 @@ rama_status scan_plan_alloc(Ctx &ctx, size_t n, int extra, ScanPlan<TO> &plan)
     return RAMA_OK;
 }
 
+// `presummed`: the tile sums are in plan.sums already (the kernel that produced f's input left them there,
+// tile by tile of kScanTile items), so the reduce launch is skipped
 template <typename TO, typename F>
-rama_status scan_totals(Ctx &ctx, F f, ScanPlan<TO> &plan)
+rama_status scan_totals(Ctx &ctx, F f, ScanPlan<TO> &plan, bool presummed = false)
 {
     plan.total = 0;
     const unsigned nb = plan.nb;
@@ -367,8 +369,8 @@ rama_status scan_totals(Ctx &ctx, F f, ScanPlan<TO> &plan)
         // short arrays, one launch: tile sums, their scan by the last workgroup, total and extra words into the
         // mailbox; longer arrays: the scan of the tile sums is a launch of its own
         const uint64_t seq = ++ctx.mail_seq;
-        const bool fused = nb <= kScanFusedMax;
-        {
+        const bool fused = nb <= kScanFusedMax && !presummed;
+        if (!presummed) {
             ProfScope ps_(ctx, kernel_name<F>("k_scan_reduce"), (double)(plan.n * F::bytes));
             k_scan_reduce<TO, F><<<nb, kBlock, 0, ctx.stream>>>(f, plan.sums.get(), plan.n, plan.offs.get(),
                                                                fused ? ctx.ticket : nullptr, mailbox(ctx), seq, plan.extra);
@@ -383,7 +385,7 @@ rama_status scan_totals(Ctx &ctx, F f, ScanPlan<TO> &plan)
         const volatile uint64_t *m = mailbox(ctx);
         for (int k = 0; k < 1 + plan.extra; ++k) back[k] = (TO)m[1 + k];
     } else if (plan.n > 0) {
-        {
+        if (!presummed) {
             ProfScope ps_(ctx, kernel_name<F>("k_scan_reduce"), (double)(plan.n * F::bytes));
             k_scan_reduce<TO, F><<<nb, kBlock, 0, ctx.stream>>>(f, plan.sums.get(), plan.n, (TO *)nullptr, (uint32_t *)nullptr,
                                                                (uint64_t *)nullptr, 0, 0);
