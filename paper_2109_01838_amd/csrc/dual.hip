@@ -254,7 +254,7 @@ struct TrianglesEmit {
     const KT *key;
     const int32_t *rowptr, *j;
     int dbits;
-    uint32_t *skey, *sval;
+    uint32_t *skey;           // per slot 3t+k the edge id: the keys of the incidence sort, whose values are the slots themselves
     const int32_t *flag_in;   // raised by the kernel that built the keys
     int32_t *flag;            // where the host will look: flag_in is carried over
     const uint32_t *origin;
@@ -280,15 +280,8 @@ struct TrianglesEmit {
         int32_t e2 = find_edge_in_row(rowptr, j, j[e0], j[e1]);
         if (e2 < 0) { *flag = 1; e2 = 0; }
         skey[3 * t + 0] = (uint32_t)e0; skey[3 * t + 1] = (uint32_t)e1; skey[3 * t + 2] = (uint32_t)e2;
-        sval[3 * t + 0] = (uint32_t)(3 * t); sval[3 * t + 1] = (uint32_t)(3 * t + 1); sval[3 * t + 2] = (uint32_t)(3 * t + 2);
     }
 };
-
-__global__ __launch_bounds__(kBlock) void k_iota_u32(size_t n, uint32_t *p)
-{
-    size_t k = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    if (k < n) p[k] = (uint32_t)k;
-}
 
 // node triple (u,v,w) of every triangle from its edges (u,v) and (u,w); tri_act holds their numbers among the active edges
 __global__ __launch_bounds__(kBlock) void k_triangle_nodes(size_t T, const uint32_t *tri_act, const uint32_t *act_edge,
@@ -642,12 +635,7 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
         LAUNCH_TRY(ctx, "triangle_keys");
         if (T_kept > 0) {   // the sort also has to tell where the kept triangles end up
             RAMA_TRY(origin.alloc(ctx, nfan));
-            {
-                ProfScope ps_(ctx, "k_iota", (double)(nfan * 4));
-                k_iota_u32<<<grid_for(nfan), kBlock, 0, ctx.stream>>>(nfan, origin.get());
-            }
-            LAUNCH_TRY(ctx, "iota");
-            RAMA_TRY((radix_sort_pairs<KT, uint32_t>(ctx, tkey, origin, nfan, kbits)));
+            RAMA_TRY((radix_sort_pairs<KT, uint32_t>(ctx, tkey, origin, nfan, kbits, true)));   // values: the fan indices 0..nfan-1
         } else {
             RAMA_TRY((radix_sort_keys<KT>(ctx, tkey, nfan, kbits)));
         }
@@ -660,10 +648,10 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
         RAMA_TRY(skey.alloc(ctx, 3 * T));
         RAMA_TRY(slot.alloc(ctx, 3 * T));
         RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, 3 * T, 1, inc_heads)));
-        TrianglesEmit<KT> te{tkey.get(), rowptr.get(), aug.j.get(), dbits, skey.get(), slot.get(), flag.get(),
+        TrianglesEmit<KT> te{tkey.get(), rowptr.get(), aug.j.get(), dbits, skey.get(), flag.get(),
                              (int32_t *)inc_heads.extra_ptr(), T_kept > 0 ? origin.get() : nullptr, cs.fan_end[kCycleLists - 1], cs.fan_end[kCycleLists],
                              T_kept > 0 ? prev->ct.get() : nullptr, ct.get()};
-        RAMA_TRY((scan_emit<uint32_t>(ctx, HeadFlagT<KT>{tkey.get()}, te, heads, (double)(T * 32 + T_kept * 24))));
+        RAMA_TRY((scan_emit<uint32_t>(ctx, HeadFlagT<KT>{tkey.get()}, te, heads, (double)(T * 20 + T_kept * 24))));
         return RAMA_OK;
     };
     if (kbits <= 32) RAMA_TRY(triangles(uint32_t{}));
@@ -671,7 +659,7 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
     if (info) info->n_triangles = (int64_t)T;
     // ---- incidence: slots of every edge in ascending triangle order ----------------------------
     // (if the flag is up, the edge ids below are placeholders -- all valid indices -- and the result is discarded)
-    RAMA_TRY((radix_sort_pairs<uint32_t, uint32_t>(ctx, skey, slot, 3 * T, bits_for((uint64_t)ma))));
+    RAMA_TRY((radix_sort_pairs<uint32_t, uint32_t>(ctx, skey, slot, 3 * T, bits_for((uint64_t)ma), true)));   // values: the slots 0..3T-1
     Buf<uint32_t> act_edge, act_start;
     size_t na = 0;
     {

@@ -673,7 +673,7 @@ __global__ __launch_bounds__(kBlock) void k_rs_scatter(const K *kin, const V *vi
         size_t idx = wave_base + (size_t)r * 64 + lane;
         bool valid = idx < n;
         key[r] = valid ? kin[idx] : (K)0;
-        if (HAS_V) val[r] = valid ? (uint32_t)vin[idx] : 0u;
+        if (HAS_V) val[r] = valid ? (vin ? (uint32_t)vin[idx] : (uint32_t)idx) : 0u;   // no array of values: a key's value is its place
     }
 #pragma unroll
     for (int r = 0; r < kSortItems; ++r) {
@@ -968,7 +968,7 @@ inline const char *rs_local_name()
 // stable LSD passes over the key bits [shift, shift + total_bits); a/b swap with every pass
 template <typename K, typename V, bool HAS_V>
 rama_status radix_passes(Ctx &ctx, K *&ka, V *&va, K *&kb, V *&vb, size_t n, int shift, int total_bits, uint32_t *hist,
-                         uint32_t *offs, bool *result_in_b)
+                         uint32_t *offs, bool *result_in_b, bool *iota)
 {
     const uint32_t nb = grid_for(n, SortTile<K>::size);
     const int passes = (total_bits + kRadixBits - 1) / kRadixBits;
@@ -980,9 +980,11 @@ rama_status radix_passes(Ctx &ctx, K *&ka, V *&va, K *&kb, V *&vb, size_t n, int
             k_rs_hist<K><<<nb, kBlock, 0, ctx.stream>>>(ka, hist, n, shift, bits, nb);
         }
         LAUNCH_TRY(ctx, "rs_hist");
+        const V *vin = (HAS_V && *iota) ? (const V *)nullptr : va;   // the first pass of a sort whose values are the places 0..n-1
+        *iota = false;
         if (nb <= kSortLocalScanTiles) {
             ProfScope ps_(ctx, rs_scatter_name<K, HAS_V>(), (double)(n * (2 * sizeof(K) + (HAS_V ? 8 : 0))));
-            k_rs_scatter<K, V, HAS_V, true><<<nb, kBlock, 0, ctx.stream>>>(ka, va, kb, vb, hist, n, shift, bits, nb);
+            k_rs_scatter<K, V, HAS_V, true><<<nb, kBlock, 0, ctx.stream>>>(ka, vin, kb, vb, hist, n, shift, bits, nb);
         } else {
             {
                 ProfScope ps_(ctx, "k_rs_rowscan", (double)(((size_t)nb << bits) * 8));
@@ -990,7 +992,7 @@ rama_status radix_passes(Ctx &ctx, K *&ka, V *&va, K *&kb, V *&vb, size_t n, int
             }
             LAUNCH_TRY(ctx, "rs_rowscan");
             ProfScope ps_(ctx, rs_scatter_name<K, HAS_V>(), (double)(n * (2 * sizeof(K) + (HAS_V ? 8 : 0))));
-            k_rs_scatter<K, V, HAS_V, false><<<nb, kBlock, 0, ctx.stream>>>(ka, va, kb, vb, offs, n, shift, bits, nb);
+            k_rs_scatter<K, V, HAS_V, false><<<nb, kBlock, 0, ctx.stream>>>(ka, vin, kb, vb, offs, n, shift, bits, nb);
         }
         LAUNCH_TRY(ctx, "rs_scatter");
         std::swap(ka, kb);
@@ -1040,8 +1042,15 @@ rama_status split_sort_tail(Ctx &ctx, K *ka, V *va, K *kb, V *vb, size_t n, int 
 // in-LDS sort of the rest.  Should the keys be so uneven that some workgroup cannot hold its
 // segments, the array (by then stably sorted by the top bits, which does no harm) is sorted by
 // passes over all bits instead.
+// `iota`: the values are the places 0..n-1 and va holds nothing yet -- the first pass makes them up instead of
+// reading them (an array one workgroup sorts alone gets them from a fill first).
+static __global__ __launch_bounds__(kBlock) void k_iota(size_t n, uint32_t *p)
+{
+    size_t k = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (k < n) p[k] = (uint32_t)k;
+}
 template <typename K, typename V, bool HAS_V>
-rama_status radix_sort_impl(Ctx &ctx, K *ka, V *va, K *kb, V *vb, size_t n, int total_bits, bool *result_in_b)
+rama_status radix_sort_impl(Ctx &ctx, K *ka, V *va, K *kb, V *vb, size_t n, int total_bits, bool *result_in_b, bool iota = false)
 {
     *result_in_b = false;
     if (n <= 1 || total_bits <= 0) return RAMA_OK;
@@ -1050,6 +1059,12 @@ rama_status radix_sort_impl(Ctx &ctx, K *ka, V *va, K *kb, V *vb, size_t n, int 
     if (total_bits < 8 * (int)sizeof(K) && ctx.sort_split_min < (size_t)INT64_MAX) {
         const bool narrow = total_bits <= 32 && n <= (size_t)LocalSort<uint32_t>::cap;
         const bool wide = !narrow && n <= (size_t)LocalSort<uint64_t>::cap;
+        if ((narrow || wide) && HAS_V && iota) {
+            ProfScope ps_(ctx, "k_iota", (double)(n * 4));
+            k_iota<<<grid_for(n), kBlock, 0, ctx.stream>>>(n, (uint32_t *)va);
+            LAUNCH_TRY(ctx, "iota");
+            iota = false;
+        }
         if (narrow || wide) {
             if (narrow) {
                 ProfScope ps_(ctx, rs_local_name<K, HAS_V, uint32_t>(), (double)(n * (2 * sizeof(K) + (HAS_V ? 8 : 0))));
@@ -1084,7 +1099,7 @@ rama_status radix_sort_impl(Ctx &ctx, K *ka, V *va, K *kb, V *vb, size_t n, int 
         const bool split = narrow || plan(LocalSort<uint64_t>::cap, &top_bits);
         if (split) {
             const int low_bits = total_bits - top_bits;
-            RAMA_TRY((radix_passes<K, V, HAS_V>(ctx, ka, va, kb, vb, n, low_bits, top_bits, hist.get(), offs.get(), result_in_b)));
+            RAMA_TRY((radix_passes<K, V, HAS_V>(ctx, ka, va, kb, vb, n, low_bits, top_bits, hist.get(), offs.get(), result_in_b, &iota)));
             bool done = false;
             if (narrow) RAMA_TRY((split_sort_tail<K, V, HAS_V, uint32_t>(ctx, ka, va, kb, vb, n, low_bits, &done)));
             else RAMA_TRY((split_sort_tail<K, V, HAS_V, uint64_t>(ctx, ka, va, kb, vb, n, low_bits, &done)));
@@ -1094,21 +1109,28 @@ rama_status radix_sort_impl(Ctx &ctx, K *ka, V *va, K *kb, V *vb, size_t n, int 
             }
         }
     }
-    return radix_passes<K, V, HAS_V>(ctx, ka, va, kb, vb, n, 0, total_bits, hist.get(), offs.get(), result_in_b);
+    return radix_passes<K, V, HAS_V>(ctx, ka, va, kb, vb, n, 0, total_bits, hist.get(), offs.get(), result_in_b, &iota);
 }
 
 // Convenience wrappers working on Buf pairs: after the call `k`/`v` hold the sorted data.
+// `iota`: v comes in unset and stands for the values 0..n-1
 template <typename K, typename V>
-rama_status radix_sort_pairs(Ctx &ctx, Buf<K> &k, Buf<V> &v, size_t n, int total_bits)
+rama_status radix_sort_pairs(Ctx &ctx, Buf<K> &k, Buf<V> &v, size_t n, int total_bits, bool iota = false)
 {
     static_assert(sizeof(V) == 4, "32-bit payload");
-    if (n <= 1) return RAMA_OK;
+    if (n <= 1 || total_bits <= 0) {
+        if (iota && n >= 1) {
+            k_iota<<<grid_for(n), kBlock, 0, ctx.stream>>>(n, (uint32_t *)v.get());
+            LAUNCH_TRY(ctx, "iota");
+        }
+        return RAMA_OK;
+    }
     Buf<K> k2;
     Buf<V> v2;
     RAMA_TRY(k2.alloc(ctx, n));
     RAMA_TRY(v2.alloc(ctx, n));
     bool in_b = false;
-    RAMA_TRY((radix_sort_impl<K, V, true>(ctx, k.get(), v.get(), k2.get(), v2.get(), n, total_bits, &in_b)));
+    RAMA_TRY((radix_sort_impl<K, V, true>(ctx, k.get(), v.get(), k2.get(), v2.get(), n, total_bits, &in_b, iota)));
     if (in_b) { k.swap(k2); v.swap(v2); }
     return RAMA_OK;
 }
