@@ -419,6 +419,9 @@ struct Graph {
     int64_t m = 0;
     Buf<int32_t> i, j;
     Buf<float> c;
+    // optional, left by the kernel that wrote c: per tile of 2048 edges the number of positive (low half) and
+    // negative (high half) costs; valid only while c is what that kernel wrote
+    Buf<uint64_t> sign_sums;
 };
 
 constexpr int kMaxCycleLen = RAMA_MAX_CYCLE_LEN;

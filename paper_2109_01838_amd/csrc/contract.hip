@@ -734,7 +734,7 @@ static rama_status contract_edges(Ctx &ctx, const Graph &g, const int32_t *fmap,
                                                            keep.sums.get());
     }
     LAUNCH_TRY(ctx, "relabel_keys");
-    RAMA_TRY((scan_totals<uint32_t>(ctx, NotLoopKey{raw.get()}, keep, true)));   // tile sums: left by k_relabel_keys
+    RAMA_TRY((scan_totals<uint32_t>(ctx, NotLoopKey{raw.get()}, keep, keep.sums.get())));   // tile sums: left by k_relabel_keys
     const uint32_t kept = keep.total;
     const int dbits = bits_for((uint64_t)keep.extra_value[0] + 1);
     if (kept == 0) {
@@ -759,7 +759,7 @@ static rama_status contract_edges(Ctx &ctx, const Graph &g, const int32_t *fmap,
     RAMA_TRY(out.i.alloc(ctx, uniq));
     RAMA_TRY(out.j.alloc(ctx, uniq));
     RAMA_TRY(out.c.alloc(ctx, uniq));
-    RAMA_TRY(reduce_runs(ctx, runs, key.get(), val.get(), dbits, out.i.get(), out.j.get(), out.c.get()));
+    RAMA_TRY(reduce_runs(ctx, runs, key.get(), val.get(), dbits, out.i.get(), out.j.get(), out.c.get(), &out.sign_sums));
     out.m = uniq;
     return RAMA_OK;
 }

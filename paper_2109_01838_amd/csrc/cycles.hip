@@ -1084,7 +1084,7 @@ rama_status find_cycles(Ctx &ctx, const Graph &g, int max_len, bool shortest_onl
     // sign partition
     ScanPlan<uint64_t> signs;
     RAMA_TRY((scan_plan_alloc<uint64_t>(ctx, m, 0, signs)));
-    RAMA_TRY((scan_totals<uint64_t>(ctx, SignFlags{g.c.get()}, signs)));
+    RAMA_TRY((scan_totals<uint64_t>(ctx, SignFlags{g.c.get()}, signs, g.sign_sums.get())));   // tile sums, if the graph brings them
     const uint32_t mp = (uint32_t)signs.total, mr = (uint32_t)(signs.total >> 32);
     out.n_attractive = mp; out.n_repulsive = mr;
     if (mp == 0 || mr == 0) return RAMA_OK;

@@ -463,6 +463,7 @@ rama_status lower_bound_now(Ctx &ctx, const float *ce, size_t m, const float *ct
 rama_status copy_graph(Ctx &ctx, const Graph &g, Graph &out)
 {
     out.n = g.n; out.m = g.m;
+    out.sign_sums.reset();
     size_t m = (size_t)(g.m > 0 ? g.m : 1);
     RAMA_TRY(out.i.alloc(ctx, m));
     RAMA_TRY(out.j.alloc(ctx, m));
@@ -737,6 +738,7 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
     }
     out.n = aug.n; out.m = aug.m;
     out.i = std::move(aug.i); out.j = std::move(aug.j); out.c = std::move(aug.c);
+    out.sign_sums.reset();   // the costs are new
     return RAMA_OK;
 }
 

@@ -7,20 +7,26 @@ namespace rama {
 namespace {
 
 // flags[0]: endpoint out of range or non-finite cost; flags[1]: list is not canonical;
-// flags[2]: largest |i-j| of a valid edge
+// flags[2]: largest |i-j| of a valid edge.  A workgroup takes one tile of the scan over NotLoop (kScanTile
+// edges) and leaves the number of edges that are no self-loops in tile_sums, so that scan needs no counting pass.
 __global__ __launch_bounds__(kBlock) void k_validate(int32_t n, size_t m, const int32_t *i, const int32_t *j,
-                                                     const float *c, int32_t *flags)
+                                                     const float *c, int32_t *flags, uint32_t *tile_sums)
 {
-    size_t e = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    uint32_t diff = 0;
-    if (e < m) {
+    const size_t base = (size_t)blockIdx.x * kScanTile + threadIdx.x;
+    uint32_t diff = 0, kept = 0;
+#pragma unroll
+    for (int q = 0; q < kScanItems; ++q) {
+        const size_t e = base + (size_t)q * kBlock;
+        if (e >= m) continue;
         int32_t a = i[e], b = j[e];
         float w = c[e];
+        kept += a != b ? 1u : 0u;
         bool bad = a < 0 || a >= n || b < 0 || b >= n || !(fabsf(w) <= 3.402823466e+38f);
         if (bad) {
             flags[0] = 1;
         } else {
-            diff = (uint32_t)abs(a - b);
+            const uint32_t d = (uint32_t)abs(a - b);
+            diff = d > diff ? d : diff;
             bool canon = a < b;
             if (canon && e > 0) {
                 int32_t pa = i[e - 1], pb = j[e - 1];
@@ -29,6 +35,8 @@ __global__ __launch_bounds__(kBlock) void k_validate(int32_t n, size_t m, const 
             if (!canon) flags[1] = 1;
         }
     }
+    kept = block_sum(kept);
+    if (threadIdx.x == 0) tile_sums[blockIdx.x] = kept;
     block_max_into(diff, (uint32_t *)&flags[2]);
 }
 
@@ -80,9 +88,11 @@ rama_status canonicalise(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const
     Buf<int32_t> flags;
     RAMA_TRY(flags.alloc(ctx, 3));
     RAMA_TRY(fill<int32_t>(ctx, flags.get(), 0, 3));
+    ScanPlan<uint32_t> keep;
+    RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, (size_t)m, 0, keep)));
     {
         ProfScope ps_(ctx, "k_validate", (double)((size_t)m * 12));
-        k_validate<<<grid_for(m), kBlock, 0, ctx.stream>>>(n, (size_t)m, i, j, c, flags.get());
+        k_validate<<<keep.nb, kBlock, 0, ctx.stream>>>(n, (size_t)m, i, j, c, flags.get(), keep.sums.get());
     }
     LAUNCH_TRY(ctx, "validate");
     int32_t hf[3];
@@ -99,9 +109,7 @@ rama_status canonicalise(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const
         return RAMA_OK;
     }
     const int nbits = bits_for((uint64_t)n), dbits = bits_for((uint64_t)hf[2] + 1);
-    ScanPlan<uint32_t> keep;
-    RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, (size_t)m, 0, keep)));
-    RAMA_TRY((scan_totals<uint32_t>(ctx, NotLoop{i, j}, keep)));
+    RAMA_TRY((scan_totals<uint32_t>(ctx, NotLoop{i, j}, keep, keep.sums.get())));   // tile sums: left by k_validate
     const uint32_t kept = keep.total;
     if (kept == 0) {
         RAMA_TRY(out.i.alloc(ctx, 1));
@@ -124,7 +132,7 @@ rama_status canonicalise(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const
     RAMA_TRY(out.i.alloc(ctx, uniq));
     RAMA_TRY(out.j.alloc(ctx, uniq));
     RAMA_TRY(out.c.alloc(ctx, uniq));
-    RAMA_TRY(reduce_runs(ctx, runs, key.get(), val.get(), dbits, out.i.get(), out.j.get(), out.c.get()));
+    RAMA_TRY(reduce_runs(ctx, runs, key.get(), val.get(), dbits, out.i.get(), out.j.get(), out.c.get(), &out.sign_sums));
     out.m = uniq;
     return RAMA_OK;
 }

@@ -357,13 +357,15 @@ rama_status scan_plan_alloc(Ctx &ctx, size_t n, int extra, ScanPlan<TO> &plan)
     return RAMA_OK;
 }
 
-// `presummed`: the tile sums are in plan.sums already (the kernel that produced f's input left them there,
-// tile by tile of kScanTile items), so the reduce launch is skipped
+// `presums`: the tile sums exist already (the kernel that produced f's input left them, tile by tile of
+// kScanTile items, in plan.sums or in an array of its own), so the counting launch is skipped
 template <typename TO, typename F>
-rama_status scan_totals(Ctx &ctx, F f, ScanPlan<TO> &plan, bool presummed = false)
+rama_status scan_totals(Ctx &ctx, F f, ScanPlan<TO> &plan, const TO *presums = nullptr)
 {
     plan.total = 0;
     const unsigned nb = plan.nb;
+    const bool presummed = presums != nullptr;
+    const TO *sums = presummed ? presums : plan.sums.get();
     TO back[3] = {0, 0, 0};
     if (plan.n > 0 && nb <= kScanMidMax) {
         // short arrays, one launch: tile sums, their scan by the last workgroup, total and extra words into the
@@ -378,7 +380,7 @@ rama_status scan_totals(Ctx &ctx, F f, ScanPlan<TO> &plan, bool presummed = fals
         LAUNCH_TRY(ctx, "scan_reduce");
         if (!fused) {
             ProfScope ps_(ctx, "k_scan_mid", (double)((size_t)nb * 2 * sizeof(TO)));
-            k_scan_mid<TO><<<1, kBlock, 0, ctx.stream>>>(plan.sums.get(), plan.offs.get(), nb, mailbox(ctx), seq, plan.extra);
+            k_scan_mid<TO><<<1, kBlock, 0, ctx.stream>>>(sums, plan.offs.get(), nb, mailbox(ctx), seq, plan.extra);
             LAUNCH_TRY(ctx, "scan_mid");
         }
         RAMA_TRY(wait_mail(ctx, seq));
@@ -393,7 +395,7 @@ rama_status scan_totals(Ctx &ctx, F f, ScanPlan<TO> &plan, bool presummed = fals
         LAUNCH_TRY(ctx, "scan_reduce");
         // the nested scan writes nb+1 words (offsets and total), nothing beyond: the caller's extra words,
         // which sit one further on, stay as they are
-        RAMA_TRY((exclusive_scan<TO, PtrInput<TO>>(ctx, PtrInput<TO>{plan.sums.get()}, plan.offs.get(), nb)));
+        RAMA_TRY((exclusive_scan<TO, PtrInput<TO>>(ctx, PtrInput<TO>{sums}, plan.offs.get(), nb)));
         RAMA_TRY(read_back(ctx, back, plan.offs.get() + nb, (size_t)(1 + plan.extra) * sizeof(TO)));
     } else if (plan.extra > 0) {
         RAMA_TRY(read_back(ctx, back + 1, plan.extra_ptr(), (size_t)plan.extra * sizeof(TO)));
@@ -1338,8 +1340,12 @@ __device__ __forceinline__ void block_max_into(uint32_t v, uint32_t *out)
 // the heads are found from the keys in registers (the left neighbour's key by a shuffle), and a run is
 // added up from LDS instead of by a chain of dependent fetches of keys and values; only a run that
 // crosses the end of the tile goes on in memory.
-static __global__ __launch_bounds__(kBlock) void k_reduce_runs(size_t m, const uint64_t *key, const uint32_t *val, int dbits,
-                                                        const uint32_t *block_offsets, int32_t *io, int32_t *jo, float *co)
+static // `sign_sums` (optional, zero on entry): per tile of kScanTile *outputs* the number of positive costs (low half)
+// and of negative costs (high half) -- the tile sums of the scan that splits the new graph by sign, which then
+// needs no counting pass.  A workgroup's outputs are contiguous and at most a tile long: two atomic adds.
+__global__ __launch_bounds__(kBlock) void k_reduce_runs(size_t m, const uint64_t *key, const uint32_t *val, int dbits,
+                                                        const uint32_t *block_offsets, int32_t *io, int32_t *jo, float *co,
+                                                        unsigned long long *sign_sums)
 {
     __shared__ float s_val[kScanTile];
     __shared__ uint8_t s_head[kScanTile];
@@ -1369,10 +1375,13 @@ static __global__ __launch_bounds__(kBlock) void k_reduce_runs(size_t m, const u
     }
     if (lane == 0) wave_tot[w] = carry;
     __syncthreads();
-    uint32_t pre = block_offsets[blockIdx.x];
+    const uint32_t pre0 = block_offsets[blockIdx.x];
+    uint32_t pre = pre0;
 #pragma unroll
     for (int j = 0; j < 3; ++j)
         if (j < w) pre += wave_tot[j];
+    const uint32_t tile_a = pre0 / (uint32_t)kScanTile;
+    unsigned long long sa = 0ull, sb = 0ull;   // sign counts of the outputs in tile_a and in the tile behind it
 #pragma unroll
     for (int q = 0; q < kScanItems; ++q) {
         if (!x[q]) continue;
@@ -1386,17 +1395,36 @@ static __global__ __launch_bounds__(kBlock) void k_reduce_runs(size_t m, const u
         io[p] = (int32_t)lo;
         jo[p] = (int32_t)(lo + (uint32_t)(k[q] & ((1ull << dbits) - 1ull)));
         co[p] = acc;
+        const unsigned long long sgn = acc > 0.0f ? 1ull : (acc < 0.0f ? (1ull << 32) : 0ull);
+        if (p / (uint32_t)kScanTile == tile_a) sa += sgn;
+        else sb += sgn;
+    }
+    if (sign_sums) {   // uniform
+        sa = block_sum(sa);
+        sb = block_sum(sb);
+        if (threadIdx.x == 0) {
+            if (sa) atomicAdd(&sign_sums[tile_a], sa);
+            if (sb) atomicAdd(&sign_sums[tile_a + 1], sb);
+        }
     }
 }
 
-// `plan`: the scan over HeadFlag{key} (scan_totals has run); uniq = its total
+// `plan`: the scan over HeadFlag{key} (scan_totals has run); uniq = its total.  `sign_sums` (optional): an array of
+// ceil(uniq / kScanTile) words that gets the sign counts of the output costs per tile.
 inline rama_status reduce_runs(Ctx &ctx, const ScanPlan<uint32_t> &plan, const uint64_t *key, const uint32_t *val, int dbits,
-                               int32_t *io, int32_t *jo, float *co)
+                               int32_t *io, int32_t *jo, float *co, Buf<uint64_t> *sign_sums = nullptr)
 {
     if (plan.n == 0) return RAMA_OK;
+    unsigned long long *ss = nullptr;
+    if (sign_sums) {
+        const size_t tiles = ((size_t)plan.total + kScanTile - 1) / kScanTile;
+        RAMA_TRY(sign_sums->alloc(ctx, tiles > 0 ? tiles : 1));
+        RAMA_TRY(fill<uint64_t>(ctx, sign_sums->get(), 0ull, tiles > 0 ? tiles : 1));
+        ss = (unsigned long long *)sign_sums->get();
+    }
     {
         ProfScope ps_(ctx, "k_reduce_runs", (double)(plan.n * 12 + (size_t)plan.total * 12));
-        k_reduce_runs<<<plan.nb, kBlock, 0, ctx.stream>>>(plan.n, key, val, dbits, plan.offs.get(), io, jo, co);
+        k_reduce_runs<<<plan.nb, kBlock, 0, ctx.stream>>>(plan.n, key, val, dbits, plan.offs.get(), io, jo, co, ss);
     }
     LAUNCH_TRY(ctx, "reduce_runs");
     return RAMA_OK;
