@@ -751,10 +751,12 @@ static rama_status contract_edges(Ctx &ctx, const Graph &g, const int32_t *fmap,
                                   keep, (double)(m * 4 + (size_t)kept * 12))));
     keep.offs.reset();
     raw.reset();
-    RAMA_TRY((radix_sort_pairs<uint64_t, uint32_t>(ctx, key, val, kept, nbits + dbits)));
+    Buf<uint32_t> head_sums;   // heads per scan tile, if the sort's last kernel could count them
+    RAMA_TRY((radix_sort_pairs<uint64_t, uint32_t>(ctx, key, val, kept, nbits + dbits, false, &head_sums)));
     ScanPlan<uint32_t> runs;
     RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, kept, 0, runs)));
-    RAMA_TRY((scan_totals<uint32_t>(ctx, HeadFlag{key.get()}, runs)));
+    RAMA_TRY((scan_totals<uint32_t>(ctx, HeadFlag{key.get()}, runs, head_sums.get())));
+    head_sums.reset();
     const uint32_t uniq = runs.total;
     RAMA_TRY(out.i.alloc(ctx, uniq));
     RAMA_TRY(out.j.alloc(ctx, uniq));

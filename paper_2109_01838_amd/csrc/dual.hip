@@ -634,15 +634,17 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
                                                                           tkey.get(), flag.get());
         }
         LAUNCH_TRY(ctx, "triangle_keys");
+        Buf<uint32_t> head_sums;   // heads per scan tile, if the sort's last kernel could count them
         if (T_kept > 0) {   // the sort also has to tell where the kept triangles end up
             RAMA_TRY(origin.alloc(ctx, nfan));
-            RAMA_TRY((radix_sort_pairs<KT, uint32_t>(ctx, tkey, origin, nfan, kbits, true)));   // values: the fan indices 0..nfan-1
+            RAMA_TRY((radix_sort_pairs<KT, uint32_t>(ctx, tkey, origin, nfan, kbits, true, &head_sums)));   // values: the fan indices 0..nfan-1
         } else {
-            RAMA_TRY((radix_sort_keys<KT>(ctx, tkey, nfan, kbits)));
+            RAMA_TRY((radix_sort_keys<KT>(ctx, tkey, nfan, kbits, &head_sums)));
         }
         ScanPlan<uint32_t> heads;
         RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, nfan, 0, heads)));
-        RAMA_TRY((scan_totals<uint32_t>(ctx, HeadFlagT<KT>{tkey.get()}, heads)));
+        RAMA_TRY((scan_totals<uint32_t>(ctx, HeadFlagT<KT>{tkey.get()}, heads, head_sums.get())));
+        head_sums.reset();
         T = heads.total;
         RAMA_TRY(ct.alloc(ctx, 3 * T));
         if (T_kept > 0) RAMA_TRY(fill<float>(ctx, ct.get(), 0.0f, 3 * T));   // otherwise the consumer below zeroes what it creates

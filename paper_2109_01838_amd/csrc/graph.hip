@@ -124,10 +124,12 @@ rama_status canonicalise(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const
     RAMA_TRY((scan_emit<uint32_t>(ctx, NotLoop{i, j}, PackEdgesEmit{i, j, c, dbits, key.get(), val.get()}, keep,
                                   (double)((size_t)m * 4 + (size_t)kept * 12))));
     keep.offs.reset();
-    RAMA_TRY((radix_sort_pairs<uint64_t, uint32_t>(ctx, key, val, kept, nbits + dbits)));
+    Buf<uint32_t> head_sums;   // heads per scan tile, if the sort's last kernel could count them
+    RAMA_TRY((radix_sort_pairs<uint64_t, uint32_t>(ctx, key, val, kept, nbits + dbits, false, &head_sums)));
     ScanPlan<uint32_t> runs;
     RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, kept, 0, runs)));
-    RAMA_TRY((scan_totals<uint32_t>(ctx, HeadFlag{key.get()}, runs)));
+    RAMA_TRY((scan_totals<uint32_t>(ctx, HeadFlag{key.get()}, runs, head_sums.get())));
+    head_sums.reset();
     const uint32_t uniq = runs.total;
     RAMA_TRY(out.i.alloc(ctx, uniq));
     RAMA_TRY(out.j.alloc(ctx, uniq));

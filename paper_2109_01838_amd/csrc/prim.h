@@ -849,7 +849,8 @@ struct LocalSort {
 };
 template <typename K, typename V, bool HAS_V, typename LK>
 __global__ __launch_bounds__(kLocalSortWaves * 64) void k_rs_local(const K *kin, const V *vin, K *kout, V *vout,
-                                                                   const uint32_t *bounds, int low_bits, uint32_t n_all)
+                                                                   const uint32_t *bounds, int low_bits, uint32_t n_all,
+                                                                   uint32_t *head_sums)
 {
     constexpr int NW = kLocalSortWaves;
     constexpr int kItems = LocalSort<LK>::items;
@@ -950,10 +951,48 @@ __global__ __launch_bounds__(kLocalSortWaves * 64) void k_rs_local(const K *kin,
         shift += bits;
         remaining -= bits;
     }
-    for (uint32_t idx = tid; idx < cnt; idx += kThreads) {
-        kout[beg + idx] = (K)((K)skey[idx] + base);
-        if (HAS_V) vout[beg + idx] = (V)sval[idx];
+    if (!head_sums) {   // uniform
+        for (uint32_t idx = tid; idx < cnt; idx += kThreads) {
+            kout[beg + idx] = (K)((K)skey[idx] + base);
+            if (HAS_V) vout[beg + idx] = (V)sval[idx];
+        }
+        return;
     }
+    // The sorted keys are at hand: count the heads of runs of equal keys per tile of kScanTile places, for a scan
+    // over the heads that follows the sort (it then needs no counting pass).  A workgroup's first key starts a
+    // new segment of top bits, so it is a head; its places span at most kHeadTiles tiles.
+    constexpr int kHeadTiles = kCap / kScanTile + 1;
+    __shared__ uint32_t s_heads[kHeadTiles];
+    if (tid < kHeadTiles) s_heads[tid] = 0;
+    __syncthreads();
+    const uint32_t tile0 = beg / (uint32_t)kScanTile;
+    for (uint32_t idx0 = 0; idx0 < cnt; idx0 += kThreads) {
+        const uint32_t idx = idx0 + tid;
+        const bool valid = idx < cnt;
+        bool head = false;
+        if (valid) {
+            const LK k = skey[idx];
+            kout[beg + idx] = (K)((K)k + base);
+            if (HAS_V) vout[beg + idx] = (V)sval[idx];
+            head = idx == 0 || k != skey[idx - 1];
+        }
+        // the wave's 64 places lie in one tile or in two
+        const uint32_t first = beg + idx0 + (uint32_t)w * 64u;
+        const uint32_t t_lo = first / (uint32_t)kScanTile, t_hi = (first + 63u) / (uint32_t)kScanTile;
+        const uint64_t heads = __ballot(head);
+        if (t_lo == t_hi) {
+            if (lane == 0 && heads) atomicAdd(&s_heads[t_lo - tile0], (uint32_t)__popcll(heads));
+        } else {
+            const uint32_t n_lo = t_hi * (uint32_t)kScanTile - first;     // places of the wave that lie in the lower tile
+            const uint64_t low = (~0ull) >> (64u - n_lo);
+            if (lane == 0) {
+                if (heads & low) atomicAdd(&s_heads[t_lo - tile0], (uint32_t)__popcll(heads & low));
+                if (heads & ~low) atomicAdd(&s_heads[t_hi - tile0], (uint32_t)__popcll(heads & ~low));
+            }
+        }
+    }
+    __syncthreads();
+    if (tid < kHeadTiles && s_heads[tid]) atomicAdd(&head_sums[tile0 + tid], s_heads[tid]);
 }
 
 template <typename K, bool HAS_V, typename LK>
@@ -1006,10 +1045,19 @@ rama_status radix_passes(Ctx &ctx, K *&ka, V *&va, K *&kb, V *&vb, size_t n, int
     return RAMA_OK;
 }
 
+// zeroed counters for the heads per scan tile of an array of n sorted keys (k_rs_local fills them)
+inline rama_status head_sums_alloc(Ctx &ctx, size_t n, Buf<uint32_t> *head_sums)
+{
+    if (!head_sums) return RAMA_OK;
+    const size_t tiles = (n + kScanTile - 1) / kScanTile + 1;
+    RAMA_TRY(head_sums->alloc(ctx, tiles));
+    return fill<uint32_t>(ctx, head_sums->get(), 0u, tiles);
+}
+
 // bounds + in-LDS sort of an array already sorted by its bits above low_bits; *done stays false
 // when some workgroup could not hold its segments (nothing has been written then)
 template <typename K, typename V, bool HAS_V, typename LK>
-rama_status split_sort_tail(Ctx &ctx, K *ka, V *va, K *kb, V *vb, size_t n, int low_bits, bool *done)
+rama_status split_sort_tail(Ctx &ctx, K *ka, V *va, K *kb, V *vb, size_t n, int low_bits, bool *done, Buf<uint32_t> *head_sums)
 {
     using LS = LocalSort<LK>;
     *done = false;
@@ -1028,9 +1076,11 @@ rama_status split_sort_tail(Ctx &ctx, K *ka, V *va, K *kb, V *vb, size_t n, int 
     uint32_t over = 0;
     RAMA_TRY(read_back(ctx, &over, oversize, 4));
     if (over) return RAMA_OK;
+    RAMA_TRY(head_sums_alloc(ctx, n, head_sums));
     {
         ProfScope ps_(ctx, rs_local_name<K, HAS_V, LK>(), (double)(n * (2 * sizeof(K) + (HAS_V ? 8 : 0))));
-        k_rs_local<K, V, HAS_V, LK><<<nbk, LS::threads, 0, ctx.stream>>>(ka, va, kb, vb, bounds.get(), low_bits, (uint32_t)n);
+        k_rs_local<K, V, HAS_V, LK><<<nbk, LS::threads, 0, ctx.stream>>>(ka, va, kb, vb, bounds.get(), low_bits, (uint32_t)n,
+                                                                      head_sums ? head_sums->get() : nullptr);
     }
     LAUNCH_TRY(ctx, "rs_local");
     *done = true;
@@ -1052,8 +1102,12 @@ static __global__ __launch_bounds__(kBlock) void k_iota(size_t n, uint32_t *p)
     if (k < n) p[k] = (uint32_t)k;
 }
 template <typename K, typename V, bool HAS_V>
-rama_status radix_sort_impl(Ctx &ctx, K *ka, V *va, K *kb, V *vb, size_t n, int total_bits, bool *result_in_b, bool iota = false)
+rama_status radix_sort_impl(Ctx &ctx, K *ka, V *va, K *kb, V *vb, size_t n, int total_bits, bool *result_in_b, bool iota = false,
+                            Buf<uint32_t> *head_sums = nullptr)
 {
+    // head_sums (optional): comes back allocated and filled -- per tile of kScanTile places the number of keys that
+    // differ from their left neighbour -- when the sort ends in the in-LDS kernel, and empty otherwise
+    if (head_sums) head_sums->reset();
     *result_in_b = false;
     if (n <= 1 || total_bits <= 0) return RAMA_OK;
     if (n >= (size_t(1) << 32)) return fail(ctx, RAMA_ERR_CAPACITY, "radix sort: more than 2^32 keys");
@@ -1068,14 +1122,16 @@ rama_status radix_sort_impl(Ctx &ctx, K *ka, V *va, K *kb, V *vb, size_t n, int 
             iota = false;
         }
         if (narrow || wide) {
+            RAMA_TRY(head_sums_alloc(ctx, n, head_sums));
+            uint32_t *hs = head_sums ? head_sums->get() : nullptr;
             if (narrow) {
                 ProfScope ps_(ctx, rs_local_name<K, HAS_V, uint32_t>(), (double)(n * (2 * sizeof(K) + (HAS_V ? 8 : 0))));
                 k_rs_local<K, V, HAS_V, uint32_t><<<1, LocalSort<uint32_t>::threads, 0, ctx.stream>>>(ka, va, kb, vb, (const uint32_t *)nullptr,
-                                                                                                  total_bits, (uint32_t)n);
+                                                                                                  total_bits, (uint32_t)n, hs);
             } else {
                 ProfScope ps_(ctx, rs_local_name<K, HAS_V, uint64_t>(), (double)(n * (2 * sizeof(K) + (HAS_V ? 8 : 0))));
                 k_rs_local<K, V, HAS_V, uint64_t><<<1, LocalSort<uint64_t>::threads, 0, ctx.stream>>>(ka, va, kb, vb, (const uint32_t *)nullptr,
-                                                                                                  total_bits, (uint32_t)n);
+                                                                                                  total_bits, (uint32_t)n, hs);
             }
             LAUNCH_TRY(ctx, "rs_local");
             *result_in_b = true;
@@ -1103,8 +1159,8 @@ rama_status radix_sort_impl(Ctx &ctx, K *ka, V *va, K *kb, V *vb, size_t n, int 
             const int low_bits = total_bits - top_bits;
             RAMA_TRY((radix_passes<K, V, HAS_V>(ctx, ka, va, kb, vb, n, low_bits, top_bits, hist.get(), offs.get(), result_in_b, &iota)));
             bool done = false;
-            if (narrow) RAMA_TRY((split_sort_tail<K, V, HAS_V, uint32_t>(ctx, ka, va, kb, vb, n, low_bits, &done)));
-            else RAMA_TRY((split_sort_tail<K, V, HAS_V, uint64_t>(ctx, ka, va, kb, vb, n, low_bits, &done)));
+            if (narrow) RAMA_TRY((split_sort_tail<K, V, HAS_V, uint32_t>(ctx, ka, va, kb, vb, n, low_bits, &done, head_sums)));
+            else RAMA_TRY((split_sort_tail<K, V, HAS_V, uint64_t>(ctx, ka, va, kb, vb, n, low_bits, &done, head_sums)));
             if (done) {
                 *result_in_b = !*result_in_b;
                 return RAMA_OK;
@@ -1117,9 +1173,11 @@ rama_status radix_sort_impl(Ctx &ctx, K *ka, V *va, K *kb, V *vb, size_t n, int 
 // Convenience wrappers working on Buf pairs: after the call `k`/`v` hold the sorted data.
 // `iota`: v comes in unset and stands for the values 0..n-1
 template <typename K, typename V>
-rama_status radix_sort_pairs(Ctx &ctx, Buf<K> &k, Buf<V> &v, size_t n, int total_bits, bool iota = false)
+rama_status radix_sort_pairs(Ctx &ctx, Buf<K> &k, Buf<V> &v, size_t n, int total_bits, bool iota = false,
+                             Buf<uint32_t> *head_sums = nullptr)
 {
     static_assert(sizeof(V) == 4, "32-bit payload");
+    if (head_sums) head_sums->reset();
     if (n <= 1 || total_bits <= 0) {
         if (iota && n >= 1) {
             k_iota<<<grid_for(n), kBlock, 0, ctx.stream>>>(n, (uint32_t *)v.get());
@@ -1132,20 +1190,21 @@ rama_status radix_sort_pairs(Ctx &ctx, Buf<K> &k, Buf<V> &v, size_t n, int total
     RAMA_TRY(k2.alloc(ctx, n));
     RAMA_TRY(v2.alloc(ctx, n));
     bool in_b = false;
-    RAMA_TRY((radix_sort_impl<K, V, true>(ctx, k.get(), v.get(), k2.get(), v2.get(), n, total_bits, &in_b, iota)));
+    RAMA_TRY((radix_sort_impl<K, V, true>(ctx, k.get(), v.get(), k2.get(), v2.get(), n, total_bits, &in_b, iota, head_sums)));
     if (in_b) { k.swap(k2); v.swap(v2); }
     return RAMA_OK;
 }
 
 template <typename K>
-rama_status radix_sort_keys(Ctx &ctx, Buf<K> &k, size_t n, int total_bits)
+rama_status radix_sort_keys(Ctx &ctx, Buf<K> &k, size_t n, int total_bits, Buf<uint32_t> *head_sums = nullptr)
 {
+    if (head_sums) head_sums->reset();
     if (n <= 1) return RAMA_OK;
     Buf<K> k2;
     RAMA_TRY(k2.alloc(ctx, n));
     bool in_b = false;
     RAMA_TRY((radix_sort_impl<K, uint32_t, false>(ctx, k.get(), (uint32_t *)nullptr, k2.get(), (uint32_t *)nullptr, n,
-                                                  total_bits, &in_b)));
+                                                  total_bits, &in_b, false, head_sums)));
     if (in_b) k.swap(k2);
     return RAMA_OK;
 }
