@@ -662,12 +662,14 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
     if (info) info->n_triangles = (int64_t)T;
     // ---- incidence: slots of every edge in ascending triangle order ----------------------------
     // (if the flag is up, the edge ids below are placeholders -- all valid indices -- and the result is discarded)
-    RAMA_TRY((radix_sort_pairs<uint32_t, uint32_t>(ctx, skey, slot, 3 * T, bits_for((uint64_t)ma), true)));   // values: the slots 0..3T-1
+    Buf<uint32_t> inc_head_sums;   // heads per scan tile, if the sort's last kernel could count them
+    RAMA_TRY((radix_sort_pairs<uint32_t, uint32_t>(ctx, skey, slot, 3 * T, bits_for((uint64_t)ma), true, &inc_head_sums)));   // values: the slots 0..3T-1
     Buf<uint32_t> act_edge, act_start;
     size_t na = 0;
     {
         ScanPlan<uint32_t> &heads = inc_heads;
-        RAMA_TRY((scan_totals<uint32_t>(ctx, HeadFlag32{skey.get()}, heads)));
+        RAMA_TRY((scan_totals<uint32_t>(ctx, HeadFlag32{skey.get()}, heads, inc_head_sums.get())));
+        inc_head_sums.reset();
         if (heads.extra_value[0]) return fail(ctx, RAMA_ERR_BAD_GRAPH, "a cycle uses an edge that is not in the graph");
         na = heads.total;
         RAMA_TRY(act_edge.alloc(ctx, na));
