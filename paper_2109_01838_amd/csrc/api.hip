@@ -324,6 +324,15 @@ rama_status rama_create(rama_ctx **out, void *hip_stream, const rama_alloc *allo
             if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
         }
     }
+    if (e == hipSuccess) {   // the page of zeroed words
+        void *z = nullptr;
+        e = ctx->pool.alloc(rama_ctx::kZeroPageWords * sizeof(uint32_t), &z);
+        if (e == hipSuccess) {
+            ctx->zero_page = (uint32_t *)z;
+            e = hipMemsetAsync(z, 0, rama_ctx::kZeroPageWords * sizeof(uint32_t), ctx->stream);
+            if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+        }
+    }
     for (int k = 0; k < rama_ctx::kStageEvents && e == hipSuccess; ++k) e = hipEventCreate(&ctx->stage_ev[k]);
     if (e == hipSuccess && ctx->device >= 0 && ctx->device < kMaxDevices) {
         // every GPU holds its own copy of the static scratch array at its own address

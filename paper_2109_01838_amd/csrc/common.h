@@ -267,6 +267,12 @@ struct rama_ctx {
     static constexpr size_t kMailWords = 64;          // 8-byte words of one message, word 0 is the number
     uint64_t mail_seq = 0;
     uint32_t *ticket = nullptr;  // device word, zero at rest: "last workgroup to finish" election of the fused scans
+    // Flags and counters that must start at zero (a dozen per round, a few words each) are handed out from one
+    // page of device words that is zero beyond zero_used; it is cleared again -- one launch -- when half of it
+    // is used up, at the start of a stage, where no word handed out before is still needed.
+    static constexpr size_t kZeroPageWords = size_t(1) << 14;
+    uint32_t *zero_page = nullptr;
+    size_t zero_used = 0;
     int cycle_search = 0;                      // see rama_set_cycle_search
     size_t sort_split_min = size_t(1) << 21;   // arrays at least this long may take the split sort ...
     int sort_split_gain = 2;                   // ... when it replaces at least this many passes
@@ -349,9 +355,15 @@ public:
         ctx_ = ctx.active; ptr_ = (T *)p; count_ = count;
         return RAMA_OK;
     }
+    // memory that somebody else owns (the ctx's page of zeroed words): never released
+    void borrow(T *p, size_t count)
+    {
+        reset();
+        ptr_ = p; count_ = count;
+    }
     void reset()
     {
-        if (ptr_) ctx_->release(ptr_);
+        if (ptr_ && ctx_) ctx_->release(ptr_);
         ptr_ = nullptr; count_ = 0; ctx_ = nullptr;
     }
     T *get() const { return ptr_; }

@@ -590,8 +590,7 @@ static rama_status forest_set(Ctx &ctx, const Graph &g, float tau, Buf<int32_t> 
     }
     LAUNCH_TRY(ctx, "iota");
     const int max_rounds = 64;   // the number of components with an outgoing edge at least halves per round
-    RAMA_TRY(counters.alloc(ctx, max_rounds));
-    RAMA_TRY(fill<uint32_t>(ctx, counters.get(), 0u, max_rounds));
+    RAMA_TRY(zeroed<uint32_t>(ctx, max_rounds, counters));
     int round = 0;
     for (; round < max_rounds && na > 0; ++round) {
         {
@@ -643,7 +642,6 @@ static rama_status forest_set(Ctx &ctx, const Graph &g, float tau, Buf<int32_t> 
     RAMA_TRY(depth.alloc(ctx, n));
     RAMA_TRY(up.alloc(ctx, n));
     RAMA_TRY(up_edge.alloc(ctx, n));
-    RAMA_TRY(changed.alloc(ctx, 1));
     {
         ProfScope ps_(ctx, "k_root_init", (double)(n * 12));
         k_root_init<<<grid_for(n), kBlock, 0, ctx.stream>>>(n, comp.get(), depth.get(), up.get());
@@ -653,7 +651,7 @@ static rama_status forest_set(Ctx &ctx, const Graph &g, float tau, Buf<int32_t> 
     for (int32_t lvl = 0;; lvl += levels_per_check) {
         // a tree is at most n-1 levels deep; the sweep after the deepest level reports no change
         if ((size_t)lvl > n + levels_per_check) return fail(ctx, RAMA_ERR_HIP, "forest rooting did not converge");
-        RAMA_TRY(fill<int32_t>(ctx, changed.get(), 0, 1));
+        RAMA_TRY(zeroed<int32_t>(ctx, 1, changed));   // a fresh word per look
         for (int q = 0; q < levels_per_check; ++q) {
             ProfScope ps_(ctx, "k_root_level", (double)((size_t)nf * 20));
             k_root_level<<<grid_for(nf), kBlock, 0, ctx.stream>>>(nf, fe.get(), g.i.get(), g.j.get(), lvl + q, depth.get(),
@@ -697,9 +695,8 @@ static rama_status components(Ctx &ctx, size_t n, size_t ns, const int32_t *si, 
     LAUNCH_TRY(ctx, "iota");
     if (ns == 0) return RAMA_OK;
     Buf<int32_t> changed;
-    RAMA_TRY(changed.alloc(ctx, 1));
     for (int it = 0; it < 64; ++it) {   // the number of trees at least halves per sweep
-        RAMA_TRY(fill<int32_t>(ctx, changed.get(), 0, 1));
+        RAMA_TRY(zeroed<int32_t>(ctx, 1, changed));   // a fresh word per sweep
         {
             ProfScope ps_(ctx, "k_hook", (double)(ns * 24));
             k_hook<<<grid_for(ns), kBlock, 0, ctx.stream>>>(ns, si, sj, rep.get(), changed.get());
@@ -752,7 +749,7 @@ static rama_status contract_edges(Ctx &ctx, const Graph &g, const int32_t *fmap,
     keep.offs.reset();
     raw.reset();
     Buf<uint32_t> head_sums;   // heads per scan tile, if the sort's last kernel could count them
-    RAMA_TRY((radix_sort_pairs<uint64_t, uint32_t>(ctx, key, val, kept, nbits + dbits, false, &head_sums)));
+    RAMA_TRY((radix_sort_pairs<uint64_t, uint32_t>(ctx, key, val, kept, nbits + dbits, false, &head_sums, (uint64_t)n_new << dbits)));
     ScanPlan<uint32_t> runs;
     RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, kept, 0, runs)));
     RAMA_TRY((scan_totals<uint32_t>(ctx, HeadFlag{key.get()}, runs, head_sums.get())));
@@ -771,6 +768,7 @@ rama_status contract_once(Ctx &ctx, const Graph &g, float tau, int rounds_cap, f
 {
     const size_t n = (size_t)g.n;
     if (used_forest) *used_forest = false;
+    RAMA_TRY(zero_page_recycle(ctx));
     Buf<int32_t> mate;
     RAMA_TRY(matching(ctx, g, tau, rounds_cap, mate, n_matched));
     n_new = g.n;
@@ -831,7 +829,7 @@ rama_status contraction_diagonal(Ctx &ctx, const Graph &g, const int32_t *fmap, 
         k_inner<<<grid_for(m), kBlock, 0, ctx.stream>>>(m, g.i.get(), g.j.get(), g.c.get(), fmap, pos.get(), key.get(), val.get());
     }
     LAUNCH_TRY(ctx, "inner");
-    RAMA_TRY((radix_sort_pairs<uint32_t, uint32_t>(ctx, key, val, kept, bits_for((uint64_t)n_new))));
+    RAMA_TRY((radix_sort_pairs<uint32_t, uint32_t>(ctx, key, val, kept, bits_for((uint64_t)n_new), false, nullptr, (uint64_t)n_new)));
     {
         ProfScope ps_(ctx, "k_diag_runs", (double)((size_t)kept * 12));
         k_diag_runs<<<grid_for(kept), kBlock, 0, ctx.stream>>>(kept, key.get(), val.get(), diag);

@@ -945,8 +945,7 @@ rama_status count_and_fill(Ctx &ctx, size_t mr, const int32_t *ri, const int32_t
     Buf<uint32_t> heavy, spill, n_heavy;   // n_heavy[0]: length of the heavy list, [1]: a count saturated, [2]: length of the spill list
     RAMA_TRY(heavy.alloc(ctx, may_be_heavy ? mr : 1));
     RAMA_TRY(spill.alloc(ctx, coop ? mr : 1));
-    RAMA_TRY(n_heavy.alloc(ctx, 3));
-    RAMA_TRY(fill<uint32_t>(ctx, n_heavy.get(), 0u, 3));
+    RAMA_TRY(zeroed<uint32_t>(ctx, 3, n_heavy));
     // mode 1 is the walk that fetches a row per path at its last level, kept for comparison; walks of at
     // most three nodes have no such level
     const bool meet = MAXL >= 5 && max_len >= 5 && ctx.cycle_search != 1;
@@ -1080,6 +1079,7 @@ rama_status find_cycles(Ctx &ctx, const Graph &g, int max_len, bool shortest_onl
     out.n_attractive = 0; out.n_repulsive = 0;
     const size_t m = (size_t)g.m;
     if (m == 0 || max_len < 3) return RAMA_OK;
+    RAMA_TRY(zero_page_recycle(ctx));
     if (max_len > kMaxCycleLen) return fail(ctx, RAMA_ERR_INVALID_ARG, "cycle length beyond the supported maximum");
     // sign partition
     ScanPlan<uint64_t> signs;
@@ -1113,11 +1113,10 @@ rama_status find_cycles(Ctx &ctx, const Graph &g, int max_len, bool shortest_onl
     const bool want_longest = max_len >= 4 && max_len <= 5 && ctx.cycle_search == 0 && 2 * (size_t)mp <= (size_t)9 * (size_t)n / 2;
     Buf<uint32_t> longest;
     if (want_longest) {
-        RAMA_TRY(longest.alloc(ctx, 1));
-        RAMA_TRY(fill<uint32_t>(ctx, longest.get(), 0u, 1));
+        RAMA_TRY(zeroed<uint32_t>(ctx, 1, longest));
     }
     RAMA_TRY((row_bounds<int32_t, int32_t>(ctx, pi.get(), mp, n, up_ptr.get())));
-    RAMA_TRY((radix_sort_pairs<uint32_t, uint32_t>(ctx, lkey, lval, mp, bits_for((uint64_t)n))));
+    RAMA_TRY((radix_sort_pairs<uint32_t, uint32_t>(ctx, lkey, lval, mp, bits_for((uint64_t)n), false, nullptr, (uint64_t)n)));
     RAMA_TRY((row_bounds<uint32_t, int32_t>(ctx, lkey.get(), mp, n, low_ptr.get())));
     {
         ProfScope ps_(ctx, "k_add_ptr", (double)(((size_t)n + 1) * 12));

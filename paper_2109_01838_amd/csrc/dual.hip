@@ -484,6 +484,7 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
 {
     if (lists < 0 || lists > kCycleLists || k_iters < 0 || (lists > 0 && (!cycles || !n_cycles)))
         return fail(ctx, RAMA_ERR_INVALID_ARG, "message passing: bad cycle lists or iteration count");
+    RAMA_TRY(zero_page_recycle(ctx));
     CycleSet cs;
     size_t ncyc = 0, nfan = 0, nch = 0;
     double cycle_bytes = 0.0;
@@ -526,8 +527,7 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
     // "a cycle uses an edge that is not in the graph": raised by the kernels that look edges up, read by the
     // host together with the next count it waits for anyway
     Buf<int32_t> flag;   // [0]: the flag, [1]: the longest row of the upper adjacency (filled in further down)
-    RAMA_TRY(flag.alloc(ctx, 2));
-    RAMA_TRY(fill<int32_t>(ctx, flag.get(), 0, 2));
+    RAMA_TRY(zeroed<int32_t>(ctx, 2, flag));
     // rows of the canonical edge list (upper CSR)
     Buf<int32_t> rowptr;
     RAMA_TRY(rowptr.alloc(ctx, (size_t)n + 1));
@@ -554,7 +554,7 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
             k_chord_keys<<<grid_for(nch), kBlock, 0, ctx.stream>>>(cs, nch, nbits, ckey.get());
         }
         LAUNCH_TRY(ctx, "chord_keys");
-        RAMA_TRY((radix_sort_keys<uint64_t>(ctx, ckey, nch, 2 * nbits)));
+        RAMA_TRY((radix_sort_keys<uint64_t>(ctx, ckey, nch, 2 * nbits, nullptr, (uint64_t)n << nbits)));
         Buf<uint32_t> cpos;
         Buf<int32_t> where;
         RAMA_TRY(cpos.alloc(ctx, nch + 1));
@@ -637,9 +637,9 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
         Buf<uint32_t> head_sums;   // heads per scan tile, if the sort's last kernel could count them
         if (T_kept > 0) {   // the sort also has to tell where the kept triangles end up
             RAMA_TRY(origin.alloc(ctx, nfan));
-            RAMA_TRY((radix_sort_pairs<KT, uint32_t>(ctx, tkey, origin, nfan, kbits, true, &head_sums)));   // values: the fan indices 0..nfan-1
+            RAMA_TRY((radix_sort_pairs<KT, uint32_t>(ctx, tkey, origin, nfan, kbits, true, &head_sums, kbits < 64 ? (uint64_t)ma << dbits : 0)));   // values: the fan indices 0..nfan-1
         } else {
-            RAMA_TRY((radix_sort_keys<KT>(ctx, tkey, nfan, kbits, &head_sums)));
+            RAMA_TRY((radix_sort_keys<KT>(ctx, tkey, nfan, kbits, &head_sums, kbits < 64 ? (uint64_t)ma << dbits : 0)));
         }
         ScanPlan<uint32_t> heads;
         RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, nfan, 0, heads)));
@@ -663,7 +663,7 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
     // ---- incidence: slots of every edge in ascending triangle order ----------------------------
     // (if the flag is up, the edge ids below are placeholders -- all valid indices -- and the result is discarded)
     Buf<uint32_t> inc_head_sums;   // heads per scan tile, if the sort's last kernel could count them
-    RAMA_TRY((radix_sort_pairs<uint32_t, uint32_t>(ctx, skey, slot, 3 * T, bits_for((uint64_t)ma), true, &inc_head_sums)));   // values: the slots 0..3T-1
+    RAMA_TRY((radix_sort_pairs<uint32_t, uint32_t>(ctx, skey, slot, 3 * T, bits_for((uint64_t)ma), true, &inc_head_sums, (uint64_t)ma)));   // values: the slots 0..3T-1
     Buf<uint32_t> act_edge, act_start;
     size_t na = 0;
     {

@@ -79,6 +79,7 @@ rama_status canonicalise(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const
     if (m >= (int64_t(1) << 31) - 1) return fail(ctx, RAMA_ERR_CAPACITY, "edge count reaches 2^31");
     out.n = n;
     out.m = 0;
+    RAMA_TRY(zero_page_recycle(ctx));
     if (m == 0) {
         RAMA_TRY(out.i.alloc(ctx, 1));
         RAMA_TRY(out.j.alloc(ctx, 1));
@@ -86,8 +87,7 @@ rama_status canonicalise(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const
         return RAMA_OK;
     }
     Buf<int32_t> flags;
-    RAMA_TRY(flags.alloc(ctx, 3));
-    RAMA_TRY(fill<int32_t>(ctx, flags.get(), 0, 3));
+    RAMA_TRY(zeroed<int32_t>(ctx, 3, flags));
     ScanPlan<uint32_t> keep;
     RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, (size_t)m, 0, keep)));
     {
@@ -125,7 +125,7 @@ rama_status canonicalise(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const
                                   (double)((size_t)m * 4 + (size_t)kept * 12))));
     keep.offs.reset();
     Buf<uint32_t> head_sums;   // heads per scan tile, if the sort's last kernel could count them
-    RAMA_TRY((radix_sort_pairs<uint64_t, uint32_t>(ctx, key, val, kept, nbits + dbits, false, &head_sums)));
+    RAMA_TRY((radix_sort_pairs<uint64_t, uint32_t>(ctx, key, val, kept, nbits + dbits, false, &head_sums, (uint64_t)n << dbits)));
     ScanPlan<uint32_t> runs;
     RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, kept, 0, runs)));
     RAMA_TRY((scan_totals<uint32_t>(ctx, HeadFlag{key.get()}, runs, head_sums.get())));

@@ -14,6 +14,29 @@ namespace rama {
 template <typename T>
 rama_status fill(Ctx &ctx, T *p, T v, size_t n);   // defined with the reductions below
 
+// `count` elements that are zero: from the ctx's page of zeroed words when they are few (no launch), else a block
+// of their own plus a fill.  Page words are for use inside one stage (see zero_page_recycle).
+template <typename T>
+rama_status zeroed(Ctx &ctx, size_t count, Buf<T> &b)
+{
+    const size_t words = (count * sizeof(T) + 15) / 16 * 4;
+    if (ctx.zero_page && words <= 1024 && ctx.zero_used + words <= rama_ctx::kZeroPageWords) {
+        b.borrow((T *)(ctx.zero_page + ctx.zero_used), count);
+        ctx.zero_used += words;
+        return RAMA_OK;
+    }
+    RAMA_TRY(b.alloc(ctx, count > 0 ? count : 1));
+    return fill<T>(ctx, b.get(), (T)0, count > 0 ? count : 1);
+}
+// At the start of a stage (nothing handed out from the page is needed any more): clear the page once half of it is used.
+inline rama_status zero_page_recycle(Ctx &ctx)
+{
+    if (!ctx.zero_page || ctx.zero_used * 2 <= rama_ctx::kZeroPageWords) return RAMA_OK;
+    RAMA_TRY(fill<uint32_t>(ctx, ctx.zero_page, 0u, rama_ctx::kZeroPageWords));
+    ctx.zero_used = 0;
+    return RAMA_OK;
+}
+
 // ------------------------------------------------------------------------------------------
 // wave / block helpers
 // ------------------------------------------------------------------------------------------
@@ -1050,8 +1073,7 @@ inline rama_status head_sums_alloc(Ctx &ctx, size_t n, Buf<uint32_t> *head_sums)
 {
     if (!head_sums) return RAMA_OK;
     const size_t tiles = (n + kScanTile - 1) / kScanTile + 1;
-    RAMA_TRY(head_sums->alloc(ctx, tiles));
-    return fill<uint32_t>(ctx, head_sums->get(), 0u, tiles);
+    return zeroed<uint32_t>(ctx, tiles, *head_sums);
 }
 
 // bounds + in-LDS sort of an array already sorted by its bits above low_bits; *done stays false
@@ -1063,10 +1085,10 @@ rama_status split_sort_tail(Ctx &ctx, K *ka, V *va, K *kb, V *vb, size_t n, int 
     *done = false;
     const uint32_t window = LS::cap / 2;
     const uint32_t nbk = grid_for(n, (int)window);
-    Buf<uint32_t> bounds;
-    RAMA_TRY(bounds.alloc(ctx, (size_t)nbk + 2));
-    uint32_t *oversize = bounds.get() + nbk + 1;
-    RAMA_TRY(fill<uint32_t>(ctx, oversize, 0u, 1));
+    Buf<uint32_t> bounds, over_flag;
+    RAMA_TRY(bounds.alloc(ctx, (size_t)nbk + 1));
+    RAMA_TRY(zeroed<uint32_t>(ctx, 1, over_flag));
+    uint32_t *oversize = over_flag.get();
     {
         ProfScope ps_(ctx, "k_seg_bounds", (double)((size_t)nbk * (4 + 32 * sizeof(K))));
         k_seg_bounds<K><<<grid_for((size_t)nbk + 1), kBlock, 0, ctx.stream>>>(ka, n, low_bits, window, (uint32_t)LS::cap,
@@ -1103,8 +1125,10 @@ static __global__ __launch_bounds__(kBlock) void k_iota(size_t n, uint32_t *p)
 }
 template <typename K, typename V, bool HAS_V>
 rama_status radix_sort_impl(Ctx &ctx, K *ka, V *va, K *kb, V *vb, size_t n, int total_bits, bool *result_in_b, bool iota = false,
-                            Buf<uint32_t> *head_sums = nullptr)
+                            Buf<uint32_t> *head_sums = nullptr, uint64_t key_limit = 0)
 {
+    // key_limit (optional): all keys are below it (and it needs total_bits bits); 0 = nothing known
+    if (key_limit && (total_bits >= 64 || key_limit > (uint64_t(1) << total_bits))) key_limit = 0;
     // head_sums (optional): comes back allocated and filled -- per tile of kScanTile places the number of keys that
     // differ from their left neighbour -- when the sort ends in the in-LDS kernel, and empty otherwise
     if (head_sums) head_sums->reset();
@@ -1144,16 +1168,21 @@ rama_status radix_sort_impl(Ctx &ctx, K *ka, V *va, K *kb, V *vb, size_t n, int 
     RAMA_TRY(offs.alloc(ctx, (size_t)kRadix * nb + kRadix));
     const int all_passes = (total_bits + kRadixBits - 1) / kRadixBits;
     if (n >= ctx.sort_split_min) {
-        // top bits: whole passes, enough of them for segments of two fifths of a workgroup's capacity on
-        // average (a workgroup takes the segments that start in half a capacity of places: what it gets stays
-        // below the capacity as long as no segment is longer than half the capacity, 1.25 times that average; with a
-        // quarter of the capacity as the limit the
-        // incidence sort of the 320^3 grid, 1.9e8 keys of 27 bits, took four passes instead of two and one in-LDS
-        // sort, +0.6 ms); a few spare low bits leave room for the top bits in which a workgroup's segments differ
+        // top bits: whole passes, enough of them for segments that a workgroup can hold.  A workgroup takes the
+        // segments that start in half a capacity of places, so what it gets stays below the capacity as long as no
+        // segment is longer than half the capacity.  Without knowledge of the keys the segments are assumed to be a
+        // quarter of the capacity on average at most (the keys seldom fill the whole range of their bits: fewer,
+        // longer segments).  With a bound on the keys (`key_limit`) the number of segments is known and two fifths of
+        // the capacity are allowed (the incidence sort of the 320^3 grid, 1.9e8 keys below 1.3e8: two top-bit passes
+        // and one in-LDS sort instead of four passes, -0.6 ms).  A few spare low bits leave room for the top bits in
+        // which a workgroup's segments differ.
         auto plan = [&](int cap, int *top_bits) {
-            const int seg = cap * 2 / 5;
-            int t = bits_for((n + seg - 1) / seg);
-            t = (t + kRadixBits - 1) / kRadixBits * kRadixBits;
+            const uint64_t seg = key_limit ? (uint64_t)cap * 2 / 5 : (uint64_t)cap / 4;
+            int t = kRadixBits;
+            for (; t < total_bits; t += kRadixBits) {
+                const uint64_t nseg = key_limit ? ((key_limit - 1) >> (total_bits - t)) + 1 : (uint64_t(1) << t);
+                if (((uint64_t)n + nseg - 1) / nseg <= seg) break;
+            }
             *top_bits = t;
             return t < total_bits && all_passes - t / kRadixBits >= ctx.sort_split_gain;
         };
@@ -1179,7 +1208,7 @@ rama_status radix_sort_impl(Ctx &ctx, K *ka, V *va, K *kb, V *vb, size_t n, int 
 // `iota`: v comes in unset and stands for the values 0..n-1
 template <typename K, typename V>
 rama_status radix_sort_pairs(Ctx &ctx, Buf<K> &k, Buf<V> &v, size_t n, int total_bits, bool iota = false,
-                             Buf<uint32_t> *head_sums = nullptr)
+                             Buf<uint32_t> *head_sums = nullptr, uint64_t key_limit = 0)
 {
     static_assert(sizeof(V) == 4, "32-bit payload");
     if (head_sums) head_sums->reset();
@@ -1195,13 +1224,13 @@ rama_status radix_sort_pairs(Ctx &ctx, Buf<K> &k, Buf<V> &v, size_t n, int total
     RAMA_TRY(k2.alloc(ctx, n));
     RAMA_TRY(v2.alloc(ctx, n));
     bool in_b = false;
-    RAMA_TRY((radix_sort_impl<K, V, true>(ctx, k.get(), v.get(), k2.get(), v2.get(), n, total_bits, &in_b, iota, head_sums)));
+    RAMA_TRY((radix_sort_impl<K, V, true>(ctx, k.get(), v.get(), k2.get(), v2.get(), n, total_bits, &in_b, iota, head_sums, key_limit)));
     if (in_b) { k.swap(k2); v.swap(v2); }
     return RAMA_OK;
 }
 
 template <typename K>
-rama_status radix_sort_keys(Ctx &ctx, Buf<K> &k, size_t n, int total_bits, Buf<uint32_t> *head_sums = nullptr)
+rama_status radix_sort_keys(Ctx &ctx, Buf<K> &k, size_t n, int total_bits, Buf<uint32_t> *head_sums = nullptr, uint64_t key_limit = 0)
 {
     if (head_sums) head_sums->reset();
     if (n <= 1) return RAMA_OK;
@@ -1209,7 +1238,7 @@ rama_status radix_sort_keys(Ctx &ctx, Buf<K> &k, size_t n, int total_bits, Buf<u
     RAMA_TRY(k2.alloc(ctx, n));
     bool in_b = false;
     RAMA_TRY((radix_sort_impl<K, uint32_t, false>(ctx, k.get(), (uint32_t *)nullptr, k2.get(), (uint32_t *)nullptr, n,
-                                                  total_bits, &in_b, false, head_sums)));
+                                                  total_bits, &in_b, false, head_sums, key_limit)));
     if (in_b) k.swap(k2);
     return RAMA_OK;
 }
