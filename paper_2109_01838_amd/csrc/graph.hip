@@ -1,19 +1,22 @@
 // Step a0: problem statement -> canonical device graph (paper Sec. 3: graph and cost vector;
 // Lemma 1(b): parallel edges carry the sum of their costs).
 #include "prim.h"
+#include <algorithm>
+#include <vector>
 
 namespace rama {
 
 namespace {
 
 // flags[0]: endpoint out of range or non-finite cost; flags[1]: list is not canonical;
-// flags[2]: largest |i-j| of a valid edge.  A workgroup takes one tile of the scan over NotLoop (kScanTile
+// flags[2]: largest |i-j| of a valid edge; flags[3]: number of places where the oriented pair (min, max) is smaller
+// than the one before it (few of them: the list is a handful of sorted runs, e.g. one per grid direction).  A workgroup takes one tile of the scan over NotLoop (kScanTile
 // edges) and leaves the number of edges that are no self-loops in tile_sums, so that scan needs no counting pass.
 __global__ __launch_bounds__(kBlock) void k_validate(int32_t n, size_t m, const int32_t *i, const int32_t *j,
                                                      const float *c, int32_t *flags, uint32_t *tile_sums)
 {
     const size_t base = (size_t)blockIdx.x * kScanTile + threadIdx.x;
-    uint32_t diff = 0, kept = 0;
+    uint32_t diff = 0, kept = 0, down = 0;
 #pragma unroll
     for (int q = 0; q < kScanItems; ++q) {
         const size_t e = base + (size_t)q * kBlock;
@@ -28,15 +31,21 @@ __global__ __launch_bounds__(kBlock) void k_validate(int32_t n, size_t m, const 
             const uint32_t d = (uint32_t)abs(a - b);
             diff = d > diff ? d : diff;
             bool canon = a < b;
-            if (canon && e > 0) {
-                int32_t pa = i[e - 1], pb = j[e - 1];
-                canon = pa < a || (pa == a && pb < b);
+            if (e > 0) {
+                const int32_t pa = i[e - 1], pb = j[e - 1];
+                canon = canon && (pa < a || (pa == a && pb < b));
+                const int32_t lo = min(a, b), hi = max(a, b), plo = min(pa, pb), phi = max(pa, pb);
+                down += (lo < plo || (lo == plo && hi < phi)) ? 1u : 0u;
             }
             if (!canon) flags[1] = 1;
         }
     }
     kept = block_sum(kept);
-    if (threadIdx.x == 0) tile_sums[blockIdx.x] = kept;
+    down = block_sum(down);
+    if (threadIdx.x == 0) {
+        tile_sums[blockIdx.x] = kept;
+        if (down) atomicAdd((uint32_t *)&flags[3], down);
+    }
     block_max_into(diff, (uint32_t *)&flags[2]);
 }
 
@@ -71,6 +80,126 @@ struct HeadFlag {
     __device__ __forceinline__ uint32_t operator()(size_t e) const { return (e == 0 || key[e] != key[e - 1]) ? 1u : 0u; }
 };
 
+// ---- a list that consists of a few sorted runs is merged instead of sorted --------------------------------------
+constexpr int kMaxRuns = 8;
+constexpr int kMergeTile = 2048;
+
+// places p >= 1 with key[p] < key[p-1]: out[0] counts them, out[1..] takes the first kMaxRuns - 1 (in any order)
+__global__ __launch_bounds__(kBlock) void k_find_descents(const uint64_t *key, size_t n, uint32_t *out)
+{
+    const size_t p = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (p == 0 || p >= n) return;
+    if (key[p] < key[p - 1]) {
+        const uint32_t k = atomicAdd(out, 1u);
+        if (k < (uint32_t)(kMaxRuns - 1)) out[1 + k] = (uint32_t)p;
+    }
+}
+
+// Merge path: split[t] = how many of the first t * kMergeTile merged elements come from a (a's elements go first among
+// equal keys, which keeps the merge stable).
+__global__ __launch_bounds__(kBlock) void k_merge_partition(const uint64_t *a, uint32_t na, const uint64_t *b, uint32_t nb,
+                                                            uint32_t ntiles, uint32_t *split)
+{
+    const uint32_t t = blockIdx.x * kBlock + threadIdx.x;
+    if (t > ntiles) return;
+    const uint64_t d64 = (uint64_t)t * kMergeTile;
+    const uint32_t diag = d64 < (uint64_t)na + nb ? (uint32_t)d64 : na + nb;
+    uint32_t lo = diag > nb ? diag - nb : 0u, hi = diag < na ? diag : na;
+    while (lo < hi) {
+        const uint32_t mid = lo + (hi - lo) / 2;
+        if (a[mid] <= b[diag - 1 - mid]) lo = mid + 1;
+        else hi = mid;
+    }
+    split[t] = lo;
+}
+
+// One tile of the merged list: its pieces of a and b go to LDS side by side, every element finds its place by a
+// bisection of the other piece, and the tile is written out in order.
+__global__ __launch_bounds__(kBlock) void k_merge_pairs(const uint64_t *ak, const uint32_t *av, uint32_t na, const uint64_t *bk,
+                                                        const uint32_t *bv, uint32_t nb, const uint32_t *split, uint64_t *ok,
+                                                        uint32_t *ov)
+{
+    __shared__ uint64_t sk[kMergeTile];
+    __shared__ uint32_t sv[kMergeTile];
+    constexpr int kPer = kMergeTile / kBlock;
+    const uint32_t t = blockIdx.x;
+    const uint32_t diag0 = t * (uint32_t)kMergeTile;
+    const uint32_t diag1 = (uint64_t)diag0 + kMergeTile < (uint64_t)na + nb ? diag0 + kMergeTile : na + nb;
+    const uint32_t a0 = split[t], a1 = split[t + 1], b0 = diag0 - a0;
+    const uint32_t cnt_a = a1 - a0, total = diag1 - diag0, cnt_b = total - cnt_a;
+    for (uint32_t x = threadIdx.x; x < total; x += kBlock) {
+        if (x < cnt_a) { sk[x] = ak[a0 + x]; sv[x] = av[a0 + x]; }
+        else { sk[x] = bk[b0 + (x - cnt_a)]; sv[x] = bv[b0 + (x - cnt_a)]; }
+    }
+    __syncthreads();
+    uint64_t k[kPer];
+    uint32_t v[kPer], r[kPer];
+#pragma unroll
+    for (int q = 0; q < kPer; ++q) {
+        const uint32_t x = threadIdx.x + (uint32_t)q * kBlock;
+        r[q] = 0xffffffffu;
+        if (x >= total) continue;
+        k[q] = sk[x]; v[q] = sv[x];
+        uint32_t lo, hi;
+        if (x < cnt_a) {           // elements of b that are smaller
+            lo = 0; hi = cnt_b;
+            while (lo < hi) { const uint32_t mid = (lo + hi) / 2; if (sk[cnt_a + mid] < k[q]) lo = mid + 1; else hi = mid; }
+            r[q] = x + lo;
+        } else {                   // elements of a that are smaller or equal
+            lo = 0; hi = cnt_a;
+            while (lo < hi) { const uint32_t mid = (lo + hi) / 2; if (sk[mid] <= k[q]) lo = mid + 1; else hi = mid; }
+            r[q] = (x - cnt_a) + lo;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < kPer; ++q)
+        if (r[q] != 0xffffffffu) { sk[r[q]] = k[q]; sv[r[q]] = v[q]; }
+    __syncthreads();
+    for (uint32_t x = threadIdx.x; x < total; x += kBlock) { ok[diag0 + x] = sk[x]; ov[diag0 + x] = sv[x]; }
+}
+
+// key/val consist of the sorted runs [start[r], start[r+1]), r < runs: rounds of pairwise stable merges
+rama_status merge_runs(Ctx &ctx, Buf<uint64_t> &key, Buf<uint32_t> &val, size_t n, std::vector<uint32_t> start)
+{
+    Buf<uint64_t> key2;
+    Buf<uint32_t> val2, split;
+    RAMA_TRY(key2.alloc(ctx, n));
+    RAMA_TRY(val2.alloc(ctx, n));
+    RAMA_TRY(split.alloc(ctx, n / kMergeTile + 2));
+    while (start.size() > 2) {
+        std::vector<uint32_t> next;
+        for (size_t r = 0; r + 1 < start.size(); r += 2) {
+            const uint32_t s0 = start[r], s1 = start[r + 1];
+            next.push_back(s0);
+            if (r + 2 >= start.size()) {   // a run without a partner moves over as it is
+                HIP_TRY(ctx, hipMemcpyAsync(key2.get() + s0, key.get() + s0, (size_t)(s1 - s0) * 8, hipMemcpyDeviceToDevice, ctx.stream));
+                HIP_TRY(ctx, hipMemcpyAsync(val2.get() + s0, val.get() + s0, (size_t)(s1 - s0) * 4, hipMemcpyDeviceToDevice, ctx.stream));
+                continue;
+            }
+            const uint32_t s2 = start[r + 2], na = s1 - s0, nb = s2 - s1;
+            const uint32_t ntiles = (na + nb + kMergeTile - 1) / kMergeTile;
+            {
+                ProfScope ps_(ctx, "k_merge_partition", (double)ntiles * 4);
+                k_merge_partition<<<grid_for((size_t)ntiles + 1), kBlock, 0, ctx.stream>>>(key.get() + s0, na, key.get() + s1, nb, ntiles,
+                                                                                      split.get());
+            }
+            LAUNCH_TRY(ctx, "merge_partition");
+            {
+                ProfScope ps_(ctx, "k_merge_pairs", (double)(na + nb) * 24);
+                k_merge_pairs<<<ntiles, kBlock, 0, ctx.stream>>>(key.get() + s0, val.get() + s0, na, key.get() + s1, val.get() + s1, nb,
+                                                               split.get(), key2.get() + s0, val2.get() + s0);
+            }
+            LAUNCH_TRY(ctx, "merge_pairs");
+        }
+        next.push_back(start.back());
+        start.swap(next);
+        key.swap(key2);
+        val.swap(val2);
+    }
+    return RAMA_OK;
+}
+
 }  // namespace
 
 rama_status canonicalise(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const int32_t *j, const float *c, Graph &out)
@@ -87,7 +216,7 @@ rama_status canonicalise(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const
         return RAMA_OK;
     }
     Buf<int32_t> flags;
-    RAMA_TRY(zeroed<int32_t>(ctx, 3, flags));
+    RAMA_TRY(zeroed<int32_t>(ctx, 4, flags));
     ScanPlan<uint32_t> keep;
     RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, (size_t)m, 0, keep)));
     {
@@ -95,7 +224,7 @@ rama_status canonicalise(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const
         k_validate<<<keep.nb, kBlock, 0, ctx.stream>>>(n, (size_t)m, i, j, c, flags.get(), keep.sums.get());
     }
     LAUNCH_TRY(ctx, "validate");
-    int32_t hf[3];
+    int32_t hf[4];
     RAMA_TRY(read_back(ctx, hf, flags.get(), sizeof hf));
     if (hf[0]) return fail(ctx, RAMA_ERR_BAD_GRAPH, "edge endpoint outside [0,n_nodes) or non-finite cost");
     if (!hf[1]) {  // already canonical: plain copy
@@ -125,7 +254,30 @@ rama_status canonicalise(Ctx &ctx, int32_t n, int64_t m, const int32_t *i, const
                                   (double)((size_t)m * 4 + (size_t)kept * 12))));
     keep.offs.reset();
     Buf<uint32_t> head_sums;   // heads per scan tile, if the sort's last kernel could count them
-    RAMA_TRY((radix_sort_pairs<uint64_t, uint32_t>(ctx, key, val, kept, nbits + dbits, false, &head_sums, (uint64_t)n << dbits)));
+    bool merged = false;
+    if ((uint32_t)hf[3] < (uint32_t)kMaxRuns && kept > (uint32_t)LocalSort<uint64_t>::cap) {
+        // few places where the order breaks: the packed list is a handful of sorted runs (dropping self-loops cannot
+        // add any): find their starts and merge them, one pass per doubling, instead of sorting by all key bits
+        Buf<uint32_t> desc;
+        RAMA_TRY(zeroed<uint32_t>(ctx, kMaxRuns, desc));
+        {
+            ProfScope ps_(ctx, "k_find_descents", (double)kept * 8);
+            k_find_descents<<<grid_for(kept), kBlock, 0, ctx.stream>>>(key.get(), kept, desc.get());
+        }
+        LAUNCH_TRY(ctx, "find_descents");
+        uint32_t hd[kMaxRuns];
+        RAMA_TRY(read_back(ctx, hd, desc.get(), sizeof hd));
+        if (hd[0] < (uint32_t)kMaxRuns) {
+            std::vector<uint32_t> start(hd + 1, hd + 1 + hd[0]);
+            start.push_back(0u);
+            start.push_back(kept);
+            std::sort(start.begin(), start.end());
+            RAMA_TRY(merge_runs(ctx, key, val, kept, start));
+            merged = true;
+        }
+    }
+    if (!merged)
+        RAMA_TRY((radix_sort_pairs<uint64_t, uint32_t>(ctx, key, val, kept, nbits + dbits, false, &head_sums, (uint64_t)n << dbits)));
     ScanPlan<uint32_t> runs;
     RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, kept, 0, runs)));
     RAMA_TRY((scan_totals<uint32_t>(ctx, HeadFlag{key.get()}, runs, head_sums.get())));

@@ -387,6 +387,31 @@ def test_canonicalisation_sums_long_runs_in_input_order(rama, oracle32, n, m):
     assert np.array_equal(np_(got["c"]), wc)
 
 
+@pytest.mark.parametrize("runs", [2, 3, 5, 8, 9])
+def test_canonicalisation_of_a_few_sorted_runs(rama, oracle32, runs):
+    # an edge list made of `runs` sorted pieces (as a grid written direction by direction): up to eight pieces are
+    # merged instead of sorted; pairs that occur in several pieces, flipped pairs and self-loops included
+    rng = np.random.default_rng(100 + runs)
+    n, m = 40000, 120000
+    a = rng.integers(0, n, m); b = rng.integers(0, n, m)
+    loops = rng.random(m) < 0.01
+    b = np.where(loops, a, b)
+    lo, hi = np.minimum(a, b), np.maximum(a, b)
+    piece = rng.integers(0, runs, m)
+    dup = rng.random(m) < 0.1                                    # a tenth of the pairs also goes into another piece
+    lo = np.concatenate([lo, lo[dup]]); hi = np.concatenate([hi, hi[dup]])
+    piece = np.concatenate([piece, (piece[dup] + 1) % runs])
+    order = np.lexsort((hi, lo, piece))                          # piece by piece, each sorted by (lo, hi)
+    lo, hi = lo[order], hi[order]
+    flip = rng.random(lo.size) < 0.3
+    i = np.where(flip, hi, lo).astype(np.int32); j = np.where(flip, lo, hi).astype(np.int32)
+    c = (-np.abs(rng.normal(size=i.size)) * 10.0 ** rng.integers(-2, 3, i.size) - 1e-3).astype(np.float32)
+    wi, wj, wc = oracle32.canonicalise(n, i, j, c)
+    got = rama.contract(n, i, j, c, repeat=1)                    # no attractive edge: the canonical form comes back
+    assert np.array_equal(np_(got["i"]), wi) and np.array_equal(np_(got["j"]), wj)
+    assert np.array_equal(np_(got["c"]), wc)
+
+
 # --------------------------------------------------------------------------------------------
 # end to end
 # --------------------------------------------------------------------------------------------
