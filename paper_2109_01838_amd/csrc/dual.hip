@@ -17,6 +17,9 @@
 //   edge kernel:     one thread per edge that lies in a triangle; adds its messages in ascending
 //                    triangle order (slot list built once per round by a stable sort) and stores
 //                    the next share c_e/N_e.  Work is proportional to the triangles, not the edges.
+// Inside the iterations an edge is known by its number among the edges that lie in a triangle (the
+// "active" edges): the shares form a dense array, and the edge id is looked at when the first shares
+// come in and when the final costs go out.
 #include <hip/hip_ext.h>
 
 #include "prim.h"
