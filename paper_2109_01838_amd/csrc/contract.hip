@@ -134,6 +134,7 @@ __global__ __launch_bounds__(kBlock) void k_advance(const uint32_t *n_list, Cand
     const size_t na = *n_list;
     if ((size_t)blockIdx.x * (kBlock * kAdvItems) >= na) return;   // the whole workgroup: nothing left of the list here
     const int w = threadIdx.x >> 6, lane = lane_id();
+    const bool short_list = gridDim.x <= 64;
     const size_t base = (size_t)blockIdx.x * (kBlock * kAdvItems) + (size_t)w * (64 * kAdvItems) + lane;
     int32_t u[kAdvItems], v[kAdvItems];
     unsigned long long r[kAdvItems];
@@ -146,10 +147,14 @@ __global__ __launch_bounds__(kBlock) void k_advance(const uint32_t *n_list, Cand
         bool ok = false, pair = false;
         if (k < na) {
             u[q] = a.u[k]; v[q] = a.v[k];
+            // a short list is all latency: its rank words come in with the endpoints instead of after the test
+            // (on a long list that costs more than it saves: most of its candidates do not survive)
+            unsigned long long rk = 0ull;
+            if (short_list) rk = a.r[k];
             const int32_t mu = mate[u[q]], mv = mate[v[q]];
             ok = mu < 0 && mv < 0;
             pair = mu == v[q];            // this very edge was matched in the round that just ended
-            if (ok) r[q] = a.r[k];
+            if (ok) r[q] = short_list ? rk : a.r[k];
         }
         pairs += (uint32_t)__popcll(__ballot(pair));
         const unsigned long long vote = __ballot(ok);
@@ -166,9 +171,14 @@ __global__ __launch_bounds__(kBlock) void k_advance(const uint32_t *n_list, Cand
     __syncthreads();
     if (threadIdx.x == 0) {
         const uint32_t total = s_wave[0] + s_wave[1] + s_wave[2] + s_wave[3];
-        s_base = total ? atomicAdd(counter, total) : 0u;
         const uint32_t made = s_pairs[0] + s_pairs[1] + s_pairs[2] + s_pairs[3];
-        if (made) atomicAdd(counter + 1, made);     // counter[1]: pairs made in this handshake round
+        if (gridDim.x == 1) {   // the only workgroup: its range starts at 0, and nobody has to wait for the counters
+            s_base = 0u;
+            counter[0] = total; counter[1] = made;
+        } else {
+            s_base = total ? atomicAdd(counter, total) : 0u;
+            if (made) atomicAdd(counter + 1, made);     // counter[1]: pairs made in this handshake round
+        }
     }
     __syncthreads();
     uint32_t off = s_base;
