@@ -30,13 +30,12 @@ struct SignFlags {
 };
 
 // consumer of the scan over SignFlags: an attractive edge goes to place low(prefix) of the attractive
-// lists (also as the pair (j,i) that the lower half of the adjacency is sorted from), a repulsive one
+// list (the lower half of the adjacency is sorted from its pairs read as (j,i)), a repulsive one
 // to place high(prefix) of the repulsive list
 struct SplitSignEmit {
     static constexpr const char *tag = "SplitSign";
     const int32_t *i, *j;
     int32_t *pi, *pj;
-    uint32_t *lkey, *lval;
     int32_t *ri, *rj;
     __device__ __forceinline__ void operator()(size_t e, uint64_t sign, uint64_t prefix) const
     {
@@ -45,7 +44,6 @@ struct SplitSignEmit {
         if (sign == 1ull) {
             const uint32_t p = (uint32_t)prefix;
             pi[p] = a; pj[p] = b;
-            lkey[p] = (uint32_t)b; lval[p] = (uint32_t)a;
         } else {
             const uint32_t p = (uint32_t)(prefix >> 32);
             ri[p] = a; rj[p] = b;
@@ -1093,13 +1091,11 @@ rama_status find_cycles(Ctx &ctx, const Graph &g, int max_len, bool shortest_onl
     Buf<uint32_t> lkey, lval;
     RAMA_TRY(pi.alloc(ctx, mp));
     RAMA_TRY(pj.alloc(ctx, mp));
-    RAMA_TRY(lkey.alloc(ctx, mp));
-    RAMA_TRY(lval.alloc(ctx, mp));
     RAMA_TRY(ri.alloc(ctx, mr));
     RAMA_TRY(rj.alloc(ctx, mr));
     RAMA_TRY((scan_emit<uint64_t>(ctx, SignFlags{g.c.get()},
-                                  SplitSignEmit{g.i.get(), g.j.get(), pi.get(), pj.get(), lkey.get(), lval.get(), ri.get(), rj.get()},
-                                  signs, (double)(m * 8 + (size_t)mp * 16 + (size_t)mr * 8))));
+                                  SplitSignEmit{g.i.get(), g.j.get(), pi.get(), pj.get(), ri.get(), rj.get()},
+                                  signs, (double)(m * 8 + (size_t)mp * 8 + (size_t)mr * 8))));
     signs.offs.reset();
     // positive CSR
     const int32_t n = g.n;
@@ -1116,7 +1112,9 @@ rama_status find_cycles(Ctx &ctx, const Graph &g, int max_len, bool shortest_onl
         RAMA_TRY(zeroed<uint32_t>(ctx, 1, longest));
     }
     RAMA_TRY((row_bounds<int32_t, int32_t>(ctx, pi.get(), mp, n, up_ptr.get())));
-    RAMA_TRY((radix_sort_pairs<uint32_t, uint32_t>(ctx, lkey, lval, mp, bits_for((uint64_t)n), false, nullptr, (uint64_t)n)));
+    // lower neighbours: the attractive pairs read as (j, i), sorted by j (stable: i stays ascending)
+    RAMA_TRY((radix_sort_pairs_from<uint32_t, uint32_t>(ctx, (const uint32_t *)pj.get(), (const uint32_t *)pi.get(), lkey, lval, mp,
+                                                        bits_for((uint64_t)n), (uint64_t)n)));
     RAMA_TRY((row_bounds<uint32_t, int32_t>(ctx, lkey.get(), mp, n, low_ptr.get())));
     {
         ProfScope ps_(ctx, "k_add_ptr", (double)(((size_t)n + 1) * 12));

@@ -1038,7 +1038,7 @@ inline const char *rs_local_name()
 // stable LSD passes over the key bits [shift, shift + total_bits); a/b swap with every pass
 template <typename K, typename V, bool HAS_V>
 rama_status radix_passes(Ctx &ctx, K *&ka, V *&va, K *&kb, V *&vb, size_t n, int shift, int total_bits, uint32_t *hist,
-                         uint32_t *offs, bool *result_in_b, bool *iota)
+                         uint32_t *offs, bool *result_in_b, bool *iota, K *&kc, V *&vc)
 {
     const uint32_t nb = grid_for(n, SortTile<K>::size);
     const int passes = (total_bits + kRadixBits - 1) / kRadixBits;
@@ -1067,6 +1067,10 @@ rama_status radix_passes(Ctx &ctx, K *&ka, V *&va, K *&kb, V *&vb, size_t n, int
         LAUNCH_TRY(ctx, "rs_scatter");
         std::swap(ka, kb);
         std::swap(va, vb);
+        if (kc) {   // the input must stay as it is: from now on the passes alternate between the two other buffers
+            kb = kc; vb = vc;
+            kc = nullptr; vc = nullptr;
+        }
         *result_in_b = !*result_in_b;
         shift += bits;
         remaining -= bits;
@@ -1131,8 +1135,11 @@ static __global__ __launch_bounds__(kBlock) void k_iota(size_t n, uint32_t *p)
 }
 template <typename K, typename V, bool HAS_V>
 rama_status radix_sort_impl(Ctx &ctx, K *ka, V *va, K *kb, V *vb, size_t n, int total_bits, bool *result_in_b, bool iota = false,
-                            Buf<uint32_t> *head_sums = nullptr, uint64_t key_limit = 0)
+                            Buf<uint32_t> *head_sums = nullptr, uint64_t key_limit = 0, K *kc = nullptr, V *vc = nullptr,
+                            K **res_k = nullptr, V **res_v = nullptr)
 {
+    // kc, vc (optional): a third pair of buffers; the input a is then only read, and the sorted data ends up in b or
+    // in c: *res_k, *res_v say where
     // key_limit (optional): all keys are below it (and it needs total_bits bits); 0 = nothing known
     if (key_limit && (total_bits >= 64 || key_limit > (uint64_t(1) << total_bits))) key_limit = 0;
     // head_sums (optional): comes back allocated and filled -- per tile of kScanTile places the number of keys that
@@ -1165,6 +1172,7 @@ rama_status radix_sort_impl(Ctx &ctx, K *ka, V *va, K *kb, V *vb, size_t n, int 
             }
             LAUNCH_TRY(ctx, "rs_local");
             *result_in_b = true;
+            if (res_k) { *res_k = kb; *res_v = vb; }
             return RAMA_OK;
         }
     }
@@ -1197,17 +1205,20 @@ rama_status radix_sort_impl(Ctx &ctx, K *ka, V *va, K *kb, V *vb, size_t n, int 
         const bool split = narrow || plan(LocalSort<uint64_t>::cap, &top_bits);
         if (split) {
             const int low_bits = total_bits - top_bits;
-            RAMA_TRY((radix_passes<K, V, HAS_V>(ctx, ka, va, kb, vb, n, low_bits, top_bits, hist.get(), offs.get(), result_in_b, &iota)));
+            RAMA_TRY((radix_passes<K, V, HAS_V>(ctx, ka, va, kb, vb, n, low_bits, top_bits, hist.get(), offs.get(), result_in_b, &iota, kc, vc)));
             bool done = false;
             if (narrow) RAMA_TRY((split_sort_tail<K, V, HAS_V, uint32_t>(ctx, ka, va, kb, vb, n, low_bits, &done, head_sums)));
             else RAMA_TRY((split_sort_tail<K, V, HAS_V, uint64_t>(ctx, ka, va, kb, vb, n, low_bits, &done, head_sums)));
             if (done) {
                 *result_in_b = !*result_in_b;
+                if (res_k) { *res_k = kb; *res_v = vb; }
                 return RAMA_OK;
             }
         }
     }
-    return radix_passes<K, V, HAS_V>(ctx, ka, va, kb, vb, n, 0, total_bits, hist.get(), offs.get(), result_in_b, &iota);
+    RAMA_TRY((radix_passes<K, V, HAS_V>(ctx, ka, va, kb, vb, n, 0, total_bits, hist.get(), offs.get(), result_in_b, &iota, kc, vc)));
+    if (res_k) { *res_k = ka; *res_v = va; }
+    return RAMA_OK;
 }
 
 // Convenience wrappers working on Buf pairs: after the call `k`/`v` hold the sorted data.
@@ -1232,6 +1243,35 @@ rama_status radix_sort_pairs(Ctx &ctx, Buf<K> &k, Buf<V> &v, size_t n, int total
     bool in_b = false;
     RAMA_TRY((radix_sort_impl<K, V, true>(ctx, k.get(), v.get(), k2.get(), v2.get(), n, total_bits, &in_b, iota, head_sums, key_limit)));
     if (in_b) { k.swap(k2); v.swap(v2); }
+    return RAMA_OK;
+}
+
+// The same sort for pairs that must stay where they are (kin, vin are only read): k, v are allocated here and hold
+// the sorted pairs on return.
+template <typename K, typename V>
+rama_status radix_sort_pairs_from(Ctx &ctx, const K *kin, const V *vin, Buf<K> &k, Buf<V> &v, size_t n, int total_bits,
+                                  uint64_t key_limit = 0)
+{
+    static_assert(sizeof(V) == 4, "32-bit payload");
+    RAMA_TRY(k.alloc(ctx, n > 0 ? n : 1));
+    RAMA_TRY(v.alloc(ctx, n > 0 ? n : 1));
+    if (n <= 1 || total_bits <= 0) {
+        if (n > 0) {
+            HIP_TRY(ctx, hipMemcpyAsync(k.get(), kin, n * sizeof(K), hipMemcpyDeviceToDevice, ctx.stream));
+            HIP_TRY(ctx, hipMemcpyAsync(v.get(), vin, n * sizeof(V), hipMemcpyDeviceToDevice, ctx.stream));
+        }
+        return RAMA_OK;
+    }
+    Buf<K> k2;
+    Buf<V> v2;
+    RAMA_TRY(k2.alloc(ctx, n));
+    RAMA_TRY(v2.alloc(ctx, n));
+    bool in_b = false;
+    K *rk = nullptr;
+    V *rv = nullptr;
+    RAMA_TRY((radix_sort_impl<K, V, true>(ctx, const_cast<K *>(kin), const_cast<V *>(vin), k.get(), v.get(), n, total_bits, &in_b, false,
+                                          nullptr, key_limit, k2.get(), v2.get(), &rk, &rv)));
+    if (rk == k2.get()) { k.swap(k2); v.swap(v2); }
     return RAMA_OK;
 }
 
