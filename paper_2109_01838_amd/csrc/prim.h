@@ -1292,7 +1292,7 @@ rama_status radix_sort_keys(Ctx &ctx, Buf<K> &k, size_t n, int total_bits, Buf<u
 // ------------------------------------------------------------------------------------------
 // deterministic sum of f(0..n-1) in double: per-block partials, then one block adds them in order
 // ------------------------------------------------------------------------------------------
-constexpr int kSumItems = 8;
+constexpr int kSumItems = 32;
 
 template <typename F>
 __global__ __launch_bounds__(kBlock) void k_sum_partial(F f, double *partial, size_t n)
