@@ -214,10 +214,21 @@ __global__ __launch_bounds__(kBlock) void k_merge_edges(size_t m, const int32_t 
 }
 
 // longest row of the upper CSR (bounds the in-row distance between two edges of one row)
+// (a workgroup takes 4096 rows: one atomic per 4096 rows on the result word)
+constexpr int kMaxRowItems = 16;
 __global__ __launch_bounds__(kBlock) void k_max_row(int32_t n, const int32_t *rowptr, uint32_t *out)
 {
-    int32_t v = blockIdx.x * kBlock + threadIdx.x;
-    block_max_into(v < n ? (uint32_t)(rowptr[v + 1] - rowptr[v]) : 0u, out);
+    const size_t base = (size_t)blockIdx.x * (kBlock * kMaxRowItems) + threadIdx.x;
+    uint32_t longest = 0;
+#pragma unroll
+    for (int q = 0; q < kMaxRowItems; ++q) {
+        const size_t v = base + (size_t)q * kBlock;
+        if (v < (size_t)n) {
+            const uint32_t len = (uint32_t)(rowptr[v + 1] - rowptr[v]);
+            longest = len > longest ? len : longest;
+        }
+    }
+    block_max_into(longest, out);
 }
 
 // A triangle u<v<w is keyed by (position e0 of edge (u,v), distance e1-e0 to edge (u,w) in the
@@ -618,7 +629,7 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
     uint32_t *maxrow = (uint32_t *)(flag.get() + 1);
     {
         ProfScope ps_(ctx, "k_max_row", (double)(((size_t)n + 1) * 4));
-        k_max_row<<<grid_for((size_t)n), kBlock, 0, ctx.stream>>>(n, rowptr.get(), maxrow);
+        k_max_row<<<grid_for((size_t)n, kBlock * kMaxRowItems), kBlock, 0, ctx.stream>>>(n, rowptr.get(), maxrow);
     }
     LAUNCH_TRY(ctx, "max_row");
     uint32_t hmax = 0;
