@@ -8,6 +8,7 @@
 #include <list>
 
 #include "common.h"
+#include <type_traits>
 
 namespace rama {
 
@@ -430,6 +431,13 @@ rama_status scan_totals(Ctx &ctx, F f, ScanPlan<TO> &plan, const TO *presums = n
     return RAMA_OK;
 }
 
+// A consumer that works with whole waves (shuffles, ballots) declares `static constexpr bool whole_wave = true`:
+// it is then also called for the places behind the end of the array, with value 0.
+template <typename E, typename = void>
+struct EmitWholeWave { static constexpr bool value = false; };
+template <typename E>
+struct EmitWholeWave<E, std::void_t<decltype(E::whole_wave)>> { static constexpr bool value = E::whole_wave; };
+
 template <typename TO, typename F, typename E>
 __global__ __launch_bounds__(kBlock) void k_scan_emit(F f, E emit, const TO *block_offsets, size_t n)
 {
@@ -458,7 +466,7 @@ __global__ __launch_bounds__(kBlock) void k_scan_emit(F f, E emit, const TO *blo
 #pragma unroll
     for (int q = 0; q < kScanItems; ++q) {
         const size_t k = base + (size_t)q * 64;
-        if (k < n) emit(k, x[q], v[q] + pre);
+        if (EmitWholeWave<E>::value || k < n) emit(k, x[q], v[q] + pre);
     }
 }
 

@@ -512,7 +512,7 @@ def test_profile_hooks_and_workspace(rama):
     prof = rama.profile_get()
     rama.profile_enable(False)
     names = {k["name"] for k in prof}
-    assert {"k_triangle_update", "k_edge_update<false>", "k_edge_update<true>", "k_count_cycles<5>", "k_count_cycles<3>", "k_propose", "k_reduce_runs"} <= names
+    assert {"k_triangle_update", "k_edge_update<false>", "k_edge_update<true>", "k_count_cycles<5>", "k_count_cycles<3>", "k_scan_emit<PackCands>", "k_reduce_runs"} <= names
     assert any(n.startswith("k_rs_scatter<") for n in names) and any(n.startswith("k_scan_apply<") for n in names)
     for k in prof:
         assert k["launches"] > 0 and k["ms"] >= 0.0 and k["bytes"] >= 0.0
