@@ -19,14 +19,24 @@ def short(name):
     return name.split("(")[0]
 
 
-def stats(path, n_solves=1):
+def stats(path, n_solves=1, top=40):
     rows = list(csv.DictReader(open(path)))
     tot = sum(int(r["TotalDurationNs"]) for r in rows)
     print(f"total kernel time {tot / 1e6:.2f} ms over {n_solves} solve(s) = {tot / 1e6 / n_solves:.2f} ms per solve")
     print(f"{'kernel':<70} {'calls':>7} {'total_ms':>10} {'avg_us':>10} {'max_us':>10} {'share':>7}")
-    for r in rows[:40]:
+    for r in rows[:top]:
         print(f"{short(r['Name'])[:70]:<70} {int(r['Calls']):>7} {int(r['TotalDurationNs']) / 1e6:>10.3f} "
               f"{float(r['AverageNs']) / 1e3:>10.1f} {int(r['MaxNs']) / 1e3:>10.1f} {float(r['Percentage']):>6.2f}%")
+    # instantiations that the library's own timers count as one kernel, taken together
+    merged = defaultdict(lambda: [0, 0, 0])
+    for r in rows:
+        a = merged[event_name(r["Name"])]
+        a[0] += 1
+        a[1] += int(r["Calls"])
+        a[2] += int(r["TotalDurationNs"])
+    for name, (k, calls, ns) in sorted(merged.items(), key=lambda kv: -kv[1][2])[:12]:
+        if k > 1:
+            print(f"{name + ' (its ' + str(k) + ' instantiations together)':<70} {calls:>7} {ns / 1e6:>10.3f} {ns / 1e3 / calls:>10.1f}")
 
 
 def pmc(path, counter, subs):
@@ -124,7 +134,7 @@ def report(raw, out):
     n_solves = 5      # bench.py default: 1 warm-up + 1 all-kernel-timed + 3 timed solves
     d = json.loads([l for l in open(os.path.join(raw, "bench_rocprof.log")) if l.startswith("{")][-1])
     r = d["roofline"]
-    stats_txt = capture(stats, os.path.join(raw, "prof_bench", "bench_kernel_stats.csv"), n_solves)
+    stats_txt = capture(stats, os.path.join(raw, "prof_bench", "bench_kernel_stats.csv"), n_solves, 26)
     with open(os.path.join(out, "cfg5_solve_kernel_trace.txt"), "w") as f:
         f.write(f"""# rocprofv3 kernel-trace summary: bench.py default run ({d['config']['workload']}, {d['config']['n_edges']} edges; 1 warm-up + 1 all-kernel-timed + 3 timed solves = {n_solves} solves)
 # command (on the GPU box; $REPO = repository root, $OUT = any scratch directory):
@@ -132,10 +142,11 @@ def report(raw, out):
 # condensed with: python -m paper_2109_01838_amd.profile_summary report $OUT profiles
 # bench.py's own HIP-event figures for the dominant kernel in the same run:
 #   {r['kernel']} avg_launch_ms {r['avg_launch_ms']:.5f} launches_per_step {r['launches_per_step']} achieved GB/s {r['achieved']:.1f} frac {r['frac']:.4f}
-#   ms_per_step {d['ms_per_step']:.2f} edges/s {d['value']:.0f} (under the profiler)
+#   ms_per_step {d['ms_per_step']:.2f} edges/s {d['value']:.0f} (under the profiler, whose interception lengthens what the
+#   events see: the run without it measures the trace's average, see the merged row at the end of the table)
 
 """)
-        f.write("\n".join(stats_txt.splitlines()[:28]) + "\n")
+        f.write(stats_txt)
     fetch = os.path.join(raw, "pmc_fetch", "fetch_counter_collection.csv")
     write = os.path.join(raw, "pmc_write", "write_counter_collection.csv")
     cf, cw = copy_calibration(fetch, "FETCH_SIZE"), copy_calibration(write, "WRITE_SIZE")
@@ -166,7 +177,7 @@ def report_workload(raw, out, workload):
     import os
     n_solves = 5
     d = json.loads([l for l in open(os.path.join(raw, f"bench_{workload}_rocprof.log")) if l.startswith("{")][-1])
-    stats_txt = capture(stats, os.path.join(raw, f"prof_{workload}", f"{workload}_kernel_stats.csv"), n_solves)
+    stats_txt = capture(stats, os.path.join(raw, f"prof_{workload}", f"{workload}_kernel_stats.csv"), n_solves, 32)
     with open(os.path.join(out, f"{workload}_solve_kernel_trace.txt"), "w") as f:
         f.write(f"""# rocprofv3 kernel-trace summary: bench.py on {d['config']['workload']} ({d['config']['n_edges']} edges; 1 warm-up + 1 all-kernel-timed + 3 timed solves = {n_solves} solves)
 # command (on the GPU box; $REPO = repository root, $OUT = any scratch directory):
@@ -175,7 +186,7 @@ def report_workload(raw, out, workload):
 # bench.py in the same run: ms_per_step {d['ms_per_step']:.2f} (under the profiler), rounds {d['rounds']}, cycles found in round 1 {d['n_cycles_first'][:3]}
 
 """)
-        f.write("\n".join(stats_txt.splitlines()[:34]) + "\n")
+        f.write(stats_txt)
 
 
 if __name__ == "__main__":
