@@ -485,69 +485,79 @@ rama_status scan_emit(Ctx &ctx, F f, E emit, const ScanPlan<TO> &plan, double by
 
 // ------------------------------------------------------------------------------------------
 // row boundaries: keys[0..m) ascending with values in [0,n); ptr[v] = first position whose key
-// is >= v, for v in [0,n]  (ptr[n] = m).
-// One thread per position fills the short gap of rows before it; rows inside a long gap (empty
-// stretches of a sparse key set) are left marked and found by binary search, one thread per row,
-// so no thread ever loops over a long stretch.
+// is >= v, for v in [0,n]  (ptr[n] = m).  One launch, and every row is written exactly once:
+//  - keys at least an eighth as many as rows: one thread per position fills the gap of rows before it when
+//    the key changes there; a gap of more than kRowGapInline rows goes to a list in LDS that the whole
+//    workgroup then fills side by side, so no thread ever loops over a long stretch alone;
+//  - fewer keys than that (the empty stretches of a sparse key set are the rule): one thread per row,
+//    binary search.
 // ------------------------------------------------------------------------------------------
 constexpr int kRowGapInline = 32;
 
 // four positions per thread, read as one 16-byte vector (keys are 4 bytes wide)
 template <typename K, typename P>
-__global__ __launch_bounds__(kBlock) void k_row_bounds_mark(const K *keys, size_t m, int64_t n, P *ptr)
+__global__ __launch_bounds__(kBlock) void k_row_bounds_fill(const K *keys, size_t m, int64_t n, P *ptr)
 {
     static_assert(sizeof(K) == 4, "32-bit keys");
+    __shared__ uint32_t s_count;
+    __shared__ int64_t s_from[kBlock * 4], s_to[kBlock * 4];
+    __shared__ P s_pos[kBlock * 4];
+    if (threadIdx.x == 0) s_count = 0u;
+    __syncthreads();
     const size_t e0 = ((size_t)blockIdx.x * kBlock + threadIdx.x) * 4;
-    if (e0 > m) return;
-    K k[4];
-    if (e0 + 4 <= m) {
-        const uint4 v = *reinterpret_cast<const uint4 *>(keys + e0);   // e0 is a multiple of 4, the array 16-byte aligned
-        k[0] = (K)v.x; k[1] = (K)v.y; k[2] = (K)v.z; k[3] = (K)v.w;
-    } else {
+    if (e0 <= m) {
+        K k[4];
+        if (e0 + 4 <= m) {
+            const uint4 v = *reinterpret_cast<const uint4 *>(keys + e0);   // e0 is a multiple of 4, the array 16-byte aligned
+            k[0] = (K)v.x; k[1] = (K)v.y; k[2] = (K)v.z; k[3] = (K)v.w;
+        } else {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) k[q] = e0 + q < m ? keys[e0 + q] : (K)0;
-    }
-    int64_t prev = (e0 == 0) ? -1 : (int64_t)keys[e0 - 1];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const size_t e = e0 + q;
-        if (e > m) break;
-        const int64_t cur = (e == m) ? n : (int64_t)k[q];
-        if (cur != prev) {
-            if (cur - prev <= kRowGapInline)
-                for (int64_t v = prev + 1; v <= cur; ++v) ptr[v] = (P)e;
-            else
-                ptr[cur] = (P)e;
+            for (int q = 0; q < 4; ++q) k[q] = e0 + q < m ? keys[e0 + q] : (K)0;
         }
-        prev = cur;
+        int64_t prev = (e0 == 0) ? -1 : (int64_t)keys[e0 - 1];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const size_t e = e0 + q;
+            if (e > m) break;
+            const int64_t cur = (e == m) ? n : (int64_t)k[q];
+            if (cur != prev) {
+                if (cur - prev <= kRowGapInline) {
+                    for (int64_t v = prev + 1; v <= cur; ++v) ptr[v] = (P)e;
+                } else {      // at most one entry per position: the list cannot overflow
+                    const uint32_t slot = atomicAdd(&s_count, 1u);
+                    s_from[slot] = prev + 1; s_to[slot] = cur; s_pos[slot] = (P)e;
+                }
+            }
+            prev = cur;
+        }
+    }
+    __syncthreads();
+    const uint32_t n_long = s_count;
+    for (uint32_t g = 0; g < n_long; ++g) {
+        const int64_t to = s_to[g];
+        const P e = s_pos[g];
+        for (int64_t v = s_from[g] + threadIdx.x; v <= to; v += kBlock) ptr[v] = e;
     }
 }
 
-// four rows per thread, looked at as one 16-byte vector (row pointers are 4 bytes wide)
+// four rows per thread; a row's search starts where the row before it ended
 template <typename K, typename P>
 __global__ __launch_bounds__(kBlock) void k_row_bounds_search(const K *keys, size_t m, int64_t n, P *ptr)
 {
-    static_assert(sizeof(P) == 4, "32-bit row pointers");
     const int64_t v0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
     if (v0 > n) return;
-    P cur[4];
-    if (v0 + 3 <= n) {
-        const uint4 w = *reinterpret_cast<const uint4 *>(ptr + v0);
-        cur[0] = (P)w.x; cur[1] = (P)w.y; cur[2] = (P)w.z; cur[3] = (P)w.w;
-    } else {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) cur[q] = v0 + q <= n ? ptr[v0 + q] : (P)0;
-    }
+    size_t from = 0;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const int64_t v = v0 + q;
-        if (v > n || cur[q] != (P)-1) continue;
-        size_t lo = 0, hi = m;
+        if (v > n) break;
+        size_t lo = from, hi = m;
         while (lo < hi) {
             size_t mid = lo + ((hi - lo) >> 1);
             if ((int64_t)keys[mid] < v) lo = mid + 1; else hi = mid;
         }
         ptr[v] = (P)lo;
+        from = lo;
     }
 }
 
@@ -1450,17 +1460,14 @@ rama_status fill(Ctx &ctx, T *p, T v, size_t n)
 template <typename K, typename P>
 rama_status row_bounds(Ctx &ctx, const K *keys, size_t m, int64_t n, P *ptr)
 {
-    RAMA_TRY(fill<P>(ctx, ptr, (P)-1, (size_t)n + 1));
-    {
-        ProfScope ps_(ctx, "k_row_bounds_mark", (double)(m * sizeof(K) + ((size_t)n + 1) * sizeof(P)));
-        k_row_bounds_mark<K, P><<<grid_for(m / 4 + 1), kBlock, 0, ctx.stream>>>(keys, m, n, ptr);
-    }
-    LAUNCH_TRY(ctx, "row_bounds_mark");
-    {
-        ProfScope ps_(ctx, "k_row_bounds_search", (double)(((size_t)n + 1) * sizeof(P)));
+    if (m >= (size_t)n / 8) {
+        ProfScope ps_(ctx, "k_row_bounds_fill", (double)(m * sizeof(K) + ((size_t)n + 1) * sizeof(P)));
+        k_row_bounds_fill<K, P><<<grid_for(m / 4 + 1), kBlock, 0, ctx.stream>>>(keys, m, n, ptr);
+    } else {
+        ProfScope ps_(ctx, "k_row_bounds_search", (double)(m * sizeof(K) + ((size_t)n + 1) * sizeof(P)));
         k_row_bounds_search<K, P><<<grid_for((size_t)n / 4 + 1), kBlock, 0, ctx.stream>>>(keys, m, n, ptr);
     }
-    LAUNCH_TRY(ctx, "row_bounds_search");
+    LAUNCH_TRY(ctx, "row_bounds");
     return RAMA_OK;
 }
 

@@ -596,6 +596,53 @@ def star_graph(n_leaves, seed):
     return dict(name=f"star_{n_leaves}", n_nodes=n_leaves + 1, i=i[perm], j=j[perm], c=c[perm])
 
 
+def gappy_graph(n, kind, seed):
+    """Graphs whose node rows have long empty stretches.  'clusters': dense little cliques-with-noise far apart
+    in the node numbering (many edges, gaps of thousands of rows between them); 'sparse': a few triangles
+    scattered over many nodes (far fewer edges than rows); 'tail': all edges among the last few nodes."""
+    rng = np.random.default_rng(seed)
+    ii, jj = [], []
+    if kind == "clusters":
+        for base in range(0, n - 64, max(64, n // 40)):
+            nodes = base + np.arange(48)
+            a = rng.choice(nodes, 400); b = rng.choice(nodes, 400)
+            ii.append(a); jj.append(b)
+    elif kind == "sparse":
+        for base in rng.choice(n - 3, 60, replace=False):
+            ii.append(np.array([base, base + 1, base])); jj.append(np.array([base + 1, base + 2, base + 2]))
+    else:
+        nodes = n - 40 + np.arange(40)
+        ii.append(rng.choice(nodes, 500)); jj.append(rng.choice(nodes, 500))
+    i = np.concatenate(ii).astype(np.int32); j = np.concatenate(jj).astype(np.int32)
+    keep = i != j
+    i, j = i[keep], j[keep]
+    mag = np.abs(rng.normal(0.0, 1.0, i.size)).astype(np.float32) + 0.05
+    c = np.where(rng.random(i.size) < 0.65, mag, -mag).astype(np.float32)
+    return dict(n_nodes=n, i=i, j=j, c=c)
+
+
+@pytest.mark.parametrize("kind", ["clusters", "sparse", "tail"])
+@pytest.mark.parametrize("n", [5000, 60000, 300000])
+def test_rows_with_long_empty_stretches(rama, oracle32, kind, n):
+    """Row pointers over node sets that are mostly empty: long gaps are filled by whole workgroups, sparse key
+    sets are searched per row; cycles, message passing and the whole solve must not notice."""
+    g = gappy_graph(n, kind, 11)
+    want = oracle32.find_conflicted_cycles(n, g["i"], g["j"], g["c"], 5)
+    got = rama.find_conflicted_cycles(n, g["i"], g["j"], g["c"], 5)
+    for a, b in zip(got, want):
+        assert np.array_equal(np_(a), b)
+    wmp = oracle32.message_passing(n, g["i"], g["j"], g["c"], want, 3)
+    mp = rama.message_passing(n, g["i"], g["j"], g["c"], want, 3)
+    assert np.array_equal(np_(mp["i"]), wmp["i"]) and np.array_equal(np_(mp["j"]), wmp["j"])
+    assert rel_close(np_(mp["c"]), wmp["c"])
+    ws = oracle32.solve(n, g["i"], g["j"], g["c"])
+    gs = rama.solve(n, g["i"], g["j"], g["c"])
+    assert gs["n_cycles_first"] == ws["n_cycles_first"] and gs["rounds"] == ws["rounds"]
+    assert np.array_equal(np_(gs["labels"]), ws["labels"])
+    assert abs(gs["lower_bound"] - ws["lower_bound"]) <= REL * max(1.0, abs(ws["lower_bound"]))
+    print(kind, n, [x.shape[0] for x in want], gs["rounds"])
+
+
 @pytest.mark.parametrize("name", list(CASES))
 def test_split_sort_stagewise(rama_split, oracle32, name):
     from paper_2109_01838_amd import default_params
