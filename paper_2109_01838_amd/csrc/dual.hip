@@ -376,7 +376,7 @@ template <bool FIRST>
 __global__ __launch_bounds__(kBlock) void k_triangle_update(size_t T, const uint32_t *tri_act, const float *share,
                                                             float *ct, float *msg)
 {
-    size_t t = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    size_t t = (size_t)xcd_block() * kBlock + threadIdx.x;
     if (t >= T) return;
     const uint32_t e0 = tri_act[3 * t], e1 = tri_act[3 * t + 1], e2 = tri_act[3 * t + 2];
     // edges -> triangles
@@ -413,7 +413,8 @@ __global__ __launch_bounds__(kBlock) void k_edge_update(size_t na, const uint32_
                                                                const uint32_t *slot, const float *msg, float *ce, float *share)
 {
     __shared__ float sm[kEdgeChunk];
-    const size_t a0 = (size_t)blockIdx.x * (kBlock * kEdgesPerThread);
+    const size_t a0 = (size_t)xcd_block() * (kBlock * kEdgesPerThread);
+    if (a0 >= na) return;      // the whole workgroup
     const size_t alast = a0 + kBlock * kEdgesPerThread < na ? a0 + kBlock * kEdgesPerThread : na;
     const uint32_t P0 = act_start[a0], P1 = act_start[alast];
     uint32_t p0[kEdgesPerThread], p1[kEdgesPerThread];
@@ -724,25 +725,25 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
             hipEvent_t ea, eb;
             ctx.prof.begin_stamped("k_triangle_update", (double)(T * (first ? 48 : 60)), &ea, &eb);
             if (first)
-                hipExtLaunchKernelGGL(k_triangle_update<true>, dim3(grid_for(T)), dim3(kBlock), 0, ctx.stream, ea, eb, 0, (size_t)T,
+                hipExtLaunchKernelGGL(k_triangle_update<true>, dim3(xcd_grid(grid_for(T))), dim3(kBlock), 0, ctx.stream, ea, eb, 0, (size_t)T,
                                       (const uint32_t *)tri_act.get(), (const float *)share.get(), (float *)ct.get(), (float *)msg.get());
             else
-                hipExtLaunchKernelGGL(k_triangle_update<false>, dim3(grid_for(T)), dim3(kBlock), 0, ctx.stream, ea, eb, 0, (size_t)T,
+                hipExtLaunchKernelGGL(k_triangle_update<false>, dim3(xcd_grid(grid_for(T))), dim3(kBlock), 0, ctx.stream, ea, eb, 0, (size_t)T,
                                       (const uint32_t *)tri_act.get(), (const float *)share.get(), (float *)ct.get(), (float *)msg.get());
         } else if (first) {
-            k_triangle_update<true><<<grid_for(T), kBlock, 0, ctx.stream>>>(T, tri_act.get(), share.get(), ct.get(), msg.get());
+            k_triangle_update<true><<<xcd_grid(grid_for(T)), kBlock, 0, ctx.stream>>>(T, tri_act.get(), share.get(), ct.get(), msg.get());
         } else {
-            k_triangle_update<false><<<grid_for(T), kBlock, 0, ctx.stream>>>(T, tri_act.get(), share.get(), ct.get(), msg.get());
+            k_triangle_update<false><<<xcd_grid(grid_for(T)), kBlock, 0, ctx.stream>>>(T, tri_act.get(), share.get(), ct.get(), msg.get());
         }
         LAUNCH_TRY(ctx, "triangle_update");
         {
             const bool store_ce = it == k_iters || lb_trace != nullptr;
             ProfScope ps_(ctx, store_ce ? "k_edge_update<true>" : "k_edge_update<false>", (double)(na * (store_ce ? 16 : 8) + 3 * T * 8));
             if (store_ce)
-                k_edge_update<true><<<grid_for(na, kBlock * kEdgesPerThread), kBlock, 0, ctx.stream>>>(na, act_edge.get(), act_start.get(), slot.get(),
+                k_edge_update<true><<<xcd_grid(grid_for(na, kBlock * kEdgesPerThread)), kBlock, 0, ctx.stream>>>(na, act_edge.get(), act_start.get(), slot.get(),
                                                                          msg.get(), ce, share.get());
             else
-                k_edge_update<false><<<grid_for(na, kBlock * kEdgesPerThread), kBlock, 0, ctx.stream>>>(na, act_edge.get(), act_start.get(), slot.get(),
+                k_edge_update<false><<<xcd_grid(grid_for(na, kBlock * kEdgesPerThread)), kBlock, 0, ctx.stream>>>(na, act_edge.get(), act_start.get(), slot.get(),
                                                                           msg.get(), ce, share.get());
         }
         LAUNCH_TRY(ctx, "edge_update");

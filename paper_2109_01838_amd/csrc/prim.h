@@ -43,6 +43,14 @@ inline rama_status zero_page_recycle(Ctx &ctx)
 // ------------------------------------------------------------------------------------------
 __device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & 63); }
 
+// Consecutive workgroups of a launch go to the eight XCDs in turn, each with an L2 of its own.  A kernel whose
+// neighbouring workgroups gather from the same stretch of an array then fetches that stretch into all eight L2s.
+// Launched with xcd_grid(nb) workgroups and numbering its work by xcd_block(), a kernel gives every XCD one
+// contiguous eighth of the work instead; numbers beyond nb - 1 come up for the padding and must leave at once.
+// (The assignment of workgroups to XCDs only decides how well this works, not what is computed.)
+inline uint32_t xcd_grid(uint32_t nb) { return ((nb + 7u) / 8u) * 8u; }
+__device__ __forceinline__ uint32_t xcd_block() { return (blockIdx.x & 7u) * (gridDim.x >> 3) + (blockIdx.x >> 3); }
+
 template <typename T>
 __device__ __forceinline__ T wave_inclusive_scan(T v)
 {
