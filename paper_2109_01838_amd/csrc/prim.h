@@ -612,18 +612,13 @@ struct alignas(16) KeyVec {
     K k[16 / sizeof(K)];
 };
 
-// The [digit][tile] tables of a pass.  A workgroup stores (and later fetches) one word in each of up to 256 rows;
-// written tile after tile, a cache line of a row collects the words of sixteen workgroups that run on eight
-// different XCDs, so each L2 holds two words of it and writes them back on their own (measured: 26 MB written for
-// a 3.2 MB table).  With `nb8` set (= tiles / 8, rounded up) the tiles of one XCD -- every eighth workgroup --
-// are neighbours in the row instead: column (tile mod 8) * nb8 + tile / 8, rows 8 * nb8 wide.  Which XCD a
-// workgroup runs on only decides how well this works, not what is computed.
-__device__ __forceinline__ size_t rs_table_col(uint32_t tile, uint32_t nb8) { return nb8 ? (size_t)(tile & 7u) * nb8 + (tile >> 3) : (size_t)tile; }
-__device__ __forceinline__ size_t rs_table_width(uint32_t nb, uint32_t nb8) { return nb8 ? (size_t)8 * nb8 : (size_t)nb; }
-
+// The [digit][tile] tables of a pass: a workgroup stores (and later fetches) one word in each of up to 256 rows.
+// Workgroups take their tiles by xcd_block(): with tile = workgroup number, a cache line of a row collected the
+// words of sixteen workgroups on eight XCDs, two words per L2, and went to memory in pieces (26 MB written for a
+// 3.2 MB table); the runs the scatter kernel writes for neighbouring tiles meet in one L2 as well.
 template <typename K>
 __global__ __launch_bounds__(kBlock) void k_rs_hist(const K *keys, uint32_t *hist, size_t n, int shift, int bits,
-                                                    uint32_t nb, uint32_t nb8)
+                                                    uint32_t nb)
 {
     constexpr int kPer = 16 / (int)sizeof(K);                 // keys per vector
     constexpr int kVecs = SortTile<K>::items / kPer;          // vectors per thread
@@ -632,7 +627,9 @@ __global__ __launch_bounds__(kBlock) void k_rs_hist(const K *keys, uint32_t *his
     for (int k = threadIdx.x; k < kRadix; k += kBlock) h[k] = 0;
     __syncthreads();
     const uint32_t mask = (1u << bits) - 1u;
-    const size_t tile = (size_t)blockIdx.x * SortTile<K>::size;
+    const uint32_t tile_id = xcd_block();
+    if (tile_id >= nb) return;      // the whole workgroup (padding of the grid)
+    const size_t tile = (size_t)tile_id * SortTile<K>::size;
     if (tile + SortTile<K>::size <= n) {                      // full tile: vector loads (tile starts are 16-byte aligned)
         const KeyVec<K> *src = reinterpret_cast<const KeyVec<K> *>(keys + tile);
 #pragma unroll
@@ -666,36 +663,30 @@ __global__ __launch_bounds__(kBlock) void k_rs_hist(const K *keys, uint32_t *his
             atomicAdd(&h[(uint32_t)(keys[idx] >> shift) & mask], 1u);
     }
     __syncthreads();
-    const size_t width = rs_table_width(nb, nb8), col = rs_table_col(blockIdx.x, nb8);
-    for (uint32_t d = threadIdx.x; d <= mask; d += kBlock) hist[(size_t)d * width + col] = h[d];
+    for (uint32_t d = threadIdx.x; d <= mask; d += kBlock) hist[(size_t)d * nb + tile_id] = h[d];
 }
 
 // Offsets of a pass from its [digit][tile] histogram: workgroup d scans row d (keys with digit d in
 // earlier tiles) and stores the row's total behind the table; the scatter kernel adds the keys of
 // smaller digits itself, from the 256 totals.  One launch instead of the three of a general scan.
-// (A thread's eight consecutive tiles sit in the eight column groups of the tables, neighbouring threads' tiles
-// next to each other in every group.)
-static __global__ __launch_bounds__(kBlock) void k_rs_rowscan(const uint32_t *hist, uint32_t *offs, uint32_t nb, uint32_t nb8,
-                                                              uint32_t *totals)
+static __global__ __launch_bounds__(kBlock) void k_rs_rowscan(const uint32_t *hist, uint32_t *offs, uint32_t nb, uint32_t *totals)
 {
-    static_assert(kScanItems == 8, "a thread's tiles start at a multiple of eight");
-    const size_t width = rs_table_width(nb, nb8);
-    const uint32_t *in = hist + (size_t)blockIdx.x * width;
-    uint32_t *out = offs + (size_t)blockIdx.x * width;
+    const uint32_t *in = hist + (size_t)blockIdx.x * nb;
+    uint32_t *out = offs + (size_t)blockIdx.x * nb;
     uint32_t carry = 0;
     for (uint32_t c0 = 0; c0 < nb; c0 += kScanTile) {
         const uint32_t base = c0 + threadIdx.x * kScanItems;
         uint32_t v[kScanItems], s = 0;
 #pragma unroll
         for (int q = 0; q < kScanItems; ++q) {
-            v[q] = (base + q < nb) ? in[rs_table_col(base + q, nb8)] : 0u;
+            v[q] = (base + q < nb) ? in[base + q] : 0u;
             s += v[q];
         }
         uint32_t tot;
         uint32_t run = block_inclusive_scan(s, &tot) - s + carry;
 #pragma unroll
         for (int q = 0; q < kScanItems; ++q) {
-            if (base + q < nb) out[rs_table_col(base + q, nb8)] = run;
+            if (base + q < nb) out[base + q] = run;
             run += v[q];
         }
         carry += tot;
@@ -725,7 +716,7 @@ constexpr uint32_t kSortLocalScanTiles = 32;
 template <typename K, typename V, bool HAS_V, bool LOCAL_SCAN>
 __global__ __launch_bounds__(kBlock) void k_rs_scatter(const K *kin, const V *vin, K *kout, V *vout,
                                                        const uint32_t *offs, size_t n, int shift, int bits,
-                                                       uint32_t nb, uint32_t nb8)
+                                                       uint32_t nb)
 {
     constexpr int kSortItems = SortTile<K>::items;
     constexpr int kSortTile = SortTile<K>::size;
@@ -735,9 +726,11 @@ __global__ __launch_bounds__(kBlock) void k_rs_scatter(const K *kin, const V *vi
     __shared__ uint32_t sval[HAS_V ? kSortTile : 1];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const uint32_t mask = (1u << bits) - 1u;
+    const uint32_t tile_id = xcd_block();
+    if (tile_id >= nb) return;      // the whole workgroup (padding of the grid)
     for (int k = tid; k < 4 * kRadix; k += kBlock) (&whist[0][0])[k] = 0;
     __syncthreads();
-    const size_t tile_base = (size_t)blockIdx.x * kSortTile;
+    const size_t tile_base = (size_t)tile_id * kSortTile;
     const size_t wave_base = tile_base + (size_t)w * (64 * kSortItems);
     const uint64_t lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
     K key[kSortItems];
@@ -784,7 +777,7 @@ __global__ __launch_bounds__(kBlock) void k_rs_scatter(const K *kin, const V *vi
                 if (d <= mask)
                     for (uint32_t b = 0; b < nb; ++b) {
                         uint32_t h = offs[(size_t)d * nb + b];
-                        if (b < blockIdx.x) before[q] += h;
+                        if (b < tile_id) before[q] += h;
                         rowsum[q] += h;
                     }
                 rows += rowsum[q];
@@ -795,8 +788,7 @@ __global__ __launch_bounds__(kBlock) void k_rs_scatter(const K *kin, const V *vi
             for (int q = 0; q < kDigitsPerThread; ++q) { goff[q] = dig + before[q]; dig += rowsum[q]; }
         } else {
             // offs: per digit the keys in earlier tiles, and behind the table the digits' totals
-            const size_t width = rs_table_width(nb, nb8), col = rs_table_col(blockIdx.x, nb8);
-            const uint32_t *totals = offs + (size_t)kRadix * width;
+            const uint32_t *totals = offs + (size_t)kRadix * nb;
             uint32_t rows = 0, rowsum[kDigitsPerThread];
 #pragma unroll
             for (int q = 0; q < kDigitsPerThread; ++q) {
@@ -809,7 +801,7 @@ __global__ __launch_bounds__(kBlock) void k_rs_scatter(const K *kin, const V *vi
 #pragma unroll
             for (int q = 0; q < kDigitsPerThread; ++q) {
                 const uint32_t d = (uint32_t)(tid * kDigitsPerThread + q);
-                goff[q] = dig + (d <= mask ? offs[(size_t)d * width + col] : 0u);
+                goff[q] = dig + (d <= mask ? offs[(size_t)d * nb + tile_id] : 0u);
                 dig += rowsum[q];
             }
         }
@@ -1086,31 +1078,28 @@ rama_status radix_passes(Ctx &ctx, K *&ka, V *&va, K *&kb, V *&vb, size_t n, int
                          uint32_t *offs, bool *result_in_b, bool *iota, K *&kc, V *&vc)
 {
     const uint32_t nb = grid_for(n, SortTile<K>::size);
-    // few tiles: the scatter kernel scans the plain table itself; many: column groups per XCD (see rs_table_col)
-    const uint32_t nb8 = nb <= kSortLocalScanTiles ? 0u : (nb + 7u) / 8u;
-    const size_t width = nb8 ? (size_t)8 * nb8 : (size_t)nb;
     const int passes = (total_bits + kRadixBits - 1) / kRadixBits;
     int remaining = total_bits;
     for (int p = 0; p < passes; ++p) {
         int bits = (remaining + (passes - p) - 1) / (passes - p);
         {
             ProfScope ps_(ctx, (sizeof(K) == 8 ? "k_rs_hist<u64>" : "k_rs_hist<u32>"), (double)(n * sizeof(K)));
-            k_rs_hist<K><<<nb, kBlock, 0, ctx.stream>>>(ka, hist, n, shift, bits, nb, nb8);
+            k_rs_hist<K><<<xcd_grid(nb), kBlock, 0, ctx.stream>>>(ka, hist, n, shift, bits, nb);
         }
         LAUNCH_TRY(ctx, "rs_hist");
         const V *vin = (HAS_V && *iota) ? (const V *)nullptr : va;   // the first pass of a sort whose values are the places 0..n-1
         *iota = false;
         if (nb <= kSortLocalScanTiles) {
             ProfScope ps_(ctx, rs_scatter_name<K, HAS_V>(), (double)(n * (2 * sizeof(K) + (HAS_V ? 8 : 0))));
-            k_rs_scatter<K, V, HAS_V, true><<<nb, kBlock, 0, ctx.stream>>>(ka, vin, kb, vb, hist, n, shift, bits, nb, 0u);
+            k_rs_scatter<K, V, HAS_V, true><<<xcd_grid(nb), kBlock, 0, ctx.stream>>>(ka, vin, kb, vb, hist, n, shift, bits, nb);
         } else {
             {
                 ProfScope ps_(ctx, "k_rs_rowscan", (double)(((size_t)nb << bits) * 8));
-                k_rs_rowscan<<<1u << bits, kBlock, 0, ctx.stream>>>(hist, offs, nb, nb8, offs + (size_t)kRadix * width);
+                k_rs_rowscan<<<1u << bits, kBlock, 0, ctx.stream>>>(hist, offs, nb, offs + (size_t)kRadix * nb);
             }
             LAUNCH_TRY(ctx, "rs_rowscan");
             ProfScope ps_(ctx, rs_scatter_name<K, HAS_V>(), (double)(n * (2 * sizeof(K) + (HAS_V ? 8 : 0))));
-            k_rs_scatter<K, V, HAS_V, false><<<nb, kBlock, 0, ctx.stream>>>(ka, vin, kb, vb, offs, n, shift, bits, nb, nb8);
+            k_rs_scatter<K, V, HAS_V, false><<<xcd_grid(nb), kBlock, 0, ctx.stream>>>(ka, vin, kb, vb, offs, n, shift, bits, nb);
         }
         LAUNCH_TRY(ctx, "rs_scatter");
         std::swap(ka, kb);
@@ -1226,8 +1215,8 @@ rama_status radix_sort_impl(Ctx &ctx, K *ka, V *va, K *kb, V *vb, size_t n, int 
     }
     const uint32_t nb = grid_for(n, SortTile<K>::size);
     Buf<uint32_t> hist, offs;
-    RAMA_TRY(hist.alloc(ctx, (size_t)kRadix * (nb + 8)));            // rows are padded to a multiple of eight tiles
-    RAMA_TRY(offs.alloc(ctx, (size_t)kRadix * (nb + 8) + kRadix));
+    RAMA_TRY(hist.alloc(ctx, (size_t)kRadix * nb));
+    RAMA_TRY(offs.alloc(ctx, (size_t)kRadix * nb + kRadix));
     const int all_passes = (total_bits + kRadixBits - 1) / kRadixBits;
     if (n >= ctx.sort_split_min) {
         // top bits: whole passes, enough of them for segments that a workgroup can hold.  A workgroup takes the
