@@ -49,7 +49,11 @@ __device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & 63); }
 // contiguous eighth of the work instead; numbers beyond nb - 1 come up for the padding and must leave at once.
 // (The assignment of workgroups to XCDs only decides how well this works, not what is computed.)
 inline uint32_t xcd_grid(uint32_t nb) { return ((nb + 7u) / 8u) * 8u; }
-__device__ __forceinline__ uint32_t xcd_block() { return (blockIdx.x & 7u) * (gridDim.x >> 3) + (blockIdx.x >> 3); }
+__device__ __forceinline__ uint32_t xcd_block()
+{
+    if (gridDim.x & 7u) return blockIdx.x;     // not launched with xcd_grid: plain numbering (every number still comes up once)
+    return (blockIdx.x & 7u) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+}
 
 template <typename T>
 __device__ __forceinline__ T wave_inclusive_scan(T v)
