@@ -149,6 +149,53 @@ __global__ __launch_bounds__(kBlock) void k_chord_keys(CycleSet s, size_t nch, i
     key[q] = ((uint64_t)(uint32_t)min(a, b) << nbits) | (uint32_t)max(a, b);
 }
 
+// Cycles of five and more nodes are listed walk by walk, and neighbouring walks from one repulsive edge share their
+// first nodes: the m-th chord of a cycle very often repeats the m-th chord of the cycle listed before it (on a
+// neighbour graph three chord candidates in four).  Those repeats are left out before the sort (the sort's
+// consumers drop equal keys anyway); what remains also spreads evenly enough for the split sort.
+template <int K>
+__device__ __forceinline__ bool chord_pick_new(const CycleSet &s, uint32_t q, int32_t &a, int32_t &b)
+{
+    if constexpr (K >= kCycleLists) {
+        a = b = 0;
+        return false;
+    } else {
+        if (q < s.chord_end[K]) {
+            const uint32_t r = q - s.chord_end[K - 1], cyc = r / (uint32_t)K, mth = r - cyc * (uint32_t)K;
+            const int32_t *v = s.c[K] + (uint32_t)(K + 3) * cyc;
+            a = v[0]; b = v[2 + mth];
+            if (cyc == 0) return true;
+            const int32_t *p = v - (K + 3);      // the cycle listed before
+            return p[0] != a || p[2 + mth] != b;
+        } else {
+            return chord_pick_new<K + 1>(s, q, a, b);
+        }
+    }
+}
+struct ChordIsNew {
+    static constexpr int bytes = 16;   // bytes read per item (two nodes of two cycles)
+    static constexpr const char *tag = "ChordIsNew";
+    CycleSet s;
+    __device__ __forceinline__ uint32_t operator()(size_t q) const
+    {
+        int32_t a, b;
+        return chord_pick_new<1>(s, (uint32_t)q, a, b) ? 1u : 0u;
+    }
+};
+struct ChordKeysEmit {
+    static constexpr const char *tag = "ChordKeys";
+    CycleSet s;
+    int nbits;
+    uint64_t *key;
+    __device__ __forceinline__ void operator()(size_t q, uint32_t is_new, uint32_t pos) const
+    {
+        if (!is_new) return;
+        int32_t a, b;
+        chord_of(s, (uint32_t)q, a, b);
+        key[pos] = ((uint64_t)(uint32_t)min(a, b) << nbits) | (uint32_t)max(a, b);
+    }
+};
+
 // For every sorted chord key: where it would be inserted in the canonical edge list, or -1 if
 // it repeats the previous key or is an edge already.  One binary search per chord, done once.
 __global__ __launch_bounds__(kBlock) void k_chord_lookup(size_t nch, const uint64_t *key, const int32_t *rowptr,
@@ -567,8 +614,16 @@ rama_status dual_update(Ctx &ctx, const Graph &g, int lists, const int32_t *cons
     uint32_t nnew = 0;
     if (nch > 0) {
         Buf<uint64_t> ckey;
-        RAMA_TRY(ckey.alloc(ctx, nch));
-        {
+        if (cs.chord_end[kCycleLists - 1] > cs.chord_end[1]) {   // cycles of five and more nodes: repeats are the rule
+            ScanPlan<uint32_t> fresh;
+            RAMA_TRY((scan_plan_alloc<uint32_t>(ctx, nch, 0, fresh)));
+            RAMA_TRY((scan_totals<uint32_t>(ctx, ChordIsNew{cs}, fresh)));
+            const size_t all = nch;
+            nch = fresh.total;        // at least one: the first chord is always new
+            RAMA_TRY(ckey.alloc(ctx, nch));
+            RAMA_TRY((scan_emit<uint32_t>(ctx, ChordIsNew{cs}, ChordKeysEmit{cs, nbits, ckey.get()}, fresh, (double)(all * 8 + nch * 8))));
+        } else {
+            RAMA_TRY(ckey.alloc(ctx, nch));
             ProfScope ps_(ctx, "k_chord_keys", (double)(nch * 24));
             k_chord_keys<<<grid_for(nch), kBlock, 0, ctx.stream>>>(cs, nch, nbits, ckey.get());
         }
