@@ -61,6 +61,10 @@ def test_profiler_names_map_onto_timer_names():
     assert f("void rama::(anonymous namespace)::k_count_cycles_listed<5, true>(unsigned int const*)") == "k_count_cycles_listed"
     assert f("void rama::(anonymous namespace)::k_count_cycles_coop(unsigned long)") == "k_count_cycles_coop"
     assert f("void rama::(anonymous namespace)::k_edge_update<false>(unsigned long)") == "k_edge_update<false>"
+    assert f("void rama::(anonymous namespace)::k_triangle_update<true>(unsigned long)") == "k_triangle_update"
+    assert f("void rama::k_row_bounds_fill<int, int>(int const*, unsigned long, long, int*)") == "k_row_bounds_fill"
+    assert (f("void rama::k_scan_emit<unsigned int, rama::(anonymous namespace)::ChordIsNew, rama::(anonymous namespace)::ChordKeysEmit>(x)")
+            == "k_scan_emit<ChordKeys>")
     assert f("void rama::k_rs_local<unsigned long, unsigned int, true, unsigned int>(unsigned long const*)") == "k_rs_local<u64,u32>"
     assert f("void rama::k_rs_local<unsigned int, unsigned int, false, unsigned int>(unsigned int const*)") == "k_rs_local<u32>"
     assert f("void rama::k_rs_local<unsigned long, unsigned int, true, unsigned long>(unsigned long const*)") == "k_rs_local<u64,u32,wide>"
